@@ -1,0 +1,17 @@
+"""fp64 CPU oracle for Lightning Attention-2 (test infrastructure only).
+
+Only the tests, the smoke check and the benchmark's cpu_baseline leg import this
+package.  It shares no code with the GPU library and never imports it.
+"""
+from .ref import (  # noqa: F401
+    build,
+    num_threads,
+    fwd_direct,
+    bwd_direct,
+    fwd_recurrent,
+    bwd_recurrent,
+    decode_step,
+    fwd_rows,
+    bwd_rows,
+)
+from .block_form import alg1_forward, alg2_backward  # noqa: F401

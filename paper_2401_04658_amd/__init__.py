@@ -1,0 +1,10 @@
+"""MI355X-native Lightning Attention-2 hot path (gfx950 HIP kernels behind a C ABI)."""
+from .binding import (  # noqa: F401
+    LA2Error,
+    lib_path,
+    load,
+    la2_fwd,
+    la2_bwd,
+    la2_decode_step,
+    la2_workspace_bytes,
+)

@@ -1,0 +1,316 @@
+"""Pins for the fp64 CPU oracle: closed forms, textbook special cases, brute force,
+finite differences and invariants.  None of these re-type the oracle's own loops."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def _attention_matrix(q, k, lam):
+    """A[t, s] = lam^(t-s) (q_t . k_s) for s <= t else 0, built with numpy (one head)."""
+    n = q.shape[0]
+    t = np.arange(n)[:, None]
+    s = np.arange(n)[None, :]
+    decay = np.where(t >= s, np.power(lam, np.maximum(t - s, 0)), 0.0)
+    return (q @ k.T) * decay
+
+
+FWD_FORMS = {
+    "direct": lambda q, k, v, lam: oracle.fwd_direct(q, k, v, lam),
+    "recurrent": lambda q, k, v, lam: oracle.fwd_recurrent(q, k, v, lam),
+}
+BWD_FORMS = {
+    "direct": oracle.bwd_direct,
+    "recurrent": oracle.bwd_recurrent,
+}
+
+
+# ---- P1: closed form (geometric series), Sec. 3.2.1 first equation with q = k = v = 1 ----------
+@pytest.mark.parametrize("form", list(FWD_FORMS))
+@pytest.mark.parametrize("d", [1, 3])
+def test_closed_form_all_ones(form, d):
+    n = 40
+    lam = np.array([0.5, 0.9, 0.99])
+    one = np.ones((2, 3, n, d))
+    o = FWD_FORMS[form](one, one, one, lam)
+    t = np.arange(1, n + 1)
+    for h in range(3):
+        expect = d * (1 - lam[h] ** t) / (1 - lam[h])
+        assert np.allclose(o[:, h], expect[None, :, None], rtol=1e-13, atol=0)
+
+
+def test_golden_geometric_series_lambda_half():
+    """Stored dyadic values of sum_{m<t} (1/2)^m; exact in binary floating point."""
+    vals = np.loadtxt(os.path.join(GOLDEN, "geometric_series_lambda_0p5.txt"), comments="#")
+    n = vals.shape[0]
+    one = np.ones((1, 1, n, 1))
+    for form in FWD_FORMS.values():
+        o = form(one, one, one, 0.5)[0, 0, :, 0]
+        assert np.array_equal(o, vals[:, 1])
+    rows = np.arange(n)
+    assert np.array_equal(oracle.fwd_rows(one[0, 0], one[0, 0], one[0, 0], 0.5, rows)[:, 0], vals[:, 1])
+    assert np.array_equal(oracle.alg1_forward(one[0, 0], one[0, 0], one[0, 0], 0.5, 4)[:, 0], vals[:, 1])
+
+
+# ---- P2: lambda = 1 is the plain causal (lower-triangular) product / a prefix sum ----------------
+@pytest.mark.parametrize("form", list(FWD_FORMS))
+def test_lambda_one_is_tril_product(form):
+    q, k, v = (_rand((1, 2, 33, 5), s) for s in (1, 2, 3))
+    o = FWD_FORMS[form](q, k, v, 1.0)
+    for h in range(2):
+        expect = np.tril(q[0, h] @ k[0, h].T) @ v[0, h]
+        assert np.allclose(o[0, h], expect, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("form", list(FWD_FORMS))
+def test_lambda_one_scalar_is_cumsum(form):
+    n = 100
+    v = _rand((1, 1, n, 1), 4)
+    one = np.ones_like(v)
+    o = FWD_FORMS[form](one, one, v, 1.0)
+    assert np.allclose(o[0, 0, :, 0], np.cumsum(v[0, 0, :, 0]), rtol=1e-12, atol=1e-12)
+
+
+# ---- brute force with explicit Python loops on a tiny case ------------------------------------------
+def test_python_triple_loop_tiny():
+    n, d, lam = 6, 2, 0.7
+    q, k, v, do = (_rand((1, 1, n, d), s) for s in (5, 6, 7, 8))
+    o = np.zeros((n, d))
+    dq, dk, dv = np.zeros((n, d)), np.zeros((n, d)), np.zeros((n, d))
+    Q, K, V, DO = q[0, 0], k[0, 0], v[0, 0], do[0, 0]
+    for t in range(n):
+        for s in range(t + 1):
+            w = lam ** (t - s)
+            qk = sum(Q[t, i] * K[s, i] for i in range(d))
+            dov = sum(DO[t, j] * V[s, j] for j in range(d))
+            for j in range(d):
+                o[t, j] += w * qk * V[s, j]
+                dv[s, j] += w * qk * DO[t, j]
+                dq[t, j] += w * dov * K[s, j]
+                dk[s, j] += w * dov * Q[t, j]
+    for f in FWD_FORMS.values():
+        assert np.allclose(f(q, k, v, lam)[0, 0], o, rtol=1e-13, atol=1e-13)
+    for f in BWD_FORMS.values():
+        g = f(q, k, v, do, lam)
+        for got, exp in zip(g, (dq, dk, dv)):
+            assert np.allclose(got[0, 0], exp, rtol=1e-13, atol=1e-13)
+
+
+# ---- matrix form with library matmuls: O = A V, dV = A^T dO, dA = (dO V^T) * decay -------------------
+@pytest.mark.parametrize("lam", [0.3, 0.95, 1.0])
+def test_matrix_form(lam):
+    n, d = 48, 8
+    q, k, v, do = (_rand((1, 1, n, d), s) for s in (9, 10, 11, 12))
+    Q, K, V, DO = q[0, 0], k[0, 0], v[0, 0], do[0, 0]
+    A = _attention_matrix(Q, K, lam)
+    G = _attention_matrix(DO, V, lam)          # dL/d(QK^T) with the decay folded in
+    for f in FWD_FORMS.values():
+        assert np.allclose(f(q, k, v, lam)[0, 0], A @ V, rtol=1e-12, atol=1e-12)
+    for f in BWD_FORMS.values():
+        dq, dk, dv = f(q, k, v, do, lam)
+        assert np.allclose(dq[0, 0], G @ K, rtol=1e-12, atol=1e-12)
+        assert np.allclose(dk[0, 0], G.T @ Q, rtol=1e-12, atol=1e-12)
+        assert np.allclose(dv[0, 0], A.T @ DO, rtol=1e-12, atol=1e-12)
+
+
+# ---- P3: the two forms agree (multi batch / multi head / per-head lambda) -----------------------------
+def test_direct_equals_recurrent():
+    shape = (2, 3, 64, 8)
+    q, k, v, do = (_rand(shape, s) for s in (13, 14, 15, 16))
+    lam = np.array([0.43, 0.9, 0.9961])
+    o1, o2 = oracle.fwd_direct(q, k, v, lam), oracle.fwd_recurrent(q, k, v, lam)
+    assert np.max(np.abs(o1 - o2)) <= 1e-12 * np.max(np.abs(o1))
+    for a, b in zip(oracle.bwd_direct(q, k, v, do, lam), oracle.bwd_recurrent(q, k, v, do, lam)):
+        assert np.max(np.abs(a - b)) <= 1e-12 * np.max(np.abs(a))
+
+
+def test_head_and_batch_indexing():
+    """Each (batch, head) slice must equal a one-head call with that head's lambda."""
+    shape = (2, 3, 20, 4)
+    q, k, v, do = (_rand(shape, s) for s in (17, 18, 19, 20))
+    lam = np.array([0.5, 0.8, 0.99])
+    o = oracle.fwd_direct(q, k, v, lam)
+    g = oracle.bwd_direct(q, k, v, do, lam)
+    for b, h in itertools.product(range(2), range(3)):
+        A = _attention_matrix(q[b, h], k[b, h], lam[h])
+        assert np.allclose(o[b, h], A @ v[b, h], rtol=1e-12, atol=1e-12)
+        assert np.allclose(g[2][b, h], A.T @ do[b, h], rtol=1e-12, atol=1e-12)
+
+
+# ---- P4: Algorithms 1 and 2 (block form) equal the definition for every B | n ---------------------------
+@pytest.mark.parametrize("B", [1, 2, 4, 8, 16, 32])
+def test_block_form_equals_direct(B):
+    n, d, lam = 32, 4, 0.85
+    q, k, v, do = (_rand((1, 1, n, d), s) for s in (21, 22, 23, 24))
+    o = oracle.fwd_direct(q, k, v, lam)[0, 0]
+    O, states = oracle.alg1_forward(q[0, 0], k[0, 0], v[0, 0], lam, B, return_states=True)
+    assert np.allclose(O, o, rtol=1e-12, atol=1e-13)
+    # carried state after block t is sum_{s <= tB} lam^(tB - s) k_s^T v_s (definition of KV_t)
+    for t, KV in enumerate(states):
+        expect = np.zeros((d, d))
+        for s in range(1, t * B + 1):
+            expect += lam ** (t * B - s) * np.outer(k[0, 0, s - 1], v[0, 0, s - 1])
+        assert np.allclose(KV, expect, rtol=1e-12, atol=1e-13)
+    dq, dk, dv = oracle.bwd_direct(q, k, v, do, lam)
+    bq, bk, bv = oracle.alg2_backward(q[0, 0], k[0, 0], v[0, 0], do[0, 0], lam, B)
+    for a, b in ((bq, dq), (bk, dk), (bv, dv)):
+        assert np.allclose(a, b[0, 0], rtol=1e-12, atol=1e-13)
+
+
+def test_recurrent_final_state_is_block_state():
+    n, d, lam = 24, 3, 0.9
+    q, k, v = (_rand((1, 1, n, d), s) for s in (25, 26, 27))
+    _, kvf = oracle.fwd_recurrent(q, k, v, lam, return_state=True)
+    _, states = oracle.alg1_forward(q[0, 0], k[0, 0], v[0, 0], lam, 8, return_states=True)
+    assert np.allclose(kvf[0, 0], states[-1], rtol=1e-12, atol=1e-13)
+
+
+# ---- P5: central finite differences of L = sum(O * dO) -------------------------------------------------
+@pytest.mark.parametrize("form", list(BWD_FORMS))
+def test_finite_differences(form):
+    shape = (1, 2, 7, 3)
+    q, k, v, do = (_rand(shape, s) for s in (28, 29, 30, 31))
+    lam = np.array([0.6, 0.97])
+    dq, dk, dv = BWD_FORMS[form](q, k, v, do, lam)
+
+    def loss(q_, k_, v_):
+        return float(np.sum(oracle.fwd_direct(q_, k_, v_, lam) * do))
+
+    eps = 1e-6
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        fd = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps
+            xm[idx] -= eps
+            args_p = {"q": q, "k": k, "v": v}
+            args_m = dict(args_p)
+            args_p[name], args_m[name] = xp, xm
+            fd[idx] = (loss(**{a + "_": args_p[a] for a in "qkv"}) - loss(**{a + "_": args_m[a] for a in "qkv"})) / (2 * eps)
+        assert np.allclose(fd, g, rtol=1e-7, atol=1e-8), name
+
+
+# ---- P6: Euler identity (L is linear in each of Q, K, V) -------------------------------------------------
+def test_euler_identity():
+    shape = (2, 2, 50, 6)
+    q, k, v, do = (_rand(shape, s) for s in (32, 33, 34, 35))
+    lam = np.array([0.7, 0.99])
+    o = oracle.fwd_direct(q, k, v, lam)
+    dq, dk, dv = oracle.bwd_direct(q, k, v, do, lam)
+    L = np.sum(o * do)
+    for g, x in ((dq, q), (dk, k), (dv, v)):
+        assert abs(np.sum(g * x) - L) <= 1e-11 * abs(L) + 1e-11
+
+
+# ---- P7: causality ------------------------------------------------------------------------------------------
+def test_causality():
+    shape = (1, 1, 30, 4)
+    q, k, v, do = (_rand(shape, s) for s in (36, 37, 38, 39))
+    lam, cut = 0.9, 17
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for x in (q2, k2, v2):
+        x[..., cut:, :] += 1.0
+    for f in FWD_FORMS.values():
+        assert np.array_equal(f(q, k, v, lam)[..., :cut, :], f(q2, k2, v2, lam)[..., :cut, :])
+    do2 = do.copy()
+    do2[..., :cut, :] -= 2.0
+    for f in BWD_FORMS.values():
+        a, b = f(q, k, v, do, lam), f(q, k, v, do2, lam)
+        assert np.array_equal(a[1][..., cut:, :], b[1][..., cut:, :])
+        assert np.array_equal(a[2][..., cut:, :], b[2][..., cut:, :])
+
+
+# ---- P8: lambda -> 0+ leaves only the diagonal term ------------------------------------------------------------
+@pytest.mark.parametrize("form", list(FWD_FORMS))
+def test_lambda_to_zero(form):
+    shape = (1, 1, 12, 5)
+    q, k, v = (_rand(shape, s) for s in (40, 41, 42))
+    o = FWD_FORMS[form](q, k, v, 1e-200)
+    expect = np.sum(q * k, axis=-1, keepdims=True) * v
+    assert np.allclose(o, expect, rtol=1e-13, atol=1e-13)
+
+
+# ---- P9: decode steps reproduce the forward, and the state's definition ---------------------------------------
+def test_decode_equals_forward():
+    b, H, n, d = 2, 2, 19, 4
+    q, k, v = (_rand((b, H, n, d), s) for s in (43, 44, 45))
+    lam = np.array([0.5, 0.95])
+    o = oracle.fwd_direct(q, k, v, lam)
+    kv = np.zeros((b, H, d, d))
+    for t in range(n):
+        ot = oracle.decode_step(q[:, :, t], k[:, :, t], v[:, :, t], lam, kv)
+        assert np.allclose(ot, o[:, :, t], rtol=1e-12, atol=1e-13)
+    for bi, h in itertools.product(range(b), range(H)):
+        expect = sum(lam[h] ** (n - 1 - s) * np.outer(k[bi, h, s], v[bi, h, s]) for s in range(n))
+        assert np.allclose(kv[bi, h], expect, rtol=1e-12, atol=1e-13)
+
+
+def test_decode_step_formula_and_order():
+    b, H, d = 2, 3, 5
+    q, k, v = (_rand((b, H, d), s) for s in (46, 47, 48))
+    kv0 = _rand((b, H, d, d), 49)
+    lam = np.array([0.4, 0.9, 1.0])
+    kv = kv0.copy()
+    o = oracle.decode_step(q, k, v, lam, kv)
+    expect_kv = lam[None, :, None, None] * kv0 + np.einsum("bhi,bhj->bhij", k, v)
+    assert np.allclose(kv, expect_kv, rtol=1e-14, atol=1e-14)
+    assert np.allclose(o, np.einsum("bhi,bhij->bhj", q, expect_kv), rtol=1e-13, atol=1e-13)
+    # the output reads the UPDATED state: from a zero state o = (q . k) v
+    z = np.zeros((b, H, d, d))
+    o0 = oracle.decode_step(q, k, v, lam, z)
+    assert np.allclose(o0, np.sum(q * k, -1, keepdims=True) * v, rtol=1e-13, atol=1e-13)
+
+
+def test_recurrent_initial_state():
+    """Running on the second half from the first half's final state equals the full run."""
+    b, H, n, d = 1, 2, 16, 3
+    q, k, v = (_rand((b, H, n, d), s) for s in (50, 51, 52))
+    lam = np.array([0.8, 0.99])
+    full = oracle.fwd_direct(q, k, v, lam)
+    _, st = oracle.fwd_recurrent(q[:, :, :8], k[:, :, :8], v[:, :, :8], lam, return_state=True)
+    second = oracle.fwd_recurrent(q[:, :, 8:], k[:, :, 8:], v[:, :, 8:], lam, kv_init=st)
+    assert np.allclose(second, full[:, :, 8:], rtol=1e-12, atol=1e-13)
+
+
+# ---- P10: time-reversal duality of the backward ---------------------------------------------------------------
+def test_time_reversal_duality():
+    shape = (1, 2, 21, 4)
+    q, k, v, do = (_rand(shape, s) for s in (53, 54, 55, 56))
+    lam = np.array([0.6, 0.98])
+    dq, dk, dv = oracle.bwd_direct(q, k, v, do, lam)
+    rev = lambda x: x[:, :, ::-1, :].copy()
+    # dV(s) = sum_{t>=s} lam^(t-s) (k_s . q_t) do_t : forward on the reversed sequence with q<-k, k<-q, v<-do
+    assert np.allclose(rev(oracle.fwd_direct(rev(k), rev(q), rev(do), lam)), dv, rtol=1e-12, atol=1e-13)
+    assert np.allclose(rev(oracle.fwd_direct(rev(v), rev(do), rev(q), lam)), dk, rtol=1e-12, atol=1e-13)
+    assert np.allclose(oracle.fwd_direct(do, v, k, lam), dq, rtol=1e-12, atol=1e-13)
+
+
+# ---- the sampled-row entry points equal the full tensors ---------------------------------------------------------
+def test_rows_equal_full():
+    n, d, lam = 70, 6, 0.93
+    q, k, v, do = (_rand((1, 1, n, d), s) for s in (57, 58, 59, 60))
+    rows = np.array([0, 1, 31, 32, 63, 64, 69])
+    o = oracle.fwd_direct(q, k, v, lam)[0, 0]
+    assert np.allclose(oracle.fwd_rows(q[0, 0], k[0, 0], v[0, 0], lam, rows), o[rows], rtol=1e-13, atol=1e-14)
+    G = _attention_matrix(do[0, 0], v[0, 0], lam)
+    A = _attention_matrix(q[0, 0], k[0, 0], lam)
+    rq, rk, rv = oracle.bwd_rows(q[0, 0], k[0, 0], v[0, 0], do[0, 0], lam, rows)
+    assert np.allclose(rq, (G @ k[0, 0])[rows], rtol=1e-12, atol=1e-13)
+    assert np.allclose(rk, (G.T @ q[0, 0])[rows], rtol=1e-12, atol=1e-13)
+    assert np.allclose(rv, (A.T @ do[0, 0])[rows], rtol=1e-12, atol=1e-13)
+
+
+def test_empty_sequence():
+    z = np.zeros((1, 1, 0, 4))
+    assert oracle.fwd_direct(z, z, z, 0.9).shape == (1, 1, 0, 4)
+    assert oracle.fwd_recurrent(z, z, z, 0.9).shape == (1, 1, 0, 4)
+    assert all(g.shape == (1, 1, 0, 4) for g in oracle.bwd_direct(z, z, z, z, 0.9))
