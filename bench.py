@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lightning Attention-2 hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One "step" is a forward + backward pass (la2_fwd + la2_bwd) at each of the four points of the
+sequence-length sweep -- (batch, n) = (64,1K), (16,4K), (4,16K), (1,64K), H=16, d=128, bf16, i.e.
+4 x 65,536 tokens -- on seeded synthetic tensors that are resident in HBM before the timed region.
+Prints ONE JSON line: whole-step tokens/s, the per-point table (tokens/s, TFLOP/s, fraction of the
+bf16 MFMA peak, flatness), the other configurations (400M-like layer, 3B-like layer, decode), the
+roofline of the dominant kernel measured live with events on the launch stream, and the fp64 CPU
+oracle timed on a bounded sample as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def flops_per_token_head(B, d, what):
+    """FLOPs of Algorithms 1 / 2 per token per head (full B x B tiles counted, as the algorithms do)."""
+    fwd = 4 * B * d + 4 * d * d
+    bwd = 12 * B * d + 10 * d * d
+    return {"fwd": fwd, "bwd": bwd, "fwd+bwd": fwd + bwd}[what]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X); --gpus %d is not supported. "
+              "Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2401_04658_amd as la2
+    from paper_2401_04658_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    la2.load()   # raises if the HIP library has not been built: there is no fallback path
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def stage(wl):
+        t = wl.tensors()
+        g = {k: v.to(dev) for k, v in t.items()}
+        g["o"] = torch.empty_like(g["q"])
+        g["grads"] = tuple(torch.empty_like(g["q"]) for _ in range(3))
+        need = max(binding.la2_workspace_bytes(g["q"], binding.LA2_OP_FWD),
+                   binding.la2_workspace_bytes(g["q"], binding.LA2_OP_BWD))
+        g["ws"] = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        g["B"] = binding.la2_block_size(g["q"])
+        return g
+
+    def fwd(g):
+        binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"], out=g["o"], workspace=g["ws"])
+
+    def bwd(g):
+        binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"], out=g["grads"], workspace=g["ws"])
+
+    def time_ms(fn, iters, warm=2):
+        """Average ms per call, HIP events on the stream the kernels are launched on."""
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    sweep = [(wl, stage(wl)) for wl in workloads.CONFIG3]
+
+    def step():
+        for _, g in sweep:
+            fwd(g)
+            bwd(g)
+
+    # ---- the timed region: W warm-up steps, then exactly K steps ----------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_step = sum(wl.tokens for wl, _ in sweep)
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # ---- per-point table ----------------------------------------------------------------------------------
+    iters = max(5, args.steps)
+    points = []
+    for wl, g in sweep:
+        f_ms = time_ms(lambda: fwd(g), iters)
+        b_ms = time_ms(lambda: bwd(g), iters)
+        th, d, B = wl.token_heads, wl.head_dim, g["B"]
+        tot = f_ms + b_ms
+        fl = flops_per_token_head(B, d, "fwd+bwd") * th
+        points.append({
+            "workload": wl.name, "batch": wl.batch, "seq_len": wl.seqlen, "B": B,
+            "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+            "tokens_per_s": round(wl.tokens / (tot * 1e-3), 1),
+            "tflops": round(fl / (tot * 1e-3) / 1e12, 2),
+            "frac_bf16_peak": round(fl / (tot * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "fwd_tflops": round(flops_per_token_head(B, d, "fwd") * th / (f_ms * 1e-3) / 1e12, 2),
+            "bwd_tflops": round(flops_per_token_head(B, d, "bwd") * th / (b_ms * 1e-3) / 1e12, 2),
+        })
+    tps = [p["tokens_per_s"] for p in points]
+    flatness = min(tps) / max(tps)
+
+    # ---- roofline of the dominant kernel: the forward scan at (16, 4K), one launch per call ---------------
+    wl_r, g_r = sweep[1]
+    assert binding.la2_workspace_bytes(g_r["q"]) == 0 or True
+    k_ms = time_ms(lambda: fwd(g_r), max(20, args.steps))
+    th, d, B = wl_r.token_heads, wl_r.head_dim, g_r["B"]
+    bytes_alg = 8 * d * th            # read Q, K, V and write O once, bf16
+    flops_alg = flops_per_token_head(B, d, "fwd") * th
+    roofline = {
+        "kernel": "scan_bf16_kernel<128,fwd> (la2_fwd, %s)" % wl_r.name,
+        "bound": "hbm",
+        "achieved": round(bytes_alg / (k_ms * 1e-3) / 1e9, 1),
+        "peak": PEAK_HBM_GBS,
+        "unit": "GB/s",
+        "frac": round(bytes_alg / (k_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "traffic": None,
+        "launch_ms": round(k_ms, 4),
+        "mfma_tflops": round(flops_alg / (k_ms * 1e-3) / 1e12, 2),
+        "mfma_frac_of_bf16_peak": round(flops_alg / (k_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "arith_intensity_flop_per_byte": round(flops_alg / bytes_alg, 1),
+    }
+
+    # ---- the other configurations -------------------------------------------------------------------------
+    others = []
+    for wl in (workloads.CONFIG2, workloads.CONFIG4):
+        g = stage(wl)
+        f_ms = time_ms(lambda: fwd(g), iters)
+        b_ms = time_ms(lambda: bwd(g), iters)
+        tot = f_ms + b_ms
+        fl = flops_per_token_head(g["B"], wl.head_dim, "fwd+bwd") * wl.token_heads
+        others.append({"workload": wl.name, "B": g["B"], "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                       "tokens_per_s": round(wl.tokens / (tot * 1e-3), 1),
+                       "tflops": round(fl / (tot * 1e-3) / 1e12, 2),
+                       "frac_bf16_peak": round(fl / (tot * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
+        del g
+    torch.cuda.empty_cache()
+
+    # decode: 1024 consecutive steps, state updated in place
+    dw = workloads.CONFIG5
+    gen = dw.generator()
+    kv = dw.initial_state(gen).to(dev)
+    lam5 = dw.decay().to(dev)
+    toks = [tuple(x.to(dev) for x in dw.token(gen)) for _ in range(16)]
+    o5 = torch.empty_like(toks[0][0])
+    for i in range(8):
+        binding.la2_decode_step(*toks[i % 16], lam5, kv, out=o5)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(dw.steps):
+        binding.la2_decode_step(*toks[i % 16], lam5, kv, out=o5)
+    e1.record()
+    torch.cuda.synchronize()
+    dec_ms = e0.elapsed_time(e1) / dw.steps
+    dd = dw.head_dim
+    dec_bytes = dw.batch * dw.heads * (2 * dd * dd * 4 + 4 * dd * 2)
+    decode = {"workload": dw.name, "steps": dw.steps, "us_per_step": round(dec_ms * 1e3, 2),
+              "tokens_per_s": round(dw.batch / (dec_ms * 1e-3), 1),
+              "achieved_GBs": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+              "frac_hbm_peak": round(dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    del kv
+
+    # ---- CPU baseline: the fp64 oracle (direct O(n^2) form) on a bounded sample ---------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        wl_c = workloads.CONFIG3[1]
+        heads_c = 2
+        t = wl_c.tensors()
+        f64 = lambda x: x[0:1, :heads_c].double().numpy()
+        q, k, v, do = (f64(t[x]) for x in ("q", "k", "v", "d_o"))
+        lam = t["lam"][:heads_c].double().numpy()
+        c0 = time.perf_counter()
+        oracle.fwd_direct(q, k, v, lam)
+        oracle.bwd_direct(q, k, v, do, lam)
+        c1 = time.perf_counter()
+        frac_of_tokens = heads_c / wl_c.heads   # a token counts once all H heads are done
+        cpu = {"value": round(wl_c.seqlen * frac_of_tokens / (c1 - c0), 2), "unit": "tokens/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "fp64 direct O(n^2) oracle, fwd+bwd, %d of %d heads of batch row 0 of %s (%.1f s)"
+                         % (heads_c, wl_c.heads, wl_c.name, c1 - c0)}
+
+    out = {
+        "metric": "causal linear-attn fwd+bwd tokens/s (sequence-length sweep n=1K-64K at 65,536 tokens per point)",
+        "value": round(value, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config3 sweep: (batch,n) in {(64,1K),(16,4K),(4,16K),(1,64K)}, H=16, d=128, "
+                               "fwd+bwd, bf16 in/out, fp32 accumulate",
+                   "tokens_per_step": tokens_per_step, "block_size_B": points[0]["B"],
+                   "flops_per_token_head": "fwd 4Bd+4d^2, bwd 12Bd+10d^2"},
+        "tflops": round(sum(flops_per_token_head(p["B"], 128, "fwd+bwd") for p in points) * 1048576
+                        / (ms_per_step * 1e-3) / 1e12, 2),
+        "flatness_min_over_max": round(flatness, 4),
+        "sweep": points,
+        "other_configs": others,
+        "decode": decode,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    out["frac_bf16_peak"] = round(out["tflops"] / PEAK_BF16_TFLOPS, 4)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,137 @@
+/*
+ * la2.h -- C ABI of the MI355X (gfx950) Lightning Attention-2 library.
+ *
+ * Causal linear attention with a per-head exponential decay lambda_h, per (batch, head):
+ *
+ *     o_t  = sum_{s<=t} lambda^(t-s) (q_t . k_s) v_s                  (Sec. 3.2.1, first equation)
+ *     dq_t = sum_{s<=t} lambda^(t-s) (do_t . v_s) k_s
+ *     dk_s = sum_{t>=s} lambda^(t-s) (do_t . v_s) q_t                 (Sec. 3.2.2, first equation,
+ *     dv_s = sum_{t>=s} lambda^(t-s) (q_t . k_s) do_t                  with kv_t, dkv_t written out)
+ *
+ * evaluated block by block as in Algorithm 1 (forward) and Algorithm 2 (backward): an
+ * intra-block masked product plus an inter-block product with a running d x d state.
+ * No 1/sqrt(d) scaling, no softmax and no output normalisation are applied.
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device.  The caller owns every
+ *     buffer, including the workspace; the library allocates nothing and never synchronises.
+ *     Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Descriptors (`la2_desc`) are HOST structs.
+ *   - Sequence tensors (q, k, v, o, d_o, dq, dk, dv) share one shape [batch, heads, seqlen, head_dim]
+ *     and one set of element strides (stride_b, stride_h, stride_n; the feature stride is 1).
+ *     Base pointers must be 16-byte aligned and every stride a multiple of 16 bytes.
+ *   - lambda is a device array of `heads` fp32 values with 0 < lambda <= 1 (a precondition; it is
+ *     not read on the host and therefore not validated).
+ *   - Outputs are fully overwritten.  Outputs must not alias inputs or each other.
+ *   - dtype LA2_BF16: bf16 storage, bf16 MFMA operands, fp32 accumulation and fp32 running state.
+ *     dtype LA2_F32: fp32 storage and fp32 arithmetic throughout.
+ *   - seqlen may be any value >= 0 (a ragged last block is masked); head_dim is 64 or 128.
+ *   - Argument errors are detected on the host BEFORE anything is launched and are reported through
+ *     the return code; nothing aborts.  A failed launch is reported as LA2_ERR_LAUNCH.
+ */
+#ifndef LA2_H_
+#define LA2_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LA2_OK = 0,
+  LA2_ERR_NULL = 1,         /* a required pointer is NULL                                   */
+  LA2_ERR_SHAPE = 2,        /* negative size, unsupported head_dim, or index range overflow */
+  LA2_ERR_DTYPE = 3,        /* dtype is neither LA2_F32 nor LA2_BF16                        */
+  LA2_ERR_STRIDE_ALIGN = 4, /* pointer or stride not 16-byte aligned, or rows overlap       */
+  LA2_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than la2_workspace_bytes()         */
+  LA2_ERR_LAUNCH = 6        /* the HIP runtime refused a launch                             */
+} la2_status;
+
+typedef enum { LA2_F32 = 0, LA2_BF16 = 1 } la2_dtype;
+
+typedef enum { LA2_OP_FWD = 0, LA2_OP_BWD = 1 } la2_op;
+
+/* Host-side description of the sequence tensors. */
+typedef struct {
+  int32_t batch;
+  int32_t heads;
+  int32_t seqlen;
+  int32_t head_dim; /* 64 or 128 */
+  int32_t dtype;    /* la2_dtype */
+  int32_t reserved; /* must be 0 */
+  int64_t stride_b; /* elements between consecutive batches   */
+  int64_t stride_h; /* elements between consecutive heads     */
+  int64_t stride_n; /* elements between consecutive positions */
+} la2_desc;
+
+/* Fills strides for a dense [batch, heads, seqlen, head_dim] tensor. */
+void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim,
+                    la2_dtype dtype);
+
+/*
+ * Bytes of device workspace la2_fwd / la2_bwd need for this problem (op is a la2_op).  The
+ * workspace holds the d x d start states of the sequence chunks that are processed in parallel
+ * when batch*heads alone cannot fill the GPU; it may be 0.  Returns 0 for an invalid descriptor.
+ * The value depends on the device's compute-unit count and on la2_set_chunk_tokens().
+ */
+size_t la2_workspace_bytes(const la2_desc* desc, int32_t op);
+
+/*
+ * Forward pass, Algorithm 1:  o = LA2(q, k, v; lambda).
+ *   q, k, v   in   device, [batch, heads, seqlen, head_dim] with the descriptor's strides
+ *   lambda    in   device, fp32 [heads]
+ *   o         out  device, same layout as q
+ *   workspace      device scratch of at least la2_workspace_bytes(desc, LA2_OP_FWD) bytes, 256-byte
+ *                  aligned; may be NULL when that size is 0
+ */
+la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
+                   const float* lambda, void* o, void* workspace, size_t workspace_bytes,
+                   void* hip_stream);
+
+/*
+ * Backward pass, Algorithm 2:  (dq, dk, dv) from (q, k, v, d_o).  dq comes from an ascending pass
+ * with the running KV state, dk and dv from a descending pass with the running dKV state.  The
+ * forward output o is not needed (Algorithm 2 lists it as loaded, but no formula uses it).
+ *   workspace: at least la2_workspace_bytes(desc, LA2_OP_BWD) bytes.
+ */
+la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v,
+                   const void* d_o, const float* lambda, void* dq, void* dk, void* dv,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * One step of the recurrent form (Sec. 3.2.1, recursive form), for every (batch, head):
+ *     kv <- lambda_h * kv + k^T v          (state updated IN PLACE)
+ *     o   = q kv                           (uses the UPDATED state, i.e. includes this token)
+ *   q, k, v   in      device, dense [batch, heads, head_dim], dtype qkv_dtype
+ *   lambda    in      device, fp32 [heads]
+ *   kv_state  in/out  device, dense fp32 [batch, heads, head_dim (key), head_dim (value)]
+ *   o         out     device, dense [batch, heads, head_dim], dtype qkv_dtype
+ * All pointers 16-byte aligned.  head_dim is 64 or 128.
+ */
+la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype,
+                           const void* q, const void* k, const void* v, const float* lambda,
+                           float* kv_state, void* o, void* hip_stream);
+
+/*
+ * Block size B (rows of the intra-block tile) the library uses for this descriptor; results do
+ * not depend on it beyond rounding.  Returns 0 for an invalid descriptor.  Used to report FLOPs
+ * with the formula of Algorithms 1 and 2.
+ */
+int32_t la2_block_size(const la2_desc* desc);
+
+/*
+ * Tuning / test knob: tokens per sequence chunk (rounded up to a multiple of the block size).
+ * 0 restores the automatic choice.  Process-global, not thread-safe; changes the value returned
+ * by la2_workspace_bytes().  Results do not depend on it beyond rounding.
+ */
+void la2_set_chunk_tokens(int32_t tokens);
+
+/* Static, NUL-terminated description of a status code. */
+const char* la2_status_string(la2_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA2_H_ */

@@ -1,0 +1,178 @@
+"""Thin ctypes binding of libla2.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; there is no CPU or
+PyTorch fallback.  torch is used for device memory and streams.  If the shared
+library is missing the first call raises (build it with
+`python -m paper_2401_04658_amd.build` or `__graft_entry__.build()`).
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libla2.so")
+_lib = None
+
+LA2_F32, LA2_BF16 = 0, 1
+LA2_OP_FWD, LA2_OP_BWD = 0, 1
+
+
+class LA2Error(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("la2 status %d: %s" % (code, message))
+        self.code = code
+
+
+class la2_desc(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("seqlen", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+    ]
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load():
+    """Loads libla2.so (no fallback: raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: the HIP library has not been built (python -m paper_2401_04658_amd.build)" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    dp = ctypes.POINTER(la2_desc)
+    lib.la2_desc_dense.argtypes = [dp, i32, i32, i32, i32, i32]
+    lib.la2_desc_dense.restype = None
+    lib.la2_workspace_bytes.argtypes = [dp, i32]
+    lib.la2_workspace_bytes.restype = sz
+    lib.la2_block_size.argtypes = [dp]
+    lib.la2_block_size.restype = i32
+    lib.la2_set_chunk_tokens.argtypes = [i32]
+    lib.la2_set_chunk_tokens.restype = None
+    lib.la2_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_fwd.restype = ctypes.c_int
+    lib.la2_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd.restype = ctypes.c_int
+    lib.la2_decode_step.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.la2_decode_step.restype = ctypes.c_int
+    lib.la2_status_string.argtypes = [ctypes.c_int]
+    lib.la2_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(code):
+    if code != 0:
+        raise LA2Error(code, load().la2_status_string(code).decode())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return LA2_BF16
+    if t.dtype == torch.float32:
+        return LA2_F32
+    raise TypeError("la2: dtype must be torch.bfloat16 or torch.float32, got %s" % t.dtype)
+
+
+def make_desc(t):
+    """Descriptor of a [batch, heads, seqlen, head_dim] tensor (feature stride must be 1)."""
+    if t.dim() != 4:
+        raise ValueError("la2: expected a [batch, heads, seqlen, head_dim] tensor")
+    if t.shape[3] > 1 and t.stride(3) != 1:
+        raise ValueError("la2: the feature dimension must be contiguous")
+    b, h, n, d = t.shape
+    return la2_desc(b, h, n, d, _dtype_code(t), 0, t.stride(0), t.stride(1), t.stride(2))
+
+
+def _same_layout(ref, *others):
+    for o in others:
+        if o.shape != ref.shape or o.stride() != ref.stride() or o.dtype != ref.dtype or o.device != ref.device:
+            raise ValueError("la2: all sequence tensors must share shape, strides, dtype and device")
+
+
+def _stream(t):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def la2_workspace_bytes(t, op=LA2_OP_FWD):
+    desc = make_desc(t)
+    return int(load().la2_workspace_bytes(ctypes.byref(desc), op))
+
+
+def la2_block_size(t):
+    desc = make_desc(t)
+    return int(load().la2_block_size(ctypes.byref(desc)))
+
+
+def la2_set_chunk_tokens(tokens):
+    load().la2_set_chunk_tokens(int(tokens))
+
+
+def _workspace(t, op, workspace):
+    need = la2_workspace_bytes(t, op)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=t.device)
+    if workspace is None:
+        return None, 0, None
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), workspace
+
+
+def la2_fwd(q, k, v, lam, out=None, workspace=None):
+    """o = LA2(q, k, v; lam) on the GPU.  q, k, v: [b, H, n, d] bf16/fp32; lam: fp32 [H] (device)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_FWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
+                           out.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
+    return out
+
+
+def la2_bwd(q, k, v, d_o, lam, out=None, workspace=None):
+    """(dq, dk, dv) of sum(o * d_o) on the GPU."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd: tensors must live on the GPU")
+    _same_layout(q, k, v, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv)
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
+                           lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr, ws_bytes,
+                           _stream(q)))
+    return dq, dk, dv
+
+
+def la2_decode_step(q, k, v, lam, kv_state, out=None):
+    """One recurrent step; kv_state (fp32 [b, H, d, d]) is updated in place, returns o [b, H, d]."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_decode_step: tensors must live on the GPU")
+    b, h, d = q.shape
+    for t in (q, k, v):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("la2_decode_step: q, k, v must be dense [b, H, d] of one dtype")
+    if kv_state.dtype != torch.float32 or tuple(kv_state.shape) != (b, h, d, d) or not kv_state.is_contiguous():
+        raise ValueError("la2_decode_step: kv_state must be dense fp32 [b, H, d, d]")
+    if out is None:
+        out = torch.empty_like(q)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_decode_step(b, h, d, _dtype_code(q), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                   lam.data_ptr(), kv_state.data_ptr(), out.data_ptr(), _stream(q)))
+    return out

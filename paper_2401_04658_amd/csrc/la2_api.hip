@@ -1,0 +1,196 @@
+// Host side of the C ABI: argument validation, chunk planning and kernel dispatch.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/la2.h"
+#include "la2_internal.h"
+
+namespace {
+
+int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
+
+int device_cu_count() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+    cached = cus;
+    return cus;
+  }
+  (void)hipGetLastError();
+  return 256;  // MI355X; used when no device is visible (host-only callers sizing a workspace)
+}
+
+int elem_size(int dtype) { return dtype == LA2_BF16 ? 2 : 4; }
+
+la2_status check_desc(const la2_desc* d) {
+  if (d == nullptr) return LA2_ERR_NULL;
+  if (d->dtype != LA2_F32 && d->dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (d->batch < 0 || d->heads < 0 || d->seqlen < 0 || d->reserved != 0) return LA2_ERR_SHAPE;
+  if (d->head_dim != 64 && d->head_dim != 128) return LA2_ERR_SHAPE;
+  if ((int64_t)d->batch * d->heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
+  const int64_t per16 = 16 / elem_size(d->dtype);
+  if (d->stride_b < 0 || d->stride_h < 0 || d->stride_n < d->head_dim) return LA2_ERR_STRIDE_ALIGN;
+  if (d->stride_b % per16 || d->stride_h % per16 || d->stride_n % per16) return LA2_ERR_STRIDE_ALIGN;
+  return LA2_OK;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int block_size(const la2_desc* d) {
+  return d->dtype == LA2_BF16 ? la2::block_size_bf16(d->head_dim) : la2::block_size_f32(d->head_dim);
+}
+
+struct Plan {
+  int nchunks;
+  int chunk_tokens;
+  size_t workspace;
+};
+
+// Sequence chunks: the block loop of one chain is sequential, so when batch*heads cannot fill the
+// compute units the sequence is cut into chunks that run in parallel from pre-computed start states.
+Plan make_plan(const la2_desc* d) {
+  const int B = block_size(d);
+  const int64_t chains = (int64_t)d->batch * d->heads;
+  const int nblocks = (d->seqlen + B - 1) / B;
+  Plan pl{1, nblocks > 0 ? nblocks * B : B, 0};
+  if (chains == 0 || nblocks <= 1) return pl;
+  int cb;  // blocks per chunk
+  if (g_chunk_tokens_override > 0) {
+    cb = (g_chunk_tokens_override + B - 1) / B;
+  } else {
+    const int cus = device_cu_count();
+    if (chains >= cus) return pl;
+    const int want = (int)((cus + chains - 1) / chains);
+    cb = (nblocks + want - 1) / want;
+    if (cb < 4) cb = 4;  // keep the state pre-pass a small fraction of the work
+  }
+  if (cb >= nblocks) return pl;
+  pl.nchunks = (nblocks + cb - 1) / cb;
+  pl.chunk_tokens = cb * B;
+  pl.workspace = (size_t)chains * pl.nchunks * d->head_dim * d->head_dim * sizeof(float);
+  return pl;
+}
+
+la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const void* x, const void* y, const void* z,
+                    void* w, const float* lambda, void* workspace, hipStream_t s) {
+  la2::ScanParams p;
+  p.x = x; p.y = y; p.z = z; p.w = w;
+  p.lambda = lambda;
+  p.states = pl.nchunks > 1 ? reinterpret_cast<float*>(workspace) : nullptr;
+  p.stride_b = d->stride_b; p.stride_h = d->stride_h; p.stride_n = d->stride_n;
+  p.batch = d->batch; p.heads = d->heads; p.n = d->seqlen;
+  p.nchunks = pl.nchunks;
+  p.chunk_tokens = pl.chunk_tokens;
+  const bool bf16 = d->dtype == LA2_BF16;
+  hipError_t e = hipSuccess;
+  if (pl.nchunks > 1) {
+    e = bf16 ? la2::launch_chunk_states_bf16(d->head_dim, reverse, p, s)
+             : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
+    if (e != hipSuccess) return LA2_ERR_LAUNCH;
+    e = la2::launch_state_scan(d->head_dim, reverse, p, s);
+    if (e != hipSuccess) return LA2_ERR_LAUNCH;
+  }
+  e = bf16 ? la2::launch_scan_bf16(d->head_dim, reverse, p, s) : la2::launch_scan_f32(d->head_dim, reverse, p, s);
+  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim,
+                    la2_dtype dtype) {
+  if (desc == nullptr) return;
+  desc->batch = batch;
+  desc->heads = heads;
+  desc->seqlen = seqlen;
+  desc->head_dim = head_dim;
+  desc->dtype = (int32_t)dtype;
+  desc->reserved = 0;
+  desc->stride_n = head_dim;
+  desc->stride_h = (int64_t)seqlen * head_dim;
+  desc->stride_b = (int64_t)heads * seqlen * head_dim;
+}
+
+size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
+  if (check_desc(desc) != LA2_OK) return 0;
+  if (op != LA2_OP_FWD && op != LA2_OP_BWD) return 0;
+  return make_plan(desc).workspace;  // the backward's three scans run one after another in the same space
+}
+
+int32_t la2_block_size(const la2_desc* desc) {
+  if (check_desc(desc) != LA2_OK) return 0;
+  return block_size(desc);
+}
+
+void la2_set_chunk_tokens(int32_t tokens) { g_chunk_tokens_override = tokens > 0 ? tokens : 0; }
+
+la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                   void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const Plan pl = make_plan(desc);
+  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
+  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;
+  return run_scan(desc, pl, false, q, k, v, o, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+                   const float* lambda, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (!q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
+      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const Plan pl = make_plan(desc);
+  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
+  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
+  st = run_scan(desc, pl, false, d_o, v, k, dq, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  // Algorithm 2, second loop (descending, running dKV): dK = [(dO V^T) * M]^T Q + decay(V) dKV^T
+  st = run_scan(desc, pl, true, v, d_o, q, dk, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  //                                                     dV = [(Q K^T) * M]^T dO + decay(K) dKV
+  return run_scan(desc, pl, true, k, q, d_o, dv, lambda, workspace, s);
+}
+
+la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
+                           const void* k, const void* v, const float* lambda, float* kv_state, void* o,
+                           void* hip_stream) {
+  if (qkv_dtype != LA2_F32 && qkv_dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (batch < 0 || heads < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
+  if ((int64_t)batch * heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
+  if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(kv_state, 16) ||
+      !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  hipError_t e = la2::launch_decode(batch, heads, head_dim, qkv_dtype == LA2_BF16, q, k, v, lambda, kv_state, o,
+                                    reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
+const char* la2_status_string(la2_status status) {
+  switch (status) {
+    case LA2_OK: return "ok";
+    case LA2_ERR_NULL: return "a required pointer is NULL";
+    case LA2_ERR_SHAPE: return "invalid shape (negative size, unsupported head_dim or too many chains)";
+    case LA2_ERR_DTYPE: return "unsupported dtype";
+    case LA2_ERR_STRIDE_ALIGN: return "pointer or stride violates the 16-byte alignment / layout rules";
+    case LA2_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LA2_ERR_LAUNCH: return "HIP kernel launch failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Recurrent decode step (Sec. 3.2.1, recursive form): kv <- lambda kv + k^T v, o = q kv, gfx950.
+//
+// Memory bound: the fp32 state (d x d per (batch, head)) is read and written once; everything
+// else is negligible.  One workgroup per (batch, head); each thread streams float4 pieces of the
+// state rows with all of its loads issued up front, then the partial q.kv sums of the row groups
+// are reduced through LDS.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "la2_internal.h"
+
+namespace la2 {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void* p, int64_t i) {
+  if (BF16) return (float)reinterpret_cast<const __bf16*>(p)[i];
+  return reinterpret_cast<const float*>(p)[i];
+}
+
+template <int D, bool BF16>
+__global__ __launch_bounds__(kThreads) void decode_kernel(const void* q, const void* k, const void* v,
+                                                          const float* lambda, float* kv, void* o, int heads) {
+  constexpr int TPR = D / 4;            // threads per state row (float4 each)
+  constexpr int RG = kThreads / TPR;    // rows in flight per sweep
+  constexpr int ITER = D / RG;
+  __shared__ float sq[D], sk[D], sv[D];
+  __shared__ float4 sacc[RG][TPR];
+
+  const int tid = threadIdx.x;
+  const int64_t chain = blockIdx.x;
+  const float lam = lambda[chain % heads];
+  if (tid < D) {
+    sq[tid] = load_elem<BF16>(q, chain * D + tid);
+    sk[tid] = load_elem<BF16>(k, chain * D + tid);
+    sv[tid] = load_elem<BF16>(v, chain * D + tid);
+  }
+  const int cg = tid % TPR, rg = tid / TPR;
+  float4* state = reinterpret_cast<float4*>(kv + chain * (int64_t)(D * D));
+  float4 s[ITER];
+#pragma unroll
+  for (int it = 0; it < ITER; it++) s[it] = state[(int64_t)(rg + RG * it) * TPR + cg];
+  __syncthreads();
+  const float4 v4 = *reinterpret_cast<const float4*>(&sv[4 * cg]);
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int i = rg + RG * it;
+    const float ki = sk[i], qi = sq[i];
+    float4 t;
+    t.x = fmaf(lam, s[it].x, ki * v4.x);
+    t.y = fmaf(lam, s[it].y, ki * v4.y);
+    t.z = fmaf(lam, s[it].z, ki * v4.z);
+    t.w = fmaf(lam, s[it].w, ki * v4.w);
+    state[(int64_t)i * TPR + cg] = t;
+    acc.x = fmaf(qi, t.x, acc.x);
+    acc.y = fmaf(qi, t.y, acc.y);
+    acc.z = fmaf(qi, t.z, acc.z);
+    acc.w = fmaf(qi, t.w, acc.w);
+  }
+  sacc[rg][cg] = acc;
+  __syncthreads();
+  if (tid < D) {
+    const float* flat = reinterpret_cast<const float*>(sacc);
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < RG; g++) sum += flat[g * D + tid];
+    if (BF16) reinterpret_cast<__bf16*>(o)[chain * D + tid] = (__bf16)sum;
+    else reinterpret_cast<float*>(o)[chain * D + tid] = sum;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_decode(int batch, int heads, int head_dim, bool bf16, const void* q, const void* k,
+                         const void* v, const float* lambda, float* kv, void* o, hipStream_t s) {
+  const int64_t chains = (int64_t)batch * heads;
+  if (chains == 0) return hipSuccess;
+  dim3 g((unsigned)chains), b(kThreads);
+  if (head_dim == 128) {
+    if (bf16) hipLaunchKernelGGL((decode_kernel<128, true>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
+    else      hipLaunchKernelGGL((decode_kernel<128, false>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
+  } else {
+    if (bf16) hipLaunchKernelGGL((decode_kernel<64, true>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
+    else      hipLaunchKernelGGL((decode_kernel<64, false>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace la2

@@ -1,0 +1,45 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#ifndef LA2_INTERNAL_H_
+#define LA2_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace la2 {
+
+// One "decayed causal scan": for every (batch, head) chain
+//     forward : w_t = sum_{s<=t} lambda^(t-s) (x_t . y_s) z_s
+//     reverse : w_t = sum_{s>=t} lambda^(s-t) (x_t . y_s) z_s
+// Algorithm 1 is the forward scan of (q, k, v).  Algorithm 2's first loop is the forward scan of
+// (dO, V, K) and its second loop is the reverse scan of (V, dO, Q) for dK and of (K, Q, dO) for dV.
+struct ScanParams {
+  const void* x;
+  const void* y;
+  const void* z;
+  void* w;
+  const float* lambda;  // [heads], device
+  float* states;        // [chains][nchunks][D][D] fp32 chunk start states, or nullptr (nchunks == 1)
+  int64_t stride_b, stride_h, stride_n;  // elements
+  int32_t batch, heads, n;
+  int32_t nchunks;       // sequence chunks processed by different workgroups
+  int32_t chunk_tokens;  // tokens per chunk (multiple of the block size); last chunk may be short
+};
+
+// Block size (rows of the intra-block tile) per data type / head dim.
+int block_size_bf16(int head_dim);
+int block_size_f32(int head_dim);
+
+// bf16 MFMA path (head_dim 64 or 128)
+hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+// fp32 path
+hipError_t launch_scan_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+// turns the per-chunk local states in p.states into chunk start states (any dtype: states are fp32)
+hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+
+hipError_t launch_decode(int batch, int heads, int head_dim, bool bf16, const void* q, const void* k,
+                         const void* v, const float* lambda, float* kv, void* o, hipStream_t s);
+
+}  // namespace la2
+#endif

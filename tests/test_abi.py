@@ -1,0 +1,174 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments with a status code before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2401_04658_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "la2.h")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH = range(7)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2401_04658_amd.build import build
+        build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(la2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_entry_points():
+    names = declared_functions()
+    for must in ("la2_fwd", "la2_bwd", "la2_decode_step", "la2_workspace_bytes", "la2_status_string"):
+        assert must in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), "libla2.so does not export %s" % name
+
+
+def dense(lib, b, h, n, d, dtype):
+    desc = binding.la2_desc()
+    lib.la2_desc_dense(ctypes.byref(desc), b, h, n, d, dtype)
+    return desc
+
+
+def test_desc_dense(lib):
+    d = dense(lib, 2, 3, 100, 64, binding.LA2_BF16)
+    assert (d.stride_n, d.stride_h, d.stride_b) == (64, 6400, 19200)
+    assert (d.batch, d.heads, d.seqlen, d.head_dim, d.dtype, d.reserved) == (2, 3, 100, 64, 1, 0)
+
+
+P = 0x10000  # a fake, suitably aligned "device pointer"; validation failures return before any use
+
+
+def fwd(lib, desc, q=P, k=P, v=P, lam=P, o=P, ws=None, ws_bytes=0):
+    return lib.la2_fwd(ctypes.byref(desc) if desc is not None else None, q, k, v, lam, o, ws, ws_bytes, None)
+
+
+def bwd(lib, desc, ptrs=None, ws=None, ws_bytes=0):
+    ptrs = ptrs or [P] * 8
+    return lib.la2_bwd(ctypes.byref(desc), *ptrs, ws, ws_bytes, None)
+
+
+def test_null_arguments(lib):
+    d = dense(lib, 1, 1, 128, 64, binding.LA2_BF16)
+    assert fwd(lib, None) == E_NULL
+    for name in ("q", "k", "v", "lam", "o"):
+        assert fwd(lib, d, **{name: None}) == E_NULL
+    for i in range(8):
+        ptrs = [P] * 8
+        ptrs[i] = None
+        assert bwd(lib, d, ptrs) == E_NULL
+    assert lib.la2_decode_step(1, 1, 64, 1, None, P, P, P, P, P, None) == E_NULL
+    assert lib.la2_decode_step(1, 1, 64, 1, P, P, P, P, None, P, None) == E_NULL
+
+
+def test_shape_errors(lib):
+    for bad in (dict(batch=-1), dict(heads=-2), dict(seqlen=-5), dict(head_dim=96), dict(head_dim=0),
+                dict(reserved=1)):
+        d = dense(lib, 1, 1, 128, 64, binding.LA2_BF16)
+        for kk, vv in bad.items():
+            setattr(d, kk, vv)
+        assert fwd(lib, d) == E_SHAPE, bad
+        assert bwd(lib, d) == E_SHAPE, bad
+        assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 0
+        assert lib.la2_block_size(ctypes.byref(d)) == 0
+    assert lib.la2_decode_step(1, 1, 100, 1, P, P, P, P, P, P, None) == E_SHAPE
+    assert lib.la2_decode_step(-1, 1, 64, 1, P, P, P, P, P, P, None) == E_SHAPE
+
+
+def test_dtype_errors(lib):
+    d = dense(lib, 1, 1, 128, 64, binding.LA2_BF16)
+    d.dtype = 7
+    assert fwd(lib, d) == E_DTYPE
+    assert bwd(lib, d) == E_DTYPE
+    assert lib.la2_decode_step(1, 1, 64, 5, P, P, P, P, P, P, None) == E_DTYPE
+
+
+def test_alignment_errors(lib):
+    d = dense(lib, 1, 1, 128, 64, binding.LA2_BF16)
+    assert fwd(lib, d, q=P + 2) == E_ALIGN
+    assert fwd(lib, d, o=P + 8) == E_ALIGN
+    d.stride_n = 68  # 136 bytes: not a multiple of 16
+    assert fwd(lib, d) == E_ALIGN
+    d = dense(lib, 1, 1, 128, 64, binding.LA2_F32)
+    d.stride_n = 32  # rows would overlap
+    assert fwd(lib, d) == E_ALIGN
+    d = dense(lib, 1, 2, 128, 64, binding.LA2_F32)
+    d.stride_h = 128 * 64 + 2
+    assert bwd(lib, d) == E_ALIGN
+    assert lib.la2_decode_step(1, 1, 64, 1, P + 4, P, P, P, P, P, None) == E_ALIGN
+
+
+def test_workspace_rules(lib):
+    try:
+        lib.la2_set_chunk_tokens(256)
+        d = dense(lib, 1, 2, 1024, 128, binding.LA2_BF16)
+        need = lib.la2_workspace_bytes(ctypes.byref(d), 0)
+        assert need == 2 * 4 * 128 * 128 * 4  # chains x chunks x d x d fp32
+        assert lib.la2_workspace_bytes(ctypes.byref(d), 1) == need
+        assert lib.la2_workspace_bytes(ctypes.byref(d), 9) == 0
+        assert fwd(lib, d) == E_WS
+        assert fwd(lib, d, ws=P, ws_bytes=need - 1) == E_WS
+        assert fwd(lib, d, ws=P + 16, ws_bytes=need) == E_WS
+        assert bwd(lib, d, ws=None, ws_bytes=need) == E_WS
+        # a chunk as long as the sequence needs no workspace
+        lib.la2_set_chunk_tokens(1024)
+        assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 0
+    finally:
+        lib.la2_set_chunk_tokens(0)
+
+
+def test_automatic_chunking_is_sized_for_the_device(lib):
+    # 16 chains on a 256-CU device: the sequence is cut so that about 256 workgroups exist
+    d = dense(lib, 1, 16, 65536, 128, binding.LA2_BF16)
+    need = lib.la2_workspace_bytes(ctypes.byref(d), 0)
+    chunks = need // (16 * 128 * 128 * 4)
+    assert 8 <= chunks <= 64
+    # enough chains already: no chunking, no workspace
+    d = dense(lib, 64, 16, 1024, 128, binding.LA2_BF16)
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 0
+
+
+def test_empty_problem_is_ok_without_a_device(lib):
+    d = dense(lib, 0, 4, 128, 64, binding.LA2_BF16)
+    assert fwd(lib, d) == OK
+    d = dense(lib, 2, 4, 0, 64, binding.LA2_F32)
+    assert fwd(lib, d) == OK
+    assert bwd(lib, d) == OK
+
+
+def test_block_size_and_status_strings(lib):
+    for dt in (binding.LA2_BF16, binding.LA2_F32):
+        for hd in (64, 128):
+            d = dense(lib, 1, 1, 128, hd, dt)
+            assert lib.la2_block_size(ctypes.byref(d)) in (32, 64, 128)
+    seen = set()
+    for code in range(7):
+        s = lib.la2_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert lib.la2_status_string(99) == b"unknown status"
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    x = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)
+    lam = torch.ones(1)
+    with pytest.raises(ValueError):
+        binding.la2_fwd(x, x, x, lam)
+    with pytest.raises(ValueError):
+        binding.la2_bwd(x, x, x, x, lam)

@@ -1,0 +1,255 @@
+"""GPU parity: la2_fwd / la2_bwd / la2_decode_step (through the C ABI) against the fp64 oracle,
+element by element on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_04658_amd import binding, workloads
+from parity import TOL, assert_close, max_rel, to64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _auto_chunking():
+    binding.la2_set_chunk_tokens(0)
+    yield
+    binding.la2_set_chunk_tokens(0)
+
+
+def make_inputs(b, H, n, d, dtype, seed, lam=None, backward=True):
+    wl = workloads.Workload("case", b, H, n, d, dtype, seed=seed, backward=backward)
+    t = wl.tensors()
+    if lam is not None:
+        t["lam"] = torch.as_tensor(lam, dtype=torch.float32).reshape(-1).expand(H).contiguous()
+    return t
+
+
+def gpu(t):
+    return {k: v.to(DEV) for k, v in t.items()}
+
+
+def check_fwd_bwd(t, dtype, tag, backward=True):
+    g = gpu(t)
+    o = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
+    torch.cuda.synchronize()
+    q, k, v, lam = to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"])
+    res = {"o": assert_close(tag + " o", o, oracle.fwd_direct(q, k, v, lam), dtype)}
+    if backward:
+        dq, dk, dv = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
+        torch.cuda.synchronize()
+        rq, rk, rv = oracle.bwd_direct(q, k, v, to64(t["d_o"]), lam)
+        res["dq"] = assert_close(tag + " dq", dq, rq, dtype)
+        res["dk"] = assert_close(tag + " dk", dk, rk, dtype)
+        res["dv"] = assert_close(tag + " dv", dv, rv, dtype)
+    return res
+
+
+# ---- configuration 1: forward, fp32 -------------------------------------------------------------------------
+def test_config1_fwd_fp32():
+    wl = workloads.CONFIG1
+    check_fwd_bwd(wl.tensors(), wl.dtype, wl.name, backward=False)
+
+
+# ---- configuration 2: 400M-model layer, bf16, full tensors against the O(n^2) oracle -----------------------------
+def test_config2_fwd_bwd_bf16_full():
+    wl = workloads.CONFIG2
+    check_fwd_bwd(wl.tensors(), wl.dtype, wl.name)
+
+
+# ---- small shapes spanning several tiles and ragged tails, both dtypes, both head dims ------------------------------
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n", [1, 31, 128, 129, 200, 384, 517])
+def test_small_shapes(dtype, d, n):
+    t = make_inputs(2, 3, n, d, dtype, seed=100 + n + d, lam=[0.5, 0.93, 1.0])
+    check_fwd_bwd(t, dtype, "n%d d%d %s" % (n, d, dtype))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("chunk", [128, 256, 384])
+@pytest.mark.parametrize("d,n", [(64, 1000), (128, 1000), (128, 1024), (64, 257)])
+def test_chunked_path(dtype, chunk, d, n):
+    """Forces the sequence-chunk path (state pre-pass + scan) incl. a ragged last chunk."""
+    binding.la2_set_chunk_tokens(chunk)
+    t = make_inputs(1, 4, n, d, dtype, seed=7 * n + d + chunk)
+    if chunk < n - 128:
+        assert binding.la2_workspace_bytes(t["q"].to(DEV)) > 0
+    check_fwd_bwd(t, dtype, "chunk%d n%d d%d %s" % (chunk, n, d, dtype))
+
+
+def test_chunking_changes_results_only_by_rounding():
+    t = gpu(make_inputs(1, 2, 2048, 128, torch.bfloat16, seed=11))
+    base = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"])
+    binding.la2_set_chunk_tokens(512)
+    chunked = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"])
+    torch.cuda.synchronize()
+    assert max_rel(to64(chunked), to64(base)) <= 1e-2
+
+
+def test_empty_and_degenerate():
+    for n in (0,):
+        t = gpu(make_inputs(2, 2, n, 64, torch.bfloat16, seed=1))
+        o = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"])
+        g = binding.la2_bwd(t["q"], t["k"], t["v"], t["d_o"], t["lam"])
+        torch.cuda.synchronize()
+        assert o.shape == (2, 2, 0, 64) and all(x.shape == (2, 2, 0, 64) for x in g)
+    # batch of zero
+    t = gpu(make_inputs(0, 2, 64, 64, torch.bfloat16, seed=1))
+    assert binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"]).numel() == 0
+
+
+def test_extreme_decays():
+    """lambda = 1 (pure causal prefix sum) and a very small lambda (only the diagonal survives)."""
+    for dtype in (torch.bfloat16, torch.float32):
+        t = make_inputs(1, 3, 300, 64, dtype, seed=21, lam=[1.0, 1e-6, 0.43])
+        check_fwd_bwd(t, dtype, "extreme decays %s" % dtype)
+
+
+def test_strided_layout():
+    """[b, n, H, d] storage viewed as [b, H, n, d]: strides go through the descriptor."""
+    b, H, n, d = 2, 4, 260, 128
+    for dtype in (torch.bfloat16, torch.float32):
+        t = make_inputs(b, H, n, d, dtype, seed=31)
+        g = {}
+        for name in ("q", "k", "v", "d_o"):
+            store = t[name].permute(0, 2, 1, 3).contiguous().to(DEV)  # [b, n, H, d]
+            g[name] = store.permute(0, 2, 1, 3)                       # view [b, H, n, d]
+            assert not g[name].is_contiguous()
+        lam = t["lam"].to(DEV)
+        o = binding.la2_fwd(g["q"], g["k"], g["v"], lam)
+        dq, dk, dv = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], lam)
+        torch.cuda.synchronize()
+        q, k, v, do, lam64 = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+        assert_close("strided o", o, oracle.fwd_direct(q, k, v, lam64), dtype)
+        for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle.bwd_direct(q, k, v, do, lam64)):
+            assert_close("strided " + name, got, ref, dtype)
+
+
+def test_deterministic_and_causal():
+    t = gpu(make_inputs(2, 2, 700, 128, torch.bfloat16, seed=41))
+    o1 = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"])
+    o2 = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"])
+    g1 = binding.la2_bwd(t["q"], t["k"], t["v"], t["d_o"], t["lam"])
+    g2 = binding.la2_bwd(t["q"], t["k"], t["v"], t["d_o"], t["lam"])
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    assert all(torch.equal(a, b) for a, b in zip(g1, g2))
+    # changing tokens after position `cut` must leave earlier outputs bit-identical
+    cut = 300
+    q2, k2, v2 = t["q"].clone(), t["k"].clone(), t["v"].clone()
+    for x in (q2, k2, v2):
+        x[:, :, cut:] += 1.0
+    o3 = binding.la2_fwd(q2, k2, v2, t["lam"])
+    torch.cuda.synchronize()
+    assert torch.equal(o1[:, :, :cut], o3[:, :, :cut])
+    # changing dO before `cut` must leave dK, dV from `cut` on bit-identical
+    do2 = t["d_o"].clone()
+    do2[:, :, :cut] -= 2.0
+    g3 = binding.la2_bwd(t["q"], t["k"], t["v"], do2, t["lam"])
+    torch.cuda.synchronize()
+    assert torch.equal(g1[1][:, :, cut:], g3[1][:, :, cut:])
+    assert torch.equal(g1[2][:, :, cut:], g3[2][:, :, cut:])
+
+
+# ---- full-size configurations 3 and 4: sampled rows against the O(n^2) oracle + Euler identity ----------------------
+def sampled_rows(n, rng, count=24):
+    fixed = [0, 1, 127, 128, 129, n // 2 - 1, n // 2, n - 129, n - 128, n - 2, n - 1]
+    rnd = rng.integers(0, n, size=count - len(fixed)).tolist()
+    return np.array(sorted(set(int(r) for r in fixed + rnd if 0 <= r < n)), dtype=np.int64)
+
+
+def check_sampled(wl):
+    t = wl.tensors()
+    g = gpu(t)
+    o = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
+    dq, dk, dv = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(wl.seed)
+    H = wl.heads
+    tol = TOL[wl.dtype]
+    for b, h in ((0, 0), (wl.batch - 1, H // 2), (0, H - 1)):
+        rows = sampled_rows(wl.seqlen, rng)
+        q, k, v, do = (to64(t[x][b, h]) for x in ("q", "k", "v", "d_o"))
+        lam = float(t["lam"][h].double())
+        ref_o = oracle.fwd_rows(q, k, v, lam, rows)
+        ref_dq, ref_dk, ref_dv = oracle.bwd_rows(q, k, v, do, lam, rows)
+        for name, got, ref in (("o", o, ref_o), ("dq", dq, ref_dq), ("dk", dk, ref_dk), ("dv", dv, ref_dv)):
+            x = to64(got[b, h])[rows]
+            # normalise by the largest magnitude of the sampled oracle rows of this chain
+            err = float(np.max(np.abs(x - ref))) / float(np.max(np.abs(ref)))
+            assert np.all(np.isfinite(x))
+            assert err <= tol, "%s %s (b%d h%d): %.3e" % (wl.name, name, b, h, err)
+    # Euler identity on the full GPU outputs: <dQ,Q> = <dK,K> = <dV,V> = <dO,O>
+    f64 = lambda x: x.to(torch.float64)
+    L = torch.sum(f64(o) * f64(g["d_o"])).item()
+    scale = torch.sum(torch.abs(f64(o) * f64(g["d_o"]))).item()
+    for name, grad, x in (("dq", dq, g["q"]), ("dk", dk, g["k"]), ("dv", dv, g["v"])):
+        val = torch.sum(f64(grad) * f64(x)).item()
+        assert abs(val - L) <= 2e-3 * scale, "%s Euler identity: %g vs %g" % (name, val, L)
+    for x in (o, dq, dk, dv):
+        assert torch.isfinite(x.float()).all()
+
+
+@pytest.mark.parametrize("idx", range(4))
+def test_config3_sweep_sampled(idx):
+    check_sampled(workloads.CONFIG3[idx])
+
+
+def test_config4_3b_layer_sampled():
+    check_sampled(workloads.CONFIG4)
+
+
+# ---- configuration 5: decode ------------------------------------------------------------------------------------
+def run_decode(wl, batch, steps):
+    g = wl.generator()
+    H, d = wl.heads, wl.head_dim
+    state0 = wl.initial_state(g)[:batch].contiguous()
+    lam = wl.decay()
+    kv_gpu = state0.to(DEV)
+    kv_ref = state0.double().numpy().copy()
+    lam_gpu, lam64 = lam.to(DEV), lam.double().numpy()
+    worst = 0.0
+    for step in range(steps):
+        q, k, v = (x[:batch].contiguous() for x in wl.token(g))
+        o = binding.la2_decode_step(q.to(DEV), k.to(DEV), v.to(DEV), lam_gpu, kv_gpu)
+        ref = oracle.decode_step(to64(q), to64(k), to64(v), lam64, kv_ref)
+        if step < 4 or step % 97 == 0 or step == steps - 1:
+            worst = max(worst, max_rel(to64(o), ref))
+            assert worst <= TOL[torch.bfloat16], "decode o at step %d: %.3e" % (step, worst)
+    torch.cuda.synchronize()
+    m = max_rel(to64(kv_gpu), kv_ref)
+    assert m <= 1e-5, "decode state after %d steps: %.3e" % (steps, m)
+
+
+def test_config5_decode_full_batch_few_steps():
+    run_decode(workloads.CONFIG5, workloads.CONFIG5.batch, 3)
+
+
+def test_config5_decode_1024_steps_one_batch_row():
+    run_decode(workloads.CONFIG5, 1, workloads.CONFIG5.steps)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_decode_matches_forward(d, dtype):
+    """n decode steps from a zero state reproduce the forward output row by row."""
+    b, H, n = 2, 3, 40
+    t = make_inputs(b, H, n, d, dtype, seed=51, backward=False)
+    g = gpu(t)
+    kv = torch.zeros(b, H, d, d, dtype=torch.float32, device=DEV)
+    rows = []
+    for s in range(n):
+        rows.append(binding.la2_decode_step(g["q"][:, :, s].contiguous(), g["k"][:, :, s].contiguous(),
+                                            g["v"][:, :, s].contiguous(), g["lam"], kv))
+    torch.cuda.synchronize()
+    o = torch.stack(rows, dim=2)
+    q, k, v, lam = (to64(t[x]) for x in ("q", "k", "v", "lam"))
+    assert_close("decode-as-forward", o, oracle.fwd_direct(q, k, v, lam), dtype)
+    _, kvf = oracle.fwd_recurrent(q, k, v, lam, return_state=True)
+    assert max_rel(to64(kv), kvf) <= 1e-5
