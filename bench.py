@@ -32,12 +32,36 @@ def flops_per_token_head(B, d, what):
     return {"fwd": fwd, "bwd": bwd, "fwd+bwd": fwd + bwd}[what]
 
 
+def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
+    """The forward scan at (batch 16, n 4K): la2_fwd is exactly one launch of the scan kernel there."""
+    assert binding.la2_workspace_bytes(g["q"]) == 0, "expected the un-chunked single-launch case"
+    k_ms = time_ms(lambda: fwd(g), iters)
+    th, d, B = wl.token_heads, wl.head_dim, g["B"]
+    bytes_alg = 8 * d * th            # read Q, K, V and write O once, bf16
+    flops_alg = flops_per_token_head(B, d, "fwd") * th
+    return {
+        "kernel": "scan_bf16_kernel<128,fwd> (la2_fwd, %s)" % wl.name,
+        "bound": "hbm",
+        "achieved": round(bytes_alg / (k_ms * 1e-3) / 1e9, 1),
+        "peak": PEAK_HBM_GBS,
+        "unit": "GB/s",
+        "frac": round(bytes_alg / (k_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "traffic": None,
+        "launch_ms": round(k_ms, 4),
+        "mfma_tflops": round(flops_alg / (k_ms * 1e-3) / 1e12, 2),
+        "mfma_frac_of_bf16_peak": round(flops_alg / (k_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "arith_intensity_flop_per_byte": round(flops_alg / bytes_alg, 1),
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="run only the dominant kernel's loop (for rocprofv3 counter passes); prints its roofline JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus %d is not supported. "
@@ -85,6 +109,18 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
+    if args.roofline_only:
+        # a plain copy of known size first: the reference that scales the FETCH_SIZE / WRITE_SIZE counters
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        wl_r = workloads.CONFIG3[1]
+        print(json.dumps(dominant_kernel_roofline(wl_r, stage(wl_r), fwd, time_ms, binding, max(20, args.steps))))
+        return
+
     sweep = [(wl, stage(wl)) for wl in workloads.CONFIG3]
 
     def step():
@@ -128,24 +164,7 @@ def main():
 
     # ---- roofline of the dominant kernel: the forward scan at (16, 4K), one launch per call ---------------
     wl_r, g_r = sweep[1]
-    assert binding.la2_workspace_bytes(g_r["q"]) == 0 or True
-    k_ms = time_ms(lambda: fwd(g_r), max(20, args.steps))
-    th, d, B = wl_r.token_heads, wl_r.head_dim, g_r["B"]
-    bytes_alg = 8 * d * th            # read Q, K, V and write O once, bf16
-    flops_alg = flops_per_token_head(B, d, "fwd") * th
-    roofline = {
-        "kernel": "scan_bf16_kernel<128,fwd> (la2_fwd, %s)" % wl_r.name,
-        "bound": "hbm",
-        "achieved": round(bytes_alg / (k_ms * 1e-3) / 1e9, 1),
-        "peak": PEAK_HBM_GBS,
-        "unit": "GB/s",
-        "frac": round(bytes_alg / (k_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-        "traffic": None,
-        "launch_ms": round(k_ms, 4),
-        "mfma_tflops": round(flops_alg / (k_ms * 1e-3) / 1e12, 2),
-        "mfma_frac_of_bf16_peak": round(flops_alg / (k_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "arith_intensity_flop_per_byte": round(flops_alg / bytes_alg, 1),
-    }
+    roofline = dominant_kernel_roofline(wl_r, g_r, fwd, time_ms, binding, max(20, args.steps))
 
     # ---- the other configurations -------------------------------------------------------------------------
     others = []

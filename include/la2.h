@@ -23,6 +23,8 @@
  *   - lambda is a device array of `heads` fp32 values with 0 < lambda <= 1 (a precondition; it is
  *     not read on the host and therefore not validated).
  *   - Outputs are fully overwritten.  Outputs must not alias inputs or each other.
+ *   - An empty problem (batch, heads or seqlen equal to 0) returns LA2_OK without touching any
+ *     pointer; pointers may then be NULL.
  *   - dtype LA2_BF16: bf16 storage, bf16 MFMA operands, fp32 accumulation and fp32 running state.
  *     dtype LA2_F32: fp32 storage and fp32 arithmetic throughout.
  *   - seqlen may be any value >= 0 (a ragged last block is masked); head_dim is 64 or 128.

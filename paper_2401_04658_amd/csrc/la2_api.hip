@@ -33,6 +33,8 @@ la2_status check_desc(const la2_desc* d) {
   const int64_t per16 = 16 / elem_size(d->dtype);
   if (d->stride_b < 0 || d->stride_h < 0 || d->stride_n < d->head_dim) return LA2_ERR_STRIDE_ALIGN;
   if (d->stride_b % per16 || d->stride_h % per16 || d->stride_n % per16) return LA2_ERR_STRIDE_ALIGN;
+  // the kernels address one chain with 32-bit byte offsets
+  if ((int64_t)d->seqlen * d->stride_n * elem_size(d->dtype) >= ((int64_t)1 << 32)) return LA2_ERR_SHAPE;
   return LA2_OK;
 }
 
@@ -131,13 +133,13 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
                    void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
   const Plan pl = make_plan(desc);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;
   return run_scan(desc, pl, false, q, k, v, o, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
@@ -146,6 +148,7 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
                    void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
       !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
@@ -153,7 +156,6 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
   const Plan pl = make_plan(desc);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
   st = run_scan(desc, pl, false, d_o, v, k, dq, lambda, workspace, s);
@@ -171,6 +173,7 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
   if (qkv_dtype != LA2_F32 && qkv_dtype != LA2_BF16) return LA2_ERR_DTYPE;
   if (batch < 0 || heads < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
+  if ((int64_t)batch * heads == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(kv_state, 16) ||
       !aligned(lambda, 4))
