@@ -75,27 +75,63 @@ Plan make_plan(const la2_desc* d) {
   return pl;
 }
 
-la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const void* x, const void* y, const void* z,
-                    void* w, const float* lambda, void* workspace, hipStream_t s) {
-  la2::ScanParams p;
-  p.x = x; p.y = y; p.z = z; p.w = w;
+struct ScanArgs {
+  const void* x;
+  const void* y;
+  const void* z;
+  void* w;
+};
+
+la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace) {
+  la2::ScanParams p{};
+  p.nscan = 1;
+  p.state_transposed = 0;
   p.lambda = lambda;
   p.states = pl.nchunks > 1 ? reinterpret_cast<float*>(workspace) : nullptr;
   p.stride_b = d->stride_b; p.stride_h = d->stride_h; p.stride_n = d->stride_n;
   p.batch = d->batch; p.heads = d->heads; p.n = d->seqlen;
   p.nchunks = pl.nchunks;
   p.chunk_tokens = pl.chunk_tokens;
+  return p;
+}
+
+// chunk start states of the scan with key-like operand y and value-like operand z -> workspace
+la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const void* y, const void* z,
+                       const float* lambda, void* workspace, hipStream_t s) {
+  if (pl.nchunks <= 1) return LA2_OK;
+  la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  p.y[0] = y; p.z[0] = z;
   const bool bf16 = d->dtype == LA2_BF16;
-  hipError_t e = hipSuccess;
-  if (pl.nchunks > 1) {
-    e = bf16 ? la2::launch_chunk_states_bf16(d->head_dim, reverse, p, s)
-             : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
-    if (e != hipSuccess) return LA2_ERR_LAUNCH;
-    e = la2::launch_state_scan(d->head_dim, reverse, p, s);
-    if (e != hipSuccess) return LA2_ERR_LAUNCH;
-  }
-  e = bf16 ? la2::launch_scan_bf16(d->head_dim, reverse, p, s) : la2::launch_scan_f32(d->head_dim, reverse, p, s);
+  hipError_t e = bf16 ? la2::launch_chunk_states_bf16(d->head_dim, reverse, p, s)
+                      : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
+  if (e != hipSuccess) return LA2_ERR_LAUNCH;
+  e = la2::launch_state_scan(d->head_dim, reverse, p, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
+la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanArgs& a, const float* lambda,
+                    void* workspace, hipStream_t s) {
+  la2_status st = run_prepass(d, pl, reverse, a.y, a.z, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  p.x[0] = a.x; p.y[0] = a.y; p.z[0] = a.z; p.w[0] = a.w;
+  const bool bf16 = d->dtype == LA2_BF16;
+  hipError_t e = bf16 ? la2::launch_scan_bf16(d->head_dim, reverse, p, s) : la2::launch_scan_f32(d->head_dim, reverse, p, s);
+  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
+// Two reverse scans whose states are transposes of each other (scan 1's y, z are scan 0's z, y): one
+// state pre-pass, one launch (bf16 path).
+la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanArgs& a0, const ScanArgs& a1,
+                                 const float* lambda, void* workspace, hipStream_t s) {
+  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  p.nscan = 2;
+  p.state_transposed = 2;   // scan 1 starts from the transposed state
+  p.x[0] = a0.x; p.y[0] = a0.y; p.z[0] = a0.z; p.w[0] = a0.w;
+  p.x[1] = a1.x; p.y[1] = a1.y; p.z[1] = a1.z; p.w[1] = a1.w;
+  return la2::launch_scan_bf16(d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -140,7 +176,7 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
   const Plan pl = make_plan(desc);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  return run_scan(desc, pl, false, q, k, v, o, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  return run_scan(desc, pl, false, ScanArgs{q, k, v, o}, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
 la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
@@ -158,13 +194,16 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
-  st = run_scan(desc, pl, false, d_o, v, k, dq, lambda, workspace, s);
+  st = run_scan(desc, pl, false, ScanArgs{d_o, v, k, dq}, lambda, workspace, s);
   if (st != LA2_OK) return st;
-  // Algorithm 2, second loop (descending, running dKV): dK = [(dO V^T) * M]^T Q + decay(V) dKV^T
-  st = run_scan(desc, pl, true, v, d_o, q, dk, lambda, workspace, s);
+  // Algorithm 2, second loop (descending, running dKV):
+  //   dV = [(Q K^T) * M]^T dO + decay(K) dKV        reverse scan of (K, Q, dO), state dKV = Q^T dO
+  //   dK = [(dO V^T) * M]^T Q + decay(V) dKV^T      reverse scan of (V, dO, Q), state dKV^T
+  const ScanArgs for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
+  if (desc->dtype == LA2_BF16) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, workspace, s);
+  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
   if (st != LA2_OK) return st;
-  //                                                     dV = [(Q K^T) * M]^T dO + decay(K) dKV
-  return run_scan(desc, pl, true, k, q, d_o, dv, lambda, workspace, s);
+  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
 }
 
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,

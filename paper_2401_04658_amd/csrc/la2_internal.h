@@ -13,12 +13,18 @@ namespace la2 {
 // Algorithm 1 is the forward scan of (q, k, v).  Algorithm 2's first loop is the forward scan of
 // (dO, V, K) and its second loop is the reverse scan of (V, dO, Q) for dK and of (K, Q, dO) for dV.
 struct ScanParams {
-  const void* x;
-  const void* y;
-  const void* z;
-  void* w;
-  const float* lambda;  // [heads], device
-  float* states;        // [chains][nchunks][D][D] fp32 chunk start states, or nullptr (nchunks == 1)
+  // Up to two scans of the same shape, direction and decay can share one launch ("dual" launch):
+  // workgroup 2 i runs scan 0 and workgroup 2 i + 1 runs scan 1 of the same (chain, chunk), so tiles
+  // that both scans read (Algorithm 2's second loop reads Q and dO for dK and for dV) are fetched
+  // from HBM once and served from cache the second time.
+  const void* x[2];
+  const void* y[2];
+  const void* z[2];
+  void* w[2];
+  int32_t nscan;             // 1 or 2
+  int32_t state_transposed;  // bit s set: scan s starts from the TRANSPOSE of the stored chunk state
+  const float* lambda;       // [heads], device
+  float* states;             // [chains][nchunks][D][D] fp32 chunk start states, or nullptr (nchunks == 1)
   int64_t stride_b, stride_h, stride_n;  // elements
   int32_t batch, heads, n;
   int32_t nchunks;       // sequence chunks processed by different workgroups

@@ -245,16 +245,20 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int rg = w >> 1, ch = w & 1;         // row group (32 rows) and value-feature half of this wave
-  const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
+  // dual launch: even workgroups run scan 0, odd workgroups scan 1 of the same (chain, chunk)
+  const int which = (p.nscan == 2) ? (int)(blockIdx.x & 1) : 0;
+  const int wg = (p.nscan == 2) ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
+  const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
   const int bi = chain / p.heads, hi = chain % p.heads;
   const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
-  const __bf16* gx = reinterpret_cast<const __bf16*>(p.x) + base;
-  const __bf16* gy = reinterpret_cast<const __bf16*>(p.y) + base;
-  const __bf16* gz = reinterpret_cast<const __bf16*>(p.z) + base;
+  const __bf16* gx = reinterpret_cast<const __bf16*>(which ? p.x[1] : p.x[0]) + base;
+  const __bf16* gy = reinterpret_cast<const __bf16*>(which ? p.y[1] : p.y[0]) + base;
+  const __bf16* gz = reinterpret_cast<const __bf16*>(which ? p.z[1] : p.z[0]) + base;
   const int n = p.n;
   const int64_t stride_n = p.stride_n;
   const uint32_t chain_bytes = ((uint32_t)(n - 1) * (uint32_t)stride_n + D) * 2u;
-  const __amdgpu_buffer_rsrc_t bw = make_rsrc(reinterpret_cast<__bf16*>(p.w) + base, chain_bytes);
+  const __amdgpu_buffer_rsrc_t bw =
+      make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
   const float l2 = log2f(p.lambda[hi]);
 
   const int nblocks = (n + kB - 1) / kB;
@@ -306,10 +310,14 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   f32x16 kv[SC];
   if (p.states != nullptr) {
     const float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+    const bool tr = (p.state_transposed >> which) & 1;
 #pragma unroll
     for (int b = 0; b < SC; b++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) kv[b][v] = gs[state_index<D>(w, l32, hh, b, v)];
+      for (int v = 0; v < 16; v++) {
+        const int idx = state_index<D>(w, l32, hh, b, v);          // dk * D + dv
+        kv[b][v] = gs[tr ? (idx % D) * D + idx / D : idx];
+      }
   } else {
 #pragma unroll
     for (int b = 0; b < SC; b++) kv[b] = zero16();
@@ -566,8 +574,8 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   const int n = p.n;
   const uint32_t stride_n = (uint32_t)p.stride_n;
   const uint32_t chain_bytes = ((uint32_t)(n - 1) * stride_n + D) * 2u;
-  const __amdgpu_buffer_rsrc_t by = make_rsrc(reinterpret_cast<const __bf16*>(p.y) + base, chain_bytes);
-  const __amdgpu_buffer_rsrc_t bz = make_rsrc(reinterpret_cast<const __bf16*>(p.z) + base, chain_bytes);
+  const __amdgpu_buffer_rsrc_t by = make_rsrc(reinterpret_cast<const __bf16*>(p.y[0]) + base, chain_bytes);
+  const __amdgpu_buffer_rsrc_t bz = make_rsrc(reinterpret_cast<const __bf16*>(p.z[0]) + base, chain_bytes);
   const float l2 = log2f(p.lambda[hi]);
   const int nblocks = (n + kB - 1) / kB;
   const int cb = p.chunk_tokens / kB;
@@ -629,7 +637,7 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
 int block_size_bf16(int) { return kB; }
 
 hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
-  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks;
+  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   if (grid == 0 || p.n == 0) return hipSuccess;
   dim3 g((unsigned)grid), b(kThreads);
   if (head_dim == 128) {

@@ -56,10 +56,10 @@ __global__ __launch_bounds__(kThreads) void scan_f32_kernel(ScanParams p) {
   const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
   const int bi = chain / p.heads, hi = chain % p.heads;
   const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
-  const float* gx = reinterpret_cast<const float*>(p.x) + base;
-  const float* gy = reinterpret_cast<const float*>(p.y) + base;
-  const float* gz = reinterpret_cast<const float*>(p.z) + base;
-  float* gw = reinterpret_cast<float*>(p.w) + base;
+  const float* gx = reinterpret_cast<const float*>(p.x[0]) + base;
+  const float* gy = reinterpret_cast<const float*>(p.y[0]) + base;
+  const float* gz = reinterpret_cast<const float*>(p.z[0]) + base;
+  float* gw = reinterpret_cast<float*>(p.w[0]) + base;
   const int n = p.n;
   const float l2 = log2f(p.lambda[hi]);
   const float lamB = exp2f(l2 * (float)B);
@@ -123,8 +123,8 @@ __global__ __launch_bounds__(kThreads) void chunk_state_f32_kernel(ScanParams p)
   if (REV ? (chunk == 0) : (chunk == p.nchunks - 1)) return;
   const int bi = chain / p.heads, hi = chain % p.heads;
   const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
-  const float* gy = reinterpret_cast<const float*>(p.y) + base;
-  const float* gz = reinterpret_cast<const float*>(p.z) + base;
+  const float* gy = reinterpret_cast<const float*>(p.y[0]) + base;
+  const float* gz = reinterpret_cast<const float*>(p.z[0]) + base;
   const int n = p.n;
   const float l2 = log2f(p.lambda[hi]);
   const float lamB = exp2f(l2 * (float)B);
