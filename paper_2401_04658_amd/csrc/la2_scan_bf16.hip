@@ -2,7 +2,7 @@
 //
 // One workgroup (4 waves) walks the blocks (B = 64 positions) of one sequence chunk of one
 // (batch, head) chain.  The X, Y, Z tiles of the NEXT block stream from HBM straight into LDS
-// (global_load_lds, no registers) while the current block is computed.
+// (global_load_lds, no registers), two blocks ahead of the block being computed (three tile buffers).
 //
 // Work split: wave w owns the 32 value features dv = 32 (w % NT) .. +31 (NT = D / 32) of the output
 // and of the running state, for all key features.  Its slice S[:, dv] of the fp32 state never
@@ -58,7 +58,8 @@ struct Cfg {
   static constexpr int TILE = kB * D;          // elements per tile
   static constexpr int DMA_PER_TILE = TILE / 512;   // wave instructions (1 KiB each) per tile
   static constexpr int DMA_PER_WAVE = DMA_PER_TILE / 4;
-  static constexpr int LW = 40;                // staging row stride (32 features + 8 pad, elements)
+  static constexpr int LW = 32;                // staging row: 32 features = 64 bytes, unpadded, 16-byte chunks
+                                               // XOR-swizzled by (row / 4) % 4 (LDS is full: no room for padding)
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -112,10 +113,22 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__device__ __forceinline__ void dma16(const void* g, __bf16* lds_wave_base) {
-  // each lane copies 16 bytes from its own global address to lds_wave_base + 16 * lane
-  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)g,
-                                   (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+// Direct global -> LDS copy, 16 bytes per lane: lane i reads base + voff (its own byte offset) and
+// writes LDS byte address lds_base + 16 i (lds_base is wave-uniform and travels in M0).  The tiles are
+// read exactly once, so the load carries the non-temporal hint (measured 5-10 % faster).
+// Written as inline assembly on purpose: the compiler then keeps no record of an asynchronous LDS
+// write and inserts no vmcnt(0) wait in front of later LDS reads (it cannot always prove that they
+// touch a different tile buffer).  Completion is tracked by hand: see the s_waitcnt at the end of
+// each block, followed by the workgroup barrier.
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+               :
+               : "v"(voff), "s"(base), "s"(lds_base)
+               : "m0", "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
 // Exchange between lanes l and l + 32 that turns a row fragment in natural k-order (this lane holds
@@ -188,7 +201,8 @@ struct TileLoader {
       const uint32_t off = ((uint32_t)pos * stride_n + (uint32_t)col[i]) * 2u;
       const int dst = 512 * (C::DMA_PER_WAVE * w + i);
 #pragma unroll
-      for (int t = 0; t < NTILES; t++) dma16(g[t] + off, &sT[t][dst]);
+      for (int t = 0; t < NTILES; t++)
+        dma16(g[t], off, __builtin_amdgcn_readfirstlane(lds_offset(&sT[t][dst])));
     }
   }
   // after this wave's loads have landed: zero the rows of a ragged last block
@@ -246,7 +260,13 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   // provably independent of the direct loads in flight into the other
   __shared__ __attribute__((aligned(1024))) __bf16 sT0[3][TILE];
   __shared__ __attribute__((aligned(1024))) __bf16 sT1[3][TILE];
+  __shared__ __attribute__((aligned(1024))) __bf16 sT2[3][TILE];
   __shared__ __attribute__((aligned(16))) __bf16 sW[4][32 * RT * LW];
+  // vector-memory operations a wave issues per block: direct loads (3 tiles) and output stores
+  constexpr int LOADS_PER_BLOCK = 3 * C::DMA_PER_WAVE, STORES_PER_BLOCK = 32 * RT * 4 / 64;
+  // s_waitcnt immediate for "at most N vector-memory operations outstanding" (gfx9 encoding)
+  constexpr int VM_YOUNGER = 2 * STORES_PER_BLOCK + LOADS_PER_BLOCK;
+  constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w % NT;                                  // this wave's value-feature tile
@@ -326,28 +346,34 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 
   // ---- prologue: first block's tiles
   {
-    const int b0 = REV ? blk_hi - 1 : blk_lo;
+    const int b0 = REV ? blk_hi - 1 : blk_lo, b1 = REV ? b0 - 1 : b0 + 1;
     loader.issue(sT0, b0);
+    if (nblk > 1) loader.issue(sT1, b1);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     loader.zero_tail(sT0, b0);
+    if (nblk > 1) loader.zero_tail(sT1, b1);
   }
   __syncthreads();
 
-  // One block of the loop.  The tile buffer index is a compile-time constant (the loop below is
-  // unrolled by two).  Returns false after the last block.
+  // One block of the loop.  Block `it` lives in tile buffer it % 3, which is a compile-time constant
+  // (the loop below is unrolled by three) so that LDS reads of one buffer are provably independent
+  // of the direct loads in flight into the others.  Returns false after the last block.
   // The body is software-pipelined by hand: LDS reads are issued a stage ahead of the MFMAs that
   // consume them, and sched_barrier keeps the compiler from sinking them back next to their uses
   // (which would expose the LDS latency before every MFMA).
 #define LA2_STAGE() __builtin_amdgcn_sched_barrier(0)
   auto block_step = [&](auto cur_tag, int it) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
+    __bf16 (*const sCur)[TILE] = cur == 0 ? sT0 : (cur == 1 ? sT1 : sT2);     // block it
+    __bf16 (*const sNext)[TILE] = cur == 0 ? sT1 : (cur == 1 ? sT2 : sT0);    // block it + 1 (in flight or landed)
+    __bf16 (*const sAhead)[TILE] = cur == 0 ? sT2 : (cur == 1 ? sT0 : sT1);   // block it + 2 (free since block it - 1)
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
-    const bool has_next = it + 1 < nblk;
+    const bool has_next = it + 1 < nblk, has_ahead = it + 2 < nblk;
     const int nb = REV ? blk - 1 : blk + 1;
-    if (has_next) loader.issue(cur ? sT0 : sT1, nb);
-    const __bf16* tX = cur ? sT1[0] : sT0[0];
-    const __bf16* tY = cur ? sT1[1] : sT0[1];
-    const __bf16* tZ = cur ? sT1[2] : sT0[2];
+    if (has_ahead) loader.issue(sAhead, REV ? blk - 2 : blk + 2);
+    const __bf16* tX = sCur[0];
+    const __bf16* tY = sCur[1];
+    const __bf16* tZ = sCur[2];
 
     auto chain = [&](const bf16x8 (&a)[KS], const bf16x8 (&b)[KS]) {
       f32x16 c = zero16();
@@ -450,14 +476,15 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
         bf16x4 pk;
 #pragma unroll
         for (int e = 0; e < 4; e++) pk[e] = (__bf16)acc[i][4 * g + e];
-        *reinterpret_cast<bf16x4*>(stage + (32 * i + l32) * LW + 8 * g + 4 * hh) = pk;
+        const int row = 32 * i + l32;
+        *reinterpret_cast<bf16x4*>(stage + row * LW + 8 * (g ^ ((row >> 2) & 3)) + 4 * hh) = pk;
       }
     // same-wave LDS write -> read: ordered by the LDS queue, no workgroup barrier needed
 #pragma unroll
     for (int i = 0; i < 32 * RT * 4 / 64; i++) {
       const int id = l + 64 * i;
       const int row = id >> 2, cc = id & 3;
-      const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + cc * 8);
+      const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
       const uint32_t off = ((uint32_t)(blk * kB + 32 * rt0 + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
       __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
     }
@@ -477,14 +504,19 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 #pragma unroll
         for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][s][q], zd, kv[t]);
       }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's direct loads of the next block have landed
-    loader.zero_tail(cur ? sT0 : sT1, nb);
+    // This wave's direct loads of block it + 1 must have landed.  Vector-memory operations complete in
+    // issue order; younger than those loads are the stores of blocks it - 1 and it and the loads of
+    // block it + 2 (if they were issued; otherwise wait for everything).
+    if (has_ahead) __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    loader.zero_tail(sNext, nb);
     lds_barrier();                       // next tiles visible to all waves; current tiles free
     return true;
   };
-  for (int it = 0; it < nblk; it += 2) {
+  for (int it = 0; it < nblk; it += 3) {
     if (!block_step(std::integral_constant<int, 0>{}, it)) break;
     if (!block_step(std::integral_constant<int, 1>{}, it + 1)) break;
+    if (!block_step(std::integral_constant<int, 2>{}, it + 2)) break;
   }
 #undef LA2_STAGE
 }
