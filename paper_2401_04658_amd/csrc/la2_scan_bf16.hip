@@ -143,6 +143,24 @@ __device__ __forceinline__ bf16x8 to_perm_order(bf16x8 f) {
   return x.v;
 }
 
+// Pins a value to this point of the program: an empty volatile asm that "rewrites" the register.
+// Arithmetic and MFMA intrinsics have no side effects, so instruction selection may place them
+// anywhere between their operands and their first use, across scheduling barriers.  Volatile asm
+// statements keep their order, so a value pinned at the end of a slot is computed inside that slot,
+// and everything computed from the pinned value comes later.
+template <typename T>
+__device__ __forceinline__ void pin(T& x) {
+  asm volatile("" : "+v"(x));
+}
+
+// The same for a value that is only ever an MFMA operand, placed right before its use: it has to be
+// in an accumulation register there.  LDS reads can target those directly, which keeps such operands
+// out of the (scarcer) registers that the vector ALU can address.
+template <typename T>
+__device__ __forceinline__ void pin_acc(T& x) {
+  asm volatile("" : "+a"(x));
+}
+
 // Per-lane addressing of the swizzled tiles.
 template <int D>
 struct LaneAddr {
@@ -205,6 +223,24 @@ struct TileLoader {
         dma16(g[t], off, __builtin_amdgcn_readfirstlane(lds_offset(&sT[t][dst])));
     }
   }
+  // The same loads one at a time (j = 0 .. NTILES DMA_PER_WAVE - 1), so that they can be spread over
+  // the block's compute slots: offsets() once per block, then issue_one(j).
+  // `valid` false (no such block): every lane reads the chain's first 16 bytes instead, a single
+  // cache line per instruction, so that the loads can be issued unconditionally (no branches inside the
+  // hand-scheduled block body, same count of outstanding operations for every block).
+  __device__ __forceinline__ void offsets(int blk, bool valid, uint32_t (&off)[C::DMA_PER_WAVE]) const {
+#pragma unroll
+    for (int i = 0; i < C::DMA_PER_WAVE; i++) {
+      const int pos = min(blk * kB + row[i], n - 1);
+      off[i] = valid ? ((uint32_t)pos * stride_n + (uint32_t)col[i]) * 2u : 0u;
+    }
+  }
+  __device__ __forceinline__ void issue_one(__bf16 (*sT)[C::TILE], const uint32_t (&off)[C::DMA_PER_WAVE],
+                                            int j) const {
+    const int i = j / NTILES, t = j % NTILES;
+    const int dst = 512 * (C::DMA_PER_WAVE * w + i);
+    dma16(g[t], off[i], __builtin_amdgcn_readfirstlane(lds_offset(&sT[t][dst])));
+  }
   // after this wave's loads have landed: zero the rows of a ragged last block
   __device__ __forceinline__ void zero_tail(__bf16 (*sT)[C::TILE], int blk) const {
     if ((blk + 1) * kB > n) {
@@ -229,25 +265,34 @@ __device__ __forceinline__ int state_index(int dvt, int l32, int hh, int t, int 
   return transposed ? dv * D + dk : dk * D + dv;
 }
 
+// A wave-uniform value, told to the compiler (lands in a scalar register instead of a vector one).
+__device__ __forceinline__ float uniform(float x) {
+  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
+}
+
 // Row weights of the state update, S <- lambda^B S + Y^T decay(Z) with row c weighted lambda^(B-1-c)
-// (forward) or lambda^c (reverse), applied to the Z fragments (permuted k-order, 16 rows from c0):
-//   weight(c0, hh, j) = step(c0) * fj[j],  all exponents non-negative.
+// (forward) or lambda^c (reverse), applied to the Z fragments (permuted k-order, 16 rows from c0).
+// Element j of lane half hh is row c0 + 4 hh + nj, nj = 8 (j / 4) + j % 4.  The weight is split into
+// a per-lane factor (one exp2 per fragment) and a wave-uniform factor per element:
+//   forward  lambda^(B-16-c0 + 4 (1-hh)) * lambda^(11-nj)      reverse  lambda^(c0 + 4 hh) * lambda^nj
+// All exponents are non-negative.
 template <bool REV>
 struct UpdateDecay {
-  float fj[8];
+  float gj[8];   // wave-uniform
   float l2;
-  __device__ __forceinline__ UpdateDecay(float l2_, int hh) : l2(l2_) {
+  int hh;
+  __device__ __forceinline__ UpdateDecay(float l2_, int hh_) : l2(l2_), hh(hh_) {
 #pragma unroll
     for (int j = 0; j < 8; j++) {
-      const int o = 8 * (j >> 2) + 4 * hh + (j & 3);   // perm(0, hh, j)
-      fj[j] = exp2f(l2 * (float)(REV ? o : 15 - o));
+      const int nj = 8 * (j >> 2) + (j & 3);
+      gj[j] = uniform(exp2f(l2 * (float)(REV ? nj : 11 - nj)));
     }
   }
   __device__ __forceinline__ bf16x8 apply(bf16x8 z, int c0) const {
-    const float step = fast_exp2(l2 * (float)(REV ? c0 : kB - 16 - c0));
+    const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh : kB - 16 - c0 + 4 * (1 - hh)));
     bf16x8 r;
 #pragma unroll
-    for (int j = 0; j < 8; j++) r[j] = (__bf16)((float)z[j] * (step * fj[j]));
+    for (int j = 0; j < 8; j++) r[j] = (__bf16)((float)z[j] * (step * gj[j]));
     return r;
   }
 };
@@ -265,15 +310,27 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   // vector-memory operations a wave issues per block: direct loads (3 tiles) and output stores
   constexpr int LOADS_PER_BLOCK = 3 * C::DMA_PER_WAVE, STORES_PER_BLOCK = 32 * RT * 4 / 64;
   // s_waitcnt immediate for "at most N vector-memory operations outstanding" (gfx9 encoding)
-  constexpr int VM_YOUNGER = 2 * STORES_PER_BLOCK + LOADS_PER_BLOCK;
+  constexpr int VM_YOUNGER = STORES_PER_BLOCK + LOADS_PER_BLOCK;
   constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w % NT;                                  // this wave's value-feature tile
   const int rt0 = (C::WPD == 1) ? 0 : (w / NT) * RT;       // its first row tile
-  // dual launch: even workgroups run scan 0, odd workgroups scan 1 of the same (chain, chunk)
-  const int which = (p.nscan == 2) ? (int)(blockIdx.x & 1) : 0;
-  const int wg = (p.nscan == 2) ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
+  // Dual launch: two workgroups run scan 0 and scan 1 of the same (chain, chunk).  Workgroups are
+  // dealt to the 8 XCDs round-robin by index and every XCD has its own L2, so the two partners are
+  // the workgroups i and i + 8 of a group of 16: same XCD, dispatched together, and the tiles both
+  // read are in that XCD's L2 for whichever comes second.  (A launch whose pair count is not a
+  // multiple of 8 pairs neighbours instead; that is correct, only the tile sharing is weaker.)
+  int which = 0, wg = (int)blockIdx.x;
+  if (p.nscan == 2) {
+    if (((gridDim.x >> 1) & 7) == 0) {
+      which = (int)(blockIdx.x >> 3) & 1;
+      wg = (int)((blockIdx.x >> 4) << 3) | (int)(blockIdx.x & 7);
+    } else {
+      which = (int)(blockIdx.x & 1);
+      wg = (int)(blockIdx.x >> 1);
+    }
+  }
   const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
   const int bi = chain / p.heads, hi = chain % p.heads;
   const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
@@ -311,19 +368,35 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
     for (int t = 0; t < NT; t++) kv[t] = zero16();
   }
 
+  // The two key tiles of the block as seen from this wave: slot 0 / slot 1.  d = 128: key tiles 0, 1.
+  // d = 64: slot 0 is the wave's own (diagonal) key tile, slot 1 the other one.
+  const int ct0 = (RT == 2) ? 0 : rt0, ct1 = 1 - ct0;
+  // Besides the diagonal pairs one (row tile, key tile) pair exists per block: forward the later row
+  // tile sees the earlier key tile, reverse the earlier row tile sees the later key tile.
+  constexpr int OFF_RT = REV ? 0 : 1;                          // row tile of that pair
+  const bool has_off = (RT == 2) || (rt0 == OFF_RT);           // wave-uniform: this wave owns that row tile
+  constexpr int OFF_ACC = (RT == 2) ? OFF_RT : 0;              // its index among the wave's row tiles
+  constexpr int OFF_SLOT = (RT == 2) ? 1 - OFF_RT : 1;         // slot of that pair's key tile
+
   // ---- per-lane constants.  Score tile S^T[c][r]: this lane's position is column l32, accumulator
   // element v is key row cc[v] = 8 (v / 4) + 4 hh + v % 4 of the key tile.  Decay mask lambda^|r-c|
   // with non-negative exponents only (lambda^r * lambda^-c would overflow):
   //   diagonal tile (key tile == row tile): lambda^(l32 - cc[v]) on the causal side, else 0
   //   the other tile (32 rows away):        lambda^(l32 + 32 - cc[v])      (reverse: l32, cc swapped)
-  float dg[16], od[16];
+  // A wave that does not own the off-diagonal pair (d = 64) computes it all the same, branch-free,
+  // with an all-zero mask.
+  // The off-diagonal mask is split into a per-lane factor and a wave-uniform factor per element
+  // (cc[v] = mv + 4 hh, mv = 8 (v / 4) + v % 4):
+  //   forward  lambda^(l32 + 5 - 4 hh) * lambda^(27 - mv)       reverse  lambda^(32 - l32 + 4 hh) * lambda^mv
+  float dg[16], ou[16];
 #pragma unroll
   for (int v = 0; v < 16; v++) {
-    const int cc = 8 * (v >> 2) + 4 * hh + (v & 3);
-    const int e = REV ? cc - l32 : l32 - cc;
+    const int mv = 8 * (v >> 2) + (v & 3);
+    const int e = REV ? mv + 4 * hh - l32 : l32 - mv - 4 * hh;
     dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
-    od[v] = exp2f(l2 * (float)(e + 32));
+    ou[v] = uniform(exp2f(l2 * (float)(REV ? mv : 27 - mv)));
   }
+  const float oa = has_off ? exp2f(l2 * (float)(REV ? 32 - l32 + 4 * hh : l32 + 5 - 4 * hh)) : 0.f;
   // weight of the carried state at this lane's position r = 32 rt + l32: forward lambda^(r+1),
   // reverse lambda^(B-r)
   float inter_scale[RT];
@@ -334,15 +407,6 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   }
   const UpdateDecay<REV> decay(l2, hh);
   const float lamB = exp2f(l2 * (float)kB);
-  // The two key tiles of the block as seen from this wave: slot 0 / slot 1.  d = 128: key tiles 0, 1.
-  // d = 64: slot 0 is the wave's own (diagonal) key tile, slot 1 the other one.
-  const int ct0 = (RT == 2) ? 0 : rt0, ct1 = 1 - ct0;
-  // Besides the diagonal pairs one (row tile, key tile) pair exists per block: forward the later row
-  // tile sees the earlier key tile, reverse the earlier row tile sees the later key tile.
-  constexpr int OFF_RT = REV ? 0 : 1;                          // row tile of that pair
-  const bool has_off = (RT == 2) || (rt0 == OFF_RT);           // wave-uniform: this wave owns that row tile
-  constexpr int OFF_ACC = (RT == 2) ? OFF_RT : 0;              // its index among the wave's row tiles
-  constexpr int OFF_SLOT = (RT == 2) ? 1 - OFF_RT : 1;         // slot of that pair's key tile
 
   // ---- prologue: first block's tiles
   {
@@ -355,170 +419,269 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   }
   __syncthreads();
 
+  // Row fragments (natural k-order, only ever MFMA operands) are read from LDS two slots ahead of
+  // the MFMAs that consume them: the X rows of this wave's row tiles for phase 1, and again together
+  // with the Y rows of the same (diagonal) key tiles and of the off-diagonal pair's key tile for
+  // phase 2.  (Reading X twice costs LDS bandwidth that is there; holding a block's fragments for two
+  // phases costs registers that are not.)  The first two k-steps of phase 1 are read across the
+  // barrier, underneath the last MFMAs of the previous block.
+  constexpr int AHEAD = 2;
+  bf16x8 xa[RT][KS];
+  auto read_xa = [&](const __bf16 (*sB)[TILE], int ks) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < RT; i++) xa[i][ks] = la.read_row(sB[0], rt0 + i, ks);
+  };
+#pragma unroll
+  for (int ks = 0; ks < AHEAD; ks++) read_xa(sT0, ks);
+
+  // State tile ks / 2, k-step ks % 2 as a bf16 MFMA operand in NATURAL k-order: the accumulator
+  // layout gives permuted order, the exchange between the wave's halves undoes it, so that the X
+  // fragments serve the score product and the inter-block product unchanged.
+  auto state_operand = [&](int ks) __attribute__((always_inline)) {
+    bf16x8 f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) f[j] = (__bf16)kv[ks >> 1][8 * (ks & 1) + j];
+    return to_perm_order(f);   // the exchange is its own inverse
+  };
+
+  // Finished output of the previous block (transposed: value feature x position), stored while the
+  // next block computes; and the first state operand of the block about to be computed.
+  f32x16 outp[RT];
+#pragma unroll
+  for (int i = 0; i < RT; i++) outp[i] = zero16();
+  bf16x8 sa_first = state_operand(0);
+  __bf16* const stage = sW[w];
+  constexpr int NST = 32 * RT * 4 / 64;   // 16-byte stores per lane and block
+  // Output of block `oblk` in three steps: pack to bf16 and stage through LDS (so that the stores are
+  // 16 bytes per lane, 64 contiguous bytes per row); read back; store.  `valid` false (no previous
+  // block): the offset is pushed out of the buffer's range and the stores are dropped.
+  auto out_pack = [&](int i) __attribute__((always_inline)) {
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      bf16x4 pk;
+#pragma unroll
+      for (int e = 0; e < 4; e++) pk[e] = (__bf16)outp[i][4 * g + e];
+      const int row = 32 * i + l32;
+      *reinterpret_cast<bf16x4*>(stage + row * LW + 8 * (g ^ ((row >> 2) & 3)) + 4 * hh) = pk;
+    }
+  };
+  auto out_read = [&](i32x4 (&ov)[NST]) __attribute__((always_inline)) {
+    // same-wave LDS write -> read: ordered by the LDS queue, no workgroup barrier needed
+#pragma unroll
+    for (int i = 0; i < NST; i++) {
+      const int id = l + 64 * i;
+      const int row = id >> 2, cc = id & 3;
+      ov[i] = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
+    }
+  };
+  auto out_store = [&](const i32x4 (&ov)[NST], int oblk, bool valid) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < NST; i++) {
+      const int id = l + 64 * i;
+      const int row = id >> 2, cc = id & 3;
+      const uint32_t off = ((uint32_t)(oblk * kB + 32 * rt0 + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
+      __builtin_amdgcn_raw_buffer_store_b128(ov[i], bw, valid ? off : 0xFFFFFFF0u, 0, 0);
+    }
+  };
+
   // One block of the loop.  Block `it` lives in tile buffer it % 3, which is a compile-time constant
-  // (the loop below is unrolled by three) so that LDS reads of one buffer are provably independent
-  // of the direct loads in flight into the others.  Returns false after the last block.
-  // The body is software-pipelined by hand: LDS reads are issued a stage ahead of the MFMAs that
-  // consume them, and sched_barrier keeps the compiler from sinking them back next to their uses
-  // (which would expose the LDS latency before every MFMA).
-#define LA2_STAGE() __builtin_amdgcn_sched_barrier(0)
-  auto block_step = [&](auto cur_tag, int it) -> bool {
+  // (the loop below is unrolled by three).
+  //
+  // A workgroup is one wave per SIMD, so nothing but this wave's own instruction order overlaps the
+  // matrix pipe with LDS reads, conversions, masks and the issue of loads and stores.  The body is
+  // therefore branch-free and written as a sequence of SLOTS: a slot holds a few MFMAs plus the side
+  // work that should run in their shadow; values produced in a slot are pinned at its end and a
+  // scheduling barrier closes it, so that the compiler keeps the slots apart and in order (inside
+  // a slot it interleaves freely).  The phases of block it:
+  //   1  inter-block  W^T = State^T X^T       (KS slots)  + output of block it-1: pack, stage, store;
+  //                                                         direct loads of block it+2; next state
+  //                                                         operand; Z reads
+  //   2  score chains S^T = Y X^T             (KS slots)  + rest of the direct loads; lambda^B on the
+  //                                                         state; position decay on W^T; update
+  //                                                         weights on Z
+  //   3  state update State += Y^T decay(Z)   (4 slots)   + decay masks of the scores
+  //      then the barrier and the first row fragments of block it+1
+  //   4  intra-block  W^T += Z^T P^T          (one slot)  + first state operand of block it+1
+  // Returns false after the last block.
+#define LA2_SLOT_END()                 \
+  do {                                 \
+    asm volatile("" ::: "memory");     \
+    __builtin_amdgcn_sched_barrier(0); \
+  } while (0)
+  constexpr int NDMA = 3 * C::DMA_PER_WAVE;   // direct loads per wave and block, one per slot of 1, 2
+  static_assert(NDMA <= 2 * KS, "one direct load per slot");
+  auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
     __bf16 (*const sCur)[TILE] = cur == 0 ? sT0 : (cur == 1 ? sT1 : sT2);     // block it
     __bf16 (*const sNext)[TILE] = cur == 0 ? sT1 : (cur == 1 ? sT2 : sT0);    // block it + 1 (in flight or landed)
     __bf16 (*const sAhead)[TILE] = cur == 0 ? sT2 : (cur == 1 ? sT0 : sT1);   // block it + 2 (free since block it - 1)
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
     const bool has_next = it + 1 < nblk, has_ahead = it + 2 < nblk;
-    const int nb = REV ? blk - 1 : blk + 1;
-    if (has_ahead) loader.issue(sAhead, REV ? blk - 2 : blk + 2);
-    const __bf16* tX = sCur[0];
+    const int nb = REV ? blk - 1 : blk + 1, pb = REV ? blk + 1 : blk - 1;
     const __bf16* tY = sCur[1];
     const __bf16* tZ = sCur[2];
+    uint32_t doff[C::DMA_PER_WAVE];
+    loader.offsets(REV ? blk - 2 : blk + 2, has_ahead, doff);
 
-    auto chain = [&](const bf16x8 (&a)[KS], const bf16x8 (&b)[KS]) {
-      f32x16 c = zero16();
+    bf16x8 zf[2][2];     // Z columns of this wave's value tile: [key-tile slot][k-step], permuted k-order
+    bf16x8 zd[2][2];     // the same, weighted for the state update
+    bf16x8 yt[NT][2][2]; // Y columns (key features): [key-feature tile][slot][k-step], permuted k-order
+    bf16x8 xb[RT][KS], yb[RT][KS], yo[KS];   // phase 2 operands
+    auto read_xy = [&](int ks) __attribute__((always_inline)) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) c = mfma(a[ks], b[ks], c);
-      return c;
+      for (int i = 0; i < RT; i++) xb[i][ks] = la.read_row(sCur[0], rt0 + i, ks);
+#pragma unroll
+      for (int i = 0; i < RT; i++) yb[i][ks] = la.read_row(sCur[1], rt0 + i, ks);
+      if (RT == 1) yo[ks] = la.read_row(sCur[1], ct1, ks);
     };
-    auto mask_pack = [&](bf16x8 (&pf)[2], const f32x16& st, const float (&m)[16]) {
+    auto read_yt = [&](int sq) __attribute__((always_inline)) {   // operands of update k-step sq
+      const int s = sq >> 1, q = sq & 1;
 #pragma unroll
-      for (int v = 0; v < 16; v++) pf[v >> 3][v & 7] = (__bf16)(st[v] * m[v]);
+      for (int t = 0; t < NT; t++) yt[t][s][q] = la.read_cols(tY, 32 * (s ? ct1 : ct0) + 16 * q, t);
     };
 
-    // ---- stage 0: X rows of this wave's row tiles and Y rows of the same (diagonal) key tiles
-    bf16x8 xf[RT][KS], yf[RT][KS], yo[KS];
+    // ---- phase 1: W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] from the state in registers
+    f32x16 inter[RT];
 #pragma unroll
-    for (int i = 0; i < RT; i++)
+    for (int i = 0; i < RT; i++) inter[i] = zero16();
+    i32x4 ov[NST];
+    bf16x8 sa = sa_first;
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) xf[i][ks] = la.read_row(tX, rt0 + i, ks);
+    for (int ks = 0; ks < KS; ks++) {
 #pragma unroll
-    for (int i = 0; i < RT; i++)
+      for (int i = 0; i < RT; i++) pin_acc(xa[i][ks]);
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) yf[i][ks] = la.read_row(tY, rt0 + i, ks);
-    LA2_STAGE();
-    // ---- stage 1: Z fragments (all 64 rows, this wave's value tile, permuted k-order); for d = 64 the
-    // Y rows of the other key tile.  Score tiles S^T[c][r] = sum_k Y[c][k] X[r][k].
-    bf16x8 zf[2][2];   // [slot][k-step within the key tile]
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      zf[0][q] = la.read_cols(tZ, 32 * ct0 + 16 * q, dvt);
-      zf[1][q] = la.read_cols(tZ, 32 * ct1 + 16 * q, dvt);
-    }
-    if (RT == 1 && has_off) {
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) yo[ks] = la.read_row(tY, ct1, ks);
-    }
-    LA2_STAGE();
-    f32x16 sd[RT], so;
-#pragma unroll
-    for (int i = 0; i < RT; i++) sd[i] = chain(yf[i], xf[i]);
-    if (RT == 2) so = chain(yf[(RT == 2) ? OFF_SLOT : 0], xf[OFF_ACC]);
-    else if (has_off) so = chain(yo, xf[0]);
-    LA2_STAGE();
-
-    // ---- inter-block part from registers: W^T[dv][r] = sum_dk S[dk][dv] X[r][dk].  The state tiles are
-    // the A operand in permuted k-order; the X fragments are brought into the same order.
-    f32x16 acc[RT];
-    {
-      bf16x8 sa[KS];
-#pragma unroll
-      for (int t = 0; t < NT; t++)
-#pragma unroll
-        for (int q = 0; q < 2; q++)
-#pragma unroll
-          for (int j = 0; j < 8; j++) sa[2 * t + q][j] = (__bf16)kv[t][8 * q + j];
-#pragma unroll
-      for (int i = 0; i < RT; i++) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) xf[i][ks] = to_perm_order(xf[i][ks]);
-        acc[i] = chain(sa, xf[i]);
+      for (int i = 0; i < RT; i++) inter[i] = mfma(sa, xa[i][ks], inter[i]);
+      if (ks + AHEAD < KS) read_xa(sCur, ks + AHEAD);
+      else read_xy(ks + AHEAD - KS);
+      if (ks + 1 < KS) { sa = state_operand(ks + 1); pin(sa); }
+      if (ks < NDMA) loader.issue_one(sAhead, doff, ks);
+      if (ks < 4) {
+        const int s = ks >> 1, q = ks & 1;
+        zf[s][q] = la.read_cols(tZ, 32 * (s ? ct1 : ct0) + 16 * q, dvt);
       }
+      if (ks < RT) out_pack(ks);
+      if (ks == RT) out_read(ov);
+      if (ks == RT + 1) out_store(ov, pb, it > 0);
+#pragma unroll
+      for (int i = 0; i < RT; i++) pin(inter[i]);
+      LA2_SLOT_END();
     }
-    // masked scores (bf16) while the inter-block MFMAs run
+
+    // ---- phase 2: score tiles S^T[c][r] = sum_k Y[c][k] X[r][k]
+    f32x16 sd[RT], so = zero16();
+#pragma unroll
+    for (int i = 0; i < RT; i++) sd[i] = zero16();
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+#pragma unroll
+      for (int i = 0; i < RT; i++) { pin_acc(xb[i][ks]); pin_acc(yb[i][ks]); }
+      if (RT == 1) pin_acc(yo[ks]);
+#pragma unroll
+      for (int i = 0; i < RT; i++) sd[i] = mfma(yb[i][ks], xb[i][ks], sd[i]);
+      if (RT == 2) so = mfma(yb[(RT == 2) ? OFF_SLOT : 0][ks], xb[OFF_ACC][ks], so);
+      else so = mfma(yo[ks], xb[0][ks], so);
+      if (ks + AHEAD < KS) read_xy(ks + AHEAD);
+      if (ks == KS - 1) read_yt(0);
+      if (KS + ks < NDMA) loader.issue_one(sAhead, doff, KS + ks);
+      // the fp32 state takes its lambda^B for the update (all its bf16 operands have been made)
+      if (ks % (KS / NT) == 0) {
+        const int t = ks / (KS / NT);
+#pragma unroll
+        for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
+        pin(kv[t]);
+      }
+      // the carried part takes the decay at this lane's position
+      if ((ks & 1) && (ks >> 1) < RT) {
+        const int i = ks >> 1;
+#pragma unroll
+        for (int v = 0; v < 16; v++) inter[i][v] *= inter_scale[i];
+        pin(inter[i]);
+      }
+      if (ks >= KS - 4) {
+        const int f = ks - (KS - 4), s = f >> 1, q = f & 1;
+        zd[s][q] = decay.apply(zf[s][q], 32 * (s ? ct1 : ct0) + 16 * q);
+        pin(zd[s][q]);
+      }
+#pragma unroll
+      for (int i = 0; i < RT; i++) pin(sd[i]);
+      pin(so);
+      LA2_SLOT_END();
+    }
+
+    // ---- phase 3: state slice <- lambda^B state + Y^T decay(Z), contraction over this block's rows in
+    // 4 k-steps; meanwhile the decay masks turn the finished score tiles into bf16 operands.
+    // (After the last block the state is not needed; the update runs anyway, branch-free.)
     bf16x8 pd[RT][2], po[2];
 #pragma unroll
-    for (int i = 0; i < RT; i++) mask_pack(pd[i], sd[i], dg);
-    if (has_off) mask_pack(po, so, od);
-    // the carried state's decay at this lane's position, then the intra-block part P Z
+    for (int sq = 0; sq < 4; sq++) {
+#pragma unroll
+      for (int t = 0; t < NT; t++) pin_acc(yt[t][sq >> 1][sq & 1]);
+#pragma unroll
+      for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][sq >> 1][sq & 1], zd[sq >> 1][sq & 1], kv[t]);
+      if (sq + 1 < 4) read_yt(sq + 1);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int v = 4 * sq + e;
+#pragma unroll
+        for (int i = 0; i < RT; i++) pd[i][v >> 3][v & 7] = (__bf16)(sd[i][v] * dg[v]);
+        po[v >> 3][v & 7] = (__bf16)((so[v] * oa) * ou[v]);
+      }
+#pragma unroll
+      for (int i = 0; i < RT; i++) pin(pd[i][sq >> 1]);
+      pin(po[sq >> 1]);
+#pragma unroll
+      for (int t = 0; t < NT; t++) pin(kv[t]);
+      LA2_SLOT_END();
+    }
+
+    if (has_next) {
+      // This wave's direct loads of block it + 1 must have landed.  Vector-memory operations complete
+      // in issue order; younger than those loads are the stores of block it - 1 and the loads (real
+      // or dummy) of block it + 2.
+      __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
+      loader.zero_tail(sNext, nb);
+      lds_barrier();                       // next tiles visible to all waves; current tiles free
+#pragma unroll
+      for (int ks = 0; ks < AHEAD; ks++) read_xa(sNext, ks);
+    }
+    LA2_SLOT_END();
+
+    // ---- phase 4: intra-block part Z^T P^T on top of the decayed carried part
 #pragma unroll
     for (int i = 0; i < RT; i++) {
 #pragma unroll
-      for (int v = 0; v < 16; v++) acc[i][v] *= inter_scale[i];
-#pragma unroll
-      for (int q = 0; q < 2; q++) acc[i] = mfma(zf[(RT == 2) ? i : 0][q], pd[i][q], acc[i]);
+      for (int q = 0; q < 2; q++) inter[i] = mfma(zf[(RT == 2) ? i : 0][q], pd[i][q], inter[i]);
     }
-    if (has_off) {
 #pragma unroll
-      for (int q = 0; q < 2; q++) acc[OFF_ACC] = mfma(zf[OFF_SLOT][q], po[q], acc[OFF_ACC]);
+    for (int q = 0; q < 2; q++) inter[OFF_ACC] = mfma(zf[OFF_SLOT][q], po[q], inter[OFF_ACC]);
+    sa_first = state_operand(0);
+    pin(sa_first);
+#pragma unroll
+    for (int i = 0; i < RT; i++) {
+      outp[i] = inter[i];
+      pin(outp[i]);
     }
-    LA2_STAGE();
-
-    // ---- operands of the state update: Y columns (key features) over all 64 rows, permuted k-order
-    bf16x8 yt[NT][2][2];   // [key-feature tile][slot][k-step]
-    if (has_next) {
-#pragma unroll
-      for (int t = 0; t < NT; t++)
-#pragma unroll
-        for (int q = 0; q < 2; q++) {
-          yt[t][0][q] = la.read_cols(tY, 32 * ct0 + 16 * q, t);
-          yt[t][1][q] = la.read_cols(tY, 32 * ct1 + 16 * q, t);
-        }
-    }
-    LA2_STAGE();
-
-    // ---- output: stage this wave's rows x 32 features, then 16-byte stores (64 bytes per row)
-    __bf16* stage = sW[w];
-#pragma unroll
-    for (int i = 0; i < RT; i++)
-#pragma unroll
-      for (int g = 0; g < 4; g++) {
-        bf16x4 pk;
-#pragma unroll
-        for (int e = 0; e < 4; e++) pk[e] = (__bf16)acc[i][4 * g + e];
-        const int row = 32 * i + l32;
-        *reinterpret_cast<bf16x4*>(stage + row * LW + 8 * (g ^ ((row >> 2) & 3)) + 4 * hh) = pk;
-      }
-    // same-wave LDS write -> read: ordered by the LDS queue, no workgroup barrier needed
-#pragma unroll
-    for (int i = 0; i < 32 * RT * 4 / 64; i++) {
-      const int id = l + 64 * i;
-      const int row = id >> 2, cc = id & 3;
-      const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
-      const uint32_t off = ((uint32_t)(blk * kB + 32 * rt0 + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
-      __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
-    }
-
-    if (!has_next) return false;         // the state after a chunk's last block is never used
-
-    // ---- state slice <- lambda^B state + Y^T decay(Z), contraction over this block's rows
-#pragma unroll
-    for (int t = 0; t < NT; t++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
-#pragma unroll
-    for (int s = 0; s < 2; s++)
-#pragma unroll
-      for (int q = 0; q < 2; q++) {
-        const bf16x8 zd = decay.apply(zf[s][q], 32 * (s ? ct1 : ct0) + 16 * q);
-#pragma unroll
-        for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][s][q], zd, kv[t]);
-      }
-    // This wave's direct loads of block it + 1 must have landed.  Vector-memory operations complete in
-    // issue order; younger than those loads are the stores of blocks it - 1 and it and the loads of
-    // block it + 2 (if they were issued; otherwise wait for everything).
-    if (has_ahead) __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
-    loader.zero_tail(sNext, nb);
-    lds_barrier();                       // next tiles visible to all waves; current tiles free
-    return true;
+    LA2_SLOT_END();
+    return has_next;
   };
-  for (int it = 0; it < nblk; it += 3) {
+  int it = 0;
+  for (;; it += 3) {
     if (!block_step(std::integral_constant<int, 0>{}, it)) break;
-    if (!block_step(std::integral_constant<int, 1>{}, it + 1)) break;
-    if (!block_step(std::integral_constant<int, 2>{}, it + 2)) break;
+    if (!block_step(std::integral_constant<int, 1>{}, it + 1)) { it += 1; break; }
+    if (!block_step(std::integral_constant<int, 2>{}, it + 2)) { it += 2; break; }
   }
-#undef LA2_STAGE
+  // output of the last block
+  {
+    const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
+    i32x4 ov[NST];
+#pragma unroll
+    for (int i = 0; i < RT; i++) out_pack(i);
+    out_read(ov);
+    out_store(ov, blk, true);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
+  }
+#undef LA2_SLOT_END
 }
 
 // Local state of every chunk that has a successor: forward sum_c lambda^(C-1-c) y_c^T z_c over the
