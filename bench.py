@@ -42,7 +42,7 @@ def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
     bytes_alg = 8 * d * th            # read Q, K, V and write O once, bf16
     flops_alg = flops_per_token_head(B, d, "fwd") * th
     return {
-        "kernel": "scan_bf16_kernel<128,fwd> (la2_fwd, %s)" % wl.name,
+        "kernel": "scan_bf16_half_kernel<fwd> (la2_fwd, %s)" % wl.name,
         "bound": "hbm",
         "achieved": round(bytes_alg / (k_ms * 1e-3) / 1e9, 1),
         "peak": PEAK_HBM_GBS,

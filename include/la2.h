@@ -117,9 +117,10 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
                            float* kv_state, void* o, void* hip_stream);
 
 /*
- * Block size B (rows of the intra-block tile) the library uses for this descriptor; results do
- * not depend on it beyond rounding.  Returns 0 for an invalid descriptor.  Used to report FLOPs
- * with the formula of Algorithms 1 and 2.
+ * Block size B (rows of the intra-block tile, Algorithm 1) of the scan kernel the library launches
+ * for this descriptor under the current la2_set_scan_variant(); results do not depend on it beyond
+ * rounding.  Returns 0 for an invalid descriptor.  Used to report FLOPs with the formula of
+ * Algorithms 1 and 2.
  */
 int32_t la2_block_size(const la2_desc* desc);
 
@@ -129,6 +130,18 @@ int32_t la2_block_size(const la2_desc* desc);
  * by la2_workspace_bytes().  Results do not depend on it beyond rounding.
  */
 void la2_set_chunk_tokens(int32_t tokens);
+
+/*
+ * Test / tuning knob: which bf16 head_dim-128 scan kernel la2_fwd / la2_bwd launch.
+ *   0  automatic (currently the half-block kernel: blocks of 32 positions, up to two workgroups per
+ *      compute unit; it measured faster than the full-block kernel at every launch size)
+ *   1  the full-block kernel (blocks of 64 positions, one workgroup per compute unit)
+ *   2  the half-block kernel
+ * Other values are taken as 0.  Both kernels implement Algorithm 1's block recurrence (the block
+ * size is the algorithm's free parameter B); results differ by rounding only.  Process-global, not
+ * thread-safe.  Ignored for fp32 and for head_dim 64.
+ */
+void la2_set_scan_variant(int32_t variant);
 
 /* Static, NUL-terminated description of a status code. */
 const char* la2_status_string(la2_status status);

@@ -55,6 +55,8 @@ def load():
     lib.la2_block_size.restype = i32
     lib.la2_set_chunk_tokens.argtypes = [i32]
     lib.la2_set_chunk_tokens.restype = None
+    lib.la2_set_scan_variant.argtypes = [i32]
+    lib.la2_set_scan_variant.restype = None
     lib.la2_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_fwd.restype = ctypes.c_int
     lib.la2_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -112,6 +114,10 @@ def la2_block_size(t):
 
 def la2_set_chunk_tokens(tokens):
     load().la2_set_chunk_tokens(int(tokens))
+
+
+def la2_set_scan_variant(variant):
+    load().la2_set_scan_variant(int(variant))
 
 
 def _workspace(t, op, workspace):

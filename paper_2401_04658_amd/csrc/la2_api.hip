@@ -8,6 +8,7 @@
 namespace {
 
 int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
+int g_scan_variant = 0;           // la2_set_scan_variant()
 
 int device_cu_count() {
   static int cached = 0;
@@ -40,6 +41,8 @@ la2_status check_desc(const la2_desc* d) {
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Granularity of the sequence chunks (the block size of the chunk-state pre-pass; a multiple of every
+// scan kernel's block size).
 int block_size(const la2_desc* d) {
   return d->dtype == LA2_BF16 ? la2::block_size_bf16(d->head_dim) : la2::block_size_f32(d->head_dim);
 }
@@ -92,6 +95,7 @@ la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lamb
   p.batch = d->batch; p.heads = d->heads; p.n = d->seqlen;
   p.nchunks = pl.nchunks;
   p.chunk_tokens = pl.chunk_tokens;
+  p.variant = g_scan_variant;
   return p;
 }
 
@@ -160,10 +164,14 @@ size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
 
 int32_t la2_block_size(const la2_desc* desc) {
   if (check_desc(desc) != LA2_OK) return 0;
+  // bf16, head_dim 128: the half-block scan kernel unless the full-block one is forced
+  if (desc->dtype == LA2_BF16 && desc->head_dim == 128 && g_scan_variant != 1) return 32;
   return block_size(desc);
 }
 
 void la2_set_chunk_tokens(int32_t tokens) { g_chunk_tokens_override = tokens > 0 ? tokens : 0; }
+
+void la2_set_scan_variant(int32_t variant) { g_scan_variant = (variant == 1 || variant == 2) ? variant : 0; }
 
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
                    void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -29,6 +29,7 @@ struct ScanParams {
   int32_t batch, heads, n;
   int32_t nchunks;       // sequence chunks processed by different workgroups
   int32_t chunk_tokens;  // tokens per chunk (multiple of the block size); last chunk may be short
+  int32_t variant;       // bf16 d = 128 scan kernel: 0 automatic, 1 full-block, 2 half-block
 };
 
 // Block size (rows of the intra-block tile) per data type / head dim.

@@ -48,14 +48,14 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 constexpr int kB = 64;        // block size (positions per block)
 constexpr int kThreads = 256; // 4 waves
 
-template <int D>
+template <int D, int B = kB>
 struct Cfg {
   static constexpr int KS = D / 16;            // MFMA k-steps along a feature dimension
   static constexpr int NT = D / 32;            // 32-wide tiles along a feature dimension
   static constexpr int WPD = 4 / NT;           // waves sharing one value-feature tile (1 or 2)
   static constexpr int RT = 2 / WPD;           // 32-row tiles of the block per wave (2 or 1)
   static constexpr int CPR = D / 8;            // 16-byte chunks per tile row
-  static constexpr int TILE = kB * D;          // elements per tile
+  static constexpr int TILE = B * D;           // elements per tile
   static constexpr int DMA_PER_TILE = TILE / 512;   // wave instructions (1 KiB each) per tile
   static constexpr int DMA_PER_WAVE = DMA_PER_TILE / 4;
   static constexpr int LW = 32;                // staging row: 32 features = 64 bytes, unpadded, 16-byte chunks
@@ -195,32 +195,33 @@ struct LaneAddr {
 // Direct HBM -> LDS loads of one tile set.  This wave issues instructions j = DMA_PER_WAVE w + i of
 // every tile; lane l of instruction j fills LDS chunk q = 64 j + l, i.e. row q / CPR, physical chunk
 // q % CPR, which holds logical chunk (q % CPR) ^ swz(row).
-template <int D, int NTILES>
+template <int D, int NTILES, int B = kB, int NW = 4>
 struct TileLoader {
-  using C = Cfg<D>;
-  int row[C::DMA_PER_WAVE], col[C::DMA_PER_WAVE];
+  using C = Cfg<D, B>;
+  static constexpr int DMA_PER_WAVE = C::DMA_PER_TILE / NW;   // NW waves share the work
+  int row[DMA_PER_WAVE], col[DMA_PER_WAVE];
   int w, l, n;
   uint32_t stride_n;
+  uint32_t wave_lds;   // byte offset of this wave's part of a tile (wave-uniform, scalar register)
   const char* g[NTILES];
   __device__ __forceinline__ TileLoader(int w_, int l_, int n_, uint32_t stride_n_)
       : w(w_), l(l_), n(n_), stride_n(stride_n_) {
+    wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane(1024 * DMA_PER_WAVE * w_);
 #pragma unroll
-    for (int i = 0; i < C::DMA_PER_WAVE; i++) {
-      const int q = 64 * (C::DMA_PER_WAVE * w + i) + l;
+    for (int i = 0; i < DMA_PER_WAVE; i++) {
+      const int q = 64 * (DMA_PER_WAVE * w + i) + l;
       row[i] = q / C::CPR;
       col[i] = 8 * ((q % C::CPR) ^ swz<D>(q / C::CPR));
     }
   }
   __device__ __forceinline__ void issue(__bf16 (*sT)[C::TILE], int blk) const {
 #pragma unroll
-    for (int i = 0; i < C::DMA_PER_WAVE; i++) {
-      const int pos = min(blk * kB + row[i], n - 1);   // rows past the end are re-zeroed by zero_tail
+    for (int i = 0; i < DMA_PER_WAVE; i++) {
+      const int pos = min(blk * B + row[i], n - 1);   // rows past the end are re-zeroed by zero_tail
       // 32-bit byte offset from the (wave-uniform) chain base; the host checked that a chain spans < 4 GiB
       const uint32_t off = ((uint32_t)pos * stride_n + (uint32_t)col[i]) * 2u;
-      const int dst = 512 * (C::DMA_PER_WAVE * w + i);
 #pragma unroll
-      for (int t = 0; t < NTILES; t++)
-        dma16(g[t], off, __builtin_amdgcn_readfirstlane(lds_offset(&sT[t][dst])));
+      for (int t = 0; t < NTILES; t++) dma16(g[t], off, lds_offset(&sT[t][0]) + wave_lds + 1024u * i);
     }
   }
   // The same loads one at a time (j = 0 .. NTILES DMA_PER_WAVE - 1), so that they can be spread over
@@ -228,29 +229,29 @@ struct TileLoader {
   // `valid` false (no such block): every lane reads the chain's first 16 bytes instead, a single
   // cache line per instruction, so that the loads can be issued unconditionally (no branches inside the
   // hand-scheduled block body, same count of outstanding operations for every block).
-  __device__ __forceinline__ void offsets(int blk, bool valid, uint32_t (&off)[C::DMA_PER_WAVE]) const {
+  __device__ __forceinline__ void offsets(int blk, bool valid, uint32_t (&off)[DMA_PER_WAVE]) const {
 #pragma unroll
-    for (int i = 0; i < C::DMA_PER_WAVE; i++) {
-      const int pos = min(blk * kB + row[i], n - 1);
+    for (int i = 0; i < DMA_PER_WAVE; i++) {
+      const int pos = min(blk * B + row[i], n - 1);
       off[i] = valid ? ((uint32_t)pos * stride_n + (uint32_t)col[i]) * 2u : 0u;
     }
   }
-  __device__ __forceinline__ void issue_one(__bf16 (*sT)[C::TILE], const uint32_t (&off)[C::DMA_PER_WAVE],
+  __device__ __forceinline__ void issue_one(__bf16 (*sT)[C::TILE], const uint32_t (&off)[DMA_PER_WAVE],
                                             int j) const {
     const int i = j / NTILES, t = j % NTILES;
-    const int dst = 512 * (C::DMA_PER_WAVE * w + i);
-    dma16(g[t], off[i], __builtin_amdgcn_readfirstlane(lds_offset(&sT[t][dst])));
+    // LDS address = tile base (a constant once the buffer index is one) + scalar wave offset
+    dma16(g[t], off[i], lds_offset(&sT[t][0]) + wave_lds + 1024u * i);
   }
   // after this wave's loads have landed: zero the rows of a ragged last block
   __device__ __forceinline__ void zero_tail(__bf16 (*sT)[C::TILE], int blk) const {
-    if ((blk + 1) * kB > n) {
+    if ((blk + 1) * B > n) {
 #pragma unroll
-      for (int i = 0; i < C::DMA_PER_WAVE; i++) {
-        if (blk * kB + row[i] >= n) {
-          const int dst = 512 * (C::DMA_PER_WAVE * w + i) + 8 * l;
+      for (int i = 0; i < DMA_PER_WAVE; i++) {
+        if (blk * B + row[i] >= n) {
           const i32x4 z = {0, 0, 0, 0};
 #pragma unroll
-          for (int t = 0; t < NTILES; t++) *reinterpret_cast<i32x4*>(&sT[t][dst]) = z;
+          for (int t = 0; t < NTILES; t++)
+            *reinterpret_cast<i32x4*>(reinterpret_cast<char*>(&sT[t][0]) + (wave_lds + 1024u * i + 16u * l)) = z;
         }
       }
     }
@@ -276,7 +277,7 @@ __device__ __forceinline__ float uniform(float x) {
 // a per-lane factor (one exp2 per fragment) and a wave-uniform factor per element:
 //   forward  lambda^(B-16-c0 + 4 (1-hh)) * lambda^(11-nj)      reverse  lambda^(c0 + 4 hh) * lambda^nj
 // All exponents are non-negative.
-template <bool REV>
+template <bool REV, int B = kB>
 struct UpdateDecay {
   float gj[8];   // wave-uniform
   float l2;
@@ -289,7 +290,7 @@ struct UpdateDecay {
     }
   }
   __device__ __forceinline__ bf16x8 apply(bf16x8 z, int c0) const {
-    const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh : kB - 16 - c0 + 4 * (1 - hh)));
+    const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh : B - 16 - c0 + 4 * (1 - hh)));
     bf16x8 r;
 #pragma unroll
     for (int j = 0; j < 8; j++) r[j] = (__bf16)((float)z[j] * (step * gj[j]));
@@ -684,6 +685,268 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 #undef LA2_SLOT_END
 }
 
+// Half-block variant for d = 128: blocks of 32 positions, 80 KiB of LDS and at most 256 registers, so
+// that TWO workgroups share a compute unit (two waves per SIMD).  One wave alone issues its
+// instructions one after the other (an MFMA holds the issue port for about half its run time, a
+// 16-byte-per-lane memory instruction for about 60 cycles), so a single wave per SIMD leaves the
+// matrix pipe idle most of the time; a second, independent wave fills those gaps.  Used when a launch
+// has enough workgroups to put two on every compute unit.  Same math as scan_bf16_kernel with a
+// single (diagonal) 32 x 32 score tile per block; wave w owns value features 32 w .. 32 w + 31.
+constexpr int kBH = 32;
+//
+// TWIN: both scans of a dual launch in ONE workgroup of 8 waves (waves 0-3 scan 0, waves 4-7 scan 1;
+// again two waves per SIMD).  The dual launch is Algorithm 2's second loop, whose two scans read the
+// same two tensors with the roles of Y and Z exchanged (dV: y = Q, z = dO; dK: y = dO, z = Q), so the
+// workgroup streams FOUR tiles per block (x of scan 0, x of scan 1, Q, dO) instead of six and every
+// tile is fetched exactly once.  Requires y[1] == z[0] and z[1] == y[0].
+template <bool REV, bool TWIN>
+__global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
+  constexpr int D = 128, B = kBH;
+  using C = Cfg<D, B>;
+  constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
+  constexpr int NW = TWIN ? 8 : 4;             // waves
+  constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
+  using Loader = TileLoader<D, NTL, B, NW>;
+  __shared__ __attribute__((aligned(1024))) __bf16 sT0[NTL][TILE];
+  __shared__ __attribute__((aligned(1024))) __bf16 sT1[NTL][TILE];
+  __shared__ __attribute__((aligned(1024))) __bf16 sT2[NTL][TILE];
+  __shared__ __attribute__((aligned(16))) __bf16 sW[NW][32 * LW];
+  constexpr int NDMA = NTL * Loader::DMA_PER_WAVE;   // direct loads per wave and block
+  constexpr int NST = 32 * 4 / 64;             // 16-byte stores per lane and block
+  static_assert(NDMA <= KS, "one direct load per slot of phase 1");
+  constexpr int VM_YOUNGER = NST + NDMA;
+  constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
+
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
+  const int dvt = w & 3;
+  int which = 0, wg = (int)blockIdx.x;
+  if (TWIN) {
+    which = __builtin_amdgcn_readfirstlane(w >> 2);
+  } else if (p.nscan == 2) {   // same pairing as scan_bf16_kernel
+    if (((gridDim.x >> 1) & 7) == 0) {
+      which = (int)(blockIdx.x >> 3) & 1;
+      wg = (int)((blockIdx.x >> 4) << 3) | (int)(blockIdx.x & 7);
+    } else {
+      which = (int)(blockIdx.x & 1);
+      wg = (int)(blockIdx.x >> 1);
+    }
+  }
+  // In a twin workgroup the two wave groups run two instantiations of the body, so that each sees
+  // its tiles at compile-time LDS offsets.
+  auto run = [&](auto wh_tag) __attribute__((always_inline)) {
+  constexpr int WH = decltype(wh_tag)::value;
+  const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
+  const int bi = chain / p.heads, hi = chain % p.heads;
+  const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
+  const int n = p.n;
+  const uint32_t stride_n = (uint32_t)p.stride_n;
+  const uint32_t chain_bytes = ((uint32_t)(n - 1) * stride_n + D) * 2u;
+  const __amdgpu_buffer_rsrc_t bw =
+      make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
+  const float l2 = log2f(p.lambda[hi]);
+
+  const int nblocks = (n + B - 1) / B;
+  const int cb = p.chunk_tokens / B;
+  const int blk_lo = chunk * cb;
+  const int blk_hi = min(blk_lo + cb, nblocks);
+  if (blk_lo >= blk_hi) return;
+  const int nblk = blk_hi - blk_lo;
+
+  Loader loader(w, l, n, stride_n);
+  if (TWIN) {
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[1]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
+    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
+  } else {
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.x[1] : p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.y[1] : p.y[0]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.z[1] : p.z[0]) + base);
+  }
+  // this wave's X, Y, Z among the tiles of a block
+  constexpr int xi = TWIN ? WH : 0, yi = TWIN ? 2 + WH : 1, zi = TWIN ? 3 - WH : 2;
+  const LaneAddr<D> la(l);
+
+  f32x16 kv[NT];
+  if (p.states != nullptr) {
+    const float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+    const bool tr = (p.state_transposed >> which) & 1;
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) kv[t][v] = gs[state_index<D>(dvt, l32, hh, t, v, tr)];
+  } else {
+#pragma unroll
+    for (int t = 0; t < NT; t++) kv[t] = zero16();
+  }
+
+  // decay mask of the score tile S^T[c][r] (lane: r = l32; element v: c = 8 (v / 4) + 4 hh + v % 4)
+  float dg[16];
+#pragma unroll
+  for (int v = 0; v < 16; v++) {
+    const int cc = 8 * (v >> 2) + 4 * hh + (v & 3);
+    const int e = REV ? cc - l32 : l32 - cc;
+    dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
+  }
+  const float inter_scale = exp2f(l2 * (float)(REV ? B - l32 : l32 + 1));
+  const UpdateDecay<REV, B> decay(l2, hh);
+  const float lamB = uniform(exp2f(l2 * (float)B));
+
+  {
+    const int b0 = REV ? blk_hi - 1 : blk_lo, b1 = REV ? b0 - 1 : b0 + 1;
+    loader.issue(sT0, b0);
+    if (nblk > 1) loader.issue(sT1, b1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    loader.zero_tail(sT0, b0);
+    if (nblk > 1) loader.zero_tail(sT1, b1);
+  }
+  __syncthreads();
+
+  constexpr int AHEAD = 1;   // LDS operands are read one slot ahead (the other wave on the SIMD covers the rest)
+  bf16x8 xa[KS];
+#pragma unroll
+  for (int ks = 0; ks < AHEAD; ks++) xa[ks] = la.read_row(sT0[xi], 0, ks);
+  auto state_operand = [&](int ks) __attribute__((always_inline)) {
+    bf16x8 f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) f[j] = (__bf16)kv[ks >> 1][8 * (ks & 1) + j];
+    return to_perm_order(f);
+  };
+  bf16x8 sa_first = state_operand(0);
+  __bf16* const stage = sW[w];
+
+#define LA2_SLOT_END()                 \
+  do {                                 \
+    asm volatile("" ::: "memory");     \
+    __builtin_amdgcn_sched_barrier(0); \
+  } while (0)
+  // Phases as in scan_bf16_kernel (1 inter-block product, 2 scores, 3 state update, barrier,
+  // 4 intra-block product), then the block's output.
+  auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
+    constexpr int cur = decltype(cur_tag)::value;
+    __bf16 (*const sCur)[TILE] = cur == 0 ? sT0 : (cur == 1 ? sT1 : sT2);
+    __bf16 (*const sNext)[TILE] = cur == 0 ? sT1 : (cur == 1 ? sT2 : sT0);
+    __bf16 (*const sAhead)[TILE] = cur == 0 ? sT2 : (cur == 1 ? sT0 : sT1);
+    const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
+    const bool has_next = it + 1 < nblk, has_ahead = it + 2 < nblk;
+    const int nb = REV ? blk - 1 : blk + 1;
+    const __bf16* tX = sCur[xi];
+    const __bf16* tY = sCur[yi];
+    const __bf16* tZ = sCur[zi];
+    uint32_t doff[Loader::DMA_PER_WAVE];
+    loader.offsets(REV ? blk - 2 : blk + 2, has_ahead, doff);
+
+    bf16x8 zf[2], zd[2], yt[2][NT], xb[KS], yb[KS];
+    auto read_xy = [&](int ks) __attribute__((always_inline)) {
+      xb[ks] = la.read_row(tX, 0, ks);
+      yb[ks] = la.read_row(tY, 0, ks);
+    };
+    // Y^T fragments of update k-step q for the key-feature tiles 2 h, 2 h + 1
+    auto read_yt = [&](int q, int h) __attribute__((always_inline)) {
+#pragma unroll
+      for (int t = 2 * h; t < 2 * h + 2; t++) yt[q][t] = la.read_cols(tY, 16 * q, t);
+    };
+
+    // ---- phase 1
+    f32x16 inter = zero16();
+    bf16x8 sa = sa_first;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      inter = mfma(sa, xa[ks], inter);
+      if (ks + AHEAD < KS) xa[ks + AHEAD] = la.read_row(tX, 0, ks + AHEAD);
+      else read_xy(ks + AHEAD - KS);
+      if (ks + 1 < KS) { sa = state_operand(ks + 1); pin(sa); }
+      if (ks < NDMA) loader.issue_one(sAhead, doff, ks);
+      if (ks < 2) zf[ks] = la.read_cols(tZ, 16 * ks, dvt);
+      pin(inter);
+      LA2_SLOT_END();
+    }
+    // ---- phase 2
+    f32x16 sd = zero16();
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      sd = mfma(yb[ks], xb[ks], sd);
+      if (ks + AHEAD < KS) read_xy(ks + AHEAD);
+      if (ks == KS - 1) read_yt(0, 0);
+      if ((ks & 1) == 0) {
+        const int t = ks >> 1;
+#pragma unroll
+        for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
+        pin(kv[t]);
+      }
+      if (ks == 1) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) inter[v] *= inter_scale;
+        pin(inter);
+      }
+      if (ks == 3 || ks == 5) {
+        const int q = (ks - 3) >> 1;
+        zd[q] = decay.apply(zf[q], 16 * q);
+        pin(zd[q]);
+      }
+      pin(sd);
+      LA2_SLOT_END();
+    }
+    // ---- phase 3
+    bf16x8 pd[2];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; s4++) {   // slot s4: k-step q = s4 / 2, key-feature tiles 2 h, 2 h + 1, h = s4 % 2
+      const int q = s4 >> 1, h = s4 & 1;
+#pragma unroll
+      for (int t = 2 * h; t < 2 * h + 2; t++) kv[t] = mfma(yt[q][t], zd[q], kv[t]);
+      if (s4 + 1 < 4) read_yt((s4 + 1) >> 1, (s4 + 1) & 1);
+#pragma unroll
+      for (int e = 0; e < 4; e++) pd[q][4 * h + e] = (__bf16)(sd[8 * q + 4 * h + e] * dg[8 * q + 4 * h + e]);
+      pin(pd[q]);
+#pragma unroll
+      for (int t = 2 * h; t < 2 * h + 2; t++) pin(kv[t]);
+      LA2_SLOT_END();
+    }
+    if (has_next) {
+      __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
+      loader.zero_tail(sNext, nb);
+      lds_barrier();
+#pragma unroll
+      for (int ks = 0; ks < AHEAD; ks++) xa[ks] = la.read_row(sNext[xi], 0, ks);
+    }
+    LA2_SLOT_END();
+    // ---- phase 4 and the block's output
+#pragma unroll
+    for (int q = 0; q < 2; q++) inter = mfma(zf[q], pd[q], inter);
+    sa_first = state_operand(0);
+    pin(sa_first);
+    pin(inter);
+    LA2_SLOT_END();
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      bf16x4 pk;
+#pragma unroll
+      for (int e = 0; e < 4; e++) pk[e] = (__bf16)inter[4 * g + e];
+      *reinterpret_cast<bf16x4*>(stage + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
+    }
+#pragma unroll
+    for (int i = 0; i < NST; i++) {
+      const int id = l + 64 * i;
+      const int row = id >> 2, cc = id & 3;
+      const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
+      const uint32_t off = ((uint32_t)(blk * B + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
+      __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
+    }
+    LA2_SLOT_END();
+    return has_next;
+  };
+  for (int it = 0;; it += 3) {
+    if (!block_step(std::integral_constant<int, 0>{}, it)) break;
+    if (!block_step(std::integral_constant<int, 1>{}, it + 1)) break;
+    if (!block_step(std::integral_constant<int, 2>{}, it + 2)) break;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
+#undef LA2_SLOT_END
+  };
+  if (TWIN && which == 1) run(std::integral_constant<int, 1>{});
+  else run(std::integral_constant<int, 0>{});
+}
+
 // Local state of every chunk that has a successor: forward sum_c lambda^(C-1-c) y_c^T z_c over the
 // chunk's positions c, reverse sum_c lambda^c y_c^T z_c.  Written fp32 row-major [dk][dv].  Same
 // streaming and the same state-update step as the scan kernel, without X, scores or outputs.
@@ -796,11 +1059,24 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
 
 int block_size_bf16(int) { return kB; }
 
+
+
 hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   if (grid == 0 || p.n == 0) return hipSuccess;
   dim3 g((unsigned)grid), b(kThreads);
-  if (head_dim == 128) {
+  const bool half = p.variant != 1;   // measured faster at every launch size, also at one workgroup per compute unit
+  if (head_dim == 128 && half && p.chunk_tokens % kBH == 0) {
+    const bool twin = p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0];
+    if (twin) {
+      dim3 gt((unsigned)(grid / 2)), bt(512);
+      if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, true>), gt, bt, 0, s, p);
+      else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, true>), gt, bt, 0, s, p);
+    } else {
+      if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, false>), g, b, 0, s, p);
+      else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, false>), g, b, 0, s, p);
+    }
+  } else if (head_dim == 128) {
     if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<128, true>), g, b, 0, s, p);
     else         hipLaunchKernelGGL((scan_bf16_kernel<128, false>), g, b, 0, s, p);
   } else {

@@ -18,8 +18,10 @@ DEV = "cuda:0"
 @pytest.fixture(autouse=True)
 def _auto_chunking():
     binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
     yield
     binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
 
 
 def make_inputs(b, H, n, d, dtype, seed, lam=None, backward=True):
@@ -69,6 +71,59 @@ def test_config2_fwd_bwd_bf16_full():
 def test_small_shapes(dtype, d, n):
     t = make_inputs(2, 3, n, d, dtype, seed=100 + n + d, lam=[0.5, 0.93, 1.0])
     check_fwd_bwd(t, dtype, "n%d d%d %s" % (n, d, dtype))
+
+
+# ---- both bf16 head_dim-128 scan kernels (full-block B = 64, half-block B = 32), forced explicitly: the
+# automatic choice depends on the launch size and would pick the full-block kernel for all small cases
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 64, 95, 129, 200, 517])
+def test_scan_variants_small_shapes(variant, n):
+    binding.la2_set_scan_variant(variant)
+    t = make_inputs(2, 3, n, 128, torch.bfloat16, seed=300 + n, lam=[0.5, 0.93, 1.0])
+    check_fwd_bwd(t, torch.bfloat16, "variant%d n%d" % (variant, n))
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("chunk,n", [(128, 1000), (192, 1024), (256, 700)])
+def test_scan_variants_chunked(variant, chunk, n):
+    binding.la2_set_scan_variant(variant)
+    binding.la2_set_chunk_tokens(chunk)
+    t = make_inputs(1, 4, n, 128, torch.bfloat16, seed=17 * n + chunk)
+    assert binding.la2_workspace_bytes(t["q"].to(DEV)) > 0
+    check_fwd_bwd(t, torch.bfloat16, "variant%d chunk%d n%d" % (variant, chunk, n))
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_scan_variants_extreme_decays_and_strides(variant):
+    binding.la2_set_scan_variant(variant)
+    t = make_inputs(1, 3, 300, 128, torch.bfloat16, seed=23, lam=[1.0, 1e-6, 0.43])
+    check_fwd_bwd(t, torch.bfloat16, "variant%d extreme decays" % variant)
+    b, H, n, d = 2, 4, 260, 128
+    t = make_inputs(b, H, n, d, torch.bfloat16, seed=33)
+    g = {}
+    for name in ("q", "k", "v", "d_o"):
+        g[name] = t[name].permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)   # [b, n, H, d] storage
+    lam = t["lam"].to(DEV)
+    o = binding.la2_fwd(g["q"], g["k"], g["v"], lam)
+    dq, dk, dv = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], lam)
+    torch.cuda.synchronize()
+    q, k, v, do, lam64 = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    assert_close("variant%d strided o" % variant, o, oracle.fwd_direct(q, k, v, lam64), torch.bfloat16)
+    for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle.bwd_direct(q, k, v, do, lam64)):
+        assert_close("variant%d strided %s" % (variant, name), got, ref, torch.bfloat16)
+
+
+def test_scan_variants_agree():
+    """The two kernels compute the same function: outputs differ by bf16 rounding only."""
+    t = gpu(make_inputs(2, 4, 1500, 128, torch.bfloat16, seed=55))
+    out = {}
+    for variant in (1, 2):
+        binding.la2_set_scan_variant(variant)
+        out[variant] = (binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"]),) + tuple(
+            binding.la2_bwd(t["q"], t["k"], t["v"], t["d_o"], t["lam"]))
+    torch.cuda.synchronize()
+    for a, b in zip(out[1], out[2]):
+        assert max_rel(to64(a), to64(b)) <= 1e-2
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
