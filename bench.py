@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch (bytes), by workload
-MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786709 + 262144) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786763 + 262146) * 1024)}
 
 
 def flops_per_token_head(B, d, what):
@@ -50,7 +50,7 @@ def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
         "frac": round(bytes_alg / (k_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         # HBM bytes per launch measured with rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the factor the
         # same counter shows for a plain copy of known size (2.00 and 1.00): see
-        # profiles/scan_bf16_fwd_b16_n4096_h16_d128_counters.txt
+        # profiles/scan_bf16_half_fwd_b16_n4096_h16_d128_counters.txt
         "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
         "algorithmic_bytes": bytes_alg,
         "launch_ms": round(k_ms, 4),
