@@ -10,6 +10,7 @@ from .ref import (  # noqa: F401
     bwd_direct,
     fwd_recurrent,
     bwd_recurrent,
+    bwd_recurrent_state,
     decode_step,
     fwd_rows,
     bwd_rows,

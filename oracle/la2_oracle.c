@@ -16,6 +16,8 @@
  *   *_recurrent  the token-by-token recursion kv_t = lambda kv_{t-1} + k_t^T v_t,
  *                o_t = q_t kv_t (Sec. 3.2.1, recursive form) and the reverse recursion
  *                dkv_{t-1} = lambda dkv_t + q_{t-1}^T do_{t-1} (Sec. 3.2.2), O(n d^2).
+ * The recurrent form also runs SEGMENTS of a sequence (start state in, final state out, and the
+ * matching gradients); the tests pin those against the direct form of the whole sequence.
  * The tests pin each against closed forms, finite differences and each other.
  *
  * The weight of the diagonal term (s == t) is exactly 1 for every lambda in (0, 1].
@@ -212,6 +214,64 @@ void la2_oracle_bwd_recurrent(int b, int H, int64_t n, int d, const double *q, c
     }
     free(kv);
     free(dkv);
+  }
+}
+
+/* The same two sweeps for a segment of a longer sequence (Sec. 3.2.1 recursion started from a
+ * non-zero kv_0 = kv_init; chain rule through the recursion when the loss also depends on the
+ * segment's final state kv_n, whose gradient d_kv_final is handed in):
+ *   forward sweep   kv_t = lambda kv_{t-1} + k_t^T v_t (kv_0 = kv_init),   dq_t = do_t kv_t^T
+ *   reverse sweep   g_n = q_n^T do_n + d_kv_final,  g_t = lambda g_{t+1} + q_t^T do_t   (total gradient
+ *                   with respect to kv_t),  dk_t = v_t g_t^T,  dv_t = k_t g_t
+ *   d_kv_init = lambda g_1   (kv_0 enters kv_1 with the factor lambda)
+ * kv_init, d_kv_final may be NULL (zero); d_kv_init may be NULL (not wanted).  n == 0: d_kv_init = d_kv_final. */
+void la2_oracle_bwd_recurrent_state(int b, int H, int64_t n, int d, const double *q, const double *k,
+                                    const double *v, const double *d_o, const double *lambda,
+                                    const double *kv_init, const double *d_kv_final, double *dq,
+                                    double *dk, double *dv, double *d_kv_init) {
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t c = 0; c < (int64_t)b * H; c++) {
+    int64_t off = c * n * d;
+    double lam = lambda[c % H];
+    double *kv = (double *)calloc((size_t)d * d, sizeof(double));
+    double *g = (double *)calloc((size_t)d * d, sizeof(double));
+    if (kv_init) memcpy(kv, kv_init + c * d * d, sizeof(double) * (size_t)d * d);
+    for (int64_t t = 0; t < n; t++) {
+      const double *kt = k + off + t * d, *vt = v + off + t * d, *dot_ = d_o + off + t * d;
+      for (int i = 0; i < d; i++)
+        for (int j = 0; j < d; j++) kv[i * d + j] = lam * kv[i * d + j] + kt[i] * vt[j];
+      for (int i = 0; i < d; i++) {
+        double s = 0.0;
+        for (int j = 0; j < d; j++) s += dot_[j] * kv[i * d + j];
+        dq[off + t * d + i] = s;
+      }
+    }
+    for (int64_t t = n - 1; t >= 0; t--) {
+      const double *qt = q + off + t * d, *kt = k + off + t * d, *vt = v + off + t * d,
+                   *dot_ = d_o + off + t * d;
+      for (int i = 0; i < d; i++)
+        for (int j = 0; j < d; j++) {
+          double carried = (t == n - 1) ? (d_kv_final ? d_kv_final[c * d * d + i * d + j] : 0.0)
+                                        : lam * g[i * d + j];
+          g[i * d + j] = carried + qt[i] * dot_[j];
+        }
+      for (int i = 0; i < d; i++) {
+        double s = 0.0;
+        for (int j = 0; j < d; j++) s += vt[j] * g[i * d + j];
+        dk[off + t * d + i] = s;
+      }
+      for (int j = 0; j < d; j++) {
+        double s = 0.0;
+        for (int i = 0; i < d; i++) s += kt[i] * g[i * d + j];
+        dv[off + t * d + j] = s;
+      }
+    }
+    if (d_kv_init) {
+      for (int i = 0; i < d * d; i++)
+        d_kv_init[c * d * d + i] = (n > 0) ? lam * g[i] : (d_kv_final ? d_kv_final[c * d * d + i] : 0.0);
+    }
+    free(kv);
+    free(g);
   }
 }
 

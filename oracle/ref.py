@@ -115,6 +115,28 @@ def bwd_recurrent(q, k, v, d_o, lam):
     return dq, dk, dv
 
 
+def bwd_recurrent_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None):
+    """Backward of one segment: gradients of a loss that depends on the segment's outputs (d_o) and
+    on its final state (d_kv_final), for a segment that started from kv_init.
+    Returns dq, dk, dv, d_kv_init."""
+    q, k, v, d_o = _f64(q), _f64(k), _f64(v), _f64(d_o)
+    b, H, n, d = _shape4(q)
+    lam = _lam(lam, H)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    dkv0 = np.empty((b, H, d, d), dtype=np.float64)
+    init = _f64(kv_init) if kv_init is not None else None
+    dfin = _f64(d_kv_final) if d_kv_final is not None else None
+    for a in (init, dfin):
+        assert a is None or a.shape == (b, H, d, d)
+    _load().la2_oracle_bwd_recurrent_state(
+        ctypes.c_int(b), ctypes.c_int(H), ctypes.c_int64(n), ctypes.c_int(d),
+        _p(q), _p(k), _p(v), _p(d_o), _p(lam),
+        _p(init) if init is not None else None, _p(dfin) if dfin is not None else None,
+        _p(dq), _p(dk), _p(dv), _p(dkv0),
+    )
+    return dq, dk, dv, dkv0
+
+
 def decode_step(q, k, v, lam, kv):
     """One recurrent step.  q, k, v: [b, H, d]; kv: [b, H, d, d] float64, updated in place.
     Returns o [b, H, d] computed from the UPDATED state."""

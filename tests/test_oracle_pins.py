@@ -314,3 +314,102 @@ def test_empty_sequence():
     assert oracle.fwd_direct(z, z, z, 0.9).shape == (1, 1, 0, 4)
     assert oracle.fwd_recurrent(z, z, z, 0.9).shape == (1, 1, 0, 4)
     assert all(g.shape == (1, 1, 0, 4) for g in oracle.bwd_direct(z, z, z, z, 0.9))
+
+
+# ---- P11: segments with state hand-over (Sec. 3.2.1 recursion started from a non-zero state; the
+# chain rule through it).  The reference is always the whole sequence in the DIRECT form, which knows
+# nothing about states.
+def _segments(n, cuts):
+    edges = [0] + list(cuts) + [n]
+    return [slice(a, b) for a, b in zip(edges[:-1], edges[1:])]
+
+
+@pytest.mark.parametrize("cuts", [(8,), (1,), (15,), (5, 11), (3, 3, 9)])
+def test_state_handover_forward_and_backward_equal_the_whole_sequence(cuts):
+    b, H, n, d = 2, 2, 16, 3
+    q, k, v, do = (_rand((b, H, n, d), s) for s in (70, 71, 72, 73))
+    lam = np.array([0.7, 0.97])
+    o_full = oracle.fwd_direct(q, k, v, lam)
+    dq_full, dk_full, dv_full = oracle.bwd_direct(q, k, v, do, lam)
+    segs = _segments(n, cuts)
+    # forward, left to right
+    state, starts, outs = None, [], []
+    for s in segs:
+        starts.append(state)
+        o, state = oracle.fwd_recurrent(q[:, :, s], k[:, :, s], v[:, :, s], lam, kv_init=state, return_state=True)
+        outs.append(o)
+    assert np.allclose(np.concatenate(outs, axis=2), o_full, rtol=1e-12, atol=1e-13)
+    # backward, right to left: the gradient of a segment's start state is the next-left segment's d_kv_final
+    g, grads = None, []
+    for s, st in zip(reversed(segs), reversed(starts)):
+        dq, dk, dv, g = oracle.bwd_recurrent_state(q[:, :, s], k[:, :, s], v[:, :, s], do[:, :, s], lam,
+                                                   kv_init=st, d_kv_final=g)
+        grads.append((dq, dk, dv))
+    grads.reverse()
+    for i, ref in enumerate((dq_full, dk_full, dv_full)):
+        assert np.allclose(np.concatenate([x[i] for x in grads], axis=2), ref, rtol=1e-12, atol=1e-13)
+
+
+def test_state_closed_form_scalar():
+    """d = 1, q = k = v = 1: kv_t = lam^t kv_0 + (1 - lam^t)/(1 - lam), o_t = kv_t."""
+    n, lam, kv0 = 25, 0.9, 3.5
+    one = np.ones((1, 1, n, 1))
+    o, kvf = oracle.fwd_recurrent(one, one, one, lam, kv_init=np.full((1, 1, 1, 1), kv0), return_state=True)
+    t = np.arange(1, n + 1)
+    expect = lam ** t * kv0 + (1 - lam ** t) / (1 - lam)
+    assert np.allclose(o[0, 0, :, 0], expect, rtol=1e-13, atol=0)
+    assert np.isclose(kvf[0, 0, 0, 0], expect[-1], rtol=1e-13, atol=0)
+    # gradients of L = sum_t w_t o_t + c kv_n with respect to kv_0: sum_t w_t lam^t + c lam^n
+    w = _rand((1, 1, n, 1), 74)
+    c = 1.7
+    *_, g0 = oracle.bwd_recurrent_state(one, one, one, w, lam, kv_init=np.full((1, 1, 1, 1), kv0),
+                                        d_kv_final=np.full((1, 1, 1, 1), c))
+    assert np.isclose(g0[0, 0, 0, 0], np.sum(w[0, 0, :, 0] * lam ** t) + c * lam ** n, rtol=1e-12, atol=0)
+
+
+def test_state_gradients_by_finite_differences():
+    b, H, n, d = 1, 2, 7, 3
+    q, k, v, do = (_rand((b, H, n, d), s) for s in (75, 76, 77, 78))
+    kv0, wfin = _rand((b, H, d, d), 79), _rand((b, H, d, d), 80)
+    lam = np.array([0.85, 0.6])
+
+    def loss(q_, k_, v_, kv0_):
+        o, kvf = oracle.fwd_recurrent(q_, k_, v_, lam, kv_init=kv0_, return_state=True)
+        return np.sum(o * do) + np.sum(kvf * wfin)
+
+    dq, dk, dv, dkv0 = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=kv0, d_kv_final=wfin)
+    eps = 1e-6
+    args = [q, k, v, kv0]
+    for ai, grad in enumerate((dq, dk, dv, dkv0)):
+        rng = np.random.default_rng(81 + ai)
+        for _ in range(12):
+            idx = tuple(rng.integers(0, s) for s in args[ai].shape)
+            hi = [a.copy() for a in args]
+            lo = [a.copy() for a in args]
+            hi[ai][idx] += eps
+            lo[ai][idx] -= eps
+            fd = (loss(*hi) - loss(*lo)) / (2 * eps)
+            assert np.isclose(grad[idx], fd, rtol=1e-6, atol=1e-8), (ai, idx, grad[idx], fd)
+
+
+def test_state_edge_cases():
+    b, H, d = 1, 2, 3
+    lam = np.array([0.9, 0.5])
+    z = np.zeros((b, H, 0, d))
+    kv0, g = _rand((b, H, d, d), 90), _rand((b, H, d, d), 91)
+    # empty segment: the state passes through unchanged in both directions
+    _, kvf = oracle.fwd_recurrent(z, z, z, lam, kv_init=kv0, return_state=True)
+    assert np.array_equal(kvf, kv0)
+    *_, g0 = oracle.bwd_recurrent_state(z, z, z, z, lam, kv_init=kv0, d_kv_final=g)
+    assert np.array_equal(g0, g)
+    # without states the segment backward is the plain backward
+    q, k, v, do = (_rand((b, H, 9, d), s) for s in (92, 93, 94, 95))
+    got = oracle.bwd_recurrent_state(q, k, v, do, lam)
+    for a, ref in zip(got[:3], oracle.bwd_direct(q, k, v, do, lam)):
+        assert np.allclose(a, ref, rtol=1e-12, atol=1e-13)
+    # prefill -> decode hand-over: the final state continues with single steps
+    o_full = oracle.fwd_direct(*(np.concatenate([x, y], axis=2) for x, y in
+                                 zip((q, k, v), (_rand((b, H, 1, d), s) for s in (96, 97, 98)))), lam)
+    qn, kn, vn = (_rand((b, H, 1, d), s)[:, :, 0] for s in (96, 97, 98))
+    _, kvf = oracle.fwd_recurrent(q, k, v, lam, return_state=True)
+    assert np.allclose(oracle.decode_step(qn, kn, vn, lam, kvf), o_full[:, :, -1], rtol=1e-12, atol=1e-13)
