@@ -187,6 +187,21 @@ def main():
                        "tflops": round(fl / (tot * 1e-3) / 1e12, 2),
                        "frac_bf16_peak": round(fl / (tot * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
         del g
+    # segments with state hand-over (start state in, final state out, their gradients) at the two middle
+    # sweep points: the un-chunked and a sequence-chunked launch
+    with_states = []
+    for wl, g in sweep[1:3]:
+        shape = (wl.batch, wl.heads, wl.head_dim, wl.head_dim)
+        st = {n_: torch.zeros(shape, dtype=torch.float32, device=dev) for n_ in ("init", "fin", "d_fin", "d_init")}
+        f_ms = time_ms(lambda: binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=st["init"], out=g["o"],
+                                                     kv_final=st["fin"], workspace=g["ws"]), iters)
+        b_ms = time_ms(lambda: binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=st["init"],
+                                                     d_kv_final=st["d_fin"], out=g["grads"], d_kv_init=st["d_init"],
+                                                     workspace=g["ws"]), iters)
+        with_states.append({"workload": wl.name + " + kv_init, kv_final, d_kv_final, d_kv_init",
+                            "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                            "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1)})
+        del st
     torch.cuda.empty_cache()
 
     # decode: 1024 consecutive steps, state updated in place
@@ -255,6 +270,7 @@ def main():
         "flatness_min_over_max": round(flatness, 4),
         "sweep": points,
         "other_configs": others,
+        "state_handover": with_states,
         "decode": decode,
         "roofline": roofline,
         "cpu_baseline": cpu,

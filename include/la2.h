@@ -103,6 +103,31 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Forward and backward pass of one SEGMENT of a longer sequence: the recursion of Sec. 3.2.1
+ * (kv_t = lambda kv_{t-1} + k_t^T v_t, o_t = q_t kv_t) started from a given state kv_0 = kv_init
+ * instead of zero, with the state after the last position handed out; Algorithm 1's KV and
+ * Algorithm 2's dKV carried across calls.  Uses: chunked prefill followed by la2_decode_step,
+ * sequences processed in pieces, sequence parallelism.
+ *   kv_init     in   device fp32 [batch, heads, head_dim, head_dim] dense (key feature = row, value
+ *                    feature = column; the layout of la2_decode_step's kv_state), or NULL for zero
+ *   kv_final    out  same layout: kv_seqlen, or NULL if not wanted
+ *   d_kv_final  in   gradient of the loss with respect to kv_final, or NULL for zero
+ *   d_kv_init   out  gradient with respect to kv_init, or NULL if not wanted
+ * la2_bwd_state needs the kv_init the forward pass was given (dq depends on it).  All other arguments
+ * as for la2_fwd / la2_bwd, which are these functions with NULL states.  State pointers are 16-byte
+ * aligned.  kv_final and d_kv_final require seqlen to be a multiple of 64 (the state after a partial
+ * block is not formed): LA2_ERR_SHAPE otherwise.  seqlen == 0 copies the state through
+ * (kv_final = kv_init, d_kv_init = d_kv_final; zero if the input is NULL).
+ */
+la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
+                         const float* lambda, const float* kv_init, void* o, float* kv_final,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
+                         const void* d_o, const float* lambda, const float* kv_init,
+                         const float* d_kv_final, void* dq, void* dk, void* dv, float* d_kv_init,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One step of the recurrent form (Sec. 3.2.1, recursive form), for every (batch, head):
  *     kv <- lambda_h * kv + k^T v          (state updated IN PLACE)
  *     o   = q kv                           (uses the UPDATED state, i.e. includes this token)

@@ -5,6 +5,8 @@ from .binding import (  # noqa: F401
     load,
     la2_fwd,
     la2_bwd,
+    la2_fwd_state,
+    la2_bwd_state,
     la2_decode_step,
     la2_workspace_bytes,
 )

@@ -61,6 +61,10 @@ def load():
     lib.la2_fwd.restype = ctypes.c_int
     lib.la2_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd.restype = ctypes.c_int
+    lib.la2_fwd_state.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_fwd_state.restype = ctypes.c_int
+    lib.la2_bwd_state.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd_state.restype = ctypes.c_int
     lib.la2_decode_step.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.la2_decode_step.restype = ctypes.c_int
     lib.la2_status_string.argtypes = [ctypes.c_int]
@@ -163,6 +167,64 @@ def la2_bwd(q, k, v, d_o, lam, out=None, workspace=None):
                            lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr, ws_bytes,
                            _stream(q)))
     return dq, dk, dv
+
+
+def _state(t, q, name):
+    """A dense fp32 [b, H, d, d] state tensor (or None) -> pointer argument."""
+    if t is None:
+        return None
+    b, h, _, d = q.shape
+    if t.dtype != torch.float32 or tuple(t.shape) != (b, h, d, d) or not t.is_contiguous() or t.device != q.device:
+        raise ValueError("%s must be dense fp32 [b, H, d, d] on the tensors' device" % name)
+    return ctypes.c_void_p(t.data_ptr()) if t.numel() else None
+
+
+def la2_fwd_state(q, k, v, lam, kv_init=None, want_final=True, out=None, kv_final=None, workspace=None):
+    """One segment of a sequence: o and the state after its last position, started from kv_init
+    (fp32 [b, H, d, d], None = zero).  Returns (o, kv_final or None)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_state: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    b, h, _, d = q.shape
+    if want_final and kv_final is None:
+        kv_final = torch.empty((b, h, d, d), dtype=torch.float32, device=q.device)
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_FWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_state(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
+                                 _state(kv_init, q, "kv_init"), out.data_ptr(),
+                                 _state(kv_final, q, "kv_final") if want_final else None,
+                                 ws_ptr, ws_bytes, _stream(q)))
+    return out, (kv_final if want_final else None)
+
+
+def la2_bwd_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_init=True, out=None,
+                  d_kv_init=None, workspace=None):
+    """Backward of one segment.  Returns (dq, dk, dv, d_kv_init or None)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd_state: tensors must live on the GPU")
+    _same_layout(q, k, v, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv)
+    b, h, _, d = q.shape
+    if want_d_kv_init and d_kv_init is None:
+        d_kv_init = torch.empty((b, h, d, d), dtype=torch.float32, device=q.device)
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd_state(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
+                                 lam.data_ptr(), _state(kv_init, q, "kv_init"),
+                                 _state(d_kv_final, q, "d_kv_final"), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                 _state(d_kv_init, q, "d_kv_init") if want_d_kv_init else None,
+                                 ws_ptr, ws_bytes, _stream(q)))
+    return dq, dk, dv, (d_kv_init if want_d_kv_init else None)
 
 
 def la2_decode_step(q, k, v, lam, kv_state, out=None):

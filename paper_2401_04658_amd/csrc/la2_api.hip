@@ -9,6 +9,8 @@ namespace {
 
 int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
 int g_scan_variant = 0;           // la2_set_scan_variant()
+// A final state is the state after whole blocks only: sequence lengths that every kernel's block size divides
+constexpr int kStateGranule = 64;
 
 int device_cu_count() {
   static int cached = 0;
@@ -83,6 +85,9 @@ struct ScanArgs {
   const void* y;
   const void* z;
   void* w;
+  const float* init = nullptr;   // start state [chains][d][d] (row = y feature) or nullptr
+  bool init_tr = false;          // ... stored transposed
+  float* fin = nullptr;          // state after the last block, or nullptr
 };
 
 la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace) {
@@ -101,10 +106,11 @@ la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lamb
 
 // chunk start states of the scan with key-like operand y and value-like operand z -> workspace
 la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const void* y, const void* z,
-                       const float* lambda, void* workspace, hipStream_t s) {
+                       const float* init, bool init_tr, const float* lambda, void* workspace, hipStream_t s) {
   if (pl.nchunks <= 1) return LA2_OK;
   la2::ScanParams p = base_params(d, pl, lambda, workspace);
   p.y[0] = y; p.z[0] = z;
+  p.init[0] = init; p.init_transposed = init_tr ? 1 : 0;
   const bool bf16 = d->dtype == LA2_BF16;
   hipError_t e = bf16 ? la2::launch_chunk_states_bf16(d->head_dim, reverse, p, s)
                       : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
@@ -115,10 +121,12 @@ la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const vo
 
 la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanArgs& a, const float* lambda,
                     void* workspace, hipStream_t s) {
-  la2_status st = run_prepass(d, pl, reverse, a.y, a.z, lambda, workspace, s);
+  la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s);
   if (st != LA2_OK) return st;
   la2::ScanParams p = base_params(d, pl, lambda, workspace);
   p.x[0] = a.x; p.y[0] = a.y; p.z[0] = a.z; p.w[0] = a.w;
+  p.init[0] = a.init; p.init_transposed = a.init_tr ? 1 : 0;
+  p.fin[0] = a.fin;
   const bool bf16 = d->dtype == LA2_BF16;
   hipError_t e = bf16 ? la2::launch_scan_bf16(d->head_dim, reverse, p, s) : la2::launch_scan_f32(d->head_dim, reverse, p, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
@@ -128,11 +136,14 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
 // state pre-pass, one launch (bf16 path).
 la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanArgs& a0, const ScanArgs& a1,
                                  const float* lambda, void* workspace, hipStream_t s) {
-  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, lambda, workspace, s);
+  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s);
   if (st != LA2_OK) return st;
   la2::ScanParams p = base_params(d, pl, lambda, workspace);
   p.nscan = 2;
   p.state_transposed = 2;   // scan 1 starts from the transposed state
+  p.init[0] = a0.init; p.init[1] = a1.init;
+  p.init_transposed = (a0.init_tr ? 1 : 0) | (a1.init_tr ? 2 : 0);
+  p.fin[0] = a0.fin; p.fin[1] = a1.fin;
   p.x[0] = a0.x; p.y[0] = a0.y; p.z[0] = a0.z; p.w[0] = a0.w;
   p.x[1] = a1.x; p.y[1] = a1.y; p.z[1] = a1.z; p.w[1] = a1.w;
   return la2::launch_scan_bf16(d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
@@ -173,45 +184,87 @@ void la2_set_chunk_tokens(int32_t tokens) { g_chunk_tokens_override = tokens > 0
 
 void la2_set_scan_variant(int32_t variant) { g_scan_variant = (variant == 1 || variant == 2) ? variant : 0; }
 
-la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
-                   void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
+la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                         const float* kv_init, void* o, float* kv_final, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  const int64_t chains = (int64_t)desc->batch * desc->heads;
+  if (chains == 0) return LA2_OK;  // nothing to do
+  if (!aligned(kv_init, 16) || !aligned(kv_final, 16)) return LA2_ERR_STRIDE_ALIGN;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  if (desc->seqlen == 0) {  // the state passes through
+    if (kv_final == nullptr) return LA2_OK;
+    return la2::launch_state_copy(kv_final, kv_init, chains * desc->head_dim * desc->head_dim, s) == hipSuccess
+               ? LA2_OK : LA2_ERR_LAUNCH;
+  }
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
+  if (kv_final != nullptr && desc->seqlen % kStateGranule != 0) return LA2_ERR_SHAPE;
   const Plan pl = make_plan(desc);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  return run_scan(desc, pl, false, ScanArgs{q, k, v, o}, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  ScanArgs a{q, k, v, o};
+  a.init = kv_init;
+  a.fin = kv_final;
+  return run_scan(desc, pl, false, a, lambda, workspace, s);
+}
+
+la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                   void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return la2_fwd_state(desc, q, k, v, lambda, nullptr, o, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
+                         void* dv, float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  const int64_t chains = (int64_t)desc->batch * desc->heads;
+  if (chains == 0) return LA2_OK;  // nothing to do
+  if (!aligned(kv_init, 16) || !aligned(d_kv_final, 16) || !aligned(d_kv_init, 16)) return LA2_ERR_STRIDE_ALIGN;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  if (desc->seqlen == 0) {  // the gradient of the state passes through
+    if (d_kv_init == nullptr) return LA2_OK;
+    return la2::launch_state_copy(d_kv_init, d_kv_final, chains * desc->head_dim * desc->head_dim, s) == hipSuccess
+               ? LA2_OK : LA2_ERR_LAUNCH;
+  }
+  if (!q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
+      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  if (d_kv_final != nullptr && desc->seqlen % kStateGranule != 0) return LA2_ERR_SHAPE;
+  const Plan pl = make_plan(desc);
+  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
+  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
+  // (forward scan of (dO, V, K); its state is KV^T, so a start state KV is read transposed)
+  ScanArgs for_dq{d_o, v, k, dq};
+  for_dq.init = kv_init;
+  for_dq.init_tr = true;
+  st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  // Algorithm 2, second loop (descending, running dKV):
+  //   dV = [(Q K^T) * M]^T dO + decay(K) dKV        reverse scan of (K, Q, dO), state dKV = Q^T dO
+  //   dK = [(dO V^T) * M]^T Q + decay(V) dKV^T      reverse scan of (V, dO, Q), state dKV^T
+  // dKV starts from the gradient of the final state and ends as the gradient of the start state.
+  ScanArgs for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
+  for_dv.init = d_kv_final;
+  for_dv.fin = d_kv_init;
+  for_dk.init = d_kv_final;
+  for_dk.init_tr = true;
+  if (desc->dtype == LA2_BF16) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, workspace, s);
+  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
 }
 
 la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                    const float* lambda, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
-  la2_status st = check_desc(desc);
-  if (st != LA2_OK) return st;
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
-  if (!q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
-  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
-      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
-    return LA2_ERR_STRIDE_ALIGN;
-  const Plan pl = make_plan(desc);
-  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
-  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
-  st = run_scan(desc, pl, false, ScanArgs{d_o, v, k, dq}, lambda, workspace, s);
-  if (st != LA2_OK) return st;
-  // Algorithm 2, second loop (descending, running dKV):
-  //   dV = [(Q K^T) * M]^T dO + decay(K) dKV        reverse scan of (K, Q, dO), state dKV = Q^T dO
-  //   dK = [(dO V^T) * M]^T Q + decay(V) dKV^T      reverse scan of (V, dO, Q), state dKV^T
-  const ScanArgs for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
-  if (desc->dtype == LA2_BF16) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, workspace, s);
-  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
-  if (st != LA2_OK) return st;
-  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
+  return la2_bwd_state(desc, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, workspace,
+                       workspace_bytes, hip_stream);
 }
 
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,

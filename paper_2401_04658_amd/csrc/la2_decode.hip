@@ -72,7 +72,18 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const void* q, const v
   }
 }
 
+__global__ void state_copy_kernel(float* dst, const float* src, int64_t count) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) dst[i] = src ? src[i] : 0.f;
+}
+
 }  // namespace
+
+hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s) {
+  if (count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(state_copy_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, dst, src, count);
+  return hipGetLastError();
+}
 
 hipError_t launch_decode(int batch, int heads, int head_dim, bool bf16, const void* q, const void* k,
                          const void* v, const float* lambda, float* kv, void* o, hipStream_t s) {

@@ -30,6 +30,18 @@ struct ScanParams {
   int32_t nchunks;       // sequence chunks processed by different workgroups
   int32_t chunk_tokens;  // tokens per chunk (multiple of the block size); last chunk may be short
   int32_t variant;       // bf16 d = 128 scan kernel: 0 automatic, 1 full-block, 2 half-block
+  // Optional start state of each scan's chains and destination of the state after each chain's last
+  // block: fp32 [chains][D][D], row = y feature, column = z feature (bit s of the *_transposed masks:
+  // scan s sees it transposed).  nullptr: zero start / not wanted.  State convention: entering a block
+  // that starts at position p the forward state is sum_{s<p} lambda^(p-1-s) y_s^T z_s (+ lambda^p init),
+  // entering a block that ends at position p (exclusive) the reverse state is
+  // sum_{s>=p} lambda^(s-p+1) y_s^T z_s (+ lambda^(n-p) init), so that both ends of a sequence need no
+  // division by lambda.  The final state is only meaningful when n is a multiple of the block size
+  // (forward) or when the reverse scan started from zero or n is such a multiple (reverse).
+  const float* init[2];
+  float* fin[2];
+  int32_t init_transposed;
+  int32_t fin_transposed;
 };
 
 // Block size (rows of the intra-block tile) per data type / head dim.
@@ -42,8 +54,12 @@ hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams
 // fp32 path
 hipError_t launch_scan_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
-// turns the per-chunk local states in p.states into chunk start states (any dtype: states are fp32)
+// turns the per-chunk local states in p.states into chunk start states (any dtype: states are fp32);
+// the first chunk starts from p.init[0] (seen through bit 0 of p.init_transposed) or zero
 hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+
+// dst[i] = src ? src[i] : 0 for count floats (a state that passes through an empty sequence)
+hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s);
 
 hipError_t launch_decode(int batch, int heads, int head_dim, bool bf16, const void* q, const void* k,
                          const void* v, const float* lambda, float* kv, void* o, hipStream_t s);

@@ -272,10 +272,10 @@ __device__ __forceinline__ float uniform(float x) {
 }
 
 // Row weights of the state update, S <- lambda^B S + Y^T decay(Z) with row c weighted lambda^(B-1-c)
-// (forward) or lambda^c (reverse), applied to the Z fragments (permuted k-order, 16 rows from c0).
+// (forward) or lambda^(c+1) (reverse), applied to the Z fragments (permuted k-order, 16 rows from c0).
 // Element j of lane half hh is row c0 + 4 hh + nj, nj = 8 (j / 4) + j % 4.  The weight is split into
 // a per-lane factor (one exp2 per fragment) and a wave-uniform factor per element:
-//   forward  lambda^(B-16-c0 + 4 (1-hh)) * lambda^(11-nj)      reverse  lambda^(c0 + 4 hh) * lambda^nj
+//   forward  lambda^(B-16-c0 + 4 (1-hh)) * lambda^(11-nj)      reverse  lambda^(c0 + 4 hh + 1) * lambda^nj
 // All exponents are non-negative.
 template <bool REV, int B = kB>
 struct UpdateDecay {
@@ -290,7 +290,7 @@ struct UpdateDecay {
     }
   }
   __device__ __forceinline__ bf16x8 apply(bf16x8 z, int c0) const {
-    const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh : B - 16 - c0 + 4 * (1 - hh)));
+    const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh + 1 : B - 16 - c0 + 4 * (1 - hh)));
     bf16x8 r;
 #pragma unroll
     for (int j = 0; j < 8; j++) r[j] = (__bf16)((float)z[j] * (step * gj[j]));
@@ -357,9 +357,16 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 
   // ---- running state slice S[:, dv tile]: NT accumulator tiles (key-feature tiles), fp32
   f32x16 kv[NT];
+  const float* gs = nullptr;   // start state: chunk start state, the caller's start state, or zero
+  bool tr = false;
   if (p.states != nullptr) {
-    const float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
-    const bool tr = (p.state_transposed >> which) & 1;
+    gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+    tr = (p.state_transposed >> which) & 1;
+  } else if (D == 64 && (which ? p.init[1] : p.init[0]) != nullptr) {   // d = 128 with states: half-block kernel
+    gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
+    tr = (p.init_transposed >> which) & 1;
+  }
+  if (gs != nullptr) {
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
@@ -399,12 +406,12 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   }
   const float oa = has_off ? exp2f(l2 * (float)(REV ? 32 - l32 + 4 * hh : l32 + 5 - 4 * hh)) : 0.f;
   // weight of the carried state at this lane's position r = 32 rt + l32: forward lambda^(r+1),
-  // reverse lambda^(B-r)
+  // reverse lambda^(B-1-r)
   float inter_scale[RT];
 #pragma unroll
   for (int i = 0; i < RT; i++) {
     const int r = 32 * (rt0 + i) + l32;
-    inter_scale[i] = exp2f(l2 * (float)(REV ? kB - r : r + 1));
+    inter_scale[i] = exp2f(l2 * (float)(REV ? kB - 1 - r : r + 1));
   }
   const UpdateDecay<REV> decay(l2, hh);
   const float lamB = exp2f(l2 * (float)kB);
@@ -682,6 +689,16 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
     out_store(ov, blk, true);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
   }
+  // state after the chain's last block, if the caller wants it (the update ran on every block)
+  float* gf = which ? p.fin[1] : p.fin[0];
+  if (D == 64 && gf != nullptr && (REV ? chunk == 0 : chunk == p.nchunks - 1) && rt0 == 0) {
+    gf += (int64_t)chain * (D * D);
+    const bool trf = (p.fin_transposed >> which) & 1;
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) gf[state_index<D>(dvt, l32, hh, t, v, trf)] = kv[t][v];
+  }
 #undef LA2_SLOT_END
 }
 
@@ -768,9 +785,16 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   const LaneAddr<D> la(l);
 
   f32x16 kv[NT];
+  const float* gs = nullptr;   // start state: chunk start state, the caller's start state, or zero
+  bool tr = false;
   if (p.states != nullptr) {
-    const float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
-    const bool tr = (p.state_transposed >> which) & 1;
+    gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+    tr = (p.state_transposed >> which) & 1;
+  } else if ((which ? p.init[1] : p.init[0]) != nullptr) {
+    gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
+    tr = (p.init_transposed >> which) & 1;
+  }
+  if (gs != nullptr) {
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
@@ -788,7 +812,7 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     const int e = REV ? cc - l32 : l32 - cc;
     dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
   }
-  const float inter_scale = exp2f(l2 * (float)(REV ? B - l32 : l32 + 1));
+  const float inter_scale = exp2f(l2 * (float)(REV ? B - 1 - l32 : l32 + 1));
   const UpdateDecay<REV, B> decay(l2, hh);
   const float lamB = uniform(exp2f(l2 * (float)B));
 
@@ -941,6 +965,16 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     if (!block_step(std::integral_constant<int, 2>{}, it + 2)) break;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
+  // state after the chain's last block, if the caller wants it (the update ran on every block)
+  float* gf = which ? p.fin[1] : p.fin[0];
+  if (gf != nullptr && (REV ? chunk == 0 : chunk == p.nchunks - 1)) {
+    gf += (int64_t)chain * (D * D);
+    const bool trf = (p.fin_transposed >> which) & 1;
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) gf[state_index<D>(dvt, l32, hh, t, v, trf)] = kv[t][v];
+  }
 #undef LA2_SLOT_END
   };
   if (TWIN && which == 1) run(std::integral_constant<int, 1>{});
@@ -1038,20 +1072,26 @@ __global__ __launch_bounds__(kThreads, 2) void chunk_state_bf16_kernel(ScanParam
 
 // In place: states[chain][j] (local state of chunk j) -> start state of chunk j.
 //   forward: G_0 = 0, G_{j+1} = lambda^C G_j + L_j        reverse: G_last = 0, G_{j-1} = lambda^C G_j + L_j
+// The chunk processed first starts from init (element e read at its transposed place if init_tr) or 0.
+// The carried state decays by lambda^(chunk length): all chunks are chunk_tokens long except the last
+// one of the sequence, which a reverse scan passes first.
 __global__ void state_scan_kernel(float* states, const float* lambda, int heads, int nchunks, int chunk_tokens,
-                                  int dd, int reverse) {
+                                  int dd, int reverse, const float* init, int init_tr, int d, int n) {
   const int chain = blockIdx.y;
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= dd) return;
-  const float lamC = exp2f(log2f(lambda[chain % heads]) * (float)chunk_tokens);
+  const float l2 = log2f(lambda[chain % heads]);
+  const float lamFull = exp2f(l2 * (float)chunk_tokens);
+  const float lamLast = exp2f(l2 * (float)(n - (nchunks - 1) * chunk_tokens));
   float* s = states + (int64_t)chain * nchunks * dd + e;
   float g = 0.f;
+  if (init != nullptr) g = init[(int64_t)chain * dd + (init_tr ? (e % d) * d + e / d : e)];
   for (int i = 0; i < nchunks; i++) {
     const int j = reverse ? nchunks - 1 - i : i;
     const bool last = (i == nchunks - 1);
     const float loc = last ? 0.f : s[(int64_t)j * dd];
     s[(int64_t)j * dd] = g;
-    g = lamC * g + loc;
+    g = (j == nchunks - 1 ? lamLast : lamFull) * g + loc;
   }
 }
 
@@ -1065,7 +1105,10 @@ hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hip
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   if (grid == 0 || p.n == 0) return hipSuccess;
   dim3 g((unsigned)grid), b(kThreads);
-  const bool half = p.variant != 1;   // measured faster at every launch size, also at one workgroup per compute unit
+  // the half-block kernel measured faster at every launch size, also at one workgroup per compute unit;
+  // it is also the only d = 128 kernel that takes start states and hands out final states
+  const bool with_state = p.init[0] || p.init[1] || p.fin[0] || p.fin[1];
+  const bool half = p.variant != 1 || with_state;
   if (head_dim == 128 && half && p.chunk_tokens % kBH == 0) {
     const bool twin = p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0];
     if (twin) {
@@ -1106,7 +1149,7 @@ hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hi
   const int dd = head_dim * head_dim;
   dim3 g((dd + 255) / 256, chains), b(256);
   hipLaunchKernelGGL(state_scan_kernel, g, b, 0, s, p.states, p.lambda, p.heads, p.nchunks, p.chunk_tokens, dd,
-                     reverse ? 1 : 0);
+                     reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n);
   return hipGetLastError();
 }
 

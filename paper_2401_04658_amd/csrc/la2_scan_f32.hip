@@ -33,7 +33,7 @@ __device__ __forceinline__ void load_tile(float* s, const float* g, int64_t stri
 }
 
 // S[k][j] <- lambda^B S[k][j] + sum_c decay_c Y[c][k] Z[c][j]; forward decay_c = lambda^(B-1-c),
-// reverse lambda^c.  sDec holds decay_c.
+// reverse lambda^(c+1).  sDec holds decay_c.
 template <int D>
 __device__ __forceinline__ void state_update(float* sS, const float* sY, const float* sZ, const float* sDec,
                                              float lamB, int tid) {
@@ -70,12 +70,21 @@ __global__ __launch_bounds__(kThreads) void scan_f32_kernel(ScanParams p) {
   const int blk_hi = min(blk_lo + cb, nblocks);
   if (blk_lo >= blk_hi) return;
 
+  // start state: chunk start state, the caller's start state (possibly stored transposed), or zero
   const float* gs = p.states ? p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D) : nullptr;
-  for (int idx = tid; idx < D * D; idx += kThreads) sS[(idx / D) * LD + idx % D] = gs ? gs[idx] : 0.f;
-  if (tid < B) {
-    sDec[tid] = exp2f(l2 * (float)(REV ? tid : B - 1 - tid));      // weight of row c in the state update
-    sInter[tid] = exp2f(l2 * (float)(REV ? B - tid : tid + 1));    // weight of the carried state for row r
+  bool tr = false;
+  if (gs == nullptr && p.init[0] != nullptr) {
+    gs = p.init[0] + (int64_t)chain * (D * D);
+    tr = p.init_transposed & 1;
   }
+  for (int idx = tid; idx < D * D; idx += kThreads)
+    sS[(idx / D) * LD + idx % D] = gs ? gs[tr ? (idx % D) * D + idx / D : idx] : 0.f;
+  if (tid < B) {
+    sDec[tid] = exp2f(l2 * (float)(REV ? tid + 1 : B - 1 - tid));      // weight of row c in the state update
+    sInter[tid] = exp2f(l2 * (float)(REV ? B - 1 - tid : tid + 1));    // weight of the carried state for row r
+  }
+  float* gf = (p.fin[0] != nullptr && (REV ? chunk == 0 : chunk == p.nchunks - 1)) ? p.fin[0] + (int64_t)chain * (D * D)
+                                                                                   : nullptr;
 
   const int nblk = blk_hi - blk_lo;
   for (int it = 0; it < nblk; it++) {
@@ -106,9 +115,14 @@ __global__ __launch_bounds__(kThreads) void scan_f32_kernel(ScanParams p) {
       const int pos = blk * B + r;
       if (pos < n) gw[(int64_t)pos * p.stride_n + j] = intra + sInter[r] * inter;
     }
-    if (it + 1 == nblk) break;  // the state after a chunk's last block is never used
+    if (it + 1 == nblk && gf == nullptr) break;  // the state after the last block is only needed on request
     __syncthreads();
     state_update<D>(sS, sY, sZ, sDec, lamB, tid);
+  }
+  if (gf != nullptr) {
+    __syncthreads();
+    const bool trf = p.fin_transposed & 1;
+    for (int idx = tid; idx < D * D; idx += kThreads) gf[trf ? (idx % D) * D + idx / D : idx] = sS[(idx / D) * LD + idx % D];
   }
 }
 
@@ -134,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void chunk_state_f32_kernel(ScanParams p)
   const int blk_hi = min(blk_lo + cb, nblocks);
 
   for (int idx = tid; idx < D * D; idx += kThreads) sS[(idx / D) * LD + idx % D] = 0.f;
-  if (tid < B) sDec[tid] = exp2f(l2 * (float)(REV ? tid : B - 1 - tid));
+  if (tid < B) sDec[tid] = exp2f(l2 * (float)(REV ? tid + 1 : B - 1 - tid));
   const int nblk = blk_hi - blk_lo;
   for (int it = 0; it < nblk; it++) {
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;

@@ -172,3 +172,35 @@ def test_binding_refuses_cpu_tensors(lib):
         binding.la2_fwd(x, x, x, lam)
     with pytest.raises(ValueError):
         binding.la2_bwd(x, x, x, x, lam)
+
+
+def fwd_state(lib, desc, kv_init=None, kv_final=None, q=P, ws=None, ws_bytes=0):
+    return lib.la2_fwd_state(ctypes.byref(desc), q, P, P, P, kv_init, P, kv_final, ws, ws_bytes, None)
+
+
+def bwd_state(lib, desc, kv_init=None, d_kv_final=None, d_kv_init=None, q=P):
+    return lib.la2_bwd_state(ctypes.byref(desc), q, P, P, P, P, kv_init, d_kv_final, P, P, P, d_kv_init, None, 0,
+                             None)
+
+
+def test_state_entry_points_validate_before_any_launch(lib):
+    # final states need whole blocks (a multiple of 64 positions)
+    for n in (1, 63, 100, 129):
+        d = dense(lib, 300, 1, n, 64, binding.LA2_BF16)
+        assert fwd_state(lib, d, kv_final=P) == E_SHAPE
+        assert bwd_state(lib, d, d_kv_final=P) == E_SHAPE
+    # misaligned state pointers
+    d = dense(lib, 300, 1, 128, 64, binding.LA2_BF16)
+    assert fwd_state(lib, d, kv_init=P + 4) == E_ALIGN
+    assert fwd_state(lib, d, kv_final=P + 8) == E_ALIGN
+    assert bwd_state(lib, d, d_kv_final=P + 4) == E_ALIGN
+    assert bwd_state(lib, d, d_kv_init=P + 4) == E_ALIGN
+    # the other checks are those of la2_fwd / la2_bwd
+    assert fwd_state(lib, d, kv_init=P, q=None) == E_NULL
+    assert bwd_state(lib, d, kv_init=P, q=None) == E_NULL
+    d.head_dim = 96
+    assert fwd_state(lib, d, kv_init=P) == E_SHAPE
+    # nothing to do: no chains; an empty sequence with no state wanted
+    assert fwd_state(lib, dense(lib, 0, 4, 128, 64, binding.LA2_BF16), kv_init=P, kv_final=P) == OK
+    assert fwd_state(lib, dense(lib, 2, 4, 0, 64, binding.LA2_BF16), kv_init=P) == OK
+    assert bwd_state(lib, dense(lib, 2, 4, 0, 64, binding.LA2_BF16), kv_init=P) == OK

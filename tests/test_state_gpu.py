@@ -1,0 +1,168 @@
+"""GPU parity of la2_fwd_state / la2_bwd_state (segments with state hand-over) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_04658_amd import binding, workloads
+from parity import TOL, assert_close, max_rel, to64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+    yield
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+
+
+def inputs(b, H, n, d, dtype, seed, lam=None):
+    t = workloads.Workload("case", b, H, n, d, dtype, seed=seed, backward=True).tensors()
+    if lam is not None:
+        t["lam"] = torch.as_tensor(lam, dtype=torch.float32).reshape(-1).expand(H).contiguous()
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed + 1000)
+    # states of the size a few hundred tokens of such inputs build up; gradients of the same order
+    t["kv_init"] = torch.randn((b, H, d, d), generator=g, dtype=torch.float32) * 0.3
+    t["d_kv_final"] = torch.randn((b, H, d, d), generator=g, dtype=torch.float32) * 0.3
+    return t
+
+
+def state_tol(dtype):
+    # states are fp32 sums of products of the (bf16 or fp32) inputs
+    return TOL[dtype]
+
+
+def check_segment(t, dtype, tag, use_init=True, use_final=True):
+    g = {k: v.to(DEV) for k, v in t.items()}
+    kv_init = g["kv_init"] if use_init else None
+    d_fin = g["d_kv_final"] if use_final else None
+    o, kvf = binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=kv_init, want_final=use_final)
+    dq, dk, dv, dkv0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=kv_init,
+                                             d_kv_final=d_fin)
+    torch.cuda.synchronize()
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    init64 = to64(t["kv_init"]) if use_init else None
+    fin64 = to64(t["d_kv_final"]) if use_final else None
+    ro, rkvf = oracle.fwd_recurrent(q, k, v, lam, kv_init=init64, return_state=True)
+    rdq, rdk, rdv, rdkv0 = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=init64, d_kv_final=fin64)
+    assert_close(tag + " o", o, ro, dtype)
+    if use_final:
+        assert_close(tag + " kv_final", kvf, rkvf, dtype)
+    assert_close(tag + " dq", dq, rdq, dtype)
+    assert_close(tag + " dk", dk, rdk, dtype)
+    assert_close(tag + " dv", dv, rdv, dtype)
+    assert_close(tag + " d_kv_init", dkv0, rdkv0, dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n", [64, 128, 320])
+def test_segment_with_all_states(dtype, d, n):
+    t = inputs(2, 3, n, d, dtype, seed=500 + n + d, lam=[0.5, 0.93, 1.0])
+    check_segment(t, dtype, "n%d d%d %s" % (n, d, dtype))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n", [1, 31, 100, 129])
+def test_ragged_segment_with_start_state_only(dtype, d, n):
+    """kv_init and d_kv_init work for any length; the final states need whole blocks."""
+    t = inputs(1, 3, n, d, dtype, seed=600 + n + d, lam=[0.43, 0.9, 0.99])
+    check_segment(t, dtype, "ragged n%d d%d %s" % (n, d, dtype), use_final=False)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    with pytest.raises(binding.LA2Error):
+        binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], want_final=True)
+    with pytest.raises(binding.LA2Error):
+        binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], d_kv_final=g["d_kv_final"])
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("chunk", [0, 128])
+@pytest.mark.parametrize("d", [64, 128])
+def test_segment_chunked_and_variants(variant, chunk, d):
+    binding.la2_set_scan_variant(variant)
+    binding.la2_set_chunk_tokens(chunk)
+    t = inputs(1, 4, 512, d, torch.bfloat16, seed=700 + d + chunk)
+    if chunk:
+        assert binding.la2_workspace_bytes(t["q"].to(DEV)) > 0
+    check_segment(t, torch.bfloat16, "variant%d chunk%d d%d" % (variant, chunk, d))
+
+
+def test_fp32_chunked_segment():
+    binding.la2_set_chunk_tokens(128)
+    t = inputs(1, 2, 384, 128, torch.float32, seed=777)
+    check_segment(t, torch.float32, "fp32 chunked")
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_two_segments_equal_the_whole_sequence(dtype):
+    """Forward left to right, backward right to left through the hand-over states, against the oracle's
+    DIRECT form of the whole sequence (which has no notion of a state)."""
+    b, H, n, d, cut = 2, 4, 448, 128, 192
+    t = inputs(b, H, n, d, dtype, seed=800)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    seg = [slice(0, cut), slice(cut, n)]
+    part = lambda name, s: g[name][:, :, s].contiguous()
+    o1, s1 = binding.la2_fwd_state(part("q", seg[0]), part("k", seg[0]), part("v", seg[0]), g["lam"])
+    o2, _ = binding.la2_fwd_state(part("q", seg[1]), part("k", seg[1]), part("v", seg[1]), g["lam"], kv_init=s1,
+                                  want_final=False)
+    dq2, dk2, dv2, gs = binding.la2_bwd_state(part("q", seg[1]), part("k", seg[1]), part("v", seg[1]),
+                                              part("d_o", seg[1]), g["lam"], kv_init=s1)
+    dq1, dk1, dv1, g0 = binding.la2_bwd_state(part("q", seg[0]), part("k", seg[0]), part("v", seg[0]),
+                                              part("d_o", seg[0]), g["lam"], d_kv_final=gs)
+    torch.cuda.synchronize()
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    assert_close("two segments o", torch.cat([o1, o2], 2), oracle.fwd_direct(q, k, v, lam), dtype)
+    rq, rk, rv = oracle.bwd_direct(q, k, v, do, lam)
+    assert_close("two segments dq", torch.cat([dq1, dq2], 2), rq, dtype)
+    assert_close("two segments dk", torch.cat([dk1, dk2], 2), rk, dtype)
+    assert_close("two segments dv", torch.cat([dv1, dv2], 2), rv, dtype)
+
+
+def test_prefill_then_decode():
+    """The final state of a prefill continues with la2_decode_step (same state layout)."""
+    b, H, n, d = 2, 4, 256, 128
+    t = inputs(b, H, n + 3, d, torch.bfloat16, seed=900)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    head = lambda name: g[name][:, :, :n].contiguous()
+    _, state = binding.la2_fwd_state(head("q"), head("k"), head("v"), g["lam"])
+    outs = []
+    for i in range(n, n + 3):
+        outs.append(binding.la2_decode_step(g["q"][:, :, i].contiguous(), g["k"][:, :, i].contiguous(),
+                                            g["v"][:, :, i].contiguous(), g["lam"], state))
+    torch.cuda.synchronize()
+    ref = oracle.fwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"]))
+    for j, o in enumerate(outs):
+        assert max_rel(to64(o), ref[:, :, n + j]) <= TOL[torch.bfloat16]
+
+
+def test_empty_segment_passes_the_state_through():
+    t = inputs(2, 2, 0, 64, torch.bfloat16, seed=1)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    _, kvf = binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=g["kv_init"])
+    *_, g0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], d_kv_final=g["d_kv_final"])
+    _, kvz = binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"])
+    torch.cuda.synchronize()
+    assert torch.equal(kvf, g["kv_init"]) and torch.equal(g0, g["d_kv_final"])
+    assert torch.count_nonzero(kvz) == 0
+
+
+@pytest.mark.parametrize("point", [1, 2])
+def test_sweep_points_with_states(point):
+    """Configuration-3 sweep points ((16, 4K) un-chunked, (4, 16K) sequence-chunked) in the launch
+    configuration bench.py times, with a start state and both state gradients; full tensors against the
+    oracle's recurrent form."""
+    wl = workloads.CONFIG3[point]
+    t = wl.tensors()
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4242 + point)
+    shape = (wl.batch, wl.heads, wl.head_dim, wl.head_dim)
+    t["kv_init"] = torch.randn(shape, generator=g, dtype=torch.float32) * 0.3
+    t["d_kv_final"] = torch.randn(shape, generator=g, dtype=torch.float32) * 0.3
+    check_segment(t, wl.dtype, wl.name + " with states")
