@@ -227,7 +227,22 @@ def main():
               "tokens_per_s": round(dw.batch / (dec_ms * 1e-3), 1),
               "achieved_GBs": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
               "frac_hbm_peak": round(dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-    del kv
+    # the same tokens 8 per launch (multi-token decode): the state is read and written once per launch
+    T = 8
+    qm, km, vm = (torch.stack([toks[i][j] for i in range(T)], 2).contiguous() for j in range(3))
+    om = torch.empty_like(qm)
+    for _ in range(4):
+        binding.la2_decode_multi(qm, km, vm, lam5, kv, out=om)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(dw.steps // T):
+        binding.la2_decode_multi(qm, km, vm, lam5, kv, out=om)
+    e1.record()
+    torch.cuda.synchronize()
+    dm_ms = e0.elapsed_time(e1) / (dw.steps // T)
+    decode["multi_token"] = {"tokens_per_launch": T, "us_per_launch": round(dm_ms * 1e3, 2),
+                             "tokens_per_s": round(dw.batch * T / (dm_ms * 1e-3), 1)}
+    del kv, qm, km, vm, om
 
     # ---- CPU baseline: the fp64 oracle (direct O(n^2) form) on a bounded sample ---------------------------
     cpu = None

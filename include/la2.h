@@ -53,7 +53,7 @@ typedef enum {
 
 typedef enum { LA2_F32 = 0, LA2_BF16 = 1 } la2_dtype;
 
-typedef enum { LA2_OP_FWD = 0, LA2_OP_BWD = 1 } la2_op;
+typedef enum { LA2_OP_FWD = 0, LA2_OP_BWD = 1, LA2_OP_FWD_STATE = 2, LA2_OP_BWD_STATE = 3 } la2_op;
 
 /* Host-side description of the sequence tensors. */
 typedef struct {
@@ -115,9 +115,10 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
  *   d_kv_init   out  gradient with respect to kv_init, or NULL if not wanted
  * la2_bwd_state needs the kv_init the forward pass was given (dq depends on it).  All other arguments
  * as for la2_fwd / la2_bwd, which are these functions with NULL states.  State pointers are 16-byte
- * aligned.  kv_final and d_kv_final require seqlen to be a multiple of 64 (the state after a partial
- * block is not formed): LA2_ERR_SHAPE otherwise.  seqlen == 0 copies the state through
- * (kv_final = kv_init, d_kv_init = d_kv_final; zero if the input is NULL).
+ * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen:
+ * when kv_final / d_kv_final is given and seqlen is not a multiple of 64, the last seqlen % 64 positions
+ * run token by token (the block kernels form states after whole blocks only).  seqlen == 0 copies the
+ * state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if the input is NULL).
  */
 la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
                          const float* lambda, const float* kv_init, void* o, float* kv_final,
@@ -140,6 +141,21 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype,
                            const void* q, const void* k, const void* v, const float* lambda,
                            float* kv_state, void* o, void* hip_stream);
+
+/*
+ * ntokens consecutive decode steps in one launch (recursive form of Sec. 3.2.1): for t = 0 .. ntokens-1
+ * kv_state <- lambda_h kv_state + k_t^T v_t, o_t = q_t kv_state.  The state is read and written once per
+ * launch instead of once per token.
+ *   q, k, v   in      device, dense [batch, heads, ntokens, head_dim], dtype qkv_dtype (la2_dtype)
+ *   lambda    in      device, fp32 [heads]
+ *   kv_state  in/out  device, fp32 dense [batch, heads, head_dim, head_dim], updated in place
+ *   o         out     device, dense [batch, heads, ntokens, head_dim], dtype qkv_dtype
+ * All pointers 16-byte aligned.  head_dim is 64 or 128; ntokens <= 65536.  Same result as ntokens calls of
+ * la2_decode_step up to rounding order.
+ */
+la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens,
+                            int32_t qkv_dtype, const void* q, const void* k, const void* v,
+                            const float* lambda, float* kv_state, void* o, void* hip_stream);
 
 /*
  * Block size B (rows of the intra-block tile, Algorithm 1) of the scan kernel the library launches

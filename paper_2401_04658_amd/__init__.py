@@ -8,5 +8,6 @@ from .binding import (  # noqa: F401
     la2_fwd_state,
     la2_bwd_state,
     la2_decode_step,
+    la2_decode_multi,
     la2_workspace_bytes,
 )

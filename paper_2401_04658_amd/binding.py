@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libla2.so")
 _lib = None
 
 LA2_F32, LA2_BF16 = 0, 1
-LA2_OP_FWD, LA2_OP_BWD = 0, 1
+LA2_OP_FWD, LA2_OP_BWD, LA2_OP_FWD_STATE, LA2_OP_BWD_STATE = 0, 1, 2, 3
 
 
 class LA2Error(RuntimeError):
@@ -65,6 +65,8 @@ def load():
     lib.la2_fwd_state.restype = ctypes.c_int
     lib.la2_bwd_state.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_state.restype = ctypes.c_int
+    lib.la2_decode_multi.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.la2_decode_multi.restype = ctypes.c_int
     lib.la2_decode_step.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.la2_decode_step.restype = ctypes.c_int
     lib.la2_status_string.argtypes = [ctypes.c_int]
@@ -193,7 +195,7 @@ def la2_fwd_state(q, k, v, lam, kv_init=None, want_final=True, out=None, kv_fina
     if want_final and kv_final is None:
         kv_final = torch.empty((b, h, d, d), dtype=torch.float32, device=q.device)
     desc = make_desc(q)
-    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_FWD, workspace)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_FWD_STATE, workspace)
     with torch.cuda.device(q.device):
         _check(lib.la2_fwd_state(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
                                  _state(kv_init, q, "kv_init"), out.data_ptr(),
@@ -217,7 +219,7 @@ def la2_bwd_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_in
     if want_d_kv_init and d_kv_init is None:
         d_kv_init = torch.empty((b, h, d, d), dtype=torch.float32, device=q.device)
     desc = make_desc(q)
-    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD, workspace)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD_STATE, workspace)
     with torch.cuda.device(q.device):
         _check(lib.la2_bwd_state(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
                                  lam.data_ptr(), _state(kv_init, q, "kv_init"),
@@ -243,4 +245,24 @@ def la2_decode_step(q, k, v, lam, kv_state, out=None):
     with torch.cuda.device(q.device):
         _check(lib.la2_decode_step(b, h, d, _dtype_code(q), q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                    lam.data_ptr(), kv_state.data_ptr(), out.data_ptr(), _stream(q)))
+    return out
+
+
+def la2_decode_multi(q, k, v, lam, kv_state, out=None):
+    """ntokens consecutive recurrent steps in one launch.  q, k, v: dense [b, H, T, d]; kv_state (fp32
+    [b, H, d, d]) is updated in place; returns o [b, H, T, d]."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_decode_multi: tensors must live on the GPU")
+    b, h, t, d = q.shape
+    for x in (q, k, v):
+        if x.shape != q.shape or x.dtype != q.dtype or not x.is_contiguous():
+            raise ValueError("la2_decode_multi: q, k, v must be dense [b, H, T, d] of one dtype")
+    if kv_state.dtype != torch.float32 or tuple(kv_state.shape) != (b, h, d, d) or not kv_state.is_contiguous():
+        raise ValueError("la2_decode_multi: kv_state must be dense fp32 [b, H, d, d]")
+    if out is None:
+        out = torch.empty_like(q)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_decode_multi(b, h, d, t, _dtype_code(q), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                    lam.data_ptr(), kv_state.data_ptr(), out.data_ptr(), _stream(q)))
     return out

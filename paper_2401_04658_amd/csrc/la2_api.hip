@@ -9,7 +9,7 @@ namespace {
 
 int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
 int g_scan_variant = 0;           // la2_set_scan_variant()
-// A final state is the state after whole blocks only: sequence lengths that every kernel's block size divides
+// The block kernels form states after whole blocks only; 64 positions is a multiple of every kernel's block size
 constexpr int kStateGranule = 64;
 
 int device_cu_count() {
@@ -149,6 +149,45 @@ la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanAr
   return la2::launch_scan_bf16(d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
+// The state entry points split a sequence whose length is not a multiple of kStateGranule into whole
+// blocks (block kernels) and a tail (token recurrence) when the state beyond the tail is asked for.
+// Their workspace: chunk states of whichever of the two plans needs more, then (backward only) one
+// d x d fp32 state per chain that carries dKV from the tail to the block kernels.
+struct StateWorkspace {
+  size_t chunk_states;   // bytes, 256-byte multiple
+  size_t total;
+};
+
+la2_desc whole_blocks(const la2_desc* d) {
+  la2_desc w = *d;
+  w.seqlen = d->seqlen - d->seqlen % kStateGranule;
+  return w;
+}
+
+StateWorkspace state_workspace(const la2_desc* d, bool backward) {
+  StateWorkspace w{make_plan(d).workspace, 0};
+  if (d->seqlen % kStateGranule != 0) {
+    const la2_desc wb = whole_blocks(d);
+    const size_t other = make_plan(&wb).workspace;
+    if (other > w.chunk_states) w.chunk_states = other;
+  }
+  w.chunk_states = (w.chunk_states + 255) & ~(size_t)255;
+  w.total = w.chunk_states;
+  if (backward && d->seqlen % kStateGranule != 0)
+    w.total += (size_t)d->batch * d->heads * d->head_dim * d->head_dim * sizeof(float);
+  return w;
+}
+
+la2::RecurParams recur_params(const la2_desc* d, const float* lambda, int t0, int t1, bool reverse) {
+  la2::RecurParams p{};
+  p.lambda = lambda;
+  p.heads = d->heads;
+  p.t0 = t0; p.t1 = t1;
+  p.reverse = reverse ? 1 : 0;
+  p.stride_b = d->stride_b; p.stride_h = d->stride_h; p.stride_n = d->stride_n;
+  return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -169,8 +208,10 @@ void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen
 
 size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
   if (check_desc(desc) != LA2_OK) return 0;
-  if (op != LA2_OP_FWD && op != LA2_OP_BWD) return 0;
-  return make_plan(desc).workspace;  // the backward's three scans run one after another in the same space
+  if (op == LA2_OP_FWD || op == LA2_OP_BWD)
+    return make_plan(desc).workspace;  // the backward's three scans run one after another in the same space
+  if (op == LA2_OP_FWD_STATE || op == LA2_OP_BWD_STATE) return state_workspace(desc, op == LA2_OP_BWD_STATE).total;
+  return 0;
 }
 
 int32_t la2_block_size(const la2_desc* desc) {
@@ -201,14 +242,25 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  if (kv_final != nullptr && desc->seqlen % kStateGranule != 0) return LA2_ERR_SHAPE;
-  const Plan pl = make_plan(desc);
+  const bool split = kv_final != nullptr && desc->seqlen % kStateGranule != 0;
+  const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the block kernels process
+  const Plan pl = make_plan(&blocks);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  ScanArgs a{q, k, v, o};
-  a.init = kv_init;
-  a.fin = kv_final;
-  return run_scan(desc, pl, false, a, lambda, workspace, s);
+  if (blocks.seqlen > 0) {
+    ScanArgs a{q, k, v, o};
+    a.init = kv_init;
+    a.fin = kv_final;
+    st = run_scan(&blocks, pl, false, a, lambda, workspace, s);
+    if (st != LA2_OK || !split) return st;
+  }
+  // the positions after the last whole block, token by token, from the state the blocks left
+  la2::RecurParams r = recur_params(desc, lambda, blocks.seqlen, desc->seqlen, false);
+  r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
+  r.init[0] = blocks.seqlen > 0 ? kv_final : kv_init;
+  r.fin[0] = kv_final;
+  return la2::launch_recur(desc->head_dim, desc->dtype == LA2_BF16, desc->batch, 1, r, s) == hipSuccess
+             ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
@@ -234,10 +286,16 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
       !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  if (d_kv_final != nullptr && desc->seqlen % kStateGranule != 0) return LA2_ERR_SHAPE;
-  const Plan pl = make_plan(desc);
-  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
-  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  // With a gradient coming in at the end of a sequence that does not end on a block boundary, the reverse
+  // pass runs the tail token by token first and hands dKV to the block kernels through the workspace.
+  const bool split = d_kv_final != nullptr && desc->seqlen % kStateGranule != 0;
+  const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the reverse block kernels process
+  const Plan pl = make_plan(desc), pl_rev = make_plan(&blocks);
+  const StateWorkspace sw = state_workspace(desc, true);
+  const size_t need = split ? sw.total : pl.workspace;
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LA2_ERR_WORKSPACE;
+  if (need > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  float* handoff = split ? reinterpret_cast<float*>(static_cast<char*>(workspace) + sw.chunk_states) : nullptr;
   // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
   // (forward scan of (dO, V, K); its state is KV^T, so a start state KV is read transposed)
   ScanArgs for_dq{d_o, v, k, dq};
@@ -249,15 +307,28 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
   //   dV = [(Q K^T) * M]^T dO + decay(K) dKV        reverse scan of (K, Q, dO), state dKV = Q^T dO
   //   dK = [(dO V^T) * M]^T Q + decay(V) dKV^T      reverse scan of (V, dO, Q), state dKV^T
   // dKV starts from the gradient of the final state and ends as the gradient of the start state.
+  const float* rev_init = d_kv_final;
+  if (split) {
+    la2::RecurParams r = recur_params(desc, lambda, blocks.seqlen, desc->seqlen, true);
+    r.x[0] = k; r.y[0] = q; r.z[0] = d_o; r.w[0] = dv;     // dv_t = k_t G_t, G = sum q^T do
+    r.x[1] = v; r.y[1] = d_o; r.z[1] = q; r.w[1] = dk;     // dk_t = v_t G_t^T
+    r.init[0] = d_kv_final; r.init[1] = d_kv_final;
+    r.init_transposed = 2;
+    r.fin[0] = blocks.seqlen > 0 ? handoff : d_kv_init;
+    if (la2::launch_recur(desc->head_dim, desc->dtype == LA2_BF16, desc->batch, 2, r, s) != hipSuccess)
+      return LA2_ERR_LAUNCH;
+    if (blocks.seqlen == 0) return LA2_OK;
+    rev_init = handoff;
+  }
   ScanArgs for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
-  for_dv.init = d_kv_final;
+  for_dv.init = rev_init;
   for_dv.fin = d_kv_init;
-  for_dk.init = d_kv_final;
+  for_dk.init = rev_init;
   for_dk.init_tr = true;
-  if (desc->dtype == LA2_BF16) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, workspace, s);
-  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
+  if (desc->dtype == LA2_BF16) return run_dual_reverse_scan(&blocks, pl_rev, for_dv, for_dk, lambda, workspace, s);
+  st = run_scan(&blocks, pl_rev, true, for_dv, lambda, workspace, s);
   if (st != LA2_OK) return st;
-  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
+  return run_scan(&blocks, pl_rev, true, for_dk, lambda, workspace, s);
 }
 
 la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
@@ -281,6 +352,28 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
   hipError_t e = la2::launch_decode(batch, heads, head_dim, qkv_dtype == LA2_BF16, q, k, v, lambda, kv_state, o,
                                     reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
+la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,
+                            const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
+                            void* o, void* hip_stream) {
+  if (qkv_dtype != LA2_F32 && qkv_dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (batch < 0 || heads < 0 || ntokens < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
+  if ((int64_t)batch * heads > (int64_t)1 << 24 || ntokens > 65536) return LA2_ERR_SHAPE;
+  if ((int64_t)batch * heads * ntokens == 0) return LA2_OK;  // nothing to do
+  if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(kv_state, 16) ||
+      !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  la2_desc d;
+  la2_desc_dense(&d, batch, heads, ntokens, head_dim, (la2_dtype)qkv_dtype);
+  la2::RecurParams r = recur_params(&d, lambda, 0, ntokens, false);
+  r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
+  r.init[0] = kv_state;
+  r.fin[0] = kv_state;
+  return la2::launch_recur(head_dim, qkv_dtype == LA2_BF16, batch, 1, r, reinterpret_cast<hipStream_t>(hip_stream)) ==
+                 hipSuccess
+             ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 const char* la2_status_string(la2_status status) {

@@ -58,6 +58,28 @@ hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams&
 // the first chunk starts from p.init[0] (seen through bit 0 of p.init_transposed) or zero
 hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 
+// Token-by-token recurrence over positions [t0, t1) of every chain, up to two instances per launch:
+//   forward (reverse == 0), ascending:   S <- lambda S + y_t^T z_t,  w_t = x_t S
+//   reverse (reverse == 1), descending:  S <- S + y_t^T z_t,  w_t = x_t S,  then S <- lambda S
+// S starts from init[i] (fp32 [chains][D][D], row = y feature; nullptr = 0; bit i of init_transposed:
+// stored transposed) and is written to fin[i] afterwards (may alias init[i]; nullptr = not wanted).
+// With these conventions the states are the ones ScanParams describes.
+struct RecurParams {
+  const void* x[2];
+  const void* y[2];
+  const void* z[2];
+  void* w[2];
+  const float* init[2];
+  float* fin[2];
+  int32_t init_transposed, fin_transposed;
+  const float* lambda;   // [heads], device
+  int32_t heads;
+  int32_t t0, t1;
+  int32_t reverse;
+  int64_t stride_b, stride_h, stride_n;  // elements, all of x, y, z, w
+};
+hipError_t launch_recur(int head_dim, bool bf16, int batch, int ninst, const RecurParams& p, hipStream_t s);
+
 // dst[i] = src ? src[i] : 0 for count floats (a state that passes through an empty sequence)
 hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s);
 

@@ -184,11 +184,15 @@ def bwd_state(lib, desc, kv_init=None, d_kv_final=None, d_kv_init=None, q=P):
 
 
 def test_state_entry_points_validate_before_any_launch(lib):
-    # final states need whole blocks (a multiple of 64 positions)
-    for n in (1, 63, 100, 129):
-        d = dense(lib, 300, 1, n, 64, binding.LA2_BF16)
-        assert fwd_state(lib, d, kv_final=P) == E_SHAPE
-        assert bwd_state(lib, d, d_kv_final=P) == E_SHAPE
+    # a gradient entering at the end of a sequence that does not end on a block boundary needs workspace
+    # (the hand-over of dKV from the token-by-token tail to the block kernels)
+    d = dense(lib, 300, 2, 100, 64, binding.LA2_BF16)
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 1) == 0
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 300 * 2 * 64 * 64 * 4
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 2) == 0
+    assert bwd_state(lib, d, d_kv_final=P) == E_WS
+    d = dense(lib, 300, 2, 128, 64, binding.LA2_BF16)
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 0
     # misaligned state pointers
     d = dense(lib, 300, 1, 128, 64, binding.LA2_BF16)
     assert fwd_state(lib, d, kv_init=P + 4) == E_ALIGN
@@ -204,3 +208,12 @@ def test_state_entry_points_validate_before_any_launch(lib):
     assert fwd_state(lib, dense(lib, 0, 4, 128, 64, binding.LA2_BF16), kv_init=P, kv_final=P) == OK
     assert fwd_state(lib, dense(lib, 2, 4, 0, 64, binding.LA2_BF16), kv_init=P) == OK
     assert bwd_state(lib, dense(lib, 2, 4, 0, 64, binding.LA2_BF16), kv_init=P) == OK
+
+
+def test_decode_multi_validation(lib):
+    dm = lambda b=1, h=1, d=64, t=4, dt=1, q=P, kv=P: lib.la2_decode_multi(b, h, d, t, dt, q, P, P, P, kv, P, None)
+    assert dm(q=None) == E_NULL and dm(kv=None) == E_NULL
+    assert dm(d=100) == E_SHAPE and dm(t=-1) == E_SHAPE and dm(b=-1) == E_SHAPE
+    assert dm(dt=5) == E_DTYPE
+    assert dm(q=P + 4) == E_ALIGN
+    assert dm(t=0, q=None) == OK and dm(b=0, q=None) == OK

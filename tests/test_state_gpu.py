@@ -70,16 +70,14 @@ def test_segment_with_all_states(dtype, d, n):
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("n", [1, 31, 100, 129])
-def test_ragged_segment_with_start_state_only(dtype, d, n):
-    """kv_init and d_kv_init work for any length; the final states need whole blocks."""
+@pytest.mark.parametrize("n", [1, 31, 64, 100, 129, 300])
+def test_ragged_segments(dtype, d, n):
+    """Lengths that do not end on a block boundary: the block kernels do the whole blocks, a token-by-token
+    tail the rest (both directions), with and without the states at the far end."""
     t = inputs(1, 3, n, d, dtype, seed=600 + n + d, lam=[0.43, 0.9, 0.99])
-    check_segment(t, dtype, "ragged n%d d%d %s" % (n, d, dtype), use_final=False)
-    g = {k: v.to(DEV) for k, v in t.items()}
-    with pytest.raises(binding.LA2Error):
-        binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], want_final=True)
-    with pytest.raises(binding.LA2Error):
-        binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], d_kv_final=g["d_kv_final"])
+    check_segment(t, dtype, "ragged n%d d%d %s start state only" % (n, d, dtype), use_final=False)
+    check_segment(t, dtype, "ragged n%d d%d %s all states" % (n, d, dtype))
+    check_segment(t, dtype, "ragged n%d d%d %s final states only" % (n, d, dtype), use_init=False)
 
 
 @pytest.mark.parametrize("variant", [1, 2])
@@ -166,3 +164,43 @@ def test_sweep_points_with_states(point):
     t["kv_init"] = torch.randn(shape, generator=g, dtype=torch.float32) * 0.3
     t["d_kv_final"] = torch.randn(shape, generator=g, dtype=torch.float32) * 0.3
     check_segment(t, wl.dtype, wl.name + " with states")
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("T", [1, 2, 7, 64])
+def test_decode_multi(dtype, d, T):
+    b, H = 3, 4
+    t = inputs(b, H, T, d, dtype, seed=1100 + T + d, lam=[0.5, 0.9, 0.99, 1.0])
+    g = {k: v.to(DEV) for k, v in t.items()}
+    state = g["kv_init"].clone()
+    o = binding.la2_decode_multi(g["q"], g["k"], g["v"], g["lam"], state)
+    # the same tokens one step at a time
+    state1 = g["kv_init"].clone()
+    o1 = [binding.la2_decode_step(g["q"][:, :, i].contiguous(), g["k"][:, :, i].contiguous(),
+                                  g["v"][:, :, i].contiguous(), g["lam"], state1) for i in range(T)]
+    torch.cuda.synchronize()
+    ro, rs = oracle.fwd_recurrent(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"]),
+                                  kv_init=to64(t["kv_init"]), return_state=True)
+    assert_close("decode_multi o", o, ro, dtype)
+    assert_close("decode_multi state", state, rs, dtype)
+    assert max_rel(to64(torch.stack(o1, 2)), ro) <= TOL[dtype]
+    assert max_rel(to64(state1), rs) <= TOL[dtype]
+
+
+def test_decode_multi_config5_shape():
+    """Configuration 5's batch and heads, 8 tokens per launch, one batch row against the oracle."""
+    dw = workloads.CONFIG5
+    gen = dw.generator()
+    kv0 = dw.initial_state(gen)
+    toks = [dw.token(gen) for _ in range(8)]
+    q, k, v = (torch.stack([tk[i] for tk in toks], 2).contiguous() for i in range(3))
+    lam = dw.decay()
+    state = kv0.to(DEV)
+    o = binding.la2_decode_multi(q.to(DEV), k.to(DEV), v.to(DEV), lam.to(DEV), state)
+    torch.cuda.synchronize()
+    rows = slice(5, 7)
+    ro, rs = oracle.fwd_recurrent(to64(q[rows]), to64(k[rows]), to64(v[rows]), to64(lam), kv_init=to64(kv0[rows]),
+                                  return_state=True)
+    assert_close("config5 multi o", o[rows], ro, torch.bfloat16)
+    assert_close("config5 multi state", state[rows], rs, torch.bfloat16)
