@@ -716,7 +716,10 @@ constexpr int kBH = 32;
 // same two tensors with the roles of Y and Z exchanged (dV: y = Q, z = dO; dK: y = dO, z = Q), so the
 // workgroup streams FOUR tiles per block (x of scan 0, x of scan 1, Q, dO) instead of six and every
 // tile is fetched exactly once.  Requires y[1] == z[0] and z[1] == y[0].
-template <bool REV, bool TWIN>
+//
+// NBUF tile buffers: block it + NBUF - 1 streams in while block it is computed.  With 3 buffers two
+// (plain) workgroups fit on a compute unit.
+template <bool REV, bool TWIN, int NBUF>
 __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
   constexpr int D = 128, B = kBH;
   using C = Cfg<D, B>;
@@ -724,14 +727,15 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   constexpr int NW = TWIN ? 8 : 4;             // waves
   constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
   using Loader = TileLoader<D, NTL, B, NW>;
-  __shared__ __attribute__((aligned(1024))) __bf16 sT0[NTL][TILE];
-  __shared__ __attribute__((aligned(1024))) __bf16 sT1[NTL][TILE];
-  __shared__ __attribute__((aligned(1024))) __bf16 sT2[NTL][TILE];
+  __shared__ __attribute__((aligned(1024))) __bf16 sT[NBUF][NTL][TILE];
   __shared__ __attribute__((aligned(16))) __bf16 sW[NW][32 * LW];
   constexpr int NDMA = NTL * Loader::DMA_PER_WAVE;   // direct loads per wave and block
   constexpr int NST = 32 * 4 / 64;             // 16-byte stores per lane and block
   static_assert(NDMA <= KS, "one direct load per slot of phase 1");
-  constexpr int VM_YOUNGER = NST + NDMA;
+  // vector-memory operations of this wave that are younger than the direct loads of block it + 1 when block
+  // it waits for them: the loads of blocks it + 2 .. it + NBUF - 1 and as many blocks' stores
+  constexpr int VM_YOUNGER = (NBUF - 2) * (NST + NDMA);
+  static_assert(VM_YOUNGER < 64, "vmcnt is a 6-bit counter");
   constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
@@ -816,20 +820,20 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   const UpdateDecay<REV, B> decay(l2, hh);
   const float lamB = uniform(exp2f(l2 * (float)B));
 
-  {
-    const int b0 = REV ? blk_hi - 1 : blk_lo, b1 = REV ? b0 - 1 : b0 + 1;
-    loader.issue(sT0, b0);
-    if (nblk > 1) loader.issue(sT1, b1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    loader.zero_tail(sT0, b0);
-    if (nblk > 1) loader.zero_tail(sT1, b1);
-  }
+  // prologue: the first NBUF - 1 blocks' tiles
+#pragma unroll
+  for (int j = 0; j < NBUF - 1; j++)
+    if (j < nblk) loader.issue(sT[j], REV ? blk_hi - 1 - j : blk_lo + j);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+#pragma unroll
+  for (int j = 0; j < NBUF - 1; j++)
+    if (j < nblk) loader.zero_tail(sT[j], REV ? blk_hi - 1 - j : blk_lo + j);
   __syncthreads();
 
   constexpr int AHEAD = 1;   // LDS operands are read one slot ahead (the other wave on the SIMD covers the rest)
   bf16x8 xa[KS];
 #pragma unroll
-  for (int ks = 0; ks < AHEAD; ks++) xa[ks] = la.read_row(sT0[xi], 0, ks);
+  for (int ks = 0; ks < AHEAD; ks++) xa[ks] = la.read_row(sT[0][xi], 0, ks);
   auto state_operand = [&](int ks) __attribute__((always_inline)) {
     bf16x8 f;
 #pragma unroll
@@ -848,17 +852,17 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   // 4 intra-block product), then the block's output.
   auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
-    __bf16 (*const sCur)[TILE] = cur == 0 ? sT0 : (cur == 1 ? sT1 : sT2);
-    __bf16 (*const sNext)[TILE] = cur == 0 ? sT1 : (cur == 1 ? sT2 : sT0);
-    __bf16 (*const sAhead)[TILE] = cur == 0 ? sT2 : (cur == 1 ? sT0 : sT1);
+    __bf16 (*const sCur)[TILE] = sT[cur];                          // block it
+    __bf16 (*const sNext)[TILE] = sT[(cur + 1) % NBUF];            // block it + 1 (in flight or landed)
+    __bf16 (*const sAhead)[TILE] = sT[(cur + NBUF - 1) % NBUF];    // block it + NBUF - 1 (free since block it - 1)
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
-    const bool has_next = it + 1 < nblk, has_ahead = it + 2 < nblk;
+    const bool has_next = it + 1 < nblk, has_ahead = it + NBUF - 1 < nblk;
     const int nb = REV ? blk - 1 : blk + 1;
     const __bf16* tX = sCur[xi];
     const __bf16* tY = sCur[yi];
     const __bf16* tZ = sCur[zi];
     uint32_t doff[Loader::DMA_PER_WAVE];
-    loader.offsets(REV ? blk - 2 : blk + 2, has_ahead, doff);
+    loader.offsets(REV ? blk - (NBUF - 1) : blk + (NBUF - 1), has_ahead, doff);
 
     bf16x8 zf[2], zd[2], yt[2][NT], xb[KS], yb[KS];
     auto read_xy = [&](int ks) __attribute__((always_inline)) {
@@ -959,10 +963,12 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     LA2_SLOT_END();
     return has_next;
   };
-  for (int it = 0;; it += 3) {
+  for (int it = 0;; it += NBUF) {   // unrolled by the number of buffers: compile-time buffer index
     if (!block_step(std::integral_constant<int, 0>{}, it)) break;
     if (!block_step(std::integral_constant<int, 1>{}, it + 1)) break;
     if (!block_step(std::integral_constant<int, 2>{}, it + 2)) break;
+    if (NBUF > 3 && !block_step(std::integral_constant<int, (NBUF > 3 ? 3 : 0)>{}, it + 3)) break;
+    if (NBUF > 4 && !block_step(std::integral_constant<int, (NBUF > 4 ? 4 : 0)>{}, it + 4)) break;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
   // state after the chain's last block, if the caller wants it (the update ran on every block)
@@ -1101,6 +1107,7 @@ int block_size_bf16(int) { return kB; }
 
 
 
+
 hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   if (grid == 0 || p.n == 0) return hipSuccess;
@@ -1111,13 +1118,16 @@ hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hip
   const bool half = p.variant != 1 || with_state;
   if (head_dim == 128 && half && p.chunk_tokens % kBH == 0) {
     const bool twin = p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0];
+    // Three tile buffers in every case.  More buffers (5 for a plain, 4 for a twin workgroup that has the
+    // compute unit to itself) measured no faster: such launches are bound by the workgroup's own
+    // instruction stream, not by the bytes in flight.
     if (twin) {
       dim3 gt((unsigned)(grid / 2)), bt(512);
-      if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, true>), gt, bt, 0, s, p);
-      else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, true>), gt, bt, 0, s, p);
+      if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, true, 3>), gt, bt, 0, s, p);
+      else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, true, 3>), gt, bt, 0, s, p);
     } else {
-      if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, false>), g, b, 0, s, p);
-      else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, false>), g, b, 0, s, p);
+      if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, false, 3>), g, b, 0, s, p);
+      else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, false, 3>), g, b, 0, s, p);
     }
   } else if (head_dim == 128) {
     if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<128, true>), g, b, 0, s, p);
