@@ -831,9 +831,12 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   __syncthreads();
 
   constexpr int AHEAD = 1;   // LDS operands are read one slot ahead (the other wave on the SIMD covers the rest)
-  bf16x8 xa[KS];
+  bf16x8 xa[KS], ya[KS];     // X and Y row fragments (natural k-order) of the block being computed
 #pragma unroll
-  for (int ks = 0; ks < AHEAD; ks++) xa[ks] = la.read_row(sT[0][xi], 0, ks);
+  for (int ks = 0; ks < AHEAD; ks++) {
+    xa[ks] = la.read_row(sT[0][xi], 0, ks);
+    ya[ks] = la.read_row(sT[0][yi], 0, ks);
+  }
   auto state_operand = [&](int ks) __attribute__((always_inline)) {
     bf16x8 f;
 #pragma unroll
@@ -848,8 +851,8 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     asm volatile("" ::: "memory");     \
     __builtin_amdgcn_sched_barrier(0); \
   } while (0)
-  // Phases as in scan_bf16_kernel (1 inter-block product, 2 scores, 3 state update, barrier,
-  // 4 intra-block product), then the block's output.
+  // Phases as in scan_bf16_kernel (1 inter-block product and 2 scores, here interleaved; 3 state update;
+  // barrier; 4 intra-block product), then the block's output.
   auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
     __bf16 (*const sCur)[TILE] = sT[cur];                          // block it
@@ -864,10 +867,10 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     uint32_t doff[Loader::DMA_PER_WAVE];
     loader.offsets(REV ? blk - (NBUF - 1) : blk + (NBUF - 1), has_ahead, doff);
 
-    bf16x8 zf[2], zd[2], yt[2][NT], xb[KS], yb[KS];
+    bf16x8 zf[2], zd[2], yt[2][NT];
     auto read_xy = [&](int ks) __attribute__((always_inline)) {
-      xb[ks] = la.read_row(tX, 0, ks);
-      yb[ks] = la.read_row(tY, 0, ks);
+      xa[ks] = la.read_row(tX, 0, ks);
+      ya[ks] = la.read_row(tY, 0, ks);
     };
     // Y^T fragments of update k-step q for the key-feature tiles 2 h, 2 h + 1
     auto read_yt = [&](int q, int h) __attribute__((always_inline)) {
@@ -875,45 +878,45 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
       for (int t = 2 * h; t < 2 * h + 2; t++) yt[q][t] = la.read_cols(tY, 16 * q, t);
     };
 
-    // ---- phase 1
-    f32x16 inter = zero16();
+    // ---- phases 1 and 2, one k-step of each per slot so that an X fragment is read from LDS once:
+    //   1  W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] from the state in registers
+    //   2  S^T[c][r]  = sum_k Y[c][k] X[r][k]
+    // Side work: the next state operand; lambda^B on a state tile once both its operands are made; the
+    // update weights on Z; the direct loads of block it + NBUF - 1.
+    f32x16 inter = zero16(), sd = zero16();
     bf16x8 sa = sa_first;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       inter = mfma(sa, xa[ks], inter);
-      if (ks + AHEAD < KS) xa[ks + AHEAD] = la.read_row(tX, 0, ks + AHEAD);
-      else read_xy(ks + AHEAD - KS);
+      sd = mfma(ya[ks], xa[ks], sd);
+      if (ks + AHEAD < KS) read_xy(ks + AHEAD);
       if (ks + 1 < KS) { sa = state_operand(ks + 1); pin(sa); }
       if (ks < NDMA) loader.issue_one(sAhead, doff, ks);
       if (ks < 2) zf[ks] = la.read_cols(tZ, 16 * ks, dvt);
-      pin(inter);
-      LA2_SLOT_END();
-    }
-    // ---- phase 2
-    f32x16 sd = zero16();
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      sd = mfma(yb[ks], xb[ks], sd);
-      if (ks + AHEAD < KS) read_xy(ks + AHEAD);
-      if (ks == KS - 1) read_yt(0, 0);
-      if ((ks & 1) == 0) {
-        const int t = ks >> 1;
+      if (ks >= 2 && (ks & 1) == 0) {   // state tile ks / 2 - 1: both operands made in slots <= ks - 1
+        const int t = (ks >> 1) - 1;
 #pragma unroll
         for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
         pin(kv[t]);
-      }
-      if (ks == 1) {
-#pragma unroll
-        for (int v = 0; v < 16; v++) inter[v] *= inter_scale;
-        pin(inter);
       }
       if (ks == 3 || ks == 5) {
         const int q = (ks - 3) >> 1;
         zd[q] = decay.apply(zf[q], 16 * q);
         pin(zd[q]);
       }
+      if (ks == KS - 1) read_yt(0, 0);
+      pin(inter);
       pin(sd);
       LA2_SLOT_END();
+    }
+    {
+#pragma unroll
+      for (int v = 0; v < 16; v++) kv[NT - 1][v] *= lamB;
+      pin(kv[NT - 1]);
+      // the carried part takes the decay at this lane's position
+#pragma unroll
+      for (int v = 0; v < 16; v++) inter[v] *= inter_scale;
+      pin(inter);
     }
     // ---- phase 3
     bf16x8 pd[2];
@@ -935,7 +938,10 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
       loader.zero_tail(sNext, nb);
       lds_barrier();
 #pragma unroll
-      for (int ks = 0; ks < AHEAD; ks++) xa[ks] = la.read_row(sNext[xi], 0, ks);
+      for (int ks = 0; ks < AHEAD; ks++) {
+        xa[ks] = la.read_row(sNext[xi], 0, ks);
+        ya[ks] = la.read_row(sNext[yi], 0, ks);
+      }
     }
     LA2_SLOT_END();
     // ---- phase 4 and the block's output
