@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch (bytes), by workload
-MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786763 + 262146) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786787 + 262151) * 1024)}
 
 
 def flops_per_token_head(B, d, what):
@@ -42,7 +42,7 @@ def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
     bytes_alg = 8 * d * th            # read Q, K, V and write O once, bf16
     flops_alg = flops_per_token_head(B, d, "fwd") * th
     return {
-        "kernel": "scan_bf16_half_kernel<fwd> (la2_fwd, %s)" % wl.name,
+        "kernel": "scan_bf16_half_kernel<fwd, plain, 3 buffers> (la2_fwd, %s)" % wl.name,
         "bound": "hbm",
         "achieved": round(bytes_alg / (k_ms * 1e-3) / 1e9, 1),
         "peak": PEAK_HBM_GBS,
