@@ -308,3 +308,43 @@ def test_decode_matches_forward(d, dtype):
     assert_close("decode-as-forward", o, oracle.fwd_direct(q, k, v, lam), dtype)
     _, kvf = oracle.fwd_recurrent(q, k, v, lam, return_state=True)
     assert max_rel(to64(kv), kvf) <= 1e-5
+
+
+def test_hip_graph_capture_and_replay():
+    """The library allocates nothing and never synchronises, so a forward + backward (incl. the chunked
+    path with its workspace) can be captured into a HIP graph.  Replays, with eager work and
+    synchronisations between them, must reproduce the eager results bit for bit."""
+    for (b, H, n, d) in ((2, 4, 700, 128), (1, 2, 2048, 128), (1, 4, 900, 64)):
+        t = gpu(make_inputs(b, H, n, d, torch.bfloat16, seed=61 + n))
+        ws = torch.empty(max(256, binding.la2_workspace_bytes(t["q"], binding.LA2_OP_BWD)), dtype=torch.uint8,
+                         device=DEV)
+        o = torch.empty_like(t["q"])
+        grads = tuple(torch.empty_like(t["q"]) for _ in range(3))
+        eager_o = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"], workspace=ws).clone()
+        eager_g = [x.clone() for x in binding.la2_bwd(t["q"], t["k"], t["v"], t["d_o"], t["lam"], workspace=ws)]
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            # warm-up on the capture stream, then capture
+            binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"], out=o, workspace=ws)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"], out=o, workspace=ws)
+                binding.la2_bwd(t["q"], t["k"], t["v"], t["d_o"], t["lam"], out=grads, workspace=ws)
+        torch.cuda.current_stream().wait_stream(side)
+        for replay in range(3):
+            o.fill_(float("nan"))
+            for x in grads:
+                x.fill_(float("nan"))
+            ws.random_(0, 255)                      # the workspace carries nothing between calls
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(o, eager_o), (n, d, replay)
+            for got, ref in zip(grads, eager_g):
+                assert torch.equal(got, ref), (n, d, replay)
+            # eager work between replays
+            assert torch.equal(binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"], workspace=ws), eager_o)
+            torch.cuda.synchronize()
