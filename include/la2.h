@@ -143,6 +143,22 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
                            float* kv_state, void* o, void* hip_stream);
 
 /*
+ * la2_bwd_state for callers that kept the forward pass's workspace (a training step): fwd_workspace is the
+ * workspace buffer that la2_fwd / la2_fwd_state used for the SAME desc, k, v, lambda and kv_init, with
+ * its contents untouched since and distinct from `workspace`.  When the sequence is processed in chunks
+ * it holds the chunk start states of the (K, V) scan, which are (transposed) those of Algorithm 2's first
+ * loop, so the backward pass skips recomputing them (one pass over K and V less).  NULL, or a problem that
+ * needs no workspace: exactly la2_bwd_state.  Not to be used with the workspace of a la2_fwd_state call
+ * that produced kv_final for a seqlen that is not a multiple of 64 (that call plans its chunks for the
+ * whole blocks only).  fwd_workspace is 256-byte aligned (LA2_ERR_WORKSPACE otherwise) and only read.
+ */
+la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v,
+                         const void* d_o, const float* lambda, const float* kv_init,
+                         const float* d_kv_final, void* dq, void* dk, void* dv, float* d_kv_init,
+                         const void* fwd_workspace, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
  * ntokens consecutive decode steps in one launch (recursive form of Sec. 3.2.1): for t = 0 .. ntokens-1
  * kv_state <- lambda_h kv_state + k_t^T v_t, o_t = q_t kv_state.  The state is read and written once per
  * launch instead of once per token.

@@ -65,6 +65,8 @@ def load():
     lib.la2_fwd_state.restype = ctypes.c_int
     lib.la2_bwd_state.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_state.restype = ctypes.c_int
+    lib.la2_bwd_saved.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd_saved.restype = ctypes.c_int
     lib.la2_decode_multi.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.la2_decode_multi.restype = ctypes.c_int
     lib.la2_decode_step.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -205,8 +207,9 @@ def la2_fwd_state(q, k, v, lam, kv_init=None, want_final=True, out=None, kv_fina
 
 
 def la2_bwd_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_init=True, out=None,
-                  d_kv_init=None, workspace=None):
-    """Backward of one segment.  Returns (dq, dk, dv, d_kv_init or None)."""
+                  d_kv_init=None, workspace=None, fwd_workspace=None):
+    """Backward of one segment.  Returns (dq, dk, dv, d_kv_init or None).  fwd_workspace: the workspace
+    tensor the forward call used (contents untouched since), to reuse its chunk states."""
     lib = load()
     if not q.is_cuda:
         raise ValueError("la2_bwd_state: tensors must live on the GPU")
@@ -221,11 +224,12 @@ def la2_bwd_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_in
     desc = make_desc(q)
     ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD_STATE, workspace)
     with torch.cuda.device(q.device):
-        _check(lib.la2_bwd_state(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
+        fwd_ws = ctypes.c_void_p(fwd_workspace.data_ptr()) if fwd_workspace is not None else None
+        _check(lib.la2_bwd_saved(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
                                  lam.data_ptr(), _state(kv_init, q, "kv_init"),
                                  _state(d_kv_final, q, "d_kv_final"), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                  _state(d_kv_init, q, "d_kv_init") if want_d_kv_init else None,
-                                 ws_ptr, ws_bytes, _stream(q)))
+                                 fwd_ws, ws_ptr, ws_bytes, _stream(q)))
     return dq, dk, dv, (d_kv_init if want_d_kv_init else None)
 
 

@@ -88,6 +88,10 @@ struct ScanArgs {
   const float* init = nullptr;   // start state [chains][d][d] (row = y feature) or nullptr
   bool init_tr = false;          // ... stored transposed
   float* fin = nullptr;          // state after the last block, or nullptr
+  // chunk start states that an earlier call left in ITS workspace for the same (y, z) (or, if saved_tr, for
+  // (z, y): the transposed states): the pre-pass is skipped.  Ignored when the plan has one chunk.
+  const float* saved_states = nullptr;
+  bool saved_tr = false;
 };
 
 la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace) {
@@ -121,9 +125,16 @@ la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const vo
 
 la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanArgs& a, const float* lambda,
                     void* workspace, hipStream_t s) {
-  la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s);
-  if (st != LA2_OK) return st;
+  const bool saved = a.saved_states != nullptr && pl.nchunks > 1;
+  if (!saved) {
+    la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s);
+    if (st != LA2_OK) return st;
+  }
   la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  if (saved) {
+    p.states = const_cast<float*>(a.saved_states);   // read only
+    p.state_transposed = a.saved_tr ? 1 : 0;
+  }
   p.x[0] = a.x; p.y[0] = a.y; p.z[0] = a.z; p.w[0] = a.w;
   p.init[0] = a.init; p.init_transposed = a.init_tr ? 1 : 0;
   p.fin[0] = a.fin;
@@ -268,10 +279,12 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
   return la2_fwd_state(desc, q, k, v, lambda, nullptr, o, nullptr, workspace, workspace_bytes, hip_stream);
 }
 
-la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                          const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
-                         void* dv, float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                         void* dv, float* d_kv_init, const void* fwd_workspace, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
+  if (st == LA2_OK && !aligned(fwd_workspace, 256)) return LA2_ERR_WORKSPACE;
   if (st != LA2_OK) return st;
   const int64_t chains = (int64_t)desc->batch * desc->heads;
   if (chains == 0) return LA2_OK;  // nothing to do
@@ -301,6 +314,9 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
   ScanArgs for_dq{d_o, v, k, dq};
   for_dq.init = kv_init;
   for_dq.init_tr = true;
+  // the forward pass's chunk start states are those of the (K, V) scan: this scan's, transposed
+  for_dq.saved_states = reinterpret_cast<const float*>(fwd_workspace);
+  for_dq.saved_tr = true;
   st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
   if (st != LA2_OK) return st;
   // Algorithm 2, second loop (descending, running dKV):
@@ -331,10 +347,17 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
   return run_scan(&blocks, pl_rev, true, for_dk, lambda, workspace, s);
 }
 
+la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
+                         void* dv, float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return la2_bwd_saved(desc, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, nullptr, workspace,
+                       workspace_bytes, hip_stream);
+}
+
 la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                    const float* lambda, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
-  return la2_bwd_state(desc, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, workspace,
+  return la2_bwd_saved(desc, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, nullptr, workspace,
                        workspace_bytes, hip_stream);
 }
 

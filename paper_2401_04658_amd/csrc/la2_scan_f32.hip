@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kThreads) void scan_f32_kernel(ScanParams p) {
 
   // start state: chunk start state, the caller's start state (possibly stored transposed), or zero
   const float* gs = p.states ? p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D) : nullptr;
-  bool tr = false;
+  bool tr = p.states != nullptr && (p.state_transposed & 1);
   if (gs == nullptr && p.init[0] != nullptr) {
     gs = p.init[0] + (int64_t)chain * (D * D);
     tr = p.init_transposed & 1;

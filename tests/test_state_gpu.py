@@ -204,3 +204,33 @@ def test_decode_multi_config5_shape():
                                   return_state=True)
     assert_close("config5 multi o", o[rows], ro, torch.bfloat16)
     assert_close("config5 multi state", state[rows], rs, torch.bfloat16)
+
+
+@pytest.mark.parametrize("dtype,d,n,chunk", [(torch.bfloat16, 128, 1024, 256), (torch.bfloat16, 64, 1000, 128),
+                                             (torch.float32, 128, 640, 128), (torch.bfloat16, 128, 900, 0)])
+def test_backward_reuses_the_forward_chunk_states(dtype, d, n, chunk):
+    """A training step: the forward call's workspace (chunk start states of the K, V scan) is handed to the
+    backward call, which then skips its own pre-pass for dQ.  Same results within tolerance, with and
+    without a start state; no effect when the launch is not chunked (chunk = 0 with enough chains)."""
+    binding.la2_set_chunk_tokens(chunk)
+    b, H = (1, 4) if chunk else (16, 16)
+    t = inputs(b, H, n, d, dtype, seed=1300 + n + d)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    need = binding.la2_workspace_bytes(g["q"], binding.LA2_OP_BWD_STATE)
+    assert (need > 0) == bool(chunk) or n % 64 != 0
+    ws_f = torch.empty(max(256, need), dtype=torch.uint8, device=DEV)
+    ws_b = torch.empty(max(256, need), dtype=torch.uint8, device=DEV)
+    for use_init in (False, True):
+        kv_init = g["kv_init"] if use_init else None
+        binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=kv_init, want_final=False, workspace=ws_f)
+        dq, dk, dv, g0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=kv_init,
+                                               workspace=ws_b, fwd_workspace=ws_f)
+        torch.cuda.synchronize()
+        q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+        rdq, rdk, rdv, rg0 = oracle.bwd_recurrent_state(q, k, v, do, lam,
+                                                        kv_init=to64(t["kv_init"]) if use_init else None)
+        tag = "saved states %s d%d n%d init=%s" % (dtype, d, n, use_init)
+        assert_close(tag + " dq", dq, rdq, dtype)
+        assert_close(tag + " dk", dk, rdk, dtype)
+        assert_close(tag + " dv", dv, rdv, dtype)
+        assert_close(tag + " d_kv_init", g0, rg0, dtype)
