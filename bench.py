@@ -202,6 +202,19 @@ def main():
                             "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                             "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1)})
         del st
+    # the forward pass as the O(n^2 d) masked left product (comparison kernel) against the block recurrence
+    crossover = []
+    short = [(wl_, stage(wl_)) for wl_ in (workloads.Workload("config3_like_b%d_n%d_h16_d128" % (b_, n_), b_, 16, n_, 128,
+                                                              torch.bfloat16, seed=40 + i_)
+                                           for i_, (b_, n_) in enumerate(((512, 128), (256, 256), (128, 512))))]
+    for wl, g in short + sweep:
+        lp_iters = max(2, min(iters, int(50e9 // (wl.seqlen * wl.tokens))))   # ~n^2 work: fewer launches when long
+        lp_ms = time_ms(lambda: binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"], out=g["o"]), lp_iters)
+        f_ms = time_ms(lambda: fwd(g), iters)
+        crossover.append({"workload": wl.name, "left_product_fwd_ms": round(lp_ms, 4),
+                          "block_recurrence_fwd_ms": round(f_ms, 4), "ratio": round(lp_ms / f_ms, 2)})
+    del short
+
     # training step that keeps the forward's workspace for the backward (la2_bwd_saved): the sequence-chunked
     # points then skip one of the backward's two chunk-state pre-passes.  Reported beside the headline, which
     # stays on the stand-alone la2_fwd + la2_bwd.
@@ -300,6 +313,7 @@ def main():
         "other_configs": others,
         "state_handover": with_states,
         "saved_forward_states": saved,
+        "left_product_comparison": crossover,
         "decode": decode,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -159,6 +159,16 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
                          void* hip_stream);
 
 /*
+ * Comparison kernel, not part of the method: the same forward pass evaluated as the masked left product
+ * O = [(Q K^T) * M] V over all earlier key blocks (Sec. 3.1 eq. (1) with the decay mask M of Sec. 3.2),
+ * O(n^2 d) instead of O(n d^2), the way the predecessor of Algorithm 1 computes it.  For measuring where
+ * the block recurrence overtakes it as n grows.  bf16 only (LA2_ERR_DTYPE otherwise); arguments as la2_fwd;
+ * no workspace.
+ */
+la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
+                                const float* lambda, void* o, void* hip_stream);
+
+/*
  * ntokens consecutive decode steps in one launch (recursive form of Sec. 3.2.1): for t = 0 .. ntokens-1
  * kv_state <- lambda_h kv_state + k_t^T v_t, o_t = q_t kv_state.  The state is read and written once per
  * launch instead of once per token.

@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     la2_bwd_state,
     la2_decode_step,
     la2_decode_multi,
+    la2_left_product_fwd,
     la2_workspace_bytes,
 )

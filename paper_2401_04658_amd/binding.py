@@ -67,6 +67,8 @@ def load():
     lib.la2_bwd_state.restype = ctypes.c_int
     lib.la2_bwd_saved.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_saved.restype = ctypes.c_int
+    lib.la2_left_product_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    lib.la2_left_product_fwd.restype = ctypes.c_int
     lib.la2_decode_multi.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.la2_decode_multi.restype = ctypes.c_int
     lib.la2_decode_step.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -269,4 +271,20 @@ def la2_decode_multi(q, k, v, lam, kv_state, out=None):
     with torch.cuda.device(q.device):
         _check(lib.la2_decode_multi(b, h, d, t, _dtype_code(q), q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                     lam.data_ptr(), kv_state.data_ptr(), out.data_ptr(), _stream(q)))
+    return out
+
+
+def la2_left_product_fwd(q, k, v, lam, out=None):
+    """The forward pass as the O(n^2 d) masked left product (comparison kernel, bf16)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_left_product_fwd: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    desc = make_desc(q)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_left_product_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
+                                        out.data_ptr(), _stream(q)))
     return out

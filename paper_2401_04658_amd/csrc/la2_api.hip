@@ -361,6 +361,22 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
                        workspace_bytes, hip_stream);
 }
 
+la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
+                                const float* lambda, void* o, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (desc->dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  Plan one{1, desc->seqlen, 0};
+  la2::ScanParams p = base_params(desc, one, lambda, nullptr);
+  p.x[0] = q; p.y[0] = k; p.z[0] = v; p.w[0] = o;
+  return la2::launch_left_product_bf16(desc->head_dim, p, reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
                            const void* k, const void* v, const float* lambda, float* kv_state, void* o,
                            void* hip_stream) {

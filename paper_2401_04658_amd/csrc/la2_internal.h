@@ -51,6 +51,8 @@ int block_size_f32(int head_dim);
 // bf16 MFMA path (head_dim 64 or 128)
 hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+// O(n^2 d) left-product evaluation of the forward pass, for comparison (bf16; uses x, y, z, w of scan 0)
+hipError_t launch_left_product_bf16(int head_dim, const ScanParams& p, hipStream_t s);
 // fp32 path
 hipError_t launch_scan_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);

@@ -348,3 +348,34 @@ def test_hip_graph_capture_and_replay():
             # eager work between replays
             assert torch.equal(binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"], workspace=ws), eager_o)
             torch.cuda.synchronize()
+
+
+# ---- the O(n^2 d) left-product comparison kernel computes the same forward pass ---------------------------------------
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n", [1, 31, 64, 128, 129, 200, 517, 1000])
+def test_left_product_kernel_small_shapes(d, n):
+    t = make_inputs(2, 3, n, d, torch.bfloat16, seed=400 + n + d, lam=[0.5, 0.93, 1.0])
+    g = gpu(t)
+    o = binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"])
+    torch.cuda.synchronize()
+    ref = oracle.fwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"]))
+    assert_close("left product n%d d%d" % (n, d), o, ref, torch.bfloat16)
+
+
+def test_left_product_kernel_config2_and_extreme_decays():
+    wl = workloads.CONFIG2
+    t = wl.tensors()
+    g = gpu(t)
+    o = binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"])
+    torch.cuda.synchronize()
+    assert_close("left product config2", o, oracle.fwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"])),
+                 torch.bfloat16)
+    t = make_inputs(1, 3, 300, 128, torch.bfloat16, seed=24, lam=[1.0, 1e-6, 0.43])
+    g = gpu(t)
+    o = binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"])
+    torch.cuda.synchronize()
+    assert_close("left product extreme decays", o,
+                 oracle.fwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"])), torch.bfloat16)
+    with pytest.raises(binding.LA2Error):
+        f = gpu(make_inputs(1, 1, 64, 64, torch.float32, seed=1))
+        binding.la2_left_product_fwd(f["q"], f["k"], f["v"], f["lam"])
