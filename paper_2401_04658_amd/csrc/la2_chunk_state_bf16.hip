@@ -1,0 +1,149 @@
+// Chunk-state pre-pass of the sequence-chunked launches, gfx950: local state of every chunk (bf16 MFMA, same
+// streaming as the scan kernels) and the scan that turns local states into chunk start states (fp32).
+#include "la2_bf16_common.h"
+
+namespace la2 {
+namespace {
+using namespace bf16k;
+
+// Local state of every chunk that has a successor: forward sum_c lambda^(C-1-c) y_c^T z_c over the
+// chunk's positions c, reverse sum_c lambda^c y_c^T z_c.  Written fp32 row-major [dk][dv].  Same
+// streaming and the same state-update step as the scan kernel, without X, scores or outputs.
+template <int D, bool REV>
+__global__ __launch_bounds__(kThreads, 2) void chunk_state_bf16_kernel(ScanParams p) {
+  using C = Cfg<D>;
+  constexpr int NT = C::NT, TILE = C::TILE;
+  __shared__ __attribute__((aligned(1024))) __bf16 sT0[2][TILE];   // [Y, Z]
+  __shared__ __attribute__((aligned(1024))) __bf16 sT1[2][TILE];
+
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
+  const int dvt = w % NT;
+  const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
+  if (REV ? (chunk == 0) : (chunk == p.nchunks - 1)) return;  // no successor needs it
+  const int bi = chain / p.heads, hi = chain % p.heads;
+  const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
+  const int n = p.n;
+  const float l2 = log2f(p.lambda[hi]);
+  const int nblocks = (n + kB - 1) / kB;
+  const int cb = p.chunk_tokens / kB;
+  const int blk_lo = chunk * cb;
+  const int blk_hi = min(blk_lo + cb, nblocks);
+  const int nblk = blk_hi - blk_lo;
+
+  TileLoader<D, 2> loader(w, l, n, (uint32_t)p.stride_n);
+  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
+  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
+  const LaneAddr<D> la(l);
+  const UpdateDecay<REV> decay(l2, hh);
+  const float lamB = exp2f(l2 * (float)kB);
+
+  f32x16 kv[NT];
+#pragma unroll
+  for (int t = 0; t < NT; t++) kv[t] = zero16();
+
+  if (nblk > 0) {
+    const int b0 = REV ? blk_hi - 1 : blk_lo;
+    loader.issue(sT0, b0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    loader.zero_tail(sT0, b0);
+  }
+  __syncthreads();
+
+  auto block_step = [&](auto cur_tag, int it) {
+    constexpr int cur = decltype(cur_tag)::value;
+    const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
+    const bool has_next = it + 1 < nblk;
+    const int nb = REV ? blk - 1 : blk + 1;
+    if (has_next) loader.issue(cur ? sT0 : sT1, nb);
+    const __bf16* tY = cur ? sT1[0] : sT0[0];
+    const __bf16* tZ = cur ? sT1[1] : sT0[1];
+    bf16x8 zf[4], yt[NT][4];   // [16-row k-step of the block]
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      zf[k] = la.read_cols(tZ, 16 * k, dvt);
+#pragma unroll
+      for (int t = 0; t < NT; t++) yt[t][k] = la.read_cols(tY, 16 * k, t);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      const bf16x8 zd = decay.apply(zf[k], 16 * k);
+#pragma unroll
+      for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][k], zd, kv[t]);
+    }
+    if (has_next) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      loader.zero_tail(cur ? sT0 : sT1, nb);
+      lds_barrier();
+    }
+  };
+  for (int it = 0; it < nblk; it += 2) {
+    block_step(std::integral_constant<int, 0>{}, it);
+    if (it + 1 < nblk) block_step(std::integral_constant<int, 1>{}, it + 1);
+  }
+
+  if (w < NT) {   // for d = 64 waves w and w + 2 hold the same slice
+    float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) gs[state_index<D>(dvt, l32, hh, t, v, false)] = kv[t][v];
+  }
+}
+
+// In place: states[chain][j] (local state of chunk j) -> start state of chunk j.
+//   forward: G_0 = 0, G_{j+1} = lambda^C G_j + L_j        reverse: G_last = 0, G_{j-1} = lambda^C G_j + L_j
+// The chunk processed first starts from init (element e read at its transposed place if init_tr) or 0.
+// The carried state decays by lambda^(chunk length): all chunks are chunk_tokens long except the last
+// one of the sequence, which a reverse scan passes first.
+__global__ void state_scan_kernel(float* states, const float* lambda, int heads, int nchunks, int chunk_tokens,
+                                  int dd, int reverse, const float* init, int init_tr, int d, int n) {
+  const int chain = blockIdx.y;
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= dd) return;
+  const float l2 = log2f(lambda[chain % heads]);
+  const float lamFull = exp2f(l2 * (float)chunk_tokens);
+  const float lamLast = exp2f(l2 * (float)(n - (nchunks - 1) * chunk_tokens));
+  float* s = states + (int64_t)chain * nchunks * dd + e;
+  float g = 0.f;
+  if (init != nullptr) g = init[(int64_t)chain * dd + (init_tr ? (e % d) * d + e / d : e)];
+  for (int i = 0; i < nchunks; i++) {
+    const int j = reverse ? nchunks - 1 - i : i;
+    const bool last = (i == nchunks - 1);
+    const float loc = last ? 0.f : s[(int64_t)j * dd];
+    s[(int64_t)j * dd] = g;
+    g = (j == nchunks - 1 ? lamLast : lamFull) * g + loc;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks;
+  if (grid == 0 || p.n == 0) return hipSuccess;
+  dim3 g((unsigned)grid), b(kThreads);
+  if (head_dim == 128) {
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<128, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<128, false>), g, b, 0, s, p);
+  } else {
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<64, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<64, false>), g, b, 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+  const int chains = p.batch * p.heads;
+  if (chains == 0 || p.n == 0) return hipSuccess;
+  const int dd = head_dim * head_dim;
+  dim3 g((dd + 255) / 256, chains), b(256);
+  hipLaunchKernelGGL(state_scan_kernel, g, b, 0, s, p.states, p.lambda, p.heads, p.nchunks, p.chunk_tokens, dd,
+                     reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n);
+  return hipGetLastError();
+}
+
+}  // namespace la2

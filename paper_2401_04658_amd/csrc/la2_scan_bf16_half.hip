@@ -1,0 +1,320 @@
+// Half-block bf16 scan kernel for head_dim 128 (B = 32 positions, two workgroups per compute unit) and its
+// twin form (both reverse scans of the backward pass in one workgroup), gfx950.  Layout notes:
+// la2_bf16_common.h.
+#include "la2_bf16_common.h"
+
+namespace la2 {
+namespace {
+using namespace bf16k;
+
+// Half-block variant for d = 128: blocks of 32 positions, 80 KiB of LDS and at most 256 registers, so
+// that TWO workgroups share a compute unit (two waves per SIMD).  One wave alone issues its
+// instructions one after the other (an MFMA holds the issue port for about half its run time, a
+// 16-byte-per-lane memory instruction for about 60 cycles), so a single wave per SIMD leaves the
+// matrix pipe idle most of the time; a second, independent wave fills those gaps.  Used when a launch
+// has enough workgroups to put two on every compute unit.  Same math as scan_bf16_kernel with a
+// single (diagonal) 32 x 32 score tile per block; wave w owns value features 32 w .. 32 w + 31.
+constexpr int kBH = 32;
+//
+// TWIN: both scans of a dual launch in ONE workgroup of 8 waves (waves 0-3 scan 0, waves 4-7 scan 1;
+// again two waves per SIMD).  The dual launch is Algorithm 2's second loop, whose two scans read the
+// same two tensors with the roles of Y and Z exchanged (dV: y = Q, z = dO; dK: y = dO, z = Q), so the
+// workgroup streams FOUR tiles per block (x of scan 0, x of scan 1, Q, dO) instead of six and every
+// tile is fetched exactly once.  Requires y[1] == z[0] and z[1] == y[0].
+//
+// NBUF tile buffers: block it + NBUF - 1 streams in while block it is computed.  With 3 buffers two
+// (plain) workgroups fit on a compute unit.
+template <bool REV, bool TWIN, int NBUF>
+__global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
+  constexpr int D = 128, B = kBH;
+  using C = Cfg<D, B>;
+  constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
+  constexpr int NW = TWIN ? 8 : 4;             // waves
+  constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
+  using Loader = TileLoader<D, NTL, B, NW>;
+  __shared__ __attribute__((aligned(1024))) __bf16 sT[NBUF][NTL][TILE];
+  __shared__ __attribute__((aligned(16))) __bf16 sW[NW][32 * LW];
+  constexpr int NDMA = NTL * Loader::DMA_PER_WAVE;   // direct loads per wave and block
+  constexpr int NST = 32 * 4 / 64;             // 16-byte stores per lane and block
+  static_assert(NDMA <= KS, "one direct load per slot of phase 1");
+  // vector-memory operations of this wave that are younger than the direct loads of block it + 1 when block
+  // it waits for them: the loads of blocks it + 2 .. it + NBUF - 1 and as many blocks' stores
+  constexpr int VM_YOUNGER = (NBUF - 2) * (NST + NDMA);
+  static_assert(VM_YOUNGER < 64, "vmcnt is a 6-bit counter");
+  constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
+
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
+  const int dvt = w & 3;
+  int which = 0, wg = (int)blockIdx.x;
+  if (TWIN) {
+    which = __builtin_amdgcn_readfirstlane(w >> 2);
+  } else if (p.nscan == 2) {   // same pairing as scan_bf16_kernel
+    if (((gridDim.x >> 1) & 7) == 0) {
+      which = (int)(blockIdx.x >> 3) & 1;
+      wg = (int)((blockIdx.x >> 4) << 3) | (int)(blockIdx.x & 7);
+    } else {
+      which = (int)(blockIdx.x & 1);
+      wg = (int)(blockIdx.x >> 1);
+    }
+  }
+  // In a twin workgroup the two wave groups run two instantiations of the body, so that each sees
+  // its tiles at compile-time LDS offsets.
+  auto run = [&](auto wh_tag) __attribute__((always_inline)) {
+  constexpr int WH = decltype(wh_tag)::value;
+  const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
+  const int bi = chain / p.heads, hi = chain % p.heads;
+  const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
+  const int n = p.n;
+  const uint32_t stride_n = (uint32_t)p.stride_n;
+  const uint32_t chain_bytes = ((uint32_t)(n - 1) * stride_n + D) * 2u;
+  const __amdgpu_buffer_rsrc_t bw =
+      make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
+  const float l2 = log2f(p.lambda[hi]);
+
+  const int nblocks = (n + B - 1) / B;
+  const int cb = p.chunk_tokens / B;
+  const int blk_lo = chunk * cb;
+  const int blk_hi = min(blk_lo + cb, nblocks);
+  if (blk_lo >= blk_hi) return;
+  const int nblk = blk_hi - blk_lo;
+
+  Loader loader(w, l, n, stride_n);
+  if (TWIN) {
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[1]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
+    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
+  } else {
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.x[1] : p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.y[1] : p.y[0]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.z[1] : p.z[0]) + base);
+  }
+  // this wave's X, Y, Z among the tiles of a block
+  constexpr int xi = TWIN ? WH : 0, yi = TWIN ? 2 + WH : 1, zi = TWIN ? 3 - WH : 2;
+  const LaneAddr<D> la(l);
+
+  f32x16 kv[NT];
+  const float* gs = nullptr;   // start state: chunk start state, the caller's start state, or zero
+  bool tr = false;
+  if (p.states != nullptr) {
+    gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+    tr = (p.state_transposed >> which) & 1;
+  } else if ((which ? p.init[1] : p.init[0]) != nullptr) {
+    gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
+    tr = (p.init_transposed >> which) & 1;
+  }
+  if (gs != nullptr) {
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) kv[t][v] = gs[state_index<D>(dvt, l32, hh, t, v, tr)];
+  } else {
+#pragma unroll
+    for (int t = 0; t < NT; t++) kv[t] = zero16();
+  }
+
+  // decay mask of the score tile S^T[c][r] (lane: r = l32; element v: c = 8 (v / 4) + 4 hh + v % 4)
+  float dg[16];
+#pragma unroll
+  for (int v = 0; v < 16; v++) {
+    const int cc = 8 * (v >> 2) + 4 * hh + (v & 3);
+    const int e = REV ? cc - l32 : l32 - cc;
+    dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
+  }
+  const float inter_scale = exp2f(l2 * (float)(REV ? B - 1 - l32 : l32 + 1));
+  const UpdateDecay<REV, B> decay(l2, hh);
+  const float lamB = uniform(exp2f(l2 * (float)B));
+
+  // prologue: the first NBUF - 1 blocks' tiles
+#pragma unroll
+  for (int j = 0; j < NBUF - 1; j++)
+    if (j < nblk) loader.issue(sT[j], REV ? blk_hi - 1 - j : blk_lo + j);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+#pragma unroll
+  for (int j = 0; j < NBUF - 1; j++)
+    if (j < nblk) loader.zero_tail(sT[j], REV ? blk_hi - 1 - j : blk_lo + j);
+  __syncthreads();
+
+  constexpr int AHEAD = 1;   // LDS operands are read one slot ahead (the other wave on the SIMD covers the rest)
+  bf16x8 xa[KS], ya[KS];     // X and Y row fragments (natural k-order) of the block being computed
+#pragma unroll
+  for (int ks = 0; ks < AHEAD; ks++) {
+    xa[ks] = la.read_row(sT[0][xi], 0, ks);
+    ya[ks] = la.read_row(sT[0][yi], 0, ks);
+  }
+  auto state_operand = [&](int ks) __attribute__((always_inline)) {
+    bf16x8 f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) f[j] = (__bf16)kv[ks >> 1][8 * (ks & 1) + j];
+    return to_perm_order(f);
+  };
+  bf16x8 sa_first = state_operand(0);
+  __bf16* const stage = sW[w];
+
+#define LA2_SLOT_END()                 \
+  do {                                 \
+    asm volatile("" ::: "memory");     \
+    __builtin_amdgcn_sched_barrier(0); \
+  } while (0)
+  // Phases as in scan_bf16_kernel (1 inter-block product and 2 scores, here interleaved; 3 state update;
+  // barrier; 4 intra-block product), then the block's output.
+  auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
+    constexpr int cur = decltype(cur_tag)::value;
+    __bf16 (*const sCur)[TILE] = sT[cur];                          // block it
+    __bf16 (*const sNext)[TILE] = sT[(cur + 1) % NBUF];            // block it + 1 (in flight or landed)
+    __bf16 (*const sAhead)[TILE] = sT[(cur + NBUF - 1) % NBUF];    // block it + NBUF - 1 (free since block it - 1)
+    const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
+    const bool has_next = it + 1 < nblk, has_ahead = it + NBUF - 1 < nblk;
+    const int nb = REV ? blk - 1 : blk + 1;
+    const __bf16* tX = sCur[xi];
+    const __bf16* tY = sCur[yi];
+    const __bf16* tZ = sCur[zi];
+    uint32_t doff[Loader::DMA_PER_WAVE];
+    loader.offsets(REV ? blk - (NBUF - 1) : blk + (NBUF - 1), has_ahead, doff);
+
+    bf16x8 zf[2], zd[2], yt[2][NT];
+    auto read_xy = [&](int ks) __attribute__((always_inline)) {
+      xa[ks] = la.read_row(tX, 0, ks);
+      ya[ks] = la.read_row(tY, 0, ks);
+    };
+    // Y^T fragments of update k-step q for the key-feature tiles 2 h, 2 h + 1
+    auto read_yt = [&](int q, int h) __attribute__((always_inline)) {
+#pragma unroll
+      for (int t = 2 * h; t < 2 * h + 2; t++) yt[q][t] = la.read_cols(tY, 16 * q, t);
+    };
+
+    // ---- phases 1 and 2, one k-step of each per slot so that an X fragment is read from LDS once:
+    //   1  W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] from the state in registers
+    //   2  S^T[c][r]  = sum_k Y[c][k] X[r][k]
+    // Side work: the next state operand; lambda^B on a state tile once both its operands are made; the
+    // update weights on Z; the direct loads of block it + NBUF - 1.
+    f32x16 inter = zero16(), sd = zero16();
+    bf16x8 sa = sa_first;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      inter = mfma(sa, xa[ks], inter);
+      sd = mfma(ya[ks], xa[ks], sd);
+      if (ks + AHEAD < KS) read_xy(ks + AHEAD);
+      if (ks + 1 < KS) { sa = state_operand(ks + 1); pin(sa); }
+      if (ks < NDMA) loader.issue_one(sAhead, doff, ks);
+      if (ks < 2) zf[ks] = la.read_cols(tZ, 16 * ks, dvt);
+      if (ks >= 2 && (ks & 1) == 0) {   // state tile ks / 2 - 1: both operands made in slots <= ks - 1
+        const int t = (ks >> 1) - 1;
+#pragma unroll
+        for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
+        pin(kv[t]);
+      }
+      if (ks == 3 || ks == 5) {
+        const int q = (ks - 3) >> 1;
+        zd[q] = decay.apply(zf[q], 16 * q);
+        pin(zd[q]);
+      }
+      if (ks == KS - 1) read_yt(0, 0);
+      pin(inter);
+      pin(sd);
+      LA2_SLOT_END();
+    }
+    {
+#pragma unroll
+      for (int v = 0; v < 16; v++) kv[NT - 1][v] *= lamB;
+      pin(kv[NT - 1]);
+      // the carried part takes the decay at this lane's position
+#pragma unroll
+      for (int v = 0; v < 16; v++) inter[v] *= inter_scale;
+      pin(inter);
+    }
+    // ---- phase 3
+    bf16x8 pd[2];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; s4++) {   // slot s4: k-step q = s4 / 2, key-feature tiles 2 h, 2 h + 1, h = s4 % 2
+      const int q = s4 >> 1, h = s4 & 1;
+#pragma unroll
+      for (int t = 2 * h; t < 2 * h + 2; t++) kv[t] = mfma(yt[q][t], zd[q], kv[t]);
+      if (s4 + 1 < 4) read_yt((s4 + 1) >> 1, (s4 + 1) & 1);
+#pragma unroll
+      for (int e = 0; e < 4; e++) pd[q][4 * h + e] = (__bf16)(sd[8 * q + 4 * h + e] * dg[8 * q + 4 * h + e]);
+      pin(pd[q]);
+#pragma unroll
+      for (int t = 2 * h; t < 2 * h + 2; t++) pin(kv[t]);
+      LA2_SLOT_END();
+    }
+    if (has_next) {
+      __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
+      loader.zero_tail(sNext, nb);
+      lds_barrier();
+#pragma unroll
+      for (int ks = 0; ks < AHEAD; ks++) {
+        xa[ks] = la.read_row(sNext[xi], 0, ks);
+        ya[ks] = la.read_row(sNext[yi], 0, ks);
+      }
+    }
+    LA2_SLOT_END();
+    // ---- phase 4 and the block's output
+#pragma unroll
+    for (int q = 0; q < 2; q++) inter = mfma(zf[q], pd[q], inter);
+    sa_first = state_operand(0);
+    pin(sa_first);
+    pin(inter);
+    LA2_SLOT_END();
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      bf16x4 pk;
+#pragma unroll
+      for (int e = 0; e < 4; e++) pk[e] = (__bf16)inter[4 * g + e];
+      *reinterpret_cast<bf16x4*>(stage + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
+    }
+#pragma unroll
+    for (int i = 0; i < NST; i++) {
+      const int id = l + 64 * i;
+      const int row = id >> 2, cc = id & 3;
+      const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
+      const uint32_t off = ((uint32_t)(blk * B + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
+      __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
+    }
+    LA2_SLOT_END();
+    return has_next;
+  };
+  for (int it = 0;; it += NBUF) {   // unrolled by the number of buffers: compile-time buffer index
+    if (!block_step(std::integral_constant<int, 0>{}, it)) break;
+    if (!block_step(std::integral_constant<int, 1>{}, it + 1)) break;
+    if (!block_step(std::integral_constant<int, 2>{}, it + 2)) break;
+    if (NBUF > 3 && !block_step(std::integral_constant<int, (NBUF > 3 ? 3 : 0)>{}, it + 3)) break;
+    if (NBUF > 4 && !block_step(std::integral_constant<int, (NBUF > 4 ? 4 : 0)>{}, it + 4)) break;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
+  // state after the chain's last block, if the caller wants it (the update ran on every block)
+  float* gf = which ? p.fin[1] : p.fin[0];
+  if (gf != nullptr && (REV ? chunk == 0 : chunk == p.nchunks - 1)) {
+    gf += (int64_t)chain * (D * D);
+    const bool trf = (p.fin_transposed >> which) & 1;
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) gf[state_index<D>(dvt, l32, hh, t, v, trf)] = kv[t][v];
+  }
+#undef LA2_SLOT_END
+  };
+  if (TWIN && which == 1) run(std::integral_constant<int, 1>{});
+  else run(std::integral_constant<int, 0>{});
+}
+
+}  // namespace
+
+hipError_t launch_scan_bf16_half(bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
+  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
+  // Three tile buffers in every case.  More buffers (5 for a plain, 4 for a twin workgroup that has the
+  // compute unit to itself) measured no faster: such launches are bound by the workgroup's own
+  // instruction stream, not by the bytes in flight.
+  if (twin) {
+    dim3 gt((unsigned)(grid / 2)), bt(512);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, true, 3>), gt, bt, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, true, 3>), gt, bt, 0, s, p);
+  } else {
+    dim3 g((unsigned)grid), b(kThreads);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, false, 3>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, false, 3>), g, b, 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace la2
