@@ -194,10 +194,10 @@ def main():
         shape = (wl.batch, wl.heads, wl.head_dim, wl.head_dim)
         st = {n_: torch.zeros(shape, dtype=torch.float32, device=dev) for n_ in ("init", "fin", "d_fin", "d_init")}
         f_ms = time_ms(lambda: binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=st["init"], out=g["o"],
-                                                     kv_final=st["fin"], workspace=g["ws"]), iters)
+                                                     kv_final=st["fin"], workspace=g["ws"]), iters, warm=40)
         b_ms = time_ms(lambda: binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=st["init"],
                                                      d_kv_final=st["d_fin"], out=g["grads"], d_kv_init=st["d_init"],
-                                                     workspace=g["ws"]), iters)
+                                                     workspace=g["ws"]), iters, warm=40)
         with_states.append({"workload": wl.name + " + kv_init, kv_final, d_kv_final, d_kv_init",
                             "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                             "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1)})
