@@ -1,0 +1,44 @@
+"""fp64 oracle of the normalised operator O = Norm(Q (K^T V)) with the decay and causal mask
+(Sec. 2.1 eq. (2) with the recurrence of Sec. 3.2.1 inside the Norm).  TEST INFRASTRUCTURE ONLY.
+
+The paper names Norm without defining it and leaves it out of its derivations (Sec. 3.2.1).  Reading
+taken here: root-mean-square normalisation of every output row over the head's feature dimension,
+without a learnable gain:
+
+    u_t = sum_{s<=t} lambda^(t-s) (q_t . k_s) v_s            (the un-normalised output row)
+    r_t = 1 / sqrt( mean_j u_{t,j}^2 + eps )
+    o_t = r_t u_t
+
+Backward: with g_t the gradient of the loss with respect to o_t, the gradient with respect to u_t is
+
+    dU_t = r_t ( g_t - o_t * mean_j(g_{t,j} o_{t,j}) )
+
+(differentiate r_t: d r_t / d u_{t,j} = - r_t^3 u_{t,j} / d; exact for any eps >= 0), and dQ, dK, dV
+are the un-normalised operator's gradients for dU.  Everything is plain numpy on top of the direct
+O(n^2) forms of the C oracle.
+"""
+import numpy as np
+
+from . import ref
+
+
+def fwd_norm(q, k, v, lam, eps):
+    """Returns (o, rstd): o [batch, heads, n, d] normalised rows, rstd [batch, heads, n] = r_t."""
+    u = ref.fwd_direct(q, k, v, lam)
+    rstd = 1.0 / np.sqrt(np.mean(u * u, axis=-1) + eps)
+    return u * rstd[..., None], rstd
+
+
+def norm_backward_rows(o, rstd, g):
+    """dU from the normalised output o, r_t and the incoming gradient g (all per row)."""
+    o = np.asarray(o, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    c = np.mean(g * o, axis=-1, keepdims=True)
+    return np.asarray(rstd, dtype=np.float64)[..., None] * (g - o * c)
+
+
+def bwd_norm(q, k, v, d_o, lam, eps):
+    """Returns (dq, dk, dv) of sum(d_o * fwd_norm(q, k, v)[0])."""
+    o, rstd = fwd_norm(q, k, v, lam, eps)
+    du = norm_backward_rows(o, rstd, d_o)
+    return ref.bwd_direct(q, k, v, du, lam)

@@ -413,3 +413,90 @@ def test_state_edge_cases():
     qn, kn, vn = (_rand((b, H, 1, d), s)[:, :, 0] for s in (96, 97, 98))
     _, kvf = oracle.fwd_recurrent(q, k, v, lam, return_state=True)
     assert np.allclose(oracle.decode_step(qn, kn, vn, lam, kvf), o_full[:, :, -1], rtol=1e-12, atol=1e-13)
+
+
+# ---- P12: the normalised operator, Sec. 2.1 eq. (2) (Norm read as RMS normalisation of every output row) -----
+def test_norm_single_position_by_hand():
+    """n = 1: u = (q . k) v, so o = sign(q . k) v / rms(v) at eps = 0 (worked by hand for d = 2)."""
+    q = np.array([[[[2.0, -1.0]]]])
+    k = np.array([[[[0.5, 3.0]]]])          # q . k = -2
+    v = np.array([[[[3.0, -4.0]]]])         # rms(v) = sqrt(12.5)
+    o, rstd = oracle.fwd_norm(q, k, v, 0.9, 0.0)
+    assert np.allclose(o[0, 0, 0], [-3.0 / np.sqrt(12.5), 4.0 / np.sqrt(12.5)], rtol=1e-15)
+    assert np.allclose(rstd[0, 0, 0], 1.0 / (2.0 * np.sqrt(12.5)), rtol=1e-15)
+    # with eps: mean(u^2) = 4 * 12.5 = 50
+    o, rstd = oracle.fwd_norm(q, k, v, 0.9, 14.0)
+    assert np.allclose(rstd[0, 0, 0], 1.0 / 8.0, rtol=1e-15)
+    assert np.allclose(o[0, 0, 0], [-6.0 / 8.0, 8.0 / 8.0], rtol=1e-15)
+
+
+def test_norm_rows_have_unit_rms_and_keep_direction():
+    shape = (2, 3, 33, 8)
+    q, k, v = (_rand(shape, s) for s in (90, 91, 92))
+    lam = np.array([0.5, 0.9, 1.0])
+    o, rstd = oracle.fwd_norm(q, k, v, lam, 0.0)
+    assert np.allclose(np.mean(o * o, axis=-1), 1.0, rtol=1e-13)
+    u = oracle.fwd_recurrent(q, k, v, lam)   # the other form of the un-normalised operator
+    assert np.allclose(o, u * rstd[..., None], rtol=1e-11, atol=1e-13)
+    assert np.all(rstd > 0)
+    # positive eps shrinks every row: rms < 1, same direction
+    o2, rstd2 = oracle.fwd_norm(q, k, v, lam, 0.3)
+    assert np.all(np.mean(o2 * o2, axis=-1) < 1.0)
+    assert np.allclose(o2 * rstd[..., None], o * rstd2[..., None], rtol=1e-12, atol=1e-15)
+    assert np.allclose(1.0 / rstd2 ** 2 - 1.0 / rstd ** 2, 0.3, rtol=1e-10)
+
+
+def test_norm_scale_invariance_and_large_eps_limit():
+    shape = (1, 2, 20, 4)
+    q, k, v = (_rand(shape, s) for s in (93, 94, 95))
+    lam = np.array([0.8, 0.97])
+    o, _ = oracle.fwd_norm(q, k, v, lam, 0.0)
+    for a, b, c in ((3.0, 1.0, 1.0), (1.0, 0.25, 1.0), (1.0, 1.0, 7.0)):
+        o2, _ = oracle.fwd_norm(a * q, b * k, c * v, lam, 0.0)
+        assert np.allclose(o2, o, rtol=1e-12, atol=1e-14)
+    o3, _ = oracle.fwd_norm(-q, k, v, lam, 0.0)
+    assert np.allclose(o3, -o, rtol=1e-12, atol=1e-14)
+    # eps far above mean(u^2): Norm tends to u / sqrt(eps), the un-normalised operator up to a constant
+    big = 1e12
+    o4, _ = oracle.fwd_norm(q, k, v, lam, big)
+    assert np.allclose(o4 * np.sqrt(big), oracle.fwd_direct(q, k, v, lam), rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.05])
+def test_norm_gradients_by_finite_differences(eps):
+    shape = (1, 2, 6, 3)
+    q, k, v, do = (_rand(shape, s) for s in (96, 97, 98, 99))
+    lam = np.array([0.6, 0.95])
+    grads = dict(zip("qkv", oracle.bwd_norm(q, k, v, do, lam, eps)))
+
+    def loss(**a):
+        return float(np.sum(oracle.fwd_norm(a["q"], a["k"], a["v"], lam, eps)[0] * do))
+
+    h = 1e-6
+    base = {"q": q, "k": k, "v": v}
+    for name in "qkv":
+        fd = np.zeros(shape)
+        for idx in np.ndindex(*shape):
+            ap, am = dict(base), dict(base)
+            ap[name], am[name] = base[name].copy(), base[name].copy()
+            ap[name][idx] += h
+            am[name][idx] -= h
+            fd[idx] = (loss(**ap) - loss(**am)) / (2 * h)
+        assert np.allclose(fd, grads[name], rtol=2e-6, atol=2e-8), name
+
+
+def test_norm_gradients_are_orthogonal_to_their_inputs_at_eps_zero():
+    """At eps = 0 the loss is homogeneous of degree 0 in each of Q, K, V: <dX, X> = 0; with eps > 0 it is not."""
+    shape = (2, 2, 40, 5)
+    q, k, v, do = (_rand(shape, s) for s in (100, 101, 102, 103))
+    lam = np.array([0.7, 0.99])
+    dq, dk, dv = oracle.bwd_norm(q, k, v, do, lam, 0.0)
+    scale = np.sum(np.abs(dq * q))
+    for g, x in ((dq, q), (dk, k), (dv, v)):
+        assert abs(np.sum(g * x)) <= 1e-11 * scale
+    # per row: dU_t is orthogonal to o_t
+    o, rstd = oracle.fwd_norm(q, k, v, lam, 0.0)
+    du = oracle.norm_backward_rows(o, rstd, do)
+    assert np.max(np.abs(np.sum(du * o, axis=-1))) <= 1e-12 * np.max(np.abs(du))
+    dq2, _, _ = oracle.bwd_norm(q, k, v, do, lam, 0.5)
+    assert abs(np.sum(dq2 * q)) > 1e-3 * np.sum(np.abs(dq2 * q))
