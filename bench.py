@@ -202,6 +202,22 @@ def main():
                             "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                             "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1)})
         del st
+    # the operator with its output normalisation (eq. (2); la2_fwd_norm / la2_bwd_norm) beside the plain one
+    normed = []
+    for wl, g in sweep[1:3]:
+        rstd = torch.empty(g["q"].shape[:3], dtype=torch.float32, device=dev)
+        d_u = torch.empty_like(g["q"])
+        f_ms = time_ms(lambda: binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], 1e-6, out=g["o"], rstd=rstd,
+                                                    workspace=g["ws"]), iters, warm=40)
+        b_ms = time_ms(lambda: binding.la2_bwd_norm(g["q"], g["k"], g["v"], g["o"], rstd, g["d_o"], g["lam"],
+                                                    out=g["grads"], d_u=d_u, workspace=g["ws"]), iters, warm=40)
+        pf_ms = time_ms(lambda: fwd(g), iters, warm=40)
+        pb_ms = time_ms(lambda: bwd(g), iters, warm=40)
+        normed.append({"workload": wl.name + " + Norm (rms over head_dim, eps 1e-6)",
+                       "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                       "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1),
+                       "plain_fwd_ms": round(pf_ms, 4), "plain_bwd_ms": round(pb_ms, 4)})
+        del rstd, d_u
     # the forward pass as the O(n^2 d) masked left product (comparison kernel) against the block recurrence
     crossover = []
     short = [(wl_, stage(wl_)) for wl_ in (workloads.Workload("config3_like_b%d_n%d_h16_d128" % (b_, n_), b_, 16, n_, 128,
@@ -313,6 +329,7 @@ def main():
         "other_configs": others,
         "state_handover": with_states,
         "saved_forward_states": saved,
+        "normalised_operator": normed,
         "left_product_comparison": crossover,
         "decode": decode,
         "roofline": roofline,

@@ -10,7 +10,8 @@
  *
  * evaluated block by block as in Algorithm 1 (forward) and Algorithm 2 (backward): an
  * intra-block masked product plus an inter-block product with a running d x d state.
- * No 1/sqrt(d) scaling, no softmax and no output normalisation are applied.
+ * No 1/sqrt(d) scaling and no softmax are applied; the output normalisation of eq. (2) only by
+ * la2_fwd_norm / la2_bwd_norm.
  *
  * Conventions common to every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device.  The caller owns every
@@ -48,7 +49,8 @@ typedef enum {
   LA2_ERR_DTYPE = 3,        /* dtype is neither LA2_F32 nor LA2_BF16                        */
   LA2_ERR_STRIDE_ALIGN = 4, /* pointer or stride not 16-byte aligned, or rows overlap       */
   LA2_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than la2_workspace_bytes()         */
-  LA2_ERR_LAUNCH = 6        /* the HIP runtime refused a launch                             */
+  LA2_ERR_LAUNCH = 6,       /* the HIP runtime refused a launch                             */
+  LA2_ERR_VALUE = 7         /* a scalar argument is out of range (eps negative or not finite) */
 } la2_status;
 
 typedef enum { LA2_F32 = 0, LA2_BF16 = 1 } la2_dtype;
@@ -127,6 +129,32 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
                          const void* d_o, const float* lambda, const float* kv_init,
                          const float* d_kv_final, void* dq, void* dk, void* dv, float* d_kv_init,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The operator with its output normalisation, eq. (2): O = Norm(Q (K^T V)) with the decay and the causal
+ * mask of Sec. 3.2.1 inside.  The paper names Norm without defining it and drops it from its derivations
+ * (Sec. 3.2.1); here it is the root-mean-square normalisation of every output row over the head's
+ * features, without a gain:
+ *     u_t = sum_{s<=t} lambda^(t-s) (q_t . k_s) v_s,   r_t = 1 / sqrt(mean_j u_tj^2 + eps),   o_t = r_t u_t
+ * Forward: Algorithm 1 with the normalisation applied to each finished output tile in registers (u never
+ * goes to memory); r is kept for the backward pass.  Backward: one pass over the rows forms
+ *     d_u_t = r_t (d_o_t - o_t mean_j(d_o_tj o_tj))
+ * (the gradient with respect to u; this is where Algorithm 2's load of O_i is used), then Algorithm 2 runs
+ * on d_u.
+ *   eps   in   host scalar, >= 0 and finite, else LA2_ERR_VALUE.  With eps == 0 a row whose u_t is all
+ *              zero yields NaN.
+ *   rstd  out (forward) / in (backward)   device fp32 [batch, heads, seqlen] dense: r_t; 4-byte aligned
+ *   o     out (forward) / in (backward)   the normalised output
+ *   d_u   out  device, same layout as d_o: the gradient with respect to u (also the scratch that
+ *              Algorithm 2 reads; fully overwritten; must not alias any other argument)
+ * Everything else, the workspace included, as for la2_fwd (LA2_OP_FWD) and la2_bwd (LA2_OP_BWD).
+ */
+la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v,
+                        const float* lambda, float eps, void* o, float* rstd, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                        const float* rstd, const void* d_o, const float* lambda, void* d_u, void* dq,
+                        void* dk, void* dv, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * One step of the recurrent form (Sec. 3.2.1, recursive form), for every (batch, head):

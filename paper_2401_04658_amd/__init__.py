@@ -7,6 +7,8 @@ from .binding import (  # noqa: F401
     la2_bwd,
     la2_fwd_state,
     la2_bwd_state,
+    la2_fwd_norm,
+    la2_bwd_norm,
     la2_decode_step,
     la2_decode_multi,
     la2_left_product_fwd,

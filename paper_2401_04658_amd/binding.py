@@ -67,6 +67,10 @@ def load():
     lib.la2_bwd_state.restype = ctypes.c_int
     lib.la2_bwd_saved.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_saved.restype = ctypes.c_int
+    lib.la2_fwd_norm.argtypes = [dp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
+    lib.la2_fwd_norm.restype = ctypes.c_int
+    lib.la2_bwd_norm.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd_norm.restype = ctypes.c_int
     lib.la2_left_product_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.la2_left_product_fwd.restype = ctypes.c_int
     lib.la2_decode_multi.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -172,6 +176,51 @@ def la2_bwd(q, k, v, d_o, lam, out=None, workspace=None):
         _check(lib.la2_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
                            lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr, ws_bytes,
                            _stream(q)))
+    return dq, dk, dv
+
+
+def la2_fwd_norm(q, k, v, lam, eps=1e-6, out=None, rstd=None, workspace=None):
+    """(o, rstd) = Norm(LA2(q, k, v; lam)): every output row scaled by rstd = 1 / sqrt(mean(row^2) + eps)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_norm: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    if rstd is None:
+        rstd = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    if rstd.dtype != torch.float32 or tuple(rstd.shape) != tuple(q.shape[:3]) or not rstd.is_contiguous():
+        raise ValueError("la2_fwd_norm: rstd must be a contiguous fp32 [batch, heads, seqlen] tensor")
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_FWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_norm(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
+                                float(eps), out.data_ptr(), rstd.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
+    return out, rstd
+
+
+def la2_bwd_norm(q, k, v, o, rstd, d_o, lam, out=None, d_u=None, workspace=None):
+    """(dq, dk, dv) of sum(la2_fwd_norm(q, k, v)[0] * d_o); o, rstd are la2_fwd_norm's results.  d_u (same
+    layout as d_o) receives the gradient with respect to the un-normalised output."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd_norm: tensors must live on the GPU")
+    _same_layout(q, k, v, o, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    if d_u is None:
+        d_u = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv, d_u)
+    if rstd.dtype != torch.float32 or tuple(rstd.shape) != tuple(q.shape[:3]) or not rstd.is_contiguous():
+        raise ValueError("la2_bwd_norm: rstd must be a contiguous fp32 [batch, heads, seqlen] tensor")
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd_norm(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                rstd.data_ptr(), d_o.data_ptr(), lam.data_ptr(), d_u.data_ptr(), dq.data_ptr(),
+                                dk.data_ptr(), dv.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
     return dq, dk, dv
 
 

@@ -92,6 +92,9 @@ struct ScanArgs {
   // (z, y): the transposed states): the pre-pass is skipped.  Ignored when the plan has one chunk.
   const float* saved_states = nullptr;
   bool saved_tr = false;
+  // Norm epilogue (forward scans): r of every position goes here, the output rows are scaled by it
+  float* rstd = nullptr;
+  float eps = 0.f;
 };
 
 la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace) {
@@ -138,6 +141,8 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
   p.x[0] = a.x; p.y[0] = a.y; p.z[0] = a.z; p.w[0] = a.w;
   p.init[0] = a.init; p.init_transposed = a.init_tr ? 1 : 0;
   p.fin[0] = a.fin;
+  p.rstd = a.rstd;
+  p.eps = a.eps;
   const bool bf16 = d->dtype == LA2_BF16;
   hipError_t e = bf16 ? la2::launch_scan_bf16(d->head_dim, reverse, p, s) : la2::launch_scan_f32(d->head_dim, reverse, p, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
@@ -361,6 +366,48 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
                        workspace_bytes, hip_stream);
 }
 
+la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                        float eps, void* o, float* rstd, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!q || !k || !v || !o || !rstd || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(rstd, 4) ||
+      !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const Plan pl = make_plan(desc);
+  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
+  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  ScanArgs a{q, k, v, o};
+  a.rstd = rstd;
+  a.eps = eps;
+  return run_scan(desc, pl, false, a, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                        const float* rstd, const void* d_o, const float* lambda, void* d_u, void* dq, void* dk,
+                        void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(dq, 16) || !aligned(dk, 16) ||
+      !aligned(dv, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const size_t need = make_plan(desc).workspace;
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
+    return LA2_ERR_WORKSPACE;
+  la2::NormBwdParams np{o, d_o, rstd, d_u, desc->stride_b, desc->stride_h, desc->stride_n,
+                        desc->batch, desc->heads, desc->seqlen};
+  if (la2::launch_norm_bwd_rows(desc->head_dim, desc->dtype == LA2_BF16, np,
+                                reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return LA2_ERR_LAUNCH;
+  return la2_bwd(desc, q, k, v, d_u, lambda, dq, dk, dv, workspace, workspace_bytes, hip_stream);
+}
+
 la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
                                 const float* lambda, void* o, void* hip_stream) {
   la2_status st = check_desc(desc);
@@ -424,6 +471,7 @@ const char* la2_status_string(la2_status status) {
     case LA2_ERR_STRIDE_ALIGN: return "pointer or stride violates the 16-byte alignment / layout rules";
     case LA2_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case LA2_ERR_LAUNCH: return "HIP kernel launch failed";
+    case LA2_ERR_VALUE: return "a scalar argument is out of range";
   }
   return "unknown status";
 }

@@ -42,7 +42,44 @@ struct ScanParams {
   float* fin[2];
   int32_t init_transposed;
   int32_t fin_transposed;
+  // Norm epilogue of a forward scan (eq. (2); scan 0 only, the fp32 kernels and the forward bf16 kernels):
+  // when rstd is not nullptr every output row is multiplied by r = 1 / sqrt(mean_j w_j^2 + eps) before it is
+  // stored, and r goes to rstd[chain * n + position] (fp32).
+  float* rstd;
+  float eps;
 };
+
+// Norm epilogue, shared by the scan kernels.  A 32 x 32 output tile sits in MFMA accumulators transposed
+// (lane = position l32, 16 features per lane, the other 16 in lane l32 + 32); the NP waves that hold the
+// feature tiles of one row exchange their partial sums of squares through `red` ([32 rows][NP] floats per
+// row tile).  Between publish and collect the caller places a workgroup barrier.
+// The exchange buffer: N floats of LDS in the kernels that ask for them, nothing otherwise.
+template <int N>
+struct NormExchange {
+  static __device__ __forceinline__ float* get() {
+    __shared__ float red[N];
+    return red;
+  }
+};
+template <>
+struct NormExchange<0> {
+  static __device__ __forceinline__ float* get() { return nullptr; }
+};
+template <int NP, typename Acc>
+__device__ __forceinline__ void norm_publish(const Acc& sq, float* red, int l32, int hh, int slot) {
+  float s = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; v++) s = fmaf(sq[v], sq[v], s);
+  s += __shfl_xor(s, 32);
+  if (hh == 0) red[l32 * NP + slot] = s;
+}
+template <int NP>
+__device__ __forceinline__ float norm_collect(const float* red, int l32, float inv_d, float eps) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NP; i++) s += red[l32 * NP + i];
+  return __builtin_amdgcn_rsqf(fmaf(s, inv_d, eps));
+}
 
 // Block size (rows of the intra-block tile) per data type / head dim.
 int block_size_bf16(int head_dim);
@@ -81,6 +118,19 @@ struct RecurParams {
   int64_t stride_b, stride_h, stride_n;  // elements, all of x, y, z, w
 };
 hipError_t launch_recur(int head_dim, bool bf16, int batch, int ninst, const RecurParams& p, hipStream_t s);
+
+// Backward of the Norm epilogue, row by row: du = rstd * (g - o * mean_j(g_j o_j)) with o the normalised
+// output and g its gradient; o, g, du share the layout given by the strides (elements), rstd is
+// [batch * heads][n] fp32.
+struct NormBwdParams {
+  const void* o;
+  const void* g;
+  const float* rstd;
+  void* du;
+  int64_t stride_b, stride_h, stride_n;
+  int32_t batch, heads, n;
+};
+hipError_t launch_norm_bwd_rows(int head_dim, bool bf16, const NormBwdParams& p, hipStream_t s);
 
 // dst[i] = src ? src[i] : 0 for count floats (a state that passes through an empty sequence)
 hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s);

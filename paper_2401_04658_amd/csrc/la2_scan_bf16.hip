@@ -7,8 +7,12 @@ namespace la2 {
 namespace {
 using namespace bf16k;
 
-template <int D, bool REV>
+// NORM: the Norm epilogue of eq. (2) on a forward scan: the waves that hold the feature tiles of a row
+// exchange their sums of squares through LDS (one more workgroup barrier per block), scale the finished
+// tile and store r.
+template <int D, bool REV, bool NORM = false>
 __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
+  static_assert(!NORM || !REV, "the Norm epilogue belongs to the forward pass");
   using C = Cfg<D>;
   constexpr int KS = C::KS, NT = C::NT, RT = C::RT, TILE = C::TILE, LW = C::LW;
   // two tile buffers as two distinct LDS objects ([X, Y, Z] each) so that reads of one buffer are
@@ -17,8 +21,9 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   __shared__ __attribute__((aligned(1024))) __bf16 sT1[3][TILE];
   __shared__ __attribute__((aligned(1024))) __bf16 sT2[3][TILE];
   __shared__ __attribute__((aligned(16))) __bf16 sW[4][32 * RT * LW];
-  // vector-memory operations a wave issues per block: direct loads (3 tiles) and output stores
-  constexpr int LOADS_PER_BLOCK = 3 * C::DMA_PER_WAVE, STORES_PER_BLOCK = 32 * RT * 4 / 64;
+  float* const sRed = NormExchange<NORM ? 2 * kB * NT : 0>::get();   // [block parity][position][feature tile]
+  // vector-memory operations a wave issues per block: direct loads (3 tiles), output stores and r
+  constexpr int LOADS_PER_BLOCK = 3 * C::DMA_PER_WAVE, STORES_PER_BLOCK = 32 * RT * 4 / 64 + (NORM ? RT : 0);
   // s_waitcnt immediate for "at most N vector-memory operations outstanding" (gfx9 encoding)
   constexpr int VM_YOUNGER = STORES_PER_BLOCK + LOADS_PER_BLOCK;
   constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
@@ -50,6 +55,9 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   const __amdgpu_buffer_rsrc_t bw =
       make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
   const float l2 = log2f(p.lambda[hi]);
+  // Norm epilogue: r of this chain's positions; stores past position n - 1 are dropped
+  const __amdgpu_buffer_rsrc_t brs =
+      make_rsrc(NORM ? p.rstd + (int64_t)chain * n : nullptr, NORM ? (uint32_t)n * 4u : 0u);
 
   const int nblocks = (n + kB - 1) / kB;
   const int cb = p.chunk_tokens / kB;
@@ -380,6 +388,26 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
       pin(outp[i]);
     }
     LA2_SLOT_END();
+    if constexpr (NORM) {
+      // Two exchange buffers, by block parity: a wave that runs ahead into the next block (whose last
+      // block has no tile barrier) must not overwrite sums that a slower wave has yet to read.
+      float* const red = sRed + (it & 1) * (kB * NT);
+#pragma unroll
+      for (int i = 0; i < RT; i++) norm_publish<NT>(outp[i], red + 32 * (rt0 + i) * NT, l32, hh, dvt);
+      lds_barrier();
+#pragma unroll
+      for (int i = 0; i < RT; i++) {
+        const float r = norm_collect<NT>(red + 32 * (rt0 + i) * NT, l32, 1.f / (float)D, p.eps);
+#pragma unroll
+        for (int v = 0; v < 16; v++) outp[i][v] *= r;
+        pin(outp[i]);
+        // the lanes that hold r of a position store it; every other lane's store is dropped
+        const uint32_t roff =
+            (dvt == 0 && hh == 0) ? (uint32_t)(blk * kB + 32 * (rt0 + i) + l32) * 4u : 0xFFFFFFF0u;
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(r), brs, roff, 0, 0);
+      }
+      LA2_SLOT_END();
+    }
     return has_next;
   };
   int it = 0;
@@ -423,6 +451,7 @@ hipError_t launch_scan_bf16_full(int head_dim, bool reverse, const ScanParams& p
     else         hipLaunchKernelGGL((scan_bf16_kernel<128, false>), g, b, 0, s, p);
   } else {
     if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<64, true>), g, b, 0, s, p);
+    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_kernel<64, false, true>), g, b, 0, s, p);
     else         hipLaunchKernelGGL((scan_bf16_kernel<64, false>), g, b, 0, s, p);
   }
   return hipGetLastError();
@@ -435,7 +464,7 @@ hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hip
   // the half-block kernel measured faster at every launch size, also at one workgroup per compute unit;
   // it is also the only d = 128 kernel that takes start states and hands out final states
   const bool with_state = p.init[0] || p.init[1] || p.fin[0] || p.fin[1];
-  const bool half = p.variant != 1 || with_state;
+  const bool half = p.variant != 1 || with_state || p.rstd != nullptr;   // also the one with the Norm epilogue
   if (head_dim == 128 && half && p.chunk_tokens % 32 == 0) {
     const bool twin = p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0];
     return launch_scan_bf16_half(reverse, twin, p, s);

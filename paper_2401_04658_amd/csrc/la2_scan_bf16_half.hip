@@ -24,8 +24,14 @@ constexpr int kBH = 32;
 //
 // NBUF tile buffers: block it + NBUF - 1 streams in while block it is computed.  With 3 buffers two
 // (plain) workgroups fit on a compute unit.
-template <bool REV, bool TWIN, int NBUF>
+//
+// NORM: the Norm epilogue of eq. (2) on a forward scan: the four waves exchange the sums of squares of
+// their quarter rows through LDS (one more workgroup barrier per block), scale the finished tile and
+// wave 0 stores r.  The LDS is full, so the room for the exchange is taken from the output staging,
+// which then handles the block in two halves of 16 positions.
+template <bool REV, bool TWIN, int NBUF, bool NORM = false>
 __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
+  static_assert(!NORM || (!REV && !TWIN), "the Norm epilogue belongs to the forward pass");
   constexpr int D = 128, B = kBH;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
@@ -33,9 +39,11 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
   using Loader = TileLoader<D, NTL, B, NW>;
   __shared__ __attribute__((aligned(1024))) __bf16 sT[NBUF][NTL][TILE];
-  __shared__ __attribute__((aligned(16))) __bf16 sW[NW][32 * LW];
+  constexpr int STAGE_ROWS = NORM ? 16 : 32;   // positions staged at a time
+  __shared__ __attribute__((aligned(16))) __bf16 sW[NW][STAGE_ROWS * LW];
+  float* const sRed = NormExchange<NORM ? 2 * 32 * 4 : 0>::get();   // [block parity][position][wave]
   constexpr int NDMA = NTL * Loader::DMA_PER_WAVE;   // direct loads per wave and block
-  constexpr int NST = 32 * 4 / 64;             // 16-byte stores per lane and block
+  constexpr int NST = 32 * 4 / 64 + (NORM ? 1 : 0);   // stores per lane and block: 16-byte output stores, r
   static_assert(NDMA <= KS, "one direct load per slot of phase 1");
   // vector-memory operations of this wave that are younger than the direct loads of block it + 1 when block
   // it waits for them: the loads of blocks it + 2 .. it + NBUF - 1 and as many blocks' stores
@@ -70,6 +78,9 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   const __amdgpu_buffer_rsrc_t bw =
       make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
   const float l2 = log2f(p.lambda[hi]);
+  // Norm epilogue: r of this chain's positions; stores past position n - 1 are dropped
+  const __amdgpu_buffer_rsrc_t brs =
+      make_rsrc(NORM ? p.rstd + (int64_t)chain * n : nullptr, NORM ? (uint32_t)n * 4u : 0u);
 
   const int nblocks = (n + B - 1) / B;
   const int cb = p.chunk_tokens / B;
@@ -256,6 +267,41 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     pin(sa_first);
     pin(inter);
     LA2_SLOT_END();
+    if constexpr (NORM) {
+      // Two exchange buffers, by block parity: a wave that runs ahead into the next block (whose last
+      // block has no tile barrier) must not overwrite sums that a slower wave has yet to read.
+      float* const red = sRed + (it & 1) * (32 * 4);
+      norm_publish<4>(inter, red, l32, hh, dvt);
+      lds_barrier();
+      const float r = norm_collect<4>(red, l32, 1.f / (float)D, p.eps);
+#pragma unroll
+      for (int v = 0; v < 16; v++) inter[v] *= r;
+      pin(inter);
+      bf16x4 pk[4];
+#pragma unroll
+      for (int g = 0; g < 4; g++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) pk[g][e] = (__bf16)inter[4 * g + e];
+#pragma unroll
+      for (int half = 0; half < 2; half++) {   // this wave's LDS operations run in order: no barrier needed
+        if ((l32 >> 4) == half) {
+#pragma unroll
+          for (int g = 0; g < 4; g++)
+            *reinterpret_cast<bf16x4*>(stage + (l32 & 15) * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk[g];
+        }
+        // Lanes read what OTHER lanes wrote under a mask: without this the compiler treats the read of a
+        // lane that wrote nothing as a repeat of its previous read and drops it.
+        asm volatile("" ::: "memory");
+        const int row = l >> 2, cc = l & 3;
+        const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
+        const uint32_t off =
+            ((uint32_t)(blk * B + 16 * half + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
+        __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
+      }
+      // r of this block's positions: the lanes of wave 0 that hold them; every other lane's store is dropped
+      const uint32_t roff = (dvt == 0 && hh == 0) ? (uint32_t)(blk * B + l32) * 4u : 0xFFFFFFF0u;
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(r), brs, roff, 0, 0);
+    } else {
 #pragma unroll
     for (int g = 0; g < 4; g++) {
       bf16x4 pk;
@@ -264,12 +310,13 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
       *reinterpret_cast<bf16x4*>(stage + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
     }
 #pragma unroll
-    for (int i = 0; i < NST; i++) {
+    for (int i = 0; i < 32 * 4 / 64; i++) {
       const int id = l + 64 * i;
       const int row = id >> 2, cc = id & 3;
       const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
       const uint32_t off = ((uint32_t)(blk * B + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
       __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
+    }
     }
     LA2_SLOT_END();
     return has_next;
@@ -312,6 +359,7 @@ hipError_t launch_scan_bf16_half(bool reverse, bool twin, const ScanParams& p, h
   } else {
     dim3 g((unsigned)grid), b(kThreads);
     if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, false, 3>), g, b, 0, s, p);
+    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_half_kernel<false, false, 3, true>), g, b, 0, s, p);
     else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, false, 3>), g, b, 0, s, p);
   }
   return hipGetLastError();

@@ -80,6 +80,7 @@ __global__ __launch_bounds__(2 * D, 1) void scan_f32_kernel(ScanParams p) {
   constexpr int NTL = STATE_ONLY ? 2 : 3;
   constexpr int DMA_PER_WAVE = (TILE * 4 / 1024) / NT;   // 1 KiB instructions per tile and wave (= 4)
   __shared__ __attribute__((aligned(1024))) float sT[2][NTL][TILE];
+  __shared__ float sRed[STATE_ONLY ? 1 : kB * NT];   // Norm epilogue: partial sums of squares, [row][wave]
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w;
@@ -224,8 +225,16 @@ __global__ __launch_bounds__(2 * D, 1) void scan_f32_kernel(ScanParams p) {
       for (int v = 0; v < 16; v++) acc[v] *= inter_scale;
 #pragma unroll
       for (int v = 0; v < 16; v++) acc = mfma(zc[v], st[v] * dg[v], acc);
-      // output: lane = position l32, elements v = 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
       const int pos = blk * kB + l32;
+      if (p.rstd != nullptr) {   // Norm epilogue (eq. (2)); the previous block's reads ended before its last barrier
+        norm_publish<NT>(acc, sRed, l32, hh, dvt);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS only: the next tiles stay in flight
+        const float r = norm_collect<NT>(sRed, l32, 1.f / (float)D, p.eps);
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[v] *= r;
+        if (dvt == 0 && hh == 0 && pos < n) p.rstd[(int64_t)chain * n + pos] = r;
+      }
+      // output: lane = position l32, elements v = 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
       if (pos < n) {
         float* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;
 #pragma unroll

@@ -11,7 +11,7 @@ from paper_2401_04658_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "la2.h")
 
-OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH = range(7)
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH, E_VALUE = range(8)
 
 
 @pytest.fixture(scope="module")
@@ -157,7 +157,7 @@ def test_block_size_and_status_strings(lib):
             d = dense(lib, 1, 1, 128, hd, dt)
             assert lib.la2_block_size(ctypes.byref(d)) in (32, 64, 128)
     seen = set()
-    for code in range(7):
+    for code in range(8):
         s = lib.la2_status_string(code)
         assert s and s not in seen
         seen.add(s)
@@ -217,3 +217,29 @@ def test_decode_multi_validation(lib):
     assert dm(dt=5) == E_DTYPE
     assert dm(q=P + 4) == E_ALIGN
     assert dm(t=0, q=None) == OK and dm(b=0, q=None) == OK
+
+
+def test_norm_entry_points_validate_before_any_launch(lib):
+    d = dense(lib, 300, 2, 128, 64, binding.LA2_BF16)
+    ref = ctypes.byref(d)
+    fn = lambda eps=1e-6, q=P, o=P, rstd=P: lib.la2_fwd_norm(ref, q, P, P, P, eps, o, rstd, None, 0, None)
+    assert fn(eps=-1.0) == E_VALUE and fn(eps=float("nan")) == E_VALUE and fn(eps=float("inf")) == E_VALUE
+    assert fn(q=None) == E_NULL and fn(rstd=None) == E_NULL
+    assert fn(o=P + 8) == E_ALIGN and fn(rstd=P + 2) == E_ALIGN
+    bn = lambda o=P, rstd=P, d_u=P, dq=P: lib.la2_bwd_norm(ref, P, P, P, o, rstd, P, P, d_u, dq, P, P, None, 0, None)
+    assert bn(o=None) == E_NULL and bn(rstd=None) == E_NULL and bn(d_u=None) == E_NULL and bn(dq=None) == E_NULL
+    assert bn(d_u=P + 4) == E_ALIGN and bn(rstd=P + 1) == E_ALIGN
+    d.head_dim = 100
+    assert fn() == E_SHAPE and bn() == E_SHAPE
+    # chunked problems need the workspace of la2_fwd / la2_bwd
+    try:
+        lib.la2_set_chunk_tokens(256)
+        d = dense(lib, 1, 2, 1024, 128, binding.LA2_F32)
+        ref = ctypes.byref(d)
+        assert fn() == E_WS and bn() == E_WS
+    finally:
+        lib.la2_set_chunk_tokens(0)
+    # nothing to do
+    d = dense(lib, 0, 2, 128, 64, binding.LA2_BF16)
+    ref = ctypes.byref(d)
+    assert fn(q=None, rstd=None) == OK and bn(o=None) == OK

@@ -1,0 +1,179 @@
+"""GPU parity of the normalised operator (la2_fwd_norm / la2_bwd_norm, through the C ABI) against the fp64
+oracle: eq. (2) with Norm read as the root-mean-square normalisation of every output row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_04658_amd import binding, workloads
+from parity import TOL, assert_close, to64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _auto_chunking():
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+    yield
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+
+
+def make_inputs(b, H, n, d, dtype, seed, lam=None):
+    t = workloads.Workload("case", b, H, n, d, dtype, seed=seed, backward=True).tensors()
+    if lam is not None:
+        t["lam"] = torch.as_tensor(lam, dtype=torch.float32).reshape(-1).expand(H).contiguous()
+    return t
+
+
+def check_norm(t, dtype, eps, tag, g=None):
+    """Forward (o, rstd) and backward (d_u, dq, dk, dv; fed with the GPU's own o and rstd, as a caller would)."""
+    g = g or {k: v.to(DEV) for k, v in t.items()}
+    o, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], eps)
+    d_u = torch.empty_like(g["d_o"])
+    dq, dk, dv = binding.la2_bwd_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], d_u=d_u)
+    torch.cuda.synchronize()
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    ref_o, ref_r = oracle.fwd_norm(q, k, v, lam, eps)
+    assert_close(tag + " o", o, ref_o, dtype)
+    assert_close(tag + " rstd", rstd, ref_r, dtype)
+    ref_du = oracle.norm_backward_rows(ref_o, ref_r, do)
+    assert_close(tag + " d_u", d_u, ref_du, dtype)
+    refs = oracle.bwd_norm(q, k, v, do, lam, eps)
+    if q.shape[2] == 1:
+        # A single position: u = (q . k) v is parallel to v and d_u is orthogonal to o, hence to v, so
+        # dq = (d_u . v) k and dk = (d_u . v) q vanish up to eps: all that is left of them is rounding,
+        # which is measured against the size of the cancelling terms instead of the (near-zero) result.
+        size = np.sum(np.abs(ref_du * v), axis=-1, keepdims=True)
+        for name, got, ref, other in (("dq", dq, refs[0], k), ("dk", dk, refs[1], q)):
+            err = np.max(np.abs(to64(got) - ref) / (size * np.max(np.abs(other))))
+            assert err <= TOL[dtype], "%s %s: %.3e of the cancelling terms" % (tag, name, err)
+        assert_close(tag + " dv", dv, refs[2], dtype)
+    else:
+        for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+            assert_close(tag + " " + name, got, ref, dtype)
+    return o, rstd, d_u, (dq, dk, dv)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n", [1, 31, 64, 129, 200, 517])
+def test_norm_small_shapes(dtype, d, n):
+    t = make_inputs(2, 3, n, d, dtype, seed=700 + n + d, lam=[0.5, 0.93, 1.0])
+    check_norm(t, dtype, 1e-6, "norm n%d d%d %s" % (n, d, dtype))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("chunk", [64, 192])
+def test_norm_chunked(dtype, d, chunk):
+    binding.la2_set_chunk_tokens(chunk)
+    t = make_inputs(1, 2, 517, d, dtype, seed=710 + d + chunk, lam=[0.8, 0.99])
+    check_norm(t, dtype, 1e-3, "norm chunk%d d%d %s" % (chunk, d, dtype))
+
+
+@pytest.mark.parametrize("eps", [0.0, 1e-6, 0.5])
+def test_norm_eps_values(eps):
+    for dtype, d in ((torch.bfloat16, 128), (torch.float32, 64)):
+        t = make_inputs(1, 2, 160, d, dtype, seed=720, lam=[0.7, 0.97])
+        o, rstd, _, _ = check_norm(t, dtype, eps, "norm eps %g %s" % (eps, dtype))
+        # every row: mean(o^2) + eps rstd^2 = 1
+        ms = torch.mean(o.double() ** 2, dim=-1) + eps * rstd.double() ** 2
+        assert torch.max(torch.abs(ms - 1.0)).item() <= (2e-2 if dtype == torch.bfloat16 else 1e-5)
+
+
+def test_norm_strided_layout():
+    """[b, n, H, d] storage viewed as [b, H, n, d]; rstd stays dense [b, H, n]."""
+    b, H, n, d = 2, 4, 260, 128
+    for dtype in (torch.bfloat16, torch.float32):
+        t = make_inputs(b, H, n, d, dtype, seed=731)
+        g = {"lam": t["lam"].to(DEV)}
+        for name in ("q", "k", "v", "d_o"):
+            g[name] = t[name].permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+            assert not g[name].is_contiguous()
+        o, _, d_u, grads = check_norm(t, dtype, 1e-4, "norm strided %s" % dtype, g=g)
+        for x in (o, d_u) + grads:
+            assert x.stride() == g["q"].stride()
+
+
+def test_norm_backward_is_algorithm2_on_d_u():
+    """la2_bwd_norm = the row pass followed by la2_bwd on d_u: bitwise the same gradients."""
+    t = make_inputs(2, 2, 300, 128, torch.bfloat16, seed=741)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    o, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], 1e-5)
+    d_u = torch.empty_like(o)
+    a = binding.la2_bwd_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], d_u=d_u)
+    b = binding.la2_bwd(g["q"], g["k"], g["v"], d_u, g["lam"])
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    # and the forward is la2_fwd's output scaled row by row (same kernels, one more rounding)
+    u = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
+    torch.cuda.synchronize()
+    err = (o.double() - u.double() * rstd.double()[..., None]).abs().max().item()
+    assert err <= 2.0 ** -7 * o.double().abs().max().item()
+
+
+def test_norm_empty_and_validation():
+    lam = torch.ones(3, device=DEV)
+    for shape in ((0, 3, 16, 64), (2, 3, 0, 64)):
+        x = torch.zeros(shape, dtype=torch.bfloat16, device=DEV)
+        o, rstd = binding.la2_fwd_norm(x, x, x, lam)
+        assert o.shape == x.shape and rstd.shape == x.shape[:3]
+        grads = binding.la2_bwd_norm(x, x, x, o, rstd, x, lam)
+        assert all(gr.shape == x.shape for gr in grads)
+    x = torch.zeros((1, 3, 8, 64), dtype=torch.bfloat16, device=DEV)
+    for bad in (-1e-6, float("nan"), float("inf")):
+        with pytest.raises(binding.LA2Error):
+            binding.la2_fwd_norm(x, x, x, lam, eps=bad)
+    with pytest.raises(ValueError):
+        binding.la2_fwd_norm(x, x, x, lam, rstd=torch.empty((1, 3, 9), device=DEV))
+
+
+def _sampled_rows(n, rng):
+    fixed = [0, 1, 31, 32, 63, 64, 65, n // 2 - 1, n // 2, n - 65, n - 64, n - 2, n - 1]
+    rows = sorted(set(r for r in fixed if 0 <= r < n) | set(int(r) for r in rng.integers(0, n, 24)))
+    return np.asarray(rows, dtype=np.int64)
+
+
+@pytest.mark.parametrize("wl", [workloads.CONFIG2, workloads.CONFIG3[1], workloads.CONFIG3[3]],
+                         ids=lambda w: w.name)
+def test_norm_full_size_sampled(wl):
+    """Benchmark shapes, in the launch configuration bench.py times: sampled rows of three chains against the
+    oracle (the chain's un-normalised output from the recurrent form, then the row formulas), and two
+    properties of the full result."""
+    eps = 1e-6
+    t = wl.tensors()
+    g = {k: v.to(DEV) for k, v in t.items()}
+    o, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], eps)
+    d_u = torch.empty_like(o)
+    dq, dk, dv = binding.la2_bwd_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], d_u=d_u)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(wl.seed)
+    H, tol = wl.heads, TOL[wl.dtype]
+    for b, h in ((0, 0), (wl.batch - 1, H // 2), (0, H - 1)):
+        rows = _sampled_rows(wl.seqlen, rng)
+        q, k, v, do = (to64(t[x][b, h]) for x in ("q", "k", "v", "d_o"))
+        lam = float(t["lam"][h].double())
+        u = oracle.fwd_recurrent(q[None, None], k[None, None], v[None, None], lam)[0, 0]
+        ref_r = 1.0 / np.sqrt(np.mean(u * u, axis=-1) + eps)
+        ref_o = u * ref_r[:, None]
+        ref_du = oracle.norm_backward_rows(ref_o, ref_r, do)
+        ref_dq, ref_dk, ref_dv = oracle.bwd_rows(q, k, v, ref_du, lam, rows)
+        for name, got, ref in (("o", o, ref_o[rows]), ("rstd", rstd, ref_r[rows]), ("d_u", d_u, ref_du[rows]),
+                               ("dq", dq, ref_dq), ("dk", dk, ref_dk), ("dv", dv, ref_dv)):
+            x = to64(got[b, h])[rows]
+            err = float(np.max(np.abs(x - ref))) / float(np.max(np.abs(ref)))
+            assert np.all(np.isfinite(x))
+            assert err <= tol, "%s %s (b%d h%d): %.3e" % (wl.name, name, b, h, err)
+    # every row has unit mean square (up to eps rstd^2) ...
+    ms = torch.mean(o.double() ** 2, dim=-1) + eps * rstd.double() ** 2
+    assert torch.max(torch.abs(ms - 1.0)).item() <= 2e-2
+    # ... and with eps this small the loss is (nearly) homogeneous of degree 0 in Q, K, V: <dX, X> ~ 0
+    for name, grad, x in (("dq", dq, g["q"]), ("dk", dk, g["k"]), ("dv", dv, g["v"])):
+        val = torch.sum(grad.double() * x.double()).item()
+        scale = torch.sum(torch.abs(grad.double() * x.double())).item()
+        assert abs(val) <= 5e-3 * scale, "%s: <grad, input> = %g against %g" % (name, val, scale)
