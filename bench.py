@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant kernel's loop (for rocprofv3 counter passes); prints its roofline JSON")
+    ap.add_argument("--roofline-op", choices=("fwd", "bwd"), default="fwd",
+                    help="with --roofline-only: loop la2_fwd (one launch of the forward scan kernel) or la2_bwd "
+                         "(the dQ forward scan and the twin dK/dV reverse scan) at (batch 16, n 4096)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus %d is not supported. "
@@ -126,6 +129,12 @@ def main():
         wl_r = workloads.CONFIG3[1]
         g_r = stage(wl_r)
         time_ms(lambda: fwd(g_r), 300)      # long warm-up: lets the clocks settle as in the full benchmark
+        if args.roofline_op == "bwd":
+            b_ms = time_ms(lambda: bwd(g_r), 200)
+            bytes_alg = 20 * wl_r.head_dim * wl_r.token_heads   # dQ scan 8d, twin dK/dV scan 12d (bf16)
+            print(json.dumps({"op": "la2_bwd (%s)" % wl_r.name, "ms": round(b_ms, 4), "algorithmic_bytes": bytes_alg,
+                              "achieved_GBs": round(bytes_alg / (b_ms * 1e-3) / 1e9, 1)}))
+            return
         print(json.dumps(dominant_kernel_roofline(wl_r, g_r, fwd, time_ms, binding, 200)))
         return
 
