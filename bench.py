@@ -187,8 +187,8 @@ def main():
     others = []
     for wl in (workloads.CONFIG2, workloads.CONFIG4):
         g = stage(wl)
-        f_ms = time_ms(lambda: fwd(g), iters)
-        b_ms = time_ms(lambda: bwd(g), iters)
+        f_ms = time_ms(lambda: fwd(g), iters, warm=40)   # freshly staged tensors: warm up as the sweep is
+        b_ms = time_ms(lambda: bwd(g), iters, warm=40)
         tot = f_ms + b_ms
         fl = flops_per_token_head(g["B"], wl.head_dim, "fwd+bwd") * wl.token_heads
         others.append({"workload": wl.name, "B": g["B"], "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
