@@ -9,8 +9,9 @@ namespace {
 
 int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
 int g_scan_variant = 0;           // la2_set_scan_variant()
-// The block kernels form states after whole blocks only; 64 positions is a multiple of every kernel's block size
-constexpr int kStateGranule = 64;
+// The block kernels form states after whole blocks only: 32 positions for the kernels that take states
+// (half-block bf16 kernel for head_dim 128, fp32 kernels), 64 for the full-block bf16 kernel of head_dim 64.
+int state_granule(const la2_desc* d) { return (d->dtype == LA2_BF16 && d->head_dim == 64) ? 64 : 32; }
 
 int device_cu_count() {
   static int cached = 0;
@@ -165,7 +166,7 @@ la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanAr
   return la2::launch_scan_bf16(d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
-// The state entry points split a sequence whose length is not a multiple of kStateGranule into whole
+// The state entry points split a sequence whose length is not a multiple of state_granule() into whole
 // blocks (block kernels) and a tail (token recurrence) when the state beyond the tail is asked for.
 // Their workspace: chunk states of whichever of the two plans needs more, then (backward only) one
 // d x d fp32 state per chain that carries dKV from the tail to the block kernels.
@@ -176,20 +177,20 @@ struct StateWorkspace {
 
 la2_desc whole_blocks(const la2_desc* d) {
   la2_desc w = *d;
-  w.seqlen = d->seqlen - d->seqlen % kStateGranule;
+  w.seqlen = d->seqlen - d->seqlen % state_granule(d);
   return w;
 }
 
 StateWorkspace state_workspace(const la2_desc* d, bool backward) {
   StateWorkspace w{make_plan(d).workspace, 0};
-  if (d->seqlen % kStateGranule != 0) {
+  if (d->seqlen % state_granule(d) != 0) {
     const la2_desc wb = whole_blocks(d);
     const size_t other = make_plan(&wb).workspace;
     if (other > w.chunk_states) w.chunk_states = other;
   }
   w.chunk_states = (w.chunk_states + 255) & ~(size_t)255;
   w.total = w.chunk_states;
-  if (backward && d->seqlen % kStateGranule != 0)
+  if (backward && d->seqlen % state_granule(d) != 0)
     w.total += (size_t)d->batch * d->heads * d->head_dim * d->head_dim * sizeof(float);
   return w;
 }
@@ -258,7 +259,7 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  const bool split = kv_final != nullptr && desc->seqlen % kStateGranule != 0;
+  const bool split = kv_final != nullptr && desc->seqlen % state_granule(desc) != 0;
   const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the block kernels process
   const Plan pl = make_plan(&blocks);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
@@ -275,8 +276,9 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = blocks.seqlen > 0 ? kv_final : kv_init;
   r.fin[0] = kv_final;
-  return la2::launch_recur(desc->head_dim, desc->dtype == LA2_BF16, desc->batch, 1, r, s) == hipSuccess
-             ? LA2_OK : LA2_ERR_LAUNCH;
+  const hipError_t e = desc->dtype == LA2_BF16 ? la2::launch_tail_bf16(desc->head_dim, desc->batch, r, s)
+                                               : la2::launch_recur(desc->head_dim, false, desc->batch, 1, r, s);
+  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
@@ -306,7 +308,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
     return LA2_ERR_STRIDE_ALIGN;
   // With a gradient coming in at the end of a sequence that does not end on a block boundary, the reverse
   // pass runs the tail token by token first and hands dKV to the block kernels through the workspace.
-  const bool split = d_kv_final != nullptr && desc->seqlen % kStateGranule != 0;
+  const bool split = d_kv_final != nullptr && desc->seqlen % state_granule(desc) != 0;
   const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the reverse block kernels process
   const Plan pl = make_plan(desc), pl_rev = make_plan(&blocks);
   const StateWorkspace sw = state_workspace(desc, true);
@@ -453,13 +455,21 @@ la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int3
     return LA2_ERR_STRIDE_ALIGN;
   la2_desc d;
   la2_desc_dense(&d, batch, heads, ntokens, head_dim, (la2_dtype)qkv_dtype);
+  // A run with at least one whole block goes through the block kernels (the state in place: a workgroup
+  // reads its chain's start state before it writes the final one) and only the rest token by token; they
+  // are 4-5x faster per position.  Not when that launch would be sequence-chunked: there is no workspace here.
+  const la2_desc wb = whole_blocks(&d);
+  if (wb.seqlen > 0 && make_plan(&wb).workspace == 0)
+    return la2_fwd_state(&d, q, k, v, lambda, kv_state, o, kv_state, nullptr, 0, hip_stream);
   la2::RecurParams r = recur_params(&d, lambda, 0, ntokens, false);
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = kv_state;
   r.fin[0] = kv_state;
-  return la2::launch_recur(head_dim, qkv_dtype == LA2_BF16, batch, 1, r, reinterpret_cast<hipStream_t>(hip_stream)) ==
-                 hipSuccess
-             ? LA2_OK : LA2_ERR_LAUNCH;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  // bf16: one block kernel launch (bf16 MFMA); fp32: token by token in fp32
+  const hipError_t e = qkv_dtype == LA2_BF16 ? la2::launch_tail_bf16(head_dim, batch, r, s)
+                                             : la2::launch_recur(head_dim, false, batch, 1, r, s);
+  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 const char* la2_status_string(la2_status status) {

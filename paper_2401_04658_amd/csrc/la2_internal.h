@@ -118,6 +118,9 @@ struct RecurParams {
   int64_t stride_b, stride_h, stride_n;  // elements, all of x, y, z, w
 };
 hipError_t launch_recur(int head_dim, bool bf16, int batch, int ninst, const RecurParams& p, hipStream_t s);
+// The forward case of the same for bf16 data (instance 0 only, reverse == 0) as a block kernel: bf16 MFMA in
+// blocks of 32 positions, the state after position t1 - 1 exact for any t1 - t0.  Needs t0 < t1.
+hipError_t launch_tail_bf16(int head_dim, int batch, const RecurParams& p, hipStream_t s);
 
 // Backward of the Norm epilogue, row by row: du = rstd * (g - o * mean_j(g_j o_j)) with o the normalised
 // output and g its gradient; o, g, du share the layout given by the strides (elements), rstd is

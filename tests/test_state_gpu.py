@@ -168,7 +168,7 @@ def test_sweep_points_with_states(point):
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("T", [1, 2, 7, 64])
+@pytest.mark.parametrize("T", [1, 2, 7, 32, 33, 64, 100])
 def test_decode_multi(dtype, d, T):
     b, H = 3, 4
     t = inputs(b, H, T, d, dtype, seed=1100 + T + d, lam=[0.5, 0.9, 0.99, 1.0])
