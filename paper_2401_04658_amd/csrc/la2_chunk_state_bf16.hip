@@ -9,12 +9,23 @@ using namespace bf16k;
 // Local state of every chunk that has a successor: forward sum_c lambda^(C-1-c) y_c^T z_c over the
 // chunk's positions c, reverse sum_c lambda^c y_c^T z_c.  Written fp32 row-major [dk][dv].  Same
 // streaming and the same state-update step as the scan kernel, without X, scores or outputs.
-template <int D, bool REV>
-__global__ __launch_bounds__(kThreads, 2) void chunk_state_bf16_kernel(ScanParams p) {
+//
+// A launch has about one workgroup per compute unit (it exists because the chains alone cannot fill the
+// device) and hardly any arithmetic, so its speed is the bytes a workgroup keeps in flight: NBUF tile
+// buffers, the tiles of block it + NBUF - 1 stream in while block it is used.  Every block's loads are
+// issued unconditionally (past the chunk's end as dummy loads of one cache line), so the count of
+// outstanding loads is the same in every iteration and one s_waitcnt immediate serves.
+template <int D, bool REV, int NBUF>
+__global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParams p) {
+  static_assert(NBUF >= 3 && NBUF <= 5, "the block loop below is unrolled for 3 to 5 buffers");
   using C = Cfg<D>;
   constexpr int NT = C::NT, TILE = C::TILE;
-  __shared__ __attribute__((aligned(1024))) __bf16 sT0[2][TILE];   // [Y, Z]
-  __shared__ __attribute__((aligned(1024))) __bf16 sT1[2][TILE];
+  using Loader = TileLoader<D, 2>;
+  __shared__ __attribute__((aligned(1024))) __bf16 sT[NBUF][2][TILE];   // [Y, Z]
+  constexpr int NDMA = 2 * Loader::DMA_PER_WAVE;   // direct loads per wave and block
+  constexpr int VM_YOUNGER = (NBUF - 2) * NDMA;    // loads younger than those of block it + 1 when it waits for them
+  static_assert(VM_YOUNGER < 64, "vmcnt is a 6-bit counter");
+  constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w % NT;
@@ -30,7 +41,7 @@ __global__ __launch_bounds__(kThreads, 2) void chunk_state_bf16_kernel(ScanParam
   const int blk_hi = min(blk_lo + cb, nblocks);
   const int nblk = blk_hi - blk_lo;
 
-  TileLoader<D, 2> loader(w, l, n, (uint32_t)p.stride_n);
+  Loader loader(w, l, n, (uint32_t)p.stride_n);
   loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
   loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
   const LaneAddr<D> la(l);
@@ -41,22 +52,27 @@ __global__ __launch_bounds__(kThreads, 2) void chunk_state_bf16_kernel(ScanParam
 #pragma unroll
   for (int t = 0; t < NT; t++) kv[t] = zero16();
 
-  if (nblk > 0) {
-    const int b0 = REV ? blk_hi - 1 : blk_lo;
-    loader.issue(sT0, b0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    loader.zero_tail(sT0, b0);
-  }
-  __syncthreads();
+  // loads of the chunk's block number `it` (real, or dummy when the chunk has no such block) into `buf`
+  auto issue_block = [&](__bf16 (*buf)[TILE], int it) __attribute__((always_inline)) {
+    uint32_t doff[Loader::DMA_PER_WAVE];
+    loader.offsets(REV ? blk_hi - 1 - it : blk_lo + it, it < nblk, doff);
+#pragma unroll
+    for (int j = 0; j < NDMA; j++) loader.issue_one(buf, doff, j);
+  };
+  if (nblk <= 0) return;
+#pragma unroll
+  for (int j = 0; j < NBUF - 1; j++) issue_block(sT[j], j);
+  __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);   // the first block's tiles
+  loader.zero_tail(sT[0], REV ? blk_hi - 1 : blk_lo);
+  lds_barrier();
 
-  auto block_step = [&](auto cur_tag, int it) {
+  auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
-    const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
     const bool has_next = it + 1 < nblk;
-    const int nb = REV ? blk - 1 : blk + 1;
-    if (has_next) loader.issue(cur ? sT0 : sT1, nb);
-    const __bf16* tY = cur ? sT1[0] : sT0[0];
-    const __bf16* tZ = cur ? sT1[1] : sT0[1];
+    const int nb = REV ? blk_hi - 2 - it : blk_lo + it + 1;
+    issue_block(sT[(cur + NBUF - 1) % NBUF], it + NBUF - 1);   // that buffer was block it - 1's
+    const __bf16* tY = sT[cur][0];
+    const __bf16* tZ = sT[cur][1];
     bf16x8 zf[4], yt[NT][4];   // [16-row k-step of the block]
 #pragma unroll
     for (int k = 0; k < 4; k++) {
@@ -76,15 +92,20 @@ __global__ __launch_bounds__(kThreads, 2) void chunk_state_bf16_kernel(ScanParam
       for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][k], zd, kv[t]);
     }
     if (has_next) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      loader.zero_tail(cur ? sT0 : sT1, nb);
-      lds_barrier();
+      __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
+      loader.zero_tail(sT[(cur + 1) % NBUF], nb);
+      lds_barrier();   // next tiles visible to all waves; this block's buffer free
     }
+    return has_next;
   };
-  for (int it = 0; it < nblk; it += 2) {
-    block_step(std::integral_constant<int, 0>{}, it);
-    if (it + 1 < nblk) block_step(std::integral_constant<int, 1>{}, it + 1);
+  for (int it = 0;; it += NBUF) {   // unrolled by the number of buffers: compile-time buffer index
+    if (!block_step(std::integral_constant<int, 0>{}, it)) break;
+    if (!block_step(std::integral_constant<int, 1>{}, it + 1)) break;
+    if (!block_step(std::integral_constant<int, 2 % NBUF>{}, it + 2)) break;
+    if (NBUF > 3 && !block_step(std::integral_constant<int, 3 % NBUF>{}, it + 3)) break;
+    if (NBUF > 4 && !block_step(std::integral_constant<int, 4 % NBUF>{}, it + 4)) break;
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy loads before the LDS is given up
 
   if (w < NT) {   // for d = 64 waves w and w + 2 hold the same slice
     float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
@@ -127,11 +148,11 @@ hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams
   if (grid == 0 || p.n == 0) return hipSuccess;
   dim3 g((unsigned)grid), b(kThreads);
   if (head_dim == 128) {
-    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<128, true>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<128, false>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<128, true, 4>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<128, false, 4>), g, b, 0, s, p);
   } else {
-    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<64, true>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<64, false>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<64, true, 4>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<64, false, 4>), g, b, 0, s, p);
   }
   return hipGetLastError();
 }

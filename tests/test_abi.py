@@ -243,3 +243,12 @@ def test_norm_entry_points_validate_before_any_launch(lib):
     d = dense(lib, 0, 2, 128, 64, binding.LA2_BF16)
     ref = ctypes.byref(d)
     assert fn(q=None, rstd=None) == OK and bn(o=None) == OK
+
+
+def test_header_is_plain_c_and_cxx():
+    """The boundary is a C ABI: the header compiles as C99 and as C++ without any HIP or torch header."""
+    import subprocess
+    for cmd in (["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c", HEADER],
+                ["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", HEADER]):
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert res.returncode == 0, res.stdout
