@@ -28,7 +28,9 @@
  *     pointer; pointers may then be NULL.
  *   - dtype LA2_BF16: bf16 storage, bf16 MFMA operands, fp32 accumulation and fp32 running state.
  *     dtype LA2_F32: fp32 storage and fp32 arithmetic throughout.
- *   - seqlen may be any value >= 0 (a ragged last block is masked); head_dim is 64 or 128.
+ *   - seqlen may be any value >= 0 (a ragged last block is masked) as long as one (batch, head) chain stays
+ *     addressable with 32-bit byte offsets: (seqlen + 128) * stride_n * sizeof(element) <= 2^32, else
+ *     LA2_ERR_SHAPE (dense bf16, head_dim 128: up to 16,777,088 positions).  head_dim is 64 or 128.
  *   - Argument errors are detected on the host BEFORE anything is launched and are reported through
  *     the return code; nothing aborts.  A failed launch is reported as LA2_ERR_LAUNCH.
  */

@@ -37,8 +37,10 @@ la2_status check_desc(const la2_desc* d) {
   const int64_t per16 = 16 / elem_size(d->dtype);
   if (d->stride_b < 0 || d->stride_h < 0 || d->stride_n < d->head_dim) return LA2_ERR_STRIDE_ALIGN;
   if (d->stride_b % per16 || d->stride_h % per16 || d->stride_n % per16) return LA2_ERR_STRIDE_ALIGN;
-  // the kernels address one chain with 32-bit byte offsets
-  if ((int64_t)d->seqlen * d->stride_n * elem_size(d->dtype) >= ((int64_t)1 << 32)) return LA2_ERR_SHAPE;
+  // The kernels address one chain with 32-bit byte offsets.  The rows of a ragged last block (up to 127
+  // positions past the end in the widest kernel) are computed and then dropped by the store's range check,
+  // so their offsets must not wrap around either.
+  if (((int64_t)d->seqlen + 128) * d->stride_n * elem_size(d->dtype) > ((int64_t)1 << 32)) return LA2_ERR_SHAPE;
   return LA2_OK;
 }
 

@@ -252,3 +252,15 @@ def test_header_is_plain_c_and_cxx():
                 ["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", HEADER]):
         res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         assert res.returncode == 0, res.stdout
+
+
+def test_chain_span_limit(lib):
+    """One chain must stay addressable with 32-bit byte offsets, ragged last block included."""
+    d = dense(lib, 1, 1, (1 << 24) - 127, 128, binding.LA2_BF16)     # one position too many
+    assert fwd(lib, d) == E_SHAPE and bwd(lib, d) == E_SHAPE
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 0
+    d = dense(lib, 1, 1, (1 << 23) - 127, 128, binding.LA2_F32)
+    assert fwd(lib, d) == E_SHAPE
+    d = dense(lib, 4, 1, 200000, 64, binding.LA2_BF16)               # [b, n, H, d] storage with a large row pitch
+    d.stride_n = 16384
+    assert fwd(lib, d) == E_SHAPE

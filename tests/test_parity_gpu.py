@@ -159,6 +159,49 @@ def test_empty_and_degenerate():
     assert binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"]).numel() == 0
 
 
+def test_longest_sequence_one_chain_spans_4_gib():
+    """Close to the longest sequence the descriptor allows for head_dim 128 in bf16: one chain of 16,777,087
+    positions, just short of 4 GiB (the kernels address a chain with 32-bit byte offsets), cut into about 256
+    chunks, ragged at the end.  Constant inputs and lambda = 1/2: contributions from more than 160 positions away are
+    below 2^-160, so every row equals a row of the oracle's result on a 160-position window."""
+    n, d, win = (1 << 24) - 129, 128, 160
+    c = 0.25
+    x = torch.full((1, 1, n, d), c, dtype=torch.bfloat16, device=DEV)
+    lam = torch.tensor([0.5], dtype=torch.float32, device=DEV)
+    w64 = np.full((1, 1, win, d), c)
+    ref_o = oracle.fwd_direct(w64, w64, w64, 0.5)[0, 0]
+    ref_dq, ref_dk, ref_dv = (r[0, 0] for r in oracle.bwd_direct(w64, w64, w64, w64, 0.5))
+    tol = TOL[torch.bfloat16]
+
+    def check(name, got, ref, forward):
+        got = got[0, 0]
+        scale = float(np.max(np.abs(ref)))
+        if forward:   # the first rows, then the steady state
+            head, steady, rest = got[:win], ref[win - 1], got[win - 1:]
+            edge_ref = ref
+        else:         # the last rows (aligned at the end), and the steady state before them
+            head, steady, rest = got[n - win:], ref[0], got[:n - win + 1]
+            edge_ref = ref
+        assert np.max(np.abs(to64(head) - edge_ref)) <= tol * scale, name + " edge rows"
+        steady_t = torch.as_tensor(steady, dtype=torch.float32, device=DEV)
+        err = (rest.float() - steady_t).abs().max().item()
+        assert err <= tol * scale, "%s steady state: %.3e" % (name, err / scale)
+
+    o = binding.la2_fwd(x, x, x, lam)
+    torch.cuda.synchronize()
+    check("o", o, ref_o, True)
+    del o
+    dq, dk, dv = binding.la2_bwd(x, x, x, x, lam)
+    torch.cuda.synchronize()
+    check("dq", dq, ref_dq, True)
+    check("dk", dk, ref_dk, False)
+    check("dv", dv, ref_dv, False)
+    # two more positions do not fit the 32-bit chain offsets: refused on the host
+    y = torch.empty((1, 1, n + 2, d), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(binding.LA2Error):
+        binding.la2_fwd(y, y, y, lam)
+
+
 def test_extreme_decays():
     """lambda = 1 (pure causal prefix sum) and a very small lambda (only the diagonal survives)."""
     for dtype in (torch.bfloat16, torch.float32):
