@@ -75,6 +75,12 @@ Plan make_plan(const la2_desc* d) {
     const int want = (int)((cus + chains - 1) / chains);
     cb = (nblocks + want - 1) / want;
     if (cb < 4) cb = 4;  // keep the state pre-pass a small fraction of the work
+    if (cb >= nblocks) return pl;
+    // Chunking shortens the scan's sequential loop from nblocks to cb blocks but adds the pre-pass (about a
+    // third of a scan block per block) and two more launches (about 15 us): not worth it for short sequences.
+    // Measured times of one block of the sequential loop, in microseconds.
+    const float t_blk = d->dtype == LA2_BF16 ? (d->head_dim == 128 ? 2.1f : 1.15f) : (d->head_dim == 128 ? 10.f : 3.f);
+    if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) return pl;
   }
   if (cb >= nblocks) return pl;
   pl.nchunks = (nblocks + cb - 1) / cb;
