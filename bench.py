@@ -227,6 +227,17 @@ def main():
                        "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1),
                        "plain_fwd_ms": round(pf_ms, 4), "plain_bwd_ms": round(pb_ms, 4)})
         del rstd, d_u
+    # the same point in the library's other two data types (fp16: the same kernels as bf16; fp32: fp32 MFMA)
+    other_dtypes = []
+    wl1 = workloads.CONFIG3[1]
+    for dt, tag in ((torch.float16, "f16"), (torch.float32, "f32")):
+        wl_d = workloads.Workload(wl1.name + "_" + tag, wl1.batch, wl1.heads, wl1.seqlen, wl1.head_dim, dt, seed=wl1.seed)
+        g_d = stage(wl_d)
+        f_ms = time_ms(lambda: fwd(g_d), iters, warm=10)
+        b_ms = time_ms(lambda: bwd(g_d), iters, warm=10)
+        other_dtypes.append({"workload": wl_d.name, "dtype": tag, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                             "tokens_per_s": round(wl_d.tokens / ((f_ms + b_ms) * 1e-3), 1)})
+        del g_d
     # the forward pass as the O(n^2 d) masked left product (comparison kernel) against the block recurrence
     crossover = []
     short = [(wl_, stage(wl_)) for wl_ in (workloads.Workload("config3_like_b%d_n%d_h16_d128" % (b_, n_), b_, 16, n_, 128,
@@ -339,6 +350,7 @@ def main():
         "state_handover": with_states,
         "saved_forward_states": saved,
         "normalised_operator": normed,
+        "other_dtypes": other_dtypes,
         "left_product_comparison": crossover,
         "decode": decode,
         "roofline": roofline,

@@ -26,7 +26,8 @@
  *   - Outputs are fully overwritten.  Outputs must not alias inputs or each other.
  *   - An empty problem (batch, heads or seqlen equal to 0) returns LA2_OK without touching any
  *     pointer; pointers may then be NULL.
- *   - dtype LA2_BF16: bf16 storage, bf16 MFMA operands, fp32 accumulation and fp32 running state.
+ *   - dtype LA2_BF16 / LA2_F16: bf16 / fp16 storage and MFMA operands, fp32 accumulation and fp32 running
+ *     state (fp16: the masked scores and the state, as matrix operands, must stay within the fp16 range).
  *     dtype LA2_F32: fp32 storage and fp32 arithmetic throughout.
  *   - seqlen may be any value >= 0 (a ragged last block is masked) as long as one (batch, head) chain stays
  *     addressable with 32-bit byte offsets: (seqlen + 128) * stride_n * sizeof(element) <= 2^32, else
@@ -48,14 +49,14 @@ typedef enum {
   LA2_OK = 0,
   LA2_ERR_NULL = 1,         /* a required pointer is NULL                                   */
   LA2_ERR_SHAPE = 2,        /* negative size, unsupported head_dim, or index range overflow */
-  LA2_ERR_DTYPE = 3,        /* dtype is neither LA2_F32 nor LA2_BF16                        */
+  LA2_ERR_DTYPE = 3,        /* dtype is not a la2_dtype (or not one this entry point takes) */
   LA2_ERR_STRIDE_ALIGN = 4, /* pointer or stride not 16-byte aligned, or rows overlap       */
   LA2_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than la2_workspace_bytes()         */
   LA2_ERR_LAUNCH = 6,       /* the HIP runtime refused a launch                             */
   LA2_ERR_VALUE = 7         /* a scalar argument is out of range (eps negative or not finite) */
 } la2_status;
 
-typedef enum { LA2_F32 = 0, LA2_BF16 = 1 } la2_dtype;
+typedef enum { LA2_F32 = 0, LA2_BF16 = 1, LA2_F16 = 2 } la2_dtype;
 
 typedef enum { LA2_OP_FWD = 0, LA2_OP_BWD = 1, LA2_OP_FWD_STATE = 2, LA2_OP_BWD_STATE = 3 } la2_op;
 

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libla2.so")
 _lib = None
 
-LA2_F32, LA2_BF16 = 0, 1
+LA2_F32, LA2_BF16, LA2_F16 = 0, 1, 2
 LA2_OP_FWD, LA2_OP_BWD, LA2_OP_FWD_STATE, LA2_OP_BWD_STATE = 0, 1, 2, 3
 
 
@@ -91,9 +91,11 @@ def _check(code):
 def _dtype_code(t):
     if t.dtype == torch.bfloat16:
         return LA2_BF16
+    if t.dtype == torch.float16:
+        return LA2_F16
     if t.dtype == torch.float32:
         return LA2_F32
-    raise TypeError("la2: dtype must be torch.bfloat16 or torch.float32, got %s" % t.dtype)
+    raise TypeError("la2: dtype must be torch.bfloat16, torch.float16 or torch.float32, got %s" % t.dtype)
 
 
 def make_desc(t):

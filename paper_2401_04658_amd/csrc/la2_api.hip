@@ -10,8 +10,9 @@ namespace {
 int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
 int g_scan_variant = 0;           // la2_set_scan_variant()
 // The block kernels form states after whole blocks only: 32 positions for the kernels that take states
-// (half-block bf16 kernel for head_dim 128, fp32 kernels), 64 for the full-block bf16 kernel of head_dim 64.
-int state_granule(const la2_desc* d) { return (d->dtype == LA2_BF16 && d->head_dim == 64) ? 64 : 32; }
+// (half-block 16-bit kernel for head_dim 128, fp32 kernels), 64 for the full-block 16-bit kernel of head_dim 64.
+bool is16(int dtype) { return dtype == LA2_BF16 || dtype == LA2_F16; }
+int state_granule(const la2_desc* d) { return (is16(d->dtype) && d->head_dim == 64) ? 64 : 32; }
 
 int device_cu_count() {
   static int cached = 0;
@@ -26,11 +27,11 @@ int device_cu_count() {
   return 256;  // MI355X; used when no device is visible (host-only callers sizing a workspace)
 }
 
-int elem_size(int dtype) { return dtype == LA2_BF16 ? 2 : 4; }
+int elem_size(int dtype) { return dtype == LA2_F32 ? 4 : 2; }
 
 la2_status check_desc(const la2_desc* d) {
   if (d == nullptr) return LA2_ERR_NULL;
-  if (d->dtype != LA2_F32 && d->dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (d->dtype != LA2_F32 && !is16(d->dtype)) return LA2_ERR_DTYPE;
   if (d->batch < 0 || d->heads < 0 || d->seqlen < 0 || d->reserved != 0) return LA2_ERR_SHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return LA2_ERR_SHAPE;
   if ((int64_t)d->batch * d->heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
@@ -49,7 +50,7 @@ bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p
 // Granularity of the sequence chunks (the block size of the chunk-state pre-pass; a multiple of every
 // scan kernel's block size).
 int block_size(const la2_desc* d) {
-  return d->dtype == LA2_BF16 ? la2::block_size_bf16(d->head_dim) : la2::block_size_f32(d->head_dim);
+  return is16(d->dtype) ? la2::block_size_bf16(d->head_dim) : la2::block_size_f32(d->head_dim);
 }
 
 struct Plan {
@@ -79,7 +80,7 @@ Plan make_plan(const la2_desc* d) {
     // Chunking shortens the scan's sequential loop from nblocks to cb blocks but adds the pre-pass (about a
     // third of a scan block per block) and two more launches (about 15 us): not worth it for short sequences.
     // Measured times of one block of the sequential loop, in microseconds.
-    const float t_blk = d->dtype == LA2_BF16 ? (d->head_dim == 128 ? 2.1f : 1.15f) : (d->head_dim == 128 ? 10.f : 3.f);
+    const float t_blk = is16(d->dtype) ? (d->head_dim == 128 ? 2.1f : 1.15f) : (d->head_dim == 128 ? 10.f : 3.f);
     if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) return pl;
   }
   if (cb >= nblocks) return pl;
@@ -127,8 +128,7 @@ la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const vo
   la2::ScanParams p = base_params(d, pl, lambda, workspace);
   p.y[0] = y; p.z[0] = z;
   p.init[0] = init; p.init_transposed = init_tr ? 1 : 0;
-  const bool bf16 = d->dtype == LA2_BF16;
-  hipError_t e = bf16 ? la2::launch_chunk_states_bf16(d->head_dim, reverse, p, s)
+  hipError_t e = is16(d->dtype) ? la2::launch_chunk_states_bf16(d->dtype, d->head_dim, reverse, p, s)
                       : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
   if (e != hipSuccess) return LA2_ERR_LAUNCH;
   e = la2::launch_state_scan(d->head_dim, reverse, p, s);
@@ -152,13 +152,13 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
   p.fin[0] = a.fin;
   p.rstd = a.rstd;
   p.eps = a.eps;
-  const bool bf16 = d->dtype == LA2_BF16;
-  hipError_t e = bf16 ? la2::launch_scan_bf16(d->head_dim, reverse, p, s) : la2::launch_scan_f32(d->head_dim, reverse, p, s);
+  hipError_t e = is16(d->dtype) ? la2::launch_scan_bf16(d->dtype, d->head_dim, reverse, p, s)
+                                : la2::launch_scan_f32(d->head_dim, reverse, p, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 // Two reverse scans whose states are transposes of each other (scan 1's y, z are scan 0's z, y): one
-// state pre-pass, one launch (bf16 path).
+// state pre-pass, one launch (16-bit path).
 la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanArgs& a0, const ScanArgs& a1,
                                  const float* lambda, void* workspace, hipStream_t s) {
   la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s);
@@ -171,7 +171,7 @@ la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanAr
   p.fin[0] = a0.fin; p.fin[1] = a1.fin;
   p.x[0] = a0.x; p.y[0] = a0.y; p.z[0] = a0.z; p.w[0] = a0.w;
   p.x[1] = a1.x; p.y[1] = a1.y; p.z[1] = a1.z; p.w[1] = a1.w;
-  return la2::launch_scan_bf16(d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  return la2::launch_scan_bf16(d->dtype, d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 // The state entry points split a sequence whose length is not a multiple of state_granule() into whole
@@ -241,8 +241,8 @@ size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
 
 int32_t la2_block_size(const la2_desc* desc) {
   if (check_desc(desc) != LA2_OK) return 0;
-  // bf16, head_dim 128: the half-block scan kernel unless the full-block one is forced
-  if (desc->dtype == LA2_BF16 && desc->head_dim == 128 && g_scan_variant != 1) return 32;
+  // 16-bit, head_dim 128: the half-block scan kernel unless the full-block one is forced
+  if (is16(desc->dtype) && desc->head_dim == 128 && g_scan_variant != 1) return 32;
   return block_size(desc);
 }
 
@@ -284,8 +284,8 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = blocks.seqlen > 0 ? kv_final : kv_init;
   r.fin[0] = kv_final;
-  const hipError_t e = desc->dtype == LA2_BF16 ? la2::launch_tail_bf16(desc->head_dim, desc->batch, r, s)
-                                               : la2::launch_recur(desc->head_dim, false, desc->batch, 1, r, s);
+  const hipError_t e = is16(desc->dtype) ? la2::launch_tail_bf16(desc->dtype, desc->head_dim, desc->batch, r, s)
+                                         : la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
@@ -346,7 +346,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
     r.init[0] = d_kv_final; r.init[1] = d_kv_final;
     r.init_transposed = 2;
     r.fin[0] = blocks.seqlen > 0 ? handoff : d_kv_init;
-    if (la2::launch_recur(desc->head_dim, desc->dtype == LA2_BF16, desc->batch, 2, r, s) != hipSuccess)
+    if (la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 2, r, s) != hipSuccess)
       return LA2_ERR_LAUNCH;
     if (blocks.seqlen == 0) return LA2_OK;
     rev_init = handoff;
@@ -356,7 +356,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   for_dv.fin = d_kv_init;
   for_dk.init = rev_init;
   for_dk.init_tr = true;
-  if (desc->dtype == LA2_BF16) return run_dual_reverse_scan(&blocks, pl_rev, for_dv, for_dk, lambda, workspace, s);
+  if (is16(desc->dtype)) return run_dual_reverse_scan(&blocks, pl_rev, for_dv, for_dk, lambda, workspace, s);
   st = run_scan(&blocks, pl_rev, true, for_dv, lambda, workspace, s);
   if (st != LA2_OK) return st;
   return run_scan(&blocks, pl_rev, true, for_dk, lambda, workspace, s);
@@ -412,7 +412,7 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
     return LA2_ERR_WORKSPACE;
   la2::NormBwdParams np{o, d_o, rstd, d_u, desc->stride_b, desc->stride_h, desc->stride_n,
                         desc->batch, desc->heads, desc->seqlen};
-  if (la2::launch_norm_bwd_rows(desc->head_dim, desc->dtype == LA2_BF16, np,
+  if (la2::launch_norm_bwd_rows(desc->head_dim, desc->dtype, np,
                                 reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return LA2_ERR_LAUNCH;
   return la2_bwd(desc, q, k, v, d_u, lambda, dq, dk, dv, workspace, workspace_bytes, hip_stream);
@@ -437,7 +437,7 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
                            const void* k, const void* v, const float* lambda, float* kv_state, void* o,
                            void* hip_stream) {
-  if (qkv_dtype != LA2_F32 && qkv_dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (qkv_dtype != LA2_F32 && !is16(qkv_dtype)) return LA2_ERR_DTYPE;
   if (batch < 0 || heads < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads == 0) return LA2_OK;  // nothing to do
@@ -445,7 +445,7 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(kv_state, 16) ||
       !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  hipError_t e = la2::launch_decode(batch, heads, head_dim, qkv_dtype == LA2_BF16, q, k, v, lambda, kv_state, o,
+  hipError_t e = la2::launch_decode(batch, heads, head_dim, qkv_dtype, q, k, v, lambda, kv_state, o,
                                     reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
@@ -453,7 +453,7 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
 la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,
                             const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
                             void* o, void* hip_stream) {
-  if (qkv_dtype != LA2_F32 && qkv_dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (qkv_dtype != LA2_F32 && !is16(qkv_dtype)) return LA2_ERR_DTYPE;
   if (batch < 0 || heads < 0 || ntokens < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24 || ntokens > 65536) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads * ntokens == 0) return LA2_OK;  // nothing to do
@@ -474,9 +474,9 @@ la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int3
   r.init[0] = kv_state;
   r.fin[0] = kv_state;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  // bf16: one block kernel launch (bf16 MFMA); fp32: token by token in fp32
-  const hipError_t e = qkv_dtype == LA2_BF16 ? la2::launch_tail_bf16(head_dim, batch, r, s)
-                                             : la2::launch_recur(head_dim, false, batch, 1, r, s);
+  // 16-bit data: one block kernel launch (MFMA); fp32: token by token in fp32
+  const hipError_t e = is16(qkv_dtype) ? la2::launch_tail_bf16(qkv_dtype, head_dim, batch, r, s)
+                                       : la2::launch_recur(head_dim, qkv_dtype, batch, 1, r, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 

@@ -1,4 +1,4 @@
-// Shared pieces of the bf16 MFMA kernels (gfx950): vector types, MFMA and LDS helpers, the swizzled tile
+// Shared pieces of the 16-bit (bf16 / fp16) MFMA kernels (gfx950): vector types, MFMA and LDS helpers, the swizzled tile
 // layout, direct HBM -> LDS tile loads, the state <-> accumulator mapping and the update weights.
 //
 // The scan kernels: one workgroup (4 waves) walks the blocks (B = 64 positions) of one sequence chunk of one
@@ -42,8 +42,10 @@ namespace la2 {
 namespace bf16k {
 
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+// 16-bit element types: __bf16 (LA2_BF16) and _Float16 (LA2_F16).  Every kernel is a template over the
+// element type E; only the conversions to and from fp32 and the MFMA instruction depend on it.
+template <typename E> using ex8 = E __attribute__((ext_vector_type(8)));
+template <typename E> using ex4 = E __attribute__((ext_vector_type(4)));
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
@@ -67,8 +69,11 @@ struct Cfg {
                                                // XOR-swizzled by (row / 4) % 4 (LDS is full: no room for padding)
 };
 
-__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+__device__ __forceinline__ f32x16 mfma(ex8<__bf16> a, ex8<__bf16> b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma(ex8<_Float16> a, ex8<_Float16> b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
 // 2^x for x <= 0 with the bare hardware instruction (no denormal-range fix-up: results below
@@ -91,7 +96,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // Transposing LDS read.  Within each group of 16 lanes, lane s passes the address of 4 consecutive
 // elements of row (s / 4), columns 4 (s % 4) .. +3 of a 4 x 16 sub-matrix; lane s receives the 4
 // rows of column s.
-__device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
+__device__ __forceinline__ s16x4 lds_read_tr(const void* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
 }
 
@@ -139,8 +144,10 @@ __device__ __forceinline__ uint32_t lds_offset(const void* p) {
 // Exchange between lanes l and l + 32 that turns a row fragment in natural k-order (this lane holds
 // features 8 hh .. 8 hh + 7 of a 16-wide k-step) into permuted k-order (features 4 hh .. 4 hh + 3 and
 // 8 + 4 hh .. 8 + 4 hh + 3).  v_permlane32_swap(a, b): lanes >= 32 of a <-> lanes < 32 of b.
-__device__ __forceinline__ bf16x8 to_perm_order(bf16x8 f) {
-  union { bf16x8 v; u32x4 u; } x;
+template <typename V>
+__device__ __forceinline__ V to_perm_order(V f) {
+  static_assert(sizeof(V) == 16, "eight 16-bit elements");
+  union { V v; u32x4 u; } x;
   x.v = f;
   const u32x2 s0 = __builtin_amdgcn_permlane32_swap(x.u[0], x.u[2], false, false);
   const u32x2 s1 = __builtin_amdgcn_permlane32_swap(x.u[1], x.u[3], false, false);
@@ -185,15 +192,17 @@ struct LaneAddr {
   }
   // Fragment for a contraction over the 16 tile rows c0 .. c0 + 15 (c0 % 16 == 0) in permuted
   // k-order, for column 32 t + l32: element j of lane (l32, hh) is row c0 + perm(0, hh, j).
-  __device__ __forceinline__ bf16x8 read_cols(const __bf16* tile, int c0, int t) const {
-    union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
+  template <typename E>
+  __device__ __forceinline__ ex8<E> read_cols(const E* tile, int c0, int t) const {
+    union { struct { s16x4 lo, hi; } s; ex8<E> v; } u;
     u.s.lo = lds_read_tr(tile + c0 * D + (tr0 ^ (32 * t)));
     u.s.hi = lds_read_tr(tile + c0 * D + (tr1 ^ (32 * t)));
     return u.v;
   }
   // Row fragment in natural k-order: features 16 ks + 8 hh .. + 7 of row 32 t + l32.
-  __device__ __forceinline__ bf16x8 read_row(const __bf16* tile, int t, int ks) const {
-    return *reinterpret_cast<const bf16x8*>(tile + 32 * t * D + (rowk ^ (16 * ks)));
+  template <typename E>
+  __device__ __forceinline__ ex8<E> read_row(const E* tile, int t, int ks) const {
+    return *reinterpret_cast<const ex8<E>*>(tile + 32 * t * D + (rowk ^ (16 * ks)));
   }
 };
 
@@ -219,7 +228,8 @@ struct TileLoader {
       col[i] = 8 * ((q % C::CPR) ^ swz<D>(q / C::CPR));
     }
   }
-  __device__ __forceinline__ void issue(__bf16 (*sT)[C::TILE], int blk) const {
+  template <typename E>
+  __device__ __forceinline__ void issue(E (*sT)[C::TILE], int blk) const {
 #pragma unroll
     for (int i = 0; i < DMA_PER_WAVE; i++) {
       const int pos = min(blk * B + row[i], n - 1);   // rows past the end are re-zeroed by zero_tail
@@ -241,14 +251,15 @@ struct TileLoader {
       off[i] = valid ? ((uint32_t)pos * stride_n + (uint32_t)col[i]) * 2u : 0u;
     }
   }
-  __device__ __forceinline__ void issue_one(__bf16 (*sT)[C::TILE], const uint32_t (&off)[DMA_PER_WAVE],
-                                            int j) const {
+  template <typename E>
+  __device__ __forceinline__ void issue_one(E (*sT)[C::TILE], const uint32_t (&off)[DMA_PER_WAVE], int j) const {
     const int i = j / NTILES, t = j % NTILES;
     // LDS address = tile base (a constant once the buffer index is one) + scalar wave offset
     dma16(g[t], off[i], lds_offset(&sT[t][0]) + wave_lds + 1024u * i);
   }
   // after this wave's loads have landed: zero the rows of a ragged last block
-  __device__ __forceinline__ void zero_tail(__bf16 (*sT)[C::TILE], int blk) const {
+  template <typename E>
+  __device__ __forceinline__ void zero_tail(E (*sT)[C::TILE], int blk) const {
     if ((blk + 1) * B > n) {
 #pragma unroll
       for (int i = 0; i < DMA_PER_WAVE; i++) {
@@ -294,11 +305,12 @@ struct UpdateDecay {
       gj[j] = uniform(exp2f(l2 * (float)(REV ? nj : 11 - nj)));
     }
   }
-  __device__ __forceinline__ bf16x8 apply(bf16x8 z, int c0) const {
+  template <typename E>
+  __device__ __forceinline__ ex8<E> apply(ex8<E> z, int c0) const {
     const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh + 1 : B - 16 - c0 + 4 * (1 - hh)));
-    bf16x8 r;
+    ex8<E> r;
 #pragma unroll
-    for (int j = 0; j < 8; j++) r[j] = (__bf16)((float)z[j] * (step * gj[j]));
+    for (int j = 0; j < 8; j++) r[j] = (E)((float)z[j] * (step * gj[j]));
     return r;
   }
 };
@@ -306,8 +318,8 @@ struct UpdateDecay {
 }  // namespace bf16k
 
 // per-kernel launchers (one translation unit each); launch_scan_bf16 picks among the first two
-hipError_t launch_scan_bf16_full(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
-hipError_t launch_scan_bf16_half(bool reverse, bool twin, const ScanParams& p, hipStream_t s);
+hipError_t launch_scan_bf16_full(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+hipError_t launch_scan_bf16_half(int dtype, bool reverse, bool twin, const ScanParams& p, hipStream_t s);
 
 }  // namespace la2
 #endif

@@ -15,13 +15,13 @@ using namespace bf16k;
 // buffers, the tiles of block it + NBUF - 1 stream in while block it is used.  Every block's loads are
 // issued unconditionally (past the chunk's end as dummy loads of one cache line), so the count of
 // outstanding loads is the same in every iteration and one s_waitcnt immediate serves.
-template <int D, bool REV, int NBUF>
+template <typename E, int D, bool REV, int NBUF>
 __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParams p) {
   static_assert(NBUF >= 3 && NBUF <= 5, "the block loop below is unrolled for 3 to 5 buffers");
   using C = Cfg<D>;
   constexpr int NT = C::NT, TILE = C::TILE;
   using Loader = TileLoader<D, 2>;
-  __shared__ __attribute__((aligned(1024))) __bf16 sT[NBUF][2][TILE];   // [Y, Z]
+  __shared__ __attribute__((aligned(1024))) E sT[NBUF][2][TILE];   // [Y, Z]
   constexpr int NDMA = 2 * Loader::DMA_PER_WAVE;   // direct loads per wave and block
   constexpr int VM_YOUNGER = (NBUF - 2) * NDMA;    // loads younger than those of block it + 1 when it waits for them
   static_assert(VM_YOUNGER < 64, "vmcnt is a 6-bit counter");
@@ -42,8 +42,8 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   const int nblk = blk_hi - blk_lo;
 
   Loader loader(w, l, n, (uint32_t)p.stride_n);
-  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
-  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
+  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
+  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
   const LaneAddr<D> la(l);
   const UpdateDecay<REV> decay(l2, hh);
   const float lamB = exp2f(l2 * (float)kB);
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   for (int t = 0; t < NT; t++) kv[t] = zero16();
 
   // loads of the chunk's block number `it` (real, or dummy when the chunk has no such block) into `buf`
-  auto issue_block = [&](__bf16 (*buf)[TILE], int it) __attribute__((always_inline)) {
+  auto issue_block = [&](E (*buf)[TILE], int it) __attribute__((always_inline)) {
     uint32_t doff[Loader::DMA_PER_WAVE];
     loader.offsets(REV ? blk_hi - 1 - it : blk_lo + it, it < nblk, doff);
 #pragma unroll
@@ -71,9 +71,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
     const bool has_next = it + 1 < nblk;
     const int nb = REV ? blk_hi - 2 - it : blk_lo + it + 1;
     issue_block(sT[(cur + NBUF - 1) % NBUF], it + NBUF - 1);   // that buffer was block it - 1's
-    const __bf16* tY = sT[cur][0];
-    const __bf16* tZ = sT[cur][1];
-    bf16x8 zf[4], yt[NT][4];   // [16-row k-step of the block]
+    const E* tY = sT[cur][0];
+    const E* tZ = sT[cur][1];
+    ex8<E> zf[4], yt[NT][4];   // [16-row k-step of the block]
 #pragma unroll
     for (int k = 0; k < 4; k++) {
       zf[k] = la.read_cols(tZ, 16 * k, dvt);
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
       for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-      const bf16x8 zd = decay.apply(zf[k], 16 * k);
+      const ex8<E> zd = decay.apply(zf[k], 16 * k);
 #pragma unroll
       for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][k], zd, kv[t]);
     }
@@ -143,18 +143,27 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
 
 }  // namespace
 
-hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+namespace {
+template <typename E>
+hipError_t launch_chunk_states(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks;
-  if (grid == 0 || p.n == 0) return hipSuccess;
   dim3 g((unsigned)grid), b(kThreads);
   if (head_dim == 128) {
-    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<128, true, 4>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<128, false, 4>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, true, 4>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, false, 4>), g, b, 0, s, p);
   } else {
-    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<64, true, 4>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<64, false, 4>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 64, true, 4>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 64, false, 4>), g, b, 0, s, p);
   }
   return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_chunk_states_bf16(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks;
+  if (grid == 0 || p.n == 0) return hipSuccess;
+  return dtype == kF16 ? launch_chunk_states<_Float16>(head_dim, reverse, p, s)
+                       : launch_chunk_states<__bf16>(head_dim, reverse, p, s);
 }
 
 hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {

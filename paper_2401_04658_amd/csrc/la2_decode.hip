@@ -14,13 +14,21 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <bool BF16>
+// element i of a tensor of type DT (kF32, kBF16 or kF16) as fp32, and the store that goes with it
+template <int DT>
 __device__ __forceinline__ float load_elem(const void* p, int64_t i) {
-  if (BF16) return (float)reinterpret_cast<const __bf16*>(p)[i];
+  if (DT == kBF16) return (float)reinterpret_cast<const __bf16*>(p)[i];
+  if (DT == kF16) return (float)reinterpret_cast<const _Float16*>(p)[i];
   return reinterpret_cast<const float*>(p)[i];
 }
+template <int DT>
+__device__ __forceinline__ void store_elem(void* p, int64_t i, float x) {
+  if (DT == kBF16) reinterpret_cast<__bf16*>(p)[i] = (__bf16)x;
+  else if (DT == kF16) reinterpret_cast<_Float16*>(p)[i] = (_Float16)x;
+  else reinterpret_cast<float*>(p)[i] = x;
+}
 
-template <int D, bool BF16>
+template <int D, int DT>
 __global__ __launch_bounds__(kThreads) void decode_kernel(const void* q, const void* k, const void* v,
                                                           const float* lambda, float* kv, void* o, int heads) {
   constexpr int TPR = D / 4;            // threads per state row (float4 each)
@@ -33,9 +41,9 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const void* q, const v
   const int64_t chain = blockIdx.x;
   const float lam = lambda[chain % heads];
   if (tid < D) {
-    sq[tid] = load_elem<BF16>(q, chain * D + tid);
-    sk[tid] = load_elem<BF16>(k, chain * D + tid);
-    sv[tid] = load_elem<BF16>(v, chain * D + tid);
+    sq[tid] = load_elem<DT>(q, chain * D + tid);
+    sk[tid] = load_elem<DT>(k, chain * D + tid);
+    sv[tid] = load_elem<DT>(v, chain * D + tid);
   }
   const int cg = tid % TPR, rg = tid / TPR;
   float4* state = reinterpret_cast<float4*>(kv + chain * (int64_t)(D * D));
@@ -71,8 +79,7 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const void* q, const v
     float sum = 0.f;
 #pragma unroll
     for (int g = 0; g < RG; g++) sum += flat[g * D + tid];
-    if (BF16) reinterpret_cast<__bf16*>(o)[chain * D + tid] = (__bf16)sum;
-    else reinterpret_cast<float*>(o)[chain * D + tid] = sum;
+    store_elem<DT>(o, chain * D + tid, sum);
   }
 }
 
@@ -89,18 +96,22 @@ hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStr
   return hipGetLastError();
 }
 
-hipError_t launch_decode(int batch, int heads, int head_dim, bool bf16, const void* q, const void* k,
+hipError_t launch_decode(int batch, int heads, int head_dim, int dtype, const void* q, const void* k,
                          const void* v, const float* lambda, float* kv, void* o, hipStream_t s) {
   const int64_t chains = (int64_t)batch * heads;
   if (chains == 0) return hipSuccess;
   dim3 g((unsigned)chains), b(kThreads);
+#define LA2_LAUNCH_DECODE(D, DT) hipLaunchKernelGGL((decode_kernel<D, DT>), g, b, 0, s, q, k, v, lambda, kv, o, heads)
   if (head_dim == 128) {
-    if (bf16) hipLaunchKernelGGL((decode_kernel<128, true>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
-    else      hipLaunchKernelGGL((decode_kernel<128, false>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
+    if (dtype == kBF16) LA2_LAUNCH_DECODE(128, kBF16);
+    else if (dtype == kF16) LA2_LAUNCH_DECODE(128, kF16);
+    else LA2_LAUNCH_DECODE(128, kF32);
   } else {
-    if (bf16) hipLaunchKernelGGL((decode_kernel<64, true>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
-    else      hipLaunchKernelGGL((decode_kernel<64, false>), g, b, 0, s, q, k, v, lambda, kv, o, heads);
+    if (dtype == kBF16) LA2_LAUNCH_DECODE(64, kBF16);
+    else if (dtype == kF16) LA2_LAUNCH_DECODE(64, kF16);
+    else LA2_LAUNCH_DECODE(64, kF32);
   }
+#undef LA2_LAUNCH_DECODE
   return hipGetLastError();
 }
 

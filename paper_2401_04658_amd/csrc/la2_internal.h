@@ -7,6 +7,9 @@
 
 namespace la2 {
 
+// element types of the sequence tensors (the values of la2_dtype)
+enum { kF32 = 0, kBF16 = 1, kF16 = 2 };
+
 // One "decayed causal scan": for every (batch, head) chain
 //     forward : w_t = sum_{s<=t} lambda^(t-s) (x_t . y_s) z_s
 //     reverse : w_t = sum_{s>=t} lambda^(s-t) (x_t . y_s) z_s
@@ -85,9 +88,9 @@ __device__ __forceinline__ float norm_collect(const float* red, int l32, float i
 int block_size_bf16(int head_dim);
 int block_size_f32(int head_dim);
 
-// bf16 MFMA path (head_dim 64 or 128)
-hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
-hipError_t launch_chunk_states_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+// 16-bit MFMA path (dtype kBF16 or kF16; head_dim 64 or 128)
+hipError_t launch_scan_bf16(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+hipError_t launch_chunk_states_bf16(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 // O(n^2 d) left-product evaluation of the forward pass, for comparison (bf16; uses x, y, z, w of scan 0)
 hipError_t launch_left_product_bf16(int head_dim, const ScanParams& p, hipStream_t s);
 // fp32 path
@@ -117,10 +120,10 @@ struct RecurParams {
   int32_t reverse;
   int64_t stride_b, stride_h, stride_n;  // elements, all of x, y, z, w
 };
-hipError_t launch_recur(int head_dim, bool bf16, int batch, int ninst, const RecurParams& p, hipStream_t s);
-// The forward case of the same for bf16 data (instance 0 only, reverse == 0) as a block kernel: bf16 MFMA in
+hipError_t launch_recur(int head_dim, int dtype, int batch, int ninst, const RecurParams& p, hipStream_t s);
+// The forward case of the same for 16-bit data (instance 0 only, reverse == 0) as a block kernel: MFMA in
 // blocks of 32 positions, the state after position t1 - 1 exact for any t1 - t0.  Needs t0 < t1.
-hipError_t launch_tail_bf16(int head_dim, int batch, const RecurParams& p, hipStream_t s);
+hipError_t launch_tail_bf16(int dtype, int head_dim, int batch, const RecurParams& p, hipStream_t s);
 
 // Backward of the Norm epilogue, row by row: du = rstd * (g - o * mean_j(g_j o_j)) with o the normalised
 // output and g its gradient; o, g, du share the layout given by the strides (elements), rstd is
@@ -133,12 +136,12 @@ struct NormBwdParams {
   int64_t stride_b, stride_h, stride_n;
   int32_t batch, heads, n;
 };
-hipError_t launch_norm_bwd_rows(int head_dim, bool bf16, const NormBwdParams& p, hipStream_t s);
+hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s);
 
 // dst[i] = src ? src[i] : 0 for count floats (a state that passes through an empty sequence)
 hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s);
 
-hipError_t launch_decode(int batch, int heads, int head_dim, bool bf16, const void* q, const void* k,
+hipError_t launch_decode(int batch, int heads, int head_dim, int dtype, const void* q, const void* k,
                          const void* v, const float* lambda, float* kv, void* o, hipStream_t s);
 
 }  // namespace la2

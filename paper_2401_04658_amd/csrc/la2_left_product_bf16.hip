@@ -4,6 +4,8 @@
 namespace la2 {
 namespace {
 using namespace bf16k;
+using bf16x8 = ex8<__bf16>;   // this comparison kernel takes bf16 only
+using bf16x4 = ex4<__bf16>;
 
 // Left-product form for comparison: O = [(Q K^T) * M] V computed tile by tile over ALL earlier key blocks
 // (the O(n^2 d) evaluation that the block recurrence replaces; Sec. 3.1 eq. (1) with the decay mask of

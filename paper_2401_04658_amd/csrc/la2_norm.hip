@@ -14,6 +14,7 @@ namespace la2 {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kThreads = 256;
@@ -30,6 +31,12 @@ template <> struct Row16<__bf16> {
   bf16x8 v;
   __device__ float get(int i) const { return (float)v[i]; }
   __device__ void set(int i, float x) { v[i] = (__bf16)x; }
+};
+template <> struct Row16<_Float16> {
+  static constexpr int N = 8;
+  f16x8 v;
+  __device__ float get(int i) const { return (float)v[i]; }
+  __device__ void set(int i, float x) { v[i] = (_Float16)x; }
 };
 
 template <typename T, int D>
@@ -72,8 +79,9 @@ hipError_t launch(const NormBwdParams& p, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_norm_bwd_rows(int head_dim, bool bf16, const NormBwdParams& p, hipStream_t s) {
-  if (bf16) return head_dim == 128 ? launch<__bf16, 128>(p, s) : launch<__bf16, 64>(p, s);
+hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s) {
+  if (dtype == kBF16) return head_dim == 128 ? launch<__bf16, 128>(p, s) : launch<__bf16, 64>(p, s);
+  if (dtype == kF16) return head_dim == 128 ? launch<_Float16, 128>(p, s) : launch<_Float16, 64>(p, s);
   return head_dim == 128 ? launch<float, 128>(p, s) : launch<float, 64>(p, s);
 }
 

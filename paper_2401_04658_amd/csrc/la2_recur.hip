@@ -20,13 +20,21 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <bool BF16>
+// element i of a tensor of type DT (kF32, kBF16 or kF16) as fp32, and the store that goes with it
+template <int DT>
 __device__ __forceinline__ float load_elem(const void* p, int64_t i) {
-  if (BF16) return (float)reinterpret_cast<const __bf16*>(p)[i];
+  if (DT == kBF16) return (float)reinterpret_cast<const __bf16*>(p)[i];
+  if (DT == kF16) return (float)reinterpret_cast<const _Float16*>(p)[i];
   return reinterpret_cast<const float*>(p)[i];
 }
+template <int DT>
+__device__ __forceinline__ void store_elem(void* p, int64_t i, float x) {
+  if (DT == kBF16) reinterpret_cast<__bf16*>(p)[i] = (__bf16)x;
+  else if (DT == kF16) reinterpret_cast<_Float16*>(p)[i] = (_Float16)x;
+  else reinterpret_cast<float*>(p)[i] = x;
+}
 
-template <int D, bool BF16>
+template <int D, int DT>
 __global__ __launch_bounds__(kThreads) void recur_kernel(RecurParams p) {
   constexpr int TPR = D / 4;            // threads per state row (float4 each)
   constexpr int RG = kThreads / TPR;    // rows in flight per sweep
@@ -68,9 +76,9 @@ __global__ __launch_bounds__(kThreads) void recur_kernel(RecurParams p) {
     const int t = p.reverse ? p.t1 - 1 - step : p.t0 + step;
     const int64_t row = base + (int64_t)t * p.stride_n;
     if (tid < D) {
-      sx[tid] = load_elem<BF16>(gx, row + tid);
-      sy[tid] = load_elem<BF16>(gy, row + tid);
-      sz[tid] = load_elem<BF16>(gz, row + tid);
+      sx[tid] = load_elem<DT>(gx, row + tid);
+      sy[tid] = load_elem<DT>(gy, row + tid);
+      sz[tid] = load_elem<DT>(gz, row + tid);
     }
     __syncthreads();
     const float4 z4 = *reinterpret_cast<const float4*>(&sz[4 * cg]);
@@ -100,8 +108,7 @@ __global__ __launch_bounds__(kThreads) void recur_kernel(RecurParams p) {
       float sum = 0.f;
 #pragma unroll
       for (int g = 0; g < RG; g++) sum += flat[g * D + tid];
-      if (BF16) reinterpret_cast<__bf16*>(gw)[row + tid] = (__bf16)sum;
-      else reinterpret_cast<float*>(gw)[row + tid] = sum;
+      store_elem<DT>(gw, row + tid, sum);
     }
     // the next step's loads into sx, sy, sz come after this step's second barrier; its first barrier
     // orders them against the reads of sacc above
@@ -126,17 +133,21 @@ __global__ __launch_bounds__(kThreads) void recur_kernel(RecurParams p) {
 
 }  // namespace
 
-hipError_t launch_recur(int head_dim, bool bf16, int batch, int ninst, const RecurParams& p, hipStream_t s) {
+hipError_t launch_recur(int head_dim, int dtype, int batch, int ninst, const RecurParams& p, hipStream_t s) {
   const int64_t chains = (int64_t)batch * p.heads;
   if (chains == 0 || ninst == 0) return hipSuccess;
   dim3 g((unsigned)chains, (unsigned)ninst), b(kThreads);
+#define LA2_LAUNCH_RECUR(D, DT) hipLaunchKernelGGL((recur_kernel<D, DT>), g, b, 0, s, p)
   if (head_dim == 128) {
-    if (bf16) hipLaunchKernelGGL((recur_kernel<128, true>), g, b, 0, s, p);
-    else      hipLaunchKernelGGL((recur_kernel<128, false>), g, b, 0, s, p);
+    if (dtype == kBF16) LA2_LAUNCH_RECUR(128, kBF16);
+    else if (dtype == kF16) LA2_LAUNCH_RECUR(128, kF16);
+    else LA2_LAUNCH_RECUR(128, kF32);
   } else {
-    if (bf16) hipLaunchKernelGGL((recur_kernel<64, true>), g, b, 0, s, p);
-    else      hipLaunchKernelGGL((recur_kernel<64, false>), g, b, 0, s, p);
+    if (dtype == kBF16) LA2_LAUNCH_RECUR(64, kBF16);
+    else if (dtype == kF16) LA2_LAUNCH_RECUR(64, kF16);
+    else LA2_LAUNCH_RECUR(64, kF32);
   }
+#undef LA2_LAUNCH_RECUR
   return hipGetLastError();
 }
 

@@ -10,17 +10,17 @@ using namespace bf16k;
 // NORM: the Norm epilogue of eq. (2) on a forward scan: the waves that hold the feature tiles of a row
 // exchange their sums of squares through LDS (one more workgroup barrier per block), scale the finished
 // tile and store r.
-template <int D, bool REV, bool NORM = false>
+template <typename E, int D, bool REV, bool NORM = false>
 __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   static_assert(!NORM || !REV, "the Norm epilogue belongs to the forward pass");
   using C = Cfg<D>;
   constexpr int KS = C::KS, NT = C::NT, RT = C::RT, TILE = C::TILE, LW = C::LW;
   // two tile buffers as two distinct LDS objects ([X, Y, Z] each) so that reads of one buffer are
   // provably independent of the direct loads in flight into the other
-  __shared__ __attribute__((aligned(1024))) __bf16 sT0[3][TILE];
-  __shared__ __attribute__((aligned(1024))) __bf16 sT1[3][TILE];
-  __shared__ __attribute__((aligned(1024))) __bf16 sT2[3][TILE];
-  __shared__ __attribute__((aligned(16))) __bf16 sW[4][32 * RT * LW];
+  __shared__ __attribute__((aligned(1024))) E sT0[3][TILE];
+  __shared__ __attribute__((aligned(1024))) E sT1[3][TILE];
+  __shared__ __attribute__((aligned(1024))) E sT2[3][TILE];
+  __shared__ __attribute__((aligned(16))) E sW[4][32 * RT * LW];
   float* const sRed = NormExchange<NORM ? 2 * kB * NT : 0>::get();   // [block parity][position][feature tile]
   // vector-memory operations a wave issues per block: direct loads (3 tiles), output stores and r
   constexpr int LOADS_PER_BLOCK = 3 * C::DMA_PER_WAVE, STORES_PER_BLOCK = 32 * RT * 4 / 64 + (NORM ? RT : 0);
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   const uint32_t stride_n = (uint32_t)p.stride_n;
   const uint32_t chain_bytes = ((uint32_t)(n - 1) * stride_n + D) * 2u;
   const __amdgpu_buffer_rsrc_t bw =
-      make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
+      make_rsrc(reinterpret_cast<E*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
   const float l2 = log2f(p.lambda[hi]);
   // Norm epilogue: r of this chain's positions; stores past position n - 1 are dropped
   const __amdgpu_buffer_rsrc_t brs =
@@ -67,9 +67,9 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   const int nblk = blk_hi - blk_lo;
 
   TileLoader<D, 3> loader(w, l, n, stride_n);
-  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.x[1] : p.x[0]) + base);
-  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.y[1] : p.y[0]) + base);
-  loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.z[1] : p.z[0]) + base);
+  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.x[1] : p.x[0]) + base);
+  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.y[1] : p.y[0]) + base);
+  loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.z[1] : p.z[0]) + base);
   const LaneAddr<D> la(l);
 
   // ---- running state slice S[:, dv tile]: NT accumulator tiles (key-feature tiles), fp32
@@ -151,8 +151,8 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   // phases costs registers that are not.)  The first two k-steps of phase 1 are read across the
   // barrier, underneath the last MFMAs of the previous block.
   constexpr int AHEAD = 2;
-  bf16x8 xa[RT][KS];
-  auto read_xa = [&](const __bf16 (*sB)[TILE], int ks) __attribute__((always_inline)) {
+  ex8<E> xa[RT][KS];
+  auto read_xa = [&](const E (*sB)[TILE], int ks) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < RT; i++) xa[i][ks] = la.read_row(sB[0], rt0 + i, ks);
   };
@@ -163,9 +163,9 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   // layout gives permuted order, the exchange between the wave's halves undoes it, so that the X
   // fragments serve the score product and the inter-block product unchanged.
   auto state_operand = [&](int ks) __attribute__((always_inline)) {
-    bf16x8 f;
+    ex8<E> f;
 #pragma unroll
-    for (int j = 0; j < 8; j++) f[j] = (__bf16)kv[ks >> 1][8 * (ks & 1) + j];
+    for (int j = 0; j < 8; j++) f[j] = (E)kv[ks >> 1][8 * (ks & 1) + j];
     return to_perm_order(f);   // the exchange is its own inverse
   };
 
@@ -174,8 +174,8 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   f32x16 outp[RT];
 #pragma unroll
   for (int i = 0; i < RT; i++) outp[i] = zero16();
-  bf16x8 sa_first = state_operand(0);
-  __bf16* const stage = sW[w];
+  ex8<E> sa_first = state_operand(0);
+  E* const stage = sW[w];
   constexpr int NST = 32 * RT * 4 / 64;   // 16-byte stores per lane and block
   // Output of block `oblk` in three steps: pack to bf16 and stage through LDS (so that the stores are
   // 16 bytes per lane, 64 contiguous bytes per row); read back; store.  `valid` false (no previous
@@ -183,11 +183,11 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   auto out_pack = [&](int i) __attribute__((always_inline)) {
 #pragma unroll
     for (int g = 0; g < 4; g++) {
-      bf16x4 pk;
+      ex4<E> pk;
 #pragma unroll
-      for (int e = 0; e < 4; e++) pk[e] = (__bf16)outp[i][4 * g + e];
+      for (int e = 0; e < 4; e++) pk[e] = (E)outp[i][4 * g + e];
       const int row = 32 * i + l32;
-      *reinterpret_cast<bf16x4*>(stage + row * LW + 8 * (g ^ ((row >> 2) & 3)) + 4 * hh) = pk;
+      *reinterpret_cast<ex4<E>*>(stage + row * LW + 8 * (g ^ ((row >> 2) & 3)) + 4 * hh) = pk;
     }
   };
   auto out_read = [&](i32x4 (&ov)[NST]) __attribute__((always_inline)) {
@@ -239,21 +239,21 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   static_assert(NDMA <= 2 * KS, "one direct load per slot");
   auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
-    __bf16 (*const sCur)[TILE] = cur == 0 ? sT0 : (cur == 1 ? sT1 : sT2);     // block it
-    __bf16 (*const sNext)[TILE] = cur == 0 ? sT1 : (cur == 1 ? sT2 : sT0);    // block it + 1 (in flight or landed)
-    __bf16 (*const sAhead)[TILE] = cur == 0 ? sT2 : (cur == 1 ? sT0 : sT1);   // block it + 2 (free since block it - 1)
+    E (*const sCur)[TILE] = cur == 0 ? sT0 : (cur == 1 ? sT1 : sT2);     // block it
+    E (*const sNext)[TILE] = cur == 0 ? sT1 : (cur == 1 ? sT2 : sT0);    // block it + 1 (in flight or landed)
+    E (*const sAhead)[TILE] = cur == 0 ? sT2 : (cur == 1 ? sT0 : sT1);   // block it + 2 (free since block it - 1)
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
     const bool has_next = it + 1 < nblk, has_ahead = it + 2 < nblk;
     const int nb = REV ? blk - 1 : blk + 1, pb = REV ? blk + 1 : blk - 1;
-    const __bf16* tY = sCur[1];
-    const __bf16* tZ = sCur[2];
+    const E* tY = sCur[1];
+    const E* tZ = sCur[2];
     uint32_t doff[C::DMA_PER_WAVE];
     loader.offsets(REV ? blk - 2 : blk + 2, has_ahead, doff);
 
-    bf16x8 zf[2][2];     // Z columns of this wave's value tile: [key-tile slot][k-step], permuted k-order
-    bf16x8 zd[2][2];     // the same, weighted for the state update
-    bf16x8 yt[NT][2][2]; // Y columns (key features): [key-feature tile][slot][k-step], permuted k-order
-    bf16x8 xb[RT][KS], yb[RT][KS], yo[KS];   // phase 2 operands
+    ex8<E> zf[2][2];     // Z columns of this wave's value tile: [key-tile slot][k-step], permuted k-order
+    ex8<E> zd[2][2];     // the same, weighted for the state update
+    ex8<E> yt[NT][2][2]; // Y columns (key features): [key-feature tile][slot][k-step], permuted k-order
+    ex8<E> xb[RT][KS], yb[RT][KS], yo[KS];   // phase 2 operands
     auto read_xy = [&](int ks) __attribute__((always_inline)) {
 #pragma unroll
       for (int i = 0; i < RT; i++) xb[i][ks] = la.read_row(sCur[0], rt0 + i, ks);
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 #pragma unroll
     for (int i = 0; i < RT; i++) inter[i] = zero16();
     i32x4 ov[NST];
-    bf16x8 sa = sa_first;
+    ex8<E> sa = sa_first;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
 #pragma unroll
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
     // ---- phase 3: state slice <- lambda^B state + Y^T decay(Z), contraction over this block's rows in
     // 4 k-steps; meanwhile the decay masks turn the finished score tiles into bf16 operands.
     // (After the last block the state is not needed; the update runs anyway, branch-free.)
-    bf16x8 pd[RT][2], po[2];
+    ex8<E> pd[RT][2], po[2];
 #pragma unroll
     for (int sq = 0; sq < 4; sq++) {
 #pragma unroll
@@ -351,8 +351,8 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
       for (int e = 0; e < 4; e++) {
         const int v = 4 * sq + e;
 #pragma unroll
-        for (int i = 0; i < RT; i++) pd[i][v >> 3][v & 7] = (__bf16)(sd[i][v] * dg[v]);
-        po[v >> 3][v & 7] = (__bf16)((so[v] * oa) * ou[v]);
+        for (int i = 0; i < RT; i++) pd[i][v >> 3][v & 7] = (E)(sd[i][v] * dg[v]);
+        po[v >> 3][v & 7] = (E)((so[v] * oa) * ou[v]);
       }
 #pragma unroll
       for (int i = 0; i < RT; i++) pin(pd[i][sq >> 1]);
@@ -445,22 +445,29 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
 
 int block_size_bf16(int) { return bf16k::kB; }
 
-hipError_t launch_scan_bf16_full(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+namespace {
+template <typename E>
+hipError_t launch_full(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   dim3 g((unsigned)grid), b(kThreads);
   if (head_dim == 128) {
-    if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<128, true>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((scan_bf16_kernel<128, false>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<E, 128, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_kernel<E, 128, false>), g, b, 0, s, p);
   } else {
-    if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<64, true>), g, b, 0, s, p);
-    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_kernel<64, false, true>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((scan_bf16_kernel<64, false>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_kernel<E, 64, true>), g, b, 0, s, p);
+    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_kernel<E, 64, false, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_kernel<E, 64, false>), g, b, 0, s, p);
   }
   return hipGetLastError();
 }
+}  // namespace
+
+hipError_t launch_scan_bf16_full(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+  return dtype == kF16 ? launch_full<_Float16>(head_dim, reverse, p, s) : launch_full<__bf16>(head_dim, reverse, p, s);
+}
 
 // Which scan kernel a launch gets.
-hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
+hipError_t launch_scan_bf16(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   if (grid == 0 || p.n == 0) return hipSuccess;
   // the half-block kernel measured faster at every launch size, also at one workgroup per compute unit;
@@ -469,9 +476,9 @@ hipError_t launch_scan_bf16(int head_dim, bool reverse, const ScanParams& p, hip
   const bool half = p.variant != 1 || with_state || p.rstd != nullptr;   // also the one with the Norm epilogue
   if (head_dim == 128 && half && p.chunk_tokens % 32 == 0) {
     const bool twin = p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0];
-    return launch_scan_bf16_half(reverse, twin, p, s);
+    return launch_scan_bf16_half(dtype, reverse, twin, p, s);
   }
-  return launch_scan_bf16_full(head_dim, reverse, p, s);
+  return launch_scan_bf16_full(dtype, head_dim, reverse, p, s);
 }
 
 }  // namespace la2

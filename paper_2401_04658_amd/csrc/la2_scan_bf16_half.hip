@@ -29,7 +29,7 @@ constexpr int kBH = 32;
 // their quarter rows through LDS (one more workgroup barrier per block), scale the finished tile and
 // wave 0 stores r.  The LDS is full, so the room for the exchange is taken from the output staging,
 // which then handles the block in two halves of 16 positions.
-template <bool REV, bool TWIN, int NBUF, bool NORM = false>
+template <typename E, bool REV, bool TWIN, int NBUF, bool NORM = false>
 __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
   static_assert(!NORM || (!REV && !TWIN), "the Norm epilogue belongs to the forward pass");
   constexpr int D = 128, B = kBH;
@@ -38,9 +38,9 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   constexpr int NW = TWIN ? 8 : 4;             // waves
   constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
   using Loader = TileLoader<D, NTL, B, NW>;
-  __shared__ __attribute__((aligned(1024))) __bf16 sT[NBUF][NTL][TILE];
+  __shared__ __attribute__((aligned(1024))) E sT[NBUF][NTL][TILE];
   constexpr int STAGE_ROWS = NORM ? 16 : 32;   // positions staged at a time
-  __shared__ __attribute__((aligned(16))) __bf16 sW[NW][STAGE_ROWS * LW];
+  __shared__ __attribute__((aligned(16))) E sW[NW][STAGE_ROWS * LW];
   float* const sRed = NormExchange<NORM ? 2 * 32 * 4 : 0>::get();   // [block parity][position][wave]
   // Cache policy of the output stores (buffer instruction bits: 2 = nt, 16 = sc1).  Measured: the twin
   // workgroup, a third of whose traffic is stores, runs 9-13 % faster with streaming write-through stores;
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   const uint32_t stride_n = (uint32_t)p.stride_n;
   const uint32_t chain_bytes = ((uint32_t)(n - 1) * stride_n + D) * 2u;
   const __amdgpu_buffer_rsrc_t bw =
-      make_rsrc(reinterpret_cast<__bf16*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
+      make_rsrc(reinterpret_cast<E*>(which ? p.w[1] : p.w[0]) + base, chain_bytes);
   const float l2 = log2f(p.lambda[hi]);
   // Norm epilogue: r of this chain's positions; stores past position n - 1 are dropped
   const __amdgpu_buffer_rsrc_t brs =
@@ -95,14 +95,14 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
 
   Loader loader(w, l, n, stride_n);
   if (TWIN) {
-    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[0]) + base);
-    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[1]) + base);
-    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
-    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[1]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
+    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
   } else {
-    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.x[1] : p.x[0]) + base);
-    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.y[1] : p.y[0]) + base);
-    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(which ? p.z[1] : p.z[0]) + base);
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.x[1] : p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.y[1] : p.y[0]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.z[1] : p.z[0]) + base);
   }
   // this wave's X, Y, Z among the tiles of a block
   constexpr int xi = TWIN ? WH : 0, yi = TWIN ? 2 + WH : 1, zi = TWIN ? 3 - WH : 2;
@@ -151,20 +151,20 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   __syncthreads();
 
   constexpr int AHEAD = 1;   // LDS operands are read one slot ahead (the other wave on the SIMD covers the rest)
-  bf16x8 xa[KS], ya[KS];     // X and Y row fragments (natural k-order) of the block being computed
+  ex8<E> xa[KS], ya[KS];     // X and Y row fragments (natural k-order) of the block being computed
 #pragma unroll
   for (int ks = 0; ks < AHEAD; ks++) {
     xa[ks] = la.read_row(sT[0][xi], 0, ks);
     ya[ks] = la.read_row(sT[0][yi], 0, ks);
   }
   auto state_operand = [&](int ks) __attribute__((always_inline)) {
-    bf16x8 f;
+    ex8<E> f;
 #pragma unroll
-    for (int j = 0; j < 8; j++) f[j] = (__bf16)kv[ks >> 1][8 * (ks & 1) + j];
+    for (int j = 0; j < 8; j++) f[j] = (E)kv[ks >> 1][8 * (ks & 1) + j];
     return to_perm_order(f);
   };
-  bf16x8 sa_first = state_operand(0);
-  __bf16* const stage = sW[w];
+  ex8<E> sa_first = state_operand(0);
+  E* const stage = sW[w];
 
 #define LA2_SLOT_END()                 \
   do {                                 \
@@ -175,19 +175,19 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   // barrier; 4 intra-block product), then the block's output.
   auto block_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
     constexpr int cur = decltype(cur_tag)::value;
-    __bf16 (*const sCur)[TILE] = sT[cur];                          // block it
-    __bf16 (*const sNext)[TILE] = sT[(cur + 1) % NBUF];            // block it + 1 (in flight or landed)
-    __bf16 (*const sAhead)[TILE] = sT[(cur + NBUF - 1) % NBUF];    // block it + NBUF - 1 (free since block it - 1)
+    E (*const sCur)[TILE] = sT[cur];                          // block it
+    E (*const sNext)[TILE] = sT[(cur + 1) % NBUF];            // block it + 1 (in flight or landed)
+    E (*const sAhead)[TILE] = sT[(cur + NBUF - 1) % NBUF];    // block it + NBUF - 1 (free since block it - 1)
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
     const bool has_next = it + 1 < nblk, has_ahead = it + NBUF - 1 < nblk;
     const int nb = REV ? blk - 1 : blk + 1;
-    const __bf16* tX = sCur[xi];
-    const __bf16* tY = sCur[yi];
-    const __bf16* tZ = sCur[zi];
+    const E* tX = sCur[xi];
+    const E* tY = sCur[yi];
+    const E* tZ = sCur[zi];
     uint32_t doff[Loader::DMA_PER_WAVE];
     loader.offsets(REV ? blk - (NBUF - 1) : blk + (NBUF - 1), has_ahead, doff);
 
-    bf16x8 zf[2], zd[2], yt[2][NT];
+    ex8<E> zf[2], zd[2], yt[2][NT];
     auto read_xy = [&](int ks) __attribute__((always_inline)) {
       xa[ks] = la.read_row(tX, 0, ks);
       ya[ks] = la.read_row(tY, 0, ks);
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     // Side work: the next state operand; lambda^B on a state tile once both its operands are made; the
     // update weights on Z; the direct loads of block it + NBUF - 1.
     f32x16 inter = zero16(), sd = zero16();
-    bf16x8 sa = sa_first;
+    ex8<E> sa = sa_first;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       inter = mfma(sa, xa[ks], inter);
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
       pin(inter);
     }
     // ---- phase 3
-    bf16x8 pd[2];
+    ex8<E> pd[2];
 #pragma unroll
     for (int s4 = 0; s4 < 4; s4++) {   // slot s4: k-step q = s4 / 2, key-feature tiles 2 h, 2 h + 1, h = s4 % 2
       const int q = s4 >> 1, h = s4 & 1;
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
       for (int t = 2 * h; t < 2 * h + 2; t++) kv[t] = mfma(yt[q][t], zd[q], kv[t]);
       if (s4 + 1 < 4) read_yt((s4 + 1) >> 1, (s4 + 1) & 1);
 #pragma unroll
-      for (int e = 0; e < 4; e++) pd[q][4 * h + e] = (__bf16)(sd[8 * q + 4 * h + e] * dg[8 * q + 4 * h + e]);
+      for (int e = 0; e < 4; e++) pd[q][4 * h + e] = (E)(sd[8 * q + 4 * h + e] * dg[8 * q + 4 * h + e]);
       pin(pd[q]);
 #pragma unroll
       for (int t = 2 * h; t < 2 * h + 2; t++) pin(kv[t]);
@@ -281,17 +281,17 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
 #pragma unroll
       for (int v = 0; v < 16; v++) inter[v] *= r;
       pin(inter);
-      bf16x4 pk[4];
+      ex4<E> pk[4];
 #pragma unroll
       for (int g = 0; g < 4; g++)
 #pragma unroll
-        for (int e = 0; e < 4; e++) pk[g][e] = (__bf16)inter[4 * g + e];
+        for (int e = 0; e < 4; e++) pk[g][e] = (E)inter[4 * g + e];
 #pragma unroll
       for (int half = 0; half < 2; half++) {   // this wave's LDS operations run in order: no barrier needed
         if ((l32 >> 4) == half) {
 #pragma unroll
           for (int g = 0; g < 4; g++)
-            *reinterpret_cast<bf16x4*>(stage + (l32 & 15) * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk[g];
+            *reinterpret_cast<ex4<E>*>(stage + (l32 & 15) * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk[g];
         }
         // Lanes read what OTHER lanes wrote under a mask: without this the compiler treats the read of a
         // lane that wrote nothing as a repeat of its previous read and drops it.
@@ -308,10 +308,10 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     } else {
 #pragma unroll
     for (int g = 0; g < 4; g++) {
-      bf16x4 pk;
+      ex4<E> pk;
 #pragma unroll
-      for (int e = 0; e < 4; e++) pk[e] = (__bf16)inter[4 * g + e];
-      *reinterpret_cast<bf16x4*>(stage + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
+      for (int e = 0; e < 4; e++) pk[e] = (E)inter[4 * g + e];
+      *reinterpret_cast<ex4<E>*>(stage + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
     }
 #pragma unroll
     for (int i = 0; i < 32 * 4 / 64; i++) {
@@ -351,22 +351,29 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
 
 }  // namespace
 
-hipError_t launch_scan_bf16_half(bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
+namespace {
+template <typename E>
+hipError_t launch_half(bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   // Three tile buffers in every case.  More buffers (5 for a plain, 4 for a twin workgroup that has the
-  // compute unit to itself) measured no faster: such launches are bound by the workgroup's own
-  // instruction stream, not by the bytes in flight.
+  // compute unit to itself) measured no faster: such launches are bound by the memory system, not by the
+  // bytes a workgroup keeps in flight.
   if (twin) {
     dim3 gt((unsigned)(grid / 2)), bt(512);
-    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, true, 3>), gt, bt, 0, s, p);
-    else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, true, 3>), gt, bt, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, true, true, 3>), gt, bt, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, true, 3>), gt, bt, 0, s, p);
   } else {
     dim3 g((unsigned)grid), b(kThreads);
-    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<true, false, 3>), g, b, 0, s, p);
-    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_half_kernel<false, false, 3, true>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((scan_bf16_half_kernel<false, false, 3>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, true, false, 3>), g, b, 0, s, p);
+    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3>), g, b, 0, s, p);
   }
   return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_scan_bf16_half(int dtype, bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
+  return dtype == kF16 ? launch_half<_Float16>(reverse, twin, p, s) : launch_half<__bf16>(reverse, twin, p, s);
 }
 
 }  // namespace la2

@@ -15,13 +15,13 @@ namespace la2 {
 namespace {
 using namespace bf16k;
 
-template <int D>
+template <typename E, int D>
 __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
   constexpr int B = 32;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
   using Loader = TileLoader<D, 3, B, NT>;
-  __shared__ __attribute__((aligned(1024))) __bf16 sT[3][TILE];   // X, Y, Z
+  __shared__ __attribute__((aligned(1024))) E sT[3][TILE];   // X, Y, Z
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w;
@@ -33,10 +33,10 @@ __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
   const float l2 = log2f(p.lambda[hi]);
 
   Loader loader(w, l, n, stride_n);
-  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.x[0]) + base);
-  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.y[0]) + base);
-  loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const __bf16*>(p.z[0]) + base);
-  __bf16* const gw = reinterpret_cast<__bf16*>(p.w[0]) + base;
+  loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
+  loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
+  loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
+  E* const gw = reinterpret_cast<E*>(p.w[0]) + base;
   const LaneAddr<D> la(l);
 
   // state slice S[:, dv tile] in accumulator layout
@@ -71,35 +71,35 @@ __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
     f32x16 acc = zero16(), sd = zero16();
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
-      const bf16x8 xa = la.read_row(sT[0], 0, ks), ya = la.read_row(sT[1], 0, ks);
-      bf16x8 f;
+      const ex8<E> xa = la.read_row(sT[0], 0, ks), ya = la.read_row(sT[1], 0, ks);
+      ex8<E> f;
 #pragma unroll
-      for (int j = 0; j < 8; j++) f[j] = (__bf16)kv[ks >> 1][8 * (ks & 1) + j];
+      for (int j = 0; j < 8; j++) f[j] = (E)kv[ks >> 1][8 * (ks & 1) + j];
       acc = mfma(to_perm_order(f), xa, acc);
       sd = mfma(ya, xa, sd);
     }
 #pragma unroll
     for (int v = 0; v < 16; v++) acc[v] *= inter_scale;
     // intra-block part Z^T P^T; the same Z fragments, weighted, update the state
-    bf16x8 zf[2];
+    ex8<E> zf[2];
 #pragma unroll
     for (int q = 0; q < 2; q++) {
       zf[q] = la.read_cols(sT[2], 16 * q, dvt);
-      bf16x8 pd;
+      ex8<E> pd;
 #pragma unroll
-      for (int j = 0; j < 8; j++) pd[j] = (__bf16)(sd[8 * q + j] * dg[8 * q + j]);
+      for (int j = 0; j < 8; j++) pd[j] = (E)(sd[8 * q + j] * dg[8 * q + j]);
       acc = mfma(zf[q], pd, acc);
     }
     // output: lane = position l32, elements 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
     const int pos = blk * B + l32;
     if (pos < n) {
-      __bf16* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;
+      E* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;
 #pragma unroll
       for (int g = 0; g < 4; g++) {
-        bf16x4 pk;
+        ex4<E> pk;
 #pragma unroll
-        for (int e = 0; e < 4; e++) pk[e] = (__bf16)acc[4 * g + e];
-        *reinterpret_cast<bf16x4*>(orow + 8 * g) = pk;
+        for (int e = 0; e < 4; e++) pk[e] = (E)acc[4 * g + e];
+        *reinterpret_cast<ex4<E>*>(orow + 8 * g) = pk;
       }
     }
     // state slice <- lambda^nv state + Y^T decay(Z): element j of a Z fragment is row 16 q + 8 (j / 4) + 4 hh + j % 4
@@ -110,11 +110,11 @@ __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
       for (int v = 0; v < 16; v++) kv[t][v] *= lam_nv;
 #pragma unroll
     for (int q = 0; q < 2; q++) {
-      bf16x8 zd;
+      ex8<E> zd;
 #pragma unroll
       for (int j = 0; j < 8; j++) {
         const int c = 16 * q + 8 * (j >> 2) + 4 * hh + (j & 3);
-        zd[j] = (__bf16)((float)zf[q][j] * exp2f(l2 * (float)max(nv - 1 - c, 0)));
+        zd[j] = (E)((float)zf[q][j] * exp2f(l2 * (float)max(nv - 1 - c, 0)));
       }
 #pragma unroll
       for (int t = 0; t < NT; t++) kv[t] = mfma(la.read_cols(sT[1], 16 * q, t), zd, kv[t]);
@@ -134,12 +134,17 @@ __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
 
 }  // namespace
 
-hipError_t launch_tail_bf16(int head_dim, int batch, const RecurParams& p, hipStream_t s) {
+hipError_t launch_tail_bf16(int dtype, int head_dim, int batch, const RecurParams& p, hipStream_t s) {
   const int64_t chains = (int64_t)batch * p.heads;
   if (chains == 0 || p.t1 <= p.t0) return hipSuccess;
   dim3 g((unsigned)chains);
-  if (head_dim == 128) hipLaunchKernelGGL((tail_bf16_kernel<128>), g, dim3(256), 0, s, p);
-  else                 hipLaunchKernelGGL((tail_bf16_kernel<64>), g, dim3(128), 0, s, p);
+  if (dtype == kF16) {
+    if (head_dim == 128) hipLaunchKernelGGL((tail_bf16_kernel<_Float16, 128>), g, dim3(256), 0, s, p);
+    else                 hipLaunchKernelGGL((tail_bf16_kernel<_Float16, 64>), g, dim3(128), 0, s, p);
+  } else {
+    if (head_dim == 128) hipLaunchKernelGGL((tail_bf16_kernel<__bf16, 128>), g, dim3(256), 0, s, p);
+    else                 hipLaunchKernelGGL((tail_bf16_kernel<__bf16, 64>), g, dim3(128), 0, s, p);
+  }
   return hipGetLastError();
 }
 

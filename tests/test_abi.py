@@ -264,3 +264,15 @@ def test_chain_span_limit(lib):
     d = dense(lib, 4, 1, 200000, 64, binding.LA2_BF16)               # [b, n, H, d] storage with a large row pitch
     d.stride_n = 16384
     assert fwd(lib, d) == E_SHAPE
+
+
+def test_fp16_is_accepted_except_by_the_comparison_kernel(lib):
+    d = dense(lib, 0, 2, 128, 64, binding.LA2_F16)          # an empty problem passes validation without a launch
+    assert fwd(lib, d) == OK and bwd(lib, d) == OK
+    d = dense(lib, 300, 2, 128, 64, binding.LA2_F16)
+    assert fwd(lib, d, q=None) == E_NULL and fwd(lib, d, o=P + 8) == E_ALIGN
+    assert lib.la2_block_size(ctypes.byref(d)) == 64
+    d = dense(lib, 300, 2, 128, 128, binding.LA2_F16)
+    assert lib.la2_block_size(ctypes.byref(d)) == 32
+    assert lib.la2_left_product_fwd(ctypes.byref(d), P, P, P, P, P, None) == E_DTYPE
+    assert lib.la2_decode_step(0, 1, 64, binding.LA2_F16, None, None, None, None, None, None, None) == OK

@@ -65,7 +65,7 @@ def test_config2_fwd_bwd_bf16_full():
 
 
 # ---- small shapes spanning several tiles and ragged tails, both dtypes, both head dims ------------------------------
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("n", [1, 31, 128, 129, 200, 384, 517])
 def test_small_shapes(dtype, d, n):
@@ -126,7 +126,7 @@ def test_scan_variants_agree():
         assert max_rel(to64(a), to64(b)) <= 1e-2
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 @pytest.mark.parametrize("chunk", [128, 256, 384])
 @pytest.mark.parametrize("d,n", [(64, 1000), (128, 1000), (128, 1024), (64, 257)])
 def test_chunked_path(dtype, chunk, d, n):
@@ -204,7 +204,7 @@ def test_longest_sequence_one_chain_spans_4_gib():
 
 def test_extreme_decays():
     """lambda = 1 (pure causal prefix sum) and a very small lambda (only the diagonal survives)."""
-    for dtype in (torch.bfloat16, torch.float32):
+    for dtype in (torch.bfloat16, torch.float16, torch.float32):
         t = make_inputs(1, 3, 300, 64, dtype, seed=21, lam=[1.0, 1e-6, 0.43])
         check_fwd_bwd(t, dtype, "extreme decays %s" % dtype)
 
@@ -212,7 +212,7 @@ def test_extreme_decays():
 def test_strided_layout():
     """[b, n, H, d] storage viewed as [b, H, n, d]: strides go through the descriptor."""
     b, H, n, d = 2, 4, 260, 128
-    for dtype in (torch.bfloat16, torch.float32):
+    for dtype in (torch.bfloat16, torch.float16, torch.float32):
         t = make_inputs(b, H, n, d, dtype, seed=31)
         g = {}
         for name in ("q", "k", "v", "d_o"):
@@ -334,7 +334,7 @@ def test_config5_decode_1024_steps_one_batch_row():
 
 
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 def test_decode_matches_forward(d, dtype):
     """n decode steps from a zero state reproduce the forward output row by row."""
     b, H, n = 2, 3, 40

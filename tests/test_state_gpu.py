@@ -60,7 +60,7 @@ def check_segment(t, dtype, tag, use_init=True, use_final=True):
     assert_close(tag + " d_kv_init", dkv0, rdkv0, dtype)
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("n", [64, 128, 320])
 def test_segment_with_all_states(dtype, d, n):
@@ -68,7 +68,7 @@ def test_segment_with_all_states(dtype, d, n):
     check_segment(t, dtype, "n%d d%d %s" % (n, d, dtype))
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("n", [1, 31, 64, 100, 129, 300])
 def test_ragged_segments(dtype, d, n):
@@ -98,7 +98,7 @@ def test_fp32_chunked_segment():
     check_segment(t, torch.float32, "fp32 chunked")
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 def test_two_segments_equal_the_whole_sequence(dtype):
     """Forward left to right, backward right to left through the hand-over states, against the oracle's
     DIRECT form of the whole sequence (which has no notion of a state)."""
@@ -166,7 +166,7 @@ def test_sweep_points_with_states(point):
     check_segment(t, wl.dtype, wl.name + " with states")
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("T", [1, 2, 7, 32, 33, 64, 100])
 def test_decode_multi(dtype, d, T):
