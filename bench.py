@@ -233,8 +233,8 @@ def main():
     for dt, tag in ((torch.float16, "f16"), (torch.float32, "f32")):
         wl_d = workloads.Workload(wl1.name + "_" + tag, wl1.batch, wl1.heads, wl1.seqlen, wl1.head_dim, dt, seed=wl1.seed)
         g_d = stage(wl_d)
-        f_ms = time_ms(lambda: fwd(g_d), iters, warm=10)
-        b_ms = time_ms(lambda: bwd(g_d), iters, warm=10)
+        f_ms = time_ms(lambda: fwd(g_d), iters, warm=40)
+        b_ms = time_ms(lambda: bwd(g_d), iters, warm=40)
         other_dtypes.append({"workload": wl_d.name, "dtype": tag, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                              "tokens_per_s": round(wl_d.tokens / ((f_ms + b_ms) * 1e-3), 1)})
         del g_d
