@@ -121,9 +121,9 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
  * la2_bwd_state needs the kv_init the forward pass was given (dq depends on it).  All other arguments
  * as for la2_fwd / la2_bwd, which are these functions with NULL states.  State pointers are 16-byte
  * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen:
- * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (64 for bf16 with head_dim 64),
- * the last seqlen % G positions run token by token (the block kernels form states after whole blocks
- * only).  seqlen == 0 copies the
+ * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (64 for 16-bit data with head_dim
+ * 64), the last seqlen % G positions run in a short-run kernel (the scan kernels form states after whole
+ * blocks only).  seqlen == 0 copies the
  * state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if the input is NULL).
  */
 la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
@@ -209,10 +209,10 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
  *   kv_state  in/out  device, fp32 dense [batch, heads, head_dim, head_dim], updated in place
  *   o         out     device, dense [batch, heads, ntokens, head_dim], dtype qkv_dtype
  * All pointers 16-byte aligned.  head_dim is 64 or 128; ntokens <= 65536.  Same result as ntokens calls of
- * la2_decode_step up to rounding: runs shorter than a block (32 positions; 64 for bf16 with head_dim 64) go
- * token by token in fp32; of longer runs the whole blocks go through la2_fwd_state's block kernels with the
- * state in place (bf16: bf16 matrix operands, as there), unless batch * heads is too small to fill the
- * device without a workspace.
+ * la2_decode_step up to rounding.  16-bit data: block kernels with bf16 / fp16 matrix operands as in la2_fwd
+ * (whole blocks through la2_fwd_state's kernels with the state in place when batch * heads fills the device
+ * without a workspace; a shorter run or the rest in one launch of a small block kernel that hands out the exact
+ * state after a partial block).  fp32 data: whole blocks as in la2_fwd_state, the rest token by token in fp32.
  */
 la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens,
                             int32_t qkv_dtype, const void* q, const void* k, const void* v,
