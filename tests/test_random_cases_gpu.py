@@ -1,0 +1,115 @@
+"""Seeded random sweep over the library's options, each case against the fp64 oracle: data type, head_dim,
+batch, heads, sequence length (ragged more often than not), sequence-chunk size, storage layout, decay,
+start / final states and their gradients, and the Norm epilogue.  The fixed cases elsewhere pick the corners
+by hand; this one looks for combinations nobody thought of."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_04658_amd import binding, workloads
+from parity import assert_close, to64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+DTYPES = (torch.bfloat16, torch.float16, torch.float32)
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+    yield
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+
+
+def draw_case(i):
+    rng = np.random.default_rng(90210 + i)
+    dtype = DTYPES[int(rng.integers(0, 3))]
+    d = int(rng.choice([64, 128]))
+    b, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    n = int(rng.choice([rng.integers(1, 70), rng.integers(70, 400), 32 * rng.integers(1, 12), rng.integers(400, 900)]))
+    chunk = int(rng.choice([0, 0, 64, 128, 192, 320]))
+    layout = str(rng.choice(["bhnd", "bnhd", "padded"]))
+    lam = rng.choice([1.0, 0.999, 0.97, 0.8, 0.3, 1e-3], size=H).astype(np.float32)
+    mode = str(rng.choice(["plain", "state", "state_nofinal", "norm", "decode_multi"]))
+    variant = int(rng.choice([0, 1, 2]))
+    return dict(dtype=dtype, d=d, b=b, H=H, n=n, chunk=chunk, layout=layout, lam=lam, mode=mode, variant=variant,
+                seed=int(rng.integers(0, 1 << 30)))
+
+
+def place(x, layout):
+    """The tensor x [b, H, n, d] stored in the given layout on the GPU, viewed as [b, H, n, d]."""
+    if layout == "bhnd":
+        return x.to(DEV)
+    if layout == "bnhd":
+        return x.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    b, H, n, d = x.shape                      # rows padded to d + 8 elements
+    store = torch.zeros((b, H, n, d + 8), dtype=x.dtype, device=DEV)
+    store[..., :d] = x.to(DEV)
+    return store[..., :d]
+
+
+@pytest.mark.parametrize("i", range(160))
+def test_random_case(i):
+    c = draw_case(i)
+    dtype, d, b, H, n = c["dtype"], c["d"], c["b"], c["H"], c["n"]
+    tag = "case %d %s" % (i, {k: (v if k != "lam" else v.tolist()) for k, v in c.items()})
+    t = workloads.Workload("random", b, H, n, d, dtype, seed=c["seed"], backward=True).tensors()
+    t["lam"] = torch.as_tensor(c["lam"])
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(c["seed"] + 1)
+    t["kv_init"] = torch.randn((b, H, d, d), generator=gen, dtype=torch.float32) * 0.3
+    t["d_kv_final"] = torch.randn((b, H, d, d), generator=gen, dtype=torch.float32) * 0.3
+    g = {name: place(t[name], c["layout"]) for name in ("q", "k", "v", "d_o")}
+    for name in ("lam", "kv_init", "d_kv_final"):
+        g[name] = t[name].to(DEV)
+    binding.la2_set_chunk_tokens(c["chunk"])
+    binding.la2_set_scan_variant(c["variant"])
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+
+    if c["mode"] == "plain":
+        o = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
+        grads = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
+        torch.cuda.synchronize()
+        assert_close(tag + " o", o, oracle.fwd_direct(q, k, v, lam), dtype)
+        for name, got, ref in zip(("dq", "dk", "dv"), grads, oracle.bwd_direct(q, k, v, do, lam)):
+            assert_close(tag + " " + name, got, ref, dtype)
+    elif c["mode"] == "decode_multi":   # dense tensors only; the state is updated in place
+        state = g["kv_init"].clone()
+        o = binding.la2_decode_multi(g["q"].contiguous(), g["k"].contiguous(), g["v"].contiguous(), g["lam"], state)
+        torch.cuda.synchronize()
+        ro, rs = oracle.fwd_recurrent(q, k, v, lam, kv_init=to64(t["kv_init"]), return_state=True)
+        assert_close(tag + " o", o, ro, dtype)
+        assert_close(tag + " state", state, rs, dtype)
+        return
+    elif c["mode"] == "norm":
+        eps = 1e-3
+        o, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], eps)
+        grads = binding.la2_bwd_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"])
+        torch.cuda.synchronize()
+        ref_o, ref_r = oracle.fwd_norm(q, k, v, lam, eps)
+        assert_close(tag + " o", o, ref_o, dtype)
+        assert_close(tag + " rstd", rstd, ref_r, dtype)
+        if n > 1:   # a single position leaves dq, dk as pure cancellation (see test_norm_gpu)
+            for name, got, ref in zip(("dq", "dk", "dv"), grads, oracle.bwd_norm(q, k, v, do, lam, eps)):
+                assert_close(tag + " " + name, got, ref, dtype)
+    else:
+        final = c["mode"] == "state"
+        o, kvf = binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=g["kv_init"], want_final=final)
+        dq, dk, dv, dkv0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=g["kv_init"],
+                                                 d_kv_final=g["d_kv_final"] if final else None)
+        torch.cuda.synchronize()
+        init64 = to64(t["kv_init"])
+        ro, rkvf = oracle.fwd_recurrent(q, k, v, lam, kv_init=init64, return_state=True)
+        refs = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=init64,
+                                          d_kv_final=to64(t["d_kv_final"]) if final else None)
+        assert_close(tag + " o", o, ro, dtype)
+        if final:
+            assert_close(tag + " kv_final", kvf, rkvf, dtype)
+        for name, got, ref in zip(("dq", "dk", "dv", "d_kv_init"), (dq, dk, dv, dkv0), refs):
+            assert_close(tag + " " + name, got, ref, dtype)
+    for x in (g["q"], o):
+        assert x.stride() == g["q"].stride()
