@@ -305,9 +305,10 @@ struct UpdateDecay {
       gj[j] = uniform(exp2f(l2 * (float)(REV ? nj : 11 - nj)));
     }
   }
+  // `scale`: one more factor on every weight (the chunk-state pre-pass folds a block's whole-block decay in)
   template <typename E>
-  __device__ __forceinline__ ex8<E> apply(ex8<E> z, int c0) const {
-    const float step = fast_exp2(l2 * (float)(REV ? c0 + 4 * hh + 1 : B - 16 - c0 + 4 * (1 - hh)));
+  __device__ __forceinline__ ex8<E> apply(ex8<E> z, int c0, float scale = 1.f) const {
+    const float step = scale * fast_exp2(l2 * (float)(REV ? c0 + 4 * hh + 1 : B - 16 - c0 + 4 * (1 - hh)));
     ex8<E> r;
 #pragma unroll
     for (int j = 0; j < 8; j++) r[j] = (E)((float)z[j] * (step * gj[j]));

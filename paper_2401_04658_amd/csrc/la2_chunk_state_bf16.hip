@@ -46,8 +46,6 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
   const LaneAddr<D> la(l);
   const UpdateDecay<REV> decay(l2, hh);
-  const float lamB = exp2f(l2 * (float)kB);
-
   f32x16 kv[NT];
 #pragma unroll
   for (int t = 0; t < NT; t++) kv[t] = zero16();
@@ -81,13 +79,15 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
       for (int t = 0; t < NT; t++) yt[t][k] = la.read_cols(tY, 16 * k, t);
     }
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int t = 0; t < NT; t++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
+    // Only the state after the chunk's last block is wanted, so instead of decaying the running sum by
+    // lambda^B per block, each block's contribution carries its whole decay up front: the block processed
+    // `it`-th has nblk - 1 - it blocks after it (forward: later positions; reverse: earlier ones), which
+    // saves a quarter of the loop's vector instructions.  Exponents are non-negative: no overflow, and what
+    // underflows is what the running decay would have wiped out as well.
+    const float blk_decay = uniform(exp2f(l2 * (float)(kB * (nblk - 1 - it))));
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-      const ex8<E> zd = decay.apply(zf[k], 16 * k);
+      const ex8<E> zd = decay.apply(zf[k], 16 * k, blk_decay);
 #pragma unroll
       for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][k], zd, kv[t]);
     }
