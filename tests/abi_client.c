@@ -1,0 +1,26 @@
+/* A plain C client of the library's C ABI, built and run by tests/test_abi.py on a machine without a GPU:
+ * it only calls entry points that do host work or that return before any launch. */
+#include <stdio.h>
+#include <string.h>
+
+#include "la2.h"
+
+int main(void) {
+  la2_desc d;
+  la2_desc_dense(&d, 2, 3, 100, 64, LA2_BF16);
+  if (d.stride_n != 64 || d.stride_h != 6400 || d.stride_b != 19200) return 1;
+  if (la2_block_size(&d) != 64) return 2;
+  if (la2_fwd(&d, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_ERR_NULL) return 3;
+  d.head_dim = 100;
+  if (la2_fwd(&d, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_ERR_SHAPE) return 4;
+  la2_desc_dense(&d, 0, 3, 100, 64, LA2_F16);
+  if (la2_bwd(&d, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_OK) return 5;
+  if (la2_fwd_norm(&d, NULL, NULL, NULL, NULL, -1.0f, NULL, NULL, NULL, 0, NULL) != LA2_ERR_VALUE) return 6;
+  if (strcmp(la2_status_string(LA2_OK), "ok") != 0) return 7;
+  la2_set_chunk_tokens(256);
+  la2_desc_dense(&d, 1, 2, 1024, 128, LA2_BF16);
+  if (la2_workspace_bytes(&d, LA2_OP_FWD) != (size_t)2 * 4 * 128 * 128 * 4) return 8;
+  la2_set_chunk_tokens(0);
+  printf("abi client ok\n");
+  return 0;
+}

@@ -276,3 +276,15 @@ def test_fp16_is_accepted_except_by_the_comparison_kernel(lib):
     assert lib.la2_block_size(ctypes.byref(d)) == 32
     assert lib.la2_left_product_fwd(ctypes.byref(d), P, P, P, P, P, None) == E_DTYPE
     assert lib.la2_decode_step(0, 1, 64, binding.LA2_F16, None, None, None, None, None, None, None) == OK
+
+
+def test_a_c_program_links_and_calls_the_library(lib, tmp_path):
+    """include/la2.h + libla2.so from plain C (gcc), host-side calls only."""
+    import subprocess
+    exe = tmp_path / "abi_client"
+    libdir = os.path.dirname(binding.lib_path())
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "abi_client.c"), "-o", str(exe),
+                           "-L", libdir, "-l:libla2.so", "-Wl,-rpath," + libdir])
+    res = subprocess.run([str(exe)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert res.returncode == 0 and "abi client ok" in res.stdout, (res.returncode, res.stdout)
