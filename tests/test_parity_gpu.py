@@ -393,6 +393,70 @@ def test_hip_graph_capture_and_replay():
             torch.cuda.synchronize()
 
 
+def test_hip_graph_capture_of_the_other_entry_points():
+    """Segments with state hand-over (ragged: block kernels + short-run kernels), the normalised operator,
+    multi-token decode and a decode step in one captured graph; replays reproduce the eager results bit for bit."""
+    b, H, n, d = 2, 3, 300, 128
+    t = gpu(make_inputs(b, H, n, d, torch.bfloat16, seed=77))
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(78)
+    kv0 = (torch.randn((b, H, d, d), generator=gen) * 0.3).to(DEV)
+    dkvn = (torch.randn((b, H, d, d), generator=gen) * 0.3).to(DEV)
+    ws = torch.empty(max(256, binding.la2_workspace_bytes(t["q"], binding.LA2_OP_BWD_STATE)), dtype=torch.uint8, device=DEV)
+    T = 8
+    qm, km, vm = (t[x][:, :, :T].contiguous() for x in ("q", "k", "v"))
+
+    def run(out):
+        o, kvf = binding.la2_fwd_state(t["q"], t["k"], t["v"], t["lam"], kv_init=kv0, out=out["o"], kv_final=out["kvf"],
+                                       workspace=ws)
+        binding.la2_bwd_state(t["q"], t["k"], t["v"], t["d_o"], t["lam"], kv_init=kv0, d_kv_final=dkvn,
+                              out=out["grads"], d_kv_init=out["dkv0"], workspace=ws)
+        binding.la2_fwd_norm(t["q"], t["k"], t["v"], t["lam"], 1e-5, out=out["on"], rstd=out["rstd"], workspace=ws)
+        binding.la2_bwd_norm(t["q"], t["k"], t["v"], out["on"], out["rstd"], t["d_o"], t["lam"], out=out["gn"],
+                             d_u=out["du"], workspace=ws)
+        out["state"].copy_(kv0)
+        binding.la2_decode_multi(qm, km, vm, t["lam"], out["state"], out=out["om"])
+        binding.la2_decode_step(qm[:, :, 0].contiguous(), km[:, :, 0].contiguous(), vm[:, :, 0].contiguous(), t["lam"],
+                                out["state"], out=out["o1"])
+
+    def buffers():
+        like = lambda: torch.empty_like(t["q"])
+        return {"o": like(), "kvf": torch.empty_like(kv0), "grads": (like(), like(), like()), "dkv0": torch.empty_like(kv0),
+                "on": like(), "rstd": torch.empty((b, H, n), device=DEV), "gn": (like(), like(), like()), "du": like(),
+                "state": torch.empty_like(kv0), "om": torch.empty_like(qm), "o1": torch.empty_like(qm[:, :, 0])}
+
+    def flat(out):
+        return [out["o"], out["kvf"], *out["grads"], out["dkv0"], out["on"], out["rstd"], *out["gn"], out["du"],
+                out["state"], out["om"], out["o1"]]
+
+    # .contiguous() inside run() allocates: do those once outside the capture by warming up first
+    eager = buffers()
+    run(eager)
+    torch.cuda.synchronize()
+    captured = buffers()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(captured)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(captured)
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(3):
+        for x in flat(captured):
+            x.fill_(float("nan"))
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(flat(captured), flat(eager))):
+            assert torch.equal(got, ref), (replay, i)
+        scratch = buffers()            # eager work between the replays
+        run(scratch)
+        torch.cuda.synchronize()
+
+
 # ---- the O(n^2 d) left-product comparison kernel computes the same forward pass ---------------------------------------
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("n", [1, 31, 64, 128, 129, 200, 517, 1000])
