@@ -123,8 +123,8 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
  * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen:
  * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (64 for 16-bit data with head_dim
  * 64), the last seqlen % G positions run in a short-run kernel (the scan kernels form states after whole
- * blocks only).  seqlen == 0 copies the
- * state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if the input is NULL).
+ * blocks only).  seqlen == 0 copies the state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if
+ * the input is NULL).
  */
 la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
                          const float* lambda, const float* kv_init, void* o, float* kv_final,
@@ -181,8 +181,8 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
  * it holds the chunk start states of the (K, V) scan, which are (transposed) those of Algorithm 2's first
  * loop, so the backward pass skips recomputing them (one pass over K and V less).  NULL, or a problem that
  * needs no workspace: exactly la2_bwd_state.  Not to be used with the workspace of a la2_fwd_state call
- * that produced kv_final for a seqlen that is not a multiple of 64 (that call plans its chunks for the
- * whole blocks only).  fwd_workspace is 256-byte aligned (LA2_ERR_WORKSPACE otherwise) and only read.
+ * that produced kv_final for a seqlen that is not a multiple of G (see la2_fwd_state; that call plans its
+ * chunks for the whole blocks only).  fwd_workspace is 256-byte aligned (LA2_ERR_WORKSPACE otherwise) and only read.
  */
 la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v,
                          const void* d_o, const float* lambda, const float* kv_init,
