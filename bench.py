@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch (bytes), by workload
-MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786793 + 262147) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786790 + 262148) * 1024)}
 
 
 def flops_per_token_head(B, d, what):
