@@ -202,6 +202,16 @@ def test_longest_sequence_one_chain_spans_4_gib():
         binding.la2_fwd(y, y, y, lam)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_unscaled_values_and_slow_decay(dtype):
+    """V and dO of unit variance (configuration 4's value scale) with decays close to 1 over a long sequence: the
+    running state grows to its largest, which is what the 16-bit state operand (fp16: range 65504) has to hold."""
+    wl = workloads.Workload("unscaled", 1, 3, 3000, 128, dtype, seed=71, v_scale=1.0)
+    t = wl.tensors()
+    t["lam"] = torch.tensor([1.0, 0.9999, 0.99], dtype=torch.float32)
+    check_fwd_bwd(t, dtype, "unscaled %s" % dtype)
+
+
 def test_extreme_decays():
     """lambda = 1 (pure causal prefix sum) and a very small lambda (only the diagonal survives)."""
     for dtype in (torch.bfloat16, torch.float16, torch.float32):
