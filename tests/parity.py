@@ -40,4 +40,11 @@ def assert_close(name, got, ref, dtype):
     m, r = max_rel(x, ref), rms_rel(x, ref)
     assert m <= TOL[dtype], "%s: max rel err %.3e > %.1e (rms rel %.3e)" % (name, m, TOL[dtype], r)
     assert r <= RMS_TOL[dtype], "%s: rms rel err %.3e > %.1e" % (name, r, RMS_TOL[dtype])
+    # element by element: the same tolerance against each element's own magnitude plus a floor of a quarter of
+    # the tensor's largest magnitude (small elements of a signed sum have no relative accuracy of their own;
+    # the floor makes their bound four times tighter than the max-norm bound above)
+    if ref.size:
+        floor = 0.25 * float(np.max(np.abs(ref)))
+        e = float(np.max(np.abs(x - ref) / (np.abs(ref) + floor))) if floor > 0 else float(np.max(np.abs(x)))
+        assert e <= TOL[dtype], "%s: element-wise err %.3e > %.1e" % (name, e, TOL[dtype])
     return m, r
