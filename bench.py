@@ -22,6 +22,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# what a register-only loop of v_mfma_f32_32x32x16_bf16 reaches on this machine (1024 workgroups x 4 waves,
+# measured once with a microbenchmark; the clock under load is below the 2.4 GHz of the spec figure)
+MEASURED_MFMA_BF16_TFLOPS = 2267.0
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch (bytes), by workload
 MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786790 + 262148) * 1024)}
@@ -173,6 +176,10 @@ def main():
             "tokens_per_s": round(wl.tokens / (tot * 1e-3), 1),
             "tflops": round(fl / (tot * 1e-3) / 1e12, 2),
             "frac_bf16_peak": round(fl / (tot * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "frac_measured_mfma_peak": round(fl / (tot * 1e-3) / 1e12 / MEASURED_MFMA_BF16_TFLOPS, 4),
+            # algorithmic HBM bytes (8 d forward, 20 d backward per token-head, bf16) over the time
+            "algorithmic_GBs": round(28 * d * th / (tot * 1e-3) / 1e9, 1),
+            "frac_hbm_peak": round(28 * d * th / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
             "fwd_tflops": round(flops_per_token_head(B, d, "fwd") * th / (f_ms * 1e-3) / 1e12, 2),
             "bwd_tflops": round(flops_per_token_head(B, d, "bwd") * th / (b_ms * 1e-3) / 1e12, 2),
         })
