@@ -148,6 +148,13 @@ def main():
             fwd(g)
             bwd(g)
 
+    # ---- roofline of the dominant kernel: the forward scan at (16, 4K), one launch per call.  Measured first,
+    # after 300 launches that let the clocks settle; the headline below then starts on a machine in its
+    # steady state whatever --warmup says.
+    wl_r, g_r = sweep[1]
+    time_ms(lambda: fwd(g_r), 300)
+    roofline = dominant_kernel_roofline(wl_r, g_r, fwd, time_ms, binding, max(100, args.steps))
+
     # ---- the timed region: W warm-up steps, then exactly K steps ----------------------------------
     for _ in range(args.warmup):
         step()
@@ -186,9 +193,6 @@ def main():
     tps = [p["tokens_per_s"] for p in points]
     flatness = min(tps) / max(tps)
 
-    # ---- roofline of the dominant kernel: the forward scan at (16, 4K), one launch per call ---------------
-    wl_r, g_r = sweep[1]
-    roofline = dominant_kernel_roofline(wl_r, g_r, fwd, time_ms, binding, max(20, args.steps))
 
     # ---- the other configurations -------------------------------------------------------------------------
     others = []
