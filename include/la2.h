@@ -161,6 +161,25 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                         void* dk, void* dv, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Algorithm 1 / Algorithm 2 over PACKED sequences of different lengths (a batch without padding): the
+ * tensors are [total_positions, heads, head_dim]; sequence b occupies positions cu_seqlens[b] ..
+ * cu_seqlens[b + 1] - 1 and is a chain of its own (zero start state, no interaction with its neighbours).
+ *   desc        batch = number of sequences, seqlen = an upper bound of the sequence lengths (the launch is
+ *               planned for it: pass the longest length), stride_n / stride_h = elements between consecutive
+ *               positions / heads (dense packing: heads * head_dim and head_dim), stride_b ignored
+ *   cu_seqlens  in   device, int32 [batch + 1], non-decreasing, cu_seqlens[0] = offset of the first
+ *               sequence; lengths above desc->seqlen are a precondition violation (not read on the host)
+ * Everything else as for la2_fwd / la2_bwd, the workspace included (la2_workspace_bytes with this desc).
+ * A sequence of length 0 is fine.
+ */
+la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
+                          const void* v, const float* lambda, void* o, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
+                          const void* v, const void* d_o, const float* lambda, void* dq, void* dk, void* dv,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One step of the recurrent form (Sec. 3.2.1, recursive form), for every (batch, head):
  *     kv <- lambda_h * kv + k^T v          (state updated IN PLACE)
  *     o   = q kv                           (uses the UPDATED state, i.e. includes this token)

@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     la2_fwd_state,
     la2_bwd_state,
     la2_fwd_norm,
+    la2_fwd_varlen,
+    la2_bwd_varlen,
     la2_bwd_norm,
     la2_decode_step,
     la2_decode_multi,

@@ -71,6 +71,10 @@ def load():
     lib.la2_fwd_norm.restype = ctypes.c_int
     lib.la2_bwd_norm.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_norm.restype = ctypes.c_int
+    lib.la2_fwd_varlen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_fwd_varlen.restype = ctypes.c_int
+    lib.la2_bwd_varlen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd_varlen.restype = ctypes.c_int
     lib.la2_left_product_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.la2_left_product_fwd.restype = ctypes.c_int
     lib.la2_decode_multi.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -223,6 +227,64 @@ def la2_bwd_norm(q, k, v, o, rstd, d_o, lam, out=None, d_u=None, workspace=None)
         _check(lib.la2_bwd_norm(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                                 rstd.data_ptr(), d_o.data_ptr(), lam.data_ptr(), d_u.data_ptr(), dq.data_ptr(),
                                 dk.data_ptr(), dv.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
+    return dq, dk, dv
+
+
+def _varlen_desc(q, cu_seqlens, max_seqlen):
+    """Descriptor of packed sequences: q is [total_positions, heads, head_dim], cu_seqlens int32 [batch + 1]."""
+    if q.dim() != 3 or q.stride(2) != 1:
+        raise ValueError("la2: packed tensors are [total_positions, heads, head_dim] with unit feature stride")
+    if cu_seqlens.dtype != torch.int32 or cu_seqlens.dim() != 1 or not cu_seqlens.is_contiguous() or not cu_seqlens.is_cuda:
+        raise ValueError("la2: cu_seqlens must be a contiguous int32 vector on the GPU")
+    return la2_desc(cu_seqlens.numel() - 1, q.shape[1], int(max_seqlen), q.shape[2], _dtype_code(q), 0,
+                    0, q.stride(1), q.stride(0))
+
+
+def _varlen_workspace(q, desc, op, workspace):
+    need = int(load().la2_workspace_bytes(ctypes.byref(desc), op))
+    if need == 0:
+        return None, 0, None
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if workspace.numel() * workspace.element_size() < need:
+        raise ValueError("la2: workspace too small (%d < %d bytes)" % (workspace.numel() * workspace.element_size(), need))
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
+
+
+def la2_fwd_varlen(q, k, v, lam, cu_seqlens, max_seqlen, out=None, workspace=None):
+    """o for packed sequences of different lengths: q, k, v [total_positions, heads, head_dim]; sequence b is
+    positions cu_seqlens[b] .. cu_seqlens[b + 1] - 1; max_seqlen bounds the lengths."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_varlen: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    desc = _varlen_desc(q, cu_seqlens, max_seqlen)
+    ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_FWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_varlen(ctypes.byref(desc), cu_seqlens.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                  lam.data_ptr(), out.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
+    return out
+
+
+def la2_bwd_varlen(q, k, v, d_o, lam, cu_seqlens, max_seqlen, out=None, workspace=None):
+    """(dq, dk, dv) for packed sequences of different lengths (see la2_fwd_varlen)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd_varlen: tensors must live on the GPU")
+    _same_layout(q, k, v, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv)
+    desc = _varlen_desc(q, cu_seqlens, max_seqlen)
+    ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_BWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd_varlen(ctypes.byref(desc), cu_seqlens.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                  d_o.data_ptr(), lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr,
+                                  ws_bytes, _stream(q)))
     return dq, dk, dv
 
 

@@ -105,10 +105,14 @@ struct ScanArgs {
   // Norm epilogue (forward scans): r of every position goes here, the output rows are scaled by it
   float* rstd = nullptr;
   float eps = 0.f;
+  // packed sequences of different lengths: device array of batch + 1 position offsets, or nullptr
+  const int32_t* cu = nullptr;
 };
 
-la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace) {
+la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace,
+                            const int32_t* cu = nullptr) {
   la2::ScanParams p{};
+  p.cu_seqlens = cu;
   p.nscan = 1;
   p.state_transposed = 0;
   p.lambda = lambda;
@@ -123,9 +127,10 @@ la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lamb
 
 // chunk start states of the scan with key-like operand y and value-like operand z -> workspace
 la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const void* y, const void* z,
-                       const float* init, bool init_tr, const float* lambda, void* workspace, hipStream_t s) {
+                       const float* init, bool init_tr, const float* lambda, void* workspace, hipStream_t s,
+                       const int32_t* cu = nullptr) {
   if (pl.nchunks <= 1) return LA2_OK;
-  la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  la2::ScanParams p = base_params(d, pl, lambda, workspace, cu);
   p.y[0] = y; p.z[0] = z;
   p.init[0] = init; p.init_transposed = init_tr ? 1 : 0;
   hipError_t e = is16(d->dtype) ? la2::launch_chunk_states_bf16(d->dtype, d->head_dim, reverse, p, s)
@@ -139,10 +144,10 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
                     void* workspace, hipStream_t s) {
   const bool saved = a.saved_states != nullptr && pl.nchunks > 1;
   if (!saved) {
-    la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s);
+    la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s, a.cu);
     if (st != LA2_OK) return st;
   }
-  la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  la2::ScanParams p = base_params(d, pl, lambda, workspace, a.cu);
   if (saved) {
     p.states = const_cast<float*>(a.saved_states);   // read only
     p.state_transposed = a.saved_tr ? 1 : 0;
@@ -161,9 +166,9 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
 // state pre-pass, one launch (16-bit path).
 la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanArgs& a0, const ScanArgs& a1,
                                  const float* lambda, void* workspace, hipStream_t s) {
-  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s);
+  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s, a0.cu);
   if (st != LA2_OK) return st;
-  la2::ScanParams p = base_params(d, pl, lambda, workspace);
+  la2::ScanParams p = base_params(d, pl, lambda, workspace, a0.cu);
   p.nscan = 2;
   p.state_transposed = 2;   // scan 1 starts from the transposed state
   p.init[0] = a0.init; p.init[1] = a1.init;
@@ -416,6 +421,50 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                                 reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return LA2_ERR_LAUNCH;
   return la2_bwd(desc, q, k, v, d_u, lambda, dq, dk, dv, workspace, workspace_bytes, hip_stream);
+}
+
+la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
+                          const void* v, const float* lambda, void* o, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!cu_seqlens || !q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
+      !aligned(cu_seqlens, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const Plan pl = make_plan(desc);
+  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace || !aligned(workspace, 256)))
+    return LA2_ERR_WORKSPACE;
+  ScanArgs a{q, k, v, o};
+  a.cu = cu_seqlens;
+  return run_scan(desc, pl, false, a, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
+                          const void* v, const void* d_o, const float* lambda, void* dq, void* dk, void* dv,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!cu_seqlens || !q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
+      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4) || !aligned(cu_seqlens, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const Plan pl = make_plan(desc);
+  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace || !aligned(workspace, 256)))
+    return LA2_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  // the three scans of la2_bwd, each chain a sequence of its own length
+  ScanArgs for_dq{d_o, v, k, dq}, for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
+  for_dq.cu = for_dv.cu = for_dk.cu = cu_seqlens;
+  for_dk.init_tr = true;
+  st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  if (is16(desc->dtype)) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, workspace, s);
+  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
 }
 
 la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,

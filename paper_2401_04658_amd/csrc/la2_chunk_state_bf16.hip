@@ -32,8 +32,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
   if (REV ? (chunk == 0) : (chunk == p.nchunks - 1)) return;  // no successor needs it
   const int bi = chain / p.heads, hi = chain % p.heads;
-  const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
-  const int n = p.n;
+  int64_t base;
+  int n;
+  chain_extent(p, bi, hi, base, n);
   const float l2 = log2f(p.lambda[hi]);
   const int nblocks = (n + kB - 1) / kB;
   const int cb = p.chunk_tokens / kB;
@@ -122,22 +123,25 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
 // The carried state decays by lambda^(chunk length): all chunks are chunk_tokens long except the last
 // one of the sequence, which a reverse scan passes first.
 __global__ void state_scan_kernel(float* states, const float* lambda, int heads, int nchunks, int chunk_tokens,
-                                  int dd, int reverse, const float* init, int init_tr, int d, int n) {
+                                  int dd, int reverse, const float* init, int init_tr, int d, int n,
+                                  const int32_t* cu_seqlens) {
   const int chain = blockIdx.y;
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= dd) return;
+  if (cu_seqlens != nullptr) n = cu_seqlens[chain / heads + 1] - cu_seqlens[chain / heads];   // this sequence's length
+  const int nch = (n + chunk_tokens - 1) / chunk_tokens;   // chunks this chain really has (<= nchunks)
   const float l2 = log2f(lambda[chain % heads]);
   const float lamFull = exp2f(l2 * (float)chunk_tokens);
-  const float lamLast = exp2f(l2 * (float)(n - (nchunks - 1) * chunk_tokens));
+  const float lamLast = exp2f(l2 * (float)(n - (nch - 1) * chunk_tokens));
   float* s = states + (int64_t)chain * nchunks * dd + e;
   float g = 0.f;
   if (init != nullptr) g = init[(int64_t)chain * dd + (init_tr ? (e % d) * d + e / d : e)];
-  for (int i = 0; i < nchunks; i++) {
-    const int j = reverse ? nchunks - 1 - i : i;
-    const bool last = (i == nchunks - 1);
+  for (int i = 0; i < nch; i++) {
+    const int j = reverse ? nch - 1 - i : i;
+    const bool last = (i == nch - 1);
     const float loc = last ? 0.f : s[(int64_t)j * dd];
     s[(int64_t)j * dd] = g;
-    g = (j == nchunks - 1 ? lamLast : lamFull) * g + loc;
+    g = (j == nch - 1 ? lamLast : lamFull) * g + loc;
   }
 }
 
@@ -172,7 +176,7 @@ hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hi
   const int dd = head_dim * head_dim;
   dim3 g((dd + 255) / 256, chains), b(256);
   hipLaunchKernelGGL(state_scan_kernel, g, b, 0, s, p.states, p.lambda, p.heads, p.nchunks, p.chunk_tokens, dd,
-                     reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n);
+                     reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n, p.cu_seqlens);
   return hipGetLastError();
 }
 

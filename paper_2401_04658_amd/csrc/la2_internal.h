@@ -50,7 +50,23 @@ struct ScanParams {
   // stored, and r goes to rstd[chain * n + position] (fp32).
   float* rstd;
   float eps;
+  // Packed sequences of different lengths (nullptr: a dense batch).  Device array of batch + 1 position
+  // offsets: sequence b is positions cu_seqlens[b] .. cu_seqlens[b + 1] - 1 of a [total, heads, d] tensor
+  // (stride_b unused); n is then the longest sequence's length, what the launch is planned for.
+  const int32_t* cu_seqlens;
 };
+
+// Element offset of chain (bi, hi)'s first position and the chain's length.
+__device__ __forceinline__ void chain_extent(const ScanParams& p, int bi, int hi, int64_t& base, int& n) {
+  if (p.cu_seqlens != nullptr) {
+    const int first = p.cu_seqlens[bi];
+    n = p.cu_seqlens[bi + 1] - first;
+    base = (int64_t)first * p.stride_n + (int64_t)hi * p.stride_h;
+  } else {
+    n = p.n;
+    base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
+  }
+}
 
 // Norm epilogue, shared by the scan kernels.  A 32 x 32 output tile sits in MFMA accumulators transposed
 // (lane = position l32, 16 features per lane, the other 16 in lane l32 + 32); the NP waves that hold the

@@ -48,8 +48,9 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   }
   const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
   const int bi = chain / p.heads, hi = chain % p.heads;
-  const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
-  const int n = p.n;
+  int64_t base;
+  int n;
+  chain_extent(p, bi, hi, base, n);
   const uint32_t stride_n = (uint32_t)p.stride_n;
   const uint32_t chain_bytes = ((uint32_t)(n - 1) * stride_n + D) * 2u;
   const __amdgpu_buffer_rsrc_t bw =

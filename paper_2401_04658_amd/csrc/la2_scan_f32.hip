@@ -87,8 +87,9 @@ __global__ __launch_bounds__(2 * D, 1) void scan_f32_kernel(ScanParams p) {
   const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
   if (STATE_ONLY && (REV ? (chunk == 0) : (chunk == p.nchunks - 1))) return;  // no later chunk needs it
   const int bi = chain / p.heads, hi = chain % p.heads;
-  const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
-  const int n = p.n;
+  int64_t base;
+  int n;
+  chain_extent(p, bi, hi, base, n);
   const uint32_t stride_n = (uint32_t)p.stride_n;
   const float l2 = log2f(p.lambda[hi]);
   const float lamB = exp2f(l2 * (float)kB);

@@ -288,3 +288,28 @@ def test_a_c_program_links_and_calls_the_library(lib, tmp_path):
                            "-L", libdir, "-l:libla2.so", "-Wl,-rpath," + libdir])
     res = subprocess.run([str(exe)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
     assert res.returncode == 0 and "abi client ok" in res.stdout, (res.returncode, res.stdout)
+
+
+def test_varlen_entry_points_validate_before_any_launch(lib):
+    d = dense(lib, 5, 2, 300, 64, binding.LA2_BF16)      # 5 sequences of at most 300 positions, [total, H, d] packing
+    d.stride_b, d.stride_h, d.stride_n = 0, 64, 128
+    ref = ctypes.byref(d)
+    fv = lambda cu=P, q=P, o=P: lib.la2_fwd_varlen(ref, cu, q, P, P, P, o, None, 0, None)
+    bv = lambda cu=P, dq=P: lib.la2_bwd_varlen(ref, cu, P, P, P, P, P, dq, P, P, None, 0, None)
+    assert fv(cu=None) == E_NULL and fv(q=None) == E_NULL and bv(cu=None) == E_NULL and bv(dq=None) == E_NULL
+    assert fv(cu=P + 2) == E_ALIGN and fv(o=P + 8) == E_ALIGN and bv(dq=P + 4) == E_ALIGN
+    d.head_dim = 80
+    assert fv() == E_SHAPE and bv() == E_SHAPE
+    d.head_dim = 64
+    d.batch = 0
+    assert fv(cu=None, q=None) == OK and bv(cu=None) == OK
+    # few long sequences: the workspace of the dense plan for (batch, max_seqlen)
+    try:
+        lib.la2_set_chunk_tokens(256)
+        d = dense(lib, 2, 2, 1024, 128, binding.LA2_BF16)
+        d.stride_b, d.stride_h, d.stride_n = 0, 128, 256
+        ref = ctypes.byref(d)
+        assert lib.la2_workspace_bytes(ref, 0) == 4 * 4 * 128 * 128 * 4
+        assert fv() == E_WS and bv() == E_WS
+    finally:
+        lib.la2_set_chunk_tokens(0)

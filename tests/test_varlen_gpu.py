@@ -1,0 +1,119 @@
+"""GPU parity of la2_fwd_varlen / la2_bwd_varlen (packed sequences of different lengths) against the fp64 oracle:
+every sequence is a chain of its own, so the reference is the oracle applied sequence by sequence."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_04658_amd import binding, workloads
+from parity import assert_close, to64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+    yield
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+
+
+def packed_inputs(lengths, H, d, dtype, seed, lead=0, trail=0):
+    """q, k, v, d_o as [lead + sum(lengths) + trail, H, d] (rows outside the sequences belong to nobody)."""
+    total = lead + int(sum(lengths)) + trail
+    wl = workloads.Workload("packed", 1, H, max(total, 1), d, dtype, seed=seed, backward=True)
+    t = wl.tensors()
+    out = {name: t[name][0, :, :total].permute(1, 0, 2).contiguous() for name in ("q", "k", "v", "d_o")}
+    out["lam"] = t["lam"]
+    cu = np.concatenate([[lead], lead + np.cumsum(lengths)]).astype(np.int32)
+    return out, torch.from_numpy(cu)
+
+
+def check_packed(lengths, H, d, dtype, seed, lead=0, trail=0, lam=None):
+    t, cu = packed_inputs(lengths, H, d, dtype, seed, lead, trail)
+    if lam is not None:
+        t["lam"] = torch.as_tensor(lam, dtype=torch.float32).reshape(-1).expand(H).contiguous()
+    g = {k: v.to(DEV) for k, v in t.items()}
+    cu_g = cu.to(DEV)
+    max_len = int(max(lengths)) if len(lengths) else 0
+    o = torch.full_like(g["q"], float("nan"))
+    grads = tuple(torch.full_like(g["q"], float("nan")) for _ in range(3))
+    binding.la2_fwd_varlen(g["q"], g["k"], g["v"], g["lam"], cu_g, max_len, out=o)
+    binding.la2_bwd_varlen(g["q"], g["k"], g["v"], g["d_o"], g["lam"], cu_g, max_len, out=grads)
+    torch.cuda.synchronize()
+    lam64 = to64(t["lam"])
+    for b, n in enumerate(lengths):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        if n == 0:
+            continue
+        seq = {name: to64(t[name][lo:hi]).transpose(1, 0, 2)[None] for name in ("q", "k", "v", "d_o")}   # [1, H, n, d]
+        tag = "lengths %s seq %d (n %d) d%d %s" % (list(lengths), b, n, d, dtype)
+        ref_o = oracle.fwd_direct(seq["q"], seq["k"], seq["v"], lam64)
+        assert_close(tag + " o", o[lo:hi].permute(1, 0, 2)[None], ref_o, dtype)
+        for name, got, ref in zip(("dq", "dk", "dv"), grads,
+                                  oracle.bwd_direct(seq["q"], seq["k"], seq["v"], seq["d_o"], lam64)):
+            assert_close(tag + " " + name, got[lo:hi].permute(1, 0, 2)[None], ref, dtype)
+    # rows that belong to no sequence are not written
+    for x in (o,) + grads:
+        assert torch.isnan(x[: int(cu[0])].float()).all() and torch.isnan(x[int(cu[-1]):].float()).all()
+        assert torch.isfinite(x[int(cu[0]): int(cu[-1])].float()).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+def test_mixed_lengths(dtype, d):
+    check_packed([70, 0, 1, 31, 32, 100, 517, 64, 3], 3, d, dtype, seed=800 + d, lam=[0.5, 0.93, 1.0])
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 128), (torch.float16, 128)])
+@pytest.mark.parametrize("chunk", [64, 192])
+def test_mixed_lengths_chunked(dtype, d, chunk):
+    """Few sequences, long ones among them: the launch is cut into sequence chunks planned for the longest;
+    shorter sequences use fewer of them."""
+    binding.la2_set_chunk_tokens(chunk)
+    check_packed([700, 130, 64, 1000, 5, 0, 383], 2, d, dtype, seed=810 + d + chunk, lam=[0.8, 0.99])
+
+
+def test_offset_first_sequence_and_unused_tail():
+    check_packed([200, 45], 2, 128, torch.bfloat16, seed=820, lead=7, trail=9)
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_scan_variants(variant):
+    binding.la2_set_scan_variant(variant)
+    check_packed([129, 64, 300], 2, 128, torch.bfloat16, seed=830 + variant)
+
+
+def test_equal_lengths_reproduce_the_dense_batch_bit_for_bit():
+    b, H, n, d = 3, 4, 260, 128
+    t = workloads.Workload("dense", b, H, n, d, torch.bfloat16, seed=840).tensors()
+    g = {k: v.to(DEV) for k, v in t.items()}
+    o = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
+    grads = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
+    pk = {name: g[name].permute(0, 2, 1, 3).reshape(b * n, H, d).contiguous() for name in ("q", "k", "v", "d_o")}
+    cu = torch.arange(0, (b + 1) * n, n, dtype=torch.int32, device=DEV)
+    o2 = binding.la2_fwd_varlen(pk["q"], pk["k"], pk["v"], g["lam"], cu, n)
+    grads2 = binding.la2_bwd_varlen(pk["q"], pk["k"], pk["v"], pk["d_o"], g["lam"], cu, n)
+    torch.cuda.synchronize()
+    unpack = lambda x: x.reshape(b, n, H, d).permute(0, 2, 1, 3)
+    assert torch.equal(unpack(o2), o)
+    for a, ref in zip(grads2, grads):
+        assert torch.equal(unpack(a), ref)
+
+
+def test_empty_cases_and_validation():
+    lam = torch.ones(2, device=DEV)
+    x = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device=DEV)
+    cu = torch.zeros(1, dtype=torch.int32, device=DEV)          # no sequences
+    assert binding.la2_fwd_varlen(x, x, x, lam, cu, 0).shape == x.shape
+    cu = torch.zeros(4, dtype=torch.int32, device=DEV)          # three empty sequences
+    assert binding.la2_fwd_varlen(x, x, x, lam, cu, 0).shape == x.shape
+    y = torch.zeros((10, 2, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(ValueError):
+        binding.la2_fwd_varlen(y, y, y, lam, cu.long(), 10)     # cu_seqlens must be int32
+    with pytest.raises(ValueError):
+        binding.la2_fwd_varlen(y[None], y[None], y[None], lam, cu, 10)   # packed tensors are 3-dimensional
