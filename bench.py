@@ -238,6 +238,22 @@ def main():
                        "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1),
                        "plain_fwd_ms": round(pf_ms, 4), "plain_bwd_ms": round(pb_ms, 4)})
         del rstd, d_u
+    # a packed batch of sequences of different lengths (la2_fwd_varlen / la2_bwd_varlen): 65,536 positions as
+    # 1 x 8192, 2 x 4096, 4 x 2048, 8 x 1024, 16 x 512, 32 x 256 and 128 x 128 positions, longest first
+    lengths = [8192] + [4096] * 2 + [2048] * 4 + [1024] * 8 + [512] * 16 + [256] * 32 + [128] * 128
+    wl_p = workloads.Workload("packed_lengths_128_to_8192_h16_d128", 1, 16, sum(lengths), 128, torch.bfloat16, seed=34)
+    tp = wl_p.tensors()
+    gp = {n_: tp[n_][0].permute(1, 0, 2).contiguous().to(dev) for n_ in ("q", "k", "v", "d_o")}   # [total, H, d]
+    gp["lam"] = tp["lam"].to(dev)
+    cu = torch.tensor([0] + list(__import__("itertools").accumulate(lengths)), dtype=torch.int32, device=dev)
+    op_, gr_ = torch.empty_like(gp["q"]), tuple(torch.empty_like(gp["q"]) for _ in range(3))
+    f_ms = time_ms(lambda: binding.la2_fwd_varlen(gp["q"], gp["k"], gp["v"], gp["lam"], cu, max(lengths), out=op_),
+                   iters, warm=40)
+    b_ms = time_ms(lambda: binding.la2_bwd_varlen(gp["q"], gp["k"], gp["v"], gp["d_o"], gp["lam"], cu, max(lengths),
+                                                  out=gr_), iters, warm=40)
+    packed = {"workload": wl_p.name, "sequences": len(lengths), "tokens": sum(lengths), "fwd_ms": round(f_ms, 4),
+              "bwd_ms": round(b_ms, 4), "tokens_per_s": round(sum(lengths) / ((f_ms + b_ms) * 1e-3), 1)}
+    del gp, op_, gr_, tp
     # the same point in the library's other two data types (fp16: the same kernels as bf16; fp32: fp32 MFMA)
     other_dtypes = []
     wl1 = workloads.CONFIG3[1]
@@ -362,6 +378,7 @@ def main():
         "saved_forward_states": saved,
         "normalised_operator": normed,
         "other_dtypes": other_dtypes,
+        "packed_varlen": packed,
         "left_product_comparison": crossover,
         "decode": decode,
         "roofline": roofline,
