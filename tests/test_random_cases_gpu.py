@@ -1,6 +1,6 @@
 """Seeded random sweep over the library's options, each case against the fp64 oracle: data type, head_dim,
 batch, heads, sequence length (ragged more often than not), sequence-chunk size, storage layout, decay,
-start / final states and their gradients, and the Norm epilogue.  The fixed cases elsewhere pick the corners
+start / final states and their gradients, the Norm epilogue, multi-token decode and packed variable-length batches.  The fixed cases elsewhere pick the corners
 by hand; this one looks for combinations nobody thought of."""
 import numpy as np
 import pytest
@@ -34,7 +34,7 @@ def draw_case(i):
     chunk = int(rng.choice([0, 0, 64, 128, 192, 320]))
     layout = str(rng.choice(["bhnd", "bnhd", "padded"]))
     lam = rng.choice([1.0, 0.999, 0.97, 0.8, 0.3, 1e-3], size=H).astype(np.float32)
-    mode = str(rng.choice(["plain", "state", "state_nofinal", "norm", "decode_multi"]))
+    mode = str(rng.choice(["plain", "state", "state_nofinal", "norm", "decode_multi", "varlen"]))
     variant = int(rng.choice([0, 1, 2]))
     return dict(dtype=dtype, d=d, b=b, H=H, n=n, chunk=chunk, layout=layout, lam=lam, mode=mode, variant=variant,
                 seed=int(rng.integers(0, 1 << 30)))
@@ -52,7 +52,7 @@ def place(x, layout):
     return store[..., :d]
 
 
-@pytest.mark.parametrize("i", range(160))
+@pytest.mark.parametrize("i", range(200))
 def test_random_case(i):
     c = draw_case(i)
     dtype, d, b, H, n = c["dtype"], c["d"], c["b"], c["H"], c["n"]
@@ -70,6 +70,27 @@ def test_random_case(i):
     binding.la2_set_scan_variant(c["variant"])
     q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
 
+    if c["mode"] == "varlen":   # the batch rows become packed sequences of random lengths <= n
+        rng = np.random.default_rng(c["seed"])
+        lengths = [int(x) for x in rng.integers(0, n + 1, size=b + 2)]
+        lengths[int(rng.integers(0, len(lengths)))] = n           # one of them reaches the stated maximum
+        total = sum(lengths)
+        tt = workloads.Workload("random", 1, H, max(total, 1), d, dtype, seed=c["seed"], backward=True).tensors()
+        pk = {name: tt[name][0, :, :total].permute(1, 0, 2).contiguous() for name in ("q", "k", "v", "d_o")}
+        gp = {name: pk[name].to(DEV) for name in pk}
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device=DEV)
+        o = binding.la2_fwd_varlen(gp["q"], gp["k"], gp["v"], g["lam"], cu, n)
+        grads = binding.la2_bwd_varlen(gp["q"], gp["k"], gp["v"], gp["d_o"], g["lam"], cu, n)
+        torch.cuda.synchronize()
+        lo = 0
+        for m in lengths:
+            if m > 0:
+                sq = {name: to64(pk[name][lo:lo + m]).transpose(1, 0, 2)[None] for name in pk}
+                assert_close(tag + " o", o[lo:lo + m].permute(1, 0, 2)[None], oracle.fwd_direct(sq["q"], sq["k"], sq["v"], lam), dtype)
+                for name, got, ref in zip(("dq", "dk", "dv"), grads, oracle.bwd_direct(sq["q"], sq["k"], sq["v"], sq["d_o"], lam)):
+                    assert_close(tag + " " + name, got[lo:lo + m].permute(1, 0, 2)[None], ref, dtype)
+            lo += m
+        return
     if c["mode"] == "plain":
         o = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
         grads = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
