@@ -26,8 +26,8 @@ constexpr int kBH = 32;
 // (plain) workgroups fit on a compute unit.
 //
 // NORM: the Norm epilogue of eq. (2) on a forward scan: the four waves exchange the sums of squares of
-// their quarter rows through LDS (one more workgroup barrier per block), scale the finished tile and
-// wave 0 stores r.  The LDS is full, so the room for the exchange is taken from the output staging,
+// their quarter rows through LDS (under the block's one barrier, which moves behind the intra-block
+// product for this), scale the finished tile and wave 0 stores r.  The LDS is full, so the room for the exchange is taken from the output staging,
 // which then handles the block in two halves of 16 positions.
 template <typename E, bool REV, bool TWIN, int NBUF, bool NORM = false>
 __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
@@ -254,14 +254,17 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
       for (int t = 2 * h; t < 2 * h + 2; t++) pin(kv[t]);
       LA2_SLOT_END();
     }
+    // NORM: the block's one barrier comes after phase 4 instead, where it also publishes the rows' sums of squares
     if (has_next) {
       __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
       loader.zero_tail(sNext, nb);
-      lds_barrier();
+      if (!NORM) {
+        lds_barrier();
 #pragma unroll
-      for (int ks = 0; ks < AHEAD; ks++) {
-        xa[ks] = la.read_row(sNext[xi], 0, ks);
-        ya[ks] = la.read_row(sNext[yi], 0, ks);
+        for (int ks = 0; ks < AHEAD; ks++) {
+          xa[ks] = la.read_row(sNext[xi], 0, ks);
+          ya[ks] = la.read_row(sNext[yi], 0, ks);
+        }
       }
     }
     LA2_SLOT_END();
@@ -273,11 +276,19 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
     pin(inter);
     LA2_SLOT_END();
     if constexpr (NORM) {
-      // Two exchange buffers, by block parity: a wave that runs ahead into the next block (whose last
-      // block has no tile barrier) must not overwrite sums that a slower wave has yet to read.
+      // Two exchange buffers, by block parity: a wave that runs ahead into the next block must not
+      // overwrite sums that a slower wave has yet to read.  The barrier is the block's only one: it also
+      // makes the next block's tiles visible and frees this block's.
       float* const red = sRed + (it & 1) * (32 * 4);
       norm_publish<4>(inter, red, l32, hh, dvt);
       lds_barrier();
+      if (has_next) {
+#pragma unroll
+        for (int ks = 0; ks < AHEAD; ks++) {
+          xa[ks] = la.read_row(sNext[xi], 0, ks);
+          ya[ks] = la.read_row(sNext[yi], 0, ks);
+        }
+      }
       const float r = norm_collect<4>(red, l32, 1.f / (float)D, p.eps);
 #pragma unroll
       for (int v = 0; v < 16; v++) inter[v] *= r;
