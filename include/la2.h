@@ -31,7 +31,11 @@
  *     dtype LA2_F32: fp32 storage and fp32 arithmetic throughout.
  *   - seqlen may be any value >= 0 (a ragged last block is masked) as long as one (batch, head) chain stays
  *     addressable with 32-bit byte offsets: (seqlen + 128) * stride_n * sizeof(element) <= 2^32, else
- *     LA2_ERR_SHAPE (dense bf16, head_dim 128: up to 16,777,088 positions).  head_dim is 64 or 128.
+ *     LA2_ERR_SHAPE (dense bf16, head_dim 128: up to 16,777,088 positions).
+ *   - head_dim is 64, 96, 128 or 256.  64 and 128 are the tuned paths and have every entry point.  96 and 256
+ *     have la2_fwd / la2_bwd, the state and packed variants and the decode entries: for the 16-bit types one
+ *     MFMA block kernel, for fp32 the token-by-token recurrence (slow: meant for checking, not for training;
+ *     no packed variant); the Norm entries and the left-product comparison return LA2_ERR_SHAPE for them.
  *   - Argument errors are detected on the host BEFORE anything is launched and are reported through
  *     the return code; nothing aborts.  A failed launch is reported as LA2_ERR_LAUNCH.
  */
@@ -65,7 +69,7 @@ typedef struct {
   int32_t batch;
   int32_t heads;
   int32_t seqlen;
-  int32_t head_dim; /* 64 or 128 */
+  int32_t head_dim; /* 64, 96, 128 or 256 */
   int32_t dtype;    /* la2_dtype */
   int32_t reserved; /* must be 0 */
   int64_t stride_b; /* elements between consecutive batches   */
@@ -122,8 +126,8 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
  * as for la2_fwd / la2_bwd, which are these functions with NULL states.  State pointers are 16-byte
  * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen:
  * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (64 for 16-bit data with head_dim
- * 64), the last seqlen % G positions run in a short-run kernel (the scan kernels form states after whole
- * blocks only).  seqlen == 0 copies the state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if
+ * 64; head_dim 96 and 256 have no such granule), the last seqlen % G positions run in a short-run kernel (the
+ * scan kernels of head_dim 64 and 128 form states after whole blocks only).  seqlen == 0 copies the state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if
  * the input is NULL).
  */
 la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
@@ -187,7 +191,7 @@ la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const
  *   lambda    in      device, fp32 [heads]
  *   kv_state  in/out  device, dense fp32 [batch, heads, head_dim (key), head_dim (value)]
  *   o         out     device, dense [batch, heads, head_dim], dtype qkv_dtype
- * All pointers 16-byte aligned.  head_dim is 64 or 128.
+ * All pointers 16-byte aligned.  head_dim is 64, 96, 128 or 256.
  */
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype,
                            const void* q, const void* k, const void* v, const float* lambda,
@@ -227,7 +231,7 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
  *   lambda    in      device, fp32 [heads]
  *   kv_state  in/out  device, fp32 dense [batch, heads, head_dim, head_dim], updated in place
  *   o         out     device, dense [batch, heads, ntokens, head_dim], dtype qkv_dtype
- * All pointers 16-byte aligned.  head_dim is 64 or 128; ntokens <= 65536.  Same result as ntokens calls of
+ * All pointers 16-byte aligned.  head_dim is 64, 96, 128 or 256; ntokens <= 65536.  Same result as ntokens calls of
  * la2_decode_step up to rounding.  16-bit data: block kernels with bf16 / fp16 matrix operands as in la2_fwd
  * (whole blocks through la2_fwd_state's kernels with the state in place when batch * heads fills the device
  * without a workspace; a shorter run or the rest in one launch of a small block kernel that hands out the exact

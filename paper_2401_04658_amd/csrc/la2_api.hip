@@ -12,7 +12,14 @@ int g_scan_variant = 0;           // la2_set_scan_variant()
 // The block kernels form states after whole blocks only: 32 positions for the kernels that take states
 // (half-block 16-bit kernel for head_dim 128, fp32 kernels), 64 for the full-block 16-bit kernel of head_dim 64.
 bool is16(int dtype) { return dtype == LA2_BF16 || dtype == LA2_F16; }
-int state_granule(const la2_desc* d) { return (is16(d->dtype) && d->head_dim == 64) ? 64 : 32; }
+// Head dimensions 96 and 256 have kernels of their own: one 16-bit block kernel that is exact at a ragged end
+// (no granule), and the token recurrence for fp32.
+bool wide(int head_dim) { return head_dim == 96 || head_dim == 256; }
+bool supported_head_dim(int head_dim) { return head_dim == 64 || head_dim == 128 || wide(head_dim); }
+int state_granule(const la2_desc* d) {
+  if (wide(d->head_dim)) return 1;
+  return (is16(d->dtype) && d->head_dim == 64) ? 64 : 32;
+}
 
 int device_cu_count() {
   static int cached = 0;
@@ -33,7 +40,7 @@ la2_status check_desc(const la2_desc* d) {
   if (d == nullptr) return LA2_ERR_NULL;
   if (d->dtype != LA2_F32 && !is16(d->dtype)) return LA2_ERR_DTYPE;
   if (d->batch < 0 || d->heads < 0 || d->seqlen < 0 || d->reserved != 0) return LA2_ERR_SHAPE;
-  if (d->head_dim != 64 && d->head_dim != 128) return LA2_ERR_SHAPE;
+  if (!supported_head_dim(d->head_dim)) return LA2_ERR_SHAPE;
   if ((int64_t)d->batch * d->heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
   const int64_t per16 = 16 / elem_size(d->dtype);
   if (d->stride_b < 0 || d->stride_h < 0 || d->stride_n < d->head_dim) return LA2_ERR_STRIDE_ALIGN;
@@ -67,6 +74,7 @@ Plan make_plan(const la2_desc* d) {
   const int nblocks = (d->seqlen + B - 1) / B;
   Plan pl{1, nblocks > 0 ? nblocks * B : B, 0};
   if (chains == 0 || nblocks <= 1) return pl;
+  if (wide(d->head_dim) && !is16(d->dtype)) return pl;   // token recurrence: one workgroup walks the chain
   int cb;  // blocks per chunk
   if (g_chunk_tokens_override > 0) {
     cb = (g_chunk_tokens_override + B - 1) / B;
@@ -80,7 +88,8 @@ Plan make_plan(const la2_desc* d) {
     // Chunking shortens the scan's sequential loop from nblocks to cb blocks but adds the pre-pass (about a
     // third of a scan block per block) and two more launches (about 15 us): not worth it for short sequences.
     // Measured times of one block of the sequential loop, in microseconds.
-    const float t_blk = is16(d->dtype) ? (d->head_dim == 128 ? 2.1f : 1.15f) : (d->head_dim == 128 ? 10.f : 3.f);
+    const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 6.f : d->head_dim == 64 ? 1.15f : 2.1f)
+                                       : (d->head_dim == 128 ? 10.f : 3.f);
     if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) return pl;
   }
   if (cb >= nblocks) return pl;
@@ -133,8 +142,9 @@ la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const vo
   la2::ScanParams p = base_params(d, pl, lambda, workspace, cu);
   p.y[0] = y; p.z[0] = z;
   p.init[0] = init; p.init_transposed = init_tr ? 1 : 0;
-  hipError_t e = is16(d->dtype) ? la2::launch_chunk_states_bf16(d->dtype, d->head_dim, reverse, p, s)
-                      : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
+  hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, true, p, s)
+                : is16(d->dtype)   ? la2::launch_chunk_states_bf16(d->dtype, d->head_dim, reverse, p, s)
+                                   : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
   if (e != hipSuccess) return LA2_ERR_LAUNCH;
   e = la2::launch_state_scan(d->head_dim, reverse, p, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
@@ -157,8 +167,9 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
   p.fin[0] = a.fin;
   p.rstd = a.rstd;
   p.eps = a.eps;
-  hipError_t e = is16(d->dtype) ? la2::launch_scan_bf16(d->dtype, d->head_dim, reverse, p, s)
-                                : la2::launch_scan_f32(d->head_dim, reverse, p, s);
+  hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, false, p, s)
+                : is16(d->dtype)   ? la2::launch_scan_bf16(d->dtype, d->head_dim, reverse, p, s)
+                                   : la2::launch_scan_f32(d->head_dim, reverse, p, s);
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
@@ -176,7 +187,9 @@ la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanAr
   p.fin[0] = a0.fin; p.fin[1] = a1.fin;
   p.x[0] = a0.x; p.y[0] = a0.y; p.z[0] = a0.z; p.w[0] = a0.w;
   p.x[1] = a1.x; p.y[1] = a1.y; p.z[1] = a1.z; p.w[1] = a1.w;
-  return la2::launch_scan_bf16(d->dtype, d->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  const hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, true, false, p, s)
+                                         : la2::launch_scan_bf16(d->dtype, d->head_dim, true, p, s);
+  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 // The state entry points split a sequence whose length is not a multiple of state_granule() into whole
@@ -248,6 +261,7 @@ int32_t la2_block_size(const la2_desc* desc) {
   if (check_desc(desc) != LA2_OK) return 0;
   // 16-bit, head_dim 128: the half-block scan kernel unless the full-block one is forced
   if (is16(desc->dtype) && desc->head_dim == 128 && g_scan_variant != 1) return 32;
+  if (wide(desc->head_dim)) return is16(desc->dtype) ? 32 : 1;
   return block_size(desc);
 }
 
@@ -272,6 +286,14 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) {   // fp32 at head_dim 96 / 256: token by token
+    la2::RecurParams r = recur_params(desc, lambda, 0, desc->seqlen, false);
+    r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
+    r.init[0] = kv_init;
+    r.fin[0] = kv_final;
+    return la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s) == hipSuccess ? LA2_OK
+                                                                                               : LA2_ERR_LAUNCH;
+  }
   const bool split = kv_final != nullptr && desc->seqlen % state_granule(desc) != 0;
   const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the block kernels process
   const Plan pl = make_plan(&blocks);
@@ -319,6 +341,21 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
       !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) {   // fp32 at head_dim 96 / 256: token by token
+    la2::RecurParams f = recur_params(desc, lambda, 0, desc->seqlen, false);
+    f.x[0] = d_o; f.y[0] = v; f.z[0] = k; f.w[0] = dq;      // dq_t = do_t KV_t^T: the (V, K) state is KV^T
+    f.init[0] = kv_init;
+    f.init_transposed = 1;
+    if (la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, f, s) != hipSuccess) return LA2_ERR_LAUNCH;
+    la2::RecurParams r = recur_params(desc, lambda, 0, desc->seqlen, true);
+    r.x[0] = k; r.y[0] = q; r.z[0] = d_o; r.w[0] = dv;     // dv_t = k_t G_t, G = sum q^T do
+    r.x[1] = v; r.y[1] = d_o; r.z[1] = q; r.w[1] = dk;     // dk_t = v_t G_t^T
+    r.init[0] = d_kv_final; r.init[1] = d_kv_final;
+    r.init_transposed = 2;
+    r.fin[0] = d_kv_init;
+    return la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 2, r, s) == hipSuccess ? LA2_OK
+                                                                                               : LA2_ERR_LAUNCH;
+  }
   // With a gradient coming in at the end of a sequence that does not end on a block boundary, the reverse
   // pass runs the tail token by token first and hands dKV to the block kernels through the workspace.
   const bool split = d_kv_final != nullptr && desc->seqlen % state_granule(desc) != 0;
@@ -386,6 +423,7 @@ la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                         void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if (wide(desc->head_dim)) return LA2_ERR_SHAPE;   // the Norm epilogue exists for head_dim 64 and 128
   if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !o || !rstd || !lambda) return LA2_ERR_NULL;
@@ -406,6 +444,7 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                         void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if (wide(desc->head_dim)) return LA2_ERR_SHAPE;   // as la2_fwd_norm
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
   if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;
@@ -428,6 +467,7 @@ la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const
                           void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // packed batches at 96 / 256: 16-bit only
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!cu_seqlens || !q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
@@ -446,6 +486,7 @@ la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // as la2_fwd_varlen
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!cu_seqlens || !q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
@@ -472,6 +513,7 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if (desc->dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (wide(desc->head_dim)) return LA2_ERR_SHAPE;   // comparison kernel: head_dim 64 and 128
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
@@ -487,7 +529,7 @@ la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32
                            const void* k, const void* v, const float* lambda, float* kv_state, void* o,
                            void* hip_stream) {
   if (qkv_dtype != LA2_F32 && !is16(qkv_dtype)) return LA2_ERR_DTYPE;
-  if (batch < 0 || heads < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
+  if (batch < 0 || heads < 0 || !supported_head_dim(head_dim)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
@@ -503,7 +545,7 @@ la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int3
                             const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
                             void* o, void* hip_stream) {
   if (qkv_dtype != LA2_F32 && !is16(qkv_dtype)) return LA2_ERR_DTYPE;
-  if (batch < 0 || heads < 0 || ntokens < 0 || (head_dim != 64 && head_dim != 128)) return LA2_ERR_SHAPE;
+  if (batch < 0 || heads < 0 || ntokens < 0 || !supported_head_dim(head_dim)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24 || ntokens > 65536) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads * ntokens == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
@@ -518,6 +560,13 @@ la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int3
   const la2_desc wb = whole_blocks(&d);
   if (wb.seqlen > 0 && make_plan(&wb).workspace == 0)
     return la2_fwd_state(&d, q, k, v, lambda, kv_state, o, kv_state, nullptr, 0, hip_stream);
+  if (wide(head_dim) && is16(qkv_dtype)) {   // the block kernel of these head dimensions, in one chunk
+    const Plan one{1, ((ntokens + 63) / 64) * 64, 0};
+    ScanArgs a{q, k, v, o};
+    a.init = kv_state;
+    a.fin = kv_state;
+    return run_scan(&d, one, false, a, lambda, nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+  }
   la2::RecurParams r = recur_params(&d, lambda, 0, ntokens, false);
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = kv_state;

@@ -59,7 +59,7 @@ template <int D, int B = kB>
 struct Cfg {
   static constexpr int KS = D / 16;            // MFMA k-steps along a feature dimension
   static constexpr int NT = D / 32;            // 32-wide tiles along a feature dimension
-  static constexpr int WPD = 4 / NT;           // waves sharing one value-feature tile (1 or 2)
+  static constexpr int WPD = NT >= 4 ? 1 : 4 / NT;   // waves sharing one value-feature tile (1 or 2)
   static constexpr int RT = 2 / WPD;           // 32-row tiles of the block per wave (2 or 1)
   static constexpr int CPR = D / 8;            // 16-byte chunks per tile row
   static constexpr int TILE = B * D;           // elements per tile
@@ -109,7 +109,10 @@ __device__ __forceinline__ int swz(int row) {
   //   land in 16 different 16-byte bank groups;
   // - 4 consecutive rows x 4 consecutive chunks (transposing reads, 32 lanes per cycle) likewise.
   // Depends on row % 16 only.
-  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  // d=256 (two lines per row): as d=128.  d=96 (12 chunks per row, rows 192 bytes apart): (row >> 2) & 3, which
+  // keeps a chunk inside its aligned group of four and still spreads 16 consecutive rows over the 16 groups.
+  if (D == 128 || D == 256) return ((row & 3) << 2) | ((row >> 2) & 3);
+  if (D == 96) return (row >> 2) & 3;
   const int m = row >> 1;
   return ((m & 1) << 2) | ((m >> 1) & 3);
 }

@@ -18,7 +18,9 @@
 namespace la2 {
 namespace {
 
-constexpr int kThreads = 256;
+// threads of a workgroup: a multiple of the D / 4 threads that share a state row, 16 or 12 float4 pieces
+// of state rows per thread
+constexpr int threads_for(int d) { return d == 256 ? 1024 : d == 96 ? 192 : 256; }
 
 // element i of a tensor of type DT (kF32, kBF16 or kF16) as fp32, and the store that goes with it
 template <int DT>
@@ -35,7 +37,8 @@ __device__ __forceinline__ void store_elem(void* p, int64_t i, float x) {
 }
 
 template <int D, int DT>
-__global__ __launch_bounds__(kThreads) void recur_kernel(RecurParams p) {
+__global__ __launch_bounds__(threads_for(D)) void recur_kernel(RecurParams p) {
+  constexpr int kThreads = threads_for(D);
   constexpr int TPR = D / 4;            // threads per state row (float4 each)
   constexpr int RG = kThreads / TPR;    // rows in flight per sweep
   constexpr int ITER = D / RG;
@@ -136,17 +139,19 @@ __global__ __launch_bounds__(kThreads) void recur_kernel(RecurParams p) {
 hipError_t launch_recur(int head_dim, int dtype, int batch, int ninst, const RecurParams& p, hipStream_t s) {
   const int64_t chains = (int64_t)batch * p.heads;
   if (chains == 0 || ninst == 0) return hipSuccess;
-  dim3 g((unsigned)chains, (unsigned)ninst), b(kThreads);
-#define LA2_LAUNCH_RECUR(D, DT) hipLaunchKernelGGL((recur_kernel<D, DT>), g, b, 0, s, p)
-  if (head_dim == 128) {
-    if (dtype == kBF16) LA2_LAUNCH_RECUR(128, kBF16);
-    else if (dtype == kF16) LA2_LAUNCH_RECUR(128, kF16);
-    else LA2_LAUNCH_RECUR(128, kF32);
-  } else {
-    if (dtype == kBF16) LA2_LAUNCH_RECUR(64, kBF16);
-    else if (dtype == kF16) LA2_LAUNCH_RECUR(64, kF16);
-    else LA2_LAUNCH_RECUR(64, kF32);
-  }
+  dim3 g((unsigned)chains, (unsigned)ninst);
+#define LA2_LAUNCH_RECUR(D, DT) hipLaunchKernelGGL((recur_kernel<D, DT>), g, dim3(threads_for(D)), 0, s, p)
+#define LA2_LAUNCH_RECUR_D(D)                         \
+  do {                                                \
+    if (dtype == kBF16) LA2_LAUNCH_RECUR(D, kBF16);   \
+    else if (dtype == kF16) LA2_LAUNCH_RECUR(D, kF16); \
+    else LA2_LAUNCH_RECUR(D, kF32);                   \
+  } while (0)
+  if (head_dim == 256) LA2_LAUNCH_RECUR_D(256);
+  else if (head_dim == 128) LA2_LAUNCH_RECUR_D(128);
+  else if (head_dim == 96) LA2_LAUNCH_RECUR_D(96);
+  else LA2_LAUNCH_RECUR_D(64);
+#undef LA2_LAUNCH_RECUR_D
 #undef LA2_LAUNCH_RECUR
   return hipGetLastError();
 }

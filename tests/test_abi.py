@@ -77,7 +77,7 @@ def test_null_arguments(lib):
 
 
 def test_shape_errors(lib):
-    for bad in (dict(batch=-1), dict(heads=-2), dict(seqlen=-5), dict(head_dim=96), dict(head_dim=0),
+    for bad in (dict(batch=-1), dict(heads=-2), dict(seqlen=-5), dict(head_dim=80), dict(head_dim=192), dict(head_dim=0),
                 dict(reserved=1)):
         d = dense(lib, 1, 1, 128, 64, binding.LA2_BF16)
         for kk, vv in bad.items():
@@ -202,7 +202,7 @@ def test_state_entry_points_validate_before_any_launch(lib):
     # the other checks are those of la2_fwd / la2_bwd
     assert fwd_state(lib, d, kv_init=P, q=None) == E_NULL
     assert bwd_state(lib, d, kv_init=P, q=None) == E_NULL
-    d.head_dim = 96
+    d.head_dim = 80
     assert fwd_state(lib, d, kv_init=P) == E_SHAPE
     # nothing to do: no chains; an empty sequence with no state wanted
     assert fwd_state(lib, dense(lib, 0, 4, 128, 64, binding.LA2_BF16), kv_init=P, kv_final=P) == OK
@@ -313,3 +313,37 @@ def test_varlen_entry_points_validate_before_any_launch(lib):
         assert fv() == E_WS and bv() == E_WS
     finally:
         lib.la2_set_chunk_tokens(0)
+
+
+def test_head_dim_96_and_256_are_accepted_where_they_have_kernels(lib):
+    for hd in (96, 256):
+        for dt in (binding.LA2_BF16, binding.LA2_F16, binding.LA2_F32):
+            d = dense(lib, 2, 2, 100, hd, dt)
+            ref = ctypes.byref(d)
+            # validation passes the shape check and goes on to the pointer checks
+            assert fwd(lib, d, q=None) == E_NULL and bwd(lib, d, [None] + [P] * 7) == E_NULL
+            assert fwd_state(lib, d, kv_init=P, q=None) == E_NULL
+            assert lib.la2_block_size(ref) == (32 if dt != binding.LA2_F32 else 1)
+            assert lib.la2_decode_step(1, 1, hd, dt, None, P, P, P, P, P, None) == E_NULL
+            assert lib.la2_decode_multi(1, 1, hd, 4, dt, None, P, P, P, P, P, None) == E_NULL
+            # no Norm epilogue and no left-product comparison at these head dimensions
+            assert lib.la2_fwd_norm(ref, P, P, P, P, 1e-6, P, P, None, 0, None) == E_SHAPE
+            assert lib.la2_bwd_norm(ref, P, P, P, P, P, P, P, P, P, P, P, None, 0, None) == E_SHAPE
+            if dt == binding.LA2_BF16:
+                assert lib.la2_left_product_fwd(ref, P, P, P, P, P, None) == E_SHAPE
+            # packed batches: the 16-bit types only
+            d.stride_b, d.stride_h, d.stride_n = 0, hd, 2 * hd
+            want = E_NULL if dt != binding.LA2_F32 else E_DTYPE
+            assert lib.la2_fwd_varlen(ref, None, P, P, P, P, P, None, 0, None) == want
+            assert lib.la2_bwd_varlen(ref, None, P, P, P, P, P, P, P, P, None, 0, None) == want
+        # fp32 runs the token recurrence: never a workspace; the 16-bit kernel is exact at ragged ends: no
+        # hand-over state in the workspace
+        try:
+            lib.la2_set_chunk_tokens(64)
+            assert lib.la2_workspace_bytes(ctypes.byref(dense(lib, 1, 2, 1000, hd, binding.LA2_F32)), 1) == 0
+            d = dense(lib, 1, 2, 1000, hd, binding.LA2_BF16)
+            nchunks = (1000 + 63) // 64
+            assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 2 * nchunks * hd * hd * 4
+            assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 2 * nchunks * hd * hd * 4
+        finally:
+            lib.la2_set_chunk_tokens(0)
