@@ -265,6 +265,21 @@ def main():
         other_dtypes.append({"workload": wl_d.name, "dtype": tag, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                              "tokens_per_s": round(wl_d.tokens / ((f_ms + b_ms) * 1e-3), 1)})
         del g_d
+    # the other head dimensions (one plain block kernel for both), at the tensor sizes of the sweep's first two
+    # points (heads x head_dim = 2048 for 256, 1536 for 96)
+    other_head_dims = []
+    for hd, heads in ((256, 8), (96, 16)):
+        for b_, n_ in ((64, 1024), (16, 4096)):
+            wl_h = workloads.Workload("b%d_n%d_h%d_d%d" % (b_, n_, heads, hd), b_, heads, n_, hd, torch.bfloat16, seed=60 + hd)
+            g_h = stage(wl_h)
+            f_ms = time_ms(lambda: fwd(g_h), iters, warm=40)
+            b_ms = time_ms(lambda: bwd(g_h), iters, warm=40)
+            unit = wl_h.token_heads * hd * 2   # bytes of one tensor
+            other_head_dims.append({"workload": wl_h.name, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                                    "tokens_per_s": round(wl_h.tokens / ((f_ms + b_ms) * 1e-3), 1),
+                                    "fwd_algorithmic_GBs": round(4 * unit / f_ms / 1e6, 1),
+                                    "bwd_algorithmic_GBs": round(10 * unit / b_ms / 1e6, 1)})
+            del g_h
     # the forward pass as the O(n^2 d) masked left product (comparison kernel) against the block recurrence
     crossover = []
     short = [(wl_, stage(wl_)) for wl_ in (workloads.Workload("config3_like_b%d_n%d_h16_d128" % (b_, n_), b_, 16, n_, 128,
@@ -378,6 +393,7 @@ def main():
         "saved_forward_states": saved,
         "normalised_operator": normed,
         "other_dtypes": other_dtypes,
+        "other_head_dims": other_head_dims,
         "packed_varlen": packed,
         "left_product_comparison": crossover,
         "decode": decode,

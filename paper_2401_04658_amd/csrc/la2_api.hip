@@ -88,7 +88,7 @@ Plan make_plan(const la2_desc* d) {
     // Chunking shortens the scan's sequential loop from nblocks to cb blocks but adds the pre-pass (about a
     // third of a scan block per block) and two more launches (about 15 us): not worth it for short sequences.
     // Measured times of one block of the sequential loop, in microseconds.
-    const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 6.f : d->head_dim == 64 ? 1.15f : 2.1f)
+    const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 9.f : d->head_dim == 96 ? 3.f : d->head_dim == 64 ? 1.15f : 2.1f)
                                        : (d->head_dim == 128 ? 10.f : 3.f);
     if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) return pl;
   }

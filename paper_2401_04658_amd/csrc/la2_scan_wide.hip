@@ -47,7 +47,7 @@ struct WideAddr {
 };
 
 template <typename E, int D, bool REV, bool STATE_ONLY>
-__global__ __launch_bounds__(2 * D) void scan_wide_kernel(ScanParams p) {
+__global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanParams p) {
   constexpr int B = 32;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(2 * D) void scan_wide_kernel(ScanParams p) {
         acc = mfma(to_perm_order(f), xa, acc);
         sd = mfma(ya, xa, sd);
       }
-      const float carried = exp2f(l2 * (float)(REV ? max(nv - 1 - l32, 0) : l32 + 1));
+      const float carried = fast_exp2(l2 * (float)(REV ? max(nv - 1 - l32, 0) : l32 + 1));
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[v] *= carried;
       // intra-block part Z^T P^T
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(2 * D) void scan_wide_kernel(ScanParams p) {
       }
     }
     // state slice <- lambda^nv state + Y^T decay(Z): element j of a Z fragment is row 16 q + 8 (j / 4) + 4 hh + j % 4
-    const float lam_nv = exp2f(l2 * (float)nv);
+    const float lam_nv = uniform(fast_exp2(l2 * (float)nv));
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(2 * D) void scan_wide_kernel(ScanParams p) {
 #pragma unroll
       for (int j = 0; j < 8; j++) {
         const int c = 16 * q + 8 * (j >> 2) + 4 * hh + (j & 3);
-        zd[j] = (E)((float)zf[q][j] * exp2f(l2 * (float)(REV ? c + 1 : max(nv - 1 - c, 0))));
+        zd[j] = (E)((float)zf[q][j] * fast_exp2(l2 * (float)(REV ? c + 1 : max(nv - 1 - c, 0))));
       }
 #pragma unroll
       for (int t = 0; t < NT; t++) kv[t] = mfma(la.read_cols(cur[YI], 16 * q, t), zd, kv[t]);
