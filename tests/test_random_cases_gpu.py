@@ -25,16 +25,16 @@ def _defaults():
     binding.la2_set_scan_variant(0)
 
 
-def draw_case(i):
-    rng = np.random.default_rng(90210 + i)
+def draw_case(i, dims=(64, 128), modes=("plain", "state", "state_nofinal", "norm", "decode_multi", "varlen"), salt=90210):
+    rng = np.random.default_rng(salt + i)
     dtype = DTYPES[int(rng.integers(0, 3))]
-    d = int(rng.choice([64, 128]))
+    d = int(rng.choice(list(dims)))
     b, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
     n = int(rng.choice([rng.integers(1, 70), rng.integers(70, 400), 32 * rng.integers(1, 12), rng.integers(400, 900)]))
     chunk = int(rng.choice([0, 0, 64, 128, 192, 320]))
     layout = str(rng.choice(["bhnd", "bnhd", "padded"]))
     lam = rng.choice([1.0, 0.999, 0.97, 0.8, 0.3, 1e-3], size=H).astype(np.float32)
-    mode = str(rng.choice(["plain", "state", "state_nofinal", "norm", "decode_multi", "varlen"]))
+    mode = str(rng.choice(list(modes)))
     variant = int(rng.choice([0, 1, 2]))
     return dict(dtype=dtype, d=d, b=b, H=H, n=n, chunk=chunk, layout=layout, lam=lam, mode=mode, variant=variant,
                 seed=int(rng.integers(0, 1 << 30)))
@@ -54,7 +54,20 @@ def place(x, layout):
 
 @pytest.mark.parametrize("i", range(200))
 def test_random_case(i):
-    c = draw_case(i)
+    run_case(i, draw_case(i))
+
+
+@pytest.mark.parametrize("i", range(80))
+def test_random_case_head_dim_96_256(i):
+    """The same sweep over the head dimensions with the plain block kernel (no Norm entries there; packed
+    batches in the 16-bit types only)."""
+    c = draw_case(i, dims=(96, 256), modes=("plain", "state", "state_nofinal", "decode_multi", "varlen"), salt=41000)
+    if c["mode"] == "varlen" and c["dtype"] == torch.float32:
+        c["dtype"] = torch.bfloat16
+    run_case(i, c)
+
+
+def run_case(i, c):
     dtype, d, b, H, n = c["dtype"], c["d"], c["b"], c["H"], c["n"]
     tag = "case %d %s" % (i, {k: (v if k != "lam" else v.tolist()) for k, v in c.items()})
     t = workloads.Workload("random", b, H, n, d, dtype, seed=c["seed"], backward=True).tensors()
