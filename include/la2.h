@@ -33,9 +33,9 @@
  *     addressable with 32-bit byte offsets: (seqlen + 128) * stride_n * sizeof(element) <= 2^32, else
  *     LA2_ERR_SHAPE (dense bf16, head_dim 128: up to 16,777,088 positions).
  *   - head_dim is 64, 96, 128 or 256.  64 and 128 are the tuned paths and have every entry point.  96 and 256
- *     have la2_fwd / la2_bwd, the state and packed variants and the decode entries: for the 16-bit types one
- *     MFMA block kernel, for fp32 the token-by-token recurrence (slow: meant for checking, not for training;
- *     no packed variant); the Norm entries and the left-product comparison return LA2_ERR_SHAPE for them.
+ *     have every entry point but the left-product comparison (LA2_ERR_SHAPE): for the 16-bit types one MFMA
+ *     block kernel, for fp32 the token-by-token recurrence (slow: meant for checking, not for training; no
+ *     packed variant: LA2_ERR_DTYPE).
  *   - Argument errors are detected on the host BEFORE anything is launched and are reported through
  *     the return code; nothing aborts.  A failed launch is reported as LA2_ERR_LAUNCH.
  */

@@ -423,7 +423,6 @@ la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                         void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
-  if (wide(desc->head_dim)) return LA2_ERR_SHAPE;   // the Norm epilogue exists for head_dim 64 and 128
   if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !o || !rstd || !lambda) return LA2_ERR_NULL;
@@ -433,6 +432,15 @@ la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, cons
   const Plan pl = make_plan(desc);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) {
+    // fp32 at head_dim 96 / 256: the token recurrence writes u, a row pass normalises it in place
+    st = la2_fwd(desc, q, k, v, lambda, o, workspace, workspace_bytes, hip_stream);
+    if (st != LA2_OK) return st;
+    return la2::launch_norm_fwd_rows_f32(desc->head_dim, static_cast<float*>(o), rstd, eps, desc->stride_b,
+                                         desc->stride_h, desc->stride_n, desc->batch, desc->heads, desc->seqlen,
+                                         reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? LA2_OK : LA2_ERR_LAUNCH;
+  }
   ScanArgs a{q, k, v, o};
   a.rstd = rstd;
   a.eps = eps;
@@ -444,7 +452,6 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                         void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
-  if (wide(desc->head_dim)) return LA2_ERR_SHAPE;   // as la2_fwd_norm
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
   if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;

@@ -156,6 +156,10 @@ struct NormBwdParams {
   int32_t batch, heads, n;
 };
 hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s);
+// The forward normalisation as a pass of its own, in place: o <- o r, r = 1 / sqrt(mean_j o_j^2 + eps) -> rstd
+// (fp32 data at head_dim 96 / 256 only: every other path normalises inside its scan kernel).
+hipError_t launch_norm_fwd_rows_f32(int head_dim, float* o, float* rstd, float eps, int64_t stride_b,
+                                    int64_t stride_h, int64_t stride_n, int batch, int heads, int n, hipStream_t s);
 
 // dst[i] = src ? src[i] : 0 for count floats (a state that passes through an empty sequence)
 hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s);

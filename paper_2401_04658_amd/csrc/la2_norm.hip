@@ -2,9 +2,12 @@
 // row): one pass over the rows that turns the gradient g of the normalised output o into the gradient of
 // the un-normalised output,
 //     du_t = r_t (g_t - o_t mean_j(g_tj o_tj)),        r_t = 1 / sqrt(mean_j u_tj^2 + eps)  (kept by the forward)
-// which Algorithm 2 then takes as its dO.  Memory-bound: 16 bytes per lane, a row per group of
-// D * sizeof(T) / 16 lanes, the row mean by lane exchanges inside the group; streaming (non-temporal)
-// loads and stores, measured 9 % faster than the default cache policy.
+// which Algorithm 2 then takes as its dO.  Memory-bound: 16-byte pieces, a row per group of a power-of-two
+// number of lanes (one piece per lane; three at head_dim 96), the row mean by lane exchanges inside the
+// group; streaming (non-temporal) loads and stores, measured 9 % faster than the default cache policy.
+//
+// Also here: the forward normalisation as a pass of its own, in place, for the one path whose scan has no
+// epilogue (fp32 data at head_dim 96 / 256, which runs the token recurrence).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -39,11 +42,23 @@ template <> struct Row16<_Float16> {
   __device__ void set(int i, float x) { v[i] = (_Float16)x; }
 };
 
+// How the lanes share a row: PPL pieces per lane, LPR lanes per row (a power of two, 4 .. 64); lane `piece`
+// of a row handles pieces piece, piece + LPR, ...
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void norm_bwd_rows_kernel(NormBwdParams p) {
-  constexpr int N = Row16<T>::N;
-  constexpr int LPR = D / N;                    // lanes per row (8 .. 32, a power of two)
-  constexpr int ROWS = kThreads / LPR;          // rows per workgroup
+struct RowSplit {
+  static constexpr int N = Row16<T>::N;
+  static constexpr int PPL = D == 96 ? 3 : 1;
+  static constexpr int LPR = D / N / PPL;
+  static constexpr int ROWS = kThreads / LPR;   // rows per workgroup
+  static_assert((LPR & (LPR - 1)) == 0 && LPR >= 1 && LPR <= 64, "lane exchanges stay inside a wave");
+};
+
+// FWD false: du = rstd (g - o mean(g o)).  FWD true: o <- o r in place with r = 1 / sqrt(mean(o^2) + eps), r -> rstd
+// (p.g unused, p.du == p.o).
+template <typename T, int D, bool FWD>
+__global__ __launch_bounds__(kThreads) void norm_rows_kernel(NormBwdParams p, float eps) {
+  using S = RowSplit<T, D>;
+  constexpr int N = S::N, PPL = S::PPL, LPR = S::LPR, ROWS = S::ROWS;
   const int64_t rows = (int64_t)p.batch * p.heads * p.n;
   const int64_t row = (int64_t)blockIdx.x * ROWS + threadIdx.x / LPR;
   const int piece = threadIdx.x % LPR;
@@ -51,38 +66,63 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_rows_kernel(NormBwdParams p
   const int64_t rr = live ? row : 0;
   const int64_t chain = rr / p.n, pos = rr % p.n;
   const int64_t off = (chain / p.heads) * p.stride_b + (chain % p.heads) * p.stride_h + pos * p.stride_n + piece * N;
-  Row16<T> o, g, du;
-  o.v = __builtin_nontemporal_load(reinterpret_cast<const decltype(o.v)*>(reinterpret_cast<const T*>(p.o) + off));
-  g.v = __builtin_nontemporal_load(reinterpret_cast<const decltype(g.v)*>(reinterpret_cast<const T*>(p.g) + off));
+  Row16<T> o[PPL], g[PPL];
   float c = 0.f;
 #pragma unroll
-  for (int i = 0; i < N; i++) c = fmaf(g.get(i), o.get(i), c);
+  for (int j = 0; j < PPL; j++) {
+    const int64_t at = off + j * LPR * N;
+    o[j].v = __builtin_nontemporal_load(reinterpret_cast<const decltype(o[j].v)*>(reinterpret_cast<const T*>(p.o) + at));
+    if (!FWD)
+      g[j].v = __builtin_nontemporal_load(reinterpret_cast<const decltype(g[j].v)*>(reinterpret_cast<const T*>(p.g) + at));
+#pragma unroll
+    for (int i = 0; i < N; i++) c = fmaf(FWD ? o[j].get(i) : g[j].get(i), o[j].get(i), c);
+  }
 #pragma unroll
   for (int m = 1; m < LPR; m <<= 1) c += __shfl_xor(c, m);
   c *= 1.f / (float)D;
-  const float r = p.rstd[rr];
+  const float r = FWD ? 1.f / sqrtf(c + eps) : p.rstd[rr];
 #pragma unroll
-  for (int i = 0; i < N; i++) du.set(i, r * (g.get(i) - o.get(i) * c));
-  if (live) __builtin_nontemporal_store(du.v, reinterpret_cast<decltype(du.v)*>(reinterpret_cast<T*>(p.du) + off));
+  for (int j = 0; j < PPL; j++) {
+    Row16<T> out;
+#pragma unroll
+    for (int i = 0; i < N; i++) out.set(i, FWD ? o[j].get(i) * r : r * (g[j].get(i) - o[j].get(i) * c));
+    if (live)
+      __builtin_nontemporal_store(out.v, reinterpret_cast<decltype(out.v)*>(reinterpret_cast<T*>(p.du) + off + j * LPR * N));
+  }
+  if (FWD && live && piece == 0) const_cast<float*>(p.rstd)[rr] = r;
 }
 
-template <typename T, int D>
-hipError_t launch(const NormBwdParams& p, hipStream_t s) {
-  constexpr int ROWS = kThreads / (D / Row16<T>::N);
+template <typename T, int D, bool FWD>
+hipError_t launch(const NormBwdParams& p, float eps, hipStream_t s) {
+  constexpr int ROWS = RowSplit<T, D>::ROWS;
   const int64_t rows = (int64_t)p.batch * p.heads * p.n;
   const int64_t grid = (rows + ROWS - 1) / ROWS;
   if (grid == 0) return hipSuccess;
   if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((norm_bwd_rows_kernel<T, D>), dim3((unsigned)grid), dim3(kThreads), 0, s, p);
+  hipLaunchKernelGGL((norm_rows_kernel<T, D, FWD>), dim3((unsigned)grid), dim3(kThreads), 0, s, p, eps);
   return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_bwd_d(int head_dim, const NormBwdParams& p, hipStream_t s) {
+  if (head_dim == 256) return launch<T, 256, false>(p, 0.f, s);
+  if (head_dim == 128) return launch<T, 128, false>(p, 0.f, s);
+  if (head_dim == 96) return launch<T, 96, false>(p, 0.f, s);
+  return launch<T, 64, false>(p, 0.f, s);
 }
 
 }  // namespace
 
 hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s) {
-  if (dtype == kBF16) return head_dim == 128 ? launch<__bf16, 128>(p, s) : launch<__bf16, 64>(p, s);
-  if (dtype == kF16) return head_dim == 128 ? launch<_Float16, 128>(p, s) : launch<_Float16, 64>(p, s);
-  return head_dim == 128 ? launch<float, 128>(p, s) : launch<float, 64>(p, s);
+  if (dtype == kBF16) return launch_bwd_d<__bf16>(head_dim, p, s);
+  if (dtype == kF16) return launch_bwd_d<_Float16>(head_dim, p, s);
+  return launch_bwd_d<float>(head_dim, p, s);
+}
+
+hipError_t launch_norm_fwd_rows_f32(int head_dim, float* o, float* rstd, float eps, int64_t stride_b,
+                                    int64_t stride_h, int64_t stride_n, int batch, int heads, int n, hipStream_t s) {
+  const NormBwdParams p{o, nullptr, rstd, o, stride_b, stride_h, stride_n, batch, heads, n};
+  return head_dim == 256 ? launch<float, 256, true>(p, eps, s) : launch<float, 96, true>(p, eps, s);
 }
 
 }  // namespace la2

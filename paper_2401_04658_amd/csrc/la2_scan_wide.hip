@@ -46,8 +46,11 @@ struct WideAddr {
   }
 };
 
-template <typename E, int D, bool REV, bool STATE_ONLY>
+// NORM: the Norm epilogue of eq. (2) on a forward scan (the waves exchange the sums of squares of their
+// 32 features of every row through LDS, one more barrier per block; wave 0 stores r).
+template <typename E, int D, bool REV, bool STATE_ONLY, bool NORM = false>
 __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanParams p) {
+  static_assert(!NORM || (!REV && !STATE_ONLY), "the Norm epilogue belongs to the forward scan");
   constexpr int B = 32;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
@@ -55,6 +58,7 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
   constexpr int YI = NTL - 2, ZI = NTL - 1;
   using Loader = TileLoader<D, NTL, B, NT>;
   __shared__ __attribute__((aligned(1024))) E sT[2][NTL][TILE];
+  float* const sRed = NormExchange<NORM ? B * (D / 32) : 0>::get();   // [position][wave]
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w;
@@ -153,6 +157,16 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
       }
       // output: lane = position l32, elements 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
       const int pos = blk * B + l32;
+      if constexpr (NORM) {
+        // The next publish comes after the barrier at the top of the next block, which no wave passes before
+        // every wave has collected: one exchange buffer is enough.
+        norm_publish<NT>(acc, sRed, l32, hh, dvt);
+        __syncthreads();
+        const float r = norm_collect<NT>(sRed, l32, 1.f / (float)D, p.eps);
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[v] *= r;
+        if (dvt == 0 && hh == 0 && pos < n) p.rstd[(int64_t)chain * n + pos] = r;
+      }
       if (pos < n) {
         E* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;
 #pragma unroll
@@ -203,7 +217,9 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
 template <typename E, int D>
 hipError_t launch_wide(bool reverse, bool state_only, const ScanParams& p, hipStream_t s) {
   const dim3 g((unsigned)((int64_t)p.batch * p.heads * p.nchunks), state_only ? 1u : (unsigned)p.nscan), b(2 * D);
-  if (state_only) {
+  if (!state_only && !reverse && p.rstd != nullptr) {
+    hipLaunchKernelGGL((scan_wide_kernel<E, D, false, false, true>), g, b, 0, s, p);
+  } else if (state_only) {
     if (reverse) hipLaunchKernelGGL((scan_wide_kernel<E, D, true, true>), g, b, 0, s, p);
     else         hipLaunchKernelGGL((scan_wide_kernel<E, D, false, true>), g, b, 0, s, p);
   } else {

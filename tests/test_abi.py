@@ -326,9 +326,9 @@ def test_head_dim_96_and_256_are_accepted_where_they_have_kernels(lib):
             assert lib.la2_block_size(ref) == (32 if dt != binding.LA2_F32 else 1)
             assert lib.la2_decode_step(1, 1, hd, dt, None, P, P, P, P, P, None) == E_NULL
             assert lib.la2_decode_multi(1, 1, hd, 4, dt, None, P, P, P, P, P, None) == E_NULL
-            # no Norm epilogue and no left-product comparison at these head dimensions
-            assert lib.la2_fwd_norm(ref, P, P, P, P, 1e-6, P, P, None, 0, None) == E_SHAPE
-            assert lib.la2_bwd_norm(ref, P, P, P, P, P, P, P, P, P, P, P, None, 0, None) == E_SHAPE
+            assert lib.la2_fwd_norm(ref, None, P, P, P, 1e-6, P, P, None, 0, None) == E_NULL
+            assert lib.la2_bwd_norm(ref, None, P, P, P, P, P, P, P, P, P, P, None, 0, None) == E_NULL
+            # no left-product comparison at these head dimensions
             if dt == binding.LA2_BF16:
                 assert lib.la2_left_product_fwd(ref, P, P, P, P, P, None) == E_SHAPE
             # packed batches: the 16-bit types only

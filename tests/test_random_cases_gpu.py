@@ -59,9 +59,9 @@ def test_random_case(i):
 
 @pytest.mark.parametrize("i", range(80))
 def test_random_case_head_dim_96_256(i):
-    """The same sweep over the head dimensions with the plain block kernel (no Norm entries there; packed
-    batches in the 16-bit types only)."""
-    c = draw_case(i, dims=(96, 256), modes=("plain", "state", "state_nofinal", "decode_multi", "varlen"), salt=41000)
+    """The same sweep over the head dimensions with the plain block kernel (packed batches in the 16-bit
+    types only)."""
+    c = draw_case(i, dims=(96, 256), salt=41000)
     if c["mode"] == "varlen" and c["dtype"] == torch.float32:
         c["dtype"] = torch.bfloat16
     run_case(i, c)

@@ -208,9 +208,28 @@ def test_decode_multi(d, dtype, T):
     assert_close("d%d %s decode_multi T%d state" % (d, dtype, T), state, rs, dtype)
 
 
-def test_what_these_head_dimensions_do_not_have():
+@pytest.mark.parametrize("n", [1, 33, 100, 517])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
+@pytest.mark.parametrize("d", DIMS)
+def test_normalised_operator(d, dtype, n):
+    eps = 1e-3
+    t, g = inputs(2, 2, n, d, dtype, seed=2000 + d + n, lam=[0.7, 0.98])
+    for chunk in (0, 64):
+        binding.la2_set_chunk_tokens(chunk)
+        o, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], eps)
+        grads = binding.la2_bwd_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"])
+        torch.cuda.synchronize()
+        q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+        ref_o, ref_r = oracle.fwd_norm(q, k, v, lam, eps)
+        tag = "d%d %s n%d chunk %d norm" % (d, dtype, n, chunk)
+        assert_close(tag + " o", o, ref_o, dtype)
+        assert_close(tag + " rstd", rstd, ref_r, dtype)
+        if n > 1:   # a single position leaves dq, dk as pure cancellation
+            for name, got, ref in zip(("dq", "dk", "dv"), grads, oracle.bwd_norm(q, k, v, do, lam, eps)):
+                assert_close(tag + " " + name, got, ref, dtype)
+
+
+def test_no_left_product_comparison_at_these_head_dimensions():
     t, g = inputs(1, 1, 40, 96, torch.bfloat16, seed=1)
-    with pytest.raises(binding.LA2Error):
-        binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], 1e-6)
     with pytest.raises(binding.LA2Error):
         binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"])
