@@ -37,6 +37,23 @@ def flops_per_token_head(B, d, what):
     return {"fwd": fwd, "bwd": bwd, "fwd+bwd": fwd + bwd}[what]
 
 
+def stream_reference(g, time_ms, binding, iters):
+    """A kernel that only streams (no arithmetic, no LDS, no dependences), timed on the buffers and byte counts
+    of the scan launches: 3 tensors in, 1 out (forward scan, dQ scan) and 4 in, 2 out (the twin dK / dV scan);
+    the better of the two store policies each.  What the memory system gives such a kernel is the bound the scan
+    kernels can reach; the 8 TB/s of the roofline entry is the pin bandwidth."""
+    import torch
+    unit = g["q"].numel() * g["q"].element_size()
+    src = torch.zeros(4 * unit, dtype=torch.uint8, device=g["q"].device)
+    dst = torch.empty(2 * unit, dtype=torch.uint8, device=g["q"].device)
+    out = {}
+    for name, r, w in (("reads3_writes1", 3, 1), ("reads4_writes2", 4, 2), ("reads3", 3, 0)):
+        best = min(time_ms(lambda: binding.la2_stream_probe(r, w, src, dst, unit, nt_stores=nts), iters, warm=20)
+                   for nts in ((False, True) if w else (False,)))
+        out[name] = {"launch_ms": round(best, 4), "GBs": round((r + w) * unit / (best * 1e-3) / 1e9, 1)}
+    return out
+
+
 def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
     """The forward scan at (batch 16, n 4K): la2_fwd is exactly one launch of the scan kernel there."""
     assert binding.la2_workspace_bytes(g["q"]) == 0, "expected the un-chunked single-launch case"
@@ -154,6 +171,17 @@ def main():
     wl_r, g_r = sweep[1]
     time_ms(lambda: fwd(g_r), 300)
     roofline = dominant_kernel_roofline(wl_r, g_r, fwd, time_ms, binding, max(100, args.steps))
+    # ... and beside it a kernel that only streams the same bytes in the same read : write mix
+    roofline["stream_reference"] = stream_reference(g_r, time_ms, binding, max(100, args.steps))
+    roofline["frac_of_stream_reference"] = round(
+        roofline["stream_reference"]["reads3_writes1"]["launch_ms"] / roofline["launch_ms"], 4)
+    bwd_r_ms = time_ms(lambda: bwd(g_r), max(100, args.steps), warm=20)
+    roofline["bwd_vs_stream_reference"] = {
+        "la2_bwd_ms": round(bwd_r_ms, 4),
+        "stream_ms": round(roofline["stream_reference"]["reads3_writes1"]["launch_ms"]
+                           + roofline["stream_reference"]["reads4_writes2"]["launch_ms"], 4)}
+    roofline["bwd_vs_stream_reference"]["frac"] = round(
+        roofline["bwd_vs_stream_reference"]["stream_ms"] / bwd_r_ms, 4)
 
     # ---- the timed region: W warm-up steps, then exactly K steps ----------------------------------
     for _ in range(args.warmup):

@@ -224,6 +224,22 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
                                 const float* lambda, void* o, void* hip_stream);
 
 /*
+ * Measurement helper, not part of the method: one launch of a kernel that only streams.  It reads `reads`
+ * (0..4) consecutive streams of bytes_per_stream bytes from `in` and writes `writes` (0..2) consecutive streams
+ * of the same size to `out` (values are arbitrary), 16 bytes per lane, non-temporal loads, stores with the
+ * non-temporal policy if nt_stores != 0.  The benchmark times it beside the scan kernels on the same bytes and
+ * read : write mix (Algorithm 1 reads three tensors and writes one; Algorithm 2's second loop reads four and
+ * writes two) as the rate the memory system gives a kernel without arithmetic.
+ *   in    device, reads * bytes_per_stream bytes (may be NULL if reads == 0), 16-byte aligned
+ *   out   device, writes * bytes_per_stream bytes; at least 16 bytes when writes == 0 (never written then);
+ *         16-byte aligned
+ * LA2_ERR_SHAPE for stream counts out of range or both zero, LA2_ERR_STRIDE_ALIGN for a size or pointer that is
+ * not a multiple of 16 bytes.
+ */
+la2_status la2_stream_probe(int32_t reads, int32_t writes, int32_t nt_stores, const void* in, void* out,
+                            size_t bytes_per_stream, void* hip_stream);
+
+/*
  * ntokens consecutive decode steps in one launch (recursive form of Sec. 3.2.1): for t = 0 .. ntokens-1
  * kv_state <- lambda_h kv_state + k_t^T v_t, o_t = q_t kv_state.  The state is read and written once per
  * launch instead of once per token.

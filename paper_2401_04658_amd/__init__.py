@@ -14,5 +14,6 @@ from .binding import (  # noqa: F401
     la2_decode_step,
     la2_decode_multi,
     la2_left_product_fwd,
+    la2_stream_probe,
     la2_workspace_bytes,
 )

@@ -57,6 +57,8 @@ def load():
     lib.la2_set_chunk_tokens.restype = None
     lib.la2_set_scan_variant.argtypes = [i32]
     lib.la2_set_scan_variant.restype = None
+    lib.la2_stream_probe.argtypes = [i32, i32, i32, vp, vp, sz, vp]
+    lib.la2_stream_probe.restype = ctypes.c_int
     lib.la2_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_fwd.restype = ctypes.c_int
     lib.la2_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -401,3 +403,17 @@ def la2_left_product_fwd(q, k, v, lam, out=None):
         _check(lib.la2_left_product_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
                                         out.data_ptr(), _stream(q)))
     return out
+
+
+def la2_stream_probe(reads, writes, src, dst, bytes_per_stream, nt_stores=False):
+    """Measurement helper: one launch of a kernel that only streams `reads` streams out of src and `writes`
+    streams into dst (uint8 tensors on the GPU, large enough for that many streams of bytes_per_stream)."""
+    lib = load()
+    if not (src.is_cuda and dst.is_cuda):
+        raise ValueError("la2_stream_probe: buffers must live on the GPU")
+    if src.numel() * src.element_size() < reads * bytes_per_stream or \
+            dst.numel() * dst.element_size() < max(writes * bytes_per_stream, 16):
+        raise ValueError("la2_stream_probe: buffer smaller than the streams asked for")
+    with torch.cuda.device(src.device):
+        _check(lib.la2_stream_probe(reads, writes, 1 if nt_stores else 0, src.data_ptr(), dst.data_ptr(),
+                                    bytes_per_stream, _stream(src)))

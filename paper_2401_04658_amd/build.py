@@ -7,7 +7,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libla2.so")
 SOURCES = ["la2_api.hip", "la2_scan_bf16.hip", "la2_scan_bf16_half.hip", "la2_chunk_state_bf16.hip",
-           "la2_left_product_bf16.hip", "la2_scan_f32.hip", "la2_decode.hip", "la2_recur.hip", "la2_norm.hip", "la2_tail_bf16.hip", "la2_scan_wide.hip"]
+           "la2_left_product_bf16.hip", "la2_scan_f32.hip", "la2_decode.hip", "la2_recur.hip", "la2_norm.hip", "la2_tail_bf16.hip", "la2_scan_wide.hip", "la2_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

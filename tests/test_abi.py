@@ -347,3 +347,13 @@ def test_head_dim_96_and_256_are_accepted_where_they_have_kernels(lib):
             assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 2 * nchunks * hd * hd * 4
         finally:
             lib.la2_set_chunk_tokens(0)
+
+
+def test_stream_probe_validation(lib):
+    lib.la2_stream_probe.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [ctypes.c_size_t, ctypes.c_void_p]
+    lib.la2_stream_probe.restype = ctypes.c_int
+    sp = lambda r=3, w=1, i=P, o=P, n=1024: lib.la2_stream_probe(r, w, 0, i, o, n, None)
+    assert sp(r=5) == E_SHAPE and sp(w=3) == E_SHAPE and sp(r=-1) == E_SHAPE and sp(r=0, w=0) == E_SHAPE
+    assert sp(n=24) == E_ALIGN and sp(i=P + 8) == E_ALIGN and sp(o=P + 4) == E_ALIGN
+    assert sp(i=None) == E_NULL and sp(o=None) == E_NULL
+    assert sp(n=0, i=None, o=None) == OK
