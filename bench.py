@@ -359,6 +359,16 @@ def main():
               "tokens_per_s": round(dw.batch / (dec_ms * 1e-3), 1),
               "achieved_GBs": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
               "frac_hbm_peak": round(dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    # beside it: a kernel that only streams the state's bytes in and as many bytes out
+    kv_bytes = kv.numel() * kv.element_size()
+    kv_u8 = kv.view(torch.uint8).reshape(-1)
+    kv_out = torch.empty_like(kv_u8)
+    sref_ms = min(time_ms(lambda: binding.la2_stream_probe(1, 1, kv_u8, kv_out, kv_bytes, nt_stores=nts), 200, warm=20)
+                  for nts in (False, True))
+    del kv_out
+    decode["stream_reference"] = {"kernel": "1 stream in, 1 out, the state's %d MiB each, no arithmetic" % (kv_bytes >> 20),
+                                  "us_per_launch": round(sref_ms * 1e3, 2),
+                                  "frac_of_stream_reference": round(sref_ms / dec_ms, 4)}
     # the same tokens 8 per launch (multi-token decode): the state is read and written once per launch
     T = 8
     qm, km, vm = (torch.stack([toks[i][j] for i in range(T)], 2).contiguous() for j in range(3))
