@@ -233,3 +233,25 @@ def test_no_left_product_comparison_at_these_head_dimensions():
     t, g = inputs(1, 1, 40, 96, torch.bfloat16, seed=1)
     with pytest.raises(binding.LA2Error):
         binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"])
+
+
+@pytest.mark.parametrize("n", [700, 1024])
+@pytest.mark.parametrize("d", DIMS)
+def test_backward_reuses_the_forward_chunk_states(d, n):
+    """la2_bwd_saved: the dQ scan starts from the chunk states the forward pass left in its workspace."""
+    binding.la2_set_chunk_tokens(128)
+    t, g = inputs(1, 2, n, d, torch.bfloat16, seed=2100 + d + n, lam=[0.85, 0.995])
+    need = binding.la2_workspace_bytes(g["q"], binding.LA2_OP_BWD_STATE)
+    assert need > 0
+    ws_f = torch.empty(need, dtype=torch.uint8, device=DEV)
+    ws_b = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for use_init in (False, True):
+        kv_init = g["kv_init"] if use_init else None
+        binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=kv_init, want_final=False, workspace=ws_f)
+        got = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=kv_init,
+                                    workspace=ws_b, fwd_workspace=ws_f)
+        torch.cuda.synchronize()
+        q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+        refs = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=to64(t["kv_init"]) if use_init else None)
+        for name, x, ref in zip(("dq", "dk", "dv", "d_kv_init"), got, refs):
+            assert_close("saved states d%d n%d init=%s %s" % (d, n, use_init, name), x, ref, torch.bfloat16)
