@@ -18,11 +18,11 @@ namespace la2 {
 namespace {
 using namespace bf16k;
 
-// Per-lane addressing of the swizzled tiles without the power-of-two shortcuts of LaneAddr.
+// Per-lane addressing of the swizzled tiles without the power-of-two shortcuts of LaneAddr (head_dim 96).
 template <int D>
-struct WideAddr {
+struct PlainAddr {
   int l32, hh, r0, trc, trh;
-  __device__ __forceinline__ WideAddr(int l) {
+  __device__ __forceinline__ PlainAddr(int l) {
     const int s16 = l & 15, g2 = (l >> 4) & 1;
     l32 = l & 31;
     hh = l >> 5;
@@ -86,7 +86,12 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
   loader.g[YI] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.y[1] : p.y[0]) + base);
   loader.g[ZI] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.z[1] : p.z[0]) + base);
   E* const gw = STATE_ONLY ? nullptr : reinterpret_cast<E*>(which ? p.w[1] : p.w[0]) + base;
-  const WideAddr<D> la(l);
+  // head_dim 256: LaneAddr's precomputed offsets (one XOR per read); its read_row takes a row tile, always 0 here
+  struct Pow2Addr : LaneAddr<D> {
+    __device__ __forceinline__ Pow2Addr(int l_) : LaneAddr<D>(l_) {}
+    __device__ __forceinline__ ex8<E> read_row(const E* tile, int ks) const { return LaneAddr<D>::read_row(tile, 0, ks); }
+  };
+  const std::conditional_t<(D & (D - 1)) == 0, Pow2Addr, PlainAddr<D>> la(l);
 
   // state slice S[:, dv tile] in accumulator layout: chunk start state, the caller's start state, or zero
   // (the pre-pass forms LOCAL states, from zero)
