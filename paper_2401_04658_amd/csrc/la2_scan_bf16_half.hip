@@ -39,8 +39,10 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
   using Loader = TileLoader<D, NTL, B, NW>;
   __shared__ __attribute__((aligned(1024))) E sT[NBUF][NTL][TILE];
-  constexpr int STAGE_ROWS = NORM ? 16 : 32;   // positions staged at a time
-  __shared__ __attribute__((aligned(16))) E sW[NW][STAGE_ROWS * LW];
+  // Output staging, 32 positions x 32 features per wave.  The NORM variant has no LDS left for it beside its
+  // exchange buffer (two workgroups of 80 KiB per compute unit) and stages in the block's own X tile instead,
+  // which is dead by then: see the epilogue.
+  __shared__ __attribute__((aligned(16))) E sW[NW][NORM ? LW : 32 * LW];
   float* const sRed = NormExchange<NORM ? 2 * 32 * 4 : 0>::get();   // [block parity][position][wave]
   // Cache policy of the output stores (buffer instruction bits: 2 = nt, 16 = sc1).  Measured: the twin
   // workgroup, a third of whose traffic is stores, runs 9-13 % faster with streaming write-through stores;
@@ -293,46 +295,28 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
 #pragma unroll
       for (int v = 0; v < 16; v++) inter[v] *= r;
       pin(inter);
-      ex4<E> pk[4];
-#pragma unroll
-      for (int g = 0; g < 4; g++)
-#pragma unroll
-        for (int e = 0; e < 4; e++) pk[g][e] = (E)inter[4 * g + e];
-#pragma unroll
-      for (int half = 0; half < 2; half++) {   // this wave's LDS operations run in order: no barrier needed
-        if ((l32 >> 4) == half) {
-#pragma unroll
-          for (int g = 0; g < 4; g++)
-            *reinterpret_cast<ex4<E>*>(stage + (l32 & 15) * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk[g];
-        }
-        // Lanes read what OTHER lanes wrote under a mask: without this the compiler treats the read of a
-        // lane that wrote nothing as a repeat of its previous read and drops it.
-        asm volatile("" ::: "memory");
-        const int row = l >> 2, cc = l & 3;
-        const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
-        const uint32_t off =
-            ((uint32_t)(blk * B + 16 * half + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
-        __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, 0);
-      }
       // r of this block's positions: the lanes of wave 0 that hold them; every other lane's store is dropped
       const uint32_t roff = (dvt == 0 && hh == 0) ? (uint32_t)(blk * B + l32) * 4u : 0xFFFFFFF0u;
       __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(r), brs, roff, 0, 0);
-    } else {
+    }
+    // Staging area of this wave.  NORM: the quarter of this block's X tile that this wave's own direct loads
+    // fill.  Every wave is past the block's last tile read (the barrier above), and the next writer of that
+    // quarter is this wave's own direct load two blocks on, issued after the reads below have returned.
+    E* const st = NORM ? const_cast<E*>(tX) + w * (TILE / 4) : stage;
 #pragma unroll
     for (int g = 0; g < 4; g++) {
       ex4<E> pk;
 #pragma unroll
       for (int e = 0; e < 4; e++) pk[e] = (E)inter[4 * g + e];
-      *reinterpret_cast<ex4<E>*>(stage + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
+      *reinterpret_cast<ex4<E>*>(st + l32 * LW + 8 * (g ^ ((l32 >> 2) & 3)) + 4 * hh) = pk;
     }
 #pragma unroll
     for (int i = 0; i < 32 * 4 / 64; i++) {
       const int id = l + 64 * i;
       const int row = id >> 2, cc = id & 3;
-      const i32x4 v = *reinterpret_cast<const i32x4*>(stage + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
+      const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * LW + 8 * (cc ^ ((row >> 2) & 3)));
       const uint32_t off = ((uint32_t)(blk * B + row) * stride_n + (uint32_t)(32 * dvt + cc * 8)) * 2u;
       __builtin_amdgcn_raw_buffer_store_b128(v, bw, off, 0, kStorePolicy);
-    }
     }
     LA2_SLOT_END();
     return has_next;
