@@ -255,3 +255,63 @@ def test_backward_reuses_the_forward_chunk_states(d, n):
         refs = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=to64(t["kv_init"]) if use_init else None)
         for name, x, ref in zip(("dq", "dk", "dv", "d_kv_init"), got, refs):
             assert_close("saved states d%d n%d init=%s %s" % (d, n, use_init, name), x, ref, torch.bfloat16)
+
+
+@pytest.mark.parametrize("d", DIMS)
+def test_hip_graph_capture_and_replay(d):
+    """A sequence-chunked forward and backward (pre-pass, state scan, scans, dual reverse launch), the normalised
+    operator and a packed batch at these head dimensions in one captured graph; every replay reproduces the
+    eager results bit for bit."""
+    binding.la2_set_chunk_tokens(128)
+    b, H, n = 1, 2, 600
+    t, g = inputs(b, H, n, d, torch.bfloat16, seed=2200 + d, lam=[0.9, 0.99])
+    ws = torch.empty(max(256, binding.la2_workspace_bytes(g["q"], 1)), dtype=torch.uint8, device=DEV)
+    lengths = [100, 0, 333, 167]
+    pk = {name: g[name][0].permute(1, 0, 2).contiguous() for name in ("q", "k", "v", "d_o")}   # [n, H, d]
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device=DEV)
+    ws_p = torch.empty(16 << 20, dtype=torch.uint8, device=DEV)
+
+    def run(out):
+        binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"], out=out["o"], workspace=ws)
+        binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"], out=out["grads"], workspace=ws)
+        binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], 1e-5, out=out["on"], rstd=out["rstd"], workspace=ws)
+        binding.la2_bwd_norm(g["q"], g["k"], g["v"], out["on"], out["rstd"], g["d_o"], g["lam"], out=out["gn"],
+                             d_u=out["du"], workspace=ws)
+        binding.la2_fwd_varlen(pk["q"], pk["k"], pk["v"], g["lam"], cu, max(lengths), out=out["op"], workspace=ws_p)
+        binding.la2_bwd_varlen(pk["q"], pk["k"], pk["v"], pk["d_o"], g["lam"], cu, max(lengths), out=out["gp"],
+                               workspace=ws_p)
+
+    def buffers():
+        like, likep = (lambda: torch.empty_like(g["q"])), (lambda: torch.empty_like(pk["q"]))
+        return {"o": like(), "grads": (like(), like(), like()), "on": like(), "rstd": torch.empty((b, H, n), device=DEV),
+                "gn": (like(), like(), like()), "du": like(), "op": likep(), "gp": (likep(), likep(), likep())}
+
+    def flat(out):
+        return [out["o"], *out["grads"], out["on"], out["rstd"], *out["gn"], out["du"], out["op"], *out["gp"]]
+
+    assert binding.la2_workspace_bytes(g["q"], 0) > 0
+    eager = buffers()
+    run(eager)
+    torch.cuda.synchronize()
+    captured = buffers()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(captured)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(captured)
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(3):
+        for x in flat(captured):
+            x.fill_(float("nan"))
+        ws.random_(0, 255)
+        ws_p.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(flat(captured), flat(eager))):
+            assert torch.equal(got, ref), (replay, i)
+        run(buffers())                 # eager work between the replays
+        torch.cuda.synchronize()
