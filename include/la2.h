@@ -165,6 +165,21 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                         void* dk, void* dv, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The normalised operator on one SEGMENT of a longer sequence: la2_fwd_norm / la2_bwd_norm with the state
+ * arguments of la2_fwd_state / la2_bwd_state (same meaning, layout and workspace: LA2_OP_FWD_STATE /
+ * LA2_OP_BWD_STATE).  The state carries the un-normalised recurrence of Sec. 3.2.1; only the output rows are
+ * normalised (eq. (2)), so kv_final and the state gradients are those of the un-normalised operator for d_u.
+ * rstd, o, d_u as in la2_fwd_norm / la2_bwd_norm.  An empty sequence passes the state (its gradient) through.
+ */
+la2_status la2_fwd_state_norm(const la2_desc* desc, const void* q, const void* k, const void* v,
+                              const float* lambda, const float* kv_init, float eps, void* o, float* rstd,
+                              float* kv_final, void* workspace, size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_state_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                              const float* rstd, const void* d_o, const float* lambda, const float* kv_init,
+                              const float* d_kv_final, void* d_u, void* dq, void* dk, void* dv,
+                              float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Algorithm 1 / Algorithm 2 over PACKED sequences of different lengths (a batch without padding): the
  * tensors are [total_positions, heads, head_dim]; sequence b occupies positions cu_seqlens[b] ..
  * cu_seqlens[b + 1] - 1 and is a chain of its own (zero start state, no interaction with its neighbours).
@@ -196,6 +211,15 @@ la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const
 la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype,
                            const void* q, const void* k, const void* v, const float* lambda,
                            float* kv_state, void* o, void* hip_stream);
+
+/*
+ * The decode step of the normalised operator (eq. (2) with Norm read as in la2_fwd_norm): the same state update,
+ * and the output row divided by sqrt(mean_j o_j^2 + eps) before it is stored.  eps as for la2_fwd_norm
+ * (LA2_ERR_VALUE).
+ */
+la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype,
+                                const void* q, const void* k, const void* v, const float* lambda,
+                                float* kv_state, float eps, void* o, void* hip_stream);
 
 /*
  * la2_bwd_state for callers that kept the forward pass's workspace (a training step): fwd_workspace is the

@@ -16,4 +16,4 @@ from .ref import (  # noqa: F401
     bwd_rows,
 )
 from .block_form import alg1_forward, alg2_backward  # noqa: F401
-from .norm import fwd_norm, bwd_norm, norm_backward_rows  # noqa: F401
+from .norm import fwd_norm, bwd_norm, norm_backward_rows, fwd_norm_state, bwd_norm_state  # noqa: F401

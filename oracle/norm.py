@@ -29,6 +29,21 @@ def fwd_norm(q, k, v, lam, eps):
     return u * rstd[..., None], rstd
 
 
+def fwd_norm_state(q, k, v, lam, eps, kv_init=None):
+    """One segment of a longer sequence (recurrence of Sec. 3.2.1 started from kv_init): returns (o, rstd,
+    kv_final).  The state carries the un-normalised recurrence; only the output rows are normalised."""
+    u, kv_final = ref.fwd_recurrent(q, k, v, lam, kv_init=kv_init, return_state=True)
+    rstd = 1.0 / np.sqrt(np.mean(u * u, axis=-1) + eps)
+    return u * rstd[..., None], rstd, kv_final
+
+
+def bwd_norm_state(q, k, v, d_o, lam, eps, kv_init=None, d_kv_final=None):
+    """Gradients (dq, dk, dv, d_kv_init) of sum(d_o * o) + sum(d_kv_final * kv_final) for fwd_norm_state."""
+    o, rstd, _ = fwd_norm_state(q, k, v, lam, eps, kv_init)
+    du = norm_backward_rows(o, rstd, d_o)
+    return ref.bwd_recurrent_state(q, k, v, du, lam, kv_init=kv_init, d_kv_final=d_kv_final)
+
+
 def norm_backward_rows(o, rstd, g):
     """dU from the normalised output o, r_t and the incoming gradient g (all per row)."""
     o = np.asarray(o, dtype=np.float64)

@@ -57,6 +57,12 @@ def load():
     lib.la2_set_chunk_tokens.restype = None
     lib.la2_set_scan_variant.argtypes = [i32]
     lib.la2_set_scan_variant.restype = None
+    lib.la2_fwd_state_norm.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, sz, vp]
+    lib.la2_fwd_state_norm.restype = ctypes.c_int
+    lib.la2_bwd_state_norm.argtypes = [dp] + [vp] * 15 + [sz, vp]
+    lib.la2_bwd_state_norm.restype = ctypes.c_int
+    lib.la2_decode_step_norm.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.la2_decode_step_norm.restype = ctypes.c_int
     lib.la2_stream_probe.argtypes = [i32, i32, i32, vp, vp, sz, vp]
     lib.la2_stream_probe.restype = ctypes.c_int
     lib.la2_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -417,3 +423,79 @@ def la2_stream_probe(reads, writes, src, dst, bytes_per_stream, nt_stores=False)
     with torch.cuda.device(src.device):
         _check(lib.la2_stream_probe(reads, writes, 1 if nt_stores else 0, src.data_ptr(), dst.data_ptr(),
                                     bytes_per_stream, _stream(src)))
+
+
+def la2_fwd_state_norm(q, k, v, lam, eps=1e-6, kv_init=None, want_final=True, out=None, rstd=None, kv_final=None,
+                       workspace=None):
+    """la2_fwd_norm on one segment of a sequence, started from kv_init.  Returns (o, rstd, kv_final or None)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_state_norm: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    b, h, n, d = q.shape
+    if rstd is None:
+        rstd = torch.empty((b, h, n), dtype=torch.float32, device=q.device)
+    if rstd.dtype != torch.float32 or tuple(rstd.shape) != (b, h, n) or not rstd.is_contiguous():
+        raise ValueError("la2_fwd_state_norm: rstd must be a contiguous fp32 [batch, heads, seqlen] tensor")
+    if want_final and kv_final is None:
+        kv_final = torch.empty((b, h, d, d), dtype=torch.float32, device=q.device)
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_FWD_STATE, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_state_norm(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
+                                      _state(kv_init, q, "kv_init"), float(eps), out.data_ptr(), rstd.data_ptr(),
+                                      _state(kv_final, q, "kv_final") if want_final else None,
+                                      ws_ptr, ws_bytes, _stream(q)))
+    return out, rstd, (kv_final if want_final else None)
+
+
+def la2_bwd_state_norm(q, k, v, o, rstd, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_init=True, out=None,
+                       d_u=None, d_kv_init=None, workspace=None):
+    """Backward of la2_fwd_state_norm.  Returns (dq, dk, dv, d_kv_init or None)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd_state_norm: tensors must live on the GPU")
+    _same_layout(q, k, v, o, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    if d_u is None:
+        d_u = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, d_u, *out)
+    b, h, n, d = q.shape
+    if rstd.dtype != torch.float32 or tuple(rstd.shape) != (b, h, n) or not rstd.is_contiguous():
+        raise ValueError("la2_bwd_state_norm: rstd must be a contiguous fp32 [batch, heads, seqlen] tensor")
+    if want_d_kv_init and d_kv_init is None:
+        d_kv_init = torch.empty((b, h, d, d), dtype=torch.float32, device=q.device)
+    desc = make_desc(q)
+    ws_ptr, ws_bytes, _keep = _workspace(q, LA2_OP_BWD_STATE, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd_state_norm(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                      rstd.data_ptr(), d_o.data_ptr(), lam.data_ptr(), _state(kv_init, q, "kv_init"),
+                                      _state(d_kv_final, q, "d_kv_final"), d_u.data_ptr(), out[0].data_ptr(),
+                                      out[1].data_ptr(), out[2].data_ptr(),
+                                      _state(d_kv_init, q, "d_kv_init") if want_d_kv_init else None,
+                                      ws_ptr, ws_bytes, _stream(q)))
+    return out[0], out[1], out[2], (d_kv_init if want_d_kv_init else None)
+
+
+def la2_decode_step_norm(q, k, v, lam, kv_state, eps=1e-6, out=None):
+    """One recurrent step of the normalised operator; kv_state (fp32 [b, H, d, d]) is updated in place, returns
+    the normalised o [b, H, d]."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_decode_step_norm: tensors must live on the GPU")
+    b, h, d = q.shape
+    for t in (q, k, v):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("la2_decode_step_norm: q, k, v must be dense [b, H, d] of one dtype")
+    if kv_state.dtype != torch.float32 or tuple(kv_state.shape) != (b, h, d, d) or not kv_state.is_contiguous():
+        raise ValueError("la2_decode_step_norm: kv_state must be dense fp32 [b, H, d, d]")
+    if out is None:
+        out = torch.empty_like(q)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_decode_step_norm(b, h, d, _dtype_code(q), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                        lam.data_ptr(), kv_state.data_ptr(), float(eps), out.data_ptr(), _stream(q)))
+    return out

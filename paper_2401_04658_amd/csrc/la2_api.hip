@@ -114,6 +114,7 @@ struct ScanArgs {
   // Norm epilogue (forward scans): r of every position goes here, the output rows are scaled by it
   float* rstd = nullptr;
   float eps = 0.f;
+  int rstd_stride = 0;   // positions per chain in rstd
   // packed sequences of different lengths: device array of batch + 1 position offsets, or nullptr
   const int32_t* cu = nullptr;
 };
@@ -167,6 +168,7 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
   p.fin[0] = a.fin;
   p.rstd = a.rstd;
   p.eps = a.eps;
+  p.rstd_stride = a.rstd_stride;
   hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, false, p, s)
                 : is16(d->dtype)   ? la2::launch_scan_bf16(d->dtype, d->head_dim, reverse, p, s)
                                    : la2::launch_scan_f32(d->head_dim, reverse, p, s);
@@ -221,6 +223,13 @@ StateWorkspace state_workspace(const la2_desc* d, bool backward) {
   return w;
 }
 
+// Workspace bytes the backward of a segment needs: the hand-over state only when a gradient comes in at a
+// ragged end.
+size_t bwd_workspace_need(const la2_desc* d, bool has_d_kv_final) {
+  const bool split = has_d_kv_final && d->seqlen % state_granule(d) != 0;
+  return split ? state_workspace(d, true).total : make_plan(d).workspace;
+}
+
 la2::RecurParams recur_params(const la2_desc* d, const float* lambda, int t0, int t1, bool reverse) {
   la2::RecurParams p{};
   p.lambda = lambda;
@@ -269,9 +278,14 @@ void la2_set_chunk_tokens(int32_t tokens) { g_chunk_tokens_override = tokens > 0
 
 void la2_set_scan_variant(int32_t variant) { g_scan_variant = (variant == 1 || variant == 2) ? variant : 0; }
 
-la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
-                         const float* kv_init, void* o, float* kv_final, void* workspace, size_t workspace_bytes,
-                         void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// la2_fwd_state, and with rstd != nullptr the same with the Norm epilogue (eps validated by the caller)
+la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                          const float* kv_init, void* o, float* kv_final, float* rstd, float eps, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   const int64_t chains = (int64_t)desc->batch * desc->heads;
@@ -284,15 +298,23 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
                ? LA2_OK : LA2_ERR_LAUNCH;
   }
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
-  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
+      !aligned(rstd, 4))
     return LA2_ERR_STRIDE_ALIGN;
+  // the Norm epilogue as a row pass of its own, in place, over positions [t0, t1): for fp32 rows that the token
+  // recurrence wrote (fp32 storage: nothing is lost between the two passes)
+  auto normalise_rows = [&](int t0, int t1) {
+    const la2::NormBwdParams np{o, nullptr, rstd, o, desc->stride_b, desc->stride_h, desc->stride_n,
+                                desc->batch, desc->heads, t1 - t0, t0, desc->seqlen};
+    return la2::launch_norm_fwd_rows(desc->head_dim, desc->dtype, np, eps, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  };
   if (wide(desc->head_dim) && !is16(desc->dtype)) {   // fp32 at head_dim 96 / 256: token by token
     la2::RecurParams r = recur_params(desc, lambda, 0, desc->seqlen, false);
     r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
     r.init[0] = kv_init;
     r.fin[0] = kv_final;
-    return la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s) == hipSuccess ? LA2_OK
-                                                                                               : LA2_ERR_LAUNCH;
+    if (la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s) != hipSuccess) return LA2_ERR_LAUNCH;
+    return rstd != nullptr ? normalise_rows(0, desc->seqlen) : LA2_OK;
   }
   const bool split = kv_final != nullptr && desc->seqlen % state_granule(desc) != 0;
   const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the block kernels process
@@ -303,6 +325,9 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
     ScanArgs a{q, k, v, o};
     a.init = kv_init;
     a.fin = kv_final;
+    a.rstd = rstd;
+    a.eps = eps;
+    a.rstd_stride = desc->seqlen;
     st = run_scan(&blocks, pl, false, a, lambda, workspace, s);
     if (st != LA2_OK || !split) return st;
   }
@@ -311,9 +336,25 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = blocks.seqlen > 0 ? kv_final : kv_init;
   r.fin[0] = kv_final;
-  const hipError_t e = is16(desc->dtype) ? la2::launch_tail_bf16(desc->dtype, desc->head_dim, desc->batch, r, s)
-                                         : la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s);
-  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  if (is16(desc->dtype)) {   // block kernel for short runs, with the epilogue
+    r.rstd = rstd;
+    r.eps = eps;
+    r.rstd_stride = desc->seqlen;
+    return la2::launch_tail_bf16(desc->dtype, desc->head_dim, desc->batch, r, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  }
+  if (la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s) != hipSuccess) return LA2_ERR_LAUNCH;
+  return rstd != nullptr ? normalise_rows(blocks.seqlen, desc->seqlen) : LA2_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                         const float* kv_init, void* o, float* kv_final, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  return fwd_state_impl(desc, q, k, v, lambda, kv_init, o, kv_final, nullptr, 0.f, workspace, workspace_bytes,
+                        hip_stream);
 }
 
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
@@ -418,33 +459,49 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
                        workspace_bytes, hip_stream);
 }
 
-la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
-                        float eps, void* o, float* rstd, void* workspace, size_t workspace_bytes,
-                        void* hip_stream) {
+la2_status la2_fwd_state_norm(const la2_desc* desc, const void* q, const void* k, const void* v,
+                              const float* lambda, const float* kv_init, float eps, void* o, float* rstd,
+                              float* kv_final, void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
-  if (!q || !k || !v || !o || !rstd || !lambda) return LA2_ERR_NULL;
-  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(rstd, 4) ||
-      !aligned(lambda, 4))
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen != 0 && rstd == nullptr) return LA2_ERR_NULL;
+  return fwd_state_impl(desc, q, k, v, lambda, kv_init, o, kv_final, rstd, eps, workspace, workspace_bytes,
+                        hip_stream);
+}
+
+la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                        float eps, void* o, float* rstd, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  return la2_fwd_state_norm(desc, q, k, v, lambda, nullptr, eps, o, rstd, nullptr, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+la2_status la2_bwd_state_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                              const float* rstd, const void* d_o, const float* lambda, const float* kv_init,
+                              const float* d_kv_final, void* d_u, void* dq, void* dk, void* dv, float* d_kv_init,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0)   // no rows: only the state's gradient passes through
+    return la2_bwd_state(desc, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, workspace,
+                         workspace_bytes, hip_stream);
+  if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(dq, 16) || !aligned(dk, 16) ||
+      !aligned(dv, 16) || !aligned(lambda, 4) || !aligned(kv_init, 16) || !aligned(d_kv_final, 16) ||
+      !aligned(d_kv_init, 16))
     return LA2_ERR_STRIDE_ALIGN;
-  const Plan pl = make_plan(desc);
-  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
-  if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  if (wide(desc->head_dim) && !is16(desc->dtype)) {
-    // fp32 at head_dim 96 / 256: the token recurrence writes u, a row pass normalises it in place
-    st = la2_fwd(desc, q, k, v, lambda, o, workspace, workspace_bytes, hip_stream);
-    if (st != LA2_OK) return st;
-    return la2::launch_norm_fwd_rows_f32(desc->head_dim, static_cast<float*>(o), rstd, eps, desc->stride_b,
-                                         desc->stride_h, desc->stride_n, desc->batch, desc->heads, desc->seqlen,
-                                         reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess
-               ? LA2_OK : LA2_ERR_LAUNCH;
-  }
-  ScanArgs a{q, k, v, o};
-  a.rstd = rstd;
-  a.eps = eps;
-  return run_scan(desc, pl, false, a, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  const size_t need = bwd_workspace_need(desc, d_kv_final != nullptr);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
+    return LA2_ERR_WORKSPACE;
+  const la2::NormBwdParams np{o, d_o, rstd, d_u, desc->stride_b, desc->stride_h, desc->stride_n,
+                              desc->batch, desc->heads, desc->seqlen, 0, desc->seqlen};
+  if (la2::launch_norm_bwd_rows(desc->head_dim, desc->dtype, np,
+                                reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return LA2_ERR_LAUNCH;
+  return la2_bwd_state(desc, q, k, v, d_u, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, workspace,
+                       workspace_bytes, hip_stream);
 }
 
 la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const void* o,
@@ -453,20 +510,8 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
-  if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
-  if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;
-  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(dq, 16) || !aligned(dk, 16) ||
-      !aligned(dv, 16) || !aligned(lambda, 4))
-    return LA2_ERR_STRIDE_ALIGN;
-  const size_t need = make_plan(desc).workspace;
-  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
-    return LA2_ERR_WORKSPACE;
-  la2::NormBwdParams np{o, d_o, rstd, d_u, desc->stride_b, desc->stride_h, desc->stride_n,
-                        desc->batch, desc->heads, desc->seqlen};
-  if (la2::launch_norm_bwd_rows(desc->head_dim, desc->dtype, np,
-                                reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
-    return LA2_ERR_LAUNCH;
-  return la2_bwd(desc, q, k, v, d_u, lambda, dq, dk, dv, workspace, workspace_bytes, hip_stream);
+  return la2_bwd_state_norm(desc, q, k, v, o, rstd, d_o, lambda, nullptr, nullptr, d_u, dq, dk, dv, nullptr,
+                            workspace, workspace_bytes, hip_stream);
 }
 
 la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
@@ -532,20 +577,39 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
              ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
-la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
-                           const void* k, const void* v, const float* lambda, float* kv_state, void* o,
-                           void* hip_stream) {
+}  // extern "C"
+
+namespace {
+la2_status decode_step_impl(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
+                            const void* k, const void* v, const float* lambda, float* kv_state, void* o, bool norm,
+                            float eps, void* hip_stream) {
   if (qkv_dtype != LA2_F32 && !is16(qkv_dtype)) return LA2_ERR_DTYPE;
   if (batch < 0 || heads < 0 || !supported_head_dim(head_dim)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
+  if (norm && (!(eps >= 0.f) || eps > 3.0e38f)) return LA2_ERR_VALUE;
   if ((int64_t)batch * heads == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(kv_state, 16) ||
       !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  hipError_t e = la2::launch_decode(batch, heads, head_dim, qkv_dtype, q, k, v, lambda, kv_state, o,
+  hipError_t e = la2::launch_decode(batch, heads, head_dim, qkv_dtype, q, k, v, lambda, kv_state, o, norm, eps,
                                     reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+}  // namespace
+
+extern "C" {
+
+la2_status la2_decode_step(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
+                           const void* k, const void* v, const float* lambda, float* kv_state, void* o,
+                           void* hip_stream) {
+  return decode_step_impl(batch, heads, head_dim, qkv_dtype, q, k, v, lambda, kv_state, o, false, 0.f, hip_stream);
+}
+
+la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, int32_t qkv_dtype, const void* q,
+                                const void* k, const void* v, const float* lambda, float* kv_state, float eps,
+                                void* o, void* hip_stream) {
+  return decode_step_impl(batch, heads, head_dim, qkv_dtype, q, k, v, lambda, kv_state, o, true, eps, hip_stream);
 }
 
 la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,

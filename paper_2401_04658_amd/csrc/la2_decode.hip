@@ -30,9 +30,12 @@ __device__ __forceinline__ void store_elem(void* p, int64_t i, float x) {
   else reinterpret_cast<float*>(p)[i] = x;
 }
 
-template <int D, int DT>
+// NORM: the output row is normalised (eq. (2) read as root-mean-square normalisation over the head's features:
+// o <- o / sqrt(mean_j o_j^2 + eps)) before it is stored.
+template <int D, int DT, bool NORM = false>
 __global__ __launch_bounds__(threads_for(D)) void decode_kernel(const void* q, const void* k, const void* v,
-                                                          const float* lambda, float* kv, void* o, int heads) {
+                                                          const float* lambda, float* kv, void* o, int heads,
+                                                          float eps) {
   constexpr int kThreads = threads_for(D);
   constexpr int TPR = D / 4;            // threads per state row (float4 each)
   constexpr int RG = kThreads / TPR;    // rows in flight per sweep
@@ -77,13 +80,26 @@ __global__ __launch_bounds__(threads_for(D)) void decode_kernel(const void* q, c
   }
   sacc[rg][cg] = acc;
   __syncthreads();
+  float sum = 0.f;
   if (tid < D) {
     const float* flat = reinterpret_cast<const float*>(sacc);
-    float sum = 0.f;
 #pragma unroll
     for (int g = 0; g < RG; g++) sum += flat[g * D + tid];
-    store_elem<DT>(o, chain * D + tid, sum);
   }
+  if (NORM) {   // sum of squares over the row: inside each wave by lane exchanges, across the waves through LDS
+    constexpr int NWAVE = (D + 63) / 64;   // waves that hold row elements
+    __shared__ float ssq[NWAVE];
+    float s2 = sum * sum;                  // 0 for tid >= D
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) s2 += __shfl_xor(s2, m);
+    if (tid < D && (tid & 63) == 0) ssq[tid >> 6] = s2;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < NWAVE; i++) tot += ssq[i];
+    sum *= 1.f / sqrtf(tot * (1.f / (float)D) + eps);
+  }
+  if (tid < D) store_elem<DT>(o, chain * D + tid, sum);
 }
 
 __global__ void state_copy_kernel(float* dst, const float* src, int64_t count) {
@@ -100,12 +116,18 @@ hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStr
 }
 
 hipError_t launch_decode(int batch, int heads, int head_dim, int dtype, const void* q, const void* k,
-                         const void* v, const float* lambda, float* kv, void* o, hipStream_t s) {
+                         const void* v, const float* lambda, float* kv, void* o, bool norm, float eps,
+                         hipStream_t s) {
   const int64_t chains = (int64_t)batch * heads;
   if (chains == 0) return hipSuccess;
   dim3 g((unsigned)chains);
-#define LA2_LAUNCH_DECODE(D, DT) \
-  hipLaunchKernelGGL((decode_kernel<D, DT>), g, dim3(threads_for(D)), 0, s, q, k, v, lambda, kv, o, heads)
+#define LA2_LAUNCH_DECODE(D, DT)                                                                                    \
+  do {                                                                                                              \
+    if (norm) hipLaunchKernelGGL((decode_kernel<D, DT, true>), g, dim3(threads_for(D)), 0, s, q, k, v, lambda, kv, \
+                                 o, heads, eps);                                                                    \
+    else      hipLaunchKernelGGL((decode_kernel<D, DT, false>), g, dim3(threads_for(D)), 0, s, q, k, v, lambda, kv, \
+                                 o, heads, eps);                                                                    \
+  } while (0)
 #define LA2_LAUNCH_DECODE_D(D)                         \
   do {                                                 \
     if (dtype == kBF16) LA2_LAUNCH_DECODE(D, kBF16);   \

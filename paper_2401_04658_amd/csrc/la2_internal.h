@@ -47,9 +47,11 @@ struct ScanParams {
   int32_t fin_transposed;
   // Norm epilogue of a forward scan (eq. (2); scan 0 only, the fp32 kernels and the forward bf16 kernels):
   // when rstd is not nullptr every output row is multiplied by r = 1 / sqrt(mean_j w_j^2 + eps) before it is
-  // stored, and r goes to rstd[chain * n + position] (fp32).
+  // stored, and r goes to rstd[chain * rstd_stride + position] (fp32; rstd_stride >= n: a launch over the whole
+  // blocks of a longer segment writes into the segment's array).
   float* rstd;
   float eps;
+  int32_t rstd_stride;
   // Packed sequences of different lengths (nullptr: a dense batch).  Device array of batch + 1 position
   // offsets: sequence b is positions cu_seqlens[b] .. cu_seqlens[b + 1] - 1 of a [total, heads, d] tensor
   // (stride_b unused); n is then the longest sequence's length, what the launch is planned for.
@@ -138,6 +140,10 @@ struct RecurParams {
   int32_t t0, t1;
   int32_t reverse;
   int64_t stride_b, stride_h, stride_n;  // elements, all of x, y, z, w
+  // Norm epilogue (launch_tail_bf16 only): as ScanParams; r of position t goes to rstd[chain * rstd_stride + t]
+  float* rstd;
+  float eps;
+  int32_t rstd_stride;
 };
 hipError_t launch_recur(int head_dim, int dtype, int batch, int ninst, const RecurParams& p, hipStream_t s);
 // The forward case of the same for 16-bit data (instance 0 only, reverse == 0) as a block kernel: MFMA in
@@ -147,6 +153,7 @@ hipError_t launch_tail_bf16(int dtype, int head_dim, int batch, const RecurParam
 // Backward of the Norm epilogue, row by row: du = rstd * (g - o * mean_j(g_j o_j)) with o the normalised
 // output and g its gradient; o, g, du share the layout given by the strides (elements), rstd is
 // [batch * heads][n] fp32.
+// The rows are positions t0 .. t0 + n - 1 of every chain; r of position t is rstd[chain * rstd_stride + t].
 struct NormBwdParams {
   const void* o;
   const void* g;
@@ -154,18 +161,21 @@ struct NormBwdParams {
   void* du;
   int64_t stride_b, stride_h, stride_n;
   int32_t batch, heads, n;
+  int32_t t0, rstd_stride;
 };
 hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s);
-// The forward normalisation as a pass of its own, in place: o <- o r, r = 1 / sqrt(mean_j o_j^2 + eps) -> rstd
-// (fp32 data at head_dim 96 / 256 only: every other path normalises inside its scan kernel).
-hipError_t launch_norm_fwd_rows_f32(int head_dim, float* o, float* rstd, float eps, int64_t stride_b,
-                                    int64_t stride_h, int64_t stride_n, int batch, int heads, int n, hipStream_t s);
+// The forward normalisation as a pass of its own, in place, over the same rows: o <- o r with
+// r = 1 / sqrt(mean_j o_j^2 + eps) written to rstd (p.g unused, p.du == p.o).  For the paths whose kernels have
+// no epilogue: the short-run kernels behind a segment's last block, and fp32 data at head_dim 96 / 256.
+hipError_t launch_norm_fwd_rows(int head_dim, int dtype, const NormBwdParams& p, float eps, hipStream_t s);
 
 // dst[i] = src ? src[i] : 0 for count floats (a state that passes through an empty sequence)
 hipError_t launch_state_copy(float* dst, const float* src, int64_t count, hipStream_t s);
 
+// norm: the output row is divided by sqrt(mean of its squares + eps) before it is stored
 hipError_t launch_decode(int batch, int heads, int head_dim, int dtype, const void* q, const void* k,
-                         const void* v, const float* lambda, float* kv, void* o, hipStream_t s);
+                         const void* v, const float* lambda, float* kv, void* o, bool norm, float eps,
+                         hipStream_t s);
 
 }  // namespace la2
 #endif

@@ -6,8 +6,9 @@
 // number of lanes (one piece per lane; three at head_dim 96), the row mean by lane exchanges inside the
 // group; streaming (non-temporal) loads and stores, measured 9 % faster than the default cache policy.
 //
-// Also here: the forward normalisation as a pass of its own, in place, for the one path whose scan has no
-// epilogue (fp32 data at head_dim 96 / 256, which runs the token recurrence).
+// Also here: the forward normalisation as a pass of its own, in place, for the paths whose kernels have no
+// epilogue (the short-run kernels behind the last whole block of a segment; fp32 data at head_dim 96 / 256,
+// which runs the token recurrence).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -64,7 +65,8 @@ __global__ __launch_bounds__(kThreads) void norm_rows_kernel(NormBwdParams p, fl
   const int piece = threadIdx.x % LPR;
   const bool live = row < rows;                 // whole row groups are live or not: the exchanges stay inside a group
   const int64_t rr = live ? row : 0;
-  const int64_t chain = rr / p.n, pos = rr % p.n;
+  const int64_t chain = rr / p.n, pos = p.t0 + rr % p.n;
+  const int64_t ri = chain * p.rstd_stride + pos;   // this row's r
   const int64_t off = (chain / p.heads) * p.stride_b + (chain % p.heads) * p.stride_h + pos * p.stride_n + piece * N;
   Row16<T> o[PPL], g[PPL];
   float c = 0.f;
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void norm_rows_kernel(NormBwdParams p, fl
 #pragma unroll
   for (int m = 1; m < LPR; m <<= 1) c += __shfl_xor(c, m);
   c *= 1.f / (float)D;
-  const float r = FWD ? 1.f / sqrtf(c + eps) : p.rstd[rr];
+  const float r = FWD ? 1.f / sqrtf(c + eps) : p.rstd[ri];
 #pragma unroll
   for (int j = 0; j < PPL; j++) {
     Row16<T> out;
@@ -89,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void norm_rows_kernel(NormBwdParams p, fl
     if (live)
       __builtin_nontemporal_store(out.v, reinterpret_cast<decltype(out.v)*>(reinterpret_cast<T*>(p.du) + off + j * LPR * N));
   }
-  if (FWD && live && piece == 0) const_cast<float*>(p.rstd)[rr] = r;
+  if (FWD && live && piece == 0) const_cast<float*>(p.rstd)[ri] = r;
 }
 
 template <typename T, int D, bool FWD>
@@ -103,26 +105,26 @@ hipError_t launch(const NormBwdParams& p, float eps, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <typename T>
-hipError_t launch_bwd_d(int head_dim, const NormBwdParams& p, hipStream_t s) {
-  if (head_dim == 256) return launch<T, 256, false>(p, 0.f, s);
-  if (head_dim == 128) return launch<T, 128, false>(p, 0.f, s);
-  if (head_dim == 96) return launch<T, 96, false>(p, 0.f, s);
-  return launch<T, 64, false>(p, 0.f, s);
+template <typename T, bool FWD>
+hipError_t launch_d(int head_dim, const NormBwdParams& p, float eps, hipStream_t s) {
+  if (head_dim == 256) return launch<T, 256, FWD>(p, eps, s);
+  if (head_dim == 128) return launch<T, 128, FWD>(p, eps, s);
+  if (head_dim == 96) return launch<T, 96, FWD>(p, eps, s);
+  return launch<T, 64, FWD>(p, eps, s);
 }
 
 }  // namespace
 
 hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s) {
-  if (dtype == kBF16) return launch_bwd_d<__bf16>(head_dim, p, s);
-  if (dtype == kF16) return launch_bwd_d<_Float16>(head_dim, p, s);
-  return launch_bwd_d<float>(head_dim, p, s);
+  if (dtype == kBF16) return launch_d<__bf16, false>(head_dim, p, 0.f, s);
+  if (dtype == kF16) return launch_d<_Float16, false>(head_dim, p, 0.f, s);
+  return launch_d<float, false>(head_dim, p, 0.f, s);
 }
 
-hipError_t launch_norm_fwd_rows_f32(int head_dim, float* o, float* rstd, float eps, int64_t stride_b,
-                                    int64_t stride_h, int64_t stride_n, int batch, int heads, int n, hipStream_t s) {
-  const NormBwdParams p{o, nullptr, rstd, o, stride_b, stride_h, stride_n, batch, heads, n};
-  return head_dim == 256 ? launch<float, 256, true>(p, eps, s) : launch<float, 96, true>(p, eps, s);
+hipError_t launch_norm_fwd_rows(int head_dim, int dtype, const NormBwdParams& p, float eps, hipStream_t s) {
+  if (dtype == kBF16) return launch_d<__bf16, true>(head_dim, p, eps, s);
+  if (dtype == kF16) return launch_d<_Float16, true>(head_dim, p, eps, s);
+  return launch_d<float, true>(head_dim, p, eps, s);
 }
 
 }  // namespace la2

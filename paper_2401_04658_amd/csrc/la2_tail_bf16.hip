@@ -15,13 +15,16 @@ namespace la2 {
 namespace {
 using namespace bf16k;
 
-template <typename E, int D>
+// NORM: the Norm epilogue of eq. (2) (the waves exchange the sums of squares of their 32 features of every row
+// through LDS, one more barrier per block; wave 0 stores r).
+template <typename E, int D, bool NORM = false>
 __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
   constexpr int B = 32;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
   using Loader = TileLoader<D, 3, B, NT>;
   __shared__ __attribute__((aligned(1024))) E sT[3][TILE];   // X, Y, Z
+  float* const sRed = NormExchange<NORM ? B * NT : 0>::get();   // [position][wave]
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w;
@@ -92,6 +95,15 @@ __global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
     }
     // output: lane = position l32, elements 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
     const int pos = blk * B + l32;
+    if constexpr (NORM) {
+      // the next publish comes after the two barriers that end this block: one exchange buffer is enough
+      norm_publish<NT>(acc, sRed, l32, hh, dvt);
+      __syncthreads();
+      const float r = norm_collect<NT>(sRed, l32, 1.f / (float)D, p.eps);
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[v] *= r;
+      if (dvt == 0 && hh == 0 && pos < n) p.rstd[chain * p.rstd_stride + p.t0 + pos] = r;
+    }
     if (pos < n) {
       E* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;
 #pragma unroll
@@ -138,13 +150,19 @@ hipError_t launch_tail_bf16(int dtype, int head_dim, int batch, const RecurParam
   const int64_t chains = (int64_t)batch * p.heads;
   if (chains == 0 || p.t1 <= p.t0) return hipSuccess;
   dim3 g((unsigned)chains);
+#define LA2_LAUNCH_TAIL(E, D)                                                                        \
+  do {                                                                                               \
+    if (p.rstd != nullptr) hipLaunchKernelGGL((tail_bf16_kernel<E, D, true>), g, dim3(2 * D), 0, s, p); \
+    else                   hipLaunchKernelGGL((tail_bf16_kernel<E, D, false>), g, dim3(2 * D), 0, s, p); \
+  } while (0)
   if (dtype == kF16) {
-    if (head_dim == 128) hipLaunchKernelGGL((tail_bf16_kernel<_Float16, 128>), g, dim3(256), 0, s, p);
-    else                 hipLaunchKernelGGL((tail_bf16_kernel<_Float16, 64>), g, dim3(128), 0, s, p);
+    if (head_dim == 128) LA2_LAUNCH_TAIL(_Float16, 128);
+    else                 LA2_LAUNCH_TAIL(_Float16, 64);
   } else {
-    if (head_dim == 128) hipLaunchKernelGGL((tail_bf16_kernel<__bf16, 128>), g, dim3(256), 0, s, p);
-    else                 hipLaunchKernelGGL((tail_bf16_kernel<__bf16, 64>), g, dim3(128), 0, s, p);
+    if (head_dim == 128) LA2_LAUNCH_TAIL(__bf16, 128);
+    else                 LA2_LAUNCH_TAIL(__bf16, 64);
   }
+#undef LA2_LAUNCH_TAIL
   return hipGetLastError();
 }
 

@@ -357,3 +357,40 @@ def test_stream_probe_validation(lib):
     assert sp(n=24) == E_ALIGN and sp(i=P + 8) == E_ALIGN and sp(o=P + 4) == E_ALIGN
     assert sp(i=None) == E_NULL and sp(o=None) == E_NULL
     assert sp(n=0, i=None, o=None) == OK
+
+
+def test_state_norm_entry_points_validate_before_any_launch(lib):
+    vp = ctypes.c_void_p
+    lib.la2_fwd_state_norm.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_float] + [vp] * 4 + [ctypes.c_size_t, vp]
+    lib.la2_fwd_state_norm.restype = ctypes.c_int
+    lib.la2_bwd_state_norm.argtypes = [vp] * 16 + [ctypes.c_size_t, vp]
+    lib.la2_bwd_state_norm.restype = ctypes.c_int
+    d = dense(lib, 2, 2, 100, 128, binding.LA2_BF16)      # ragged: 100 = 3 * 32 + 4
+    ref = ctypes.byref(d)
+    fn = lambda eps=1e-6, q=P, rstd=P, kv0=None, kvn=None, ws=None, wsb=0: \
+        lib.la2_fwd_state_norm(ref, q, P, P, P, kv0, eps, P, rstd, kvn, ws, wsb, None)
+    assert fn(eps=-1.0) == E_VALUE and fn(eps=float("nan")) == E_VALUE
+    assert fn(q=None) == E_NULL and fn(rstd=None) == E_NULL
+    assert fn(rstd=P + 2) == E_ALIGN and fn(kv0=P + 4) == E_ALIGN and fn(kvn=P + 8) == E_ALIGN
+    bn = lambda o=P, rstd=P, d_u=P, dkvn=None, dkv0=None, ws=None, wsb=0: \
+        lib.la2_bwd_state_norm(ref, P, P, P, o, rstd, P, P, None, dkvn, d_u, P, P, P, dkv0, ws, wsb, None)
+    assert bn(o=None) == E_NULL and bn(rstd=None) == E_NULL and bn(d_u=None) == E_NULL
+    assert bn(d_u=P + 4) == E_ALIGN and bn(dkvn=P + 4) == E_ALIGN and bn(dkv0=P + 8) == E_ALIGN
+    # a gradient coming in at a ragged end needs the hand-over state in the workspace: checked before the row pass
+    assert bn(dkvn=P) == E_WS
+    need = lib.la2_workspace_bytes(ref, 3)
+    assert need == 2 * 2 * 128 * 128 * 4
+    # an empty segment: nothing to check but the descriptor
+    e = dense(lib, 2, 2, 0, 128, binding.LA2_BF16)
+    assert lib.la2_fwd_state_norm(ctypes.byref(e), None, None, None, None, None, 1e-6, None, None, None, None, 0, None) == OK
+
+
+def test_decode_step_norm_validation(lib):
+    vp = ctypes.c_void_p
+    lib.la2_decode_step_norm.argtypes = [ctypes.c_int32] * 4 + [vp] * 5 + [ctypes.c_float, vp, vp]
+    lib.la2_decode_step_norm.restype = ctypes.c_int
+    dn = lambda b=1, h=1, d=64, dt=1, q=P, kv=P, eps=1e-6, o=P: lib.la2_decode_step_norm(b, h, d, dt, q, P, P, P, kv, eps, o, None)
+    assert dn(eps=-1.0) == E_VALUE and dn(eps=float("inf")) == E_VALUE
+    assert dn(d=100) == E_SHAPE and dn(b=-1) == E_SHAPE and dn(dt=9) == E_DTYPE
+    assert dn(q=None) == E_NULL and dn(kv=None) == E_NULL and dn(o=P + 8) == E_ALIGN
+    assert dn(b=0, q=None, kv=None, o=None) == OK

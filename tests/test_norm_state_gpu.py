@@ -1,0 +1,130 @@
+"""GPU parity of la2_fwd_state_norm / la2_bwd_state_norm (the normalised operator on a segment with state
+hand-over) against the fp64 oracle: all dtypes and head dimensions, ragged lengths (block kernels + short-run
+kernels), sequence chunks, with and without the final state and its gradient, two segments against the whole."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_04658_amd import binding, workloads
+from parity import assert_close, to64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+EPS = 1e-3
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+    yield
+    binding.la2_set_chunk_tokens(0)
+    binding.la2_set_scan_variant(0)
+
+
+def inputs(b, H, n, d, dtype, seed, lam=None):
+    t = workloads.Workload("norm_state", b, H, n, d, dtype, seed=seed, backward=True).tensors()
+    if lam is not None:
+        t["lam"] = torch.as_tensor(lam, dtype=torch.float32).reshape(-1).expand(H).contiguous()
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed + 1)
+    t["kv_init"] = torch.randn((b, H, d, d), generator=gen, dtype=torch.float32) * 0.3
+    t["d_kv_final"] = torch.randn((b, H, d, d), generator=gen, dtype=torch.float32) * 0.3
+    return t, {k: v.to(DEV) for k, v in t.items()}
+
+
+def check(t, g, dtype, tag, final=True, init=True):
+    kv0 = g["kv_init"] if init else None
+    o, rstd, kvf = binding.la2_fwd_state_norm(g["q"], g["k"], g["v"], g["lam"], EPS, kv_init=kv0, want_final=final)
+    dq, dk, dv, dkv0 = binding.la2_bwd_state_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], kv_init=kv0,
+                                                  d_kv_final=g["d_kv_final"] if final else None)
+    torch.cuda.synchronize()
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    init64 = to64(t["kv_init"]) if init else None
+    ro, rr, rkvf = oracle.fwd_norm_state(q, k, v, lam, EPS, init64)
+    refs = oracle.bwd_norm_state(q, k, v, do, lam, EPS, init64, to64(t["d_kv_final"]) if final else None)
+    assert_close(tag + " o", o, ro, dtype)
+    assert_close(tag + " rstd", rstd, rr, dtype)
+    if final:
+        assert_close(tag + " kv_final", kvf, rkvf, dtype)
+    if q.shape[2] > 1 or init:   # one position from a zero state leaves dq, dk as pure cancellation
+        for name, got, ref in zip(("dq", "dk", "dv", "d_kv_init"), (dq, dk, dv, dkv0), refs):
+            assert_close(tag + " " + name, got, ref, dtype)
+
+
+@pytest.mark.parametrize("final", [True, False])
+@pytest.mark.parametrize("n", [1, 31, 32, 45, 64, 100, 300])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
+@pytest.mark.parametrize("d", [64, 96, 128, 256])
+def test_segment(d, dtype, n, final):
+    if dtype == torch.float32 and d in (96, 256) and n > 100:
+        n = 100    # fp32 at these head dimensions is the token recurrence
+    t, g = inputs(2, 2, n, d, dtype, seed=3000 + d + n, lam=[0.7, 0.98])
+    check(t, g, dtype, "d%d %s n%d final %s" % (d, dtype, n, final), final)
+
+
+@pytest.mark.parametrize("chunk", [64, 192])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 128),
+                                     (torch.float16, 128), (torch.bfloat16, 256), (torch.bfloat16, 96)])
+def test_segment_chunked(dtype, d, chunk):
+    binding.la2_set_chunk_tokens(chunk)
+    t, g = inputs(1, 2, 700, d, dtype, seed=3100 + d + chunk, lam=[0.8, 0.99])
+    check(t, g, dtype, "d%d %s chunk %d" % (d, dtype, chunk))
+    check(t, g, dtype, "d%d %s chunk %d, zero start" % (d, dtype, chunk), init=False)
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_two_segments_against_the_whole_sequence(d):
+    t, g = inputs(1, 2, 150, d, torch.bfloat16, seed=3200 + d, lam=[0.9, 0.97])
+    cut = 77
+    first = [g[x][:, :, :cut].contiguous() for x in ("q", "k", "v")]
+    second = [g[x][:, :, cut:].contiguous() for x in ("q", "k", "v")]
+    o1, r1, s1 = binding.la2_fwd_state_norm(*first, g["lam"], EPS)
+    o2, r2, s2 = binding.la2_fwd_state_norm(*second, g["lam"], EPS, kv_init=s1)
+    ow, rw = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], EPS)
+    torch.cuda.synchronize()
+    q, k, v, lam = (to64(t[x]) for x in ("q", "k", "v", "lam"))
+    ro, rr, rs = oracle.fwd_norm_state(q, k, v, lam, EPS)
+    assert_close("segments o", torch.cat([o1, o2], dim=2), ro, torch.bfloat16)
+    assert_close("segments rstd", torch.cat([r1, r2], dim=2), rr, torch.bfloat16)
+    assert_close("segments state", s2, rs, torch.bfloat16)
+    assert_close("whole o", ow, ro, torch.bfloat16)
+
+
+def test_strided_layout_and_given_buffers():
+    t, g = inputs(2, 3, 90, 128, torch.bfloat16, seed=3300)
+    for name in ("q", "k", "v", "d_o"):
+        g[name] = t[name].permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    check(t, g, torch.bfloat16, "bnhd")
+
+
+def test_empty_sequence_passes_the_state_through():
+    d = 64
+    t, g = inputs(2, 2, 0, d, torch.bfloat16, seed=3400)
+    o, rstd, kvf = binding.la2_fwd_state_norm(g["q"], g["k"], g["v"], g["lam"], EPS, kv_init=g["kv_init"])
+    dq, dk, dv, dkv0 = binding.la2_bwd_state_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"],
+                                                  kv_init=g["kv_init"], d_kv_final=g["d_kv_final"])
+    torch.cuda.synchronize()
+    assert torch.equal(kvf, g["kv_init"]) and torch.equal(dkv0, g["d_kv_final"])
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
+@pytest.mark.parametrize("d", [64, 96, 128, 256])
+def test_normalised_decode_steps_follow_the_segment(d, dtype):
+    """Prefill a segment with la2_fwd_state_norm, then decode token by token with la2_decode_step_norm: the
+    outputs are those of the normalised operator on the whole sequence."""
+    b, H, n, steps = 2, 3, 40, 6
+    t, g = inputs(b, H, n + steps, d, dtype, seed=3500 + d, lam=[0.5, 0.9, 1.0])
+    pre = [g[x][:, :, :n].contiguous() for x in ("q", "k", "v")]
+    o_pre, _, state = binding.la2_fwd_state_norm(*pre, g["lam"], EPS, kv_init=g["kv_init"])
+    outs = [o_pre]
+    for i in range(n, n + steps):
+        outs.append(binding.la2_decode_step_norm(g["q"][:, :, i].contiguous(), g["k"][:, :, i].contiguous(),
+                                                 g["v"][:, :, i].contiguous(), g["lam"], state, EPS)[:, :, None])
+    torch.cuda.synchronize()
+    q, k, v, lam = (to64(t[x]) for x in ("q", "k", "v", "lam"))
+    ro, _, rs = oracle.fwd_norm_state(q, k, v, lam, EPS, to64(t["kv_init"]))
+    assert_close("d%d %s prefill + decode o" % (d, dtype), torch.cat(outs, dim=2), ro, dtype)
+    assert_close("d%d %s prefill + decode state" % (d, dtype), state, rs, dtype)

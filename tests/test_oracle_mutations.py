@@ -134,7 +134,24 @@ def _norm_mutants():
         o, g = np.asarray(o, dtype=np.float64), np.asarray(g, dtype=np.float64)
         return g - o * np.mean(g * o, axis=-1, keepdims=True)
 
-    return [("rstd from the sum of squares", {"fwd_norm": fwd_sum_instead_of_mean}),
+    def state_output_ignores_the_start_state(q, k, v, lam, eps, kv_init=None):
+        u = ref.fwd_recurrent(q, k, v, lam)
+        _, kvn = ref.fwd_recurrent(q, k, v, lam, kv_init=kv_init, return_state=True)
+        r = 1.0 / np.sqrt(np.mean(u * u, axis=-1) + eps)
+        return u * r[..., None], r, kvn
+
+    def state_backward_drops_the_final_state_gradient(q, k, v, d_o, lam, eps, kv_init=None, d_kv_final=None):
+        from oracle import norm as nm
+        o, rstd, _ = nm.fwd_norm_state(q, k, v, lam, eps, kv_init)
+        return ref.bwd_recurrent_state(q, k, v, nm.norm_backward_rows(o, rstd, d_o), lam, kv_init=kv_init)
+
+    def state_backward_without_the_row_pass(q, k, v, d_o, lam, eps, kv_init=None, d_kv_final=None):
+        return ref.bwd_recurrent_state(q, k, v, d_o, lam, kv_init=kv_init, d_kv_final=d_kv_final)
+
+    return [("segment output ignores the start state", {"fwd_norm_state": state_output_ignores_the_start_state}),
+            ("segment backward drops d_kv_final", {"bwd_norm_state": state_backward_drops_the_final_state_gradient}),
+            ("segment backward takes d_o for d_u", {"bwd_norm_state": state_backward_without_the_row_pass}),
+            ("rstd from the sum of squares", {"fwd_norm": fwd_sum_instead_of_mean}),
             ("eps added outside the root", {"fwd_norm": fwd_eps_outside_the_root}),
             ("backward without the projection term", {"norm_backward_rows": rows_without_projection}),
             ("backward projection not averaged", {"norm_backward_rows": rows_projection_not_averaged}),

@@ -485,6 +485,43 @@ def test_norm_gradients_by_finite_differences(eps):
         assert np.allclose(fd, grads[name], rtol=2e-6, atol=2e-8), name
 
 
+def test_norm_with_state_by_finite_differences_and_composition():
+    """The normalised operator on a segment with state hand-over: two segments compose to the whole sequence,
+    and the gradients (also with respect to the start state, also of a loss on the final state) match central
+    finite differences of the forward function."""
+    shape = (1, 2, 7, 3)
+    q, k, v, do = (_rand(shape, s) for s in (196, 197, 198, 199))
+    kv0, dkvn = _rand((1, 2, 3, 3), 200), _rand((1, 2, 3, 3), 201)
+    lam, eps = np.array([0.6, 0.95]), 0.05
+    # composition: [0, 4) then [4, 7) from the first segment's state == the whole sequence, == fwd_norm from zero
+    o, r, kvn = oracle.fwd_norm_state(q, k, v, lam, eps, kv0)
+    o1, r1, s1 = oracle.fwd_norm_state(q[:, :, :4], k[:, :, :4], v[:, :, :4], lam, eps, kv0)
+    o2, r2, s2 = oracle.fwd_norm_state(q[:, :, 4:], k[:, :, 4:], v[:, :, 4:], lam, eps, s1)
+    assert np.allclose(np.concatenate([o1, o2], 2), o, rtol=1e-12, atol=1e-14)
+    assert np.allclose(np.concatenate([r1, r2], 2), r, rtol=1e-12) and np.allclose(s2, kvn, rtol=1e-12, atol=1e-14)
+    oz, rz, _ = oracle.fwd_norm_state(q, k, v, lam, eps, None)
+    of, rf = oracle.fwd_norm(q, k, v, lam, eps)
+    assert np.allclose(oz, of, rtol=1e-12, atol=1e-14) and np.allclose(rz, rf, rtol=1e-12)
+    # gradients
+    grads = dict(zip(("q", "k", "v", "kv0"), oracle.bwd_norm_state(q, k, v, do, lam, eps, kv0, dkvn)))
+
+    def loss(**a):
+        o_, _, kvn_ = oracle.fwd_norm_state(a["q"], a["k"], a["v"], lam, eps, a["kv0"])
+        return float(np.sum(o_ * do) + np.sum(kvn_ * dkvn))
+
+    h = 1e-6
+    base = {"q": q, "k": k, "v": v, "kv0": kv0}
+    for name in base:
+        fd = np.zeros(base[name].shape)
+        for idx in np.ndindex(*base[name].shape):
+            ap, am = dict(base), dict(base)
+            ap[name], am[name] = base[name].copy(), base[name].copy()
+            ap[name][idx] += h
+            am[name][idx] -= h
+            fd[idx] = (loss(**ap) - loss(**am)) / (2 * h)
+        assert np.allclose(fd, grads[name], rtol=2e-6, atol=2e-8), name
+
+
 def test_norm_gradients_are_orthogonal_to_their_inputs_at_eps_zero():
     """At eps = 0 the loss is homogeneous of degree 0 in each of Q, K, V: <dX, X> = 0; with eps > 0 it is not."""
     shape = (2, 2, 40, 5)
