@@ -67,6 +67,12 @@ def test_random_case_head_dim_96_256(i):
     run_case(i, c)
 
 
+@pytest.mark.parametrize("i", range(80))
+def test_random_case_norm_with_state(i):
+    """The normalised operator with state hand-over, all four head dimensions."""
+    run_case(i, draw_case(i, dims=(64, 96, 128, 256), modes=("norm_state", "norm_state_nofinal"), salt=52000))
+
+
 def run_case(i, c):
     dtype, d, b, H, n = c["dtype"], c["d"], c["b"], c["H"], c["n"]
     tag = "case %d %s" % (i, {k: (v if k != "lam" else v.tolist()) for k, v in c.items()})
@@ -119,6 +125,23 @@ def run_case(i, c):
         assert_close(tag + " o", o, ro, dtype)
         assert_close(tag + " state", state, rs, dtype)
         return
+    elif c["mode"] in ("norm_state", "norm_state_nofinal"):
+        final = c["mode"] == "norm_state"
+        eps = 1e-3
+        o, rstd, kvf = binding.la2_fwd_state_norm(g["q"], g["k"], g["v"], g["lam"], eps, kv_init=g["kv_init"],
+                                                  want_final=final)
+        got = binding.la2_bwd_state_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], kv_init=g["kv_init"],
+                                         d_kv_final=g["d_kv_final"] if final else None)
+        torch.cuda.synchronize()
+        init64 = to64(t["kv_init"])
+        ro, rr, rkvf = oracle.fwd_norm_state(q, k, v, lam, eps, init64)
+        refs = oracle.bwd_norm_state(q, k, v, do, lam, eps, init64, to64(t["d_kv_final"]) if final else None)
+        assert_close(tag + " o", o, ro, dtype)
+        assert_close(tag + " rstd", rstd, rr, dtype)
+        if final:
+            assert_close(tag + " kv_final", kvf, rkvf, dtype)
+        for name, x, ref in zip(("dq", "dk", "dv", "d_kv_init"), got, refs):
+            assert_close(tag + " " + name, x, ref, dtype)
     elif c["mode"] == "norm":
         eps = 1e-3
         o, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], eps)
