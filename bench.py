@@ -8,8 +8,9 @@ sequence-length sweep -- (batch, n) = (64,1K), (16,4K), (4,16K), (1,64K), H=16, 
 4 x 65,536 tokens -- on seeded synthetic tensors that are resident in HBM before the timed region.
 Prints ONE JSON line: whole-step tokens/s, the per-point table (tokens/s, TFLOP/s, fraction of the
 bf16 MFMA peak, flatness), the other configurations (400M-like layer, 3B-like layer, decode), the
-roofline of the dominant kernel measured live with events on the launch stream, and the fp64 CPU
-oracle timed on a bounded sample as a baseline.
+roofline of the dominant kernel measured live with events on the launch stream (and beside it a kernel that
+only streams the same bytes in the same read : write mix, la2_stream_probe: the rate the memory system gives
+any kernel with that traffic), and the fp64 CPU oracle timed on a bounded sample as a baseline.
 """
 import argparse
 import json
