@@ -218,6 +218,11 @@ def main():
             "frac_hbm_peak": round(28 * d * th / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
             "fwd_tflops": round(flops_per_token_head(B, d, "fwd") * th / (f_ms * 1e-3) / 1e12, 2),
             "bwd_tflops": round(flops_per_token_head(B, d, "bwd") * th / (b_ms * 1e-3) / 1e12, 2),
+            # device memory beside the 8 tensors of a training step (q, k, v, o, d_o, dq, dk, dv: linear in n):
+            # the library's own workspace (chunk start states; 0 when the chains alone fill the GPU)
+            "tensor_MiB": round(8 * th * d * 2 / 2**20, 1),
+            "workspace_MiB": round(max(binding.la2_workspace_bytes(g["q"], binding.LA2_OP_FWD),
+                                       binding.la2_workspace_bytes(g["q"], binding.LA2_OP_BWD)) / 2**20, 1),
         })
     tps = [p["tokens_per_s"] for p in points]
     flatness = min(tps) / max(tps)
