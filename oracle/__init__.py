@@ -15,5 +15,5 @@ from .ref import (  # noqa: F401
     fwd_rows,
     bwd_rows,
 )
-from .block_form import alg1_forward, alg2_backward  # noqa: F401
+from .block_form import block_forward, block_backward, state_update_residuals  # noqa: F401
 from .norm import fwd_norm, bwd_norm, norm_backward_rows, fwd_norm_state, bwd_norm_state  # noqa: F401

@@ -33,8 +33,12 @@ def build(force=False):
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        # LA2_ORACLE_LIB: a build of la2_oracle.c made elsewhere (the sanitizer test's instrumented one)
+        path = os.environ.get("LA2_ORACLE_LIB")
+        if not path:
+            build()
+            path = _LIB
+        _lib = ctypes.CDLL(path)
         _lib.la2_oracle_num_threads.restype = ctypes.c_int
     return _lib
 

@@ -58,7 +58,7 @@ def test_golden_geometric_series_lambda_half():
         assert np.array_equal(o, vals[:, 1])
     rows = np.arange(n)
     assert np.array_equal(oracle.fwd_rows(one[0, 0], one[0, 0], one[0, 0], 0.5, rows)[:, 0], vals[:, 1])
-    assert np.array_equal(oracle.alg1_forward(one[0, 0], one[0, 0], one[0, 0], 0.5, 4)[:, 0], vals[:, 1])
+    assert np.array_equal(oracle.block_forward(one[0, 0], one[0, 0], one[0, 0], 0.5, 4)[0][:, 0], vals[:, 1])
 
 
 # ---- P2: lambda = 1 is the plain causal (lower-triangular) product / a prefix sum ----------------
@@ -146,32 +146,51 @@ def test_head_and_batch_indexing():
         assert np.allclose(g[2][b, h], A.T @ do[b, h], rtol=1e-12, atol=1e-12)
 
 
-# ---- P4: Algorithms 1 and 2 (block form) equal the definition for every B | n ---------------------------
+# ---- P4: the block decomposition of Algorithms 1 and 2 equals the definition for every B | n --------------
 @pytest.mark.parametrize("B", [1, 2, 4, 8, 16, 32])
 def test_block_form_equals_direct(B):
     n, d, lam = 32, 4, 0.85
     q, k, v, do = (_rand((1, 1, n, d), s) for s in (21, 22, 23, 24))
     o = oracle.fwd_direct(q, k, v, lam)[0, 0]
-    O, states = oracle.alg1_forward(q[0, 0], k[0, 0], v[0, 0], lam, B, return_states=True)
+    O, states = oracle.block_forward(q[0, 0], k[0, 0], v[0, 0], lam, B)
     assert np.allclose(O, o, rtol=1e-12, atol=1e-13)
-    # carried state after block t is sum_{s <= tB} lam^(tB - s) k_s^T v_s (definition of KV_t)
+    # the state at block boundary t is sum_{s <= tB} lam^(tB - s) k_s^T v_s (definition of KV_t), spelled out here
+    # with plain loops
     for t, KV in enumerate(states):
         expect = np.zeros((d, d))
         for s in range(1, t * B + 1):
             expect += lam ** (t * B - s) * np.outer(k[0, 0, s - 1], v[0, 0, s - 1])
         assert np.allclose(KV, expect, rtol=1e-12, atol=1e-13)
     dq, dk, dv = oracle.bwd_direct(q, k, v, do, lam)
-    bq, bk, bv = oracle.alg2_backward(q[0, 0], k[0, 0], v[0, 0], do[0, 0], lam, B)
+    bq, bk, bv, dstates = oracle.block_backward(q[0, 0], k[0, 0], v[0, 0], do[0, 0], lam, B)
     for a, b in ((bq, dq), (bk, dk), (bv, dv)):
         assert np.allclose(a, b[0, 0], rtol=1e-12, atol=1e-13)
+    for t, dKV in enumerate(dstates):
+        expect = np.zeros((d, d))
+        for s in range(t * B + 1, n + 1):
+            expect += lam ** (s - t * B) * np.outer(q[0, 0, s - 1], do[0, 0, s - 1])
+        assert np.allclose(dKV, expect, rtol=1e-12, atol=1e-13)
+    # ... and the states obey the one-step updates the two algorithms carry from block to block
+    rf, rr = oracle.state_update_residuals(q[0, 0], k[0, 0], v[0, 0], do[0, 0], lam, B)
+    assert rf <= 1e-13 and rr <= 1e-13
 
 
 def test_recurrent_final_state_is_block_state():
     n, d, lam = 24, 3, 0.9
     q, k, v = (_rand((1, 1, n, d), s) for s in (25, 26, 27))
     _, kvf = oracle.fwd_recurrent(q, k, v, lam, return_state=True)
-    _, states = oracle.alg1_forward(q[0, 0], k[0, 0], v[0, 0], lam, 8, return_states=True)
+    _, states = oracle.block_forward(q[0, 0], k[0, 0], v[0, 0], lam, 8)
     assert np.allclose(kvf[0, 0], states[-1], rtol=1e-12, atol=1e-13)
+
+
+def test_reverse_state_at_the_first_boundary_is_the_gradient_of_the_start_state():
+    """dKV_0 of the block form is d_kv_init of the segment backward (Sec. 3.2.2's recursion carried one step past
+    the first position)."""
+    n, d, lam = 24, 3, 0.8
+    q, k, v, do = (_rand((1, 1, n, d), s) for s in (35, 36, 37, 38))
+    *_, g0 = oracle.bwd_recurrent_state(q, k, v, do, lam)
+    *_, dstates = oracle.block_backward(q[0, 0], k[0, 0], v[0, 0], do[0, 0], lam, 6)
+    assert np.allclose(g0[0, 0], dstates[0], rtol=1e-12, atol=1e-13)
 
 
 # ---- P5: central finite differences of L = sum(O * dO) -------------------------------------------------
