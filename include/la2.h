@@ -15,7 +15,8 @@
  *
  * Conventions common to every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device.  The caller owns every
- *     buffer, including the workspace; the library allocates nothing and never synchronises.
+ *     buffer, including the workspace; the library allocates nothing and never synchronises.  Its only
+ *     state between calls are the two tuning knobs at the end of this header.
  *     Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
  *   - Descriptors (`la2_desc`) are HOST structs.
  *   - Sequence tensors (q, k, v, o, d_o, dq, dk, dv) share one shape [batch, heads, seqlen, head_dim]
@@ -88,6 +89,15 @@ void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen
  * The value depends on the device's compute-unit count and on la2_set_chunk_tokens().
  */
 size_t la2_workspace_bytes(const la2_desc* desc, int32_t op);
+
+/*
+ * How la2_fwd / la2_bwd cut this problem's sequences into chunks that run in parallel (host query, launches
+ * nothing): *nchunks chunks of *chunk_tokens positions each (the last one may be shorter); 1 chunk = the block
+ * loop of Algorithm 1 / 2 runs over the whole sequence in one workgroup per (batch, head).  The workspace
+ * holds one d x d fp32 start state per (batch, head, chunk) when nchunks > 1.  Depends on the device's
+ * compute-unit count and on la2_set_chunk_tokens(), like la2_workspace_bytes().
+ */
+la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk_tokens);
 
 /*
  * Forward pass, Algorithm 1:  o = LA2(q, k, v; lambda).
@@ -222,20 +232,25 @@ la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, 
                                 float* kv_state, float eps, void* o, void* hip_stream);
 
 /*
- * la2_bwd_state for callers that kept the forward pass's workspace (a training step): fwd_workspace is the
- * workspace buffer that la2_fwd / la2_fwd_state used for the SAME desc, k, v, lambda and kv_init, with
- * its contents untouched since and distinct from `workspace`.  When the sequence is processed in chunks
- * it holds the chunk start states of the (K, V) scan, which are (transposed) those of Algorithm 2's first
- * loop, so the backward pass skips recomputing them (one pass over K and V less).  NULL, or a problem that
- * needs no workspace: exactly la2_bwd_state.  Not to be used with the workspace of a la2_fwd_state call
- * that produced kv_final for a seqlen that is not a multiple of G (see la2_fwd_state; that call plans its
- * chunks for the whole blocks only).  fwd_workspace is 256-byte aligned (LA2_ERR_WORKSPACE otherwise) and only read.
+ * la2_bwd_state for callers that kept the forward pass's workspace (a training step).  When the sequence is
+ * processed in chunks that buffer holds the chunk start states of the (K, V) scan, which are (transposed)
+ * those of Algorithm 2's first loop, so the backward pass skips recomputing them (one pass over K and V less).
+ *   fwd_workspace        in  the workspace buffer that la2_fwd / la2_fwd_state (or their _norm forms) used for
+ *                            the SAME desc, k, v, lambda and kv_init, contents untouched since, distinct from
+ *                            `workspace`; 256-byte aligned (LA2_ERR_WORKSPACE otherwise); only read.  NULL, or a
+ *                            problem that needs no workspace: exactly la2_bwd_state.
+ *   fwd_workspace_bytes      its size; smaller than what that forward call needed: LA2_ERR_WORKSPACE
+ *   fwd_wrote_kv_final       non-zero if that forward call was given a kv_final pointer.  Such a call plans its
+ *                            chunks for the whole blocks of a ragged seqlen only (see la2_fwd_state); if that plan
+ *                            differs from this call's, the saved states are not used and the result is that of
+ *                            la2_bwd_state.
+ * The chunk plan also depends on la2_set_chunk_tokens() and the device: both calls must see the same.
  */
 la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v,
                          const void* d_o, const float* lambda, const float* kv_init,
                          const float* d_kv_final, void* dq, void* dk, void* dv, float* d_kv_init,
-                         const void* fwd_workspace, void* workspace, size_t workspace_bytes,
-                         void* hip_stream);
+                         const void* fwd_workspace, size_t fwd_workspace_bytes, int32_t fwd_wrote_kv_final,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Comparison kernel, not part of the method: the same forward pass evaluated as the masked left product
@@ -246,22 +261,6 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
  */
 la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
                                 const float* lambda, void* o, void* hip_stream);
-
-/*
- * Measurement helper, not part of the method: one launch of a kernel that only streams.  It reads `reads`
- * (0..4) consecutive streams of bytes_per_stream bytes from `in` and writes `writes` (0..2) consecutive streams
- * of the same size to `out` (values are arbitrary), 16 bytes per lane, non-temporal loads, stores with the
- * non-temporal policy if nt_stores != 0.  The benchmark times it beside the scan kernels on the same bytes and
- * read : write mix (Algorithm 1 reads three tensors and writes one; Algorithm 2's second loop reads four and
- * writes two) as the rate the memory system gives a kernel without arithmetic.
- *   in    device, reads * bytes_per_stream bytes (may be NULL if reads == 0), 16-byte aligned
- *   out   device, writes * bytes_per_stream bytes; at least 16 bytes when writes == 0 (never written then);
- *         16-byte aligned
- * LA2_ERR_SHAPE for stream counts out of range or both zero, LA2_ERR_STRIDE_ALIGN for a size or pointer that is
- * not a multiple of 16 bytes.
- */
-la2_status la2_stream_probe(int32_t reads, int32_t writes, int32_t nt_stores, const void* in, void* out,
-                            size_t bytes_per_stream, void* hip_stream);
 
 /*
  * ntokens consecutive decode steps in one launch (recursive form of Sec. 3.2.1): for t = 0 .. ntokens-1
@@ -291,8 +290,9 @@ int32_t la2_block_size(const la2_desc* desc);
 
 /*
  * Tuning / test knob: tokens per sequence chunk (rounded up to a multiple of the block size).
- * 0 restores the automatic choice.  Process-global, not thread-safe; changes the value returned
- * by la2_workspace_bytes().  Results do not depend on it beyond rounding.
+ * 0 restores the automatic choice.  Process-global (an atomic that every call reads once: setting it while
+ * another thread is inside a call gives that call either value); changes the value returned by
+ * la2_workspace_bytes().  Results do not depend on it beyond rounding.
  */
 void la2_set_chunk_tokens(int32_t tokens);
 
@@ -303,8 +303,8 @@ void la2_set_chunk_tokens(int32_t tokens);
  *   1  the full-block kernel (blocks of 64 positions, one workgroup per compute unit)
  *   2  the half-block kernel
  * Other values are taken as 0.  Both kernels implement Algorithm 1's block recurrence (the block
- * size is the algorithm's free parameter B); results differ by rounding only.  Process-global, not
- * thread-safe.  Ignored for fp32 and for head_dim 64.
+ * size is the algorithm's free parameter B); results differ by rounding only.  Process-global, as
+ * la2_set_chunk_tokens.  Ignored for fp32 and for head_dim 64.
  */
 void la2_set_scan_variant(int32_t variant);
 

@@ -51,6 +51,8 @@ def load():
     lib.la2_desc_dense.restype = None
     lib.la2_workspace_bytes.argtypes = [dp, i32]
     lib.la2_workspace_bytes.restype = sz
+    lib.la2_chunk_plan.argtypes = [dp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.la2_chunk_plan.restype = ctypes.c_int
     lib.la2_block_size.argtypes = [dp]
     lib.la2_block_size.restype = i32
     lib.la2_set_chunk_tokens.argtypes = [i32]
@@ -63,8 +65,6 @@ def load():
     lib.la2_bwd_state_norm.restype = ctypes.c_int
     lib.la2_decode_step_norm.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.la2_decode_step_norm.restype = ctypes.c_int
-    lib.la2_stream_probe.argtypes = [i32, i32, i32, vp, vp, sz, vp]
-    lib.la2_stream_probe.restype = ctypes.c_int
     lib.la2_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_fwd.restype = ctypes.c_int
     lib.la2_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -73,7 +73,7 @@ def load():
     lib.la2_fwd_state.restype = ctypes.c_int
     lib.la2_bwd_state.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_state.restype = ctypes.c_int
-    lib.la2_bwd_saved.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd_saved.argtypes = [dp] + [vp] * 12 + [sz, i32, vp, sz, vp]
     lib.la2_bwd_saved.restype = ctypes.c_int
     lib.la2_fwd_norm.argtypes = [dp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.la2_fwd_norm.restype = ctypes.c_int
@@ -133,6 +133,14 @@ def _stream(t):
 def la2_workspace_bytes(t, op=LA2_OP_FWD):
     desc = make_desc(t)
     return int(load().la2_workspace_bytes(ctypes.byref(desc), op))
+
+
+def la2_chunk_plan(t):
+    """(nchunks, chunk_tokens) of the sequence chunks la2_fwd / la2_bwd run in parallel for this tensor."""
+    desc = make_desc(t)
+    n, c = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().la2_chunk_plan(ctypes.byref(desc), ctypes.byref(n), ctypes.byref(c)))
+    return int(n.value), int(c.value)
 
 
 def la2_block_size(t):
@@ -330,9 +338,10 @@ def la2_fwd_state(q, k, v, lam, kv_init=None, want_final=True, out=None, kv_fina
 
 
 def la2_bwd_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_init=True, out=None,
-                  d_kv_init=None, workspace=None, fwd_workspace=None):
+                  d_kv_init=None, workspace=None, fwd_workspace=None, fwd_wrote_kv_final=False):
     """Backward of one segment.  Returns (dq, dk, dv, d_kv_init or None).  fwd_workspace: the workspace
-    tensor the forward call used (contents untouched since), to reuse its chunk states."""
+    tensor the forward call used (contents untouched since), to reuse its chunk states; fwd_wrote_kv_final:
+    whether that call handed out kv_final."""
     lib = load()
     if not q.is_cuda:
         raise ValueError("la2_bwd_state: tensors must live on the GPU")
@@ -352,7 +361,8 @@ def la2_bwd_state(q, k, v, d_o, lam, kv_init=None, d_kv_final=None, want_d_kv_in
                                  lam.data_ptr(), _state(kv_init, q, "kv_init"),
                                  _state(d_kv_final, q, "d_kv_final"), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                  _state(d_kv_init, q, "d_kv_init") if want_d_kv_init else None,
-                                 fwd_ws, ws_ptr, ws_bytes, _stream(q)))
+                                 fwd_ws, fwd_workspace.numel() * fwd_workspace.element_size() if fwd_workspace is not None else 0,
+                                 1 if fwd_wrote_kv_final else 0, ws_ptr, ws_bytes, _stream(q)))
     return dq, dk, dv, (d_kv_init if want_d_kv_init else None)
 
 
@@ -409,20 +419,6 @@ def la2_left_product_fwd(q, k, v, lam, out=None):
         _check(lib.la2_left_product_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
                                         out.data_ptr(), _stream(q)))
     return out
-
-
-def la2_stream_probe(reads, writes, src, dst, bytes_per_stream, nt_stores=False):
-    """Measurement helper: one launch of a kernel that only streams `reads` streams out of src and `writes`
-    streams into dst (uint8 tensors on the GPU, large enough for that many streams of bytes_per_stream)."""
-    lib = load()
-    if not (src.is_cuda and dst.is_cuda):
-        raise ValueError("la2_stream_probe: buffers must live on the GPU")
-    if src.numel() * src.element_size() < reads * bytes_per_stream or \
-            dst.numel() * dst.element_size() < max(writes * bytes_per_stream, 16):
-        raise ValueError("la2_stream_probe: buffer smaller than the streams asked for")
-    with torch.cuda.device(src.device):
-        _check(lib.la2_stream_probe(reads, writes, 1 if nt_stores else 0, src.data_ptr(), dst.data_ptr(),
-                                    bytes_per_stream, _stream(src)))
 
 
 def la2_fwd_state_norm(q, k, v, lam, eps=1e-6, kv_init=None, want_final=True, out=None, rstd=None, kv_final=None,

@@ -2,13 +2,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/la2.h"
 #include "la2_internal.h"
 
 namespace {
 
-int g_chunk_tokens_override = 0;  // la2_set_chunk_tokens()
-int g_scan_variant = 0;           // la2_set_scan_variant()
+// The two test / tuning knobs are the library's only mutable state: plain atomics, read once per call.
+std::atomic<int> g_chunk_tokens_override{0};  // la2_set_chunk_tokens()
+std::atomic<int> g_scan_variant{0};           // la2_set_scan_variant()
 // The block kernels form states after whole blocks only: 32 positions for the kernels that take states
 // (half-block 16-bit kernel for head_dim 128, fp32 kernels), 64 for the full-block 16-bit kernel of head_dim 64.
 bool is16(int dtype) { return dtype == LA2_BF16 || dtype == LA2_F16; }
@@ -36,12 +39,15 @@ int device_cu_count() {
 
 int elem_size(int dtype) { return dtype == LA2_F32 ? 4 : 2; }
 
-la2_status check_desc(const la2_desc* d) {
+la2_status check_desc_fields(const la2_desc* d) {
   if (d == nullptr) return LA2_ERR_NULL;
   if (d->dtype != LA2_F32 && !is16(d->dtype)) return LA2_ERR_DTYPE;
   if (d->batch < 0 || d->heads < 0 || d->seqlen < 0 || d->reserved != 0) return LA2_ERR_SHAPE;
   if (!supported_head_dim(d->head_dim)) return LA2_ERR_SHAPE;
   if ((int64_t)d->batch * d->heads > (int64_t)1 << 24) return LA2_ERR_SHAPE;
+  // rows of one tensor: keeps the grids of the row passes (4 rows per workgroup at least) and of the left-product
+  // comparison (128 rows per workgroup) below 2^31; more rows than this fit no device's memory anyway
+  if ((int64_t)d->batch * d->heads * d->seqlen > (int64_t)1 << 32) return LA2_ERR_SHAPE;
   const int64_t per16 = 16 / elem_size(d->dtype);
   if (d->stride_b < 0 || d->stride_h < 0 || d->stride_n < d->head_dim) return LA2_ERR_STRIDE_ALIGN;
   if (d->stride_b % per16 || d->stride_h % per16 || d->stride_n % per16) return LA2_ERR_STRIDE_ALIGN;
@@ -76,8 +82,9 @@ Plan make_plan(const la2_desc* d) {
   if (chains == 0 || nblocks <= 1) return pl;
   if (wide(d->head_dim) && !is16(d->dtype)) return pl;   // token recurrence: one workgroup walks the chain
   int cb;  // blocks per chunk
-  if (g_chunk_tokens_override > 0) {
-    cb = (g_chunk_tokens_override + B - 1) / B;
+  const int chunk_override = g_chunk_tokens_override.load(std::memory_order_relaxed);
+  if (chunk_override > 0) {
+    cb = (chunk_override + B - 1) / B;
   } else {
     const int cus = device_cu_count();
     if (chains >= cus) return pl;
@@ -97,6 +104,27 @@ Plan make_plan(const la2_desc* d) {
   pl.chunk_tokens = cb * B;
   pl.workspace = (size_t)chains * pl.nchunks * d->head_dim * d->head_dim * sizeof(float);
   return pl;
+}
+
+// Grid sizes of every launch a plan leads to, checked on the host before the first one: the scan kernels take
+// chains * nchunks workgroups per scan (two scans in a dual launch), the state scan chains * d * d / 256.
+bool plan_fits_a_grid(const la2_desc* d, const Plan& pl) {
+  const int64_t chains = (int64_t)d->batch * d->heads;
+  const int64_t limit = ((int64_t)1 << 31) - 1;
+  if (chains * pl.nchunks * 2 > limit) return false;
+  if (pl.nchunks > 1 && chains * ((d->head_dim * d->head_dim + 255) / 256) > limit) return false;
+  return true;
+}
+
+la2_desc whole_blocks(const la2_desc* d);
+
+// Everything that can be rejected from the descriptor alone, the launch grids included.
+la2_status check_desc(const la2_desc* d) {
+  const la2_status st = check_desc_fields(d);
+  if (st != LA2_OK) return st;
+  const la2_desc wb = whole_blocks(d);   // the state entry points may run the block kernels on the whole blocks only
+  if (!plan_fits_a_grid(d, make_plan(d)) || !plan_fits_a_grid(&wb, make_plan(&wb))) return LA2_ERR_SHAPE;
+  return LA2_OK;
 }
 
 struct ScanArgs {
@@ -131,7 +159,7 @@ la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lamb
   p.batch = d->batch; p.heads = d->heads; p.n = d->seqlen;
   p.nchunks = pl.nchunks;
   p.chunk_tokens = pl.chunk_tokens;
-  p.variant = g_scan_variant;
+  p.variant = g_scan_variant.load(std::memory_order_relaxed);
   return p;
 }
 
@@ -266,17 +294,27 @@ size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
   return 0;
 }
 
+la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk_tokens) {
+  const la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (nchunks == nullptr || chunk_tokens == nullptr) return LA2_ERR_NULL;
+  const Plan pl = make_plan(desc);
+  *nchunks = pl.nchunks;
+  *chunk_tokens = pl.chunk_tokens;
+  return LA2_OK;
+}
+
 int32_t la2_block_size(const la2_desc* desc) {
   if (check_desc(desc) != LA2_OK) return 0;
   // 16-bit, head_dim 128: the half-block scan kernel unless the full-block one is forced
-  if (is16(desc->dtype) && desc->head_dim == 128 && g_scan_variant != 1) return 32;
+  if (is16(desc->dtype) && desc->head_dim == 128 && g_scan_variant.load(std::memory_order_relaxed) != 1) return 32;
   if (wide(desc->head_dim)) return is16(desc->dtype) ? 32 : 1;
   return block_size(desc);
 }
 
-void la2_set_chunk_tokens(int32_t tokens) { g_chunk_tokens_override = tokens > 0 ? tokens : 0; }
+void la2_set_chunk_tokens(int32_t tokens) { g_chunk_tokens_override.store(tokens > 0 ? tokens : 0); }
 
-void la2_set_scan_variant(int32_t variant) { g_scan_variant = (variant == 1 || variant == 2) ? variant : 0; }
+void la2_set_scan_variant(int32_t variant) { g_scan_variant.store((variant == 1 || variant == 2) ? variant : 0); }
 
 }  // extern "C"
 
@@ -364,8 +402,8 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
 
 la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                          const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
-                         void* dv, float* d_kv_init, const void* fwd_workspace, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+                         void* dv, float* d_kv_init, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                         int32_t fwd_wrote_kv_final, void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st == LA2_OK && !aligned(fwd_workspace, 256)) return LA2_ERR_WORKSPACE;
   if (st != LA2_OK) return st;
@@ -412,9 +450,19 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   ScanArgs for_dq{d_o, v, k, dq};
   for_dq.init = kv_init;
   for_dq.init_tr = true;
-  // the forward pass's chunk start states are those of the (K, V) scan: this scan's, transposed
-  for_dq.saved_states = reinterpret_cast<const float*>(fwd_workspace);
-  for_dq.saved_tr = true;
+  // The forward pass's chunk start states are those of the (K, V) scan: this scan's, transposed.  Only when
+  // that call cut the sequence into the same chunks as this one does (a forward call that handed out kv_final
+  // for a ragged length planned its chunks for the whole blocks only); otherwise they are recomputed.
+  if (fwd_workspace != nullptr && pl.nchunks > 1) {
+    const bool fwd_split = fwd_wrote_kv_final != 0 && desc->seqlen % state_granule(desc) != 0;
+    const la2_desc fwd_blocks = fwd_split ? whole_blocks(desc) : *desc;
+    const Plan pl_fwd = make_plan(&fwd_blocks);
+    if (pl_fwd.nchunks == pl.nchunks && pl_fwd.chunk_tokens == pl.chunk_tokens) {
+      if (fwd_workspace_bytes < pl_fwd.workspace) return LA2_ERR_WORKSPACE;   // not the buffer of that call
+      for_dq.saved_states = reinterpret_cast<const float*>(fwd_workspace);
+      for_dq.saved_tr = true;
+    }
+  }
   st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
   if (st != LA2_OK) return st;
   // Algorithm 2, second loop (descending, running dKV):
@@ -448,14 +496,14 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
 la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                          const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
                          void* dv, float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return la2_bwd_saved(desc, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, nullptr, workspace,
-                       workspace_bytes, hip_stream);
+  return la2_bwd_saved(desc, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, nullptr, 0, 0,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                    const float* lambda, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
-  return la2_bwd_saved(desc, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, nullptr, workspace,
+  return la2_bwd_saved(desc, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, nullptr, 0, 0, workspace,
                        workspace_bytes, hip_stream);
 }
 

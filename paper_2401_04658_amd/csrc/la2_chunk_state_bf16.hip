@@ -125,8 +125,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
 __global__ void state_scan_kernel(float* states, const float* lambda, int heads, int nchunks, int chunk_tokens,
                                   int dd, int reverse, const float* init, int init_tr, int d, int n,
                                   const int32_t* cu_seqlens) {
-  const int chain = blockIdx.y;
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_chain = (dd + (int)blockDim.x - 1) / (int)blockDim.x;   // workgroups per chain
+  const int chain = (int)(blockIdx.x / per_chain);
+  const int e = (int)(blockIdx.x % per_chain) * (int)blockDim.x + (int)threadIdx.x;
   if (e >= dd) return;
   if (cu_seqlens != nullptr) n = cu_seqlens[chain / heads + 1] - cu_seqlens[chain / heads];   // this sequence's length
   const int nch = (n + chunk_tokens - 1) / chunk_tokens;   // chunks this chain really has (<= nchunks)
@@ -174,7 +175,7 @@ hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hi
   const int chains = p.batch * p.heads;
   if (chains == 0 || p.n == 0) return hipSuccess;
   const int dd = head_dim * head_dim;
-  dim3 g((dd + 255) / 256, chains), b(256);
+  dim3 g((unsigned)((int64_t)chains * ((dd + 255) / 256))), b(256);   // the host checked that this fits a grid
   hipLaunchKernelGGL(state_scan_kernel, g, b, 0, s, p.states, p.lambda, p.heads, p.nchunks, p.chunk_tokens, dd,
                      reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n, p.cu_seqlens);
   return hipGetLastError();

@@ -349,14 +349,52 @@ def test_head_dim_96_and_256_are_accepted_where_they_have_kernels(lib):
             lib.la2_set_chunk_tokens(0)
 
 
-def test_stream_probe_validation(lib):
-    lib.la2_stream_probe.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [ctypes.c_size_t, ctypes.c_void_p]
-    lib.la2_stream_probe.restype = ctypes.c_int
-    sp = lambda r=3, w=1, i=P, o=P, n=1024: lib.la2_stream_probe(r, w, 0, i, o, n, None)
+def test_bench_helpers_are_a_library_of_their_own(lib):
+    """The measurement kernels live in libla2_bench.so; the C-ABI library does not export them."""
+    from paper_2401_04658_amd import bench_probe
+    assert not hasattr(lib, "la2_stream_probe") and not hasattr(lib, "la2_bench_stream_probe")
+    bl = bench_probe.load()
+    sp = lambda r=3, w=1, i=P, o=P, n=1024: bl.la2_bench_stream_probe(r, w, 0, i, o, n, None)
     assert sp(r=5) == E_SHAPE and sp(w=3) == E_SHAPE and sp(r=-1) == E_SHAPE and sp(r=0, w=0) == E_SHAPE
     assert sp(n=24) == E_ALIGN and sp(i=P + 8) == E_ALIGN and sp(o=P + 4) == E_ALIGN
     assert sp(i=None) == E_NULL and sp(o=None) == E_NULL
     assert sp(n=0, i=None, o=None) == OK
+    assert bl.la2_bench_mfma_peak(0, 10, P, None) == E_SHAPE and bl.la2_bench_mfma_peak(4, 10, None, None) == E_NULL
+
+
+def test_bwd_saved_checks_the_forward_workspace(lib):
+    vp = ctypes.c_void_p
+    lib.la2_bwd_saved.argtypes = [vp] * 13 + [ctypes.c_size_t, ctypes.c_int32, vp, ctypes.c_size_t, vp]
+    lib.la2_bwd_saved.restype = ctypes.c_int
+    try:
+        lib.la2_set_chunk_tokens(256)
+        d = dense(lib, 1, 2, 1024, 128, binding.LA2_BF16)
+        need = lib.la2_workspace_bytes(ctypes.byref(d), 3)
+        assert need > 0
+        call = lambda fws, fbytes, ws=P * 16, wsb=need: lib.la2_bwd_saved(
+            ctypes.byref(d), P, P, P, P, P, None, None, P, P, P, None, fws, fbytes, 0, ws, wsb, None)
+        assert call(P * 16 + 8, need) == E_WS        # misaligned
+        assert call(P * 16, need - 1) == E_WS        # smaller than what the forward call needed
+        assert call(P * 16, need, wsb=need - 1) == E_WS
+    finally:
+        lib.la2_set_chunk_tokens(0)
+
+
+def test_launch_grids_are_checked_before_any_launch(lib):
+    """Chains x chunks beyond what a grid can index is a shape error of the descriptor, whatever the entry point."""
+    try:
+        lib.la2_set_chunk_tokens(64)
+        d = dense(lib, 1 << 12, 1 << 12, 8192, 64, binding.LA2_BF16)    # 2^24 chains x 128 chunks x 2 scans = 2^32
+        d.stride_b = d.stride_h = 0                                      # (overlapping chains: never launched)
+        assert fwd(lib, d) == E_SHAPE and bwd(lib, d) == E_SHAPE
+        assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 0
+        d = dense(lib, 1 << 8, 1 << 8, 8192, 64, binding.LA2_BF16)      # 2^16 chains x 128 chunks: fine for a grid
+        assert fwd(lib, d, ws=None, ws_bytes=0) == E_WS                 # (and then the workspace is asked for)
+    finally:
+        lib.la2_set_chunk_tokens(0)
+    d = dense(lib, 1 << 12, 1 << 12, 512, 64, binding.LA2_BF16)         # 2^33 rows
+    d.stride_b = d.stride_h = 0
+    assert fwd(lib, d) == E_SHAPE
 
 
 def test_state_norm_entry_points_validate_before_any_launch(lib):

@@ -234,3 +234,32 @@ def test_backward_reuses_the_forward_chunk_states(dtype, d, n, chunk):
         assert_close(tag + " dk", dk, rdk, dtype)
         assert_close(tag + " dv", dv, rdv, dtype)
         assert_close(tag + " d_kv_init", g0, rg0, dtype)
+
+
+@pytest.mark.parametrize("d,n,chunk", [(64, 1000, 128), (128, 1025, 256), (128, 1000, 256)])
+def test_backward_after_a_forward_that_wrote_kv_final_at_a_ragged_length(d, n, chunk):
+    """The forward call that hands out kv_final for a ragged length plans its chunks for the whole blocks only.
+    Told so, the backward call uses the saved chunk states when the two plans agree ((64, 1000, 128) and
+    (128, 1000, 256)) and recomputes them when they do not ((128, 1025, 256): 5 chunks against 4)."""
+    dtype = torch.bfloat16
+    binding.la2_set_chunk_tokens(chunk)
+    try:
+        t = inputs(1, 4, n, d, dtype, seed=1400 + n + d)
+        g = {k: v.to(DEV) for k, v in t.items()}
+        need_f = binding.la2_workspace_bytes(g["q"], binding.LA2_OP_FWD_STATE)
+        need_b = binding.la2_workspace_bytes(g["q"], binding.LA2_OP_BWD_STATE)
+        ws_f = torch.full((need_f,), 0xFF, dtype=torch.uint8, device=DEV)      # NaN patterns where nothing is written
+        ws_b = torch.empty(need_b, dtype=torch.uint8, device=DEV)
+        o, kvn = binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=g["kv_init"], workspace=ws_f)
+        dq, dk, dv, g0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=g["kv_init"],
+                                               workspace=ws_b, fwd_workspace=ws_f, fwd_wrote_kv_final=True)
+        torch.cuda.synchronize()
+    finally:
+        binding.la2_set_chunk_tokens(0)
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    rdq, rdk, rdv, rg0 = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=to64(t["kv_init"]))
+    tag = "saved after kv_final d%d n%d" % (d, n)
+    assert_close(tag + " dq", dq, rdq, dtype)
+    assert_close(tag + " dk", dk, rdk, dtype)
+    assert_close(tag + " dv", dv, rdv, dtype)
+    assert_close(tag + " d_kv_init", g0, rg0, dtype)
