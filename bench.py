@@ -9,7 +9,7 @@ sequence-length sweep -- (batch, n) = (64,1K), (16,4K), (4,16K), (1,64K), H=16, 
 Prints ONE JSON line: whole-step tokens/s, the per-point table (tokens/s, TFLOP/s, fraction of the
 bf16 MFMA peak, flatness), the other configurations (400M-like layer, 3B-like layer, decode), the
 roofline of the dominant kernel measured live with events on the launch stream (and beside it a kernel that
-only streams the same bytes in the same read : write mix, la2_stream_probe: the rate the memory system gives
+only streams the same bytes in the same read : write mix, bench_probe.stream_probe: the rate the memory system gives
 any kernel with that traffic), and the fp64 CPU oracle timed on a bounded sample as a baseline.
 """
 import argparse
@@ -23,12 +23,34 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
-# what a register-only loop of v_mfma_f32_32x32x16_bf16 reaches on this machine (1024 workgroups x 4 waves,
-# measured once with a microbenchmark; the clock under load is below the 2.4 GHz of the spec figure)
-MEASURED_MFMA_BF16_TFLOPS = 2267.0
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch (bytes), by workload
-MEASURED_TRAFFIC_BYTES = {"config3_sweep_b16_n4096_h16_d128": int((786790 + 262148) * 1024)}
+# rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch: the committed summary carries a
+# line "traffic_bytes_per_launch: N" (FETCH_SIZE and WRITE_SIZE, each scaled by the plain-copy reference)
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "scan_bf16_half_fwd_b16_n4096_h16_d128_counters.txt")
+
+
+def measured_traffic_bytes():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def mfma_peak_tflops(time_ms, bench_probe, dev):
+    """What a register-only loop of v_mfma_f32_32x32x16_bf16 reaches on this machine right now (1024 workgroups
+    x 4 waves; the clock under load is below the 2.4 GHz behind the data sheet's 2.5 PFLOP/s)."""
+    import torch
+    sink = torch.zeros(16, dtype=torch.float32, device=dev)
+    flops = [0]
+
+    def run():
+        flops[0] = bench_probe.mfma_peak(1024, 2000, sink)
+    ms = time_ms(run, 20, warm=5)
+    return flops[0] / (ms * 1e-3) / 1e12
 
 
 def flops_per_token_head(B, d, what):
@@ -38,7 +60,7 @@ def flops_per_token_head(B, d, what):
     return {"fwd": fwd, "bwd": bwd, "fwd+bwd": fwd + bwd}[what]
 
 
-def stream_reference(g, time_ms, binding, iters):
+def stream_reference(g, time_ms, bench_probe, iters):
     """A kernel that only streams (no arithmetic, no LDS, no dependences), timed on the buffers and byte counts
     of the scan launches: 3 tensors in, 1 out (forward scan, dQ scan) and 4 in, 2 out (the twin dK / dV scan);
     the better of the two store policies each.  What the memory system gives such a kernel is the bound the scan
@@ -49,7 +71,7 @@ def stream_reference(g, time_ms, binding, iters):
     dst = torch.empty(2 * unit, dtype=torch.uint8, device=g["q"].device)
     out = {}
     for name, r, w in (("reads3_writes1", 3, 1), ("reads4_writes2", 4, 2), ("reads3", 3, 0)):
-        best = min(time_ms(lambda: binding.la2_stream_probe(r, w, src, dst, unit, nt_stores=nts), iters, warm=20)
+        best = min(time_ms(lambda: bench_probe.stream_probe(r, w, src, dst, unit, nt_stores=nts), iters, warm=20)
                    for nts in ((False, True) if w else (False,)))
         out[name] = {"launch_ms": round(best, 4), "GBs": round((r + w) * unit / (best * 1e-3) / 1e9, 1)}
     return out
@@ -70,9 +92,9 @@ def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
         "unit": "GB/s",
         "frac": round(bytes_alg / (k_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         # HBM bytes per launch measured with rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the factor the
-        # same counter shows for a plain copy of known size (2.00 and 1.00): see
+        # same counter shows for a plain copy of known size (2.00 and 1.00): read from
         # profiles/scan_bf16_half_fwd_b16_n4096_h16_d128_counters.txt
-        "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+        "traffic": measured_traffic_bytes(),
         "algorithmic_bytes": bytes_alg,
         "launch_ms": round(k_ms, 4),
         "mfma_tflops": round(flops_alg / (k_ms * 1e-3) / 1e12, 2),
@@ -92,6 +114,12 @@ def main():
     ap.add_argument("--roofline-op", choices=("fwd", "bwd"), default="fwd",
                     help="with --roofline-only: loop la2_fwd (one launch of the forward scan kernel) or la2_bwd "
                          "(the dQ forward scan and the twin dK/dV reverse scan) at (batch 16, n 4096)")
+    ap.add_argument("--profile", metavar="OP:WORKLOAD",
+                    help="for rocprofv3 passes: after the plain-copy reference and a warm-up, loop one operation on one "
+                         "workload and print its time.  OP: fwd, bwd, bwd_saved (backward from the forward's chunk "
+                         "states), fwd_norm, bwd_norm, decode, decode8 (8 tokens per launch).  WORKLOAD: c3_0 .. c3_3 "
+                         "(the sweep points), c2, c4 (decode ops take c5)")
+    ap.add_argument("--profile-iters", type=int, default=100)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus %d is not supported. "
@@ -100,7 +128,7 @@ def main():
 
     import torch
     import paper_2401_04658_amd as la2
-    from paper_2401_04658_amd import binding, workloads
+    from paper_2401_04658_amd import bench_probe, binding, workloads
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -139,14 +167,66 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
-    if args.roofline_only:
+    def copy_reference():
         # a plain copy of known size first: the reference that scales the FETCH_SIZE / WRITE_SIZE counters
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-        del src, dst
+
+    if args.profile:
+        op, _, wname = args.profile.partition(":")
+        copy_reference()
+        iters = args.profile_iters
+        if op in ("decode", "decode8"):
+            dw = workloads.CONFIG5
+            gen = dw.generator()
+            kv = dw.initial_state(gen).to(dev)
+            lam5 = dw.decay().to(dev)
+            toks = [tuple(x.to(dev) for x in dw.token(gen)) for _ in range(8)]
+            if op == "decode":
+                o5 = torch.empty_like(toks[0][0])
+                ms = time_ms(lambda: binding.la2_decode_step(*toks[0], lam5, kv, out=o5), iters, warm=20)
+            else:
+                qm, km, vm = (torch.stack([toks[i][j] for i in range(8)], 2).contiguous() for j in range(3))
+                om = torch.empty_like(qm)
+                ms = time_ms(lambda: binding.la2_decode_multi(qm, km, vm, lam5, kv, out=om), iters, warm=20)
+            print(json.dumps({"op": op, "workload": dw.name, "ms": round(ms, 5)}))
+            return
+        table = {"c3_%d" % i: w_ for i, w_ in enumerate(workloads.CONFIG3)}
+        table.update({"c2": workloads.CONFIG2, "c4": workloads.CONFIG4})
+        wl_p = table[wname]
+        g_p = stage(wl_p)
+        time_ms(lambda: fwd(g_p), 100)      # warm-up: lets the clocks settle
+        if op == "fwd":
+            ms = time_ms(lambda: fwd(g_p), iters)
+        elif op == "bwd":
+            ms = time_ms(lambda: bwd(g_p), iters)
+        elif op == "bwd_saved":
+            ws_b = torch.empty_like(g_p["ws"])
+            fwd(g_p)
+            ms = time_ms(lambda: binding.la2_bwd_state(g_p["q"], g_p["k"], g_p["v"], g_p["d_o"], g_p["lam"],
+                                                       want_d_kv_init=False, out=g_p["grads"], workspace=ws_b,
+                                                       fwd_workspace=g_p["ws"]), iters)
+        elif op in ("fwd_norm", "bwd_norm"):
+            rstd = torch.empty(g_p["q"].shape[:3], dtype=torch.float32, device=dev)
+            d_u = torch.empty_like(g_p["q"])
+            f_n = lambda: binding.la2_fwd_norm(g_p["q"], g_p["k"], g_p["v"], g_p["lam"], 1e-6, out=g_p["o"], rstd=rstd,
+                                               workspace=g_p["ws"])
+            f_n()
+            ms = time_ms(f_n if op == "fwd_norm" else
+                         (lambda: binding.la2_bwd_norm(g_p["q"], g_p["k"], g_p["v"], g_p["o"], rstd, g_p["d_o"],
+                                                       g_p["lam"], out=g_p["grads"], d_u=d_u, workspace=g_p["ws"])), iters)
+        else:
+            raise SystemExit("bench.py: unknown --profile operation %r" % op)
+        print(json.dumps({"op": op, "workload": wl_p.name, "ms": round(ms, 5),
+                          "chunk_plan": binding.la2_chunk_plan(g_p["q"]),
+                          "token_heads": wl_p.token_heads, "head_dim": wl_p.head_dim}))
+        return
+
+    if args.roofline_only:
+        copy_reference()
         wl_r = workloads.CONFIG3[1]
         g_r = stage(wl_r)
         time_ms(lambda: fwd(g_r), 300)      # long warm-up: lets the clocks settle as in the full benchmark
@@ -171,9 +251,11 @@ def main():
     # steady state whatever --warmup says.
     wl_r, g_r = sweep[1]
     time_ms(lambda: fwd(g_r), 300)
+    mfma_measured = mfma_peak_tflops(time_ms, bench_probe, dev)
     roofline = dominant_kernel_roofline(wl_r, g_r, fwd, time_ms, binding, max(100, args.steps))
+    roofline["mfma_loop_tflops_measured_in_this_run"] = round(mfma_measured, 1)
     # ... and beside it a kernel that only streams the same bytes in the same read : write mix
-    roofline["stream_reference"] = stream_reference(g_r, time_ms, binding, max(100, args.steps))
+    roofline["stream_reference"] = stream_reference(g_r, time_ms, bench_probe, max(100, args.steps))
     roofline["frac_of_stream_reference"] = round(
         roofline["stream_reference"]["reads3_writes1"]["launch_ms"] / roofline["launch_ms"], 4)
     bwd_r_ms = time_ms(lambda: bwd(g_r), max(100, args.steps), warm=20)
@@ -212,7 +294,7 @@ def main():
             "tokens_per_s": round(wl.tokens / (tot * 1e-3), 1),
             "tflops": round(fl / (tot * 1e-3) / 1e12, 2),
             "frac_bf16_peak": round(fl / (tot * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-            "frac_measured_mfma_peak": round(fl / (tot * 1e-3) / 1e12 / MEASURED_MFMA_BF16_TFLOPS, 4),
+            "frac_measured_mfma_peak": round(fl / (tot * 1e-3) / 1e12 / mfma_measured, 4),
             # algorithmic HBM bytes (8 d forward, 20 d backward per token-head, bf16) over the time
             "algorithmic_GBs": round(28 * d * th / (tot * 1e-3) / 1e9, 1),
             "frac_hbm_peak": round(28 * d * th / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
@@ -331,7 +413,7 @@ def main():
     # points then skip one of the backward's two chunk-state pre-passes.  Reported beside the headline, which
     # stays on the stand-alone la2_fwd + la2_bwd.
     saved = []
-    for wl, g in sweep[2:4]:
+    for wl, g in sweep:
         ws_b = torch.empty_like(g["ws"])
         f_ms = time_ms(lambda: fwd(g), iters)
         b_ms = time_ms(lambda: binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], want_d_kv_init=False,
@@ -340,6 +422,12 @@ def main():
                       "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                       "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1)})
         del ws_b
+    tps_saved = [p_["tokens_per_s"] for p_ in saved]
+    training_step = {"what": "la2_fwd, then la2_bwd_saved on the forward call's workspace, at the four sweep points",
+                     "flatness_min_over_max": round(min(tps_saved) / max(tps_saved), 4),
+                     "tokens_per_s": round(sum(wl.tokens for wl, _ in sweep)
+                                           / sum((p_["fwd_ms"] + p_["bwd_ms"]) * 1e-3 for p_ in saved), 1),
+                     "sweep": saved}
     torch.cuda.empty_cache()
 
     # decode: 1024 consecutive steps, state updated in place
@@ -369,7 +457,7 @@ def main():
     kv_bytes = kv.numel() * kv.element_size()
     kv_u8 = kv.view(torch.uint8).reshape(-1)
     kv_out = torch.empty_like(kv_u8)
-    sref_ms = min(time_ms(lambda: binding.la2_stream_probe(1, 1, kv_u8, kv_out, kv_bytes, nt_stores=nts), 200, warm=20)
+    sref_ms = min(time_ms(lambda: bench_probe.stream_probe(1, 1, kv_u8, kv_out, kv_bytes, nt_stores=nts), 200, warm=20)
                   for nts in (False, True))
     del kv_out
     decode["stream_reference"] = {"kernel": "1 stream in, 1 out, the state's %d MiB each, no arithmetic" % (kv_bytes >> 20),
@@ -406,10 +494,16 @@ def main():
         oracle.fwd_direct(q, k, v, lam)
         oracle.bwd_direct(q, k, v, do, lam)
         c1 = time.perf_counter()
+        # ... and the oracle's O(n d^2) recurrent form (what the all-chain full-size parity tests use) on the same sample
+        oracle.fwd_recurrent(q, k, v, lam)
+        oracle.bwd_recurrent(q, k, v, do, lam)
+        c2 = time.perf_counter()
         cpu = {"value": round(wl_c.seqlen * rows_c / (c1 - c0), 2), "unit": "tokens/s",
                "cores": oracle.num_threads(), "kind": "oracle",
                "sample": "fp64 direct O(n^2) oracle, fwd+bwd, all %d heads of batch rows 0..%d of %s (%.1f s)"
-                         % (heads_c, rows_c - 1, wl_c.name, c1 - c0)}
+                         % (heads_c, rows_c - 1, wl_c.name, c1 - c0),
+               "recurrent_form": {"value": round(wl_c.seqlen * rows_c / (c2 - c1), 2), "unit": "tokens/s",
+                                  "sample": "fp64 token recurrence, fwd+bwd, same sample (%.1f s)" % (c2 - c1)}}
 
     out = {
         "metric": "causal linear-attn fwd+bwd tokens/s (sequence-length sweep n=1K-64K at 65,536 tokens per point)",
@@ -434,7 +528,7 @@ def main():
         "sweep": points,
         "other_configs": others,
         "state_handover": with_states,
-        "saved_forward_states": saved,
+        "training_step_saved_forward_states": training_step,
         "normalised_operator": normed,
         "other_dtypes": other_dtypes,
         "other_head_dims": other_head_dims,
