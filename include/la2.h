@@ -16,7 +16,8 @@
  * Conventions common to every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device.  The caller owns every
  *     buffer, including the workspace; the library allocates nothing and never synchronises.  Its only
- *     state between calls are the two tuning knobs at the end of this header.
+ *     state between calls are the two tuning knobs at the end of this header and, per device, the address of
+ *     la2_fwd_noalloc's built-in scratch.
  *     Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
  *   - Descriptors (`la2_desc`) are HOST structs.
  *   - Sequence tensors (q, k, v, o, d_o, dq, dk, dv) share one shape [batch, heads, seqlen, head_dim]
@@ -110,6 +111,25 @@ la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
                    const float* lambda, void* o, void* workspace, size_t workspace_bytes,
                    void* hip_stream);
+
+/*
+ * la2_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * la2_fwd, without the workspace: the chunk start states live in LA2_NOALLOC_SCRATCH_BYTES of device memory
+ * that is part of the library's code object (each GPU the library runs on holds that much until the process
+ * ends).  The call allocates nothing and frees nothing; its first use on a device looks up the scratch
+ * address there (which may load the code object on that device), later calls only enqueue kernels.
+ *   - A problem whose la2_workspace_bytes(desc, LA2_OP_FWD) exceeds LA2_NOALLOC_SCRATCH_BYTES is refused with
+ *     LA2_ERR_WORKSPACE before anything is launched (the sweep's (4, 16K) and (1, 64K) points need exactly
+ *     that much on a 256-CU device; problems whose chains fill the device need none).
+ *   - All calls on one GPU share that GPU's scratch, whatever their stream: calls that overlap in time on one
+ *     GPU race on it.  Calls on one stream, or otherwise ordered, are fine; the scratch keeps the previous
+ *     call's contents and every call overwrites what it reads, so nothing needs clearing in between.
+ *   - LA2_ERR_LAUNCH if the current device cannot be determined or holds no copy of the scratch.
+ */
+#define LA2_NOALLOC_SCRATCH_BYTES (16u << 20)
+la2_status la2_fwd_noalloc(const la2_desc* desc, const void* q, const void* k, const void* v,
+                           const float* lambda, void* o, void* hip_stream);
 
 /*
  * Backward pass, Algorithm 2:  (dq, dk, dv) from (q, k, v, d_o).  dq comes from an ascending pass

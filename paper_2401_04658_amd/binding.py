@@ -67,6 +67,8 @@ def load():
     lib.la2_decode_step_norm.restype = ctypes.c_int
     lib.la2_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_fwd.restype = ctypes.c_int
+    lib.la2_fwd_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    lib.la2_fwd_noalloc.restype = ctypes.c_int
     lib.la2_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd.restype = ctypes.c_int
     lib.la2_fwd_state.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -179,6 +181,20 @@ def la2_fwd(q, k, v, lam, out=None, workspace=None):
     with torch.cuda.device(q.device):
         _check(lib.la2_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
                            out.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
+    return out
+
+
+def la2_fwd_noalloc(q, k, v, lam, out):
+    """la2_fwd into `out` with the library's built-in scratch instead of a workspace; the call itself allocates
+    nothing (so `out` is required)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_noalloc: tensors must live on the GPU")
+    _same_layout(q, k, v, out)
+    desc = make_desc(q)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_noalloc(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
+                                   out.data_ptr(), _stream(q)))
     return out
 
 

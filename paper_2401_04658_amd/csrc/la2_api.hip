@@ -7,9 +7,15 @@
 #include "../../include/la2.h"
 #include "la2_internal.h"
 
+// Chunk start states of la2_fwd_noalloc: device memory that belongs to the library's code object, so that the
+// entry point needs no workspace argument and never allocates.  Every GPU the library runs on holds its own
+// copy at its own address; in host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[LA2_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
-// The two test / tuning knobs are the library's only mutable state: plain atomics, read once per call.
+// The two test / tuning knobs are the library's only mutable state besides the per-device scratch address:
+// plain atomics, read once per call.
 std::atomic<int> g_chunk_tokens_override{0};  // la2_set_chunk_tokens()
 std::atomic<int> g_scan_variant{0};           // la2_set_scan_variant()
 // The block kernels form states after whole blocks only: 32 positions for the kernels that take states
@@ -38,6 +44,29 @@ int device_cu_count() {
 }
 
 int elem_size(int dtype) { return dtype == LA2_F32 ? 4 : 2; }
+
+// Device address of `scratch` on the current device, looked up once per device (the first call on a device
+// may load the code object there; later calls only read the cached pointer).
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+la2_status scratch_on_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return LA2_ERR_LAUNCH;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return LA2_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // two threads racing here store the same address
+  }
+  *out = ptr;
+  return LA2_OK;
+}
 
 la2_status check_desc_fields(const la2_desc* d) {
   if (d == nullptr) return LA2_ERR_NULL;
@@ -398,6 +427,26 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
                    void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return la2_fwd_state(desc, q, k, v, lambda, nullptr, o, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+la2_status la2_fwd_noalloc(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                           void* o, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const size_t need = make_plan(desc).workspace;
+  if (need > (size_t)LA2_NOALLOC_SCRATCH_BYTES) return LA2_ERR_WORKSPACE;   // chunk states beyond the built-in scratch
+  void* ws = nullptr;
+  if (need > 0) {
+    st = scratch_on_current_device(&ws);
+    if (st != LA2_OK) return st;
+  }
+  // Nothing in the scratch has to start at zero: the pre-pass writes the local state of every chunk that has a
+  // successor and the state scan overwrites all of them, before the scan kernel reads any.
+  return fwd_state_impl(desc, q, k, v, lambda, nullptr, o, nullptr, nullptr, 0.f, ws, need, hip_stream);
 }
 
 la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,

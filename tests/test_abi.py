@@ -362,6 +362,24 @@ def test_bench_helpers_are_a_library_of_their_own(lib):
     assert bl.la2_bench_mfma_peak(0, 10, P, None) == E_SHAPE and bl.la2_bench_mfma_peak(4, 10, None, None) == E_NULL
 
 
+def test_noalloc_entry_validates_on_the_host(lib):
+    fn = lambda d, q=P, k=P, v=P, lam=P, o=P: lib.la2_fwd_noalloc(ctypes.byref(d) if d is not None else None,
+                                                                  q, k, v, lam, o, None)
+    d = dense(lib, 1, 8, 8192, 128, binding.LA2_BF16)
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 16 << 20      # exactly what the built-in scratch holds
+    assert fn(None) == E_NULL
+    for name in ("q", "k", "v", "lam", "o"):
+        assert fn(d, **{name: None}) == E_NULL
+    assert fn(d, q=P + 2) == E_ALIGN
+    d.head_dim = 80
+    assert fn(d) == E_SHAPE
+    big = dense(lib, 1, 200, 1 << 18, 128, binding.LA2_BF16)            # 25 MiB of chunk states
+    assert lib.la2_workspace_bytes(ctypes.byref(big), 0) > 16 << 20
+    assert fn(big) == E_WS
+    empty = dense(lib, 0, 8, 8192, 128, binding.LA2_BF16)
+    assert fn(empty, q=None, k=None, v=None, lam=None, o=None) == OK
+
+
 def test_bwd_saved_checks_the_forward_workspace(lib):
     vp = ctypes.c_void_p
     lib.la2_bwd_saved.argtypes = [vp] * 13 + [ctypes.c_size_t, ctypes.c_int32, vp, ctypes.c_size_t, vp]
