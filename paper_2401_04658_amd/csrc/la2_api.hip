@@ -174,6 +174,10 @@ struct ScanArgs {
   int rstd_stride = 0;   // positions per chain in rstd
   // packed sequences of different lengths: device array of batch + 1 position offsets, or nullptr
   const int32_t* cu = nullptr;
+  // forward 16-bit scan of head_dim 128 in chunks: also accumulate the reverse local chunk states of the
+  // (acc_y, x) pair into acc_states (ScanParams::acc_y)
+  const void* acc_y = nullptr;
+  float* acc_states = nullptr;
 };
 
 la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace,
@@ -193,14 +197,16 @@ la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lamb
 }
 
 // chunk start states of the scan with key-like operand y and value-like operand z -> workspace
+// (local_ready: an earlier launch already left the chunks' local states there; only the scan over them runs)
 la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const void* y, const void* z,
                        const float* init, bool init_tr, const float* lambda, void* workspace, hipStream_t s,
-                       const int32_t* cu = nullptr) {
+                       const int32_t* cu = nullptr, bool local_ready = false) {
   if (pl.nchunks <= 1) return LA2_OK;
   la2::ScanParams p = base_params(d, pl, lambda, workspace, cu);
   p.y[0] = y; p.z[0] = z;
   p.init[0] = init; p.init_transposed = init_tr ? 1 : 0;
-  hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, true, p, s)
+  hipError_t e = local_ready          ? hipSuccess
+                : wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, true, p, s)
                 : is16(d->dtype)   ? la2::launch_chunk_states_bf16(d->dtype, d->head_dim, reverse, p, s)
                                    : la2::launch_chunk_states_f32(d->head_dim, reverse, p, s);
   if (e != hipSuccess) return LA2_ERR_LAUNCH;
@@ -226,6 +232,8 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
   p.rstd = a.rstd;
   p.eps = a.eps;
   p.rstd_stride = a.rstd_stride;
+  p.acc_y = a.acc_y;
+  p.acc_states = a.acc_states;
   hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, false, p, s)
                 : is16(d->dtype)   ? la2::launch_scan_bf16(d->dtype, d->head_dim, reverse, p, s)
                                    : la2::launch_scan_f32(d->head_dim, reverse, p, s);
@@ -234,9 +242,10 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
 
 // Two reverse scans whose states are transposes of each other (scan 1's y, z are scan 0's z, y): one
 // state pre-pass, one launch (16-bit path).
+// (local_ready: the workspace already holds the chunks' local states, left there by the dQ scan's launch)
 la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanArgs& a0, const ScanArgs& a1,
-                                 const float* lambda, void* workspace, hipStream_t s) {
-  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s, a0.cu);
+                                 const float* lambda, void* workspace, hipStream_t s, bool local_ready = false) {
+  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s, a0.cu, local_ready);
   if (st != LA2_OK) return st;
   la2::ScanParams p = base_params(d, pl, lambda, workspace, a0.cu);
   p.nscan = 2;
@@ -266,8 +275,14 @@ la2_desc whole_blocks(const la2_desc* d) {
   return w;
 }
 
+// Algorithm 2 on a sequence-chunked problem, 16-bit data, head_dim 128: the dQ scan's launch also forms the local
+// dKV states of the chunks (its second wave group), so the backward pass keeps two sets of chunk states.
+bool fuses_reverse_states(const la2_desc* d) {
+  return is16(d->dtype) && d->head_dim == 128 && g_scan_variant.load(std::memory_order_relaxed) != 1;
+}
+
 StateWorkspace state_workspace(const la2_desc* d, bool backward) {
-  StateWorkspace w{make_plan(d).workspace, 0};
+  StateWorkspace w{make_plan(d).workspace * ((backward && fuses_reverse_states(d)) ? 2 : 1), 0};
   if (d->seqlen % state_granule(d) != 0) {
     const la2_desc wb = whole_blocks(d);
     const size_t other = make_plan(&wb).workspace;
@@ -284,7 +299,7 @@ StateWorkspace state_workspace(const la2_desc* d, bool backward) {
 // ragged end.
 size_t bwd_workspace_need(const la2_desc* d, bool has_d_kv_final) {
   const bool split = has_d_kv_final && d->seqlen % state_granule(d) != 0;
-  return split ? state_workspace(d, true).total : make_plan(d).workspace;
+  return split ? state_workspace(d, true).total : make_plan(d).workspace * (fuses_reverse_states(d) ? 2 : 1);
 }
 
 la2::RecurParams recur_params(const la2_desc* d, const float* lambda, int t0, int t1, bool reverse) {
@@ -317,8 +332,9 @@ void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen
 
 size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
   if (check_desc(desc) != LA2_OK) return 0;
-  if (op == LA2_OP_FWD || op == LA2_OP_BWD)
-    return make_plan(desc).workspace;  // the backward's three scans run one after another in the same space
+  if (op == LA2_OP_FWD) return make_plan(desc).workspace;
+  if (op == LA2_OP_BWD)   // the chunk states of the dQ scan and (when its launch forms them) those of the dK / dV scan
+    return make_plan(desc).workspace * (fuses_reverse_states(desc) ? 2 : 1);
   if (op == LA2_OP_FWD_STATE || op == LA2_OP_BWD_STATE) return state_workspace(desc, op == LA2_OP_BWD_STATE).total;
   return 0;
 }
@@ -489,11 +505,6 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   const bool split = d_kv_final != nullptr && desc->seqlen % state_granule(desc) != 0;
   const la2_desc blocks = split ? whole_blocks(desc) : *desc;   // what the reverse block kernels process
   const Plan pl = make_plan(desc), pl_rev = make_plan(&blocks);
-  const StateWorkspace sw = state_workspace(desc, true);
-  const size_t need = split ? sw.total : pl.workspace;
-  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LA2_ERR_WORKSPACE;
-  if (need > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
-  float* handoff = split ? reinterpret_cast<float*>(static_cast<char*>(workspace) + sw.chunk_states) : nullptr;
   // Algorithm 2, first loop (ascending, running KV):  dQ = [(dO V^T) * M] K + Lambda dO KV^T
   // (forward scan of (dO, V, K); its state is KV^T, so a start state KV is read transposed)
   ScanArgs for_dq{d_o, v, k, dq};
@@ -511,6 +522,23 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
       for_dq.saved_states = reinterpret_cast<const float*>(fwd_workspace);
       for_dq.saved_tr = true;
     }
+  }
+  // Sequence chunks, 16-bit data, head_dim 128: the dQ scan's launch also forms the local dKV states of the
+  // chunks (from dO, which it streams anyway, and Q), so the second loop needs no pass of its own over Q and dO
+  // before it can start its chunks.  Those states live behind the dQ scan's own chunk states in the workspace
+  // (or at its start when the dQ scan reads the forward call's).  Not when the reverse scans run on the whole
+  // blocks only (their chunks may then differ from the dQ scan's).
+  const bool fuse = !split && pl.nchunks > 1 && fuses_reverse_states(desc);
+  const StateWorkspace sw = state_workspace(desc, true);
+  const size_t need = split ? sw.total : fuse ? pl.workspace * (for_dq.saved_states != nullptr ? 1 : 2) : pl.workspace;
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LA2_ERR_WORKSPACE;
+  if (need > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  float* handoff = split ? reinterpret_cast<float*>(static_cast<char*>(workspace) + sw.chunk_states) : nullptr;
+  void* rev_workspace = workspace;
+  if (fuse) {
+    if (for_dq.saved_states == nullptr) rev_workspace = static_cast<char*>(workspace) + pl.workspace;
+    for_dq.acc_y = q;
+    for_dq.acc_states = reinterpret_cast<float*>(rev_workspace);
   }
   st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
   if (st != LA2_OK) return st;
@@ -536,7 +564,8 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   for_dv.fin = d_kv_init;
   for_dk.init = rev_init;
   for_dk.init_tr = true;
-  if (is16(desc->dtype)) return run_dual_reverse_scan(&blocks, pl_rev, for_dv, for_dk, lambda, workspace, s);
+  if (is16(desc->dtype))
+    return run_dual_reverse_scan(&blocks, pl_rev, for_dv, for_dk, lambda, rev_workspace, s, /*local_ready=*/fuse);
   st = run_scan(&blocks, pl_rev, true, for_dv, lambda, workspace, s);
   if (st != LA2_OK) return st;
   return run_scan(&blocks, pl_rev, true, for_dk, lambda, workspace, s);

@@ -122,26 +122,60 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
 // The chunk processed first starts from init (element e read at its transposed place if init_tr) or 0.
 // The carried state decays by lambda^(chunk length): all chunks are chunk_tokens long except the last
 // one of the sequence, which a reverse scan passes first.
+// A thread owns four consecutive elements of the d x d state.  With up to MAXC chunks it fetches all local
+// states first (independent loads, all in flight together) and then runs the recurrence on registers; the
+// launch sits between two kernels that wait for it, so its latency is what counts, not its bytes.
+constexpr int kScanMaxChunks = 32;
 __global__ void state_scan_kernel(float* states, const float* lambda, int heads, int nchunks, int chunk_tokens,
                                   int dd, int reverse, const float* init, int init_tr, int d, int n,
                                   const int32_t* cu_seqlens) {
-  const int per_chain = (dd + (int)blockDim.x - 1) / (int)blockDim.x;   // workgroups per chain
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  const int dd4 = dd >> 2;
+  const int per_chain = (dd4 + (int)blockDim.x - 1) / (int)blockDim.x;   // workgroups per chain
   const int chain = (int)(blockIdx.x / per_chain);
-  const int e = (int)(blockIdx.x % per_chain) * (int)blockDim.x + (int)threadIdx.x;
-  if (e >= dd) return;
+  const int e4 = (int)(blockIdx.x % per_chain) * (int)blockDim.x + (int)threadIdx.x;
+  if (e4 >= dd4) return;
   if (cu_seqlens != nullptr) n = cu_seqlens[chain / heads + 1] - cu_seqlens[chain / heads];   // this sequence's length
   const int nch = (n + chunk_tokens - 1) / chunk_tokens;   // chunks this chain really has (<= nchunks)
   const float l2 = log2f(lambda[chain % heads]);
   const float lamFull = exp2f(l2 * (float)chunk_tokens);
   const float lamLast = exp2f(l2 * (float)(n - (nch - 1) * chunk_tokens));
-  float* s = states + (int64_t)chain * nchunks * dd + e;
-  float g = 0.f;
-  if (init != nullptr) g = init[(int64_t)chain * dd + (init_tr ? (e % d) * d + e / d : e)];
+  f32x4* s = reinterpret_cast<f32x4*>(states + (int64_t)chain * nchunks * dd) + e4;
+  f32x4 g = {0.f, 0.f, 0.f, 0.f};
+  if (init != nullptr) {
+    const float* gi = init + (int64_t)chain * dd;
+    const int e = 4 * e4;   // d is a multiple of 4: the four elements share a row
+    if (init_tr) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) g[i] = gi[((e + i) % d) * d + e / d];
+    } else {
+      g = *reinterpret_cast<const f32x4*>(gi + e);
+    }
+  }
+  if (nch <= kScanMaxChunks) {
+    f32x4 loc[kScanMaxChunks];
+#pragma unroll
+    for (int i = 0; i < kScanMaxChunks; i++) {
+      const int j = reverse ? nch - 1 - i : i;
+      if (i < nch - 1) loc[i] = s[(int64_t)j * dd4];   // the chunk processed last has no successor: not read
+    }
+#pragma unroll
+    for (int i = 0; i < kScanMaxChunks; i++) {
+      if (i < nch) {
+        const int j = reverse ? nch - 1 - i : i;
+        s[(int64_t)j * dd4] = g;
+        const float decay = (j == nch - 1) ? lamLast : lamFull;
+        if (i < nch - 1) g = decay * g + loc[i];
+      }
+    }
+    return;
+  }
   for (int i = 0; i < nch; i++) {
     const int j = reverse ? nch - 1 - i : i;
     const bool last = (i == nch - 1);
-    const float loc = last ? 0.f : s[(int64_t)j * dd];
-    s[(int64_t)j * dd] = g;
+    f32x4 loc = {0.f, 0.f, 0.f, 0.f};
+    if (!last) loc = s[(int64_t)j * dd4];
+    s[(int64_t)j * dd4] = g;
     g = (j == nch - 1 ? lamLast : lamFull) * g + loc;
   }
 }
@@ -175,7 +209,7 @@ hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hi
   const int chains = p.batch * p.heads;
   if (chains == 0 || p.n == 0) return hipSuccess;
   const int dd = head_dim * head_dim;
-  dim3 g((unsigned)((int64_t)chains * ((dd + 255) / 256))), b(256);   // the host checked that this fits a grid
+  dim3 g((unsigned)((int64_t)chains * ((dd / 4 + 255) / 256))), b(256);   // the host checked that this fits a grid
   hipLaunchKernelGGL(state_scan_kernel, g, b, 0, s, p.states, p.lambda, p.heads, p.nchunks, p.chunk_tokens, dd,
                      reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n, p.cu_seqlens);
   return hipGetLastError();

@@ -56,6 +56,14 @@ struct ScanParams {
   // offsets: sequence b is positions cu_seqlens[b] .. cu_seqlens[b + 1] - 1 of a [total, heads, d] tensor
   // (stride_b unused); n is then the longest sequence's length, what the launch is planned for.
   const int32_t* cu_seqlens;
+  // Forward 16-bit scan of head_dim 128 only: a second group of waves in every workgroup accumulates, from the
+  // scan's own X tiles (as value-like operand) and the tiles of acc_y (as key-like operand), the REVERSE local
+  // state of the workgroup's chunk, sum_c lambda^(c+1) acc_y_c^T x_c over the chunk's positions c (counted from
+  // the chunk's first), into acc_states [chains][nchunks][D][D] (chunk 0 of a chain is not written: no chunk
+  // follows it in a reverse scan).  Algorithm 2: the dQ scan streams dO anyway; with Q beside it, it leaves
+  // the local dKV states that the dK / dV scan's chunks start from.  nullptr: off.
+  const void* acc_y;
+  float* acc_states;
 };
 
 // Element offset of chain (bi, hi)'s first position and the chain's length.

@@ -27,22 +27,30 @@ constexpr int kBH = 32;
 //
 // NORM: the Norm epilogue of eq. (2) on a forward scan: the four waves exchange the sums of squares of
 // their quarter rows through LDS (under the block's one barrier, which moves behind the intra-block
-// product for this), scale the finished tile and wave 0 stores r.  The LDS is full, so the room for the exchange is taken from the output staging,
-// which then handles the block in two halves of 16 positions.
-template <typename E, bool REV, bool TWIN, int NBUF, bool NORM = false>
-__global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
+// product for this), scale the finished tile and wave 0 stores r.  The LDS is full, so this variant has no
+// staging buffer of its own: it stages each wave's output in the block's X tile, which is dead by then.
+//
+// ACC: a forward scan whose workgroup has a second group of four waves (8 waves, one workgroup per compute
+// unit, FOUR tiles per block: X, Y, Z and p.acc_y).  Waves 0-3 run the scan as usual; waves 4-7 accumulate
+// the reverse local state of the chunk for ANOTHER pair of scans, sum_c lambda^(c+1) acc_y_c^T x_c (c counted
+// from the chunk's first position), and leave it in p.acc_states.  Algorithm 2: the dQ scan (x = dO) with
+// acc_y = Q leaves the local dKV states of the sequence chunks, so the dK / dV scan needs no pass of its own
+// over Q and dO to form them.
+template <typename E, bool REV, bool TWIN, int NBUF, bool NORM = false, bool ACC = false>
+__global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
   static_assert(!NORM || (!REV && !TWIN), "the Norm epilogue belongs to the forward pass");
+  static_assert(!ACC || (!REV && !TWIN && !NORM), "the accumulating wave group rides on a plain forward scan");
   constexpr int D = 128, B = kBH;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
-  constexpr int NW = TWIN ? 8 : 4;             // waves
-  constexpr int NTL = TWIN ? 4 : 3;            // tiles per block
+  constexpr int NW = (TWIN || ACC) ? 8 : 4;    // waves
+  constexpr int NTL = (TWIN || ACC) ? 4 : 3;   // tiles per block
   using Loader = TileLoader<D, NTL, B, NW>;
   __shared__ __attribute__((aligned(1024))) E sT[NBUF][NTL][TILE];
   // Output staging, 32 positions x 32 features per wave.  The NORM variant has no LDS left for it beside its
   // exchange buffer (two workgroups of 80 KiB per compute unit) and stages in the block's own X tile instead,
   // which is dead by then: see the epilogue.
-  __shared__ __attribute__((aligned(16))) E sW[NW][NORM ? LW : 32 * LW];
+  __shared__ __attribute__((aligned(16))) E sW[ACC ? 4 : NW][NORM ? LW : 32 * LW];
   float* const sRed = NormExchange<NORM ? 2 * 32 * 4 : 0>::get();   // [block parity][position][wave]
   // Cache policy of the output stores (buffer instruction bits: 2 = nt, 16 = sc1).  Measured: the twin
   // workgroup, a third of whose traffic is stores, runs 9-13 % faster with streaming write-through stores;
@@ -60,8 +68,11 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w & 3;
   int which = 0, wg = (int)blockIdx.x;
+  const int group = __builtin_amdgcn_readfirstlane(w >> 2);   // TWIN: which scan; ACC: scan waves or accumulating waves
   if (TWIN) {
-    which = __builtin_amdgcn_readfirstlane(w >> 2);
+    which = group;
+  } else if (ACC) {
+    // one scan only
   } else if (p.nscan == 2) {   // same pairing as scan_bf16_kernel
     if (((gridDim.x >> 1) & 7) == 0) {
       which = (int)(blockIdx.x >> 3) & 1;
@@ -97,7 +108,12 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   const int nblk = blk_hi - blk_lo;
 
   Loader loader(w, l, n, stride_n);
-  if (TWIN) {
+  if (ACC) {
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
+    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.acc_y) + base);
+  } else if (TWIN) {
     loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
     loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[1]) + base);
     loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
@@ -110,6 +126,74 @@ __global__ __launch_bounds__(TWIN ? 512 : 256, TWIN ? 1 : 2) void scan_bf16_half
   // this wave's X, Y, Z among the tiles of a block
   constexpr int xi = TWIN ? WH : 0, yi = TWIN ? 2 + WH : 1, zi = TWIN ? 3 - WH : 2;
   const LaneAddr<D> la(l);
+
+  if constexpr (ACC) {
+    if (group == 1) {
+      // ---- the accumulating waves: same loads, same barriers as the scan waves; per block only the state
+      // update step, on (acc_y, X) with reverse weights.  The block processed it-th lies it blocks above the
+      // chunk's first position: its contribution carries lambda^(B it) up front, the sum needs no running decay.
+      constexpr int ACC_YOUNGER = (NBUF - 2) * NDMA;   // no stores in this wave group
+      constexpr int ACC_WAIT = (ACC_YOUNGER & 15) | ((ACC_YOUNGER >> 4) << 14) | 0x0F70;
+      const UpdateDecay<true, B> adecay(l2, hh);
+      f32x16 acc[NT];
+#pragma unroll
+      for (int t = 0; t < NT; t++) acc[t] = zero16();
+#pragma unroll
+      for (int j = 0; j < NBUF - 1; j++)
+        if (j < nblk) loader.issue(sT[j], blk_lo + j);
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+#pragma unroll
+      for (int j = 0; j < NBUF - 1; j++)
+        if (j < nblk) loader.zero_tail(sT[j], blk_lo + j);
+      __syncthreads();
+      auto acc_step = [&](auto cur_tag, int it) __attribute__((always_inline)) -> bool {
+        constexpr int cur = decltype(cur_tag)::value;
+        const bool has_next = it + 1 < nblk, has_ahead = it + NBUF - 1 < nblk;
+        uint32_t doff[Loader::DMA_PER_WAVE];
+        loader.offsets(blk_lo + it + (NBUF - 1), has_ahead, doff);
+#pragma unroll
+        for (int j = 0; j < NDMA; j++) loader.issue_one(sT[(cur + NBUF - 1) % NBUF], doff, j);
+        const E* tY = sT[cur][NTL - 1];
+        const E* tZ = sT[cur][0];
+        ex8<E> zf[2], yt[2][NT];
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          zf[q] = la.read_cols(tZ, 16 * q, dvt);
+#pragma unroll
+          for (int t = 0; t < NT; t++) yt[q][t] = la.read_cols(tY, 16 * q, t);
+        }
+        const float blk_decay = uniform(exp2f(l2 * (float)(B * it)));
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          const ex8<E> zd = adecay.apply(zf[q], 16 * q, blk_decay);
+#pragma unroll
+          for (int t = 0; t < NT; t++) acc[t] = mfma(yt[q][t], zd, acc[t]);
+        }
+        if (has_next) {
+          __builtin_amdgcn_s_waitcnt(ACC_WAIT);
+          loader.zero_tail(sT[(cur + 1) % NBUF], blk_lo + it + 1);
+          lds_barrier();
+        }
+        return has_next;
+      };
+      for (int it = 0;; it += NBUF) {
+        if (!acc_step(std::integral_constant<int, 0>{}, it)) break;
+        if (!acc_step(std::integral_constant<int, 1>{}, it + 1)) break;
+        if (!acc_step(std::integral_constant<int, 2 % NBUF>{}, it + 2)) break;
+        if (NBUF > 3 && !acc_step(std::integral_constant<int, 3 % NBUF>{}, it + 3)) break;
+        if (NBUF > 4 && !acc_step(std::integral_constant<int, 4 % NBUF>{}, it + 4)) break;
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
+      if (chunk != 0) {   // chunk 0 is the last one a reverse scan reaches: nobody starts from its local state
+        float* gs = p.acc_states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) gs[state_index<D>(dvt, l32, hh, t, v, false)] = acc[t][v];
+      }
+      return;
+    }
+  }
 
   f32x16 kv[NT];
   const float* gs = nullptr;   // start state: chunk start state, the caller's start state, or zero
@@ -361,6 +445,8 @@ hipError_t launch_half(bool reverse, bool twin, const ScanParams& p, hipStream_t
   } else {
     dim3 g((unsigned)grid), b(kThreads);
     if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, true, false, 3>), g, b, 0, s, p);
+    else if (p.acc_states != nullptr)
+      hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3, false, true>), g, dim3(512), 0, s, p);
     else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3, true>), g, b, 0, s, p);
     else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3>), g, b, 0, s, p);
   }

@@ -119,12 +119,16 @@ def test_workspace_rules(lib):
         d = dense(lib, 1, 2, 1024, 128, binding.LA2_BF16)
         need = lib.la2_workspace_bytes(ctypes.byref(d), 0)
         assert need == 2 * 4 * 128 * 128 * 4  # chains x chunks x d x d fp32
-        assert lib.la2_workspace_bytes(ctypes.byref(d), 1) == need
+        # backward, 16-bit head_dim 128: the dQ scan's chunk states and the dK / dV scan's, side by side
+        assert lib.la2_workspace_bytes(ctypes.byref(d), 1) == 2 * need
+        d64 = dense(lib, 1, 2, 1024, 64, binding.LA2_BF16)
+        assert lib.la2_workspace_bytes(ctypes.byref(d64), 1) == lib.la2_workspace_bytes(ctypes.byref(d64), 0) > 0
         assert lib.la2_workspace_bytes(ctypes.byref(d), 9) == 0
         assert fwd(lib, d) == E_WS
         assert fwd(lib, d, ws=P, ws_bytes=need - 1) == E_WS
         assert fwd(lib, d, ws=P + 16, ws_bytes=need) == E_WS
-        assert bwd(lib, d, ws=None, ws_bytes=need) == E_WS
+        assert bwd(lib, d, ws=None, ws_bytes=2 * need) == E_WS
+        assert bwd(lib, d, ws=P * 16, ws_bytes=2 * need - 1) == E_WS
         # a chunk as long as the sequence needs no workspace
         lib.la2_set_chunk_tokens(1024)
         assert lib.la2_workspace_bytes(ctypes.byref(d), 0) == 0
@@ -388,12 +392,14 @@ def test_bwd_saved_checks_the_forward_workspace(lib):
         lib.la2_set_chunk_tokens(256)
         d = dense(lib, 1, 2, 1024, 128, binding.LA2_BF16)
         need = lib.la2_workspace_bytes(ctypes.byref(d), 3)
-        assert need > 0
+        fneed = lib.la2_workspace_bytes(ctypes.byref(d), 2)
+        assert need > 0 and fneed > 0
         call = lambda fws, fbytes, ws=P * 16, wsb=need: lib.la2_bwd_saved(
             ctypes.byref(d), P, P, P, P, P, None, None, P, P, P, None, fws, fbytes, 0, ws, wsb, None)
-        assert call(P * 16 + 8, need) == E_WS        # misaligned
-        assert call(P * 16, need - 1) == E_WS        # smaller than what the forward call needed
-        assert call(P * 16, need, wsb=need - 1) == E_WS
+        assert call(P * 16 + 8, fneed) == E_WS        # misaligned
+        assert call(P * 16, fneed - 1) == E_WS        # smaller than what the forward call needed
+        # with the forward call's chunk states at hand the backward pass needs room for the dK / dV scan's only
+        assert call(P * 16, fneed, wsb=fneed - 1) == E_WS
     finally:
         lib.la2_set_chunk_tokens(0)
 

@@ -263,3 +263,31 @@ def test_backward_after_a_forward_that_wrote_kv_final_at_a_ragged_length(d, n, c
     assert_close(tag + " dk", dk, rdk, dtype)
     assert_close(tag + " dv", dv, rdv, dtype)
     assert_close(tag + " d_kv_init", g0, rg0, dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("n,chunk", [(1024, 256), (1000, 128), (777, 64), (4096, 512)])
+def test_dq_launch_forms_the_reverse_chunk_states(dtype, n, chunk):
+    """Sequence chunks at head_dim 128: the dQ scan's launch also accumulates the local dKV states of the chunks
+    (second wave group), the dK / dV scan starts from them.  Against the oracle, with start state and incoming
+    state gradient, whole and ragged lengths, single-block chunks (64) included; and against the path that does
+    not fuse (full-block kernel forced: separate pre-pass over Q and dO)."""
+    t = inputs(2, 3, n, 128, dtype, seed=1500 + n, lam=[0.37, 0.9, 0.999])
+    g = {k: v.to(DEV) for k, v in t.items()}
+    binding.la2_set_chunk_tokens(chunk)
+    assert binding.la2_chunk_plan(g["q"])[0] > 1
+    use_final = n % 32 == 0   # an incoming gradient at a ragged end splits the reverse pass: not the fused path
+    d_fin = g["d_kv_final"] if use_final else None
+    dq, dk, dv, g0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=g["kv_init"],
+                                           d_kv_final=d_fin)
+    binding.la2_set_scan_variant(1)
+    uq, uk, uv, u0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=g["kv_init"],
+                                           d_kv_final=d_fin)
+    torch.cuda.synchronize()
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    rdq, rdk, rdv, rg0 = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=to64(t["kv_init"]),
+                                                    d_kv_final=to64(t["d_kv_final"]) if use_final else None)
+    tag = "fused reverse states %s n%d chunk%d" % (dtype, n, chunk)
+    for name, got, other, ref in (("dq", dq, uq, rdq), ("dk", dk, uk, rdk), ("dv", dv, uv, rdv), ("d_kv_init", g0, u0, rg0)):
+        assert_close(tag + " " + name, got, ref, dtype)
+        assert_close(tag + " unfused " + name, other, ref, dtype)
