@@ -396,7 +396,7 @@ def main():
                                     "fwd_algorithmic_GBs": round(4 * unit / f_ms / 1e6, 1),
                                     "bwd_algorithmic_GBs": round(10 * unit / b_ms / 1e6, 1)})
             del g_h
-    # the forward pass as the O(n^2 d) masked left product (comparison kernel) against the block recurrence
+    # forward and backward pass as O(n^2 d) masked left products (comparison kernel) against the block recurrence
     crossover = []
     short = [(wl_, stage(wl_)) for wl_ in (workloads.Workload("config3_like_b%d_n%d_h16_d128" % (b_, n_), b_, 16, n_, 128,
                                                               torch.bfloat16, seed=40 + i_)
@@ -404,9 +404,14 @@ def main():
     for wl, g in short + sweep:
         lp_iters = max(2, min(iters, int(50e9 // (wl.seqlen * wl.tokens))))   # ~n^2 work: fewer launches when long
         lp_ms = time_ms(lambda: binding.la2_left_product_fwd(g["q"], g["k"], g["v"], g["lam"], out=g["o"]), lp_iters)
+        lpb_ms = time_ms(lambda: binding.la2_left_product_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"], out=g["grads"]),
+                         max(2, lp_iters // 3))
         f_ms = time_ms(lambda: fwd(g), iters)
+        b_ms = time_ms(lambda: bwd(g), iters)
         crossover.append({"workload": wl.name, "left_product_fwd_ms": round(lp_ms, 4),
-                          "block_recurrence_fwd_ms": round(f_ms, 4), "ratio": round(lp_ms / f_ms, 2)})
+                          "block_recurrence_fwd_ms": round(f_ms, 4), "ratio": round(lp_ms / f_ms, 2),
+                          "left_product_bwd_ms": round(lpb_ms, 4), "block_recurrence_bwd_ms": round(b_ms, 4),
+                          "bwd_ratio": round(lpb_ms / b_ms, 2)})
     del short
 
     # training step that keeps the forward's workspace for the backward (la2_bwd_saved): the sequence-chunked

@@ -276,11 +276,21 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
  * Comparison kernel, not part of the method: the same forward pass evaluated as the masked left product
  * O = [(Q K^T) * M] V over all earlier key blocks (Sec. 3.1 eq. (1) with the decay mask M of Sec. 3.2),
  * O(n^2 d) instead of O(n d^2), the way the predecessor of Algorithm 1 computes it.  For measuring where
- * the block recurrence overtakes it as n grows.  bf16 only (LA2_ERR_DTYPE otherwise); arguments as la2_fwd;
- * no workspace.
+ * the block recurrence overtakes it as n grows.  bf16 only (LA2_ERR_DTYPE otherwise), head_dim 64 or 128
+ * (LA2_ERR_SHAPE otherwise); arguments as la2_fwd; no workspace.
  */
 la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,
                                 const float* lambda, void* o, void* hip_stream);
+
+/*
+ * The backward pass of the same comparison: the gradients of Sec. 3.2.2 evaluated as masked products over all
+ * earlier (dq) or all later (dk, dv) positions, dQ = [(dO V^T) * M] K, dK = [(dO V^T) * M]^T Q,
+ * dV = [(Q K^T) * M]^T dO, O(n^2 d), three launches of the comparison kernel.  bf16 only, head_dim 64 or 128;
+ * arguments as la2_bwd; no workspace.
+ */
+la2_status la2_left_product_bwd(const la2_desc* desc, const void* q, const void* k, const void* v,
+                                const void* d_o, const float* lambda, void* dq, void* dk, void* dv,
+                                void* hip_stream);
 
 /*
  * ntokens consecutive decode steps in one launch (recursive form of Sec. 3.2.1): for t = 0 .. ntokens-1

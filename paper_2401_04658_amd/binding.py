@@ -87,6 +87,8 @@ def load():
     lib.la2_bwd_varlen.restype = ctypes.c_int
     lib.la2_left_product_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.la2_left_product_fwd.restype = ctypes.c_int
+    lib.la2_left_product_bwd.argtypes = [dp] + [vp] * 9
+    lib.la2_left_product_bwd.restype = ctypes.c_int
     lib.la2_decode_multi.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.la2_decode_multi.restype = ctypes.c_int
     lib.la2_decode_step.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -435,6 +437,23 @@ def la2_left_product_fwd(q, k, v, lam, out=None):
         _check(lib.la2_left_product_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), lam.data_ptr(),
                                         out.data_ptr(), _stream(q)))
     return out
+
+
+def la2_left_product_bwd(q, k, v, d_o, lam, out=None):
+    """(dq, dk, dv) as O(n^2 d) masked products (comparison kernel, bf16)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_left_product_bwd: tensors must live on the GPU")
+    _same_layout(q, k, v, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv)
+    desc = make_desc(q)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_left_product_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
+                                        lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _stream(q)))
+    return dq, dk, dv
 
 
 def la2_fwd_state_norm(q, k, v, lam, eps=1e-6, kv_init=None, want_final=True, out=None, rstd=None, kv_final=None,

@@ -699,8 +699,31 @@ la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void*
   Plan one{1, desc->seqlen, 0};
   la2::ScanParams p = base_params(desc, one, lambda, nullptr);
   p.x[0] = q; p.y[0] = k; p.z[0] = v; p.w[0] = o;
-  return la2::launch_left_product_bf16(desc->head_dim, p, reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess
+  return la2::launch_left_product_bf16(desc->head_dim, false, p, reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? LA2_OK : LA2_ERR_LAUNCH;
+}
+
+la2_status la2_left_product_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+                                const float* lambda, void* dq, void* dk, void* dv, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (desc->dtype != LA2_BF16) return LA2_ERR_DTYPE;
+  if (wide(desc->head_dim)) return LA2_ERR_SHAPE;   // comparison kernel: head_dim 64 and 128
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (!q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
+      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  Plan one{1, desc->seqlen, 0};
+  la2::ScanParams p = base_params(desc, one, lambda, nullptr);
+  // the three gradients of Sec. 3.2.2 as masked products over all earlier (dQ) or all later (dK, dV) positions
+  p.x[0] = d_o; p.y[0] = v; p.z[0] = k; p.w[0] = dq;       // dQ = [(dO V^T) * M] K
+  if (la2::launch_left_product_bf16(desc->head_dim, false, p, s) != hipSuccess) return LA2_ERR_LAUNCH;
+  p.x[0] = k; p.y[0] = q; p.z[0] = d_o; p.w[0] = dv;       // dV = [(Q K^T) * M]^T dO = [(K Q^T) * M^T] dO
+  if (la2::launch_left_product_bf16(desc->head_dim, true, p, s) != hipSuccess) return LA2_ERR_LAUNCH;
+  p.x[0] = v; p.y[0] = d_o; p.z[0] = q; p.w[0] = dk;       // dK = [(dO V^T) * M]^T Q = [(V dO^T) * M^T] Q
+  return la2::launch_left_product_bf16(desc->head_dim, true, p, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
 }
 
 }  // extern "C"

@@ -120,8 +120,9 @@ hipError_t launch_chunk_states_bf16(int dtype, int head_dim, bool reverse, const
 // 16-bit path of head_dim 96 and 256: the scan (one or two per launch, as above), or (state_only) the local
 // chunk states of its pre-pass; ragged ends are exact, so final states are meaningful for any n
 hipError_t launch_scan_wide(int dtype, int head_dim, bool reverse, bool state_only, const ScanParams& p, hipStream_t s);
-// O(n^2 d) left-product evaluation of the forward pass, for comparison (bf16; uses x, y, z, w of scan 0)
-hipError_t launch_left_product_bf16(int head_dim, const ScanParams& p, hipStream_t s);
+// O(n^2 d) left-product evaluation of one scan, for comparison (bf16; uses x, y, z, w of scan 0):
+// w = [(x y^T) * M] z over all earlier blocks, or with `reverse` the transposed mask over all later blocks
+hipError_t launch_left_product_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 // fp32 path
 hipError_t launch_scan_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);

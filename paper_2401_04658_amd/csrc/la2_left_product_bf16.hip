@@ -1,4 +1,4 @@
-// Left-product form of the forward pass, for comparison (bf16 MFMA, gfx950).
+// Left-product form of the forward and backward pass, for comparison (bf16 MFMA, gfx950).
 #include "la2_bf16_common.h"
 
 namespace la2 {
@@ -9,10 +9,14 @@ using bf16x4 = ex4<__bf16>;
 
 // Left-product form for comparison: O = [(Q K^T) * M] V computed tile by tile over ALL earlier key blocks
 // (the O(n^2 d) evaluation that the block recurrence replaces; Sec. 3.1 eq. (1) with the decay mask of
-// Sec. 3.2).  Forward only, bf16.  One workgroup per (chain, 128 query rows); wave w owns query rows
+// Sec. 3.2).  bf16.  One workgroup per (chain, 128 query rows); wave w owns query rows
 // 32 w .. 32 w + 31 and all value features; the key and value blocks (64 positions) stream through LDS,
 // double buffered.  Same MFMA operand layouts, LDS tile layout and mask tables as the scan kernels.
-template <int D>
+// As with the scan kernels this is one generic operation on (x, y, z): forward W = [(X Y^T) * M] Z (O from
+// (Q, K, V); dQ from (dO, V, K)), and with REV the transposed mask, W = [(X Y^T) * M^T] Z over all LATER
+// blocks of y and z (dV from (K, Q, dO), dK from (V, dO, Q): the gradients of Sec. 3.2.2 as plain masked
+// products).
+template <int D, bool REV>
 __global__ __launch_bounds__(kThreads, 1) void left_product_bf16_kernel(ScanParams p) {
   using C = Cfg<D>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
@@ -23,7 +27,8 @@ __global__ __launch_bounds__(kThreads, 1) void left_product_bf16_kernel(ScanPara
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int nqb = (p.n + QB - 1) / QB;
   const int chain = blockIdx.x / nqb;
-  const int qb = nqb - 1 - (int)(blockIdx.x % nqb);   // long rows of the triangle first
+  // long rows of the triangle first: the last query block looks back furthest, with REV the first looks ahead furthest
+  const int qb = REV ? (int)(blockIdx.x % nqb) : nqb - 1 - (int)(blockIdx.x % nqb);
   const int bi = chain / p.heads, hi = chain % p.heads;
   const int64_t base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
   const int n = p.n;
@@ -51,7 +56,7 @@ __global__ __launch_bounds__(kThreads, 1) void left_product_bf16_kernel(ScanPara
 #pragma unroll
   for (int v = 0; v < 16; v++) {
     const int cc = 8 * (v >> 2) + 4 * hh + (v & 3);
-    const int e = l32 - cc;
+    const int e = REV ? cc - l32 : l32 - cc;
     dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
     od[v] = exp2f(l2 * (float)(e + 32));
   }
@@ -65,23 +70,25 @@ __global__ __launch_bounds__(kThreads, 1) void left_product_bf16_kernel(ScanPara
 #pragma unroll
   for (int t = 0; t < NT; t++) acc[t] = zero16();
 
-  // key blocks 0 .. jmax reach this query block
+  // key blocks jmin .. jmax reach this query block: all earlier ones and its own, or (REV) its own and all later
   const int nkb = (n + kB - 1) / kB;
-  const int jmax = min((qb * QB + QB - 1) / kB, nkb - 1);
-  loader.issue(sT[0], 0);
+  const int jmin = REV ? (qb * QB) / kB : 0;
+  const int jmax = REV ? nkb - 1 : min((qb * QB + QB - 1) / kB, nkb - 1);
+  loader.issue(sT[0], jmin);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-  loader.zero_tail(sT[0], 0);
+  loader.zero_tail(sT[0], jmin);
   __syncthreads();
-  for (int j = 0; j <= jmax; j++) {
-    const int cur = j & 1;
+  for (int j = jmin; j <= jmax; j++) {
+    const int cur = (j - jmin) & 1;
     if (j < jmax) loader.issue(sT[cur ^ 1], j + 1);
     const __bf16* tK = sT[cur][0];
     const __bf16* tV = sT[cur][1];
 #pragma unroll
     for (int kt = 0; kt < 2; kt++) {
       // distance between this wave's first query row and the key tile's first row: a multiple of 32
-      const int dist = qb * QB + 32 * w - (j * kB + 32 * kt);
-      if (dist < 0) continue;   // wave-uniform: the whole tile is above the diagonal
+      const int ahead = qb * QB + 32 * w - (j * kB + 32 * kt);
+      const int dist = REV ? -ahead : ahead;
+      if (dist < 0) continue;   // wave-uniform: the whole tile is on the masked side of the diagonal
       f32x16 st = zero16();
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) st = mfma(la.read_row(tK, kt, ks), xf[ks], st);
@@ -130,12 +137,17 @@ __global__ __launch_bounds__(kThreads, 1) void left_product_bf16_kernel(ScanPara
 
 }  // namespace
 
-hipError_t launch_left_product_bf16(int head_dim, const ScanParams& p, hipStream_t s) {
+hipError_t launch_left_product_bf16(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * ((p.n + 127) / 128);
   if (grid == 0 || p.n == 0) return hipSuccess;
   dim3 g((unsigned)grid), b(kThreads);
-  if (head_dim == 128) hipLaunchKernelGGL((left_product_bf16_kernel<128>), g, b, 0, s, p);
-  else                 hipLaunchKernelGGL((left_product_bf16_kernel<64>), g, b, 0, s, p);
+  if (head_dim == 128) {
+    if (reverse) hipLaunchKernelGGL((left_product_bf16_kernel<128, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((left_product_bf16_kernel<128, false>), g, b, 0, s, p);
+  } else {
+    if (reverse) hipLaunchKernelGGL((left_product_bf16_kernel<64, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((left_product_bf16_kernel<64, false>), g, b, 0, s, p);
+  }
   return hipGetLastError();
 }
 

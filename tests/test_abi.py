@@ -279,6 +279,13 @@ def test_fp16_is_accepted_except_by_the_comparison_kernel(lib):
     d = dense(lib, 300, 2, 128, 128, binding.LA2_F16)
     assert lib.la2_block_size(ctypes.byref(d)) == 32
     assert lib.la2_left_product_fwd(ctypes.byref(d), P, P, P, P, P, None) == E_DTYPE
+    assert lib.la2_left_product_bwd(ctypes.byref(d), P, P, P, P, P, P, P, P, None) == E_DTYPE
+    db = dense(lib, 2, 2, 128, 128, binding.LA2_BF16)
+    assert lib.la2_left_product_bwd(ctypes.byref(db), P, P, P, None, P, P, P, P, None) == E_NULL
+    assert lib.la2_left_product_bwd(ctypes.byref(db), P, P, P, P, P, P, P + 8, P, None) == E_ALIGN
+    db.head_dim = 96
+    db.stride_n = 96
+    assert lib.la2_left_product_bwd(ctypes.byref(db), P, P, P, P, P, P, P, P, None) == E_SHAPE
     assert lib.la2_decode_step(0, 1, 64, binding.LA2_F16, None, None, None, None, None, None, None) == OK
 
 

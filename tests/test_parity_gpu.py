@@ -496,3 +496,40 @@ def test_left_product_kernel_config2_and_extreme_decays():
     with pytest.raises(binding.LA2Error):
         f = gpu(make_inputs(1, 1, 64, 64, torch.float32, seed=1))
         binding.la2_left_product_fwd(f["q"], f["k"], f["v"], f["lam"])
+
+
+# ---- ... and its backward form the same gradients ------------------------------------------------------------------
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n", [1, 31, 64, 128, 129, 200, 517, 1000])
+def test_left_product_backward_small_shapes(d, n):
+    t = make_inputs(2, 3, n, d, torch.bfloat16, seed=450 + n + d, lam=[0.5, 0.93, 1.0])
+    g = gpu(t)
+    dq, dk, dv = binding.la2_left_product_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
+    torch.cuda.synchronize()
+    refs = oracle.bwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["d_o"]), to64(t["lam"]))
+    for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+        assert_close("left product %s n%d d%d" % (name, n, d), got, ref, torch.bfloat16)
+
+
+def test_left_product_backward_config2_and_extreme_decays():
+    for t in (workloads.CONFIG2.tensors(), make_inputs(1, 3, 300, 128, torch.bfloat16, seed=25, lam=[1.0, 1e-6, 0.43])):
+        g = gpu(t)
+        got = binding.la2_left_product_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"])
+        torch.cuda.synchronize()
+        refs = oracle.bwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["d_o"]), to64(t["lam"]))
+        for name, x, ref in zip(("dq", "dk", "dv"), got, refs):
+            assert_close("left product bwd " + name, x, ref, torch.bfloat16)
+    # strided layout ([b, n, H, d] storage)
+    t = make_inputs(2, 3, 333, 128, torch.bfloat16, seed=26)
+    g = {}
+    for name in ("q", "k", "v", "d_o"):
+        g[name] = t[name].permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    lam = t["lam"].to(DEV)
+    got = binding.la2_left_product_bwd(g["q"], g["k"], g["v"], g["d_o"], lam)
+    torch.cuda.synchronize()
+    refs = oracle.bwd_direct(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["d_o"]), to64(t["lam"]))
+    for name, x, ref in zip(("dq", "dk", "dv"), got, refs):
+        assert_close("left product bwd strided " + name, x, ref, torch.bfloat16)
+    with pytest.raises(binding.LA2Error):
+        f = gpu(make_inputs(1, 1, 64, 64, torch.float16, seed=1))
+        binding.la2_left_product_bwd(f["q"], f["k"], f["v"], f["d_o"], f["lam"])
