@@ -155,10 +155,10 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
  * la2_bwd_state needs the kv_init the forward pass was given (dq depends on it).  All other arguments
  * as for la2_fwd / la2_bwd, which are these functions with NULL states.  State pointers are 16-byte
  * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen:
- * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (64 for 16-bit data with head_dim
- * 64; head_dim 96 and 256 have no such granule), the last seqlen % G positions run in a short-run kernel (the
- * scan kernels of head_dim 64 and 128 form states after whole blocks only).  seqlen == 0 copies the state through (kv_final = kv_init, d_kv_init = d_kv_final; zero if
- * the input is NULL).
+ * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (head_dim 96 and 256 have no such
+ * granule), the last seqlen % G positions run in a short-run kernel (the scan kernels of head_dim 64 and 128
+ * form states after whole blocks only).  seqlen == 0 copies the state through (kv_final = kv_init,
+ * d_kv_init = d_kv_final; zero if the input is NULL).
  */
 la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
                          const float* lambda, const float* kv_init, void* o, float* kv_final,
@@ -327,14 +327,16 @@ int32_t la2_block_size(const la2_desc* desc);
 void la2_set_chunk_tokens(int32_t tokens);
 
 /*
- * Test / tuning knob: which bf16 head_dim-128 scan kernel la2_fwd / la2_bwd launch.
+ * Test / tuning knob: which 16-bit scan kernel la2_fwd / la2_bwd launch at head_dim 64 and 128.
  *   0  automatic (currently the half-block kernel: blocks of 32 positions, up to two workgroups per
  *      compute unit; it measured faster than the full-block kernel at every launch size)
  *   1  the full-block kernel (blocks of 64 positions, one workgroup per compute unit)
  *   2  the half-block kernel
  * Other values are taken as 0.  Both kernels implement Algorithm 1's block recurrence (the block
  * size is the algorithm's free parameter B); results differ by rounding only.  Process-global, as
- * la2_set_chunk_tokens.  Ignored for fp32 and for head_dim 64.
+ * la2_set_chunk_tokens.  Ignored for fp32, for head_dim 96 / 256, and by calls that carry states or the Norm
+ * epilogue (only the half-block kernel has those).  With 1 the backward pass of a sequence-chunked problem forms
+ * the chunk states of its second loop in a pass of its own instead of inside the first loop's launch.
  */
 void la2_set_scan_variant(int32_t variant);
 

@@ -19,15 +19,14 @@ namespace {
 std::atomic<int> g_chunk_tokens_override{0};  // la2_set_chunk_tokens()
 std::atomic<int> g_scan_variant{0};           // la2_set_scan_variant()
 // The block kernels form states after whole blocks only: 32 positions for the kernels that take states
-// (half-block 16-bit kernel for head_dim 128, fp32 kernels), 64 for the full-block 16-bit kernel of head_dim 64.
+// (half-block 16-bit kernel of head_dim 64 and 128, fp32 kernels).
 bool is16(int dtype) { return dtype == LA2_BF16 || dtype == LA2_F16; }
 // Head dimensions 96 and 256 have kernels of their own: one 16-bit block kernel that is exact at a ragged end
 // (no granule), and the token recurrence for fp32.
 bool wide(int head_dim) { return head_dim == 96 || head_dim == 256; }
 bool supported_head_dim(int head_dim) { return head_dim == 64 || head_dim == 128 || wide(head_dim); }
 int state_granule(const la2_desc* d) {
-  if (wide(d->head_dim)) return 1;
-  return (is16(d->dtype) && d->head_dim == 64) ? 64 : 32;
+  return wide(d->head_dim) ? 1 : 32;
 }
 
 int device_cu_count() {
@@ -275,10 +274,10 @@ la2_desc whole_blocks(const la2_desc* d) {
   return w;
 }
 
-// Algorithm 2 on a sequence-chunked problem, 16-bit data, head_dim 128: the dQ scan's launch also forms the local
-// dKV states of the chunks (its second wave group), so the backward pass keeps two sets of chunk states.
+// Algorithm 2 on a sequence-chunked problem, 16-bit data, head_dim 64 / 128: the dQ scan's launch also forms the
+// local dKV states of the chunks (its second wave group), so the backward pass keeps two sets of chunk states.
 bool fuses_reverse_states(const la2_desc* d) {
-  return is16(d->dtype) && d->head_dim == 128 && g_scan_variant.load(std::memory_order_relaxed) != 1;
+  return is16(d->dtype) && !wide(d->head_dim) && g_scan_variant.load(std::memory_order_relaxed) != 1;
 }
 
 StateWorkspace state_workspace(const la2_desc* d, bool backward) {
@@ -351,8 +350,8 @@ la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk
 
 int32_t la2_block_size(const la2_desc* desc) {
   if (check_desc(desc) != LA2_OK) return 0;
-  // 16-bit, head_dim 128: the half-block scan kernel unless the full-block one is forced
-  if (is16(desc->dtype) && desc->head_dim == 128 && g_scan_variant.load(std::memory_order_relaxed) != 1) return 32;
+  // 16-bit, head_dim 64 / 128: the half-block scan kernel unless the full-block one is forced
+  if (is16(desc->dtype) && !wide(desc->head_dim) && g_scan_variant.load(std::memory_order_relaxed) != 1) return 32;
   if (wide(desc->head_dim)) return is16(desc->dtype) ? 32 : 1;
   return block_size(desc);
 }
@@ -523,7 +522,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
       for_dq.saved_tr = true;
     }
   }
-  // Sequence chunks, 16-bit data, head_dim 128: the dQ scan's launch also forms the local dKV states of the
+  // Sequence chunks, 16-bit data, head_dim 64 / 128: the dQ scan's launch also forms the local dKV states of the
   // chunks (from dO, which it streams anyway, and Q), so the second loop needs no pass of its own over Q and dO
   // before it can start its chunks.  Those states live behind the dQ scan's own chunk states in the workspace
   // (or at its start when the dQ scan reads the forward call's).  Not when the reverse scans run on the whole

@@ -323,7 +323,7 @@ struct UpdateDecay {
 
 // per-kernel launchers (one translation unit each); launch_scan_bf16 picks among the first two
 hipError_t launch_scan_bf16_full(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
-hipError_t launch_scan_bf16_half(int dtype, bool reverse, bool twin, const ScanParams& p, hipStream_t s);
+hipError_t launch_scan_bf16_half(int dtype, int head_dim, bool reverse, bool twin, const ScanParams& p, hipStream_t s);
 
 }  // namespace la2
 #endif

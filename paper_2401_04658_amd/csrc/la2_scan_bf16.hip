@@ -471,13 +471,14 @@ hipError_t launch_scan_bf16_full(int dtype, int head_dim, bool reverse, const Sc
 hipError_t launch_scan_bf16(int dtype, int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   if (grid == 0 || p.n == 0) return hipSuccess;
-  // the half-block kernel measured faster at every launch size, also at one workgroup per compute unit;
-  // it is also the only d = 128 kernel that takes start states and hands out final states
+  // the half-block kernel measured faster at every launch size, also at one workgroup per compute unit; it is
+  // also the only one that takes start states, hands out final states, has the Norm epilogue at both head
+  // dimensions and can form the reverse chunk states on the side
   const bool with_state = p.init[0] || p.init[1] || p.fin[0] || p.fin[1];
-  const bool half = p.variant != 1 || with_state || p.rstd != nullptr;   // also the one with the Norm epilogue
-  if (head_dim == 128 && half && p.chunk_tokens % 32 == 0) {
+  const bool half = p.variant != 1 || with_state || p.rstd != nullptr || p.acc_states != nullptr;
+  if (half && p.chunk_tokens % 32 == 0) {
     const bool twin = p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0];
-    return launch_scan_bf16_half(dtype, reverse, twin, p, s);
+    return launch_scan_bf16_half(dtype, head_dim, reverse, twin, p, s);
   }
   return launch_scan_bf16_full(dtype, head_dim, reverse, p, s);
 }

@@ -1,14 +1,14 @@
-// Half-block bf16 scan kernel for head_dim 128 (B = 32 positions, two workgroups per compute unit) and its
-// twin form (both reverse scans of the backward pass in one workgroup), gfx950.  Layout notes:
-// la2_bf16_common.h.
+// Half-block 16-bit scan kernel for head_dim 128 and 64 (B = 32 positions, two waves per SIMD) and its twin
+// form (both reverse scans of the backward pass in one workgroup), gfx950.  Layout notes: la2_bf16_common.h.
 #include "la2_bf16_common.h"
 
 namespace la2 {
 namespace {
 using namespace bf16k;
 
-// Half-block variant for d = 128: blocks of 32 positions, 80 KiB of LDS and at most 256 registers, so
-// that TWO workgroups share a compute unit (two waves per SIMD).  One wave alone issues its
+// Blocks of 32 positions, one wave per 32 value features (D / 32 waves per scan: 4 for d = 128, 2 for d = 64),
+// at most 256 registers and 80 KiB (d = 128) or 38 KiB (d = 64) of LDS, so that TWO (d = 128) or FOUR (d = 64)
+// workgroups share a compute unit: two waves per SIMD.  One wave alone issues its
 // instructions one after the other (an MFMA holds the issue port for about half its run time, a
 // 16-byte-per-lane memory instruction for about 60 cycles), so a single wave per SIMD leaves the
 // matrix pipe idle most of the time; a second, independent wave fills those gaps.  Used when a launch
@@ -16,8 +16,8 @@ using namespace bf16k;
 // single (diagonal) 32 x 32 score tile per block; wave w owns value features 32 w .. 32 w + 31.
 constexpr int kBH = 32;
 //
-// TWIN: both scans of a dual launch in ONE workgroup of 8 waves (waves 0-3 scan 0, waves 4-7 scan 1;
-// again two waves per SIMD).  The dual launch is Algorithm 2's second loop, whose two scans read the
+// TWIN: both scans of a dual launch in ONE workgroup of two wave groups (d = 128: waves 0-3 scan 0, waves 4-7
+// scan 1; d = 64: waves 0-1 and 2-3; again two waves per SIMD).  The dual launch is Algorithm 2's second loop, whose two scans read the
 // same two tensors with the roles of Y and Z exchanged (dV: y = Q, z = dO; dK: y = dO, z = Q), so the
 // workgroup streams FOUR tiles per block (x of scan 0, x of scan 1, Q, dO) instead of six and every
 // tile is fetched exactly once.  Requires y[1] == z[0] and z[1] == y[0].
@@ -30,35 +30,38 @@ constexpr int kBH = 32;
 // product for this), scale the finished tile and wave 0 stores r.  The LDS is full, so this variant has no
 // staging buffer of its own: it stages each wave's output in the block's X tile, which is dead by then.
 //
-// ACC: a forward scan whose workgroup has a second group of four waves (8 waves, one workgroup per compute
-// unit, FOUR tiles per block: X, Y, Z and p.acc_y).  Waves 0-3 run the scan as usual; waves 4-7 accumulate
+// ACC: a forward scan whose workgroup has a second group of waves (as many again; FOUR tiles per block: X, Y,
+// Z and p.acc_y).  The first group runs the scan as usual; the second accumulates
 // the reverse local state of the chunk for ANOTHER pair of scans, sum_c lambda^(c+1) acc_y_c^T x_c (c counted
 // from the chunk's first position), and leave it in p.acc_states.  Algorithm 2: the dQ scan (x = dO) with
 // acc_y = Q leaves the local dKV states of the sequence chunks, so the dK / dV scan needs no pass of its own
 // over Q and dO to form them.
-template <typename E, bool REV, bool TWIN, int NBUF, bool NORM = false, bool ACC = false>
-__global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) void scan_bf16_half_kernel(ScanParams p) {
+template <typename E, int D, bool REV, bool TWIN, int NBUF, bool NORM = false, bool ACC = false>
+__global__ __launch_bounds__(((TWIN || ACC) ? 4 : 2) * D, ((TWIN || ACC) ? 1 : 2) * (128 / D))
+void scan_bf16_half_kernel(ScanParams p) {
+  static_assert(D == 128 || D == 64, "head_dim");
   static_assert(!NORM || (!REV && !TWIN), "the Norm epilogue belongs to the forward pass");
   static_assert(!ACC || (!REV && !TWIN && !NORM), "the accumulating wave group rides on a plain forward scan");
-  constexpr int D = 128, B = kBH;
+  constexpr int B = kBH;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
-  constexpr int NW = (TWIN || ACC) ? 8 : 4;    // waves
-  constexpr int NTL = (TWIN || ACC) ? 4 : 3;   // tiles per block
+  constexpr int SW = NT;                              // waves of one scan: one per tile of 32 value features
+  constexpr int NW = (TWIN || ACC) ? 2 * SW : SW;     // waves
+  constexpr int NTL = (TWIN || ACC) ? 4 : 3;          // tiles per block
   using Loader = TileLoader<D, NTL, B, NW>;
   __shared__ __attribute__((aligned(1024))) E sT[NBUF][NTL][TILE];
   // Output staging, 32 positions x 32 features per wave.  The NORM variant has no LDS left for it beside its
   // exchange buffer (two workgroups of 80 KiB per compute unit) and stages in the block's own X tile instead,
   // which is dead by then: see the epilogue.
-  __shared__ __attribute__((aligned(16))) E sW[ACC ? 4 : NW][NORM ? LW : 32 * LW];
-  float* const sRed = NormExchange<NORM ? 2 * 32 * 4 : 0>::get();   // [block parity][position][wave]
+  __shared__ __attribute__((aligned(16))) E sW[ACC ? SW : NW][NORM ? LW : 32 * LW];
+  float* const sRed = NormExchange<NORM ? 2 * 32 * SW : 0>::get();   // [block parity][position][wave]
   // Cache policy of the output stores (buffer instruction bits: 2 = nt, 16 = sc1).  Measured: the twin
   // workgroup, a third of whose traffic is stores, runs 9-13 % faster with streaming write-through stores;
   // the plain kernel is 8 % slower with any non-temporal store policy and keeps the default.
   constexpr int kStorePolicy = TWIN ? 18 : 0;
   constexpr int NDMA = NTL * Loader::DMA_PER_WAVE;   // direct loads per wave and block
   constexpr int NST = 32 * 4 / 64 + (NORM ? 1 : 0);   // stores per lane and block: 16-byte output stores, r
-  static_assert(NDMA <= KS, "one direct load per slot of phase 1");
+  constexpr int DMA_PER_SLOT = (NDMA + KS - 1) / KS;   // direct loads issued in each slot of phase 1
   // vector-memory operations of this wave that are younger than the direct loads of block it + 1 when block
   // it waits for them: the loads of blocks it + 2 .. it + NBUF - 1 and as many blocks' stores
   constexpr int VM_YOUNGER = (NBUF - 2) * (NST + NDMA);
@@ -66,9 +69,9 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
   constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
-  const int dvt = w & 3;
+  const int dvt = w % SW;
   int which = 0, wg = (int)blockIdx.x;
-  const int group = __builtin_amdgcn_readfirstlane(w >> 2);   // TWIN: which scan; ACC: scan waves or accumulating waves
+  const int group = __builtin_amdgcn_readfirstlane(w / SW);   // TWIN: which scan; ACC: scan waves or accumulating waves
   if (TWIN) {
     which = group;
   } else if (ACC) {
@@ -298,7 +301,9 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
       sd = mfma(ya[ks], xa[ks], sd);
       if (ks + AHEAD < KS) read_xy(ks + AHEAD);
       if (ks + 1 < KS) { sa = state_operand(ks + 1); pin(sa); }
-      if (ks < NDMA) loader.issue_one(sAhead, doff, ks);
+#pragma unroll
+      for (int u = 0; u < DMA_PER_SLOT; u++)
+        if (ks * DMA_PER_SLOT + u < NDMA) loader.issue_one(sAhead, doff, ks * DMA_PER_SLOT + u);
       if (ks < 2) zf[ks] = la.read_cols(tZ, 16 * ks, dvt);
       if (ks >= 2 && (ks & 1) == 0) {   // state tile ks / 2 - 1: both operands made in slots <= ks - 1
         const int t = (ks >> 1) - 1;
@@ -306,8 +311,9 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
         for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
         pin(kv[t]);
       }
-      if (ks == 3 || ks == 5) {
-        const int q = (ks - 3) >> 1;
+      // the update weights on the Z fragments, two slots after their LDS reads (d = 64: in the last two slots)
+      if ((KS == 8 && (ks == 3 || ks == 5)) || (KS == 4 && (ks == 2 || ks == 3))) {
+        const int q = KS == 8 ? (ks - 3) >> 1 : ks - 2;
         zd[q] = decay.apply(zf[q], 16 * q);
         pin(zd[q]);
       }
@@ -327,14 +333,20 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
     }
     // ---- phase 3
     ex8<E> pd[2];
+    constexpr int NH = NT / 2;          // pairs of key-feature tiles
+    constexpr int NS3 = 2 * NH;         // slots of this phase
+    constexpr int PPS = 16 / NS3;       // elements of the masked score tile converted per slot
 #pragma unroll
-    for (int s4 = 0; s4 < 4; s4++) {   // slot s4: k-step q = s4 / 2, key-feature tiles 2 h, 2 h + 1, h = s4 % 2
-      const int q = s4 >> 1, h = s4 & 1;
+    for (int s4 = 0; s4 < NS3; s4++) {   // slot s4: k-step q = s4 / NH, key-feature tiles 2 h, 2 h + 1, h = s4 % NH
+      const int q = s4 / NH, h = s4 % NH;
 #pragma unroll
       for (int t = 2 * h; t < 2 * h + 2; t++) kv[t] = mfma(yt[q][t], zd[q], kv[t]);
-      if (s4 + 1 < 4) read_yt((s4 + 1) >> 1, (s4 + 1) & 1);
+      if (s4 + 1 < NS3) read_yt((s4 + 1) / NH, (s4 + 1) % NH);
 #pragma unroll
-      for (int e = 0; e < 4; e++) pd[q][4 * h + e] = (E)(sd[8 * q + 4 * h + e] * dg[8 * q + 4 * h + e]);
+      for (int e = 0; e < PPS; e++) {
+        const int v = PPS * s4 + e;     // element v of the score tile belongs to the P fragment of k-step v / 8
+        pd[v >> 3][v & 7] = (E)(sd[v] * dg[v]);
+      }
       pin(pd[q]);
 #pragma unroll
       for (int t = 2 * h; t < 2 * h + 2; t++) pin(kv[t]);
@@ -365,8 +377,8 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
       // Two exchange buffers, by block parity: a wave that runs ahead into the next block must not
       // overwrite sums that a slower wave has yet to read.  The barrier is the block's only one: it also
       // makes the next block's tiles visible and frees this block's.
-      float* const red = sRed + (it & 1) * (32 * 4);
-      norm_publish<4>(inter, red, l32, hh, dvt);
+      float* const red = sRed + (it & 1) * (32 * SW);
+      norm_publish<SW>(inter, red, l32, hh, dvt);
       lds_barrier();
       if (has_next) {
 #pragma unroll
@@ -375,7 +387,7 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
           ya[ks] = la.read_row(sNext[yi], 0, ks);
         }
       }
-      const float r = norm_collect<4>(red, l32, 1.f / (float)D, p.eps);
+      const float r = norm_collect<SW>(red, l32, 1.f / (float)D, p.eps);
 #pragma unroll
       for (int v = 0; v < 16; v++) inter[v] *= r;
       pin(inter);
@@ -386,7 +398,7 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
     // Staging area of this wave.  NORM: the quarter of this block's X tile that this wave's own direct loads
     // fill.  Every wave is past the block's last tile read (the barrier above), and the next writer of that
     // quarter is this wave's own direct load two blocks on, issued after the reads below have returned.
-    E* const st = NORM ? const_cast<E*>(tX) + w * (TILE / 4) : stage;
+    E* const st = NORM ? const_cast<E*>(tX) + w * (TILE / SW) : stage;
 #pragma unroll
     for (int g = 0; g < 4; g++) {
       ex4<E> pk;
@@ -432,30 +444,33 @@ __global__ __launch_bounds__((TWIN || ACC) ? 512 : 256, (TWIN || ACC) ? 1 : 2) v
 }  // namespace
 
 namespace {
-template <typename E>
+template <typename E, int D>
 hipError_t launch_half(bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
   const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
   // Three tile buffers in every case.  More buffers (5 for a plain, 4 for a twin workgroup that has the
   // compute unit to itself) measured no faster: such launches are bound by the memory system, not by the
   // bytes a workgroup keeps in flight.
+  constexpr int kPlain = 2 * D, kDouble = 4 * D;   // threads: one wave per 32 value features, or two such groups
   if (twin) {
-    dim3 gt((unsigned)(grid / 2)), bt(512);
-    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, true, true, 3>), gt, bt, 0, s, p);
-    else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, true, 3>), gt, bt, 0, s, p);
+    dim3 gt((unsigned)(grid / 2)), bt(kDouble);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, true, true, 3>), gt, bt, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, true, 3>), gt, bt, 0, s, p);
   } else {
-    dim3 g((unsigned)grid), b(kThreads);
-    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, true, false, 3>), g, b, 0, s, p);
+    dim3 g((unsigned)grid), b(kPlain);
+    if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, true, false, 3>), g, b, 0, s, p);
     else if (p.acc_states != nullptr)
-      hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3, false, true>), g, dim3(512), 0, s, p);
-    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3, true>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, false, false, 3>), g, b, 0, s, p);
+      hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, false, 3, false, true>), g, dim3(kDouble), 0, s, p);
+    else if (p.rstd != nullptr) hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, false, 3, true>), g, b, 0, s, p);
+    else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, false, 3>), g, b, 0, s, p);
   }
   return hipGetLastError();
 }
 }  // namespace
 
-hipError_t launch_scan_bf16_half(int dtype, bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
-  return dtype == kF16 ? launch_half<_Float16>(reverse, twin, p, s) : launch_half<__bf16>(reverse, twin, p, s);
+hipError_t launch_scan_bf16_half(int dtype, int head_dim, bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
+  if (head_dim == 64)
+    return dtype == kF16 ? launch_half<_Float16, 64>(reverse, twin, p, s) : launch_half<__bf16, 64>(reverse, twin, p, s);
+  return dtype == kF16 ? launch_half<_Float16, 128>(reverse, twin, p, s) : launch_half<__bf16, 128>(reverse, twin, p, s);
 }
 
 }  // namespace la2

@@ -9,7 +9,7 @@ int main(void) {
   la2_desc d;
   la2_desc_dense(&d, 2, 3, 100, 64, LA2_BF16);
   if (d.stride_n != 64 || d.stride_h != 6400 || d.stride_b != 19200) return 1;
-  if (la2_block_size(&d) != 64) return 2;
+  if (la2_block_size(&d) != 32) return 2;
   if (la2_fwd(&d, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_ERR_NULL) return 3;
   d.head_dim = 100;
   if (la2_fwd(&d, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_ERR_SHAPE) return 4;

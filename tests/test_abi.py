@@ -121,8 +121,8 @@ def test_workspace_rules(lib):
         assert need == 2 * 4 * 128 * 128 * 4  # chains x chunks x d x d fp32
         # backward, 16-bit head_dim 128: the dQ scan's chunk states and the dK / dV scan's, side by side
         assert lib.la2_workspace_bytes(ctypes.byref(d), 1) == 2 * need
-        d64 = dense(lib, 1, 2, 1024, 64, binding.LA2_BF16)
-        assert lib.la2_workspace_bytes(ctypes.byref(d64), 1) == lib.la2_workspace_bytes(ctypes.byref(d64), 0) > 0
+        d32 = dense(lib, 1, 2, 1024, 128, binding.LA2_F32)
+        assert lib.la2_workspace_bytes(ctypes.byref(d32), 1) == lib.la2_workspace_bytes(ctypes.byref(d32), 0) > 0
         assert lib.la2_workspace_bytes(ctypes.byref(d), 9) == 0
         assert fwd(lib, d) == E_WS
         assert fwd(lib, d, ws=P, ws_bytes=need - 1) == E_WS
@@ -275,7 +275,7 @@ def test_fp16_is_accepted_except_by_the_comparison_kernel(lib):
     assert fwd(lib, d) == OK and bwd(lib, d) == OK
     d = dense(lib, 300, 2, 128, 64, binding.LA2_F16)
     assert fwd(lib, d, q=None) == E_NULL and fwd(lib, d, o=P + 8) == E_ALIGN
-    assert lib.la2_block_size(ctypes.byref(d)) == 64
+    assert lib.la2_block_size(ctypes.byref(d)) == 32
     d = dense(lib, 300, 2, 128, 128, binding.LA2_F16)
     assert lib.la2_block_size(ctypes.byref(d)) == 32
     assert lib.la2_left_product_fwd(ctypes.byref(d), P, P, P, P, P, None) == E_DTYPE

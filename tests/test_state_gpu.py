@@ -266,13 +266,14 @@ def test_backward_after_a_forward_that_wrote_kv_final_at_a_ragged_length(d, n, c
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("n,chunk", [(1024, 256), (1000, 128), (777, 64), (4096, 512)])
-def test_dq_launch_forms_the_reverse_chunk_states(dtype, n, chunk):
-    """Sequence chunks at head_dim 128: the dQ scan's launch also accumulates the local dKV states of the chunks
+def test_dq_launch_forms_the_reverse_chunk_states(dtype, d, n, chunk):
+    """Sequence chunks at head_dim 64 / 128: the dQ scan's launch also accumulates the local dKV states of the chunks
     (second wave group), the dK / dV scan starts from them.  Against the oracle, with start state and incoming
     state gradient, whole and ragged lengths, single-block chunks (64) included; and against the path that does
     not fuse (full-block kernel forced: separate pre-pass over Q and dO)."""
-    t = inputs(2, 3, n, 128, dtype, seed=1500 + n, lam=[0.37, 0.9, 0.999])
+    t = inputs(2, 3, n, d, dtype, seed=1500 + n + d, lam=[0.37, 0.9, 0.999])
     g = {k: v.to(DEV) for k, v in t.items()}
     binding.la2_set_chunk_tokens(chunk)
     assert binding.la2_chunk_plan(g["q"])[0] > 1
@@ -287,7 +288,7 @@ def test_dq_launch_forms_the_reverse_chunk_states(dtype, n, chunk):
     q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
     rdq, rdk, rdv, rg0 = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=to64(t["kv_init"]),
                                                     d_kv_final=to64(t["d_kv_final"]) if use_final else None)
-    tag = "fused reverse states %s n%d chunk%d" % (dtype, n, chunk)
+    tag = "fused reverse states %s d%d n%d chunk%d" % (dtype, d, n, chunk)
     for name, got, other, ref in (("dq", dq, uq, rdq), ("dk", dk, uk, rdk), ("dv", dv, uv, rdv), ("d_kv_init", g0, u0, rg0)):
         assert_close(tag + " " + name, got, ref, dtype)
         assert_close(tag + " unfused " + name, other, ref, dtype)
