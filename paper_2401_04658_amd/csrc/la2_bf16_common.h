@@ -47,6 +47,7 @@ namespace bf16k {
 template <typename E> using ex8 = E __attribute__((ext_vector_type(8)));
 template <typename E> using ex4 = E __attribute__((ext_vector_type(4)));
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;

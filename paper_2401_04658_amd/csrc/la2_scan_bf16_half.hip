@@ -137,6 +137,12 @@ void scan_bf16_half_kernel(ScanParams p) {
       // chunk's first position: its contribution carries lambda^(B it) up front, the sum needs no running decay.
       constexpr int ACC_YOUNGER = (NBUF - 2) * NDMA;   // no stores in this wave group
       constexpr int ACC_WAIT = (ACC_YOUNGER & 15) | ((ACC_YOUNGER >> 4) << 14) | 0x0F70;
+      // the scan waves may first stage transposed start states in the tile buffers (below): join their barriers
+      // before the first tile load
+      if ((p.state_transposed | p.init_transposed) != 0) {
+#pragma unroll 1
+        for (int gsel = 0; gsel < NW / SW; gsel++) __syncthreads();
+      }
       const UpdateDecay<true, B> adecay(l2, hh);
       f32x16 acc[NT];
 #pragma unroll
@@ -208,14 +214,44 @@ void scan_bf16_half_kernel(ScanParams p) {
     gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
     tr = (p.init_transposed >> which) & 1;
   }
-  if (gs != nullptr) {
+  if (gs != nullptr && !tr) {
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) kv[t][v] = gs[state_index<D>(dvt, l32, hh, t, v, tr)];
-  } else {
+      for (int v = 0; v < 16; v++) kv[t][v] = gs[state_index<D>(dvt, l32, hh, t, v, false)];
+  } else if (gs == nullptr) {
 #pragma unroll
     for (int t = 0; t < NT; t++) kv[t] = zero16();
+  }
+  // A state stored transposed: this wave's slice is then the 32 ROWS 32 dvt .. + 31 of the stored matrix, 32 D
+  // consecutive floats.  Read element by element each lane would touch a cache line of its own (measured
+  // +20 us per launch at 256 workgroups); instead the wave copies its rows with 16-byte loads into the tile
+  // buffers, which nothing has used yet, and each lane picks its elements out of LDS (row stride D + 1 floats:
+  // no bank conflicts).  One wave group at a time, a workgroup barrier after each: the first tile loads, from
+  // any wave, overwrite that LDS.  Whether the launch has transposed states at all is uniform over the grid.
+  if ((p.state_transposed | p.init_transposed) != 0) {
+    float* const lds = reinterpret_cast<float*>(&sT[0][0][0]) + dvt * (32 * (D + 1));
+    static_assert(sizeof(sT) >= (size_t)SW * 32 * (D + 1) * sizeof(float), "room for one wave group's slices");
+#pragma unroll 1
+    for (int gsel = 0; gsel < NW / SW; gsel++) {
+      if (gs != nullptr && tr && group == gsel) {
+        const float* rows = gs + (int64_t)(32 * dvt) * D;
+#pragma unroll
+        for (int i = 0; i < 32 * D / 256; i++) {
+          const int at = 4 * (64 * i + l);
+          const f32x4 x = *reinterpret_cast<const f32x4*>(rows + at);
+          float* dst = lds + (at / D) * (D + 1) + at % D;
+          dst[0] = x[0]; dst[1] = x[1]; dst[2] = x[2]; dst[3] = x[3];
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's own writes, before its own reads
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+          for (int v = 0; v < 16; v++)
+            kv[t][v] = lds[l32 * (D + 1) + 32 * t + 8 * (v >> 2) + 4 * hh + (v & 3)];
+      }
+      __syncthreads();
+    }
   }
 
   // decay mask of the score tile S^T[c][r] (lane: r = l32; element v: c = 8 (v / 4) + 4 hh + v % 4)
