@@ -368,7 +368,8 @@ def main():
     b_ms = time_ms(lambda: binding.la2_bwd_varlen(gp["q"], gp["k"], gp["v"], gp["d_o"], gp["lam"], cu, max(lengths),
                                                   out=gr_), iters, warm=40)
     packed = {"workload": wl_p.name, "sequences": len(lengths), "tokens": sum(lengths), "fwd_ms": round(f_ms, 4),
-              "bwd_ms": round(b_ms, 4), "tokens_per_s": round(sum(lengths) / ((f_ms + b_ms) * 1e-3), 1)}
+              "bwd_ms": round(b_ms, 4), "tokens_per_s": round(sum(lengths) / ((f_ms + b_ms) * 1e-3), 1),
+              "note": "the library cuts the long sequences into chunks (planned from the longest length and the total)"}
     del gp, op_, gr_, tp
     # the same point in the library's other two data types (fp16: the same kernels as bf16; fp32: fp32 MFMA)
     other_dtypes = []

@@ -213,20 +213,29 @@ la2_status la2_bwd_state_norm(const la2_desc* desc, const void* q, const void* k
  * Algorithm 1 / Algorithm 2 over PACKED sequences of different lengths (a batch without padding): the
  * tensors are [total_positions, heads, head_dim]; sequence b occupies positions cu_seqlens[b] ..
  * cu_seqlens[b + 1] - 1 and is a chain of its own (zero start state, no interaction with its neighbours).
- *   desc        batch = number of sequences, seqlen = an upper bound of the sequence lengths (the launch is
- *               planned for it: pass the longest length), stride_n / stride_h = elements between consecutive
- *               positions / heads (dense packing: heads * head_dim and head_dim), stride_b ignored
- *   cu_seqlens  in   device, int32 [batch + 1], non-decreasing, cu_seqlens[0] = offset of the first
- *               sequence; lengths above desc->seqlen are a precondition violation (not read on the host)
- * Everything else as for la2_fwd / la2_bwd, the workspace included (la2_workspace_bytes with this desc).
+ *   desc             batch = number of sequences, seqlen = an upper bound of the sequence lengths (the launch is
+ *                    planned for it: pass the longest length), stride_n / stride_h = elements between consecutive
+ *                    positions / heads (dense packing: heads * head_dim and head_dim), stride_b ignored
+ *   cu_seqlens       in   device, int32 [batch + 1], non-decreasing, cu_seqlens[0] = offset of the first
+ *                    sequence; lengths above desc->seqlen are a precondition violation (not read on the host)
+ *   total_positions  host scalar: the number of positions in all sequences together (the packed tensors' first
+ *                    extent), or 0 if not known; negative: LA2_ERR_SHAPE.  A planning hint only: the lengths
+ *                    stay on the device, and with it the host can tell a batch of about equal lengths from one
+ *                    whose longest sequence would run long after all the others have finished.  Such a batch is
+ *                    cut into sequence chunks (an eighth of desc->seqlen) although it has chains enough to
+ *                    fill the device; the short sequences are single chunks and pay nothing for it.
+ * Everything else as for la2_fwd / la2_bwd.  Workspace: la2_varlen_workspace_bytes(desc, total_positions, op) with
+ * op = LA2_OP_FWD or LA2_OP_BWD (with total_positions = 0: la2_workspace_bytes(desc, op)).
  * A sequence of length 0 is fine.
  */
-la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
-                          const void* v, const float* lambda, void* o, void* workspace,
-                          size_t workspace_bytes, void* hip_stream);
-la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
-                          const void* v, const void* d_o, const float* lambda, void* dq, void* dk, void* dv,
+size_t la2_varlen_workspace_bytes(const la2_desc* desc, int64_t total_positions, int32_t op);
+la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                          const void* q, const void* k, const void* v, const float* lambda, void* o,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                          const void* q, const void* k, const void* v, const void* d_o, const float* lambda,
+                          void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
 
 /*
  * One step of the recurrent form (Sec. 3.2.1, recursive form), for every (batch, head):

@@ -81,9 +81,11 @@ def load():
     lib.la2_fwd_norm.restype = ctypes.c_int
     lib.la2_bwd_norm.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_norm.restype = ctypes.c_int
-    lib.la2_fwd_varlen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_varlen_workspace_bytes.argtypes = [dp, ctypes.c_int64, i32]
+    lib.la2_varlen_workspace_bytes.restype = sz
+    lib.la2_fwd_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_fwd_varlen.restype = ctypes.c_int
-    lib.la2_bwd_varlen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_bwd_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_varlen.restype = ctypes.c_int
     lib.la2_left_product_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.la2_left_product_fwd.restype = ctypes.c_int
@@ -275,7 +277,7 @@ def _varlen_desc(q, cu_seqlens, max_seqlen):
 
 
 def _varlen_workspace(q, desc, op, workspace):
-    need = int(load().la2_workspace_bytes(ctypes.byref(desc), op))
+    need = int(load().la2_varlen_workspace_bytes(ctypes.byref(desc), q.shape[0], op))
     if need == 0:
         return None, 0, None
     if workspace is None:
@@ -298,7 +300,7 @@ def la2_fwd_varlen(q, k, v, lam, cu_seqlens, max_seqlen, out=None, workspace=Non
     desc = _varlen_desc(q, cu_seqlens, max_seqlen)
     ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_FWD, workspace)
     with torch.cuda.device(q.device):
-        _check(lib.la2_fwd_varlen(ctypes.byref(desc), cu_seqlens.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+        _check(lib.la2_fwd_varlen(ctypes.byref(desc), cu_seqlens.data_ptr(), q.shape[0], q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                   lam.data_ptr(), out.data_ptr(), ws_ptr, ws_bytes, _stream(q)))
     return out
 
@@ -316,7 +318,7 @@ def la2_bwd_varlen(q, k, v, d_o, lam, cu_seqlens, max_seqlen, out=None, workspac
     desc = _varlen_desc(q, cu_seqlens, max_seqlen)
     ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_BWD, workspace)
     with torch.cuda.device(q.device):
-        _check(lib.la2_bwd_varlen(ctypes.byref(desc), cu_seqlens.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+        _check(lib.la2_bwd_varlen(ctypes.byref(desc), cu_seqlens.data_ptr(), q.shape[0], q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                   d_o.data_ptr(), lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr,
                                   ws_bytes, _stream(q)))
     return dq, dk, dv

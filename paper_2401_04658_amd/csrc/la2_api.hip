@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <atomic>
 
 #include "../../include/la2.h"
@@ -97,7 +98,12 @@ int block_size(const la2_desc* d) {
 struct Plan {
   int nchunks;
   int chunk_tokens;
-  size_t workspace;
+  size_t workspace;     // bytes of chunk states (one set)
+  // packed batch with a compact launch grid (make_plan_varlen): (sequence, chunk) pairs the grid has room for and
+  // bytes of the pair map that sits in front of the states; 0 otherwise
+  int wg_pairs = 0;
+  int nlong = 0;        // sequences of more than one chunk the plan has room for (the state scan's units)
+  size_t map_bytes = 0;
 };
 
 // Sequence chunks: the block loop of one chain is sequential, so when batch*heads cannot fill the
@@ -134,11 +140,65 @@ Plan make_plan(const la2_desc* d) {
   return pl;
 }
 
+// Packed batch of sequences of different lengths (batch chains per head, the longest of seqlen positions,
+// total_positions in all; 0 = not known).  With few chains the dense rule above already cuts the sequences.
+// With many chains it does not, and then a batch of very unequal lengths runs as long as its longest sequence's
+// sequential block loop: when that loop is estimated to outlast the whole batch's memory traffic, the sequences
+// are cut into chunks of a quarter of the longest one (at least four blocks).  Shorter sequences then have one
+// chunk and no pre-pass work; only the long ones pay the second read of their key-like and value-like rows.
+// The launch grid of such a plan is compact: one workgroup per (sequence, chunk) pair that exists and head (a
+// grid of batch x heads x nchunks workgroups, most of them for chunks the short sequences do not have, costs
+// about 10 ns per empty workgroup and launch: measured 1.16 ms against 0.34 ms uncut for 191 sequences x 16
+// heads x 8 chunks).  A sequence of len positions has at most len / C + 1 pairs, and only sequences longer than
+// C need state slots, at most 2 len / C each.  16-bit data at head_dim 64 / 128 (the half-block kernels) only.
+constexpr int kPackedCut = 4;   // pieces the longest sequence of such a batch is cut into
+Plan make_plan_varlen(const la2_desc* d, int64_t total_positions) {
+  Plan pl = make_plan(d);
+  if (total_positions <= 0 || d->batch <= 0) return pl;
+  if (!is16(d->dtype) || wide(d->head_dim) || g_scan_variant.load(std::memory_order_relaxed) == 1) return pl;
+  const int B = block_size(d);
+  const int nblocks = (d->seqlen + B - 1) / B;
+  auto compact = [&](Plan c) {   // the compact grid and its map for a plan that has chunks
+    const int64_t all = (int64_t)d->batch * c.nchunks;
+    const int64_t pairs = std::min<int64_t>(all, total_positions / c.chunk_tokens + d->batch);
+    const int64_t slots = std::min<int64_t>(all, 2 * total_positions / c.chunk_tokens);
+    const int64_t nlong = std::min<int64_t>(d->batch, total_positions / c.chunk_tokens);
+    if (pairs > ((int64_t)1 << 30)) return c;
+    c.wg_pairs = (int)pairs;
+    c.nlong = (int)nlong;
+    c.map_bytes = ((size_t)pairs * sizeof(int4) + (size_t)nlong * sizeof(int32_t) + 255) & ~(size_t)255;
+    c.workspace = (size_t)slots * d->heads * d->head_dim * d->head_dim * sizeof(float);
+    return c;
+  };
+  // the dense rule (few chains) or the test knob already cut the sequences: same chunks, compact grid
+  if (pl.nchunks > 1) return compact(pl);
+  if (g_chunk_tokens_override.load(std::memory_order_relaxed) > 0) return pl;
+  if (nblocks < 8) return pl;
+  if ((int64_t)d->seqlen * d->batch <= 2 * total_positions) return pl;   // lengths about equal
+  // microseconds: the longest chain's loop (measured times per block, as in make_plan) against the batch's forward
+  // traffic at 5.5 TB/s
+  const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 9.f : d->head_dim == 96 ? 3.f : d->head_dim == 64 ? 1.15f : 2.1f)
+                                     : (d->head_dim == 128 ? 10.f : 3.f);
+  const float t_longest = (float)nblocks * t_blk;
+  const float t_traffic = (float)total_positions * d->heads * d->head_dim * 4.f * elem_size(d->dtype) / 5.5e6f;
+  if (t_longest <= 1.25f * t_traffic) return pl;
+  int cb = (nblocks + kPackedCut - 1) / kPackedCut;
+  if (cb < 4) cb = 4;
+  if (cb >= nblocks) return pl;
+  pl.nchunks = (nblocks + cb - 1) / cb;
+  pl.chunk_tokens = cb * B;
+  pl.workspace = (size_t)d->batch * d->heads * pl.nchunks * d->head_dim * d->head_dim * sizeof(float);
+  const Plan c = compact(pl);
+  return c.wg_pairs > 0 ? c : make_plan(d);
+}
+
 // Grid sizes of every launch a plan leads to, checked on the host before the first one: the scan kernels take
 // chains * nchunks workgroups per scan (two scans in a dual launch), the state scan chains * d * d / 256.
 bool plan_fits_a_grid(const la2_desc* d, const Plan& pl) {
   const int64_t chains = (int64_t)d->batch * d->heads;
   const int64_t limit = ((int64_t)1 << 31) - 1;
+  if (pl.wg_pairs > 0)   // compact grid: pairs x heads workgroups, and as many units in the state scan
+    return (int64_t)pl.wg_pairs * d->heads * ((d->head_dim * d->head_dim + 255) / 256) <= limit;
   if (chains * pl.nchunks * 2 > limit) return false;
   if (pl.nchunks > 1 && chains * ((d->head_dim * d->head_dim + 255) / 256) > limit) return false;
   return true;
@@ -177,6 +237,8 @@ struct ScanArgs {
   // (acc_y, x) pair into acc_states (ScanParams::acc_y)
   const void* acc_y = nullptr;
   float* acc_states = nullptr;
+  // compact launch grid of a packed batch in chunks: the pair map (device), built by launch_varlen_map
+  const int4* map = nullptr;
 };
 
 la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace,
@@ -199,9 +261,13 @@ la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lamb
 // (local_ready: an earlier launch already left the chunks' local states there; only the scan over them runs)
 la2_status run_prepass(const la2_desc* d, const Plan& pl, bool reverse, const void* y, const void* z,
                        const float* init, bool init_tr, const float* lambda, void* workspace, hipStream_t s,
-                       const int32_t* cu = nullptr, bool local_ready = false) {
+                       const int32_t* cu = nullptr, bool local_ready = false, const int4* map = nullptr) {
   if (pl.nchunks <= 1) return LA2_OK;
   la2::ScanParams p = base_params(d, pl, lambda, workspace, cu);
+  p.wg_map = map;
+  p.wg_pairs = pl.wg_pairs;
+  p.long_list = map != nullptr ? reinterpret_cast<const int32_t*>(map + pl.wg_pairs) : nullptr;
+  p.nlong = pl.nlong;
   p.y[0] = y; p.z[0] = z;
   p.init[0] = init; p.init_transposed = init_tr ? 1 : 0;
   hipError_t e = local_ready          ? hipSuccess
@@ -217,10 +283,12 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
                     void* workspace, hipStream_t s) {
   const bool saved = a.saved_states != nullptr && pl.nchunks > 1;
   if (!saved) {
-    la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s, a.cu);
+    la2_status st = run_prepass(d, pl, reverse, a.y, a.z, a.init, a.init_tr, lambda, workspace, s, a.cu, false, a.map);
     if (st != LA2_OK) return st;
   }
   la2::ScanParams p = base_params(d, pl, lambda, workspace, a.cu);
+  p.wg_map = a.map;
+  p.wg_pairs = pl.wg_pairs;
   if (saved) {
     p.states = const_cast<float*>(a.saved_states);   // read only
     p.state_transposed = a.saved_tr ? 1 : 0;
@@ -244,9 +312,11 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
 // (local_ready: the workspace already holds the chunks' local states, left there by the dQ scan's launch)
 la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanArgs& a0, const ScanArgs& a1,
                                  const float* lambda, void* workspace, hipStream_t s, bool local_ready = false) {
-  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s, a0.cu, local_ready);
+  la2_status st = run_prepass(d, pl, true, a0.y, a0.z, a0.init, a0.init_tr, lambda, workspace, s, a0.cu, local_ready, a0.map);
   if (st != LA2_OK) return st;
   la2::ScanParams p = base_params(d, pl, lambda, workspace, a0.cu);
+  p.wg_map = a0.map;
+  p.wg_pairs = pl.wg_pairs;
   p.nscan = 2;
   p.state_transposed = 2;   // scan 1 starts from the transposed state
   p.init[0] = a0.init; p.init[1] = a1.init;
@@ -346,6 +416,15 @@ la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk
   *nchunks = pl.nchunks;
   *chunk_tokens = pl.chunk_tokens;
   return LA2_OK;
+}
+
+size_t la2_varlen_workspace_bytes(const la2_desc* desc, int64_t total_positions, int32_t op) {
+  if (check_desc(desc) != LA2_OK || total_positions < 0) return 0;
+  const Plan pl = make_plan_varlen(desc, total_positions);
+  if (!plan_fits_a_grid(desc, pl)) return 0;
+  if (op == LA2_OP_FWD) return pl.map_bytes + pl.workspace;
+  if (op == LA2_OP_BWD) return pl.map_bytes + pl.workspace * (fuses_reverse_states(desc) ? 2 : 1);
+  return 0;
 }
 
 int32_t la2_block_size(const la2_desc* desc) {
@@ -639,47 +718,80 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                             workspace, workspace_bytes, hip_stream);
 }
 
-la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
-                          const void* v, const float* lambda, void* o, void* workspace, size_t workspace_bytes,
-                          void* hip_stream) {
+la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
+                          const void* k, const void* v, const float* lambda, void* o, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if (total_positions < 0) return LA2_ERR_SHAPE;
   if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // packed batches at 96 / 256: 16-bit only
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!cu_seqlens || !q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
       !aligned(cu_seqlens, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  const Plan pl = make_plan(desc);
-  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace || !aligned(workspace, 256)))
+  const Plan pl = make_plan_varlen(desc, total_positions);
+  if (!plan_fits_a_grid(desc, pl)) return LA2_ERR_SHAPE;
+  const size_t need = pl.map_bytes + pl.workspace;
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
     return LA2_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   ScanArgs a{q, k, v, o};
   a.cu = cu_seqlens;
-  return run_scan(desc, pl, false, a, lambda, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  if (pl.wg_pairs > 0) {   // the pair map of the compact grid, in front of the states
+    la2::ScanParams mp = base_params(desc, pl, lambda, nullptr, cu_seqlens);
+    mp.wg_pairs = pl.wg_pairs;
+    mp.nlong = pl.nlong;
+    int4* map = reinterpret_cast<int4*>(workspace);
+    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), s) != hipSuccess)
+      return LA2_ERR_LAUNCH;
+    a.map = map;
+  }
+  return run_scan(desc, pl, false, a, lambda, static_cast<char*>(workspace) + pl.map_bytes, s);
 }
 
-la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, const void* q, const void* k,
-                          const void* v, const void* d_o, const float* lambda, void* dq, void* dk, void* dv,
-                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
+                          const void* k, const void* v, const void* d_o, const float* lambda, void* dq, void* dk,
+                          void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
+  if (total_positions < 0) return LA2_ERR_SHAPE;
   if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // as la2_fwd_varlen
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
   if (!cu_seqlens || !q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
       !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4) || !aligned(cu_seqlens, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  const Plan pl = make_plan(desc);
-  if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace || !aligned(workspace, 256)))
+  const Plan pl = make_plan_varlen(desc, total_positions);
+  if (!plan_fits_a_grid(desc, pl)) return LA2_ERR_SHAPE;
+  // as la2_bwd: with sequence chunks the dQ scan's launch forms the local dKV states behind its own chunk states
+  const bool fuse = pl.nchunks > 1 && fuses_reverse_states(desc);
+  const size_t need = pl.map_bytes + pl.workspace * (fuse ? 2 : 1);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
     return LA2_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   // the three scans of la2_bwd, each chain a sequence of its own length
   ScanArgs for_dq{d_o, v, k, dq}, for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
   for_dq.cu = for_dv.cu = for_dk.cu = cu_seqlens;
   for_dk.init_tr = true;
+  if (pl.wg_pairs > 0) {   // the pair map of the compact grid, in front of the states
+    la2::ScanParams mp = base_params(desc, pl, lambda, nullptr, cu_seqlens);
+    mp.wg_pairs = pl.wg_pairs;
+    mp.nlong = pl.nlong;
+    int4* map = reinterpret_cast<int4*>(workspace);
+    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), s) != hipSuccess)
+      return LA2_ERR_LAUNCH;
+    for_dq.map = for_dv.map = for_dk.map = map;
+  }
+  workspace = static_cast<char*>(workspace) + pl.map_bytes;   // the states
+  void* rev_workspace = fuse ? static_cast<char*>(workspace) + pl.workspace : workspace;
+  if (fuse) {
+    for_dq.acc_y = q;
+    for_dq.acc_states = reinterpret_cast<float*>(rev_workspace);
+  }
   st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
   if (st != LA2_OK) return st;
-  if (is16(desc->dtype)) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, workspace, s);
+  if (is16(desc->dtype)) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, rev_workspace, s, fuse);
   st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
   if (st != LA2_OK) return st;
   return run_scan(desc, pl, true, for_dk, lambda, workspace, s);

@@ -29,9 +29,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w % NT;
-  const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
-  if (REV ? (chunk == 0) : (chunk == p.nchunks - 1)) return;  // no successor needs it
-  const int bi = chain / p.heads, hi = chain % p.heads;
+  int bi, hi, chunk, slot_stride;
+  int64_t slot;
+  if (!place_workgroup(p, (int)blockIdx.x, bi, hi, chunk, slot, slot_stride)) return;
   int64_t base;
   int n;
   chain_extent(p, bi, hi, base, n);
@@ -41,6 +41,8 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   const int blk_lo = chunk * cb;
   const int blk_hi = min(blk_lo + cb, nblocks);
   const int nblk = blk_hi - blk_lo;
+  // the chunk a scan of THIS chain passes last has no successor (a packed batch: chains of different lengths)
+  if (REV ? (chunk == 0) : (blk_hi >= nblocks)) return;
 
   Loader loader(w, l, n, (uint32_t)p.stride_n);
   loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy loads before the LDS is given up
 
   if (w < NT) {   // for d = 64 waves w and w + 2 hold the same slice
-    float* gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+    float* gs = p.states + slot * (D * D);   // a chunk with a successor: its chain has state slots
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
@@ -126,21 +128,41 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
 // states first (independent loads, all in flight together) and then runs the recurrence on registers; the
 // launch sits between two kernels that wait for it, so its latency is what counts, not its bytes.
 constexpr int kScanMaxChunks = 32;
+// wg_map != nullptr (packed batch with a compact grid, see ScanParams): a "unit" is a sequence of long_list and a
+// head; the chain's states are `heads` slots apart.
 __global__ void state_scan_kernel(float* states, const float* lambda, int heads, int nchunks, int chunk_tokens,
                                   int dd, int reverse, const float* init, int init_tr, int d, int n,
-                                  const int32_t* cu_seqlens) {
+                                  const int32_t* cu_seqlens, const int4* wg_map, const int32_t* long_list) {
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   const int dd4 = dd >> 2;
   const int per_chain = (dd4 + (int)blockDim.x - 1) / (int)blockDim.x;   // workgroups per chain
-  const int chain = (int)(blockIdx.x / per_chain);
+  const int unit = (int)(blockIdx.x / per_chain);
   const int e4 = (int)(blockIdx.x % per_chain) * (int)blockDim.x + (int)threadIdx.x;
   if (e4 >= dd4) return;
-  if (cu_seqlens != nullptr) n = cu_seqlens[chain / heads + 1] - cu_seqlens[chain / heads];   // this sequence's length
+  int bi, hi;
+  int64_t first_slot, stride;   // the chain's chunk-0 state slot, slots between its consecutive chunks
+  if (wg_map != nullptr) {
+    const int pair = long_list[unit / heads];
+    if (pair < 0) return;
+    const int4 m = wg_map[pair];
+    bi = m.x;
+    hi = unit % heads;
+    first_slot = (int64_t)m.z * heads + hi;
+    stride = heads;
+  } else {
+    bi = unit / heads;
+    hi = unit % heads;
+    first_slot = (int64_t)unit * nchunks;
+    stride = 1;
+  }
+  const int chain = bi * heads + hi;
+  if (cu_seqlens != nullptr) n = cu_seqlens[bi + 1] - cu_seqlens[bi];   // this sequence's length
   const int nch = (n + chunk_tokens - 1) / chunk_tokens;   // chunks this chain really has (<= nchunks)
-  const float l2 = log2f(lambda[chain % heads]);
+  const float l2 = log2f(lambda[hi]);
   const float lamFull = exp2f(l2 * (float)chunk_tokens);
   const float lamLast = exp2f(l2 * (float)(n - (nch - 1) * chunk_tokens));
-  f32x4* s = reinterpret_cast<f32x4*>(states + (int64_t)chain * nchunks * dd) + e4;
+  f32x4* s = reinterpret_cast<f32x4*>(states + first_slot * dd) + e4;
+  const int64_t step = stride * dd4;   // f32x4 elements between consecutive chunks' states
   f32x4 g = {0.f, 0.f, 0.f, 0.f};
   if (init != nullptr) {
     const float* gi = init + (int64_t)chain * dd;
@@ -157,13 +179,13 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
 #pragma unroll
     for (int i = 0; i < kScanMaxChunks; i++) {
       const int j = reverse ? nch - 1 - i : i;
-      if (i < nch - 1) loc[i] = s[(int64_t)j * dd4];   // the chunk processed last has no successor: not read
+      if (i < nch - 1) loc[i] = s[(int64_t)j * step];   // the chunk processed last has no successor: not read
     }
 #pragma unroll
     for (int i = 0; i < kScanMaxChunks; i++) {
       if (i < nch) {
         const int j = reverse ? nch - 1 - i : i;
-        s[(int64_t)j * dd4] = g;
+        s[(int64_t)j * step] = g;
         const float decay = (j == nch - 1) ? lamLast : lamFull;
         if (i < nch - 1) g = decay * g + loc[i];
       }
@@ -174,10 +196,54 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
     const int j = reverse ? nch - 1 - i : i;
     const bool last = (i == nch - 1);
     f32x4 loc = {0.f, 0.f, 0.f, 0.f};
-    if (!last) loc = s[(int64_t)j * dd4];
-    s[(int64_t)j * dd4] = g;
+    if (!last) loc = s[(int64_t)j * step];
+    s[(int64_t)j * step] = g;
     g = (j == nch - 1 ? lamLast : lamFull) * g + loc;
   }
+}
+
+// Packed batch in sequence chunks: the (sequence, chunk) pairs in order, for the compact launch grid.  One
+// workgroup walks the sequences 256 at a time with a running count of pairs and of state slots.
+//   map[pair] = {sequence, chunk, first state slot of the sequence (-1: single chunk, no slots), its chunk count}
+// Entries past the last pair, up to npairs, get sequence -1.  A batch whose lengths sum to more than the host was
+// told would need more entries than the map has: such pairs are dropped (never written past the end).
+// long_list[i] = pair of chunk 0 of the i-th sequence with state slots (i < nlong), -1 past the last.
+__global__ __launch_bounds__(256) void varlen_map_kernel(const int32_t* cu_seqlens, int batch, int chunk_tokens, int npairs,
+                                                         int4* map, int nlong, int32_t* long_list) {
+  __shared__ int s_pairs[256], s_slots[256], s_long[256];
+  __shared__ int base_pairs, base_slots, base_long;
+  const int t = (int)threadIdx.x;
+  if (t == 0) { base_pairs = 0; base_slots = 0; base_long = 0; }
+  __syncthreads();
+  for (int b0 = 0; b0 < batch; b0 += 256) {
+    const int b = b0 + t;
+    int nch = 0;
+    if (b < batch) nch = (cu_seqlens[b + 1] - cu_seqlens[b] + chunk_tokens - 1) / chunk_tokens;
+    const int slots = nch > 1 ? nch : 0;
+    s_pairs[t] = nch;
+    s_slots[t] = slots;
+    s_long[t] = slots ? 1 : 0;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {   // inclusive scan of the three counts
+      const int ap = t >= off ? s_pairs[t - off] : 0, as = t >= off ? s_slots[t - off] : 0,
+                al = t >= off ? s_long[t - off] : 0;
+      __syncthreads();
+      s_pairs[t] += ap;
+      s_slots[t] += as;
+      s_long[t] += al;
+      __syncthreads();
+    }
+    const int first_pair = base_pairs + s_pairs[t] - nch;
+    const int first_slot = base_slots + s_slots[t] - slots;
+    for (int j = 0; j < nch; j++)
+      if (first_pair + j < npairs) map[first_pair + j] = make_int4(b, j, slots ? first_slot : -1, nch);
+    if (slots && base_long + s_long[t] - 1 < nlong && first_pair < npairs) long_list[base_long + s_long[t] - 1] = first_pair;
+    __syncthreads();
+    if (t == 255) { base_pairs += s_pairs[255]; base_slots += s_slots[255]; base_long += s_long[255]; }
+    __syncthreads();
+  }
+  for (int i = base_pairs + t; i < npairs; i += 256) map[i] = make_int4(-1, 0, -1, 0);
+  for (int i = base_long + t; i < nlong; i += 256) long_list[i] = -1;
 }
 
 }  // namespace
@@ -185,7 +251,7 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
 namespace {
 template <typename E>
 hipError_t launch_chunk_states(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
-  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks;
+  const int64_t grid = p.wg_map != nullptr ? (int64_t)p.wg_pairs * p.heads : (int64_t)p.batch * p.heads * p.nchunks;
   dim3 g((unsigned)grid), b(kThreads);
   if (head_dim == 128) {
     if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, true, 4>), g, b, 0, s, p);
@@ -206,12 +272,19 @@ hipError_t launch_chunk_states_bf16(int dtype, int head_dim, bool reverse, const
 }
 
 hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
-  const int chains = p.batch * p.heads;
-  if (chains == 0 || p.n == 0) return hipSuccess;
+  const int64_t units = p.wg_map != nullptr ? (int64_t)p.nlong * p.heads : (int64_t)p.batch * p.heads;
+  if (units == 0 || p.n == 0) return hipSuccess;
   const int dd = head_dim * head_dim;
-  dim3 g((unsigned)((int64_t)chains * ((dd / 4 + 255) / 256))), b(256);   // the host checked that this fits a grid
+  dim3 g((unsigned)(units * ((dd / 4 + 255) / 256))), b(256);   // the host checked that this fits a grid
   hipLaunchKernelGGL(state_scan_kernel, g, b, 0, s, p.states, p.lambda, p.heads, p.nchunks, p.chunk_tokens, dd,
-                     reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n, p.cu_seqlens);
+                     reverse ? 1 : 0, p.init[0], p.init_transposed & 1, head_dim, p.n, p.cu_seqlens, p.wg_map, p.long_list);
+  return hipGetLastError();
+}
+
+hipError_t launch_varlen_map(const ScanParams& p, int4* map, int32_t* long_list, hipStream_t s) {
+  if (p.wg_pairs <= 0) return hipSuccess;
+  hipLaunchKernelGGL(varlen_map_kernel, dim3(1), dim3(256), 0, s, p.cu_seqlens, p.batch, p.chunk_tokens, p.wg_pairs, map,
+                     p.nlong, long_list);
   return hipGetLastError();
 }
 

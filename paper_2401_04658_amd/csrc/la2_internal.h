@@ -64,7 +64,45 @@ struct ScanParams {
   // the local dKV states that the dK / dV scan's chunks start from.  nullptr: off.
   const void* acc_y;
   float* acc_states;
+  // Packed batch cut into sequence chunks (16-bit half-block path only; nullptr otherwise): a compact launch
+  // grid.  Instead of batch * heads * nchunks workgroups, most of them for chunks that short sequences do not
+  // have, the launch has wg_pairs * heads workgroups and workgroup i serves head i % heads of the (sequence,
+  // chunk) pair wg_map[i / heads] = {sequence, chunk, state slot or -1, chunks of the sequence}; entries past
+  // the last pair carry sequence -1.  Only sequences of more than one chunk have state slots: chunk j of
+  // such a sequence keeps its state at states[(slot + j') * heads + head], consecutive chunks heads states apart.
+  // The map is written by varlen_map_kernel from cu_seqlens (launch_varlen_map).
+  const int4* wg_map;
+  int32_t wg_pairs;
+  // ... and the pairs of chunk 0 of the sequences that have state slots, in order (entries past the last: -1):
+  // the units of the state scan's launch, which would otherwise be mostly workgroups with nothing to do
+  const int32_t* long_list;
+  int32_t nlong;
 };
+
+// Which (batch row or sequence, head, chunk) a workgroup of a scan-type launch serves, and where that chunk's
+// state lives ([D][D] floats at states + slot * D * D; slot < 0: the chain has a single chunk and no state slot).
+// slot_stride: slots between consecutive chunks of the chain.  false: no work for this workgroup.
+__device__ __forceinline__ bool place_workgroup(const ScanParams& p, int wg, int& bi, int& hi, int& chunk,
+                                                int64_t& slot, int& slot_stride) {
+  if (p.wg_map == nullptr) {
+    const int chain = wg / p.nchunks;
+    chunk = wg % p.nchunks;
+    bi = chain / p.heads;
+    hi = chain % p.heads;
+    slot = (int64_t)chain * p.nchunks + chunk;
+    slot_stride = 1;
+    return true;
+  }
+  const int4 m = p.wg_map[wg / p.heads];
+  // the same for every lane: say so (the chain's base address has to sit in scalar registers)
+  const int seq = __builtin_amdgcn_readfirstlane(m.x), first_slot = __builtin_amdgcn_readfirstlane(m.z);
+  hi = wg % p.heads;
+  bi = seq;
+  chunk = __builtin_amdgcn_readfirstlane(m.y);
+  slot = first_slot < 0 ? -1 : ((int64_t)first_slot + chunk) * p.heads + hi;
+  slot_stride = p.heads;
+  return seq >= 0;
+}
 
 // Element offset of chain (bi, hi)'s first position and the chain's length.
 __device__ __forceinline__ void chain_extent(const ScanParams& p, int bi, int hi, int64_t& base, int& n) {
@@ -76,6 +114,12 @@ __device__ __forceinline__ void chain_extent(const ScanParams& p, int bi, int hi
     n = p.n;
     base = (int64_t)bi * p.stride_b + (int64_t)hi * p.stride_h;
   }
+  // Both are the same for every lane of the workgroup; told to the compiler, so that the chain's base address
+  // lives in scalar registers whatever path the indices took (the direct loads take it as a scalar operand).
+  n = __builtin_amdgcn_readfirstlane(n);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+  const uint32_t hi32 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)base >> 32));
+  base = (int64_t)(((uint64_t)hi32 << 32) | lo);
 }
 
 // Norm epilogue, shared by the scan kernels.  A 32 x 32 output tile sits in MFMA accumulators transposed
@@ -126,6 +170,8 @@ hipError_t launch_left_product_bf16(int head_dim, bool reverse, const ScanParams
 // fp32 path
 hipError_t launch_scan_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
+// packed batch in chunks: fills map[0 .. p.wg_pairs) and long_list[0 .. p.nlong) from p.cu_seqlens (one small workgroup)
+hipError_t launch_varlen_map(const ScanParams& p, int4* map, int32_t* long_list, hipStream_t s);
 // turns the per-chunk local states in p.states into chunk start states (any dtype: states are fp32);
 // the first chunk starts from p.init[0] (seen through bit 0 of p.init_transposed) or zero
 hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);

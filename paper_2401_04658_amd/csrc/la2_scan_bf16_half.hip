@@ -89,8 +89,10 @@ void scan_bf16_half_kernel(ScanParams p) {
   // its tiles at compile-time LDS offsets.
   auto run = [&](auto wh_tag) __attribute__((always_inline)) {
   constexpr int WH = decltype(wh_tag)::value;
-  const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
-  const int bi = chain / p.heads, hi = chain % p.heads;
+  int bi, hi, chunk, slot_stride;
+  int64_t slot;
+  if (!place_workgroup(p, wg, bi, hi, chunk, slot, slot_stride)) return;
+  const int chain = bi * p.heads + hi;
   int64_t base;
   int n;
   chain_extent(p, bi, hi, base, n);
@@ -194,7 +196,7 @@ void scan_bf16_half_kernel(ScanParams p) {
       }
       __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
       if (chunk != 0) {   // chunk 0 is the last one a reverse scan reaches: nobody starts from its local state
-        float* gs = p.acc_states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+        float* gs = p.acc_states + slot * (D * D);   // a chain with a chunk 1 has state slots
 #pragma unroll
         for (int t = 0; t < NT; t++)
 #pragma unroll
@@ -207,8 +209,8 @@ void scan_bf16_half_kernel(ScanParams p) {
   f32x16 kv[NT];
   const float* gs = nullptr;   // start state: chunk start state, the caller's start state, or zero
   bool tr = false;
-  if (p.states != nullptr) {
-    gs = p.states + ((int64_t)chain * p.nchunks + chunk) * (D * D);
+  if (p.states != nullptr && slot >= 0) {
+    gs = p.states + slot * (D * D);
     tr = (p.state_transposed >> which) & 1;
   } else if ((which ? p.init[1] : p.init[0]) != nullptr) {
     gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
@@ -482,7 +484,7 @@ void scan_bf16_half_kernel(ScanParams p) {
 namespace {
 template <typename E, int D>
 hipError_t launch_half(bool reverse, bool twin, const ScanParams& p, hipStream_t s) {
-  const int64_t grid = (int64_t)p.batch * p.heads * p.nchunks * p.nscan;
+  const int64_t grid = (p.wg_map != nullptr ? (int64_t)p.wg_pairs * p.heads : (int64_t)p.batch * p.heads * p.nchunks) * p.nscan;
   // Three tile buffers in every case.  More buffers (5 for a plain, 4 for a twin workgroup that has the
   // compute unit to itself) measured no faster: such launches are bound by the memory system, not by the
   // bytes a workgroup keeps in flight.

@@ -85,7 +85,6 @@ __global__ __launch_bounds__(2 * D, 1) void scan_f32_kernel(ScanParams p) {
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w;
   const int chain = blockIdx.x / p.nchunks, chunk = blockIdx.x % p.nchunks;
-  if (STATE_ONLY && (REV ? (chunk == 0) : (chunk == p.nchunks - 1))) return;  // no later chunk needs it
   const int bi = chain / p.heads, hi = chain % p.heads;
   int64_t base;
   int n;
@@ -99,6 +98,8 @@ __global__ __launch_bounds__(2 * D, 1) void scan_f32_kernel(ScanParams p) {
   const int blk_lo = chunk * cb;
   const int blk_hi = min(blk_lo + cb, nblocks);
   if (!STATE_ONLY && blk_lo >= blk_hi) return;
+  // pre-pass: the chunk a scan of THIS chain passes last has no successor (packed batch: chains of different lengths)
+  if (STATE_ONLY && (REV ? (chunk == 0) : (blk_hi >= nblocks))) return;
   const int nblk = max(blk_hi - blk_lo, 0);
 
   const char* g[3];

@@ -305,8 +305,9 @@ def test_varlen_entry_points_validate_before_any_launch(lib):
     d = dense(lib, 5, 2, 300, 64, binding.LA2_BF16)      # 5 sequences of at most 300 positions, [total, H, d] packing
     d.stride_b, d.stride_h, d.stride_n = 0, 64, 128
     ref = ctypes.byref(d)
-    fv = lambda cu=P, q=P, o=P: lib.la2_fwd_varlen(ref, cu, q, P, P, P, o, None, 0, None)
-    bv = lambda cu=P, dq=P: lib.la2_bwd_varlen(ref, cu, P, P, P, P, P, dq, P, P, None, 0, None)
+    fv = lambda cu=P, q=P, o=P, total=0: lib.la2_fwd_varlen(ref, cu, total, q, P, P, P, o, None, 0, None)
+    bv = lambda cu=P, dq=P, total=0: lib.la2_bwd_varlen(ref, cu, total, P, P, P, P, P, dq, P, P, None, 0, None)
+    assert fv(total=-1) == E_SHAPE and bv(total=-1) == E_SHAPE
     assert fv(cu=None) == E_NULL and fv(q=None) == E_NULL and bv(cu=None) == E_NULL and bv(dq=None) == E_NULL
     assert fv(cu=P + 2) == E_ALIGN and fv(o=P + 8) == E_ALIGN and bv(dq=P + 4) == E_ALIGN
     d.head_dim = 80
@@ -345,8 +346,8 @@ def test_head_dim_96_and_256_are_accepted_where_they_have_kernels(lib):
             # packed batches: the 16-bit types only
             d.stride_b, d.stride_h, d.stride_n = 0, hd, 2 * hd
             want = E_NULL if dt != binding.LA2_F32 else E_DTYPE
-            assert lib.la2_fwd_varlen(ref, None, P, P, P, P, P, None, 0, None) == want
-            assert lib.la2_bwd_varlen(ref, None, P, P, P, P, P, P, P, P, None, 0, None) == want
+            assert lib.la2_fwd_varlen(ref, None, 0, P, P, P, P, P, None, 0, None) == want
+            assert lib.la2_bwd_varlen(ref, None, 0, P, P, P, P, P, P, P, P, None, 0, None) == want
         # fp32 runs the token recurrence: never a workspace; the 16-bit kernel is exact at ragged ends: no
         # hand-over state in the workspace
         try:
@@ -389,6 +390,32 @@ def test_noalloc_entry_validates_on_the_host(lib):
     assert fn(big) == E_WS
     empty = dense(lib, 0, 8, 8192, 128, binding.LA2_BF16)
     assert fn(empty, q=None, k=None, v=None, lam=None, o=None) == OK
+
+
+def test_packed_batches_of_unequal_lengths_are_cut_into_chunks(lib):
+    """191 sequences of 128 .. 8192 positions (65,536 in all) x 16 heads fill the device many times over, yet the
+    longest sequence's block loop would outlast the rest: with the total known the plan cuts at an eighth of the
+    longest length; with equal lengths, or the total unknown, it does not."""
+    lib.la2_varlen_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
+    lib.la2_varlen_workspace_bytes.restype = ctypes.c_size_t
+    d = dense(lib, 191, 16, 8192, 128, binding.LA2_BF16)
+    d.stride_b, d.stride_h, d.stride_n = 0, 128, 16 * 128
+    ref = ctypes.byref(d)
+    # chunks of 2048 positions (a quarter of the longest): at most 65536 / 2048 + 191 (sequence, chunk) pairs, 16
+    # bytes of map each, plus 4 bytes for each of the at most 32 sequences longer than a chunk; at most
+    # 2 * 65536 / 2048 state slots (only those sequences have them), times 16 heads
+    map_bytes, states = 3840, 64 * 16 * 128 * 128 * 4
+    assert lib.la2_varlen_workspace_bytes(ref, 65536, 0) == map_bytes + states
+    assert lib.la2_varlen_workspace_bytes(ref, 65536, 1) == map_bytes + 2 * states
+    assert lib.la2_varlen_workspace_bytes(ref, 0, 0) == 0 == lib.la2_workspace_bytes(ref, 0)
+    assert lib.la2_varlen_workspace_bytes(ref, 191 * 8192, 0) == 0          # all sequences as long as the longest
+    assert lib.la2_varlen_workspace_bytes(ref, 191 * 5000, 0) == 0          # about equal
+    assert lib.la2_varlen_workspace_bytes(ref, -1, 0) == 0
+    assert lib.la2_fwd_varlen(ref, P, 65536, P, P, P, P, P, None, 0, None) == E_WS
+    assert lib.la2_bwd_varlen(ref, P, 65536, P, P, P, P, P, P, P, P, P * 16, map_bytes + states, None) == E_WS
+    short = dense(lib, 4000, 16, 256, 128, binding.LA2_BF16)                 # nothing long enough to matter
+    short.stride_b, short.stride_h, short.stride_n = 0, 128, 16 * 128
+    assert lib.la2_varlen_workspace_bytes(ctypes.byref(short), 4000 * 40, 0) == 0
 
 
 def test_bwd_saved_checks_the_forward_workspace(lib):

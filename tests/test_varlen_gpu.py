@@ -73,9 +73,26 @@ def test_mixed_lengths(dtype, d):
 @pytest.mark.parametrize("chunk", [64, 192])
 def test_mixed_lengths_chunked(dtype, d, chunk):
     """Few sequences, long ones among them: the launch is cut into sequence chunks planned for the longest;
-    shorter sequences use fewer of them."""
+    shorter sequences use fewer of them (16-bit data: one workgroup per chunk that exists; fp32: a dense grid)."""
     binding.la2_set_chunk_tokens(chunk)
     check_packed([700, 130, 64, 1000, 5, 0, 383], 2, d, dtype, seed=810 + d + chunk, lam=[0.8, 0.99])
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float16, 128)])
+def test_skewed_lengths_with_many_chains_are_chunked(dtype, d):
+    """Chains enough to fill the device, but one sequence 32 times longer than the others: told the total number
+    of positions the library cuts the sequences into chunks of a quarter of the longest (the short ones are
+    single chunks, interleaved here with the long one); same results."""
+    import ctypes
+    lengths = [64] * 150 + [2048] + [37] * 120 + [300, 0, 1]
+    H = 2
+    desc = binding.la2_desc(len(lengths), H, 2048, d, binding._dtype_code(torch.empty(0, dtype=dtype)), 0, 0, d, H * d)
+    total, C = int(sum(lengths)), 512
+    pairs, slots, nlong = total // C + len(lengths), 2 * total // C, total // C
+    assert binding.load().la2_varlen_workspace_bytes(ctypes.byref(desc), total, binding.LA2_OP_FWD) == \
+        ((pairs * 16 + nlong * 4 + 255) // 256) * 256 + slots * H * d * d * 4
+    assert binding.load().la2_varlen_workspace_bytes(ctypes.byref(desc), 0, binding.LA2_OP_FWD) == 0
+    check_packed(lengths, H, d, dtype, seed=850 + d, lam=[0.7, 0.995])
 
 
 def test_offset_first_sequence_and_unused_tail():
