@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # rocprofv3 --pmc measurement of the dominant kernel's HBM traffic per launch: the committed summary carries a
 # line "traffic_bytes_per_launch: N" (FETCH_SIZE and WRITE_SIZE, each scaled by the plain-copy reference)
-TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "scan_bf16_half_fwd_b16_n4096_h16_d128_counters.txt")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "la2_fwd_bwd_b16_n4096_h16_d128_kernel_trace_traffic_and_counters.txt")
 
 
 def measured_traffic_bytes():
@@ -93,7 +93,7 @@ def dominant_kernel_roofline(wl, g, fwd, time_ms, binding, iters):
         "frac": round(bytes_alg / (k_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         # HBM bytes per launch measured with rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the factor the
         # same counter shows for a plain copy of known size (2.00 and 1.00): read from
-        # profiles/scan_bf16_half_fwd_b16_n4096_h16_d128_counters.txt
+        # profiles/la2_fwd_bwd_b16_n4096_h16_d128_kernel_trace_traffic_and_counters.txt
         "traffic": measured_traffic_bytes(),
         "algorithmic_bytes": bytes_alg,
         "launch_ms": round(k_ms, 4),
