@@ -238,6 +238,24 @@ la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64
                           void* hip_stream);
 
 /*
+ * The normalised operator (eq. (2), Norm read as in la2_fwd_norm) over packed sequences: la2_fwd_norm / la2_bwd_norm
+ * with the packed layout and planning arguments of la2_fwd_varlen / la2_bwd_varlen.
+ *   total_positions  here the packed tensors' first extent exactly (> 0, < 2^31; LA2_ERR_SHAPE otherwise): it is
+ *                    the row length of rstd
+ *   rstd   out (forward) / in (backward)   device fp32 [heads, total_positions] dense: r of packed position t and
+ *          head h at rstd[h * total_positions + t]; entries of positions outside every sequence are not touched
+ *   o, d_u, eps as in la2_fwd_norm / la2_bwd_norm; rows of d_u outside every sequence are not written
+ * Workspace as for la2_fwd_varlen / la2_bwd_varlen.
+ */
+la2_status la2_fwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                               const void* q, const void* k, const void* v, const float* lambda, float eps,
+                               void* o, float* rstd, void* workspace, size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                               const void* q, const void* k, const void* v, const void* o, const float* rstd,
+                               const void* d_o, const float* lambda, void* d_u, void* dq, void* dk, void* dv,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One step of the recurrent form (Sec. 3.2.1, recursive form), for every (batch, head):
  *     kv <- lambda_h * kv + k^T v          (state updated IN PLACE)
  *     o   = q kv                           (uses the UPDATED state, i.e. includes this token)
@@ -318,6 +336,17 @@ la2_status la2_left_product_bwd(const la2_desc* desc, const void* q, const void*
 la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens,
                             int32_t qkv_dtype, const void* q, const void* k, const void* v,
                             const float* lambda, float* kv_state, void* o, void* hip_stream);
+
+/*
+ * la2_decode_multi for the normalised operator: every output row divided by sqrt(mean_j o_j^2 + eps) before it is
+ * stored (the state keeps the un-normalised recurrence), r_t handed out as by la2_fwd_norm.
+ *   eps    host scalar as for la2_fwd_norm (LA2_ERR_VALUE)
+ *   rstd   out  device fp32 dense [batch, heads, ntokens]; required
+ */
+la2_status la2_decode_multi_norm(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens,
+                                 int32_t qkv_dtype, const void* q, const void* k, const void* v,
+                                 const float* lambda, float* kv_state, float eps, void* o, float* rstd,
+                                 void* hip_stream);
 
 /*
  * Block size B (rows of the intra-block tile, Algorithm 1) of the scan kernel the library launches

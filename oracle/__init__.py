@@ -16,4 +16,6 @@ from .ref import (  # noqa: F401
     bwd_rows,
 )
 from .block_form import block_forward, block_backward, state_update_residuals  # noqa: F401
-from .norm import fwd_norm, bwd_norm, norm_backward_rows, fwd_norm_state, bwd_norm_state  # noqa: F401
+from .norm import (  # noqa: F401
+    fwd_norm, bwd_norm, norm_backward_rows, fwd_norm_state, bwd_norm_state, fwd_norm_packed, bwd_norm_packed,
+)

@@ -57,3 +57,34 @@ def bwd_norm(q, k, v, d_o, lam, eps):
     o, rstd = fwd_norm(q, k, v, lam, eps)
     du = norm_backward_rows(o, rstd, d_o)
     return ref.bwd_direct(q, k, v, du, lam)
+
+
+def fwd_norm_packed(q, k, v, lam, cu_seqlens, eps):
+    """The normalised operator over PACKED sequences: q, k, v are [total_positions, heads, d]; sequence b is the rows
+    cu_seqlens[b] .. cu_seqlens[b + 1] - 1 and a chain of its own.  Returns (o [total, heads, d], rstd [heads, total]);
+    rows outside every sequence are zero."""
+    q, k, v = (np.asarray(x, dtype=np.float64) for x in (q, k, v))
+    total, heads, _ = q.shape
+    o = np.zeros_like(q)
+    rstd = np.zeros((heads, total))
+    for b in range(len(cu_seqlens) - 1):
+        lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        if hi > lo:
+            seq = [np.ascontiguousarray(x[lo:hi].transpose(1, 0, 2))[None] for x in (q, k, v)]   # [1, heads, n, d]
+            ob, rb = fwd_norm(seq[0], seq[1], seq[2], lam, eps)
+            o[lo:hi] = ob[0].transpose(1, 0, 2)
+            rstd[:, lo:hi] = rb[0]
+    return o, rstd
+
+
+def bwd_norm_packed(q, k, v, d_o, lam, cu_seqlens, eps):
+    """(dq, dk, dv), each [total_positions, heads, d], of sum(d_o * fwd_norm_packed(...)[0]); zero outside the sequences."""
+    q, k, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, k, v, d_o))
+    grads = [np.zeros_like(q) for _ in range(3)]
+    for b in range(len(cu_seqlens) - 1):
+        lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        if hi > lo:
+            seq = [np.ascontiguousarray(x[lo:hi].transpose(1, 0, 2))[None] for x in (q, k, v, d_o)]
+            for dst, gb in zip(grads, bwd_norm(seq[0], seq[1], seq[2], seq[3], lam, eps)):
+                dst[lo:hi] = gb[0].transpose(1, 0, 2)
+    return tuple(grads)

@@ -87,6 +87,12 @@ def load():
     lib.la2_fwd_varlen.restype = ctypes.c_int
     lib.la2_bwd_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_varlen.restype = ctypes.c_int
+    lib.la2_fwd_varlen_norm.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
+    lib.la2_fwd_varlen_norm.restype = ctypes.c_int
+    lib.la2_bwd_varlen_norm.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 11 + [vp, sz, vp]
+    lib.la2_bwd_varlen_norm.restype = ctypes.c_int
+    lib.la2_decode_multi_norm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp]
+    lib.la2_decode_multi_norm.restype = ctypes.c_int
     lib.la2_left_product_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.la2_left_product_fwd.restype = ctypes.c_int
     lib.la2_left_product_bwd.argtypes = [dp] + [vp] * 9
@@ -322,6 +328,74 @@ def la2_bwd_varlen(q, k, v, d_o, lam, cu_seqlens, max_seqlen, out=None, workspac
                                   d_o.data_ptr(), lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr,
                                   ws_bytes, _stream(q)))
     return dq, dk, dv
+
+
+def la2_fwd_varlen_norm(q, k, v, lam, cu_seqlens, max_seqlen, eps=1e-6, out=None, rstd=None, workspace=None):
+    """(o, rstd) of the normalised operator over packed sequences; rstd is fp32 [heads, total_positions]."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_varlen_norm: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    if rstd is None:
+        rstd = torch.empty((q.shape[1], q.shape[0]), dtype=torch.float32, device=q.device)
+    if rstd.dtype != torch.float32 or tuple(rstd.shape) != (q.shape[1], q.shape[0]) or not rstd.is_contiguous():
+        raise ValueError("la2_fwd_varlen_norm: rstd must be a contiguous fp32 [heads, total_positions] tensor")
+    desc = _varlen_desc(q, cu_seqlens, max_seqlen)
+    ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_FWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_varlen_norm(ctypes.byref(desc), cu_seqlens.data_ptr(), q.shape[0], q.data_ptr(), k.data_ptr(),
+                                       v.data_ptr(), lam.data_ptr(), float(eps), out.data_ptr(), rstd.data_ptr(), ws_ptr,
+                                       ws_bytes, _stream(q)))
+    return out, rstd
+
+
+def la2_bwd_varlen_norm(q, k, v, o, rstd, d_o, lam, cu_seqlens, max_seqlen, out=None, d_u=None, workspace=None):
+    """(dq, dk, dv) of the normalised operator over packed sequences (o, rstd from la2_fwd_varlen_norm)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd_varlen_norm: tensors must live on the GPU")
+    _same_layout(q, k, v, o, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    if d_u is None:
+        d_u = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv, d_u)
+    if rstd.dtype != torch.float32 or tuple(rstd.shape) != (q.shape[1], q.shape[0]) or not rstd.is_contiguous():
+        raise ValueError("la2_bwd_varlen_norm: rstd must be a contiguous fp32 [heads, total_positions] tensor")
+    desc = _varlen_desc(q, cu_seqlens, max_seqlen)
+    ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_BWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd_varlen_norm(ctypes.byref(desc), cu_seqlens.data_ptr(), q.shape[0], q.data_ptr(), k.data_ptr(),
+                                       v.data_ptr(), o.data_ptr(), rstd.data_ptr(), d_o.data_ptr(), lam.data_ptr(),
+                                       d_u.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr, ws_bytes,
+                                       _stream(q)))
+    return dq, dk, dv
+
+
+def la2_decode_multi_norm(q, k, v, lam, kv_state, eps=1e-6, out=None, rstd=None):
+    """ntokens consecutive steps of the normalised operator in one launch; returns (o, rstd [b, H, T])."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_decode_multi_norm: tensors must live on the GPU")
+    b, h, t, d = q.shape
+    for x in (q, k, v):
+        if x.shape != q.shape or x.dtype != q.dtype or not x.is_contiguous():
+            raise ValueError("la2_decode_multi_norm: q, k, v must be dense [b, H, T, d] of one dtype")
+    if kv_state.dtype != torch.float32 or tuple(kv_state.shape) != (b, h, d, d) or not kv_state.is_contiguous():
+        raise ValueError("la2_decode_multi_norm: kv_state must be dense fp32 [b, H, d, d]")
+    if out is None:
+        out = torch.empty_like(q)
+    if rstd is None:
+        rstd = torch.empty((b, h, t), dtype=torch.float32, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_decode_multi_norm(b, h, d, t, _dtype_code(q), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                         lam.data_ptr(), kv_state.data_ptr(), float(eps), out.data_ptr(), rstd.data_ptr(),
+                                         _stream(q)))
+    return out, rstd
 
 
 def _state(t, q, name):

@@ -718,9 +718,13 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
                             workspace, workspace_bytes, hip_stream);
 }
 
-la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
-                          const void* k, const void* v, const float* lambda, void* o, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// la2_fwd_varlen, and with rstd != nullptr the same with the Norm epilogue (eps validated by the caller)
+la2_status fwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
+                           const void* k, const void* v, const float* lambda, void* o, float* rstd, float eps,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if (total_positions < 0) return LA2_ERR_SHAPE;
@@ -738,6 +742,9 @@ la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   ScanArgs a{q, k, v, o};
   a.cu = cu_seqlens;
+  a.rstd = rstd;   // packed layout [heads][total_positions]
+  a.eps = eps;
+  a.rstd_stride = (int)total_positions;
   if (pl.wg_pairs > 0) {   // the pair map of the compact grid, in front of the states
     la2::ScanParams mp = base_params(desc, pl, lambda, nullptr, cu_seqlens);
     mp.wg_pairs = pl.wg_pairs;
@@ -748,6 +755,59 @@ la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64
     a.map = map;
   }
   return run_scan(desc, pl, false, a, lambda, static_cast<char*>(workspace) + pl.map_bytes, s);
+}
+}  // namespace
+
+extern "C" {
+
+la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
+                          const void* k, const void* v, const float* lambda, void* o, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, o, nullptr, 0.f, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+la2_status la2_fwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                               const void* q, const void* k, const void* v, const float* lambda, float eps, void* o,
+                               float* rstd, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  // r is laid out [heads][total_positions]: the total has to be the packed tensors' real extent here
+  if (total_positions <= 0 || total_positions > 0x7FFFFFFF) return LA2_ERR_SHAPE;
+  if (rstd == nullptr) return LA2_ERR_NULL;
+  if (!aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;
+  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, o, rstd, eps, workspace, workspace_bytes,
+                         hip_stream);
+}
+
+la2_status la2_bwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                               const void* q, const void* k, const void* v, const void* o, const float* rstd,
+                               const void* d_o, const float* lambda, void* d_u, void* dq, void* dk, void* dv,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // as la2_fwd_varlen
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  if (total_positions <= 0 || total_positions > 0x7FFFFFFF) return LA2_ERR_SHAPE;
+  if (!cu_seqlens || !q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(d_o, 16) ||
+      !aligned(d_u, 16) || !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4) ||
+      !aligned(rstd, 4) || !aligned(cu_seqlens, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const size_t need = la2_varlen_workspace_bytes(desc, total_positions, LA2_OP_BWD);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
+    return LA2_ERR_WORKSPACE;
+  // the row pass over all packed positions that belong to a sequence (one "chain" per head), then Algorithm 2 on d_u
+  la2::NormBwdParams np{o, d_o, rstd, d_u, 0, desc->stride_h, desc->stride_n, 1, desc->heads, (int32_t)total_positions,
+                        0, (int32_t)total_positions};
+  np.bounds = cu_seqlens;
+  np.nbounds = desc->batch;
+  if (la2::launch_norm_bwd_rows(desc->head_dim, desc->dtype, np, reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return LA2_ERR_LAUNCH;
+  return la2_bwd_varlen(desc, cu_seqlens, total_positions, q, k, v, d_u, lambda, dq, dk, dv, workspace, workspace_bytes,
+                        hip_stream);
 }
 
 la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
@@ -872,16 +932,20 @@ la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, 
   return decode_step_impl(batch, heads, head_dim, qkv_dtype, q, k, v, lambda, kv_state, o, true, eps, hip_stream);
 }
 
-la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,
-                            const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
-                            void* o, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// la2_decode_multi, and with rstd != nullptr the same with the Norm epilogue on every output row
+la2_status decode_multi_impl(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,
+                             const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
+                             float* rstd, float eps, void* o, void* hip_stream) {
   if (qkv_dtype != LA2_F32 && !is16(qkv_dtype)) return LA2_ERR_DTYPE;
   if (batch < 0 || heads < 0 || ntokens < 0 || !supported_head_dim(head_dim)) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads > (int64_t)1 << 24 || ntokens > 65536) return LA2_ERR_SHAPE;
   if ((int64_t)batch * heads * ntokens == 0) return LA2_OK;  // nothing to do
   if (!q || !k || !v || !lambda || !kv_state || !o) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(kv_state, 16) ||
-      !aligned(lambda, 4))
+      !aligned(lambda, 4) || !aligned(rstd, 4))
     return LA2_ERR_STRIDE_ALIGN;
   la2_desc d;
   la2_desc_dense(&d, batch, heads, ntokens, head_dim, (la2_dtype)qkv_dtype);
@@ -890,23 +954,52 @@ la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int3
   // are 4-5x faster per position.  Not when that launch would be sequence-chunked: there is no workspace here.
   const la2_desc wb = whole_blocks(&d);
   if (wb.seqlen > 0 && make_plan(&wb).workspace == 0)
-    return la2_fwd_state(&d, q, k, v, lambda, kv_state, o, kv_state, nullptr, 0, hip_stream);
+    return fwd_state_impl(&d, q, k, v, lambda, kv_state, o, kv_state, rstd, eps, nullptr, 0, hip_stream);
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   if (wide(head_dim) && is16(qkv_dtype)) {   // the block kernel of these head dimensions, in one chunk
     const Plan one{1, ((ntokens + 63) / 64) * 64, 0};
     ScanArgs a{q, k, v, o};
     a.init = kv_state;
     a.fin = kv_state;
-    return run_scan(&d, one, false, a, lambda, nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+    a.rstd = rstd;
+    a.eps = eps;
+    a.rstd_stride = ntokens;
+    return run_scan(&d, one, false, a, lambda, nullptr, s);
   }
   la2::RecurParams r = recur_params(&d, lambda, 0, ntokens, false);
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = kv_state;
   r.fin[0] = kv_state;
-  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  // 16-bit data: one block kernel launch (MFMA); fp32: token by token in fp32
-  const hipError_t e = is16(qkv_dtype) ? la2::launch_tail_bf16(qkv_dtype, head_dim, batch, r, s)
-                                       : la2::launch_recur(head_dim, qkv_dtype, batch, 1, r, s);
-  return e == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  if (is16(qkv_dtype)) {   // 16-bit data: one block kernel launch (MFMA), with the epilogue
+    r.rstd = rstd;
+    r.eps = eps;
+    r.rstd_stride = ntokens;
+    return la2::launch_tail_bf16(qkv_dtype, head_dim, batch, r, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  }
+  // fp32: token by token in fp32, then (Norm) a row pass in place over the rows just written
+  if (la2::launch_recur(head_dim, qkv_dtype, batch, 1, r, s) != hipSuccess) return LA2_ERR_LAUNCH;
+  if (rstd == nullptr) return LA2_OK;
+  const la2::NormBwdParams np{o, nullptr, rstd, o, d.stride_b, d.stride_h, d.stride_n, batch, heads, ntokens, 0, ntokens};
+  return la2::launch_norm_fwd_rows(head_dim, qkv_dtype, np, eps, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+}
+}  // namespace
+
+extern "C" {
+
+la2_status la2_decode_multi(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,
+                            const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
+                            void* o, void* hip_stream) {
+  return decode_multi_impl(batch, heads, head_dim, ntokens, qkv_dtype, q, k, v, lambda, kv_state, nullptr, 0.f, o,
+                           hip_stream);
+}
+
+la2_status la2_decode_multi_norm(int32_t batch, int32_t heads, int32_t head_dim, int32_t ntokens, int32_t qkv_dtype,
+                                 const void* q, const void* k, const void* v, const float* lambda, float* kv_state,
+                                 float eps, void* o, float* rstd, void* hip_stream) {
+  if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
+  if (batch > 0 && heads > 0 && ntokens > 0 && rstd == nullptr) return LA2_ERR_NULL;
+  return decode_multi_impl(batch, heads, head_dim, ntokens, qkv_dtype, q, k, v, lambda, kv_state, rstd, eps, o,
+                           hip_stream);
 }
 
 const char* la2_status_string(la2_status status) {

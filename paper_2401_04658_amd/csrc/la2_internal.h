@@ -122,6 +122,13 @@ __device__ __forceinline__ void chain_extent(const ScanParams& p, int bi, int hi
   base = (int64_t)(((uint64_t)hi32 << 32) | lo);
 }
 
+// Where a chain's r values start in p.rstd: dense batches [batch * heads][rstd_stride positions]; packed batches
+// [heads][rstd_stride = total positions], a sequence's values at its packed positions.
+__device__ __forceinline__ int64_t rstd_chain_offset(const ScanParams& p, int bi, int hi) {
+  if (p.cu_seqlens != nullptr) return (int64_t)hi * p.rstd_stride + p.cu_seqlens[bi];
+  return ((int64_t)bi * p.heads + hi) * p.rstd_stride;
+}
+
 // Norm epilogue, shared by the scan kernels.  A 32 x 32 output tile sits in MFMA accumulators transposed
 // (lane = position l32, 16 features per lane, the other 16 in lane l32 + 32); the NP waves that hold the
 // feature tiles of one row exchange their partial sums of squares through `red` ([32 rows][NP] floats per
@@ -217,6 +224,10 @@ struct NormBwdParams {
   int64_t stride_b, stride_h, stride_n;
   int32_t batch, heads, n;
   int32_t t0, rstd_stride;
+  // packed batch (rows = all packed positions, batch = 1): only positions row_lo <= t < row_hi belong to a
+  // sequence, with row_lo = bounds[0], row_hi = bounds[nbounds] read on the device (cu_seqlens); nullptr: all rows
+  const int32_t* bounds;
+  int32_t nbounds;
 };
 hipError_t launch_norm_bwd_rows(int head_dim, int dtype, const NormBwdParams& p, hipStream_t s);
 // The forward normalisation as a pass of its own, in place, over the same rows: o <- o r with

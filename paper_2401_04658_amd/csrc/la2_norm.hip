@@ -63,8 +63,13 @@ __global__ __launch_bounds__(kThreads) void norm_rows_kernel(NormBwdParams p, fl
   const int64_t rows = (int64_t)p.batch * p.heads * p.n;
   const int64_t row = (int64_t)blockIdx.x * ROWS + threadIdx.x / LPR;
   const int piece = threadIdx.x % LPR;
-  const bool live = row < rows;                 // whole row groups are live or not: the exchanges stay inside a group
-  const int64_t rr = live ? row : 0;
+  bool live = row < rows;                       // whole row groups are live or not: the exchanges stay inside a group
+  int64_t rr = live ? row : 0;
+  if (p.bounds != nullptr) {                    // packed batch: rows in front of the first and behind the last sequence
+    const int64_t t = rr % p.n;
+    live = live && t >= p.bounds[0] && t < p.bounds[p.nbounds];
+    if (!live) rr = (rr / p.n) * p.n + min((int64_t)p.bounds[0], (int64_t)p.n - 1);
+  }
   const int64_t chain = rr / p.n, pos = p.t0 + rr % p.n;
   const int64_t ri = chain * p.rstd_stride + pos;   // this row's r
   const int64_t off = (chain / p.heads) * p.stride_b + (chain % p.heads) * p.stride_h + pos * p.stride_n + piece * N;

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kThreads, 1) void scan_bf16_kernel(ScanParams p) {
   const float l2 = log2f(p.lambda[hi]);
   // Norm epilogue: r of this chain's positions; stores past position n - 1 are dropped
   const __amdgpu_buffer_rsrc_t brs =
-      make_rsrc(NORM ? p.rstd + (int64_t)chain * p.rstd_stride : nullptr, NORM ? (uint32_t)n * 4u : 0u);
+      make_rsrc(NORM ? p.rstd + rstd_chain_offset(p, bi, hi) : nullptr, NORM ? (uint32_t)n * 4u : 0u);
 
   const int nblocks = (n + kB - 1) / kB;
   const int cb = p.chunk_tokens / kB;

@@ -103,7 +103,7 @@ void scan_bf16_half_kernel(ScanParams p) {
   const float l2 = log2f(p.lambda[hi]);
   // Norm epilogue: r of this chain's positions; stores past position n - 1 are dropped
   const __amdgpu_buffer_rsrc_t brs =
-      make_rsrc(NORM ? p.rstd + (int64_t)chain * p.rstd_stride : nullptr, NORM ? (uint32_t)n * 4u : 0u);
+      make_rsrc(NORM ? p.rstd + rstd_chain_offset(p, bi, hi) : nullptr, NORM ? (uint32_t)n * 4u : 0u);
 
   const int nblocks = (n + B - 1) / B;
   const int cb = p.chunk_tokens / B;

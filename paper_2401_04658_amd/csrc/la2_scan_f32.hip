@@ -234,7 +234,7 @@ __global__ __launch_bounds__(2 * D, 1) void scan_f32_kernel(ScanParams p) {
         const float r = norm_collect<NT>(sRed, l32, 1.f / (float)D, p.eps);
 #pragma unroll
         for (int v = 0; v < 16; v++) acc[v] *= r;
-        if (dvt == 0 && hh == 0 && pos < n) p.rstd[(int64_t)chain * p.rstd_stride + pos] = r;
+        if (dvt == 0 && hh == 0 && pos < n) p.rstd[rstd_chain_offset(p, bi, hi) + pos] = r;
       }
       // output: lane = position l32, elements v = 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
       if (pos < n) {

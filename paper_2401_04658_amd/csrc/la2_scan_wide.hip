@@ -170,7 +170,7 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
         const float r = norm_collect<NT>(sRed, l32, 1.f / (float)D, p.eps);
 #pragma unroll
         for (int v = 0; v < 16; v++) acc[v] *= r;
-        if (dvt == 0 && hh == 0 && pos < n) p.rstd[(int64_t)chain * p.rstd_stride + pos] = r;
+        if (dvt == 0 && hh == 0 && pos < n) p.rstd[rstd_chain_offset(p, bi, hi) + pos] = r;
       }
       if (pos < n) {
         E* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;

@@ -418,6 +418,28 @@ def test_packed_batches_of_unequal_lengths_are_cut_into_chunks(lib):
     assert lib.la2_varlen_workspace_bytes(ctypes.byref(short), 4000 * 40, 0) == 0
 
 
+def test_packed_norm_and_multi_token_norm_validate_before_any_launch(lib):
+    vp, i64, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float
+    lib.la2_fwd_varlen_norm.argtypes = [vp, vp, i64, vp, vp, vp, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.la2_fwd_varlen_norm.restype = ctypes.c_int
+    lib.la2_bwd_varlen_norm.argtypes = [vp, vp, i64] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
+    lib.la2_bwd_varlen_norm.restype = ctypes.c_int
+    lib.la2_decode_multi_norm.argtypes = [ctypes.c_int32] * 5 + [vp] * 5 + [f32, vp, vp, vp]
+    lib.la2_decode_multi_norm.restype = ctypes.c_int
+    d = dense(lib, 5, 2, 300, 64, binding.LA2_BF16)
+    d.stride_b, d.stride_h, d.stride_n = 0, 64, 128
+    ref = ctypes.byref(d)
+    fn = lambda total=900, eps=1e-6, cu=P, rstd=P, q=P: lib.la2_fwd_varlen_norm(ref, cu, total, q, P, P, P, eps, P, rstd, None, 0, None)
+    assert fn(eps=-1.0) == E_VALUE and fn(total=0) == E_SHAPE and fn(total=1 << 31) == E_SHAPE
+    assert fn(rstd=None) == E_NULL and fn(cu=None) == E_NULL and fn(q=None) == E_NULL and fn(rstd=P + 2) == E_ALIGN
+    bn = lambda total=900, o=P, rstd=P, d_u=P: lib.la2_bwd_varlen_norm(ref, P, total, P, P, P, o, rstd, P, P, d_u, P, P, P, None, 0, None)
+    assert bn(total=0) == E_SHAPE and bn(o=None) == E_NULL and bn(rstd=None) == E_NULL and bn(d_u=None) == E_NULL
+    assert bn(d_u=P + 8) == E_ALIGN
+    dm = lambda eps=1e-6, rstd=P, q=P, T=8, hd=128: lib.la2_decode_multi_norm(2, 2, hd, T, 1, q, P, P, P, P, eps, P, rstd, None)
+    assert dm(eps=float("nan")) == E_VALUE and dm(rstd=None) == E_NULL and dm(q=None) == E_NULL and dm(hd=100) == E_SHAPE
+    assert dm(T=0, rstd=None, q=None) == OK and dm(rstd=P + 2) == E_ALIGN
+
+
 def test_bwd_saved_checks_the_forward_workspace(lib):
     vp = ctypes.c_void_p
     lib.la2_bwd_saved.argtypes = [vp] * 13 + [ctypes.c_size_t, ctypes.c_int32, vp, ctypes.c_size_t, vp]

@@ -128,3 +128,79 @@ def test_normalised_decode_steps_follow_the_segment(d, dtype):
     ro, _, rs = oracle.fwd_norm_state(q, k, v, lam, EPS, to64(t["kv_init"]))
     assert_close("d%d %s prefill + decode o" % (d, dtype), torch.cat(outs, dim=2), ro, dtype)
     assert_close("d%d %s prefill + decode state" % (d, dtype), state, rs, dtype)
+
+
+# ---- the normalised operator over packed sequences and in multi-token decode ---------------------------------------
+def _packed(lengths, H, d, dtype, seed, lead=0, trail=0):
+    import numpy as np
+    total = lead + int(sum(lengths)) + trail
+    t = workloads.Workload("packed", 1, H, total, d, dtype, seed=seed, backward=True).tensors()
+    out = {name: t[name][0].permute(1, 0, 2).contiguous() for name in ("q", "k", "v", "d_o")}
+    out["lam"] = t["lam"]
+    cu = np.concatenate([[lead], lead + np.cumsum(lengths)]).astype(np.int32)
+    return out, cu
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float16, 128), (torch.float32, 64),
+                                     (torch.bfloat16, 96)])
+@pytest.mark.parametrize("chunk", [0, 128])
+def test_norm_over_packed_sequences(dtype, d, chunk):
+    import numpy as np
+    lengths = [70, 0, 1, 31, 300, 517, 64]
+    t, cu = _packed(lengths, 2, d, dtype, seed=900 + d, lead=3, trail=5)
+    g = {k_: v_.to(DEV) for k_, v_ in t.items()}
+    cu_g = torch.from_numpy(cu).to(DEV)
+    eps = 1e-5
+    binding.la2_set_chunk_tokens(chunk)
+    try:
+        o = torch.full_like(g["q"], float("nan"))
+        rstd = torch.full((2, g["q"].shape[0]), float("nan"), dtype=torch.float32, device=DEV)
+        binding.la2_fwd_varlen_norm(g["q"], g["k"], g["v"], g["lam"], cu_g, max(lengths), eps, out=o, rstd=rstd)
+        grads = tuple(torch.full_like(g["q"], float("nan")) for _ in range(3))
+        d_u = torch.full_like(g["q"], float("nan"))
+        binding.la2_bwd_varlen_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], cu_g, max(lengths), out=grads, d_u=d_u)
+        torch.cuda.synchronize()
+    finally:
+        binding.la2_set_chunk_tokens(0)
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    ro, rr = oracle.fwd_norm_packed(q, k, v, lam, cu, eps)
+    lo, hi = int(cu[0]), int(cu[-1])
+    tag = "packed norm %s d%d chunk%d" % (dtype, d, chunk)
+    assert_close(tag + " o", o[lo:hi], ro[lo:hi], dtype)
+    assert_close(tag + " rstd", rstd[:, lo:hi], rr[:, lo:hi], dtype)
+    # the backward pass from the GPU's own (rounded) o and rstd, as a training step has them
+    du_ref = oracle.norm_backward_rows(to64(o)[lo:hi], to64(rstd)[:, lo:hi].T, do[lo:hi])
+    assert_close(tag + " d_u", d_u[lo:hi], du_ref, dtype)
+    for b in range(len(lengths)):
+        s0, s1 = int(cu[b]), int(cu[b + 1])
+        if s1 == s0:
+            continue
+        seq = [np.ascontiguousarray(x[s0:s1].transpose(1, 0, 2))[None] for x in (q, k, v)]
+        du_seq = np.ascontiguousarray(to64(d_u)[s0:s1].transpose(1, 0, 2))[None]
+        for name, got, ref in zip(("dq", "dk", "dv"), grads, oracle.bwd_direct(seq[0], seq[1], seq[2], du_seq, lam)):
+            assert_close("%s seq %d %s" % (tag, b, name), got[s0:s1].permute(1, 0, 2)[None], ref, dtype)
+    # nothing outside the sequences is written
+    for x in (o, d_u) + grads:
+        assert torch.isnan(x[:lo].float()).all() and torch.isnan(x[hi:].float()).all()
+    assert torch.isnan(rstd[:, :lo]).all() and torch.isnan(rstd[:, hi:]).all()
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 128), (torch.float16, 256),
+                                     (torch.float32, 96)])
+@pytest.mark.parametrize("T", [1, 8, 33, 70])
+def test_multi_token_decode_with_norm(dtype, d, T):
+    b, H = 3, 2
+    t = workloads.Workload("dm", b, H, T, d, dtype, seed=950 + d + T, backward=False).tensors()
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(7)
+    kv0 = torch.randn((b, H, d, d), generator=gen, dtype=torch.float32) * 0.2
+    g = {k_: v_.to(DEV) for k_, v_ in t.items()}
+    state = kv0.to(DEV)
+    eps = 1e-5
+    o, rstd = binding.la2_decode_multi_norm(g["q"], g["k"], g["v"], g["lam"], state, eps)
+    torch.cuda.synchronize()
+    ro, rr, rs = oracle.fwd_norm_state(to64(t["q"]), to64(t["k"]), to64(t["v"]), to64(t["lam"]), eps, kv_init=to64(kv0))
+    tag = "decode multi norm %s d%d T%d" % (dtype, d, T)
+    assert_close(tag + " o", o, ro, dtype)
+    assert_close(tag + " rstd", rstd, rr, dtype)
+    assert_close(tag + " state", state, rs, dtype)

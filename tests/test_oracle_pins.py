@@ -556,3 +556,45 @@ def test_norm_gradients_are_orthogonal_to_their_inputs_at_eps_zero():
     assert np.max(np.abs(np.sum(du * o, axis=-1))) <= 1e-12 * np.max(np.abs(du))
     dq2, _, _ = oracle.bwd_norm(q, k, v, do, lam, 0.5)
     assert abs(np.sum(dq2 * q)) > 1e-3 * np.sum(np.abs(dq2 * q))
+
+
+def test_norm_packed_is_the_dense_operator_sequence_by_sequence():
+    """Packed sequences are chains of their own: equal lengths reproduce the dense batch; a sequence's rows do not
+    depend on its neighbours; finite differences of the packed loss agree with the packed gradients."""
+    H, d, eps = 2, 3, 1e-3
+    lam = np.array([0.7, 0.95])
+    # equal lengths == dense batch
+    b, n = 3, 5
+    q, k, v, g = (_rand((b, H, n, d), s) for s in (90, 91, 92, 93))
+    pack = lambda x: np.ascontiguousarray(x.transpose(0, 2, 1, 3).reshape(b * n, H, d))
+    cu = np.arange(0, (b + 1) * n, n)
+    o_p, r_p = oracle.fwd_norm_packed(pack(q), pack(k), pack(v), lam, cu, eps)
+    o_d, r_d = oracle.fwd_norm(q, k, v, lam, eps)
+    assert np.array_equal(o_p, pack(o_d))
+    assert np.array_equal(r_p, r_d.transpose(1, 0, 2).reshape(H, b * n))
+    for got, ref in zip(oracle.bwd_norm_packed(pack(q), pack(k), pack(v), pack(g), lam, cu, eps), oracle.bwd_norm(q, k, v, g, lam, eps)):
+        assert np.array_equal(got, pack(ref))
+    # unequal lengths with a gap in front: neighbours do not interact, rows outside stay zero
+    cu = np.array([2, 6, 6, 13])
+    total = 15
+    q, k, v, g = (_rand((total, H, d), s) for s in (94, 95, 96, 97))
+    o1, r1 = oracle.fwd_norm_packed(q, k, v, lam, cu, eps)
+    k2 = k.copy()
+    k2[6:13] += 1.0                      # the last sequence changes
+    o2, _ = oracle.fwd_norm_packed(q, k2, v, lam, cu, eps)
+    assert np.array_equal(o1[:6], o2[:6]) and not np.allclose(o1[6:13], o2[6:13])
+    assert np.all(o1[:2] == 0) and np.all(o1[13:] == 0) and np.all(r1[:, :2] == 0)
+    dq, dk, dv = oracle.bwd_norm_packed(q, k, v, g, lam, cu, eps)
+    loss = lambda q_, k_, v_: float(np.sum(oracle.fwd_norm_packed(q_, k_, v_, lam, cu, eps)[0] * g))
+    rng = np.random.default_rng(5)
+    for name, x, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        for _ in range(6):
+            idx = (int(rng.integers(0, total)), int(rng.integers(0, H)), int(rng.integers(0, d)))
+            h = 1e-6
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += h
+            xm[idx] -= h
+            args_p = {"q": q, "k": k, "v": v}; args_m = dict(args_p)
+            args_p[name], args_m[name] = xp, xm
+            fd = (loss(args_p["q"], args_p["k"], args_p["v"]) - loss(args_m["q"], args_m["k"], args_m["v"])) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
