@@ -15,12 +15,16 @@ using namespace bf16k;
 // buffers, the tiles of block it + NBUF - 1 stream in while block it is used.  Every block's loads are
 // issued unconditionally (past the chunk's end as dummy loads of one cache line), so the count of
 // outstanding loads is the same in every iteration and one s_waitcnt immediate serves.
+// Two waves per SIMD: 2 NT waves (8 at d = 128, 4 at d = 64); wave w owns value features 32 (w % NT) .. + 31 and
+// the key-feature tiles of half w / NT of the state slice, so that one wave's LDS and MFMA latencies hide behind
+// the other's instructions (a wave issues one instruction at a time).
 template <typename E, int D, bool REV, int NBUF>
-__global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParams p) {
+__global__ __launch_bounds__(128 * (D / 32), 1) void chunk_state_bf16_kernel(ScanParams p) {
   static_assert(NBUF >= 3 && NBUF <= 5, "the block loop below is unrolled for 3 to 5 buffers");
   using C = Cfg<D>;
   constexpr int NT = C::NT, TILE = C::TILE;
-  using Loader = TileLoader<D, 2>;
+  constexpr int KT = NT / 2;   // key-feature tiles per wave
+  using Loader = TileLoader<D, 2, kB, 2 * NT>;
   __shared__ __attribute__((aligned(1024))) E sT[NBUF][2][TILE];   // [Y, Z]
   constexpr int NDMA = 2 * Loader::DMA_PER_WAVE;   // direct loads per wave and block
   constexpr int VM_YOUNGER = (NBUF - 2) * NDMA;    // loads younger than those of block it + 1 when it waits for them
@@ -28,7 +32,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   constexpr int WAIT_NEXT_TILES = (VM_YOUNGER & 15) | ((VM_YOUNGER >> 4) << 14) | 0x0F70;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
-  const int dvt = w % NT;
+  const int dvt = w % NT, kt0 = (w / NT) * KT;
   int bi, hi, chunk, slot_stride;
   int64_t slot;
   if (!place_workgroup(p, (int)blockIdx.x, bi, hi, chunk, slot, slot_stride)) return;
@@ -49,9 +53,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
   const LaneAddr<D> la(l);
   const UpdateDecay<REV> decay(l2, hh);
-  f32x16 kv[NT];
+  f32x16 kv[KT];
 #pragma unroll
-  for (int t = 0; t < NT; t++) kv[t] = zero16();
+  for (int t = 0; t < KT; t++) kv[t] = zero16();
 
   // loads of the chunk's block number `it` (real, or dummy when the chunk has no such block) into `buf`
   auto issue_block = [&](E (*buf)[TILE], int it) __attribute__((always_inline)) {
@@ -74,12 +78,12 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
     issue_block(sT[(cur + NBUF - 1) % NBUF], it + NBUF - 1);   // that buffer was block it - 1's
     const E* tY = sT[cur][0];
     const E* tZ = sT[cur][1];
-    ex8<E> zf[4], yt[NT][4];   // [16-row k-step of the block]
+    ex8<E> zf[4], yt[KT][4];   // [16-row k-step of the block]
 #pragma unroll
     for (int k = 0; k < 4; k++) {
       zf[k] = la.read_cols(tZ, 16 * k, dvt);
 #pragma unroll
-      for (int t = 0; t < NT; t++) yt[t][k] = la.read_cols(tY, 16 * k, t);
+      for (int t = 0; t < KT; t++) yt[t][k] = la.read_cols(tY, 16 * k, kt0 + t);
     }
     __builtin_amdgcn_sched_barrier(0);
     // Only the state after the chunk's last block is wanted, so instead of decaying the running sum by
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
     for (int k = 0; k < 4; k++) {
       const ex8<E> zd = decay.apply(zf[k], 16 * k, blk_decay);
 #pragma unroll
-      for (int t = 0; t < NT; t++) kv[t] = mfma(yt[t][k], zd, kv[t]);
+      for (int t = 0; t < KT; t++) kv[t] = mfma(yt[t][k], zd, kv[t]);
     }
     if (has_next) {
       __builtin_amdgcn_s_waitcnt(WAIT_NEXT_TILES);
@@ -110,13 +114,11 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_state_bf16_kernel(ScanParam
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy loads before the LDS is given up
 
-  if (w < NT) {   // for d = 64 waves w and w + 2 hold the same slice
-    float* gs = p.states + slot * (D * D);   // a chunk with a successor: its chain has state slots
+  float* gs = p.states + slot * (D * D);   // a chunk with a successor: its chain has state slots
 #pragma unroll
-    for (int t = 0; t < NT; t++)
+  for (int t = 0; t < KT; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) gs[state_index<D>(dvt, l32, hh, t, v, false)] = kv[t][v];
-  }
+    for (int v = 0; v < 16; v++) gs[state_index<D>(dvt, l32, hh, kt0 + t, v, false)] = kv[t][v];
 }
 
 // In place: states[chain][j] (local state of chunk j) -> start state of chunk j.
@@ -252,13 +254,13 @@ namespace {
 template <typename E>
 hipError_t launch_chunk_states(int head_dim, bool reverse, const ScanParams& p, hipStream_t s) {
   const int64_t grid = p.wg_map != nullptr ? (int64_t)p.wg_pairs * p.heads : (int64_t)p.batch * p.heads * p.nchunks;
-  dim3 g((unsigned)grid), b(kThreads);
+  dim3 g((unsigned)grid);
   if (head_dim == 128) {
-    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, true, 4>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, false, 4>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, true, 4>), g, dim3(512), 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 128, false, 4>), g, dim3(512), 0, s, p);
   } else {
-    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 64, true, 4>), g, b, 0, s, p);
-    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 64, false, 4>), g, b, 0, s, p);
+    if (reverse) hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 64, true, 4>), g, dim3(256), 0, s, p);
+    else         hipLaunchKernelGGL((chunk_state_bf16_kernel<E, 64, false, 4>), g, dim3(256), 0, s, p);
   }
   return hipGetLastError();
 }
