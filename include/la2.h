@@ -222,7 +222,7 @@ la2_status la2_bwd_state_norm(const la2_desc* desc, const void* q, const void* k
  *                    extent), or 0 if not known; negative: LA2_ERR_SHAPE.  A planning hint only: the lengths
  *                    stay on the device, and with it the host can tell a batch of about equal lengths from one
  *                    whose longest sequence would run long after all the others have finished.  Such a batch is
- *                    cut into sequence chunks (an eighth of desc->seqlen) although it has chains enough to
+ *                    cut into sequence chunks (a quarter of desc->seqlen) although it has chains enough to
  *                    fill the device; the short sequences are single chunks and pay nothing for it.
  * Everything else as for la2_fwd / la2_bwd.  Workspace: la2_varlen_workspace_bytes(desc, total_positions, op) with
  * op = LA2_OP_FWD or LA2_OP_BWD (with total_positions = 0: la2_workspace_bytes(desc, op)).
@@ -236,6 +236,31 @@ la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64
                           const void* q, const void* k, const void* v, const void* d_o, const float* lambda,
                           void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                           void* hip_stream);
+
+/*
+ * Packed sequences as SEGMENTS of longer ones (Sec. 3.2.1, recursive form: what a sequence's past contributes is
+ * its state): la2_fwd_varlen / la2_bwd_varlen with the state arguments of la2_fwd_state / la2_bwd_state, one state
+ * per (sequence, head).  A prefill over a packed batch of prompts hands kv_final to la2_decode_step; a long
+ * prompt can be fed in pieces, each call starting from the state the previous one left.
+ *   kv_init     in   device fp32 [batch, heads, head_dim, head_dim] dense (sequence b, head h at
+ *               ((b * heads + h) * head_dim + i) * head_dim + j, i = key feature, j = value feature), or NULL: zero
+ *   kv_final    out  same layout, or NULL: the state right after each sequence's last position, whatever its length
+ *   d_kv_final  in   gradient with respect to kv_final, or NULL: zero
+ *   d_kv_init   out  gradient with respect to kv_init, or NULL: not wanted
+ * All state pointers 16-byte aligned (LA2_ERR_STRIDE_ALIGN).  A sequence of length 0 passes its state (its state's
+ * gradient) through.  Data types LA2_BF16 and LA2_F16 (LA2_ERR_DTYPE otherwise) at head_dim 64 and 128
+ * (LA2_ERR_SHAPE otherwise): the kernels of these form the state at a sequence end that is not a block boundary
+ * inside the block loop.  With every state pointer NULL the calls are la2_fwd_varlen / la2_bwd_varlen.
+ * Workspace as for la2_fwd_varlen / la2_bwd_varlen.
+ */
+la2_status la2_fwd_varlen_state(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                                const void* q, const void* k, const void* v, const float* lambda,
+                                const float* kv_init, void* o, float* kv_final, void* workspace,
+                                size_t workspace_bytes, void* hip_stream);
+la2_status la2_bwd_varlen_state(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                                const void* q, const void* k, const void* v, const void* d_o, const float* lambda,
+                                const float* kv_init, const float* d_kv_final, void* dq, void* dk, void* dv,
+                                float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * The normalised operator (eq. (2), Norm read as in la2_fwd_norm) over packed sequences: la2_fwd_norm / la2_bwd_norm

@@ -87,6 +87,10 @@ def load():
     lib.la2_fwd_varlen.restype = ctypes.c_int
     lib.la2_bwd_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.la2_bwd_varlen.restype = ctypes.c_int
+    lib.la2_fwd_varlen_state.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.la2_fwd_varlen_state.restype = ctypes.c_int
+    lib.la2_bwd_varlen_state.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 11 + [vp, sz, vp]
+    lib.la2_bwd_varlen_state.restype = ctypes.c_int
     lib.la2_fwd_varlen_norm.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.la2_fwd_varlen_norm.restype = ctypes.c_int
     lib.la2_bwd_varlen_norm.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 11 + [vp, sz, vp]
@@ -328,6 +332,68 @@ def la2_bwd_varlen(q, k, v, d_o, lam, cu_seqlens, max_seqlen, out=None, workspac
                                   d_o.data_ptr(), lam.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws_ptr,
                                   ws_bytes, _stream(q)))
     return dq, dk, dv
+
+
+def _packed_state(t, q, cu_seqlens, name):
+    """A dense fp32 [sequences, H, d, d] state tensor (or None) -> pointer argument."""
+    if t is None:
+        return None
+    nseq, h, d = cu_seqlens.numel() - 1, q.shape[1], q.shape[2]
+    if t.dtype != torch.float32 or tuple(t.shape) != (nseq, h, d, d) or not t.is_contiguous() or t.device != q.device:
+        raise ValueError("%s must be dense fp32 [sequences, H, d, d] on the tensors' device" % name)
+    return ctypes.c_void_p(t.data_ptr()) if t.numel() else None
+
+
+def la2_fwd_varlen_state(q, k, v, lam, cu_seqlens, max_seqlen, kv_init=None, want_final=True, out=None, kv_final=None,
+                         workspace=None):
+    """Packed sequences as segments: o and every sequence's state after its last position, each started from its
+    kv_init (fp32 [sequences, H, d, d], None = zero).  Returns (o, kv_final or None)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_fwd_varlen_state: tensors must live on the GPU")
+    _same_layout(q, k, v)
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, out)
+    desc = _varlen_desc(q, cu_seqlens, max_seqlen)
+    if want_final and kv_final is None:
+        kv_final = torch.empty((cu_seqlens.numel() - 1, q.shape[1], q.shape[2], q.shape[2]), dtype=torch.float32,
+                               device=q.device)
+    ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_FWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_fwd_varlen_state(ctypes.byref(desc), cu_seqlens.data_ptr(), q.shape[0], q.data_ptr(), k.data_ptr(),
+                                        v.data_ptr(), lam.data_ptr(), _packed_state(kv_init, q, cu_seqlens, "kv_init"),
+                                        out.data_ptr(),
+                                        _packed_state(kv_final, q, cu_seqlens, "kv_final") if want_final else None,
+                                        ws_ptr, ws_bytes, _stream(q)))
+    return out, (kv_final if want_final else None)
+
+
+def la2_bwd_varlen_state(q, k, v, d_o, lam, cu_seqlens, max_seqlen, kv_init=None, d_kv_final=None, want_d_kv_init=True,
+                         out=None, d_kv_init=None, workspace=None):
+    """Backward of la2_fwd_varlen_state.  Returns (dq, dk, dv, d_kv_init or None)."""
+    lib = load()
+    if not q.is_cuda:
+        raise ValueError("la2_bwd_varlen_state: tensors must live on the GPU")
+    _same_layout(q, k, v, d_o)
+    if out is None:
+        out = tuple(torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device) for _ in range(3))
+    dq, dk, dv = out
+    _same_layout(q, dq, dk, dv)
+    desc = _varlen_desc(q, cu_seqlens, max_seqlen)
+    if want_d_kv_init and d_kv_init is None:
+        d_kv_init = torch.empty((cu_seqlens.numel() - 1, q.shape[1], q.shape[2], q.shape[2]), dtype=torch.float32,
+                                device=q.device)
+    ws_ptr, ws_bytes, _keep = _varlen_workspace(q, desc, LA2_OP_BWD, workspace)
+    with torch.cuda.device(q.device):
+        _check(lib.la2_bwd_varlen_state(ctypes.byref(desc), cu_seqlens.data_ptr(), q.shape[0], q.data_ptr(), k.data_ptr(),
+                                        v.data_ptr(), d_o.data_ptr(), lam.data_ptr(),
+                                        _packed_state(kv_init, q, cu_seqlens, "kv_init"),
+                                        _packed_state(d_kv_final, q, cu_seqlens, "d_kv_final"), dq.data_ptr(),
+                                        dk.data_ptr(), dv.data_ptr(),
+                                        _packed_state(d_kv_init, q, cu_seqlens, "d_kv_init") if want_d_kv_init else None,
+                                        ws_ptr, ws_bytes, _stream(q)))
+    return dq, dk, dv, (d_kv_init if want_d_kv_init else None)
 
 
 def la2_fwd_varlen_norm(q, k, v, lam, cu_seqlens, max_seqlen, eps=1e-6, out=None, rstd=None, workspace=None):

@@ -239,6 +239,8 @@ struct ScanArgs {
   float* acc_states = nullptr;
   // compact launch grid of a packed batch in chunks: the pair map (device), built by launch_varlen_map
   const int4* map = nullptr;
+  // states at sequence ends that are not block boundaries (ScanParams::ragged_state; 16-bit half-block kernels)
+  bool ragged_state = false;
 };
 
 la2::ScanParams base_params(const la2_desc* d, const Plan& pl, const float* lambda, void* workspace,
@@ -301,6 +303,7 @@ la2_status run_scan(const la2_desc* d, const Plan& pl, bool reverse, const ScanA
   p.rstd_stride = a.rstd_stride;
   p.acc_y = a.acc_y;
   p.acc_states = a.acc_states;
+  p.ragged_state = a.ragged_state ? 1 : 0;
   hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, reverse, false, p, s)
                 : is16(d->dtype)   ? la2::launch_scan_bf16(d->dtype, d->head_dim, reverse, p, s)
                                    : la2::launch_scan_f32(d->head_dim, reverse, p, s);
@@ -322,6 +325,7 @@ la2_status run_dual_reverse_scan(const la2_desc* d, const Plan& pl, const ScanAr
   p.init[0] = a0.init; p.init[1] = a1.init;
   p.init_transposed = (a0.init_tr ? 1 : 0) | (a1.init_tr ? 2 : 0);
   p.fin[0] = a0.fin; p.fin[1] = a1.fin;
+  p.ragged_state = a0.ragged_state ? 1 : 0;
   p.x[0] = a0.x; p.y[0] = a0.y; p.z[0] = a0.z; p.w[0] = a0.w;
   p.x[1] = a1.x; p.y[1] = a1.y; p.z[1] = a1.z; p.w[1] = a1.w;
   const hipError_t e = wide(d->head_dim) ? la2::launch_scan_wide(d->dtype, d->head_dim, true, false, p, s)
@@ -721,15 +725,35 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
 }  // extern "C"
 
 namespace {
-// la2_fwd_varlen, and with rstd != nullptr the same with the Norm epilogue (eps validated by the caller)
+// Packed batches with state hand-over run on the 16-bit half-block kernels (head_dim 64 / 128) only: they are the
+// ones that form a state at a sequence end that is no block boundary.
+la2_status packed_state_supported(const la2_desc* d) {
+  if (!is16(d->dtype)) return LA2_ERR_DTYPE;
+  if (wide(d->head_dim)) return LA2_ERR_SHAPE;
+  return LA2_OK;
+}
+
+// la2_fwd_varlen and la2_fwd_varlen_state, and with rstd != nullptr la2_fwd_varlen_norm (eps validated by the caller)
 la2_status fwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
-                           const void* k, const void* v, const float* lambda, void* o, float* rstd, float eps,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+                           const void* k, const void* v, const float* lambda, const float* kv_init, void* o,
+                           float* kv_final, float* rstd, float eps, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if (total_positions < 0) return LA2_ERR_SHAPE;
   if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // packed batches at 96 / 256: 16-bit only
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  const bool with_state = kv_init != nullptr || kv_final != nullptr;
+  if (with_state) {   // the half-block kernels' ragged-end states
+    st = packed_state_supported(desc);
+    if (st != LA2_OK) return st;
+    if (!aligned(kv_init, 16) || !aligned(kv_final, 16)) return LA2_ERR_STRIDE_ALIGN;
+  }
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) {
+    if (kv_final == nullptr || (int64_t)desc->batch * desc->heads == 0) return LA2_OK;  // nothing to do
+    // sequences without positions: the states pass through
+    return la2::launch_state_copy(kv_final, kv_init, (int64_t)desc->batch * desc->heads * desc->head_dim * desc->head_dim,
+                                  reinterpret_cast<hipStream_t>(hip_stream)) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  }
   if (!cu_seqlens || !q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
       !aligned(cu_seqlens, 4))
@@ -745,6 +769,9 @@ la2_status fwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int6
   a.rstd = rstd;   // packed layout [heads][total_positions]
   a.eps = eps;
   a.rstd_stride = (int)total_positions;
+  a.init = kv_init;
+  a.fin = kv_final;
+  a.ragged_state = with_state;
   if (pl.wg_pairs > 0) {   // the pair map of the compact grid, in front of the states
     la2::ScanParams mp = base_params(desc, pl, lambda, nullptr, cu_seqlens);
     mp.wg_pairs = pl.wg_pairs;
@@ -756,6 +783,72 @@ la2_status fwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int6
   }
   return run_scan(desc, pl, false, a, lambda, static_cast<char*>(workspace) + pl.map_bytes, s);
 }
+
+// la2_bwd_varlen and la2_bwd_varlen_state
+la2_status bwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
+                           const void* k, const void* v, const void* d_o, const float* lambda, const float* kv_init,
+                           const float* d_kv_final, void* dq, void* dk, void* dv, float* d_kv_init, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  la2_status st = check_desc(desc);
+  if (st != LA2_OK) return st;
+  if (total_positions < 0) return LA2_ERR_SHAPE;
+  if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // as la2_fwd_varlen
+  const bool with_state = kv_init != nullptr || d_kv_final != nullptr || d_kv_init != nullptr;
+  if (with_state) {
+    st = packed_state_supported(desc);
+    if (st != LA2_OK) return st;
+    if (!aligned(kv_init, 16) || !aligned(d_kv_final, 16) || !aligned(d_kv_init, 16)) return LA2_ERR_STRIDE_ALIGN;
+  }
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) {
+    if (d_kv_init == nullptr || (int64_t)desc->batch * desc->heads == 0) return LA2_OK;  // nothing to do
+    // sequences without positions: the gradient of the state passes through
+    return la2::launch_state_copy(d_kv_init, d_kv_final, (int64_t)desc->batch * desc->heads * desc->head_dim * desc->head_dim,
+                                  s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
+  }
+  if (!cu_seqlens || !q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
+      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4) || !aligned(cu_seqlens, 4))
+    return LA2_ERR_STRIDE_ALIGN;
+  const Plan pl = make_plan_varlen(desc, total_positions);
+  if (!plan_fits_a_grid(desc, pl)) return LA2_ERR_SHAPE;
+  // as la2_bwd: with sequence chunks the dQ scan's launch forms the local dKV states behind its own chunk states
+  const bool fuse = pl.nchunks > 1 && fuses_reverse_states(desc);
+  const size_t need = pl.map_bytes + pl.workspace * (fuse ? 2 : 1);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
+    return LA2_ERR_WORKSPACE;
+  // the three scans of la2_bwd, each chain a sequence of its own length; states as in la2_bwd_state
+  ScanArgs for_dq{d_o, v, k, dq}, for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
+  for_dq.cu = for_dv.cu = for_dk.cu = cu_seqlens;
+  for_dq.init = kv_init;
+  for_dq.init_tr = true;
+  for_dv.init = d_kv_final;
+  for_dv.fin = d_kv_init;
+  for_dk.init = d_kv_final;
+  for_dk.init_tr = true;
+  for_dv.ragged_state = for_dk.ragged_state = with_state;   // the forward dQ scan hands out no state
+  if (pl.wg_pairs > 0) {   // the pair map of the compact grid, in front of the states
+    la2::ScanParams mp = base_params(desc, pl, lambda, nullptr, cu_seqlens);
+    mp.wg_pairs = pl.wg_pairs;
+    mp.nlong = pl.nlong;
+    int4* map = reinterpret_cast<int4*>(workspace);
+    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), s) != hipSuccess)
+      return LA2_ERR_LAUNCH;
+    for_dq.map = for_dv.map = for_dk.map = map;
+  }
+  workspace = static_cast<char*>(workspace) + pl.map_bytes;   // the states
+  void* rev_workspace = fuse ? static_cast<char*>(workspace) + pl.workspace : workspace;
+  if (fuse) {
+    for_dq.acc_y = q;
+    for_dq.acc_states = reinterpret_cast<float*>(rev_workspace);
+  }
+  st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  if (is16(desc->dtype)) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, rev_workspace, s, fuse);
+  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
+  if (st != LA2_OK) return st;
+  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
+}
 }  // namespace
 
 extern "C" {
@@ -763,8 +856,24 @@ extern "C" {
 la2_status la2_fwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
                           const void* k, const void* v, const float* lambda, void* o, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
-  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, o, nullptr, 0.f, workspace,
-                         workspace_bytes, hip_stream);
+  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, nullptr, o, nullptr, nullptr, 0.f,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+la2_status la2_fwd_varlen_state(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                                const void* q, const void* k, const void* v, const float* lambda,
+                                const float* kv_init, void* o, float* kv_final, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, kv_init, o, kv_final, nullptr, 0.f,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+la2_status la2_bwd_varlen_state(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
+                                const void* q, const void* k, const void* v, const void* d_o, const float* lambda,
+                                const float* kv_init, const float* d_kv_final, void* dq, void* dk, void* dv,
+                                float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return bwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv,
+                         d_kv_init, workspace, workspace_bytes, hip_stream);
 }
 
 la2_status la2_fwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
@@ -778,8 +887,8 @@ la2_status la2_fwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, 
   if (total_positions <= 0 || total_positions > 0x7FFFFFFF) return LA2_ERR_SHAPE;
   if (rstd == nullptr) return LA2_ERR_NULL;
   if (!aligned(rstd, 4)) return LA2_ERR_STRIDE_ALIGN;
-  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, o, rstd, eps, workspace, workspace_bytes,
-                         hip_stream);
+  return fwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, lambda, nullptr, o, nullptr, rstd, eps, workspace,
+                         workspace_bytes, hip_stream);
 }
 
 la2_status la2_bwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions,
@@ -813,48 +922,8 @@ la2_status la2_bwd_varlen_norm(const la2_desc* desc, const int32_t* cu_seqlens, 
 la2_status la2_bwd_varlen(const la2_desc* desc, const int32_t* cu_seqlens, int64_t total_positions, const void* q,
                           const void* k, const void* v, const void* d_o, const float* lambda, void* dq, void* dk,
                           void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  la2_status st = check_desc(desc);
-  if (st != LA2_OK) return st;
-  if (total_positions < 0) return LA2_ERR_SHAPE;
-  if (wide(desc->head_dim) && !is16(desc->dtype)) return LA2_ERR_DTYPE;   // as la2_fwd_varlen
-  if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
-  if (!cu_seqlens || !q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
-  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
-      !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4) || !aligned(cu_seqlens, 4))
-    return LA2_ERR_STRIDE_ALIGN;
-  const Plan pl = make_plan_varlen(desc, total_positions);
-  if (!plan_fits_a_grid(desc, pl)) return LA2_ERR_SHAPE;
-  // as la2_bwd: with sequence chunks the dQ scan's launch forms the local dKV states behind its own chunk states
-  const bool fuse = pl.nchunks > 1 && fuses_reverse_states(desc);
-  const size_t need = pl.map_bytes + pl.workspace * (fuse ? 2 : 1);
-  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
-    return LA2_ERR_WORKSPACE;
-  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  // the three scans of la2_bwd, each chain a sequence of its own length
-  ScanArgs for_dq{d_o, v, k, dq}, for_dv{k, q, d_o, dv}, for_dk{v, d_o, q, dk};
-  for_dq.cu = for_dv.cu = for_dk.cu = cu_seqlens;
-  for_dk.init_tr = true;
-  if (pl.wg_pairs > 0) {   // the pair map of the compact grid, in front of the states
-    la2::ScanParams mp = base_params(desc, pl, lambda, nullptr, cu_seqlens);
-    mp.wg_pairs = pl.wg_pairs;
-    mp.nlong = pl.nlong;
-    int4* map = reinterpret_cast<int4*>(workspace);
-    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), s) != hipSuccess)
-      return LA2_ERR_LAUNCH;
-    for_dq.map = for_dv.map = for_dk.map = map;
-  }
-  workspace = static_cast<char*>(workspace) + pl.map_bytes;   // the states
-  void* rev_workspace = fuse ? static_cast<char*>(workspace) + pl.workspace : workspace;
-  if (fuse) {
-    for_dq.acc_y = q;
-    for_dq.acc_states = reinterpret_cast<float*>(rev_workspace);
-  }
-  st = run_scan(desc, pl, false, for_dq, lambda, workspace, s);
-  if (st != LA2_OK) return st;
-  if (is16(desc->dtype)) return run_dual_reverse_scan(desc, pl, for_dv, for_dk, lambda, rev_workspace, s, fuse);
-  st = run_scan(desc, pl, true, for_dv, lambda, workspace, s);
-  if (st != LA2_OK) return st;
-  return run_scan(desc, pl, true, for_dk, lambda, workspace, s);
+  return bwd_varlen_impl(desc, cu_seqlens, total_positions, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv,
+                         nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 la2_status la2_left_product_fwd(const la2_desc* desc, const void* q, const void* k, const void* v,

@@ -220,7 +220,8 @@ __global__ __launch_bounds__(256) void varlen_map_kernel(const int32_t* cu_seqle
   for (int b0 = 0; b0 < batch; b0 += 256) {
     const int b = b0 + t;
     int nch = 0;
-    if (b < batch) nch = (cu_seqlens[b + 1] - cu_seqlens[b] + chunk_tokens - 1) / chunk_tokens;
+    // (a sequence without positions keeps one pair: its workgroups pass a start state on where one is handed over)
+    if (b < batch) nch = max(1, (cu_seqlens[b + 1] - cu_seqlens[b] + chunk_tokens - 1) / chunk_tokens);
     const int slots = nch > 1 ? nch : 0;
     s_pairs[t] = nch;
     s_slots[t] = slots;

@@ -77,6 +77,12 @@ struct ScanParams {
   // the units of the state scan's launch, which would otherwise be mostly workgroups with nothing to do
   const int32_t* long_list;
   int32_t nlong;
+  // 16-bit half-block kernels only: states at sequence ends that are no block boundaries.  Non-zero: a forward
+  // scan hands out in fin the state right after a chain's last position even if that position is not a block's
+  // last (the update of a ragged last block then weights row c by lambda^(rem-1-c) and the carried state by
+  // lambda^rem, rem = rows of that block), a reverse scan's start state enters right behind the chain's last
+  // position likewise, and a chain of no positions passes its start state (or zero) on to fin.
+  int32_t ragged_state;
 };
 
 // Which (batch row or sequence, head, chunk) a workgroup of a scan-type launch serves, and where that chunk's

@@ -36,12 +36,20 @@ constexpr int kBH = 32;
 // from the chunk's first position), and leave it in p.acc_states.  Algorithm 2: the dQ scan (x = dO) with
 // acc_y = Q leaves the local dKV states of the sequence chunks, so the dK / dV scan needs no pass of its own
 // over Q and dO to form them.
-template <typename E, int D, bool REV, bool TWIN, int NBUF, bool NORM = false, bool ACC = false>
+//
+// RS: states at sequence ends that are not block boundaries (ScanParams::ragged_state; packed batches with state
+// hand-over, where every sequence has a length of its own).  Forward: when the chain's last block has rem < B
+// rows and the final state is wanted, that block's update weighs row c by lambda^(rem-1-c) and the carried state
+// by lambda^rem, which gives the state right after the last position.  Reverse: a start state that enters behind
+// such a block reaches row r with lambda^(rem-1-r) and is carried on with lambda^rem.  A chain without positions
+// hands its start state (or zero) to fin.  All of it is off the per-block path of a chain's other blocks.
+template <typename E, int D, bool REV, bool TWIN, int NBUF, bool NORM = false, bool ACC = false, bool RS = false>
 __global__ __launch_bounds__(((TWIN || ACC) ? 4 : 2) * D, ((TWIN || ACC) ? 1 : 2) * (128 / D))
 void scan_bf16_half_kernel(ScanParams p) {
   static_assert(D == 128 || D == 64, "head_dim");
   static_assert(!NORM || (!REV && !TWIN), "the Norm epilogue belongs to the forward pass");
   static_assert(!ACC || (!REV && !TWIN && !NORM), "the accumulating wave group rides on a plain forward scan");
+  static_assert(!RS || (!ACC && !NORM), "ragged-end states: plain forward scans and reverse scans");
   constexpr int B = kBH;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
@@ -109,6 +117,20 @@ void scan_bf16_half_kernel(ScanParams p) {
   const int cb = p.chunk_tokens / B;
   const int blk_lo = chunk * cb;
   const int blk_hi = min(blk_lo + cb, nblocks);
+  if (RS && n == 0 && chunk == 0) {   // no positions: the state passes through
+    float* gf0 = which ? p.fin[1] : p.fin[0];
+    if (gf0 != nullptr) {
+      const float* gi0 = which ? p.init[1] : p.init[0];
+      const bool tri = (p.init_transposed >> which) & 1, trf = (p.fin_transposed >> which) & 1;
+      gf0 += (int64_t)chain * (D * D);
+      if (gi0 != nullptr) gi0 += (int64_t)chain * (D * D);
+#pragma unroll
+      for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int v = 0; v < 16; v++)
+          gf0[state_index<D>(dvt, l32, hh, t, v, trf)] = gi0 != nullptr ? gi0[state_index<D>(dvt, l32, hh, t, v, tri)] : 0.f;
+    }
+  }
   if (blk_lo >= blk_hi) return;
   const int nblk = blk_hi - blk_lo;
 
@@ -267,6 +289,14 @@ void scan_bf16_half_kernel(ScanParams p) {
   const float inter_scale = exp2f(l2 * (float)(REV ? B - 1 - l32 : l32 + 1));
   const UpdateDecay<REV, B> decay(l2, hh);
   const float lamB = uniform(exp2f(l2 * (float)B));
+  // RS: rows of the chain's ragged last block when this chunk holds it and its end state matters (forward: the
+  // final state is wanted; reverse: a start state comes in behind it), else 0
+  int rag_rem = 0;
+  if (RS && blk_hi >= nblocks && n % B != 0) {
+    if (REV ? gs != nullptr : (which ? p.fin[1] : p.fin[0]) != nullptr) rag_rem = n % B;
+  }
+  rag_rem = __builtin_amdgcn_readfirstlane(rag_rem);
+  const float lamRag = uniform(exp2f(l2 * (float)rag_rem));
 
   // prologue: the first NBUF - 1 blocks' tiles
 #pragma unroll
@@ -309,6 +339,9 @@ void scan_bf16_half_kernel(ScanParams p) {
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
     const bool has_next = it + 1 < nblk, has_ahead = it + NBUF - 1 < nblk;
     const int nb = REV ? blk - 1 : blk + 1;
+    // RS: this is the ragged block whose state weights differ (a reverse scan meets it first, a forward scan last)
+    const bool rag = RS && rag_rem != 0 && (REV ? it == 0 : !has_next);
+    const float lam_blk = (RS && rag) ? lamRag : lamB;
     const E* tX = sCur[xi];
     const E* tY = sCur[yi];
     const E* tZ = sCur[zi];
@@ -346,13 +379,18 @@ void scan_bf16_half_kernel(ScanParams p) {
       if (ks >= 2 && (ks & 1) == 0) {   // state tile ks / 2 - 1: both operands made in slots <= ks - 1
         const int t = (ks >> 1) - 1;
 #pragma unroll
-        for (int v = 0; v < 16; v++) kv[t][v] *= lamB;
+        for (int v = 0; v < 16; v++) kv[t][v] *= lam_blk;
         pin(kv[t]);
       }
       // the update weights on the Z fragments, two slots after their LDS reads (d = 64: in the last two slots)
       if ((KS == 8 && (ks == 3 || ks == 5)) || (KS == 4 && (ks == 2 || ks == 3))) {
         const int q = KS == 8 ? (ks - 3) >> 1 : ks - 2;
-        zd[q] = decay.apply(zf[q], 16 * q);
+        if constexpr (RS && !REV) {
+          if (rag) zd[q] = decay.apply_ragged(zf[q], 16 * q, rag_rem);
+          else zd[q] = decay.apply(zf[q], 16 * q);
+        } else {
+          zd[q] = decay.apply(zf[q], 16 * q);
+        }
         pin(zd[q]);
       }
       if (ks == KS - 1) read_yt(0, 0);
@@ -362,11 +400,15 @@ void scan_bf16_half_kernel(ScanParams p) {
     }
     {
 #pragma unroll
-      for (int v = 0; v < 16; v++) kv[NT - 1][v] *= lamB;
+      for (int v = 0; v < 16; v++) kv[NT - 1][v] *= lam_blk;
       pin(kv[NT - 1]);
       // the carried part takes the decay at this lane's position
+      float isc = inter_scale;
+      if constexpr (RS && REV) {   // the start state sits right behind row rag_rem - 1
+        if (rag) isc = l32 < rag_rem ? exp2f(l2 * (float)(rag_rem - 1 - l32)) : 0.f;
+      }
 #pragma unroll
-      for (int v = 0; v < 16; v++) inter[v] *= inter_scale;
+      for (int v = 0; v < 16; v++) inter[v] *= isc;
       pin(inter);
     }
     // ---- phase 3
@@ -465,7 +507,7 @@ void scan_bf16_half_kernel(ScanParams p) {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the dummy direct loads before the LDS is given up
   // state after the chain's last block, if the caller wants it (the update ran on every block)
   float* gf = which ? p.fin[1] : p.fin[0];
-  if (gf != nullptr && (REV ? chunk == 0 : chunk == p.nchunks - 1)) {
+  if (gf != nullptr && (REV ? chunk == 0 : blk_hi >= nblocks)) {   // the chunk this chain's scan passes last
     gf += (int64_t)chain * (D * D);
     const bool trf = (p.fin_transposed >> which) & 1;
 #pragma unroll
@@ -489,7 +531,16 @@ hipError_t launch_half(bool reverse, bool twin, const ScanParams& p, hipStream_t
   // compute unit to itself) measured no faster: such launches are bound by the memory system, not by the
   // bytes a workgroup keeps in flight.
   constexpr int kPlain = 2 * D, kDouble = 4 * D;   // threads: one wave per 32 value features, or two such groups
-  if (twin) {
+  if (p.ragged_state != 0) {   // the host pairs this only with a reverse twin launch or a plain forward scan
+    if (twin && reverse)
+      hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, true, true, 3, false, false, true>), dim3((unsigned)(grid / 2)),
+                         dim3(kDouble), 0, s, p);
+    else if (!twin && !reverse && p.acc_states == nullptr && p.rstd == nullptr)
+      hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, false, 3, false, false, true>), dim3((unsigned)grid),
+                         dim3(kPlain), 0, s, p);
+    else
+      return hipErrorInvalidValue;
+  } else if (twin) {
     dim3 gt((unsigned)(grid / 2)), bt(kDouble);
     if (reverse) hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, true, true, 3>), gt, bt, 0, s, p);
     else         hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, true, 3>), gt, bt, 0, s, p);

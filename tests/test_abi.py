@@ -327,6 +327,40 @@ def test_varlen_entry_points_validate_before_any_launch(lib):
         lib.la2_set_chunk_tokens(0)
 
 
+def test_packed_state_entry_points_validate_before_any_launch(lib):
+    vp = ctypes.c_void_p
+    lib.la2_fwd_varlen_state.argtypes = [vp, vp, ctypes.c_int64] + [vp] * 8 + [ctypes.c_size_t, vp]
+    lib.la2_fwd_varlen_state.restype = ctypes.c_int
+    lib.la2_bwd_varlen_state.argtypes = [vp, vp, ctypes.c_int64] + [vp] * 12 + [ctypes.c_size_t, vp]
+    lib.la2_bwd_varlen_state.restype = ctypes.c_int
+    d = dense(lib, 5, 2, 300, 64, binding.LA2_BF16)
+    d.stride_b, d.stride_h, d.stride_n = 0, 64, 128
+    ref = ctypes.byref(d)
+    fs = lambda cu=P, q=P, init=P, fin=P, total=0: lib.la2_fwd_varlen_state(ref, cu, total, q, P, P, P, init, P, fin, None, 0, None)
+    bs = lambda cu=P, dq=P, init=P, dfin=P, dinit=P, total=0: lib.la2_bwd_varlen_state(
+        ref, cu, total, P, P, P, P, P, init, dfin, dq, P, P, dinit, None, 0, None)
+    assert fs(total=-1) == E_SHAPE and bs(total=-1) == E_SHAPE
+    assert fs(cu=None) == E_NULL and fs(q=None) == E_NULL and bs(cu=None) == E_NULL and bs(dq=None) == E_NULL
+    assert fs(init=P + 4) == E_ALIGN and fs(fin=P + 8) == E_ALIGN
+    assert bs(init=P + 4) == E_ALIGN and bs(dfin=P + 8) == E_ALIGN and bs(dinit=P + 4) == E_ALIGN
+    # state hand-over over packed batches: the 16-bit types at head_dim 64 and 128
+    d.dtype = binding.LA2_F32
+    assert fs() == E_DTYPE and bs() == E_DTYPE
+    assert fs(init=None, fin=None, cu=None) == E_NULL      # without states: la2_fwd_varlen, which takes fp32
+    d.dtype = binding.LA2_F16
+    assert fs(cu=None) == E_NULL
+    for hd in (96, 256):
+        w = dense(lib, 5, 2, 300, hd, binding.LA2_BF16)
+        w.stride_b, w.stride_h, w.stride_n = 0, hd, 2 * hd
+        wr = ctypes.byref(w)
+        assert lib.la2_fwd_varlen_state(wr, P, 0, P, P, P, P, P, P, P, None, 0, None) == E_SHAPE
+        assert lib.la2_bwd_varlen_state(wr, P, 0, P, P, P, P, P, P, P, P, P, P, P, None, 0, None) == E_SHAPE
+        assert lib.la2_fwd_varlen_state(wr, None, 0, P, P, P, P, None, P, None, None, 0, None) == E_NULL
+    d.dtype = binding.LA2_BF16
+    d.batch = 0
+    assert fs(cu=None, q=None) == OK and bs(cu=None) == OK
+
+
 def test_head_dim_96_and_256_are_accepted_where_they_have_kernels(lib):
     for hd in (96, 256):
         for dt in (binding.LA2_BF16, binding.LA2_F16, binding.LA2_F32):
