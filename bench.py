@@ -154,8 +154,17 @@ def main():
     def bwd(g):
         binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], g["lam"], out=g["grads"], workspace=g["ws"])
 
-    def time_ms(fn, iters, warm=2):
-        """Average ms per call, HIP events on the stream the kernels are launched on."""
+    def time_ms(fn, iters, warm=2, settle_ms=0.0):
+        """Average ms per call, HIP events on the stream the kernels are launched on.  settle_ms: keep calling for
+        that long first, untimed.  After an idle spell (the host staging the next tensors) the device needs about
+        40 ms of continuous work to reach its steady clocks: launches of 0.183 ms in the steady state take
+        0.23-0.29 ms in the first 10 ms and 0.19 ms after 30 ms (measured with windows of 50 launches)."""
+        if settle_ms > 0:
+            t_end = time.perf_counter() + settle_ms * 1e-3
+            while time.perf_counter() < t_end:
+                for _ in range(20):
+                    fn()
+                torch.cuda.synchronize()
         for _ in range(warm):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -311,8 +320,8 @@ def main():
     others = []
     for wl in (workloads.CONFIG2, workloads.CONFIG4):
         g = stage(wl)
-        f_ms = time_ms(lambda: fwd(g), iters, warm=40)   # freshly staged tensors: warm up as the sweep is
-        b_ms = time_ms(lambda: bwd(g), iters, warm=40)
+        f_ms = time_ms(lambda: fwd(g), iters, warm=40, settle_ms=80)   # freshly staged tensors: warm up as the sweep is
+        b_ms = time_ms(lambda: bwd(g), iters, warm=40, settle_ms=80)
         tot = f_ms + b_ms
         fl = flops_per_token_head(g["B"], wl.head_dim, "fwd+bwd") * wl.token_heads
         others.append({"workload": wl.name, "B": g["B"], "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
@@ -327,10 +336,10 @@ def main():
         shape = (wl.batch, wl.heads, wl.head_dim, wl.head_dim)
         st = {n_: torch.zeros(shape, dtype=torch.float32, device=dev) for n_ in ("init", "fin", "d_fin", "d_init")}
         f_ms = time_ms(lambda: binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=st["init"], out=g["o"],
-                                                     kv_final=st["fin"], workspace=g["ws"]), iters, warm=40)
+                                                     kv_final=st["fin"], workspace=g["ws"]), iters, warm=40, settle_ms=80)
         b_ms = time_ms(lambda: binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=st["init"],
                                                      d_kv_final=st["d_fin"], out=g["grads"], d_kv_init=st["d_init"],
-                                                     workspace=g["ws"]), iters, warm=40)
+                                                     workspace=g["ws"]), iters, warm=40, settle_ms=80)
         with_states.append({"workload": wl.name + " + kv_init, kv_final, d_kv_final, d_kv_init",
                             "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                             "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1)})
@@ -341,11 +350,11 @@ def main():
         rstd = torch.empty(g["q"].shape[:3], dtype=torch.float32, device=dev)
         d_u = torch.empty_like(g["q"])
         f_ms = time_ms(lambda: binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], 1e-6, out=g["o"], rstd=rstd,
-                                                    workspace=g["ws"]), iters, warm=40)
+                                                    workspace=g["ws"]), iters, warm=40, settle_ms=80)
         b_ms = time_ms(lambda: binding.la2_bwd_norm(g["q"], g["k"], g["v"], g["o"], rstd, g["d_o"], g["lam"],
-                                                    out=g["grads"], d_u=d_u, workspace=g["ws"]), iters, warm=40)
-        pf_ms = time_ms(lambda: fwd(g), iters, warm=40)
-        pb_ms = time_ms(lambda: bwd(g), iters, warm=40)
+                                                    out=g["grads"], d_u=d_u, workspace=g["ws"]), iters, warm=40, settle_ms=80)
+        pf_ms = time_ms(lambda: fwd(g), iters, warm=40, settle_ms=80)
+        pb_ms = time_ms(lambda: bwd(g), iters, warm=40, settle_ms=80)
         normed.append({"workload": wl.name + " + Norm (rms over head_dim, eps 1e-6)",
                        "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                        "tokens_per_s": round(wl.tokens / ((f_ms + b_ms) * 1e-3), 1),
@@ -361,9 +370,9 @@ def main():
     cu = torch.tensor([0] + list(__import__("itertools").accumulate(lengths)), dtype=torch.int32, device=dev)
     op_, gr_ = torch.empty_like(gp["q"]), tuple(torch.empty_like(gp["q"]) for _ in range(3))
     f_ms = time_ms(lambda: binding.la2_fwd_varlen(gp["q"], gp["k"], gp["v"], gp["lam"], cu, max(lengths), out=op_),
-                   iters, warm=40)
+                   iters, warm=40, settle_ms=80)
     b_ms = time_ms(lambda: binding.la2_bwd_varlen(gp["q"], gp["k"], gp["v"], gp["d_o"], gp["lam"], cu, max(lengths),
-                                                  out=gr_), iters, warm=40)
+                                                  out=gr_), iters, warm=40, settle_ms=80)
     packed = {"workload": wl_p.name, "sequences": len(lengths), "tokens": sum(lengths), "fwd_ms": round(f_ms, 4),
               "bwd_ms": round(b_ms, 4), "tokens_per_s": round(sum(lengths) / ((f_ms + b_ms) * 1e-3), 1),
               "note": "the library cuts the long sequences into chunks (planned from the longest length and the total)"}
@@ -374,8 +383,8 @@ def main():
     for dt, tag in ((torch.float16, "f16"), (torch.float32, "f32")):
         wl_d = workloads.Workload(wl1.name + "_" + tag, wl1.batch, wl1.heads, wl1.seqlen, wl1.head_dim, dt, seed=wl1.seed)
         g_d = stage(wl_d)
-        f_ms = time_ms(lambda: fwd(g_d), iters, warm=40)
-        b_ms = time_ms(lambda: bwd(g_d), iters, warm=40)
+        f_ms = time_ms(lambda: fwd(g_d), iters, warm=40, settle_ms=80)
+        b_ms = time_ms(lambda: bwd(g_d), iters, warm=40, settle_ms=80)
         other_dtypes.append({"workload": wl_d.name, "dtype": tag, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                              "tokens_per_s": round(wl_d.tokens / ((f_ms + b_ms) * 1e-3), 1)})
         del g_d
@@ -386,8 +395,8 @@ def main():
         for b_, n_ in ((64, 1024), (16, 4096)):
             wl_h = workloads.Workload("b%d_n%d_h%d_d%d" % (b_, n_, heads, hd), b_, heads, n_, hd, torch.bfloat16, seed=60 + hd)
             g_h = stage(wl_h)
-            f_ms = time_ms(lambda: fwd(g_h), iters, warm=40)
-            b_ms = time_ms(lambda: bwd(g_h), iters, warm=40)
+            f_ms = time_ms(lambda: fwd(g_h), iters, warm=40, settle_ms=80)
+            b_ms = time_ms(lambda: bwd(g_h), iters, warm=40, settle_ms=80)
             unit = wl_h.token_heads * hd * 2   # bytes of one tensor
             other_head_dims.append({"workload": wl_h.name, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                                     "tokens_per_s": round(wl_h.tokens / ((f_ms + b_ms) * 1e-3), 1),
@@ -418,7 +427,7 @@ def main():
     saved = []
     for wl, g in sweep:
         ws_b = torch.empty_like(g["ws"])
-        f_ms = time_ms(lambda: fwd(g), iters)
+        f_ms = time_ms(lambda: fwd(g), iters, settle_ms=40)
         b_ms = time_ms(lambda: binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], want_d_kv_init=False,
                                                      out=g["grads"], workspace=ws_b, fwd_workspace=g["ws"]), iters)
         saved.append({"workload": wl.name + " (backward reuses the forward's chunk states)",
@@ -440,7 +449,7 @@ def main():
     lam5 = dw.decay().to(dev)
     toks = [tuple(x.to(dev) for x in dw.token(gen)) for _ in range(16)]
     o5 = torch.empty_like(toks[0][0])
-    for i in range(8):
+    for i in range(768):   # about 60 ms: the host staged the state and the tokens, the device has been idle
         binding.la2_decode_step(*toks[i % 16], lam5, kv, out=o5)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
