@@ -219,7 +219,9 @@ la2_status la2_bwd_state_norm(const la2_desc* desc, const void* q, const void* k
  *   cu_seqlens       in   device, int32 [batch + 1], non-decreasing, cu_seqlens[0] = offset of the first
  *                    sequence; lengths above desc->seqlen are a precondition violation (not read on the host)
  *   total_positions  host scalar: the number of positions in all sequences together (the packed tensors' first
- *                    extent), or 0 if not known; negative: LA2_ERR_SHAPE.  A planning hint only: the lengths
+ *                    extent), or 0 if not known; negative: LA2_ERR_SHAPE.  It sizes the plan and the workspace
+ *                    (a value below the real sum of the lengths is safe but leaves sequences that do not fit
+ *                    the workspace planned from it uncomputed); the lengths
  *                    stay on the device, and with it the host can tell a batch of about equal lengths from one
  *                    whose longest sequence would run long after all the others have finished.  Such a batch is
  *                    cut into sequence chunks (a quarter of desc->seqlen) although it has chains enough to

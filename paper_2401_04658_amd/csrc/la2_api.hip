@@ -103,6 +103,7 @@ struct Plan {
   // bytes of the pair map that sits in front of the states; 0 otherwise
   int wg_pairs = 0;
   int nlong = 0;        // sequences of more than one chunk the plan has room for (the state scan's units)
+  int64_t wg_slots = 0; // state slots (per head) the workspace has room for
   size_t map_bytes = 0;
 };
 
@@ -166,6 +167,7 @@ Plan make_plan_varlen(const la2_desc* d, int64_t total_positions) {
     if (pairs > ((int64_t)1 << 30)) return c;
     c.wg_pairs = (int)pairs;
     c.nlong = (int)nlong;
+    c.wg_slots = slots;
     c.map_bytes = ((size_t)pairs * sizeof(int4) + (size_t)nlong * sizeof(int32_t) + 255) & ~(size_t)255;
     c.workspace = (size_t)slots * d->heads * d->head_dim * d->head_dim * sizeof(float);
     return c;
@@ -777,7 +779,7 @@ la2_status fwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int6
     mp.wg_pairs = pl.wg_pairs;
     mp.nlong = pl.nlong;
     int4* map = reinterpret_cast<int4*>(workspace);
-    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), s) != hipSuccess)
+    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), pl.wg_slots, s) != hipSuccess)
       return LA2_ERR_LAUNCH;
     a.map = map;
   }
@@ -832,7 +834,7 @@ la2_status bwd_varlen_impl(const la2_desc* desc, const int32_t* cu_seqlens, int6
     mp.wg_pairs = pl.wg_pairs;
     mp.nlong = pl.nlong;
     int4* map = reinterpret_cast<int4*>(workspace);
-    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), s) != hipSuccess)
+    if (la2::launch_varlen_map(mp, map, reinterpret_cast<int32_t*>(map + pl.wg_pairs), pl.wg_slots, s) != hipSuccess)
       return LA2_ERR_LAUNCH;
     for_dq.map = for_dv.map = for_dk.map = map;
   }

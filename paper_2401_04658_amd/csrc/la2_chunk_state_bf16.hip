@@ -1,5 +1,7 @@
 // Chunk-state pre-pass of the sequence-chunked launches, gfx950: local state of every chunk (bf16 MFMA, same
 // streaming as the scan kernels) and the scan that turns local states into chunk start states (fp32).
+#include <algorithm>
+
 #include "la2_bf16_common.h"
 
 namespace la2 {
@@ -159,7 +161,10 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
   }
   const int chain = bi * heads + hi;
   if (cu_seqlens != nullptr) n = cu_seqlens[bi + 1] - cu_seqlens[bi];   // this sequence's length
-  const int nch = (n + chunk_tokens - 1) / chunk_tokens;   // chunks this chain really has (<= nchunks)
+  int nch = (n + chunk_tokens - 1) / chunk_tokens;   // chunks this chain really has (<= nchunks)
+  // (a packed sequence longer than the launch was planned for is the caller's error; it must not reach past the
+  // chain's slots.  With a pair map the sequence's slots were counted from this same length.)
+  if (wg_map == nullptr) nch = min(nch, nchunks);
   const float l2 = log2f(lambda[hi]);
   const float lamFull = exp2f(l2 * (float)chunk_tokens);
   const float lamLast = exp2f(l2 * (float)(n - (nch - 1) * chunk_tokens));
@@ -208,10 +213,11 @@ __global__ void state_scan_kernel(float* states, const float* lambda, int heads,
 // workgroup walks the sequences 256 at a time with a running count of pairs and of state slots.
 //   map[pair] = {sequence, chunk, first state slot of the sequence (-1: single chunk, no slots), its chunk count}
 // Entries past the last pair, up to npairs, get sequence -1.  A batch whose lengths sum to more than the host was
-// told would need more entries than the map has: such pairs are dropped (never written past the end).
+// told would need more entries than the map has, or more state slots than the workspace (nslots per head): such
+// pairs are dropped (nothing is written past the end of either; their sequences are not computed).
 // long_list[i] = pair of chunk 0 of the i-th sequence with state slots (i < nlong), -1 past the last.
 __global__ __launch_bounds__(256) void varlen_map_kernel(const int32_t* cu_seqlens, int batch, int chunk_tokens, int npairs,
-                                                         int4* map, int nlong, int32_t* long_list) {
+                                                         int4* map, int nlong, int32_t* long_list, int nslots) {
   __shared__ int s_pairs[256], s_slots[256], s_long[256];
   __shared__ int base_pairs, base_slots, base_long;
   const int t = (int)threadIdx.x;
@@ -238,9 +244,10 @@ __global__ __launch_bounds__(256) void varlen_map_kernel(const int32_t* cu_seqle
     }
     const int first_pair = base_pairs + s_pairs[t] - nch;
     const int first_slot = base_slots + s_slots[t] - slots;
+    const bool fits = first_pair + nch <= npairs && (!slots || first_slot + slots <= nslots);
     for (int j = 0; j < nch; j++)
-      if (first_pair + j < npairs) map[first_pair + j] = make_int4(b, j, slots ? first_slot : -1, nch);
-    if (slots && base_long + s_long[t] - 1 < nlong && first_pair < npairs) long_list[base_long + s_long[t] - 1] = first_pair;
+      if (first_pair + j < npairs) map[first_pair + j] = make_int4(fits ? b : -1, j, slots ? first_slot : -1, nch);
+    if (slots && base_long + s_long[t] - 1 < nlong) long_list[base_long + s_long[t] - 1] = fits ? first_pair : -1;
     __syncthreads();
     if (t == 255) { base_pairs += s_pairs[255]; base_slots += s_slots[255]; base_long += s_long[255]; }
     __syncthreads();
@@ -284,10 +291,10 @@ hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hi
   return hipGetLastError();
 }
 
-hipError_t launch_varlen_map(const ScanParams& p, int4* map, int32_t* long_list, hipStream_t s) {
+hipError_t launch_varlen_map(const ScanParams& p, int4* map, int32_t* long_list, int64_t nslots, hipStream_t s) {
   if (p.wg_pairs <= 0) return hipSuccess;
   hipLaunchKernelGGL(varlen_map_kernel, dim3(1), dim3(256), 0, s, p.cu_seqlens, p.batch, p.chunk_tokens, p.wg_pairs, map,
-                     p.nlong, long_list);
+                     p.nlong, long_list, (int)std::min<int64_t>(nslots, 0x7FFFFFFF));
   return hipGetLastError();
 }
 

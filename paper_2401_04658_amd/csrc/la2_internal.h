@@ -184,7 +184,7 @@ hipError_t launch_left_product_bf16(int head_dim, bool reverse, const ScanParams
 hipError_t launch_scan_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 hipError_t launch_chunk_states_f32(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);
 // packed batch in chunks: fills map[0 .. p.wg_pairs) and long_list[0 .. p.nlong) from p.cu_seqlens (one small workgroup)
-hipError_t launch_varlen_map(const ScanParams& p, int4* map, int32_t* long_list, hipStream_t s);
+hipError_t launch_varlen_map(const ScanParams& p, int4* map, int32_t* long_list, int64_t nslots, hipStream_t s);
 // turns the per-chunk local states in p.states into chunk start states (any dtype: states are fp32);
 // the first chunk starts from p.init[0] (seen through bit 0 of p.init_transposed) or zero
 hipError_t launch_state_scan(int head_dim, bool reverse, const ScanParams& p, hipStream_t s);

@@ -122,6 +122,51 @@ def test_equal_lengths_reproduce_the_dense_batch_bit_for_bit():
         assert torch.equal(unpack(a), ref)
 
 
+def test_a_total_below_the_real_one_drops_sequences_and_stays_inside_the_workspace():
+    """total_positions sizes the pair map and the state slots.  Told less than the lengths add up to, the library
+    computes the sequences that fit its map and slots, leaves the others untouched and writes nothing past the
+    workspace it asked for (the bytes behind it keep their pattern)."""
+    import ctypes
+    binding.la2_set_chunk_tokens(64)
+    lengths, H, d, dtype = [700, 130, 64, 1000, 5, 383], 2, 128, torch.bfloat16
+    t, cu = packed_inputs(lengths, H, d, dtype, seed=870)
+    g = {k: v.to(DEV) for k, v in t.items()}
+    cu_g = cu.to(DEV)
+    lib, told, guard = binding.load(), 600, 4096
+    desc = binding._varlen_desc(g["q"], cu_g, max(lengths))
+    # 600 / 64 + 6 = 15 pairs, 2 * 600 / 64 = 18 slots: sequences 0 (11 chunks), 1 (3 chunks) and 2 (1 chunk) fit
+    fits = [True, True, True, False, False, False]
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    o = torch.full_like(g["q"], float("nan"))
+    grads = tuple(torch.full_like(g["q"], float("nan")) for _ in range(3))
+    for op in (binding.LA2_OP_FWD, binding.LA2_OP_BWD):
+        need = int(lib.la2_varlen_workspace_bytes(ctypes.byref(desc), told, op))
+        assert 0 < need < int(lib.la2_varlen_workspace_bytes(ctypes.byref(desc), g["q"].shape[0], op))
+        ws = torch.full((need + guard,), 0xAB, dtype=torch.uint8, device=DEV)
+        if op == binding.LA2_OP_FWD:
+            st = lib.la2_fwd_varlen(ctypes.byref(desc), cu_g.data_ptr(), told, g["q"].data_ptr(), g["k"].data_ptr(),
+                                    g["v"].data_ptr(), g["lam"].data_ptr(), o.data_ptr(), ws.data_ptr(), need, stream)
+        else:
+            st = lib.la2_bwd_varlen(ctypes.byref(desc), cu_g.data_ptr(), told, g["q"].data_ptr(), g["k"].data_ptr(),
+                                    g["v"].data_ptr(), g["d_o"].data_ptr(), g["lam"].data_ptr(), grads[0].data_ptr(),
+                                    grads[1].data_ptr(), grads[2].data_ptr(), ws.data_ptr(), need, stream)
+        assert st == 0
+        torch.cuda.synchronize()
+        assert bool((ws[need:] == 0xAB).all())
+    lam64 = to64(t["lam"])
+    for b, n in enumerate(lengths):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        if not fits[b]:
+            for x in (o,) + grads:
+                assert torch.isnan(x[lo:hi].float()).all(), b
+            continue
+        seq = {name: to64(t[name][lo:hi]).transpose(1, 0, 2)[None] for name in ("q", "k", "v", "d_o")}
+        assert_close("seq %d o" % b, o[lo:hi].permute(1, 0, 2)[None], oracle.fwd_direct(seq["q"], seq["k"], seq["v"], lam64), dtype)
+        for name, got, ref in zip(("dq", "dk", "dv"), grads,
+                                  oracle.bwd_direct(seq["q"], seq["k"], seq["v"], seq["d_o"], lam64)):
+            assert_close("seq %d %s" % (b, name), got[lo:hi].permute(1, 0, 2)[None], ref, dtype)
+
+
 def test_empty_cases_and_validation():
     lam = torch.ones(2, device=DEV)
     x = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device=DEV)

@@ -179,3 +179,66 @@ def test_two_packed_calls_equal_one():
                                  ("dv", (dv1, dv2), rg[2])):
             got = torch.cat([parts[0][int(off[0][b]):int(off[0][b + 1])], parts[1][int(off[1][b]):int(off[1][b + 1])]])
             assert_close("two calls, seq %d %s" % (b, name), got.permute(1, 0, 2)[None], ref, dtype)
+
+
+def test_hip_graph_capture_of_the_packed_entry_points():
+    """The packed calls in one captured graph, cut into sequence chunks (pair map kernel, pre-pass, state scans,
+    accumulating dQ launch, twin launch): replays, with the workspace scribbled over and eager work in between,
+    reproduce the eager results bit for bit."""
+    binding.la2_set_chunk_tokens(128)
+    lengths, H, d, dtype = [300, 0, 77, 512, 33], 2, 128, torch.bfloat16
+    t, cu = packed_inputs(lengths, H, d, dtype, seed=970, lam=[0.9, 0.99])
+    g = {k: v.to(DEV) for k, v in t.items()}
+    cu_g = cu.to(DEV)
+    n_max = max(lengths)
+    desc = binding._varlen_desc(g["q"], cu_g, n_max)
+    import ctypes
+    need = int(binding.load().la2_varlen_workspace_bytes(ctypes.byref(desc), g["q"].shape[0], binding.LA2_OP_BWD))
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+
+    def buffers():
+        like = lambda: torch.empty_like(g["q"])
+        return {"o": like(), "kvf": torch.empty_like(g["kv_init"]), "grads": (like(), like(), like()),
+                "dkv0": torch.empty_like(g["kv_init"]), "o_plain": like(), "g_plain": (like(), like(), like()),
+                "on": like(), "rstd": torch.empty((H, g["q"].shape[0]), device=DEV)}
+
+    def run(out):
+        binding.la2_fwd_varlen_state(g["q"], g["k"], g["v"], g["lam"], cu_g, n_max, kv_init=g["kv_init"], out=out["o"],
+                                     kv_final=out["kvf"], workspace=ws)
+        binding.la2_bwd_varlen_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], cu_g, n_max, kv_init=g["kv_init"],
+                                     d_kv_final=g["d_kv_final"], out=out["grads"], d_kv_init=out["dkv0"], workspace=ws)
+        binding.la2_fwd_varlen(g["q"], g["k"], g["v"], g["lam"], cu_g, n_max, out=out["o_plain"], workspace=ws)
+        binding.la2_bwd_varlen(g["q"], g["k"], g["v"], g["d_o"], g["lam"], cu_g, n_max, out=out["g_plain"], workspace=ws)
+        binding.la2_fwd_varlen_norm(g["q"], g["k"], g["v"], g["lam"], cu_g, n_max, 1e-5, out=out["on"], rstd=out["rstd"],
+                                    workspace=ws)
+
+    def flat(out):
+        return [out["o"], out["kvf"], *out["grads"], out["dkv0"], out["o_plain"], *out["g_plain"], out["on"]]
+
+    eager = buffers()
+    run(eager)
+    torch.cuda.synchronize()
+    captured = buffers()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(captured)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(captured)
+    torch.cuda.current_stream().wait_stream(side)
+    rows = slice(int(cu[0]), int(cu[-1]))
+    for replay in range(3):
+        for x in flat(captured):
+            x.fill_(float("nan"))
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(flat(captured), flat(eager))):
+            assert torch.equal(got[rows] if got.shape == g["q"].shape else got, ref[rows] if ref.shape == g["q"].shape else ref), (replay, i)
+        scratch = buffers()            # eager work between the replays
+        run(scratch)
+        torch.cuda.synchronize()
