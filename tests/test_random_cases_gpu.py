@@ -73,6 +73,16 @@ def test_random_case_norm_with_state(i):
     run_case(i, draw_case(i, dims=(64, 96, 128, 256), modes=("norm_state", "norm_state_nofinal"), salt=52000))
 
 
+@pytest.mark.parametrize("i", range(60))
+def test_random_case_packed_with_states(i):
+    """Packed batches with a start state, a final state and their gradients per sequence (16-bit types, head_dim 64
+    and 128), random lengths on and off the block boundaries, chunked and not."""
+    c = draw_case(i, modes=("varlen_state", "varlen_state_nofinal"), salt=63000)
+    if c["dtype"] == torch.float32:
+        c["dtype"] = torch.bfloat16 if i % 2 else torch.float16
+    run_case(i, c)
+
+
 def run_case(i, c):
     dtype, d, b, H, n = c["dtype"], c["d"], c["b"], c["H"], c["n"]
     tag = "case %d %s" % (i, {k: (v if k != "lam" else v.tolist()) for k, v in c.items()})
@@ -89,6 +99,42 @@ def run_case(i, c):
     binding.la2_set_scan_variant(c["variant"])
     q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
 
+    if c["mode"] in ("varlen_state", "varlen_state_nofinal"):   # packed sequences, each with states of its own
+        final = c["mode"] == "varlen_state"
+        rng = np.random.default_rng(c["seed"])
+        lengths = [int(x) for x in rng.integers(0, n + 1, size=b + 3)]
+        lengths[int(rng.integers(0, len(lengths)))] = n           # one of them reaches the stated maximum
+        total = sum(lengths)
+        tt = workloads.Workload("random", 1, H, max(total, 1), d, dtype, seed=c["seed"], backward=True).tensors()
+        pk = {name: tt[name][0, :, :total].permute(1, 0, 2).contiguous() for name in ("q", "k", "v", "d_o")}
+        gp = {name: pk[name].to(DEV) for name in pk}
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device=DEV)
+        init = torch.randn((len(lengths), H, d, d), generator=gen, dtype=torch.float32) * 0.3
+        dfin = torch.randn((len(lengths), H, d, d), generator=gen, dtype=torch.float32) * 0.3
+        o, kvf = binding.la2_fwd_varlen_state(gp["q"], gp["k"], gp["v"], g["lam"], cu, n, kv_init=init.to(DEV),
+                                              want_final=final)
+        dq, dk, dv, dkv0 = binding.la2_bwd_varlen_state(gp["q"], gp["k"], gp["v"], gp["d_o"], g["lam"], cu, n,
+                                                        kv_init=init.to(DEV), d_kv_final=dfin.to(DEV) if final else None)
+        torch.cuda.synchronize()
+        lo = 0
+        for s_, m in enumerate(lengths):
+            i64, f64 = to64(init[s_:s_ + 1]), (to64(dfin[s_:s_ + 1]) if final else None)
+            if m == 0:
+                if final:
+                    assert torch.equal(kvf[s_].cpu(), init[s_]), tag
+                assert torch.equal(dkv0[s_].cpu(), dfin[s_] if final else torch.zeros_like(dfin[s_])), tag
+                continue
+            sq = {name: to64(pk[name][lo:lo + m]).transpose(1, 0, 2)[None] for name in pk}
+            ro, rkvf = oracle.fwd_recurrent(sq["q"], sq["k"], sq["v"], lam, kv_init=i64, return_state=True)
+            refs = oracle.bwd_recurrent_state(sq["q"], sq["k"], sq["v"], sq["d_o"], lam, kv_init=i64, d_kv_final=f64)
+            assert_close(tag + " seq %d o" % s_, o[lo:lo + m].permute(1, 0, 2)[None], ro, dtype)
+            if final:
+                assert_close(tag + " seq %d kv_final" % s_, kvf[s_:s_ + 1], rkvf, dtype)
+            for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs[:3]):
+                assert_close(tag + " seq %d %s" % (s_, name), got[lo:lo + m].permute(1, 0, 2)[None], ref, dtype)
+            assert_close(tag + " seq %d d_kv_init" % s_, dkv0[s_:s_ + 1], refs[3], dtype)
+            lo += m
+        return
     if c["mode"] == "varlen":   # the batch rows become packed sequences of random lengths <= n
         rng = np.random.default_rng(c["seed"])
         lengths = [int(x) for x in rng.integers(0, n + 1, size=b + 2)]
