@@ -119,7 +119,11 @@ def main():
                          "workload and print its time.  OP: fwd, bwd, bwd_saved (backward from the forward's chunk "
                          "states), fwd_norm, bwd_norm, decode, decode8 (8 tokens per launch).  WORKLOAD: c3_0 .. c3_3 "
                          "(the sweep points), c2, c4 (decode ops take c5)")
-    ap.add_argument("--profile-iters", type=int, default=100)
+    ap.add_argument("--profile-iters", type=int, default=400)
+    ap.add_argument("--profile-settle-ms", type=float, default=80.0,
+                    help="with --profile: call the operation for this long before the timed loop (0 for counter passes, "
+                         "whose values do not depend on the clocks); a kernel-trace summary then takes each kernel's "
+                         "steady-state duration from the last third of its dispatches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus %d is not supported. "
@@ -196,28 +200,30 @@ def main():
             toks = [tuple(x.to(dev) for x in dw.token(gen)) for _ in range(8)]
             if op == "decode":
                 o5 = torch.empty_like(toks[0][0])
-                ms = time_ms(lambda: binding.la2_decode_step(*toks[0], lam5, kv, out=o5), iters, warm=20)
+                ms = time_ms(lambda: binding.la2_decode_step(*toks[0], lam5, kv, out=o5), iters, warm=20,
+                             settle_ms=args.profile_settle_ms)
             else:
                 qm, km, vm = (torch.stack([toks[i][j] for i in range(8)], 2).contiguous() for j in range(3))
                 om = torch.empty_like(qm)
-                ms = time_ms(lambda: binding.la2_decode_multi(qm, km, vm, lam5, kv, out=om), iters, warm=20)
-            print(json.dumps({"op": op, "workload": dw.name, "ms": round(ms, 5)}))
+                ms = time_ms(lambda: binding.la2_decode_multi(qm, km, vm, lam5, kv, out=om), iters, warm=20,
+                             settle_ms=args.profile_settle_ms)
+            print(json.dumps({"op": op, "workload": dw.name, "ms": round(ms, 5), "timed_calls": iters}))
             return
         table = {"c3_%d" % i: w_ for i, w_ in enumerate(workloads.CONFIG3)}
         table.update({"c2": workloads.CONFIG2, "c4": workloads.CONFIG4})
         wl_p = table[wname]
         g_p = stage(wl_p)
-        time_ms(lambda: fwd(g_p), 100)      # warm-up: lets the clocks settle
+        settle = args.profile_settle_ms
         if op == "fwd":
-            ms = time_ms(lambda: fwd(g_p), iters)
+            ms = time_ms(lambda: fwd(g_p), iters, settle_ms=settle)
         elif op == "bwd":
-            ms = time_ms(lambda: bwd(g_p), iters)
+            ms = time_ms(lambda: bwd(g_p), iters, settle_ms=settle)
         elif op == "bwd_saved":
             ws_b = torch.empty_like(g_p["ws"])
             fwd(g_p)
             ms = time_ms(lambda: binding.la2_bwd_state(g_p["q"], g_p["k"], g_p["v"], g_p["d_o"], g_p["lam"],
                                                        want_d_kv_init=False, out=g_p["grads"], workspace=ws_b,
-                                                       fwd_workspace=g_p["ws"]), iters)
+                                                       fwd_workspace=g_p["ws"]), iters, settle_ms=settle)
         elif op in ("fwd_norm", "bwd_norm"):
             rstd = torch.empty(g_p["q"].shape[:3], dtype=torch.float32, device=dev)
             d_u = torch.empty_like(g_p["q"])
@@ -226,10 +232,11 @@ def main():
             f_n()
             ms = time_ms(f_n if op == "fwd_norm" else
                          (lambda: binding.la2_bwd_norm(g_p["q"], g_p["k"], g_p["v"], g_p["o"], rstd, g_p["d_o"],
-                                                       g_p["lam"], out=g_p["grads"], d_u=d_u, workspace=g_p["ws"])), iters)
+                                                       g_p["lam"], out=g_p["grads"], d_u=d_u, workspace=g_p["ws"])), iters,
+                         settle_ms=settle)
         else:
             raise SystemExit("bench.py: unknown --profile operation %r" % op)
-        print(json.dumps({"op": op, "workload": wl_p.name, "ms": round(ms, 5),
+        print(json.dumps({"op": op, "workload": wl_p.name, "ms": round(ms, 5), "timed_calls": iters,
                           "chunk_plan": binding.la2_chunk_plan(g_p["q"]),
                           "token_heads": wl_p.token_heads, "head_dim": wl_p.head_dim}))
         return
