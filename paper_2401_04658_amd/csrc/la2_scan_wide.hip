@@ -62,8 +62,21 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w;
-  const int which = (int)blockIdx.y;   // scan 0 or 1 of a dual launch
-  const int chain = (int)blockIdx.x / p.nchunks, chunk = (int)blockIdx.x % p.nchunks;
+  // A dual launch (the dK and the dV scan of Algorithm 2, which both read Q and dO) has two workgroups per (chain,
+  // chunk), one per scan.  They sit eight workgroup numbers apart, i.e. on the same XCD and started at about the same
+  // time, so that the second read of a shared tile can hit that XCD's L2 (workgroup numbers go round the eight XCDs);
+  // when the count of pairs is no multiple of eight they are neighbours instead.
+  int which = 0, wg = (int)blockIdx.x;
+  if (!STATE_ONLY && p.nscan == 2) {
+    if (((gridDim.x >> 1) & 7) == 0) {
+      which = (int)(blockIdx.x >> 3) & 1;
+      wg = (int)((blockIdx.x >> 4) << 3) | (int)(blockIdx.x & 7);
+    } else {
+      which = (int)(blockIdx.x & 1);
+      wg = (int)(blockIdx.x >> 1);
+    }
+  }
+  const int chain = wg / p.nchunks, chunk = wg % p.nchunks;
   const int bi = chain / p.heads, hi = chain % p.heads;
   int64_t base;
   int n;
@@ -221,7 +234,7 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
 
 template <typename E, int D>
 hipError_t launch_wide(bool reverse, bool state_only, const ScanParams& p, hipStream_t s) {
-  const dim3 g((unsigned)((int64_t)p.batch * p.heads * p.nchunks), state_only ? 1u : (unsigned)p.nscan), b(2 * D);
+  const dim3 g((unsigned)((int64_t)p.batch * p.heads * p.nchunks * (state_only ? 1 : p.nscan))), b(2 * D);
   if (!state_only && !reverse && p.rstd != nullptr) {
     hipLaunchKernelGGL((scan_wide_kernel<E, D, false, false, true>), g, b, 0, s, p);
   } else if (state_only) {
