@@ -242,3 +242,38 @@ def test_hip_graph_capture_of_the_packed_entry_points():
         scratch = buffers()            # eager work between the replays
         run(scratch)
         torch.cuda.synchronize()
+
+
+def test_padded_rows_and_head_major_storage():
+    """Packed tensors need not be dense: rows padded to d + 8 elements, and heads stored outermost ([H, total, d]
+    viewed as [total, H, d]); states stay dense."""
+    lengths, H, d, dtype = [75, 0, 200, 33], 3, 128, torch.bfloat16
+    t, cu = packed_inputs(lengths, H, d, dtype, seed=980, lam=[0.9, 0.95, 0.99])
+    cu_g = cu.to(DEV)
+    total = int(sum(lengths))
+
+    def padded(x):
+        store = torch.zeros((total, H, d + 8), dtype=x.dtype, device=DEV)
+        store[..., :d] = x.to(DEV)
+        return store[..., :d]
+
+    def head_major(x):
+        return x.permute(1, 0, 2).contiguous().to(DEV).permute(1, 0, 2)
+
+    dense = {k: v.to(DEV) for k, v in t.items()}
+    ref_o, ref_kvf = binding.la2_fwd_varlen_state(dense["q"], dense["k"], dense["v"], dense["lam"], cu_g, max(lengths),
+                                                  kv_init=dense["kv_init"])
+    ref_g = binding.la2_bwd_varlen_state(dense["q"], dense["k"], dense["v"], dense["d_o"], dense["lam"], cu_g, max(lengths),
+                                         kv_init=dense["kv_init"], d_kv_final=dense["d_kv_final"])
+    for place in (padded, head_major):
+        g = {name: place(t[name]) for name in ("q", "k", "v", "d_o")}
+        assert not g["q"].is_contiguous()
+        o, kvf = binding.la2_fwd_varlen_state(g["q"], g["k"], g["v"], dense["lam"], cu_g, max(lengths),
+                                              kv_init=dense["kv_init"])
+        got = binding.la2_bwd_varlen_state(g["q"], g["k"], g["v"], g["d_o"], dense["lam"], cu_g, max(lengths),
+                                           kv_init=dense["kv_init"], d_kv_final=dense["d_kv_final"])
+        torch.cuda.synchronize()
+        assert o.stride() == g["q"].stride()
+        assert torch.equal(o, ref_o) and torch.equal(kvf, ref_kvf), place.__name__
+        for a, b in zip(got, ref_g):
+            assert torch.equal(a, b), place.__name__
