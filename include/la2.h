@@ -154,10 +154,11 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
  *   d_kv_init   out  gradient with respect to kv_init, or NULL if not wanted
  * la2_bwd_state needs the kv_init the forward pass was given (dq depends on it).  All other arguments
  * as for la2_fwd / la2_bwd, which are these functions with NULL states.  State pointers are 16-byte
- * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen:
- * when kv_final / d_kv_final is given and seqlen is not a multiple of G = 32 (head_dim 96 and 256 have no such
- * granule), the last seqlen % G positions run in a short-run kernel (the scan kernels of head_dim 64 and 128
- * form states after whole blocks only).  seqlen == 0 copies the state through (kv_final = kv_init,
+ * aligned.  Workspace: la2_workspace_bytes(desc, LA2_OP_FWD_STATE / LA2_OP_BWD_STATE).  Any seqlen: the 16-bit
+ * kernels form the state right after (and take the gradient right behind) the last position inside their block
+ * loop, whatever the length; for LA2_F32 at head_dim 64 and 128, when kv_final / d_kv_final is given and seqlen
+ * is not a multiple of 32, the last seqlen % 32 positions run in a short-run kernel (those block kernels form
+ * states after whole blocks only).  seqlen == 0 copies the state through (kv_final = kv_init,
  * d_kv_init = d_kv_final; zero if the input is NULL).
  */
 la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, const void* v,
@@ -314,10 +315,10 @@ la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, 
  *                            `workspace`; 256-byte aligned (LA2_ERR_WORKSPACE otherwise); only read.  NULL, or a
  *                            problem that needs no workspace: exactly la2_bwd_state.
  *   fwd_workspace_bytes      its size; smaller than what that forward call needed: LA2_ERR_WORKSPACE
- *   fwd_wrote_kv_final       non-zero if that forward call was given a kv_final pointer.  Such a call plans its
- *                            chunks for the whole blocks of a ragged seqlen only (see la2_fwd_state); if that plan
- *                            differs from this call's, the saved states are not used and the result is that of
- *                            la2_bwd_state.
+ *   fwd_wrote_kv_final       non-zero if that forward call was given a kv_final pointer.  With LA2_F32 data such
+ *                            a call plans its chunks for the whole blocks of a ragged seqlen only (see
+ *                            la2_fwd_state); if that plan differs from this call's, the saved states are not used
+ *                            and the result is that of la2_bwd_state.
  * The chunk plan also depends on la2_set_chunk_tokens() and the device: both calls must see the same.
  */
 la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v,

@@ -19,15 +19,20 @@ namespace {
 // plain atomics, read once per call.
 std::atomic<int> g_chunk_tokens_override{0};  // la2_set_chunk_tokens()
 std::atomic<int> g_scan_variant{0};           // la2_set_scan_variant()
-// The block kernels form states after whole blocks only: 32 positions for the kernels that take states
-// (half-block 16-bit kernel of head_dim 64 and 128, fp32 kernels).
 bool is16(int dtype) { return dtype == LA2_BF16 || dtype == LA2_F16; }
 // Head dimensions 96 and 256 have kernels of their own: one 16-bit block kernel that is exact at a ragged end
 // (no granule), and the token recurrence for fp32.
 bool wide(int head_dim) { return head_dim == 96 || head_dim == 256; }
 bool supported_head_dim(int head_dim) { return head_dim == 64 || head_dim == 128 || wide(head_dim); }
+// The fp32 block kernels (head_dim 64 and 128) form states after whole blocks of 32 positions only; the 16-bit
+// kernels form the state at a ragged end inside their block loop (no granule).
 int state_granule(const la2_desc* d) {
-  return wide(d->head_dim) ? 1 : 32;
+  return (wide(d->head_dim) || is16(d->dtype)) ? 1 : 32;
+}
+// 16-bit half-block kernels (head_dim 64 / 128): a state wanted behind, or coming in behind, a last block that is
+// not full needs their ragged-end instantiation (ScanParams::ragged_state)
+bool ragged_end(const la2_desc* d) {
+  return is16(d->dtype) && !wide(d->head_dim) && d->seqlen % 32 != 0;
 }
 
 int device_cu_count() {
@@ -492,6 +497,7 @@ la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, co
     ScanArgs a{q, k, v, o};
     a.init = kv_init;
     a.fin = kv_final;
+    a.ragged_state = kv_final != nullptr && ragged_end(desc);
     a.rstd = rstd;
     a.eps = eps;
     a.rstd_stride = desc->seqlen;
@@ -648,6 +654,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   for_dv.fin = d_kv_init;
   for_dk.init = rev_init;
   for_dk.init_tr = true;
+  for_dv.ragged_state = for_dk.ragged_state = d_kv_final != nullptr && ragged_end(desc);
   if (is16(desc->dtype))
     return run_dual_reverse_scan(&blocks, pl_rev, for_dv, for_dk, lambda, rev_workspace, s, /*local_ready=*/fuse);
   st = run_scan(&blocks, pl_rev, true, for_dv, lambda, workspace, s);

@@ -318,21 +318,6 @@ struct UpdateDecay {
     for (int j = 0; j < 8; j++) r[j] = (E)((float)z[j] * (step * gj[j]));
     return r;
   }
-  // Forward update of a chain's ragged last block of rem < B rows, when the state right after row rem - 1 is
-  // wanted: row c weighs lambda^(rem-1-c), rows from rem on nothing (they are zero, but a weight with a negative
-  // exponent could be infinite).  One exp2 per element: runs once per chain.
-  template <typename E>
-  __device__ __forceinline__ ex8<E> apply_ragged(ex8<E> z, int c0, int rem) const {
-    static_assert(!REV, "reverse weights count from the block's first row: a ragged block needs no others");
-    ex8<E> r;
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-      const int c = c0 + 4 * hh + 8 * (j >> 2) + (j & 3);
-      const float wgt = c < rem ? fast_exp2(l2 * (float)(rem - 1 - c)) : 0.f;
-      r[j] = (E)((float)z[j] * wgt);
-    }
-    return r;
-  }
 };
 
 }  // namespace bf16k

@@ -37,8 +37,8 @@ constexpr int kBH = 32;
 // acc_y = Q leaves the local dKV states of the sequence chunks, so the dK / dV scan needs no pass of its own
 // over Q and dO to form them.
 //
-// RS: states at sequence ends that are not block boundaries (ScanParams::ragged_state; packed batches with state
-// hand-over, where every sequence has a length of its own).  Forward: when the chain's last block has rem < B
+// RS: states at sequence ends that are not block boundaries (ScanParams::ragged_state; segments of a ragged length
+// and packed batches with state hand-over, where every sequence has a length of its own).  Forward: when the chain's last block has rem < B
 // rows and the final state is wanted, that block's update weighs row c by lambda^(rem-1-c) and the carried state
 // by lambda^rem, which gives the state right after the last position.  Reverse: a start state that enters behind
 // such a block reaches row r with lambda^(rem-1-r) and is carried on with lambda^rem.  A chain without positions
@@ -49,7 +49,7 @@ void scan_bf16_half_kernel(ScanParams p) {
   static_assert(D == 128 || D == 64, "head_dim");
   static_assert(!NORM || (!REV && !TWIN), "the Norm epilogue belongs to the forward pass");
   static_assert(!ACC || (!REV && !TWIN && !NORM), "the accumulating wave group rides on a plain forward scan");
-  static_assert(!RS || (!ACC && !NORM), "ragged-end states: plain forward scans and reverse scans");
+  static_assert(!RS || !ACC, "ragged-end states: forward scans (with or without the Norm epilogue) and reverse scans");
   constexpr int B = kBH;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE, LW = C::LW;
@@ -296,7 +296,28 @@ void scan_bf16_half_kernel(ScanParams p) {
     if (REV ? gs != nullptr : (which ? p.fin[1] : p.fin[0]) != nullptr) rag_rem = n % B;
   }
   rag_rem = __builtin_amdgcn_readfirstlane(rag_rem);
-  const float lamRag = uniform(exp2f(l2 * (float)rag_rem));
+  // The per-block code has no branch for that block.  The factors that differ there are variables which change
+  // between two blocks: the carried state's decay, the weight of the carried part of a row (reverse) and the update
+  // weights of the Z fragments (forward: kept in registers in this instantiation, element j of fragment q is row
+  // c = 16 q + 4 hh + 8 (j / 4) + j % 4), switched at the top of the block step, outside its scheduled slots.
+  float lam_var = lamB, isc_var = inter_scale;
+  float wz[2][8];
+  auto set_update_weights = [&](int rows) __attribute__((always_inline)) {   // rows valid in the block (B: a full one)
+#pragma unroll
+    for (int q = 0; q < 2; q++)
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        const int c = 16 * q + 4 * hh + 8 * (j >> 2) + (j & 3);
+        wz[q][j] = c < rows ? fast_exp2(l2 * (float)(rows - 1 - c)) : 0.f;
+      }
+  };
+  if constexpr (RS && !REV) set_update_weights(B);
+  if constexpr (RS && REV) {
+    if (rag_rem != 0) {   // the first block this scan meets: the start state sits right behind row rag_rem - 1
+      lam_var = uniform(exp2f(l2 * (float)rag_rem));
+      isc_var = l32 < rag_rem ? exp2f(l2 * (float)(rag_rem - 1 - l32)) : 0.f;
+    }
+  }
 
   // prologue: the first NBUF - 1 blocks' tiles
 #pragma unroll
@@ -339,9 +360,19 @@ void scan_bf16_half_kernel(ScanParams p) {
     const int blk = REV ? blk_hi - 1 - it : blk_lo + it;
     const bool has_next = it + 1 < nblk, has_ahead = it + NBUF - 1 < nblk;
     const int nb = REV ? blk - 1 : blk + 1;
-    // RS: this is the ragged block whose state weights differ (a reverse scan meets it first, a forward scan last)
-    const bool rag = RS && rag_rem != 0 && (REV ? it == 0 : !has_next);
-    const float lam_blk = (RS && rag) ? lamRag : lamB;
+    if constexpr (RS && !REV) {   // the ragged block is the last one a forward scan meets
+      if (rag_rem != 0 && !has_next) {
+        set_update_weights(rag_rem);
+        lam_var = uniform(exp2f(l2 * (float)rag_rem));
+      }
+    }
+    if constexpr (RS && REV) {    // ... and the first one of a reverse scan: back to a full block's factors
+      if (rag_rem != 0 && it == 1) {
+        lam_var = lamB;
+        isc_var = inter_scale;
+      }
+    }
+    const float lam_blk = RS ? lam_var : lamB;
     const E* tX = sCur[xi];
     const E* tY = sCur[yi];
     const E* tZ = sCur[zi];
@@ -386,8 +417,8 @@ void scan_bf16_half_kernel(ScanParams p) {
       if ((KS == 8 && (ks == 3 || ks == 5)) || (KS == 4 && (ks == 2 || ks == 3))) {
         const int q = KS == 8 ? (ks - 3) >> 1 : ks - 2;
         if constexpr (RS && !REV) {
-          if (rag) zd[q] = decay.apply_ragged(zf[q], 16 * q, rag_rem);
-          else zd[q] = decay.apply(zf[q], 16 * q);
+#pragma unroll
+          for (int j = 0; j < 8; j++) zd[q][j] = (E)((float)zf[q][j] * wz[q][j]);
         } else {
           zd[q] = decay.apply(zf[q], 16 * q);
         }
@@ -403,10 +434,7 @@ void scan_bf16_half_kernel(ScanParams p) {
       for (int v = 0; v < 16; v++) kv[NT - 1][v] *= lam_blk;
       pin(kv[NT - 1]);
       // the carried part takes the decay at this lane's position
-      float isc = inter_scale;
-      if constexpr (RS && REV) {   // the start state sits right behind row rag_rem - 1
-        if (rag) isc = l32 < rag_rem ? exp2f(l2 * (float)(rag_rem - 1 - l32)) : 0.f;
-      }
+      const float isc = (RS && REV) ? isc_var : inter_scale;
 #pragma unroll
       for (int v = 0; v < 16; v++) inter[v] *= isc;
       pin(inter);
@@ -531,12 +559,15 @@ hipError_t launch_half(bool reverse, bool twin, const ScanParams& p, hipStream_t
   // compute unit to itself) measured no faster: such launches are bound by the memory system, not by the
   // bytes a workgroup keeps in flight.
   constexpr int kPlain = 2 * D, kDouble = 4 * D;   // threads: one wave per 32 value features, or two such groups
-  if (p.ragged_state != 0) {   // the host pairs this only with a reverse twin launch or a plain forward scan
+  if (p.ragged_state != 0) {   // the host pairs this only with a reverse twin launch or a forward scan without ACC
     if (twin && reverse)
       hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, true, true, 3, false, false, true>), dim3((unsigned)(grid / 2)),
                          dim3(kDouble), 0, s, p);
     else if (!twin && !reverse && p.acc_states == nullptr && p.rstd == nullptr)
       hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, false, 3, false, false, true>), dim3((unsigned)grid),
+                         dim3(kPlain), 0, s, p);
+    else if (!twin && !reverse && p.acc_states == nullptr)
+      hipLaunchKernelGGL((scan_bf16_half_kernel<E, D, false, false, 3, true, false, true>), dim3((unsigned)grid),
                          dim3(kPlain), 0, s, p);
     else
       return hipErrorInvalidValue;

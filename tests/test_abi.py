@@ -188,14 +188,17 @@ def bwd_state(lib, desc, kv_init=None, d_kv_final=None, d_kv_init=None, q=P):
 
 
 def test_state_entry_points_validate_before_any_launch(lib):
-    # a gradient entering at the end of a sequence that does not end on a block boundary needs workspace
+    # fp32 data: a gradient entering at the end of a sequence that does not end on a block boundary needs workspace
     # (the hand-over of dKV from the token-by-token tail to the block kernels)
-    d = dense(lib, 300, 2, 100, 64, binding.LA2_BF16)
+    d = dense(lib, 300, 2, 100, 64, binding.LA2_F32)
     assert lib.la2_workspace_bytes(ctypes.byref(d), 1) == 0
     assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 300 * 2 * 64 * 64 * 4
     assert lib.la2_workspace_bytes(ctypes.byref(d), 2) == 0
     assert bwd_state(lib, d, d_kv_final=P) == E_WS
-    d = dense(lib, 300, 2, 128, 64, binding.LA2_BF16)
+    d = dense(lib, 300, 2, 128, 64, binding.LA2_F32)
+    assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 0
+    # the 16-bit kernels form the state at a ragged end themselves: no tail, no hand-over
+    d = dense(lib, 300, 2, 100, 64, binding.LA2_BF16)
     assert lib.la2_workspace_bytes(ctypes.byref(d), 3) == 0
     # misaligned state pointers
     d = dense(lib, 300, 1, 128, 64, binding.LA2_BF16)
@@ -528,10 +531,13 @@ def test_state_norm_entry_points_validate_before_any_launch(lib):
         lib.la2_bwd_state_norm(ref, P, P, P, o, rstd, P, P, None, dkvn, d_u, P, P, P, dkv0, ws, wsb, None)
     assert bn(o=None) == E_NULL and bn(rstd=None) == E_NULL and bn(d_u=None) == E_NULL
     assert bn(d_u=P + 4) == E_ALIGN and bn(dkvn=P + 4) == E_ALIGN and bn(dkv0=P + 8) == E_ALIGN
-    # a gradient coming in at a ragged end needs the hand-over state in the workspace: checked before the row pass
+    # fp32 data: a gradient coming in at a ragged end needs the hand-over state in the workspace: checked before
+    # the row pass (the 16-bit kernels form the state at a ragged end themselves)
+    assert lib.la2_workspace_bytes(ref, 3) == 0
+    d.dtype = binding.LA2_F32
+    d.stride_b, d.stride_h, d.stride_n = 2 * 100 * 128, 100 * 128, 128
     assert bn(dkvn=P) == E_WS
-    need = lib.la2_workspace_bytes(ref, 3)
-    assert need == 2 * 2 * 128 * 128 * 4
+    assert lib.la2_workspace_bytes(ref, 3) == 2 * 2 * 128 * 128 * 4
     # an empty segment: nothing to check but the descriptor
     e = dense(lib, 2, 2, 0, 128, binding.LA2_BF16)
     assert lib.la2_fwd_state_norm(ctypes.byref(e), None, None, None, None, None, 1e-6, None, None, None, None, 0, None) == OK
