@@ -504,17 +504,11 @@ la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, co
     st = run_scan(&blocks, pl, false, a, lambda, workspace, s);
     if (st != LA2_OK || !split) return st;
   }
-  // the positions after the last whole block, token by token, from the state the blocks left
+  // fp32 data: the positions after the last whole block, token by token, from the state the blocks left
   la2::RecurParams r = recur_params(desc, lambda, blocks.seqlen, desc->seqlen, false);
   r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
   r.init[0] = blocks.seqlen > 0 ? kv_final : kv_init;
   r.fin[0] = kv_final;
-  if (is16(desc->dtype)) {   // block kernel for short runs, with the epilogue
-    r.rstd = rstd;
-    r.eps = eps;
-    r.rstd_stride = desc->seqlen;
-    return la2::launch_tail_bf16(desc->dtype, desc->head_dim, desc->batch, r, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
-  }
   if (la2::launch_recur(desc->head_dim, desc->dtype, desc->batch, 1, r, s) != hipSuccess) return LA2_ERR_LAUNCH;
   return rstd != nullptr ? normalise_rows(blocks.seqlen, desc->seqlen) : LA2_OK;
 }
@@ -1027,11 +1021,12 @@ la2_status decode_multi_impl(int32_t batch, int32_t heads, int32_t head_dim, int
     return LA2_ERR_STRIDE_ALIGN;
   la2_desc d;
   la2_desc_dense(&d, batch, heads, ntokens, head_dim, (la2_dtype)qkv_dtype);
-  // A run with at least one whole block goes through the block kernels (the state in place: a workgroup
-  // reads its chain's start state before it writes the final one) and only the rest token by token; they
-  // are 4-5x faster per position.  Not when that launch would be sequence-chunked: there is no workspace here.
-  const la2_desc wb = whole_blocks(&d);
-  if (wb.seqlen > 0 && make_plan(&wb).workspace == 0)
+  // A run of at least one whole block goes through the scan kernels (the state in place: a workgroup reads its
+  // chain's start state before it writes the final one; fp32 data: only the rest token by token).  Not when that
+  // launch would be sequence-chunked: there is no workspace here.  Shorter 16-bit runs take the single-buffered
+  // block kernel below, which measured 2-5 us faster on 2 to 8 positions.
+  const la2_desc wb = whole_blocks(&d);   // what the scan kernels would process (fp32: the whole blocks only)
+  if (ntokens >= 32 && make_plan(&wb).workspace == 0)
     return fwd_state_impl(&d, q, k, v, lambda, kv_state, o, kv_state, rstd, eps, nullptr, 0, hip_stream);
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   if (wide(head_dim) && is16(qkv_dtype)) {   // the block kernel of these head dimensions, in one chunk
