@@ -21,6 +21,20 @@ int main(void) {
   la2_desc_dense(&d, 1, 2, 1024, 128, LA2_BF16);
   if (la2_workspace_bytes(&d, LA2_OP_FWD) != (size_t)2 * 4 * 128 * 128 * 4) return 8;
   la2_set_chunk_tokens(0);
+  /* packed batches: a negative total, a missing offset array; states over packed batches take the 16-bit types */
+  la2_desc_dense(&d, 4, 2, 300, 128, LA2_BF16);
+  d.stride_b = 0; d.stride_h = 128; d.stride_n = 256;
+  if (la2_fwd_varlen(&d, NULL, -1, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_ERR_SHAPE) return 9;
+  if (la2_fwd_varlen_state(&d, NULL, 0, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != LA2_ERR_NULL) return 10;
+  d.dtype = LA2_F32;
+  {
+    float state[4];
+    if (la2_fwd_varlen_state(&d, NULL, 0, NULL, NULL, NULL, NULL, state, NULL, NULL, NULL, 0, NULL) != LA2_ERR_DTYPE) return 11;
+    if (la2_bwd_varlen_state(&d, NULL, 0, NULL, NULL, NULL, NULL, NULL, NULL, state, NULL, NULL, NULL, NULL, NULL, 0, NULL) !=
+        LA2_ERR_DTYPE)
+      return 12;
+  }
+  if (la2_varlen_workspace_bytes(&d, 0, LA2_OP_FWD) != la2_workspace_bytes(&d, LA2_OP_FWD)) return 13;
   printf("abi client ok\n");
   return 0;
 }
