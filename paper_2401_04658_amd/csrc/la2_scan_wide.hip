@@ -48,26 +48,34 @@ struct PlainAddr {
 
 // NORM: the Norm epilogue of eq. (2) on a forward scan (the waves exchange the sums of squares of their
 // 32 features of every row through LDS, one more barrier per block; wave 0 stores r).
-template <typename E, int D, bool REV, bool STATE_ONLY, bool NORM = false>
-__global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanParams p) {
+// TWIN (head_dim 96, reverse): both scans of Algorithm 2's second loop in one workgroup of two wave groups, as
+// in the kernels for head_dim 64 / 128: the two scans read the same two tensors with the roles of Y and Z
+// exchanged (requires y[1] == z[0] and z[1] == y[0]), so the workgroup streams four tiles per block (x of scan
+// 0, x of scan 1, Q, dO) and fetches each exactly once.  (Head_dim 256: sixteen waves of 128 state registers do
+// not fit a compute unit.)
+template <typename E, int D, bool REV, bool STATE_ONLY, bool NORM = false, bool TWIN = false>
+__global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) void scan_wide_kernel(ScanParams p) {
   static_assert(!NORM || (!REV && !STATE_ONLY), "the Norm epilogue belongs to the forward scan");
+  static_assert(!TWIN || (REV && !STATE_ONLY && !NORM), "the twin workgroup is the backward pass's reverse launch");
   constexpr int B = 32;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
-  constexpr int NTL = STATE_ONLY ? 2 : 3;   // tiles of a block: [X,] Y, Z
-  constexpr int YI = NTL - 2, ZI = NTL - 1;
-  using Loader = TileLoader<D, NTL, B, NT>;
+  constexpr int NTL = TWIN ? 4 : STATE_ONLY ? 2 : 3;   // tiles of a block: [X,] Y, Z; twin: X0, X1, Y0 = Z1, Z0 = Y1
+  using Loader = TileLoader<D, NTL, B, (TWIN ? 2 : 1) * NT>;
   __shared__ __attribute__((aligned(1024))) E sT[2][NTL][TILE];
   float* const sRed = NormExchange<NORM ? B * (D / 32) : 0>::get();   // [position][wave]
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
-  const int dvt = w;
+  const int dvt = w % NT;
+  const int group = TWIN ? __builtin_amdgcn_readfirstlane(w / NT) : 0;   // twin: which scan this wave belongs to
+  // this wave's X, Y, Z among the tiles of a block
+  const int xi = TWIN ? group : 0, yi = TWIN ? 2 + group : NTL - 2, zi = TWIN ? 3 - group : NTL - 1;
   // A dual launch (the dK and the dV scan of Algorithm 2, which both read Q and dO) has two workgroups per (chain,
   // chunk), one per scan.  They sit eight workgroup numbers apart, i.e. on the same XCD and started at about the same
   // time, so that the second read of a shared tile can hit that XCD's L2 (workgroup numbers go round the eight XCDs);
   // when the count of pairs is no multiple of eight they are neighbours instead.
-  int which = 0, wg = (int)blockIdx.x;
-  if (!STATE_ONLY && p.nscan == 2) {
+  int which = group, wg = (int)blockIdx.x;
+  if (!TWIN && !STATE_ONLY && p.nscan == 2) {
     if (((gridDim.x >> 1) & 7) == 0) {
       which = (int)(blockIdx.x >> 3) & 1;
       wg = (int)((blockIdx.x >> 4) << 3) | (int)(blockIdx.x & 7);
@@ -94,10 +102,17 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
   const float l2 = log2f(p.lambda[hi]);
 
   Loader loader(w, l, n, stride_n);
-  if (!STATE_ONLY)
-    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.x[1] : p.x[0]) + base);
-  loader.g[YI] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.y[1] : p.y[0]) + base);
-  loader.g[ZI] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.z[1] : p.z[0]) + base);
+  if (TWIN) {
+    loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
+    loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[1]) + base);
+    loader.g[2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.y[0]) + base);
+    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.z[0]) + base);
+  } else {
+    if (!STATE_ONLY)
+      loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.x[1] : p.x[0]) + base);
+    loader.g[NTL - 2] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.y[1] : p.y[0]) + base);
+    loader.g[NTL - 1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(which ? p.z[1] : p.z[0]) + base);
+  }
   E* const gw = STATE_ONLY ? nullptr : reinterpret_cast<E*>(which ? p.w[1] : p.w[0]) + base;
   // head_dim 256: LaneAddr's precomputed offsets (one XOR per read); its read_row takes a row tile, always 0 here
   struct Pow2Addr : LaneAddr<D> {
@@ -148,14 +163,14 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
 
     ex8<E> zf[2];
 #pragma unroll
-    for (int q = 0; q < 2; q++) zf[q] = la.read_cols(cur[ZI], 16 * q, dvt);
+    for (int q = 0; q < 2; q++) zf[q] = la.read_cols(cur[zi], 16 * q, dvt);
 
     if (!STATE_ONLY) {
       // inter-block part W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] and scores S^T[c][r] = sum_k Y[c][k] X[r][k]
       f32x16 acc = zero16(), sd = zero16();
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
-        const ex8<E> xa = la.read_row(cur[0], ks), ya = la.read_row(cur[YI], ks);
+        const ex8<E> xa = la.read_row(cur[xi], ks), ya = la.read_row(cur[yi], ks);
         ex8<E> f;
 #pragma unroll
         for (int j = 0; j < 8; j++) f[j] = (E)kv[ks >> 1][8 * (ks & 1) + j];
@@ -211,7 +226,7 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
         zd[j] = (E)((float)zf[q][j] * fast_exp2(l2 * (float)(REV ? c + 1 : max(nv - 1 - c, 0))));
       }
 #pragma unroll
-      for (int t = 0; t < NT; t++) kv[t] = mfma(la.read_cols(cur[YI], 16 * q, t), zd, kv[t]);
+      for (int t = 0; t < NT; t++) kv[t] = mfma(la.read_cols(cur[yi], 16 * q, t), zd, kv[t]);
     }
   }
 
@@ -235,6 +250,13 @@ __global__ __launch_bounds__(2 * D, D == 96 ? 3 : 2) void scan_wide_kernel(ScanP
 template <typename E, int D>
 hipError_t launch_wide(bool reverse, bool state_only, const ScanParams& p, hipStream_t s) {
   const dim3 g((unsigned)((int64_t)p.batch * p.heads * p.nchunks * (state_only ? 1 : p.nscan))), b(2 * D);
+  if constexpr (D == 96) {
+    if (!state_only && reverse && p.nscan == 2 && p.y[1] == p.z[0] && p.z[1] == p.y[0]) {
+      hipLaunchKernelGGL((scan_wide_kernel<E, D, true, false, false, true>),
+                         dim3((unsigned)((int64_t)p.batch * p.heads * p.nchunks)), dim3(4 * D), 0, s, p);
+      return hipGetLastError();
+    }
+  }
   if (!state_only && !reverse && p.rstd != nullptr) {
     hipLaunchKernelGGL((scan_wide_kernel<E, D, false, false, true>), g, b, 0, s, p);
   } else if (state_only) {
