@@ -150,6 +150,15 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
   }
 
+  // The decay of the carried state is applied lazily: the registers hold S_st with S = 2^pend S_st (pend <= 0, the
+  // same for the whole wave), the carried part of a row and the update weights take the factor instead, and S_st is
+  // rescaled only when 2^-pend would grow past 2^40 (for a decay near 1 once in dozens of blocks; for a strong
+  // decay every block, which is the plain scheme).  At head_dim 256 the launch is bound by its vector instructions,
+  // and the 128 multiplies per lane and block were a fifth of them.  bf16 only: S_st and the scaled update rows
+  // are MFMA operands, and fp16's five exponent bits have no room for a factor like that (limit 0: the registers
+  // are brought up to date after every block).
+  constexpr float kPendLimit = std::is_same<E, __bf16>::value ? -40.f : 0.f;
+  float pend = 0.f;
   auto block_at = [&](int it) { return REV ? blk_hi - 1 - it : blk_lo + it; };
   loader.issue(sT[0], block_at(0));
   for (int it = 0; it < nblk; it++) {
@@ -177,7 +186,7 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
         acc = mfma(to_perm_order(f), xa, acc);
         sd = mfma(ya, xa, sd);
       }
-      const float carried = fast_exp2(l2 * (float)(REV ? max(nv - 1 - l32, 0) : l32 + 1));
+      const float carried = fast_exp2(l2 * (float)(REV ? max(nv - 1 - l32, 0) : l32 + 1) + pend);
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[v] *= carried;
       // intra-block part Z^T P^T
@@ -212,18 +221,22 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
       }
     }
     // state slice <- lambda^nv state + Y^T decay(Z): element j of a Z fragment is row 16 q + 8 (j / 4) + 4 hh + j % 4
-    const float lam_nv = uniform(fast_exp2(l2 * (float)nv));
+    pend = uniform(pend + l2 * (float)nv);
+    if (pend < kPendLimit) {   // (wave-uniform) bring the registers up to date
+      const float scale = uniform(fast_exp2(pend));
 #pragma unroll
-    for (int t = 0; t < NT; t++)
+      for (int t = 0; t < NT; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) kv[t][v] *= lam_nv;
+        for (int v = 0; v < 16; v++) kv[t][v] *= scale;
+      pend = 0.f;
+    }
 #pragma unroll
     for (int q = 0; q < 2; q++) {
       ex8<E> zd;
 #pragma unroll
       for (int j = 0; j < 8; j++) {
         const int c = 16 * q + 8 * (j >> 2) + 4 * hh + (j & 3);
-        zd[j] = (E)((float)zf[q][j] * fast_exp2(l2 * (float)(REV ? c + 1 : max(nv - 1 - c, 0))));
+        zd[j] = (E)((float)zf[q][j] * fast_exp2(l2 * (float)(REV ? c + 1 : max(nv - 1 - c, 0)) - pend));
       }
 #pragma unroll
       for (int t = 0; t < NT; t++) kv[t] = mfma(la.read_cols(cur[yi], 16 * q, t), zd, kv[t]);
@@ -240,10 +253,11 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     trf = (p.fin_transposed >> which) & 1;
   }
   if (gf != nullptr) {
+    const float scale = fast_exp2(pend);   // the pending decay
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) gf[state_index<D>(dvt, l32, hh, t, v, trf)] = kv[t][v];
+      for (int v = 0; v < 16; v++) gf[state_index<D>(dvt, l32, hh, t, v, trf)] = kv[t][v] * scale;
   }
 }
 
