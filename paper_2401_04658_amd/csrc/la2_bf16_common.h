@@ -77,6 +77,15 @@ __device__ __forceinline__ f32x16 mfma(ex8<_Float16> a, ex8<_Float16> b, f32x16 
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
+// MFMA 16x16x32: A 16 x 32 (lane l: row l % 16, k = 8 (l / 16) .. + 7), B 32 x 16 (column l % 16, same k),
+// D 16 x 16 (column l % 16, rows 4 (l / 16) .. + 3).
+__device__ __forceinline__ f32x4 mfma16(ex8<__bf16> a, ex8<__bf16> b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(ex8<_Float16> a, ex8<_Float16> b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
 // 2^x for x <= 0 with the bare hardware instruction (no denormal-range fix-up: results below
 // 2^-126 flush to 0, which is where these decay weights are negligible anyway).
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -284,6 +293,17 @@ __device__ __forceinline__ int state_index(int dvt, int l32, int hh, int t, int 
   const int dk = 32 * t + 8 * (v >> 2) + 4 * hh + (v & 3);
   const int dv = 32 * dvt + l32;
   return transposed ? dv * D + dk : dk * D + dv;
+}
+
+// A wave-uniform value moved to a scalar register for good: the compiler folds the builtin below away when it can
+// prove the value uniform, and then keeps a loop invariant like that in a vector register (or spills it).
+// The compiler does not look into an asm statement for the wait states that gfx950 wants between a vector
+// instruction that writes a register and a lane read of it, and between a vector instruction that writes a scalar
+// register and one that reads it: the statement brings its own.
+__device__ __forceinline__ float scalar_reg(float x) {
+  uint32_t r;
+  asm("s_nop 1\n\tv_readfirstlane_b32 %0, %1\n\ts_nop 1" : "=s"(r) : "v"(__float_as_uint(x)));
+  return __uint_as_float(r);
 }
 
 // A wave-uniform value, told to the compiler (lands in a scalar register instead of a vector one).

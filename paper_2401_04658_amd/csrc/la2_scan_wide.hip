@@ -27,18 +27,19 @@ struct PlainAddr {
     l32 = l & 31;
     hh = l >> 5;
     r0 = 4 * hh + (s16 >> 2);
-    trc = 2 * g2 + ((s16 & 3) >> 1);
-    trh = 4 * (s16 & 1);
+    // lane s of a group of sixteen takes the 8-byte piece with the two bits of its index s % 4 exchanged (read_cols_pi)
+    trc = 2 * g2 + (s16 & 1);
+    trh = 4 * ((s16 & 3) >> 1);
   }
   // Row fragment in natural k-order: features 16 ks + 8 hh .. + 7 of row l32.
   template <typename E>
   __device__ __forceinline__ ex8<E> read_row(const E* tile, int ks) const {
     return *reinterpret_cast<const ex8<E>*>(tile + l32 * D + 8 * ((2 * ks + hh) ^ swz<D>(l32)));
   }
-  // Fragment for a contraction over the 16 tile rows c0 .. c0 + 15 (c0 % 16 == 0) in permuted k-order, for
-  // column 32 t + l32 (see LaneAddr::read_cols).
+  // Fragment for a contraction over the 16 tile rows c0 .. c0 + 15 (c0 % 16 == 0) in permuted k-order (see
+  // LaneAddr::read_cols), for column 32 t + pi(l32), pi = bits 2 and 3 of the index exchanged.
   template <typename E>
-  __device__ __forceinline__ ex8<E> read_cols(const E* tile, int c0, int t) const {
+  __device__ __forceinline__ ex8<E> read_cols_pi(const E* tile, int c0, int t) const {
     union { struct { s16x4 lo, hi; } s; ex8<E> v; } u;
     u.s.lo = lds_read_tr(tile + (c0 + r0) * D + 8 * ((4 * t + trc) ^ swz<D>(r0)) + trh);
     u.s.hi = lds_read_tr(tile + (c0 + r0 + 8) * D + 8 * ((4 * t + trc) ^ swz<D>(r0 + 8)) + trh);
@@ -64,6 +65,15 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   using Loader = TileLoader<D, NTL, B, (TWIN ? 2 : 1) * NT>;
   __shared__ __attribute__((aligned(1024))) E sT[2][NTL][TILE];
   float* const sRed = NormExchange<NORM ? B * (D / 32) : 0>::get();   // [position][wave]
+  // Head_dim 256: the masked, decayed score tile of a block is the same for the eight waves.  Waves 0 .. 3 compute a
+  // 16 x 16 quarter each (16x16x32 MFMAs) and leave it in LDS in 16 bits, in the order in which a lane takes it as
+  // the intra-block product's operand: row r (80 bytes apart: sixteen rows fall into sixteen different 16-byte bank
+  // groups) holds, for k-step q and lane half hh, the eight columns c = 16 q + 8 (j / 4) + 4 hh + j % 4.  Per wave and
+  // block that is 16 MFMAs, 16 LDS reads and the 16 accumulators of a score tile less, for one more barrier.
+  constexpr bool SHP = D == 256 && !STATE_ONLY;
+  constexpr int PROW = 40;
+  __shared__ __attribute__((aligned(16))) E sP[SHP ? 32 * PROW : 8];
+  __shared__ f32x4 sDg[(STATE_ONLY || SHP) ? 1 : 4][64];               // decay mask, [element group][lane]
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w % NT;
@@ -116,11 +126,34 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   E* const gw = STATE_ONLY ? nullptr : reinterpret_cast<E*>(which ? p.w[1] : p.w[0]) + base;
   // head_dim 256: LaneAddr's precomputed offsets (one XOR per read); its read_row takes a row tile, always 0 here
   struct Pow2Addr : LaneAddr<D> {
-    __device__ __forceinline__ Pow2Addr(int l_) : LaneAddr<D>(l_) {}
+    int tp0, tp1;   // as LaneAddr's tr0, tr1 with the bits of the piece index exchanged (read_cols_pi)
+    __device__ __forceinline__ Pow2Addr(int l_) : LaneAddr<D>(l_) {
+      const int h = l_ >> 5, s16 = l_ & 15, g2 = (l_ >> 4) & 1;
+      const int trcp = 2 * g2 + (s16 & 1), trhp = 4 * ((s16 & 3) >> 1);
+      const int r0 = 4 * h + (s16 >> 2), r1 = r0 + 8;
+      tp0 = r0 * D + 8 * (trcp ^ swz<D>(r0)) + trhp;
+      tp1 = r1 * D + 8 * (trcp ^ swz<D>(r1)) + trhp;
+    }
+    __device__ __forceinline__ ex8<E> read_cols_pi(const E* tile, int c0, int t) const {
+      union { struct { s16x4 lo, hi; } s; ex8<E> v; } u;
+      u.s.lo = lds_read_tr(tile + c0 * D + (tp0 ^ (32 * t)));
+      u.s.hi = lds_read_tr(tile + c0 * D + (tp1 ^ (32 * t)));
+      return u.v;
+    }
     __device__ __forceinline__ ex8<E> read_row(const E* tile, int ks) const { return LaneAddr<D>::read_row(tile, 0, ks); }
   };
   const std::conditional_t<(D & (D - 1)) == 0, Pow2Addr, PlainAddr<D>> la(l);
 
+  // Every transposing read takes the columns of its tile in the order pi (read_cols_pi: bits 2 and 3 of the index
+  // exchanged).  Element v of state tile t in a lane is therefore value feature dv = 32 dvt + pi(l32) and key feature
+  // dk = 32 t + pi(m), m = 8 (v / 4) + 4 hh + v % 4 the accumulator row: the eight elements a lane converts for a
+  // k-step are key features 16 ks + 8 hh .. + 7, the order of a row fragment of X, so the state operand needs no
+  // lane shuffle; and a lane's sixteen outputs are value features 32 dvt + 16 (v / 8) + 8 hh + v % 8: two 16-byte stores.
+  auto state_index_pi = [&](int t, int v, bool transposed) {
+    const int dk = 32 * t + 16 * (v >> 3) + 8 * hh + 4 * ((v >> 2) & 1) + (v & 3);
+    const int dv = 32 * dvt + ((l32 & 19) | ((l32 & 4) << 1) | ((l32 & 8) >> 1));
+    return transposed ? dv * D + dk : dk * D + dv;
+  };
   // state slice S[:, dv tile] in accumulator layout: chunk start state, the caller's start state, or zero
   // (the pre-pass forms LOCAL states, from zero)
   f32x16 kv[NT];
@@ -139,16 +172,25 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) kv[t][v] = gs ? gs[state_index<D>(dvt, l32, hh, t, v, tr)] : 0.f;
+      for (int v = 0; v < 16; v++) kv[t][v] = gs ? gs[state_index_pi(t, v, tr)] : 0.f;
   }
-  // decay mask of the score tile S^T[c][r] (lane: r = l32; element v: c = 8 (v / 4) + 4 hh + v % 4)
-  float dg[16];
+  // decay mask of the score tile S^T[c][r] (lane: r = l32; element v: c = 8 (v / 4) + 4 hh + v % 4): the same for
+  // every wave and every block.  It lives in LDS, four elements per lane and read, not in sixteen registers: the
+  // state slice leaves none to spare, and a register spilled inside the block loop is reloaded through the vector
+  // memory counter, behind the tile loads in flight.
+  if (!STATE_ONLY && !SHP && w == 0) {
 #pragma unroll
-  for (int v = 0; v < 16; v++) {
-    const int cc = 8 * (v >> 2) + 4 * hh + (v & 3);
-    const int e = REV ? cc - l32 : l32 - cc;
-    dg[v] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
-  }
+    for (int g = 0; g < 4; g++) {
+      f32x4 m;
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++) {
+        const int cc = 8 * g + 4 * hh + e4;
+        const int e = REV ? cc - l32 : l32 - cc;
+        m[e4] = (e >= 0) ? exp2f(l2 * (float)e) : 0.f;
+      }
+      sDg[g][l] = m;
+    }
+  }   // (the first block's barrier comes before the first read)
 
   // The decay of the carried state is applied lazily: the registers hold S_st with S = 2^pend S_st (pend <= 0, the
   // same for the whole wave), the carried part of a row and the update weights take the factor instead, and S_st is
@@ -159,6 +201,38 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   // are brought up to date after every block).
   constexpr float kPendLimit = std::is_same<E, __bf16>::value ? -40.f : 0.f;
   float pend = 0.f;
+
+  // The block body is laid out in slots, each closed by a scheduling barrier: a slot issues its MFMAs first, then the
+  // LDS reads and the conversions that the NEXT slot's MFMAs take, and pins the results at its end (see pin()).  Left
+  // to itself the compiler reads every operand right before the MFMA that takes it, and the wave then sits out an LDS
+  // round trip per k-step with one other wave on its SIMD to cover it.
+#define LA2_SLOT_END()                 \
+  do {                                 \
+    asm volatile("" ::: "memory");     \
+    __builtin_amdgcn_sched_barrier(0); \
+  } while (0)
+  constexpr int NU = 2 * NT;                           // MFMAs of a block's state update: (k-step q, key tile t), q-major
+  constexpr int NS3 = (NU + 1) / 2;                    // ... in slots of two
+  constexpr int PPS = NS3 >= 8 ? 2 : NS3 >= 4 ? 4 : 8; // elements of the masked score tile converted per update slot
+  auto state_operand = [&](int ks) __attribute__((always_inline)) {
+    ex8<E> f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) f[j] = (E)kv[ks >> 1][8 * (ks & 1) + j];
+    return f;
+  };
+  // Update weights of a full block: lambda^(31 - c) forward, lambda^(c + 1) reverse, for row c = cu + 4 hh with
+  // cu = 16 q + 8 (j / 4) + j % 4, as a wave-uniform factor (sixteen scalar registers) times a lane factor, both <= 1
+  // for any decay; the block loop then spends two multiplies per element on them instead of an exponential.
+  float wu[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    const int cu = 16 * (i >> 3) + 8 * ((i >> 2) & 1) + (i & 3);
+    wu[i] = scalar_reg(exp2f(l2 * (float)(REV ? cu : 27 - cu)));
+  }
+  const float wl = exp2f(l2 * (float)(REV ? 4 * hh + 1 : 4 - 4 * hh));
+  ex8<E> sa_first = {};
+  if (!STATE_ONLY) sa_first = state_operand(0);
+
   auto block_at = [&](int it) { return REV ? blk_hi - 1 - it : blk_lo + it; };
   loader.issue(sT[0], block_at(0));
   for (int it = 0; it < nblk; it++) {
@@ -169,35 +243,168 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     __syncthreads();                      // ... and everybody's; the other buffer is free (block it - 1 is done)
     if (it + 1 < nblk) loader.issue(sT[(it + 1) & 1], block_at(it + 1));
     const int nv = min(B, n - blk * B);   // valid rows of this block
-
-    ex8<E> zf[2];
+    if constexpr (SHP) {
+      if (w < 4) {
+        // quarter (a, b) of S^T[c][r] = sum_k Y[c][k] X[r][k]: c = 16 a + 4 (lane / 16) + v, r = 16 b + lane % 16.
+        // Every address and mask value is made here from the lane number, not kept in registers over the loop.
+        int lo = l;
+        asm volatile("" : "+v"(lo));
+        const int qa = w >> 1, qb = w & 1, l16 = lo & 15, pg = lo >> 4;
+        const int ra = 16 * qa + l16, rb = 16 * qb + l16;
+        const E* const pa = cur[yi] + ra * D + 8 * (pg ^ (swz<D>(ra) & 3));
+        const E* const pb = cur[xi] + rb * D + 8 * (pg ^ (swz<D>(rb) & 3));
+        const int sa4 = 32 * (swz<D>(ra) >> 2), sb4 = 32 * (swz<D>(rb) >> 2);   // chunk bits 2, 3 (elements)
+        f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int q = 0; q < 2; q++) zf[q] = la.read_cols(cur[zi], 16 * q, dvt);
+        for (int kk = 0; kk < D / 32; kk++) {
+          const ex8<E> fa = *reinterpret_cast<const ex8<E>*>(pa + ((32 * kk) ^ sa4));
+          const ex8<E> fb = *reinterpret_cast<const ex8<E>*>(pb + ((32 * kk) ^ sb4));
+          s4 = mfma16(fa, fb, s4);
+        }
+        ex4<E> pk;
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          const int e = REV ? (16 * qa + 4 * pg + v) - rb : rb - (16 * qa + 4 * pg + v);
+          pk[v] = (E)(e >= 0 ? s4[v] * fast_exp2(l2 * (float)e) : 0.f);
+        }
+        *reinterpret_cast<ex4<E>*>(sP + rb * PROW + 16 * qa + 8 * (pg & 1) + 4 * (pg >> 1)) = pk;
+      }
+    }
+    const E* const tX = cur[xi];
+    const E* const tY = cur[yi];
+    const E* const tZ = cur[zi];
 
-    if (!STATE_ONLY) {
-      // inter-block part W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] and scores S^T[c][r] = sum_k Y[c][k] X[r][k]
-      f32x16 acc = zero16(), sd = zero16();
+    // (wave-uniform) the decay this block adds to the pending one, and whether the registers are brought up to date
+    const float pend_new = uniform(pend + l2 * (float)nv);
+    const bool rescale = pend_new < kPendLimit;
+    const float pend_upd = rescale ? 0.f : pend_new;   // the registers' exponent once this block's update is in
+
+    ex8<E> zf[2], zd[2], yt[NU];
+    auto read_yt = [&](int idx) __attribute__((always_inline)) {
+      if (idx < NU) yt[idx] = la.read_cols_pi(tY, 16 * (idx / NT), idx % NT);
+    };
+    // update weights on the Z fragments (element j of fragment q is row c = 16 q + 8 (j / 4) + 4 hh + j % 4)
+    auto weigh_z = [&]() __attribute__((always_inline)) {
+      if (REV || nv == B) {
+        const float ls = wl * fast_exp2(-pend_upd);
+#pragma unroll
+        for (int q = 0; q < 2; q++)
+#pragma unroll
+          for (int j = 0; j < 8; j++) zd[q][j] = (E)(((float)zf[q][j] * ls) * wu[8 * q + j]);
+      } else {   // ragged last block of a forward scan: lambda^(nv - 1 - c), clamped for the rows past the end
+#pragma unroll
+        for (int q = 0; q < 2; q++)
+#pragma unroll
+          for (int j = 0; j < 8; j++) {
+            const int c = 16 * q + 8 * (j >> 2) + 4 * hh + (j & 3);
+            zd[q][j] = (E)((float)zf[q][j] * fast_exp2(l2 * (float)max(nv - 1 - c, 0) - pend_upd));
+          }
+      }
+      pin(zd[0]);
+      pin(zd[1]);
+    };
+    f32x16 acc = zero16(), sd = zero16();
+    if constexpr (!STATE_ONLY) {
+      // inter-block part W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] and scores S^T[c][r] = sum_k Y[c][k] X[r][k],
+      // one k-step of each per slot
+      ex8<E> xa[KS], ya[KS];
+      xa[0] = la.read_row(tX, 0);
+      if constexpr (!SHP) ya[0] = la.read_row(tY, 0);
+      ex8<E> sa = sa_first;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
-        const ex8<E> xa = la.read_row(cur[xi], ks), ya = la.read_row(cur[yi], ks);
-        ex8<E> f;
-#pragma unroll
-        for (int j = 0; j < 8; j++) f[j] = (E)kv[ks >> 1][8 * (ks & 1) + j];
-        acc = mfma(to_perm_order(f), xa, acc);
-        sd = mfma(ya, xa, sd);
+        if (ks + 1 < KS) {
+          xa[ks + 1] = la.read_row(tX, ks + 1);
+          if constexpr (!SHP) ya[ks + 1] = la.read_row(tY, ks + 1);
+        }
+        if (ks == KS - 3 || ks == KS - 2) zf[ks - (KS - 3)] = la.read_cols_pi(tZ, 16 * (ks - (KS - 3)), dvt);
+        if (ks == KS - 1) { read_yt(0); read_yt(1); }
+        __builtin_amdgcn_sched_barrier(0);   // the reads above are issued before the MFMAs below
+        acc = mfma(sa, xa[ks], acc);
+        if constexpr (!SHP) sd = mfma(ya[ks], xa[ks], sd);
+        if (ks + 1 < KS) {
+          sa = state_operand(ks + 1);
+          pin(sa);
+          pin(xa[ks + 1]);
+          if constexpr (!SHP) pin(ya[ks + 1]);
+        }
+        pin(acc);
+        if constexpr (!SHP) pin(sd);
+        LA2_SLOT_END();
       }
+      // the carried part takes the decay at this lane's position (and the pending decay of the registers)
       const float carried = fast_exp2(l2 * (float)(REV ? max(nv - 1 - l32, 0) : l32 + 1) + pend);
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[v] *= carried;
-      // intra-block part Z^T P^T
+      pin(acc);
+    } else {
 #pragma unroll
-      for (int q = 0; q < 2; q++) {
-        ex8<E> pd;
+      for (int q = 0; q < 2; q++) zf[q] = la.read_cols_pi(tZ, 16 * q, dvt);
+      read_yt(0);
+      read_yt(1);
+    }
+    weigh_z();
+    if (rescale) {
+      const float scale = uniform(fast_exp2(pend_new));
 #pragma unroll
-        for (int j = 0; j < 8; j++) pd[j] = (E)(sd[8 * q + j] * dg[8 * q + j]);
-        acc = mfma(zf[q], pd, acc);
+      for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) kv[t][v] *= scale;
+    }
+    pend = pend_upd;
+    LA2_SLOT_END();
+
+    // state slice <- (decayed) state + Y^T weighted(Z); side work: the masked, decayed score tile in 16 bits
+    ex8<E> pd[2];
+    f32x4 dgv[(PPS + 3) / 4];
+#pragma unroll
+    for (int s3 = 0; s3 < NS3; s3++) {
+      read_yt(2 * s3 + 2);
+      read_yt(2 * s3 + 3);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const int idx = 2 * s3 + u;
+        if (idx < NU) kv[idx % NT] = mfma(yt[idx], zd[idx / NT], kv[idx % NT]);
       }
-      // output: lane = position l32, elements 4 g .. 4 g + 3 are value features 32 dvt + 8 g + 4 hh .. + 3
+      if constexpr (!STATE_ONLY && !SHP) {
+        if (PPS * s3 < 16) {
+          if ((PPS * s3) % 4 == 0) {
+#pragma unroll
+            for (int g = 0; g < (PPS + 3) / 4; g++) dgv[g] = sDg[(PPS * s3) / 4 + g][l];
+          }
+#pragma unroll
+          for (int e = 0; e < PPS; e++) {
+            const int v = PPS * s3 + e;
+            pd[v >> 3][v & 7] = (E)(sd[v] * dgv[PPS >= 4 ? e >> 2 : 0][v & 3]);
+          }
+          pin(pd[(PPS * s3) >> 3]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        if (2 * s3 + u < NU) pin(kv[(2 * s3 + u) % NT]);
+        if (2 * s3 + 2 + u < NU) pin(yt[2 * s3 + 2 + u]);
+      }
+      LA2_SLOT_END();
+    }
+
+    if constexpr (!STATE_ONLY) {
+      // intra-block part Z^T P^T, and the first state operand of the next block
+      if constexpr (SHP) {
+        // The quarters were written at the top of the block; the next block's are written after its first barrier,
+        // which no wave passes before every wave has read these.
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 2; q++) pd[q] = *reinterpret_cast<const ex8<E>*>(sP + l32 * PROW + 16 * q + 8 * hh);
+      }
+#pragma unroll
+      for (int q = 0; q < 2; q++) acc = mfma(zf[q], pd[q], acc);
+      sa_first = state_operand(0);
+      pin(sa_first);
+      pin(acc);
+      LA2_SLOT_END();
+      // output: lane = position l32, elements 8 g .. 8 g + 7 are value features 32 dvt + 16 g + 8 hh .. + 7
       const int pos = blk * B + l32;
       if constexpr (NORM) {
         // The next publish comes after the barrier at the top of the next block, which no wave passes before
@@ -210,38 +417,19 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
         if (dvt == 0 && hh == 0 && pos < n) p.rstd[rstd_chain_offset(p, bi, hi) + pos] = r;
       }
       if (pos < n) {
-        E* orow = gw + (int64_t)pos * stride_n + 32 * dvt + 4 * hh;
+        // wave-uniform base + 32-bit byte offset (a chain spans < 4 GiB, checked on the host)
+        char* const orow = reinterpret_cast<char*>(gw) + ((uint32_t)pos * stride_n + (uint32_t)(32 * dvt + 8 * hh)) * 2u;
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          ex4<E> pk;
+        for (int g = 0; g < 2; g++) {
+          ex8<E> pk;
 #pragma unroll
-          for (int e = 0; e < 4; e++) pk[e] = (E)acc[4 * g + e];
-          *reinterpret_cast<ex4<E>*>(orow + 8 * g) = pk;
+          for (int e = 0; e < 8; e++) pk[e] = (E)acc[8 * g + e];
+          *reinterpret_cast<ex8<E>*>(orow + 32 * g) = pk;
         }
       }
     }
-    // state slice <- lambda^nv state + Y^T decay(Z): element j of a Z fragment is row 16 q + 8 (j / 4) + 4 hh + j % 4
-    pend = uniform(pend + l2 * (float)nv);
-    if (pend < kPendLimit) {   // (wave-uniform) bring the registers up to date
-      const float scale = uniform(fast_exp2(pend));
-#pragma unroll
-      for (int t = 0; t < NT; t++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) kv[t][v] *= scale;
-      pend = 0.f;
-    }
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      ex8<E> zd;
-#pragma unroll
-      for (int j = 0; j < 8; j++) {
-        const int c = 16 * q + 8 * (j >> 2) + 4 * hh + (j & 3);
-        zd[j] = (E)((float)zf[q][j] * fast_exp2(l2 * (float)(REV ? c + 1 : max(nv - 1 - c, 0)) - pend));
-      }
-#pragma unroll
-      for (int t = 0; t < NT; t++) kv[t] = mfma(la.read_cols(cur[yi], 16 * q, t), zd, kv[t]);
-    }
   }
+#undef LA2_SLOT_END
 
   // the state after the chunk: the pre-pass keeps every chunk's, a scan hands out the one after its last block
   float* gf = nullptr;
@@ -257,7 +445,7 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) gf[state_index<D>(dvt, l32, hh, t, v, trf)] = kv[t][v] * scale;
+      for (int v = 0; v < 16; v++) gf[state_index_pi(t, v, trf)] = kv[t][v] * scale;
   }
 }
 
