@@ -62,7 +62,13 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
   constexpr int NTL = TWIN ? 4 : STATE_ONLY ? 2 : 3;   // tiles of a block: [X,] Y, Z; twin: X0, X1, Y0 = Z1, Z0 = Y1
-  using Loader = TileLoader<D, NTL, B, (TWIN ? 2 : 1) * NT>;
+  constexpr bool SHP = D == 256 && !STATE_ONLY;   // shared score tile (see sP below)
+  // The tile loads of a block: every wave its share.  With the shared score tile, waves 4 .. 7 load (one
+  // instruction per slot of the inter-block product, so that eight waves do not queue 48 of them at the tile
+  // addresser right after the barrier) while waves 0 .. 3 compute the score tile.
+  constexpr int NLW = SHP ? 4 : (TWIN ? 2 : 1) * NT;
+  using Loader = TileLoader<D, NTL, B, NLW>;
+  constexpr int NDMA = NTL * Loader::DMA_PER_WAVE;
   __shared__ __attribute__((aligned(1024))) E sT[2][NTL][TILE];
   float* const sRed = NormExchange<NORM ? B * (D / 32) : 0>::get();   // [position][wave]
   // Head_dim 256: the masked, decayed score tile of a block is the same for the eight waves.  Waves 0 .. 3 compute a
@@ -70,7 +76,6 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   // the intra-block product's operand: row r (80 bytes apart: sixteen rows fall into sixteen different 16-byte bank
   // groups) holds, for k-step q and lane half hh, the eight columns c = 16 q + 8 (j / 4) + 4 hh + j % 4.  Per wave and
   // block that is 16 MFMAs, 16 LDS reads and the 16 accumulators of a score tile less, for one more barrier.
-  constexpr bool SHP = D == 256 && !STATE_ONLY;
   constexpr int PROW = 40;
   __shared__ __attribute__((aligned(16))) E sP[SHP ? 32 * PROW : 8];
   __shared__ f32x4 sDg[(STATE_ONLY || SHP) ? 1 : 4][64];               // decay mask, [element group][lane]
@@ -111,7 +116,8 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   const uint32_t stride_n = (uint32_t)p.stride_n;
   const float l2 = log2f(p.lambda[hi]);
 
-  Loader loader(w, l, n, stride_n);
+  const bool loads = !SHP || w >= 4;
+  Loader loader(SHP ? (w & 3) : w, l, n, stride_n);
   if (TWIN) {
     loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
     loader.g[1] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[1]) + base);
@@ -211,6 +217,8 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     asm volatile("" ::: "memory");     \
     __builtin_amdgcn_sched_barrier(0); \
   } while (0)
+  constexpr int AH1 = SHP ? 3 : 1;   // slots by which the LDS reads run ahead of their MFMAs: inter-block product,
+  constexpr int AH3 = D == 256 ? 2 : 1;   // state update (a slot of one MFMA is shorter than an LDS round trip)
   constexpr int NU = 2 * NT;                           // MFMAs of a block's state update: (k-step q, key tile t), q-major
   constexpr int NS3 = (NU + 1) / 2;                    // ... in slots of two
   constexpr int PPS = NS3 >= 8 ? 2 : NS3 >= 4 ? 4 : 8; // elements of the masked score tile converted per update slot
@@ -234,14 +242,25 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   if (!STATE_ONLY) sa_first = state_operand(0);
 
   auto block_at = [&](int it) { return REV ? blk_hi - 1 - it : blk_lo + it; };
-  loader.issue(sT[0], block_at(0));
+  if (loads) loader.issue(sT[0], block_at(0));
   for (int it = 0; it < nblk; it++) {
     const int blk = block_at(it);
     E (*const cur)[TILE] = sT[it & 1];
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the block's tiles has landed
-    loader.zero_tail(cur, blk);
+    // This wave's part of the block's tiles has landed.  Vector memory operations complete in the order of their
+    // issue, and the only ones younger than those loads are the two output stores per lane of the block before
+    // (always issued: every block has a valid first row; a Norm scan's r store comes before them): they may stay in
+    // flight, a store's acknowledgement takes as long as a load.
+    if (STATE_ONLY || it == 0) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0F72);                         // vmcnt(2)
+    if (loads) loader.zero_tail(cur, blk);
     __syncthreads();                      // ... and everybody's; the other buffer is free (block it - 1 is done)
-    if (it + 1 < nblk) loader.issue(sT[(it + 1) & 1], block_at(it + 1));
+    const bool load_next = loads && it + 1 < nblk;
+    uint32_t doff[Loader::DMA_PER_WAVE];
+    if constexpr (SHP) {
+      loader.offsets(block_at(it + 1), load_next, doff);
+    } else {
+      if (load_next) loader.issue(sT[(it + 1) & 1], block_at(it + 1));
+    }
     const int nv = min(B, n - blk * B);   // valid rows of this block
     if constexpr (SHP) {
       if (w < 4) {
@@ -255,12 +274,19 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
         const E* const pb = cur[xi] + rb * D + 8 * (pg ^ (swz<D>(rb) & 3));
         const int sa4 = 32 * (swz<D>(ra) >> 2), sb4 = 32 * (swz<D>(rb) >> 2);   // chunk bits 2, 3 (elements)
         f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
+        ex8<E> fa[D / 32], fb[D / 32];   // all sixteen reads in flight at once (the registers are free here)
 #pragma unroll
         for (int kk = 0; kk < D / 32; kk++) {
-          const ex8<E> fa = *reinterpret_cast<const ex8<E>*>(pa + ((32 * kk) ^ sa4));
-          const ex8<E> fb = *reinterpret_cast<const ex8<E>*>(pb + ((32 * kk) ^ sb4));
-          s4 = mfma16(fa, fb, s4);
+          fa[kk] = *reinterpret_cast<const ex8<E>*>(pa + ((32 * kk) ^ sa4));
+          fb[kk] = *reinterpret_cast<const ex8<E>*>(pb + ((32 * kk) ^ sb4));
         }
+#pragma unroll
+        for (int kk = 0; kk < D / 32; kk++) {
+          pin(fa[kk]);
+          pin(fb[kk]);
+        }
+#pragma unroll
+        for (int kk = 0; kk < D / 32; kk++) s4 = mfma16(fa[kk], fb[kk], s4);
         ex4<E> pk;
 #pragma unroll
         for (int v = 0; v < 4; v++) {
@@ -308,17 +334,23 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
       // inter-block part W^T[dv][r] = sum_dk State[dk][dv] X[r][dk] and scores S^T[c][r] = sum_k Y[c][k] X[r][k],
       // one k-step of each per slot
       ex8<E> xa[KS], ya[KS];
-      xa[0] = la.read_row(tX, 0);
-      if constexpr (!SHP) ya[0] = la.read_row(tY, 0);
+#pragma unroll
+      for (int a = 0; a < AH1; a++) {
+        xa[a] = la.read_row(tX, a);
+        if constexpr (!SHP) ya[a] = la.read_row(tY, a);
+      }
       ex8<E> sa = sa_first;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
-        if (ks + 1 < KS) {
-          xa[ks + 1] = la.read_row(tX, ks + 1);
-          if constexpr (!SHP) ya[ks + 1] = la.read_row(tY, ks + 1);
+        if (ks + AH1 < KS) {
+          xa[ks + AH1] = la.read_row(tX, ks + AH1);
+          if constexpr (!SHP) ya[ks + AH1] = la.read_row(tY, ks + AH1);
         }
         if (ks == KS - 3 || ks == KS - 2) zf[ks - (KS - 3)] = la.read_cols_pi(tZ, 16 * (ks - (KS - 3)), dvt);
-        if (ks == KS - 1) { read_yt(0); read_yt(1); }
+        if (ks == KS - 1) {
+#pragma unroll
+          for (int i = 0; i < 2 * AH3; i++) read_yt(i);
+        }
         __builtin_amdgcn_sched_barrier(0);   // the reads above are issued before the MFMAs below
         acc = mfma(sa, xa[ks], acc);
         if constexpr (!SHP) sd = mfma(ya[ks], xa[ks], sd);
@@ -327,6 +359,9 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
           pin(sa);
           pin(xa[ks + 1]);
           if constexpr (!SHP) pin(ya[ks + 1]);
+        }
+        if constexpr (SHP) {
+          if (ks < NDMA && load_next) loader.issue_one(sT[(it + 1) & 1], doff, ks);
         }
         pin(acc);
         if constexpr (!SHP) pin(sd);
@@ -340,8 +375,8 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     } else {
 #pragma unroll
       for (int q = 0; q < 2; q++) zf[q] = la.read_cols_pi(tZ, 16 * q, dvt);
-      read_yt(0);
-      read_yt(1);
+#pragma unroll
+      for (int i = 0; i < 2 * AH3; i++) read_yt(i);
     }
     weigh_z();
     if (rescale) {
@@ -359,8 +394,8 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     f32x4 dgv[(PPS + 3) / 4];
 #pragma unroll
     for (int s3 = 0; s3 < NS3; s3++) {
-      read_yt(2 * s3 + 2);
-      read_yt(2 * s3 + 3);
+      read_yt(2 * (s3 + AH3));
+      read_yt(2 * (s3 + AH3) + 1);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < 2; u++) {
