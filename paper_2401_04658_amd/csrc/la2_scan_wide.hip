@@ -77,7 +77,12 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   // groups) holds, for k-step q and lane half hh, the eight columns c = 16 q + 8 (j / 4) + 4 hh + j % 4.  Per wave and
   // block that is 16 MFMAs, 16 LDS reads and the 16 accumulators of a score tile less, for one more barrier.
   constexpr int PROW = 40;
-  __shared__ __attribute__((aligned(16))) E sP[SHP ? 32 * PROW : 8];
+  // Without the Norm epilogue the block's last two steps (intra-block product, output store) wait until the next
+  // block's first barrier has been passed, which orders them after the score tile's writes as well: one barrier
+  // per block again, two score-tile buffers by block parity, and the output stores of a block overlap the next
+  // block's first LDS reads.
+  constexpr bool DEFER = SHP && !NORM;
+  __shared__ __attribute__((aligned(16))) E sP[DEFER ? 2 : 1][SHP ? 32 * PROW : 8];
   __shared__ f32x4 sDg[(STATE_ONLY || SHP) ? 1 : 4][64];               // decay mask, [element group][lane]
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
@@ -241,6 +246,32 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   ex8<E> sa_first = {};
   if (!STATE_ONLY) sa_first = state_operand(0);
 
+  // output: lane = position l32, elements 8 g .. 8 g + 7 are value features 32 dvt + 16 g + 8 hh .. + 7
+  auto store_block = [&](const f32x16& a, int pos) __attribute__((always_inline)) {
+    if (pos < n) {
+      // wave-uniform base + 32-bit byte offset (a chain spans < 4 GiB, checked on the host)
+      char* const orow = reinterpret_cast<char*>(gw) + ((uint32_t)pos * stride_n + (uint32_t)(32 * dvt + 8 * hh)) * 2u;
+#pragma unroll
+      for (int g = 0; g < 2; g++) {
+        ex8<E> pk;
+#pragma unroll
+        for (int e = 0; e < 8; e++) pk[e] = (E)a[8 * g + e];
+        *reinterpret_cast<ex8<E>*>(orow + 32 * g) = pk;
+      }
+    }
+  };
+  // deferred tail of a block: intra-block part Z^T P^T from the shared score tile, then the output
+  f32x16 acc_prev = zero16();
+  ex8<E> zf_prev[2] = {};
+  int blk_prev = 0;
+  auto finish_block = [&](f32x16 a, const ex8<E> (&zfv)[2], int blkv, const E* tile) __attribute__((always_inline)) {
+    ex8<E> pv[2];
+#pragma unroll
+    for (int q = 0; q < 2; q++) pv[q] = *reinterpret_cast<const ex8<E>*>(tile + l32 * PROW + 16 * q + 8 * hh);
+#pragma unroll
+    for (int q = 0; q < 2; q++) a = mfma(zfv[q], pv[q], a);
+    store_block(a, blkv * B + l32);
+  };
   auto block_at = [&](int it) { return REV ? blk_hi - 1 - it : blk_lo + it; };
   if (loads) loader.issue(sT[0], block_at(0));
   for (int it = 0; it < nblk; it++) {
@@ -250,10 +281,14 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
     // issue, and the only ones younger than those loads are the two output stores per lane of the block before
     // (always issued: every block has a valid first row; a Norm scan's r store comes before them): they may stay in
     // flight, a store's acknowledgement takes as long as a load.
-    if (STATE_ONLY || it == 0) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    else __builtin_amdgcn_s_waitcnt(0x0F72);                         // vmcnt(2)
+    // (With the deferred tail the stores are issued before the block's loads and have had a block's time.)
+    if (STATE_ONLY || DEFER || it == 0) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0F72);                                  // vmcnt(2)
     if (loads) loader.zero_tail(cur, blk);
     __syncthreads();                      // ... and everybody's; the other buffer is free (block it - 1 is done)
+    if constexpr (DEFER) {
+      if (it > 0) finish_block(acc_prev, zf_prev, blk_prev, sP[(it - 1) & 1]);
+    }
     const bool load_next = loads && it + 1 < nblk;
     uint32_t doff[Loader::DMA_PER_WAVE];
     if constexpr (SHP) {
@@ -293,7 +328,7 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
           const int e = REV ? (16 * qa + 4 * pg + v) - rb : rb - (16 * qa + 4 * pg + v);
           pk[v] = (E)(e >= 0 ? s4[v] * fast_exp2(l2 * (float)e) : 0.f);
         }
-        *reinterpret_cast<ex4<E>*>(sP + rb * PROW + 16 * qa + 8 * (pg & 1) + 4 * (pg >> 1)) = pk;
+        *reinterpret_cast<ex4<E>*>(sP[DEFER ? it & 1 : 0] + rb * PROW + 16 * qa + 8 * (pg & 1) + 4 * (pg >> 1)) = pk;
       }
     }
     const E* const tX = cur[xi];
@@ -424,14 +459,21 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
       LA2_SLOT_END();
     }
 
-    if constexpr (!STATE_ONLY) {
+    if constexpr (DEFER) {
+      sa_first = state_operand(0);   // the first state operand of the next block
+      pin(sa_first);
+      acc_prev = acc;
+      zf_prev[0] = zf[0];
+      zf_prev[1] = zf[1];
+      blk_prev = blk;
+    } else if constexpr (!STATE_ONLY) {
       // intra-block part Z^T P^T, and the first state operand of the next block
       if constexpr (SHP) {
         // The quarters were written at the top of the block; the next block's are written after its first barrier,
         // which no wave passes before every wave has read these.
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < 2; q++) pd[q] = *reinterpret_cast<const ex8<E>*>(sP + l32 * PROW + 16 * q + 8 * hh);
+        for (int q = 0; q < 2; q++) pd[q] = *reinterpret_cast<const ex8<E>*>(sP[0] + l32 * PROW + 16 * q + 8 * hh);
       }
 #pragma unroll
       for (int q = 0; q < 2; q++) acc = mfma(zf[q], pd[q], acc);
@@ -451,18 +493,12 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
         for (int v = 0; v < 16; v++) acc[v] *= r;
         if (dvt == 0 && hh == 0 && pos < n) p.rstd[rstd_chain_offset(p, bi, hi) + pos] = r;
       }
-      if (pos < n) {
-        // wave-uniform base + 32-bit byte offset (a chain spans < 4 GiB, checked on the host)
-        char* const orow = reinterpret_cast<char*>(gw) + ((uint32_t)pos * stride_n + (uint32_t)(32 * dvt + 8 * hh)) * 2u;
-#pragma unroll
-        for (int g = 0; g < 2; g++) {
-          ex8<E> pk;
-#pragma unroll
-          for (int e = 0; e < 8; e++) pk[e] = (E)acc[8 * g + e];
-          *reinterpret_cast<ex8<E>*>(orow + 32 * g) = pk;
-        }
-      }
+      store_block(acc, pos);
     }
+  }
+  if constexpr (DEFER) {
+    __syncthreads();
+    finish_block(acc_prev, zf_prev, blk_prev, sP[(nblk - 1) & 1]);
   }
 #undef LA2_SLOT_END
 
