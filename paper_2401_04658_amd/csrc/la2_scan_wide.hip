@@ -309,19 +309,21 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
         const E* const pb = cur[xi] + rb * D + 8 * (pg ^ (swz<D>(rb) & 3));
         const int sa4 = 32 * (swz<D>(ra) >> 2), sb4 = 32 * (swz<D>(rb) >> 2);   // chunk bits 2, 3 (elements)
         f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
-        ex8<E> fa[D / 32], fb[D / 32];   // all sixteen reads in flight at once (the registers are free here)
+        if (REV ? w != 1 : w != 2) {   // (the quarter with every c > r, or every c < r in a reverse scan, is all zero)
+          ex8<E> fa[D / 32], fb[D / 32];   // all sixteen reads in flight at once (the registers are free here)
 #pragma unroll
-        for (int kk = 0; kk < D / 32; kk++) {
-          fa[kk] = *reinterpret_cast<const ex8<E>*>(pa + ((32 * kk) ^ sa4));
-          fb[kk] = *reinterpret_cast<const ex8<E>*>(pb + ((32 * kk) ^ sb4));
+          for (int kk = 0; kk < D / 32; kk++) {
+            fa[kk] = *reinterpret_cast<const ex8<E>*>(pa + ((32 * kk) ^ sa4));
+            fb[kk] = *reinterpret_cast<const ex8<E>*>(pb + ((32 * kk) ^ sb4));
+          }
+#pragma unroll
+          for (int kk = 0; kk < D / 32; kk++) {
+            pin(fa[kk]);
+            pin(fb[kk]);
+          }
+#pragma unroll
+          for (int kk = 0; kk < D / 32; kk++) s4 = mfma16(fa[kk], fb[kk], s4);
         }
-#pragma unroll
-        for (int kk = 0; kk < D / 32; kk++) {
-          pin(fa[kk]);
-          pin(fb[kk]);
-        }
-#pragma unroll
-        for (int kk = 0; kk < D / 32; kk++) s4 = mfma16(fa[kk], fb[kk], s4);
         ex4<E> pk;
 #pragma unroll
         for (int v = 0; v < 4; v++) {
