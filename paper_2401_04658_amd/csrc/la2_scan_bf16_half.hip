@@ -134,6 +134,15 @@ void scan_bf16_half_kernel(ScanParams p) {
   if (blk_lo >= blk_hi) return;
   const int nblk = blk_hi - blk_lo;
 
+  // Start state: the chunk's start state or the caller's, or zero; with self_prefix (ScanParams) it is formed here.
+  // Terms in scan order: the caller's start state, then the local states of the chunks passed before this one.
+  // A term stored transposed goes through LDS with workgroup barriers, so the count is the same for every wave.
+  const int nch = (nblocks + cb - 1) / cb;   // chunks this chain really has
+  const bool any_tr = (p.state_transposed | p.init_transposed) != 0;
+  const bool init_any = p.init[0] != nullptr || p.init[1] != nullptr;
+  const bool sp = p.self_prefix != 0 && p.states != nullptr && slot >= 0;
+  const int nterms = sp ? (init_any ? 1 : 0) + (REV ? nch - 1 - chunk : chunk) : 1;
+
   Loader loader(w, l, n, stride_n);
   if (ACC) {
     loader.g[0] = reinterpret_cast<const char*>(reinterpret_cast<const E*>(p.x[0]) + base);
@@ -163,9 +172,9 @@ void scan_bf16_half_kernel(ScanParams p) {
       constexpr int ACC_WAIT = (ACC_YOUNGER & 15) | ((ACC_YOUNGER >> 4) << 14) | 0x0F70;
       // the scan waves may first stage transposed start states in the tile buffers (below): join their barriers
       // before the first tile load
-      if ((p.state_transposed | p.init_transposed) != 0) {
+      if (any_tr) {
 #pragma unroll 1
-        for (int gsel = 0; gsel < NW / SW; gsel++) __syncthreads();
+        for (int k = 0; k < nterms * (NW / SW); k++) __syncthreads();
       }
       const UpdateDecay<true, B> adecay(l2, hh);
       f32x16 acc[NT];
@@ -229,52 +238,81 @@ void scan_bf16_half_kernel(ScanParams p) {
   }
 
   f32x16 kv[NT];
-  const float* gs = nullptr;   // start state: chunk start state, the caller's start state, or zero
-  bool tr = false;
-  if (p.states != nullptr && slot >= 0) {
-    gs = p.states + slot * (D * D);
-    tr = (p.state_transposed >> which) & 1;
-  } else if ((which ? p.init[1] : p.init[0]) != nullptr) {
-    gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
-    tr = (p.init_transposed >> which) & 1;
-  }
-  if (gs != nullptr && !tr) {
-#pragma unroll
-    for (int t = 0; t < NT; t++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) kv[t][v] = gs[state_index<D>(dvt, l32, hh, t, v, false)];
-  } else if (gs == nullptr) {
-#pragma unroll
-    for (int t = 0; t < NT; t++) kv[t] = zero16();
-  }
-  // A state stored transposed: this wave's slice is then the 32 ROWS 32 dvt .. + 31 of the stored matrix, 32 D
-  // consecutive floats.  Read element by element each lane would touch a cache line of its own (measured
-  // +20 us per launch at 256 workgroups); instead the wave copies its rows with 16-byte loads into the tile
-  // buffers, which nothing has used yet, and each lane picks its elements out of LDS (row stride D + 1 floats:
-  // no bank conflicts).  One wave group at a time, a workgroup barrier after each: the first tile loads, from
-  // any wave, overwrite that LDS.  Whether the launch has transposed states at all is uniform over the grid.
-  if ((p.state_transposed | p.init_transposed) != 0) {
+  bool have = false;   // a term is in (the next one is added to the decayed sum)
+  {
+    const float lam_full = exp2f(l2 * (float)p.chunk_tokens);
+    const float lam_last = exp2f(l2 * (float)(n - (nch - 1) * p.chunk_tokens));
     float* const lds = reinterpret_cast<float*>(&sT[0][0][0]) + dvt * (32 * (D + 1));
     static_assert(sizeof(sT) >= (size_t)SW * 32 * (D + 1) * sizeof(float), "room for one wave group's slices");
 #pragma unroll 1
-    for (int gsel = 0; gsel < NW / SW; gsel++) {
-      if (gs != nullptr && tr && group == gsel) {
-        const float* rows = gs + (int64_t)(32 * dvt) * D;
-#pragma unroll
-        for (int i = 0; i < 32 * D / 256; i++) {
-          const int at = 4 * (64 * i + l);
-          const f32x4 x = *reinterpret_cast<const f32x4*>(rows + at);
-          float* dst = lds + (at / D) * (D + 1) + at % D;
-          dst[0] = x[0]; dst[1] = x[1]; dst[2] = x[2]; dst[3] = x[3];
+    for (int k = 0; k < nterms; k++) {
+      const float* gs = nullptr;
+      bool tr = false;
+      float decay = 0.f;
+      if (!sp) {
+        if (p.states != nullptr && slot >= 0) {
+          gs = p.states + slot * (D * D);
+          tr = (p.state_transposed >> which) & 1;
+        } else if ((which ? p.init[1] : p.init[0]) != nullptr) {
+          gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
+          tr = (p.init_transposed >> which) & 1;
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's own writes, before its own reads
+      } else if (init_any && k == 0) {
+        if ((which ? p.init[1] : p.init[0]) != nullptr) {
+          gs = (which ? p.init[1] : p.init[0]) + (int64_t)chain * (D * D);
+          tr = (p.init_transposed >> which) & 1;
+        }
+      } else {
+        const int i = k - (init_any ? 1 : 0);
+        const int j = REV ? nch - 1 - i : i;   // the chunk whose local state is added
+        gs = p.states + (slot + (int64_t)(j - chunk) * slot_stride) * (D * D);
+        tr = (p.state_transposed >> which) & 1;
+        decay = j == nch - 1 ? lam_last : lam_full;
+      }
+      if (gs != nullptr && !tr) {
 #pragma unroll
         for (int t = 0; t < NT; t++)
 #pragma unroll
-          for (int v = 0; v < 16; v++)
-            kv[t][v] = lds[l32 * (D + 1) + 32 * t + 8 * (v >> 2) + 4 * hh + (v & 3)];
+          for (int v = 0; v < 16; v++) {
+            const float x = gs[state_index<D>(dvt, l32, hh, t, v, false)];
+            kv[t][v] = have ? fmaf(decay, kv[t][v], x) : x;
+          }
       }
-      __syncthreads();
+      // A state stored transposed: this wave's slice is then the 32 ROWS 32 dvt .. + 31 of the stored matrix, 32 D
+      // consecutive floats.  Read element by element each lane would touch a cache line of its own (measured
+      // +20 us per launch at 256 workgroups); instead the wave copies its rows with 16-byte loads into the tile
+      // buffers, which nothing has used yet, and each lane picks its elements out of LDS (row stride D + 1 floats:
+      // no bank conflicts).  One wave group at a time, a workgroup barrier after each: the first tile loads, from
+      // any wave, overwrite that LDS.  Whether the launch has transposed states at all is uniform over the grid.
+      if (any_tr) {
+#pragma unroll 1
+        for (int gsel = 0; gsel < NW / SW; gsel++) {
+          if (gs != nullptr && tr && group == gsel) {
+            const float* rows = gs + (int64_t)(32 * dvt) * D;
+#pragma unroll
+            for (int i = 0; i < 32 * D / 256; i++) {
+              const int at = 4 * (64 * i + l);
+              const f32x4 x = *reinterpret_cast<const f32x4*>(rows + at);
+              float* dst = lds + (at / D) * (D + 1) + at % D;
+              dst[0] = x[0]; dst[1] = x[1]; dst[2] = x[2]; dst[3] = x[3];
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's own writes, before its own reads
+#pragma unroll
+            for (int t = 0; t < NT; t++)
+#pragma unroll
+              for (int v = 0; v < 16; v++) {
+                const float x = lds[l32 * (D + 1) + 32 * t + 8 * (v >> 2) + 4 * hh + (v & 3)];
+                kv[t][v] = have ? fmaf(decay, kv[t][v], x) : x;
+              }
+          }
+          __syncthreads();
+        }
+      }
+      if (gs != nullptr) have = true;
+    }
+    if (!have) {
+#pragma unroll
+      for (int t = 0; t < NT; t++) kv[t] = zero16();
     }
   }
 
@@ -293,7 +331,7 @@ void scan_bf16_half_kernel(ScanParams p) {
   // final state is wanted; reverse: a start state comes in behind it), else 0
   int rag_rem = 0;
   if (RS && blk_hi >= nblocks && n % B != 0) {
-    if (REV ? gs != nullptr : (which ? p.fin[1] : p.fin[0]) != nullptr) rag_rem = n % B;
+    if (REV ? have : (which ? p.fin[1] : p.fin[0]) != nullptr) rag_rem = n % B;
   }
   rag_rem = __builtin_amdgcn_readfirstlane(rag_rem);
   // The per-block code has no branch for that block.  The factors that differ there are variables which change
