@@ -1,6 +1,8 @@
 """Builds libla2.so (the C-ABI library) and libla2_bench.so (the benchmark's measurement kernels) for gfx950 with
 hipcc, in-tree."""
+import json
 import os
+import re
 import subprocess
 import sys
 
@@ -16,8 +18,38 @@ FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
     "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA accumulators in VGPRs: VALU touches them without AGPR copies
+    "-Rpass-analysis=kernel-resource-usage",   # registers, scratch, LDS of every kernel -> _build/kernel_resources.json
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
 ]
+
+
+RESOURCES = os.path.join(_HERE, "_build", "kernel_resources.json")
+_REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|TotalSGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|"
+                     r"VGPRs Spill|SGPRs Spill|LDS Size \[bytes/block\]|Dynamic Stack):\s+(\S+)")
+
+
+def _take_resource_remarks(out, resources):
+    """Moves the compiler's per-kernel resource remarks of the device pass from `out` into `resources`
+    ({mangled kernel name: {"VGPRs": .., "ScratchSize": .., "Occupancy": .., "LDS": .., ...}}); returns the rest."""
+    rest, name, skip = [], None, 0
+    for line in out.splitlines():
+        if "-Rpass-analysis=kernel-resource-usage" in line:
+            m = _REMARK.search(line)
+            if m:
+                key, val = m.group(1).split(" [")[0].replace(" Size", "").replace(" ", "_"), m.group(2)
+                if key == "Function_Name":
+                    name = val
+                    resources[name] = {}
+                elif name is not None:
+                    resources[name][key] = int(val) if val.isdigit() else val
+            skip = 2   # the two source-excerpt lines that follow a remark's first line
+            continue
+        if skip and (line.lstrip().startswith("|") or re.match(r"\s*\d+ \|", line)):
+            skip -= 1
+            continue
+        skip = 0
+        rest.append(line)
+    return "\n".join(rest)
 
 
 def build(verbose=False):
@@ -33,13 +65,17 @@ def build(verbose=False):
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    resources = {}
     for src, pr in procs:
         out, _ = pr.communicate()
+        out = _take_resource_remarks(out, resources)
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if pr.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, out))
         if verbose and out.strip():
             print(out)
+    with open(os.path.join(bdir, "kernel_resources.json"), "w") as f:
+        json.dump(resources, f, indent=1, sort_keys=True)
     for lib, part in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
         tmp = lib + ".tmp%d" % os.getpid()
         subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + part)
