@@ -2,10 +2,17 @@
 // (Algorithm 1; both loops of Algorithm 2) and, as a template flag, the chunk-state pre-pass for them.
 //
 // Same arithmetic, MFMA layouts and direct HBM -> LDS tile loads as the kernels for head_dim 64 / 128
-// (la2_bf16_common.h), in the plainest arrangement: blocks of 32 positions, D / 32 waves (wave w owns value
-// features 32 w .. 32 w + 31 and that slice of the fp32 state in accumulators), two tile buffers (the next
-// block's tiles stream in while this block is computed), one barrier per block, no hand scheduling.
-// Head_dim 256 makes a workgroup of 8 waves with 128 state registers per lane; head_dim 96 one of 3 waves.
+// (la2_bf16_common.h): blocks of 32 positions, D / 32 waves (wave w owns value features 32 w .. 32 w + 31 and that
+// slice of the fp32 state in accumulators), two tile buffers (the next block's tiles stream in while this block
+// is computed), one barrier per block (two with the Norm epilogue, three at head_dim 256).  Head_dim 256 makes a
+// workgroup of 8 waves with 128 state registers per lane, which leaves no register to spare; head_dim 96 one of
+// 3 waves (6 in the twin form).  What differs from those kernels:
+//   - the block body is a sequence of slots closed by scheduling barriers (LDS reads issued ahead of their MFMAs);
+//   - transposing reads take their columns in a permuted order (read_cols_pi), so that the state operand needs no
+//     lane shuffle and a lane stores 16 bytes at a time;
+//   - lane-dependent loop invariants live in LDS or scalar registers, not in vector registers;
+//   - head_dim 256: one masked score tile per workgroup instead of one per wave (waves 0 .. 3 compute a quarter
+//     each while waves 4 .. 7 issue the tile loads), and a block's last two steps run behind the next block's barrier.
 //
 // A ragged last block (nv < 32 valid rows) is handled exactly in both directions, so the state entry points
 // need no token-by-token tail for these head dimensions:
