@@ -85,8 +85,9 @@ void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen
 
 /*
  * Bytes of device workspace la2_fwd / la2_bwd need for this problem (op is a la2_op).  The
- * workspace holds the d x d start states of the sequence chunks that are processed in parallel
- * when batch*heads alone cannot fill the GPU; it may be 0.  Returns 0 for an invalid descriptor.
+ * workspace holds the d x d states of the sequence chunks that are processed in parallel when
+ * batch*heads alone cannot fill the GPU (their start states; for a plan of at most four chunks their local
+ * states, from which every workgroup forms its own start state); it may be 0.  Returns 0 for an invalid descriptor.
  * The value depends on the device's compute-unit count and on la2_set_chunk_tokens().
  */
 size_t la2_workspace_bytes(const la2_desc* desc, int32_t op);
@@ -308,7 +309,7 @@ la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, 
 
 /*
  * la2_bwd_state for callers that kept the forward pass's workspace (a training step).  When the sequence is
- * processed in chunks that buffer holds the chunk start states of the (K, V) scan, which are (transposed)
+ * processed in chunks that buffer holds the chunk states of the (K, V) scan, which are (transposed)
  * those of Algorithm 2's first loop, so the backward pass skips recomputing them (one pass over K and V less).
  *   fwd_workspace        in  the workspace buffer that la2_fwd / la2_fwd_state (or their _norm forms) used for
  *                            the SAME desc, k, v, lambda and kv_init, contents untouched since, distinct from
