@@ -254,8 +254,8 @@ struct ScanArgs {
 // local states; every scan workgroup forms its own start state from them (ScanParams::self_prefix).  At that size
 // the launches are a few microseconds each and run one after the other, so a dependent launch less is worth more
 // than the few extra state reads (batch 4, H 16, n 2048, d 64, four chunks: each fold takes a 4.3 us launch away and
-// adds 1.7-2 us to the prologue of the scan that follows; forward + backward 0.0871 -> 0.0845 ms).
-constexpr int kSelfPrefixMaxChunks = 4;
+// adds 1-2 us to the prologue of the scan that follows; forward + backward 0.0871 -> 0.081-0.084 ms).
+constexpr int kSelfPrefixMaxChunks = la2::kMaxPrefixTerms;   // a start state and the local states of chunks - 1 chunks
 bool self_prefix(const la2_desc* d, const Plan& pl, const int32_t* cu) {
   return cu == nullptr && pl.nchunks > 1 && pl.nchunks <= kSelfPrefixMaxChunks && is16(d->dtype) &&
          !wide(d->head_dim) && pl.chunk_tokens % 32 == 0 && g_scan_variant.load(std::memory_order_relaxed) != 1;

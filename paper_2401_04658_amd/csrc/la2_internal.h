@@ -89,6 +89,8 @@ struct ScanParams {
   // For a few chunks on a small problem that is cheaper than one more dependent launch between two short kernels.
   int32_t self_prefix;
 };
+// self_prefix: most terms a start state is formed from (the caller's start state and the local states of three chunks)
+constexpr int kMaxPrefixTerms = 4;
 
 // Which (batch row or sequence, head, chunk) a workgroup of a scan-type launch serves, and where that chunk's
 // state lives ([D][D] floats at states + slot * D * D; slot < 0: the chain has a single chunk and no state slot).

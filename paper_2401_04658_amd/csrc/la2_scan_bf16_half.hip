@@ -244,11 +244,11 @@ void scan_bf16_half_kernel(ScanParams p) {
     const float lam_last = exp2f(l2 * (float)(n - (nch - 1) * p.chunk_tokens));
     float* const lds = reinterpret_cast<float*>(&sT[0][0][0]) + dvt * (32 * (D + 1));
     static_assert(sizeof(sT) >= (size_t)SW * 32 * (D + 1) * sizeof(float), "room for one wave group's slices");
-#pragma unroll 1
-    for (int k = 0; k < nterms; k++) {
-      const float* gs = nullptr;
-      bool tr = false;
-      float decay = 0.f;
+    // Term k: where it lives, whether it is stored transposed, the decay the sum so far takes before it is added.
+    auto term = [&](int k, const float*& gs, bool& tr, float& decay) __attribute__((always_inline)) {
+      gs = nullptr;
+      tr = false;
+      decay = 0.f;
       if (!sp) {
         if (p.states != nullptr && slot >= 0) {
           gs = p.states + slot * (D * D);
@@ -269,46 +269,82 @@ void scan_bf16_half_kernel(ScanParams p) {
         tr = (p.state_transposed >> which) & 1;
         decay = j == nch - 1 ? lam_last : lam_full;
       }
-      if (gs != nullptr && !tr) {
+    };
+    // The global loads of the next terms are issued before term k is consumed (a term's loads take about a microsecond
+    // and the launches that form their start states here are a few microseconds long).  A wave's slice of a term is
+    // NT * 16 floats either way: its elements one by one, or (stored transposed) its 32 rows in 16-byte pieces.
+    constexpr int NX = NT * 16;
+    static_assert(32 * D / 256 * 4 == NX, "a wave's rows in 16-byte pieces per lane");
+    constexpr int FA = D == 64 ? kMaxPrefixTerms - 1 : 1;   // terms fetched ahead (head_dim 128: 64 registers a term)
+    float xb[FA + 1][NX];
+    auto fetch = [&](int k, float (&x)[NX]) __attribute__((always_inline)) {
+      const float* gs;
+      bool tr;
+      float decay;
+      term(k, gs, tr, decay);
+      if (gs == nullptr) return;
+      if (!tr) {
 #pragma unroll
         for (int t = 0; t < NT; t++)
 #pragma unroll
-          for (int v = 0; v < 16; v++) {
-            const float x = gs[state_index<D>(dvt, l32, hh, t, v, false)];
-            kv[t][v] = have ? fmaf(decay, kv[t][v], x) : x;
-          }
-      }
-      // A state stored transposed: this wave's slice is then the 32 ROWS 32 dvt .. + 31 of the stored matrix, 32 D
-      // consecutive floats.  Read element by element each lane would touch a cache line of its own (measured
-      // +20 us per launch at 256 workgroups); instead the wave copies its rows with 16-byte loads into the tile
-      // buffers, which nothing has used yet, and each lane picks its elements out of LDS (row stride D + 1 floats:
-      // no bank conflicts).  One wave group at a time, a workgroup barrier after each: the first tile loads, from
-      // any wave, overwrite that LDS.  Whether the launch has transposed states at all is uniform over the grid.
-      if (any_tr) {
-#pragma unroll 1
-        for (int gsel = 0; gsel < NW / SW; gsel++) {
-          if (gs != nullptr && tr && group == gsel) {
-            const float* rows = gs + (int64_t)(32 * dvt) * D;
+          for (int v = 0; v < 16; v++) x[16 * t + v] = gs[state_index<D>(dvt, l32, hh, t, v, false)];
+      } else {
+        const float* rows = gs + (int64_t)(32 * dvt) * D;
 #pragma unroll
-            for (int i = 0; i < 32 * D / 256; i++) {
-              const int at = 4 * (64 * i + l);
-              const f32x4 x = *reinterpret_cast<const f32x4*>(rows + at);
-              float* dst = lds + (at / D) * (D + 1) + at % D;
-              dst[0] = x[0]; dst[1] = x[1]; dst[2] = x[2]; dst[3] = x[3];
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's own writes, before its own reads
-#pragma unroll
-            for (int t = 0; t < NT; t++)
-#pragma unroll
-              for (int v = 0; v < 16; v++) {
-                const float x = lds[l32 * (D + 1) + 32 * t + 8 * (v >> 2) + 4 * hh + (v & 3)];
-                kv[t][v] = have ? fmaf(decay, kv[t][v], x) : x;
-              }
-          }
-          __syncthreads();
+        for (int i = 0; i < 32 * D / 256; i++) {
+          const f32x4 r = *reinterpret_cast<const f32x4*>(rows + 4 * (64 * i + l));
+          x[4 * i] = r[0]; x[4 * i + 1] = r[1]; x[4 * i + 2] = r[2]; x[4 * i + 3] = r[3];
         }
       }
-      if (gs != nullptr) have = true;
+    };
+#pragma unroll
+    for (int a = 0; a < FA; a++)
+      if (a < nterms) fetch(a, xb[a]);
+#pragma unroll
+    for (int k = 0; k < kMaxPrefixTerms; k++) {
+      if (k < nterms) {   // (the same for every wave of the workgroup)
+        if (k + FA < nterms) fetch(k + FA, xb[(k + FA) % (FA + 1)]);
+        const float(&x)[NX] = xb[k % (FA + 1)];
+        const float* gs;
+        bool tr;
+        float decay;
+        term(k, gs, tr, decay);
+        if (gs != nullptr && !tr) {
+#pragma unroll
+          for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) kv[t][v] = have ? fmaf(decay, kv[t][v], x[16 * t + v]) : x[16 * t + v];
+        }
+        // A state stored transposed: this wave's slice is then the 32 ROWS 32 dvt .. + 31 of the stored matrix, 32 D
+        // consecutive floats.  Read element by element each lane would touch a cache line of its own (measured
+        // +20 us per launch at 256 workgroups); instead the wave copies its rows with 16-byte loads through the tile
+        // buffers, which nothing has used yet, and each lane picks its elements out of LDS (row stride D + 1 floats:
+        // no bank conflicts).  One wave group at a time, a workgroup barrier after each: the first tile loads, from
+        // any wave, overwrite that LDS.  Whether the launch has transposed states at all is uniform over the grid.
+        if (any_tr) {
+#pragma unroll 1
+          for (int gsel = 0; gsel < NW / SW; gsel++) {
+            if (gs != nullptr && tr && group == gsel) {
+#pragma unroll
+              for (int i = 0; i < 32 * D / 256; i++) {
+                const int at = 4 * (64 * i + l);
+                float* dst = lds + (at / D) * (D + 1) + at % D;
+                dst[0] = x[4 * i]; dst[1] = x[4 * i + 1]; dst[2] = x[4 * i + 2]; dst[3] = x[4 * i + 3];
+              }
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's own writes, before its own reads
+#pragma unroll
+              for (int t = 0; t < NT; t++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                  const float y = lds[l32 * (D + 1) + 32 * t + 8 * (v >> 2) + 4 * hh + (v & 3)];
+                  kv[t][v] = have ? fmaf(decay, kv[t][v], y) : y;
+                }
+            }
+            __syncthreads();
+          }
+        }
+        if (gs != nullptr) have = true;
+      }
     }
     if (!have) {
 #pragma unroll
