@@ -83,7 +83,7 @@ struct ScanParams {
   // lambda^rem, rem = rows of that block), a reverse scan's start state enters right behind the chain's last
   // position likewise, and a chain of no positions passes its start state (or zero) on to fin.
   int32_t ragged_state;
-  // 16-bit half-block kernels only, dense batches: non-zero = `states` holds the chunks' LOCAL states (no scan over
+  // 16-bit half-block kernels only: non-zero = `states` holds the chunks' LOCAL states (no scan over
   // them has run) and every workgroup forms its own start state from the local states of the chunks its scan
   // passes before: G <- init (or 0); for those chunks j in scan order: G <- lambda^(length of chunk j) G + L_j.
   // For a few chunks on a small problem that is cheaper than one more dependent launch between two short kernels.
