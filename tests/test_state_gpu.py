@@ -92,6 +92,27 @@ def test_segment_chunked_and_variants(variant, chunk, d):
     check_segment(t, torch.bfloat16, "variant%d chunk%d d%d" % (variant, chunk, d))
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("nchunks", [2, 3, 4, 5])
+def test_plans_of_few_chunks_form_their_start_states_in_the_scan(nchunks, d, dtype):
+    """Up to four chunks the scan over the chunk states has no launch of its own: every scan workgroup combines the
+    local states of the chunks before it (with the caller's start state in front, also where it is read transposed
+    or enters behind a ragged last block); five chunks take the launch.  Same results either way, with all four
+    states, with none, and for a last chunk that is shorter than the others and ends inside a block."""
+    chunk = 128
+    for n in (nchunks * chunk, nchunks * chunk - 45):
+        binding.la2_set_chunk_tokens(chunk)
+        t = inputs(2, 3, n, d, dtype, seed=900 + 10 * nchunks + d + n, lam=[0.6, 0.95, 1.0])
+        whole = {k: (v[:, :, : n - n % 32] if k in ("q", "k", "v", "d_o") else v) for k, v in t.items()}
+        plan = binding.la2_chunk_plan(whole["q"].contiguous().to(DEV))
+        assert plan == (nchunks, chunk), plan
+        tag = "%d chunks n%d d%d %s" % (nchunks, n, d, dtype)
+        check_segment(t, dtype, tag + " all states")
+        check_segment(t, dtype, tag + " no states", use_init=False, use_final=False)
+        check_segment(t, dtype, tag + " start state only", use_final=False)
+
+
 def test_fp32_chunked_segment():
     binding.la2_set_chunk_tokens(128)
     t = inputs(1, 2, 384, 128, torch.float32, seed=777)
