@@ -92,7 +92,7 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   __shared__ __attribute__((aligned(16))) E sP[DEFER ? 2 : 1][SHP ? 32 * PROW : 8];
   __shared__ f32x4 sDg[(STATE_ONLY || SHP) ? 1 : 4][64];               // decay mask, [element group][lane]
 
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l32 = l & 31, hh = l >> 5;
   const int dvt = w % NT;
   const int group = TWIN ? __builtin_amdgcn_readfirstlane(w / NT) : 0;   // twin: which scan this wave belongs to
   // this wave's X, Y, Z among the tiles of a block
@@ -254,10 +254,13 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   if (!STATE_ONLY) sa_first = state_operand(0);
 
   // output: lane = position l32, elements 8 g .. 8 g + 7 are value features 32 dvt + 16 g + 8 hh .. + 7
-  auto store_block = [&](const f32x16& a, int pos) __attribute__((always_inline)) {
+  // (lr, lh: the lane's position and half; the deferred tail makes them from the lane number inside the loop, so that
+  // no lane-dependent address waits in a register, or in scratch, over the block loop)
+  auto store_block = [&](const f32x16& a, int blkv, int lr, int lh) __attribute__((always_inline)) {
+    const int pos = blkv * B + lr;
     if (pos < n) {
       // wave-uniform base + 32-bit byte offset (a chain spans < 4 GiB, checked on the host)
-      char* const orow = reinterpret_cast<char*>(gw) + ((uint32_t)pos * stride_n + (uint32_t)(32 * dvt + 8 * hh)) * 2u;
+      char* const orow = reinterpret_cast<char*>(gw) + ((uint32_t)pos * stride_n + (uint32_t)(32 * dvt + 8 * lh)) * 2u;
 #pragma unroll
       for (int g = 0; g < 2; g++) {
         ex8<E> pk;
@@ -272,12 +275,15 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
   ex8<E> zf_prev[2] = {};
   int blk_prev = 0;
   auto finish_block = [&](f32x16 a, const ex8<E> (&zfv)[2], int blkv, const E* tile) __attribute__((always_inline)) {
+    int lo = l;
+    asm volatile("" : "+v"(lo));
+    const int lr = lo & 31, lh = lo >> 5;
     ex8<E> pv[2];
 #pragma unroll
-    for (int q = 0; q < 2; q++) pv[q] = *reinterpret_cast<const ex8<E>*>(tile + l32 * PROW + 16 * q + 8 * hh);
+    for (int q = 0; q < 2; q++) pv[q] = *reinterpret_cast<const ex8<E>*>(tile + lr * PROW + 16 * q + 8 * lh);
 #pragma unroll
     for (int q = 0; q < 2; q++) a = mfma(zfv[q], pv[q], a);
-    store_block(a, blkv * B + l32);
+    store_block(a, blkv, lr, lh);
   };
   auto block_at = [&](int it) { return REV ? blk_hi - 1 - it : blk_lo + it; };
   if (loads) loader.issue(sT[0], block_at(0));
@@ -502,7 +508,7 @@ __global__ __launch_bounds__((TWIN ? 4 : 2) * D, TWIN ? 2 : (D == 96 ? 3 : 2)) v
         for (int v = 0; v < 16; v++) acc[v] *= r;
         if (dvt == 0 && hh == 0 && pos < n) p.rstd[rstd_chain_offset(p, bi, hi) + pos] = r;
       }
-      store_block(acc, pos);
+      store_block(acc, blk, l32, hh);
     }
   }
   if constexpr (DEFER) {
