@@ -135,9 +135,20 @@ Plan make_plan(const la2_desc* d) {
     // Chunking shortens the scan's sequential loop from nblocks to cb blocks but adds the pre-pass (about a
     // third of a scan block per block) and two more launches (about 15 us): not worth it for short sequences.
     // Measured times of one block of the sequential loop, in microseconds.
-    const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 9.f : d->head_dim == 96 ? 3.f : d->head_dim == 64 ? 1.15f : 2.1f)
+    const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 3.3f : d->head_dim == 96 ? 3.f : d->head_dim == 64 ? 1.15f : 2.1f)
                                        : (d->head_dim == 128 ? 10.f : 3.f);
-    if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) return pl;
+    if (is16(d->dtype) && d->head_dim == 256) {
+      // One workgroup of this kernel fills a compute unit, and a block takes it 3.3 us with every unit busy but
+      // 2.3 us with half of them idle; the pre-pass costs 0.6 of a scan block per block.  Measured at 128 chains of
+      // 4096 positions: 0.29 + 0.68 ms uncut (half the units idle) against 0.35 + 0.92 ms in two chunks.
+      const int nch = (nblocks + cb - 1) / cb;
+      const float rounds = (float)((chains * nch + cus - 1) / cus), pre_rounds = (float)((chains * (nch - 1) + cus - 1) / cus);
+      const float t_uncut = (float)nblocks * (chains * 2 <= cus ? 2.3f : 3.3f);
+      const float t_cut = (rounds + 0.6f * pre_rounds) * (float)cb * 3.3f + 15.f;
+      if (t_cut >= t_uncut) return pl;
+    } else if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) {
+      return pl;
+    }
   }
   if (cb >= nblocks) return pl;
   pl.nchunks = (nblocks + cb - 1) / cb;
@@ -184,7 +195,7 @@ Plan make_plan_varlen(const la2_desc* d, int64_t total_positions) {
   if ((int64_t)d->seqlen * d->batch <= 2 * total_positions) return pl;   // lengths about equal
   // microseconds: the longest chain's loop (measured times per block, as in make_plan) against the batch's forward
   // traffic at 5.5 TB/s
-  const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 9.f : d->head_dim == 96 ? 3.f : d->head_dim == 64 ? 1.15f : 2.1f)
+  const float t_blk = is16(d->dtype) ? (d->head_dim == 256 ? 3.3f : d->head_dim == 96 ? 3.f : d->head_dim == 64 ? 1.15f : 2.1f)
                                      : (d->head_dim == 128 ? 10.f : 3.f);
   const float t_longest = (float)nblocks * t_blk;
   const float t_traffic = (float)total_positions * d->heads * d->head_dim * 4.f * elem_size(d->dtype) / 5.5e6f;
