@@ -112,6 +112,8 @@ struct Plan {
   size_t map_bytes = 0;
 };
 
+bool self_prefix(const la2_desc* d, const Plan& pl, const int32_t* cu);
+
 // Sequence chunks: the block loop of one chain is sequential, so when batch*heads cannot fill the
 // compute units the sequence is cut into chunks that run in parallel from pre-computed start states.
 Plan make_plan(const la2_desc* d) {
@@ -128,7 +130,15 @@ Plan make_plan(const la2_desc* d) {
   } else {
     const int cus = device_cu_count();
     if (chains >= cus) return pl;
-    const int want = (int)((cus + chains - 1) / chains);
+    // More chains than half the compute units: two chunks would make between one and two workgroups per unit, the
+    // launch would move 1.4 times the bytes and most of the bandwidth is already in use (192 chains of 4096
+    // positions, forward + backward: 0.58 ms uncut against 0.76 ms in two chunks at head_dim 128, 0.31 / 0.36 at 64,
+    // 0.47 / 0.66 at 96).  Head_dim 96, whose kernel runs four workgroups a unit, also at exactly half (0.42 / 0.46).
+    if (chains * 2 > cus || (d->head_dim == 96 && chains * 2 == cus)) return pl;
+    // workgroups to aim for: one per compute unit; two at head_dim 96 (64 chains of 8192 positions: 0.43 ms in eight
+    // chunks against 0.47 ms in four)
+    const int64_t aim = d->head_dim == 96 ? 2 * (int64_t)cus : cus;
+    const int want = (int)((aim + chains - 1) / chains);
     cb = (nblocks + want - 1) / want;
     if (cb < 4) cb = 4;  // keep the state pre-pass a small fraction of the work
     if (cb >= nblocks) return pl;
@@ -146,8 +156,11 @@ Plan make_plan(const la2_desc* d) {
       const float t_uncut = (float)nblocks * (chains * 2 <= cus ? 2.3f : 3.3f);
       const float t_cut = (rounds + 0.6f * pre_rounds) * (float)cb * 3.3f + 15.f;
       if (t_cut >= t_uncut) return pl;
-    } else if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - 15.f <= 0.f) {
-      return pl;
+    } else {
+      // the extra launches: the pre-pass and the scan over the chunk states, which plans of a few chunks do without
+      Plan cut{(nblocks + cb - 1) / cb, cb * B, 0};
+      const float launches = self_prefix(d, cut, nullptr) ? 8.f : 15.f;
+      if ((float)(nblocks - cb) * t_blk - 0.35f * (float)cb * t_blk - launches <= 0.f) return pl;
     }
   }
   if (cb >= nblocks) return pl;
