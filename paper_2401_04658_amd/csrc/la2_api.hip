@@ -137,8 +137,12 @@ Plan make_plan(const la2_desc* d) {
     if (chains * 2 > cus || (d->head_dim == 96 && chains * 2 == cus)) return pl;
     // workgroups to aim for: one per compute unit; two at head_dim 96 (64 chains of 8192 positions: 0.43 ms in eight
     // chunks against 0.47 ms in four)
+    // ... and never more than that: the workgroups past one per unit double up on some units while others have one,
+    // and the launch takes as long as the doubled ones (48 chains of 4096 positions at head_dim 128, forward +
+    // backward: 0.22 ms in four or five chunks, 0.31 ms in six; the same cliff at head_dim 64 and 256).
     const int64_t aim = d->head_dim == 96 ? 2 * (int64_t)cus : cus;
-    const int want = (int)((aim + chains - 1) / chains);
+    const int want = (int)(aim / chains);
+    if (want < 2) return pl;
     cb = (nblocks + want - 1) / want;
     if (cb < 4) cb = 4;  // keep the state pre-pass a small fraction of the work
     if (cb >= nblocks) return pl;

@@ -422,7 +422,7 @@ def test_noalloc_entry_validates_on_the_host(lib):
     assert fn(d, q=P + 2) == E_ALIGN
     d.head_dim = 80
     assert fn(d) == E_SHAPE
-    big = dense(lib, 1, 100, 1 << 18, 128, binding.LA2_BF16)            # 19 MiB of chunk states (three chunks)
+    big = dense(lib, 1, 64, 1 << 16, 256, binding.LA2_BF16)             # 64 MiB of chunk states (four chunks, head_dim 256)
     assert lib.la2_workspace_bytes(ctypes.byref(big), 0) > 16 << 20
     assert fn(big) == E_WS
     empty = dense(lib, 0, 8, 8192, 128, binding.LA2_BF16)

@@ -48,7 +48,7 @@ def test_noalloc_matches_la2_fwd_two_calls_in_a_row():
 def test_noalloc_refuses_what_the_scratch_cannot_hold():
     lib = binding.load()
     desc = binding.la2_desc()
-    lib.la2_desc_dense(ctypes.byref(desc), 1, 100, 1 << 18, 128, binding.LA2_BF16)   # three chunks: 19 MiB of states
+    lib.la2_desc_dense(ctypes.byref(desc), 1, 64, 1 << 16, 256, binding.LA2_BF16)   # four chunks at head_dim 256: 64 MiB of states
     assert lib.la2_workspace_bytes(ctypes.byref(desc), 0) > (16 << 20)
     P = ctypes.c_void_p(0x10000)   # never dereferenced: the call is refused on the host
     assert lib.la2_fwd_noalloc(ctypes.byref(desc), P, P, P, P, P, None) == 5   # LA2_ERR_WORKSPACE
