@@ -140,8 +140,11 @@ Plan make_plan(const la2_desc* d) {
     // ... and never more than that: the workgroups past one per unit double up on some units while others have one,
     // and the launch takes as long as the doubled ones (48 chains of 4096 positions at head_dim 128, forward +
     // backward: 0.22 ms in four or five chunks, 0.31 ms in six; the same cliff at head_dim 64 and 256).
-    const int64_t aim = d->head_dim == 96 ? 2 * (int64_t)cus : cus;
-    const int want = (int)(aim / chains);
+    int want = (int)(cus / chains);
+    if (d->head_dim == 96) {   // ... two per unit while the chunks stay 640 positions or longer (8 chains of 32768
+      const int want2 = (int)(2 * (int64_t)cus / chains);   // positions: 0.25 ms in 32 chunks, 0.27 ms in 64)
+      if (d->seqlen / want2 >= 640) want = want2;
+    }
     if (want < 2) return pl;
     cb = (nblocks + want - 1) / want;
     if (cb < 4) cb = 4;  // keep the state pre-pass a small fraction of the work
