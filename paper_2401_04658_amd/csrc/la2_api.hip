@@ -134,7 +134,7 @@ Plan make_plan(const la2_desc* d) {
     // launch would move 1.4 times the bytes and most of the bandwidth is already in use (192 chains of 4096
     // positions, forward + backward: 0.58 ms uncut against 0.76 ms in two chunks at head_dim 128, 0.31 / 0.36 at 64,
     // 0.47 / 0.66 at 96).  Head_dim 96, whose kernel runs four workgroups a unit, also at exactly half (0.42 / 0.46).
-    if (chains * 2 > cus || (d->head_dim == 96 && chains * 2 == cus)) return pl;
+    if (is16(d->dtype) && (chains * 2 > cus || (d->head_dim == 96 && chains * 2 == cus))) return pl;
     // workgroups to aim for: one per compute unit; two at head_dim 96 (64 chains of 8192 positions: 0.43 ms in eight
     // chunks against 0.47 ms in four)
     // ... and never more than that: the workgroups past one per unit double up on some units while others have one,
@@ -145,6 +145,10 @@ Plan make_plan(const la2_desc* d) {
       const int want2 = (int)(2 * (int64_t)cus / chains);   // positions: 0.25 ms in 32 chunks, 0.27 ms in 64)
       if (d->seqlen / want2 >= 640) want = want2;
     }
+    // fp32 data at head_dim 64: that kernel is bound by its arithmetic and three of its workgroups share a unit
+    // (192 chains of 4096 positions, forward + backward: 2.2 ms uncut, 1.38 ms in four chunks; 64 chains: 0.79 ms in
+    // four chunks, 0.57 ms in eleven)
+    if (!is16(d->dtype) && d->head_dim == 64) want = (int)(3 * (int64_t)cus / chains);
     if (want < 2) return pl;
     cb = (nblocks + want - 1) / want;
     if (cb < 4) cb = 4;  // keep the state pre-pass a small fraction of the work
