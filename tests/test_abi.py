@@ -552,3 +552,44 @@ def test_decode_step_norm_validation(lib):
     assert dn(d=100) == E_SHAPE and dn(b=-1) == E_SHAPE and dn(dt=9) == E_DTYPE
     assert dn(q=None) == E_NULL and dn(kv=None) == E_NULL and dn(o=P + 8) == E_ALIGN
     assert dn(b=0, q=None, kv=None, o=None) == OK
+
+
+def plan(lib, b, h, n, d, dtype):
+    desc = dense(lib, b, h, n, d, dtype)
+    nch, ct = ctypes.c_int32(0), ctypes.c_int32(0)
+    assert lib.la2_chunk_plan(ctypes.byref(desc), ctypes.byref(nch), ctypes.byref(ct)) == OK
+    return nch.value, ct.value
+
+
+def test_the_chunk_planner_keeps_its_measured_rules(lib):
+    """The rules of the sequence-chunk planner, each taken from a measurement (256 compute units, which is also what
+    the library assumes when it sees no device)."""
+    lib.la2_set_chunk_tokens(0)
+    BF, F32 = binding.LA2_BF16, binding.LA2_F32
+    # enough chains for every compute unit: no cut
+    assert plan(lib, 16, 16, 4096, 128, BF) == (1, 4096)
+    assert plan(lib, 64, 16, 1024, 128, BF)[0] == 1
+    # few chains: as many chunks as keep the workgroups at or below one per compute unit, never more
+    assert plan(lib, 4, 16, 16384, 128, BF) == (4, 4096)
+    assert plan(lib, 1, 16, 65536, 128, BF) == (16, 4096)
+    assert plan(lib, 4, 16, 2048, 64, BF) == (4, 512)
+    for b, h, n, d in ((3, 16, 4096, 128), (5, 16, 4096, 128), (6, 16, 8192, 128), (7, 16, 4096, 128), (3, 16, 4096, 64),
+                       (5, 16, 4096, 64), (7, 8, 4096, 256), (5, 8, 16384, 256)):
+        nch, _ = plan(lib, b, h, n, d, BF)
+        assert nch > 1 and b * h * nch <= 256 < b * h * (nch + 1), (b, h, n, d, nch)
+    # more chains than half the compute units: no cut (two chunks would move 1.4 times the bytes for little)
+    for d in (64, 96, 128, 256):
+        assert plan(lib, 12, 16, 4096, d, BF)[0] == 1, d
+        assert plan(lib, 9, 16, 4096, d, BF)[0] == 1, d
+    # head_dim 96 also at exactly half, and two workgroups per unit while the chunks stay 640 positions or longer
+    assert plan(lib, 8, 16, 4096, 96, BF)[0] == 1
+    assert plan(lib, 4, 16, 8192, 96, BF) == (8, 1024)
+    assert plan(lib, 1, 8, 32768, 96, BF) == (32, 1024)
+    # head_dim 256: half-idle compute units run a block faster than busy ones, so 128 chains stay whole
+    assert plan(lib, 16, 8, 4096, 256, BF)[0] == 1
+    assert plan(lib, 8, 8, 8192, 256, BF) == (4, 2048)
+    # fp32 at head_dim 64: three workgroups per compute unit
+    assert plan(lib, 4, 16, 4096, 64, F32)[0] == 12 or plan(lib, 4, 16, 4096, 64, F32)[0] == 11
+    assert plan(lib, 12, 16, 4096, 64, F32)[0] == 4
+    # short sequences are not worth a pre-pass
+    assert plan(lib, 8, 16, 256, 128, BF)[0] == 1
