@@ -239,6 +239,53 @@ def test_strided_layout():
             assert_close("strided " + name, got, ref, dtype)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("b,H,n,d,strided", [(20, 16, 2048, 128, False), (18, 16, 2100, 64, True), (11, 32, 4096, 128, False)])
+def test_batches_a_little_above_the_compute_unit_count(b, H, n, d, strided, dtype):
+    """A few more chains than compute units: la2_fwd / la2_bwd run the first rows whole and the remaining rows in
+    chunks, as two calls on the same stream.  Chains on both sides of that cut, at sampled positions (block and chunk
+    borders among them) against the O(n^2) oracle, and the Euler identity over everything."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    t = make_inputs(b, H, n, d, dtype, seed=53)
+    g = {}
+    for name in ("q", "k", "v", "d_o"):
+        if strided:
+            g[name] = t[name].permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+        else:
+            g[name] = t[name].to(DEV)
+    lam = t["lam"].to(DEV)
+    cut = min(max(cus // H, 1), b - 1)
+    nch, chunk = binding.la2_chunk_plan(g["q"][cut:])
+    if cus == 256:     # the split is what runs: its workspace is that of the remaining rows' plan
+        assert nch > 1
+        assert binding.la2_workspace_bytes(g["q"]) == binding.la2_workspace_bytes(g["q"][cut:]) > 0
+    o = binding.la2_fwd(g["q"], g["k"], g["v"], lam)
+    dq, dk, dv = binding.la2_bwd(g["q"], g["k"], g["v"], g["d_o"], lam)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(53)
+    tol = TOL[dtype]
+    borders = [c * chunk + e for c in range(1, nch) for e in (-1, 0, 1)]
+    for row in sorted({0, cut - 1, cut, b - 1}):
+        for h in (0, H // 2, H - 1):
+            rows = np.array(sorted(set(sampled_rows(n, rng).tolist() + [r for r in borders if 0 <= r < n])), dtype=np.int64)
+            q, k, v, do = (to64(t[x][row, h]) for x in ("q", "k", "v", "d_o"))
+            lam_h = float(t["lam"][h].double())
+            ref_o = oracle.fwd_rows(q, k, v, lam_h, rows)
+            ref_dq, ref_dk, ref_dv = oracle.bwd_rows(q, k, v, do, lam_h, rows)
+            for name, got, ref in (("o", o, ref_o), ("dq", dq, ref_dq), ("dk", dk, ref_dk), ("dv", dv, ref_dv)):
+                x = to64(got[row, h])[rows]
+                assert np.all(np.isfinite(x))
+                err = float(np.max(np.abs(x - ref))) / float(np.max(np.abs(ref)))
+                assert err <= tol, "%s (b%d h%d): %.3e" % (name, row, h, err)
+    f64 = lambda x: x.to(torch.float64)
+    L = torch.sum(f64(o) * f64(g["d_o"])).item()
+    scale = torch.sum(torch.abs(f64(o) * f64(g["d_o"]))).item()
+    for name, grad, x in (("dq", dq, g["q"]), ("dk", dk, g["k"]), ("dv", dv, g["v"])):
+        assert abs(torch.sum(f64(grad) * f64(x)).item() - L) <= 2e-3 * scale, name
+    for x in (o, dq, dk, dv):
+        assert torch.isfinite(x.float()).all()
+
+
 def test_deterministic_and_causal():
     t = gpu(make_inputs(2, 2, 700, 128, torch.bfloat16, seed=41))
     o1 = binding.la2_fwd(t["q"], t["k"], t["v"], t["lam"])
