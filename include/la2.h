@@ -98,12 +98,14 @@ size_t la2_workspace_bytes(const la2_desc* desc, int32_t op);
  * loop of Algorithm 1 / 2 runs over the whole sequence in one workgroup per (batch, head).  The workspace
  * holds one d x d fp32 start state per (batch, head, chunk) when nchunks > 1.  Depends on the device's
  * compute-unit count and on la2_set_chunk_tokens(), like la2_workspace_bytes().
- * One case it does not describe: a 16-bit batch (head_dim 64 / 128, seqlen >= 2048, no la2_set_chunk_tokens())
- * with between 1 and 1.4 chains per compute unit (1.25 under 4096 positions), which as one launch gives some units two workgroups and takes
- * nearly twice as long as one chain per unit.  la2_fwd / la2_bwd run it as two calls on the given stream: the
- * first floor(units / heads) batch rows by the plan of that many rows (one chunk), the remaining rows by the plan
- * of a descriptor with that many rows (several chunks); la2_workspace_bytes(LA2_OP_FWD / LA2_OP_BWD) answers for
- * the second.  Results are those of the same block loop either way, up to the rounding of the chunk states.
+ * One case it does not describe: a batch with a few more chains than one (or two) per compute unit, which as one
+ * launch gives some units a workgroup more than the others and takes nearly as long as the next whole round (fp32:
+ * twice the time of one chain per unit for anything between one and two).  la2_fwd / la2_bwd run it as two calls
+ * on the given stream: the first floor(rounds * units / heads) batch rows by the plan of that many rows (one chunk),
+ * the remaining rows by the plan of a descriptor with that many rows (several chunks);
+ * la2_workspace_bytes(LA2_OP_FWD / LA2_OP_BWD) answers for both.  Which shapes: seqlen >= 2048 (fp32: 1024), no
+ * la2_set_chunk_tokens(), and a partial round of at most 1/8 to 4/8 of the unit count, by dtype and head_dim, as
+ * measured.  Results are those of the same block loop either way, up to the rounding of the chunk states.
  */
 la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk_tokens);
 

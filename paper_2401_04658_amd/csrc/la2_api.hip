@@ -113,6 +113,7 @@ struct Plan {
 };
 
 bool self_prefix(const la2_desc* d, const Plan& pl, const int32_t* cu);
+bool fuses_reverse_states(const la2_desc* d);
 
 // Sequence chunks: the block loop of one chain is sequential, so when batch*heads cannot fill the
 // compute units the sequence is cut into chunks that run in parallel from pre-computed start states.
@@ -257,28 +258,65 @@ la2_status check_desc(const la2_desc* d) {
   return LA2_OK;
 }
 
-// A dense batch with a few more chains than compute units: the units that get a second workgroup set the launch's time
-// (n 4096, head_dim 128, forward + backward: 256 chains 0.67 ms, 320 chains 1.14 ms).  la2_fwd / la2_bwd run such a
-// batch as two calls: the first rows, about one chain per unit, whole; the rest by the plan for that many chains,
-// i.e. in chunks (320 chains: 0.67 + 0.27 ms).  Returns the rows of the first call, 0 for one call.
-// Measured, two calls against one, forward + backward, head_dim 64 and 128, 8 / 16 / 32 heads:
-//   chains   n 1024     n 2048       n 4096       n 8192
-//   272     0.95-1.09  0.81-0.92    0.76-0.81    0.72-0.75
-//   320     1.04-1.12  0.92-0.95    0.86-0.90    0.85-0.86
-//   352     1.06-1.07  0.98-1.05    0.96-0.98    0.94-0.95
+// A dense batch with a few more chains than a whole number of chains per compute unit: the units that get one
+// workgroup more set the launch's time (n 4096, head_dim 128, bf16, forward + backward: 256 chains 0.67 ms, 320
+// chains 1.14 ms; fp32: 9.5 ms for anything from 272 to 480 chains).  la2_fwd / la2_bwd run such a batch as two
+// calls: the first rows, one or two chains per unit, whole; the rest by the plan for that many chains, i.e. in
+// chunks (320 chains: 0.67 + 0.27 ms).  Returns the rows of the first call, 0 for one call.
+// Measured, two calls against one, forward + backward, n 2048 / 4096 / 8192 (256 units):
+//   chains           272          288          320          352          384
+//   bf16 d 64, 128   0.81-0.92    0.80-0.93    0.85-0.95    0.94-1.05    -         (n 1024: 0.95-1.12)
+//   bf16 d 96        0.76-0.88    0.82-0.91    0.91-0.98    0.98-1.11    1.04-1.07
+//   bf16 d 256       0.82-0.86    0.87-0.96    0.96-1.05    1.01-1.03    1.01
+//   fp32 d 128       0.53-0.59    0.57-0.64    0.66-0.71    0.82-0.86    0.84-0.87 (n 1024: 0.64, -, 0.74, -, 0.90)
+//   fp32 d 64        0.64-0.67    0.66-0.72    0.72-0.77    0.78-0.81    0.84-0.87 (n 1024: 0.75, -, 0.85, -, 0.94)
+//   chains           544          576          640
+//   bf16 d 64, 128   0.86-0.98    0.90-0.99    0.98-1.05    (n 4096 and 8192: 0.86-0.90, 0.90-0.94)
+//   bf16 d 96        0.87-0.93    0.92-0.98    1.03
+//   bf16 d 256       0.96         1.01         1.01
+//   fp32 d 128       0.73         0.79         0.91         (n 4096)
+//   fp32 d 64        1.06         1.11         1.23         (two workgroups per unit: no step at 512)
+// The rule below takes the cells at 0.95 or under.
 int rows_of_first_call(const la2_desc* d) {
-  if (!is16(d->dtype) || wide(d->head_dim) || d->seqlen < 2048) return 0;
   if (g_chunk_tokens_override.load(std::memory_order_relaxed) > 0) return 0;   // the caller plans
   const int cus = device_cu_count();
+  const int n = d->seqlen, hd = d->head_dim;
   const int64_t chains = (int64_t)d->batch * d->heads;
-  const int64_t most = d->seqlen >= 4096 ? (int64_t)cus * 14 / 10 : (int64_t)cus * 5 / 4;
-  if (chains <= cus || chains > most || d->heads > cus) return 0;
-  const int rows = cus / d->heads;
-  if (rows < 1 || rows >= d->batch) return 0;
+  const int64_t k = chains / cus;   // whole rounds of one chain per unit
+  if (k < 1 || k > 2 || d->heads > cus) return 0;
+  // the largest partial round, in eighths of the unit count, that is worth a call of its own
+  int eighths = 0;
+  if (d->dtype == LA2_F32) {
+    if (wide(hd)) return 0;
+    if (k == 1) eighths = n >= 1024 ? 4 : 0;
+    else eighths = hd == 128 && n >= 2048 ? 2 : 0;
+  } else if (hd == 256) {
+    eighths = k == 1 && n >= 2048 ? 1 : 0;
+  } else if (hd == 96) {
+    eighths = k == 1 ? (n >= 4096 ? 2 : n >= 2048 ? 1 : 0) : (n >= 4096 ? 1 : 0);
+  } else {
+    eighths = k == 1 ? (n >= 4096 ? 3 : n >= 2048 ? 2 : 0) : (n >= 4096 ? 2 : 0);
+  }
+  const int64_t rows = k * cus / d->heads;
+  const int64_t rest_chains = chains - rows * d->heads;
+  if (rows < 1 || rest_chains <= 0 || rest_chains * 8 > (int64_t)cus * eighths) return 0;
   la2_desc rest = *d;
-  rest.batch = d->batch - rows;
+  rest.batch = d->batch - (int)rows;
   if (make_plan(&rest).nchunks <= 1) return 0;   // sequences too short to cut: the rest would run whole as well
-  return rows;
+  return (int)rows;
+}
+
+// Workspace of the two calls (they run one after the other on one stream and share it).
+size_t split_workspace(const la2_desc* d, int rows, bool bwd) {
+  size_t need = 0;
+  for (int part = 0; part < 2; ++part) {
+    la2_desc s = *d;
+    s.batch = part == 0 ? rows : d->batch - rows;
+    // backward: the chunk states of the dQ scan and (when its launch forms them) those of the dK / dV scan
+    const size_t w = make_plan(&s).workspace * ((bwd && fuses_reverse_states(&s)) ? 2 : 1);
+    need = w > need ? w : need;
+  }
+  return need;
 }
 
 struct ScanArgs {
@@ -487,10 +525,10 @@ void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen
 size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
   if (check_desc(desc) != LA2_OK) return 0;
   if (op == LA2_OP_FWD || op == LA2_OP_BWD) {
-    la2_desc d = *desc;
-    d.batch -= rows_of_first_call(desc);   // two calls: the first needs none, the second its own plan's
+    const int rows = rows_of_first_call(desc);
+    if (rows > 0) return split_workspace(desc, rows, op == LA2_OP_BWD);
     // backward: the chunk states of the dQ scan and (when its launch forms them) those of the dK / dV scan
-    return make_plan(&d).workspace * ((op == LA2_OP_BWD && fuses_reverse_states(&d)) ? 2 : 1);
+    return make_plan(desc).workspace * ((op == LA2_OP_BWD && fuses_reverse_states(desc)) ? 2 : 1);
   }
   if (op == LA2_OP_FWD_STATE || op == LA2_OP_BWD_STATE) return state_workspace(desc, op == LA2_OP_BWD_STATE).total;
   return 0;
@@ -612,7 +650,7 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
     la2_desc a = *desc, b = *desc;
     a.batch = rows;
     b.batch = desc->batch - rows;
-    const size_t need = make_plan(&b).workspace;
+    const size_t need = split_workspace(desc, rows, false);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
     const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
     const la2_status st = la2_fwd_state(&a, q, k, v, lambda, nullptr, o, nullptr, workspace, workspace_bytes, hip_stream);
@@ -770,7 +808,7 @@ la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const voi
     la2_desc a = *desc, b = *desc;
     a.batch = rows;
     b.batch = desc->batch - rows;
-    const size_t need = make_plan(&b).workspace * (fuses_reverse_states(&b) ? 2 : 1);
+    const size_t need = split_workspace(desc, rows, true);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
     const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
     auto at = [off](const void* p) { return static_cast<const void*>(static_cast<const char*>(p) + off); };

@@ -596,31 +596,39 @@ def test_the_chunk_planner_keeps_its_measured_rules(lib):
 
 
 def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remaining_rows(lib):
-    """la2_fwd / la2_bwd run a 16-bit batch of up to 1.4 chains per compute unit as two calls: about one chain per unit
-    whole, the remaining rows by their own plan.  The workspace query answers for exactly that (256 units assumed
-    without a device); la2_chunk_plan still describes one call over the whole batch."""
+    """la2_fwd / la2_bwd run a batch with a few more chains than one (or two) per compute unit as two calls: the rows
+    that make whole rounds, un-chunked, and the remaining rows by their own plan.  The workspace query answers for
+    exactly that (256 units assumed without a device); la2_chunk_plan still describes one call over the whole batch.
+    Which shapes: those where two calls measured at least 5 % faster than one."""
     lib.la2_set_chunk_tokens(0)
     BF, F16, F32 = binding.LA2_BF16, binding.LA2_F16, binding.LA2_F32
     ws = lambda desc, op: lib.la2_workspace_bytes(ctypes.byref(desc), op)
-    for dt in (BF, F16):
-        for b, h, n, d in ((20, 16, 4096, 128), (18, 16, 2048, 64), (11, 32, 4096, 128), (22, 16, 4096, 128),
-                           (20, 16, 2048, 128), (40, 8, 3072, 64)):
-            whole, rest = dense(lib, b, h, n, d, dt), dense(lib, b - 256 // h, h, n, d, dt)
-            assert plan(lib, b, h, n, d, dt)[0] == 1
-            assert plan(lib, b - 256 // h, h, n, d, dt)[0] > 1
-            for op in (0, 1):
-                assert ws(whole, op) == ws(rest, op) > 0, (b, h, n, d, op)
-            assert ws(whole, 3) == 0          # the state entry points run the batch as one call
-    # not split: fp32, wide heads, too many chains (above 1.4 per unit; above 1.25 under 4096 tokens), exactly one per
-    # unit, sequences under 2048 tokens (two calls measured slower there), a caller's chunk
-    for b, h, n, d, dt in ((20, 16, 4096, 128, F32), (40, 8, 4096, 256, BF), (23, 16, 4096, 128, BF),
-                           (21, 16, 2048, 128, BF), (16, 16, 4096, 128, BF), (20, 16, 1024, 128, BF),
-                           (20, 16, 2047, 64, F16)):
-        assert ws(dense(lib, b, h, n, d, dt), 0) == 0, (b, h, n, d)
-    lib.la2_set_chunk_tokens(1024)
+    split = [(20, 16, 4096, 128, BF), (18, 16, 2048, 64, F16), (11, 32, 4096, 128, BF), (22, 16, 4096, 128, F16),
+             (20, 16, 2048, 128, BF), (40, 8, 3072, 64, BF), (22, 12, 4096, 128, BF),      # up to 1.25 / 1.375 per unit
+             (36, 16, 4096, 128, BF), (34, 16, 8192, 64, F16),                             # a little above two per unit
+             (34, 8, 2048, 256, BF), (36, 8, 4096, 256, F16),                              # head_dim 256: up to 1.125
+             (18, 16, 2048, 96, BF), (20, 16, 4096, 96, BF), (34, 16, 4096, 96, F16),      # head_dim 96
+             (20, 16, 4096, 128, F32), (24, 16, 1024, 64, F32), (34, 16, 4096, 128, F32)]  # fp32: up to 1.5
+    for b, h, n, d, dt in split:
+        first = (b * h // 256) * 256 // h
+        whole, rest = dense(lib, b, h, n, d, dt), dense(lib, b - first, h, n, d, dt)
+        assert plan(lib, b, h, n, d, dt)[0] == 1
+        assert plan(lib, first, h, n, d, dt)[0] == 1
+        assert plan(lib, b - first, h, n, d, dt)[0] > 1
+        for op in (0, 1):
+            assert ws(whole, op) == ws(rest, op) > 0, (b, h, n, d, dt, op)
+        assert ws(whole, 3) == 0          # the state entry points run the batch as one call
+    # not split: too many chains for the shape, a whole number of rounds, sequences too short, three rounds
+    for b, h, n, d, dt in ((23, 16, 4096, 128, BF), (21, 16, 2048, 128, BF), (16, 16, 4096, 128, BF),
+                           (20, 16, 1024, 128, BF), (20, 16, 2047, 64, F16), (36, 16, 2048, 128, BF),
+                           (38, 8, 2048, 256, BF), (34, 8, 1024, 256, BF), (68, 8, 4096, 256, BF),
+                           (20, 16, 2048, 96, BF), (36, 16, 4096, 96, BF), (25, 16, 4096, 64, F32),
+                           (24, 16, 512, 64, F32), (34, 16, 4096, 64, F32), (50, 16, 4096, 128, BF),
+                           (32, 16, 4096, 128, BF)):
+        assert ws(dense(lib, b, h, n, d, dt), 0) == 0, (b, h, n, d, dt)
+    lib.la2_set_chunk_tokens(1024)       # a caller's chunk size: one call, cut as asked
     try:
         d = dense(lib, 20, 16, 4096, 128, BF)
         assert ws(d, 0) == 20 * 16 * 4 * 128 * 128 * 4
     finally:
         lib.la2_set_chunk_tokens(0)
-

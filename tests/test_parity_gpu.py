@@ -239,12 +239,21 @@ def test_strided_layout():
             assert_close("strided " + name, got, ref, dtype)
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
-@pytest.mark.parametrize("b,H,n,d,strided", [(20, 16, 2048, 128, False), (18, 16, 2100, 64, True), (11, 32, 4096, 128, False)])
+SPLIT_CASES = [(b, H, n, d, st, dt) for dt in (torch.bfloat16, torch.float16)
+               for b, H, n, d, st in ((20, 16, 2048, 128, False), (18, 16, 2100, 64, True), (11, 32, 4096, 128, False))]
+SPLIT_CASES += [(36, 16, 4096, 128, False, torch.float16), (34, 16, 4100, 64, True, torch.bfloat16),   # two rounds
+                (34, 8, 2048, 256, False, torch.bfloat16), (36, 8, 2100, 256, True, torch.float16),
+                (18, 16, 2048, 96, False, torch.float16), (34, 16, 4096, 96, False, torch.bfloat16),
+                (24, 16, 1024, 64, False, torch.float32), (20, 16, 1100, 128, True, torch.float32),
+                (34, 16, 2048, 128, False, torch.float32)]
+
+
+@pytest.mark.parametrize("b,H,n,d,strided,dtype", SPLIT_CASES)
 def test_batches_a_little_above_the_compute_unit_count(b, H, n, d, strided, dtype):
-    """A few more chains than compute units: la2_fwd / la2_bwd run the first rows whole and the remaining rows in
-    chunks, as two calls on the same stream.  Chains on both sides of that cut, at sampled positions (block and chunk
-    borders among them) against the O(n^2) oracle, and the Euler identity over everything."""
+    """A few more chains than one (or two) per compute unit: la2_fwd / la2_bwd run the rows that make whole rounds
+    un-chunked and the remaining rows in chunks, as two calls on the same stream.  Chains on both sides of that cut,
+    at sampled positions (block and chunk borders among them) against the O(n^2) oracle, and the Euler identity over
+    everything."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     t = make_inputs(b, H, n, d, dtype, seed=53)
     g = {}
@@ -254,7 +263,7 @@ def test_batches_a_little_above_the_compute_unit_count(b, H, n, d, strided, dtyp
         else:
             g[name] = t[name].to(DEV)
     lam = t["lam"].to(DEV)
-    cut = min(max(cus // H, 1), b - 1)
+    cut = min(max((b * H // cus) * cus // H, 1), b - 1)
     nch, chunk = binding.la2_chunk_plan(g["q"][cut:])
     if cus == 256:     # the split is what runs: its workspace is that of the remaining rows' plan
         assert nch > 1
