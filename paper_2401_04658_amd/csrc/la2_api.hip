@@ -837,6 +837,27 @@ la2_status la2_fwd_state_norm(const la2_desc* desc, const void* q, const void* k
 la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
                         float eps, void* o, float* rstd, void* workspace, size_t workspace_bytes,
                         void* hip_stream) {
+  const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
+  if (rows > 0) {   // two calls, as in la2_fwd; rstd is [batch][heads][seqlen]
+    if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
+    if (!q || !k || !v || !o || !lambda || !rstd) return LA2_ERR_NULL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
+        !aligned(rstd, 4))
+      return LA2_ERR_STRIDE_ALIGN;
+    la2_desc a = *desc, b = *desc;
+    a.batch = rows;
+    b.batch = desc->batch - rows;
+    const size_t need = split_workspace(desc, rows, false);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
+    const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
+    const int64_t roff = (int64_t)rows * desc->heads * desc->seqlen;
+    const la2_status st = la2_fwd_state_norm(&a, q, k, v, lambda, nullptr, eps, o, rstd, nullptr, workspace,
+                                             workspace_bytes, hip_stream);
+    if (st != LA2_OK) return st;
+    return la2_fwd_state_norm(&b, static_cast<const char*>(q) + off, static_cast<const char*>(k) + off,
+                              static_cast<const char*>(v) + off, lambda, nullptr, eps, static_cast<char*>(o) + off,
+                              rstd + roff, nullptr, workspace, workspace_bytes, hip_stream);
+  }
   return la2_fwd_state_norm(desc, q, k, v, lambda, nullptr, eps, o, rstd, nullptr, workspace, workspace_bytes,
                             hip_stream);
 }
@@ -874,6 +895,28 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
+  const int rows = rows_of_first_call(desc);
+  if (rows > 0) {   // two calls, as in la2_bwd
+    if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
+    if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4) || !aligned(q, 16) ||
+        !aligned(k, 16) || !aligned(v, 16) || !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) ||
+        !aligned(lambda, 4))
+      return LA2_ERR_STRIDE_ALIGN;
+    la2_desc a = *desc, b = *desc;
+    a.batch = rows;
+    b.batch = desc->batch - rows;
+    const size_t need = split_workspace(desc, rows, true);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
+    const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
+    const int64_t roff = (int64_t)rows * desc->heads * desc->seqlen;
+    auto at = [off](const void* p) { return static_cast<const void*>(static_cast<const char*>(p) + off); };
+    auto atw = [off](void* p) { return static_cast<void*>(static_cast<char*>(p) + off); };
+    st = la2_bwd_state_norm(&a, q, k, v, o, rstd, d_o, lambda, nullptr, nullptr, d_u, dq, dk, dv, nullptr, workspace,
+                            workspace_bytes, hip_stream);
+    if (st != LA2_OK) return st;
+    return la2_bwd_state_norm(&b, at(q), at(k), at(v), at(o), rstd + roff, at(d_o), lambda, nullptr, nullptr, atw(d_u),
+                              atw(dq), atw(dk), atw(dv), nullptr, workspace, workspace_bytes, hip_stream);
+  }
   return la2_bwd_state_norm(desc, q, k, v, o, rstd, d_o, lambda, nullptr, nullptr, d_u, dq, dk, dv, nullptr,
                             workspace, workspace_bytes, hip_stream);
 }

@@ -632,3 +632,32 @@ def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remai
         assert ws(d, 0) == 20 * 16 * 4 * 128 * 128 * 4
     finally:
         lib.la2_set_chunk_tokens(0)
+
+
+def test_two_call_batches_are_validated_before_the_first_launch(lib):
+    """Everything either of the two calls would refuse is refused before the first one launches anything (fake
+    pointers: a launch would fault)."""
+    lib.la2_set_chunk_tokens(0)
+    d = dense(lib, 20, 16, 4096, 128, binding.LA2_BF16)
+    ref = ctypes.byref(d)
+    need_f, need_b = lib.la2_workspace_bytes(ref, 0), lib.la2_workspace_bytes(ref, 1)
+    assert 0 < need_f < need_b
+    assert fwd(lib, d) == E_WS and fwd(lib, d, ws=P, ws_bytes=need_f - 1) == E_WS
+    assert fwd(lib, d, ws=P + 16, ws_bytes=need_f) == E_WS
+    assert fwd(lib, d, q=None, ws=P, ws_bytes=need_f) == E_NULL and fwd(lib, d, o=None, ws=P, ws_bytes=need_f) == E_NULL
+    assert fwd(lib, d, v=P + 8, ws=P, ws_bytes=need_f) == E_ALIGN
+    assert bwd(lib, d) == E_WS and bwd(lib, d, ws=P, ws_bytes=need_b - 1) == E_WS
+    for i in range(8):
+        ptrs = [P] * 8
+        ptrs[i] = None
+        assert bwd(lib, d, ptrs, ws=P, ws_bytes=need_b) == E_NULL
+    fn = lambda eps=1e-6, q=P, o=P, rstd=P, ws=P, wb=need_f: lib.la2_fwd_norm(ref, q, P, P, P, eps, o, rstd, ws, wb, None)
+    assert fn(eps=-1.0) == E_VALUE and fn(q=None) == E_NULL and fn(rstd=None) == E_NULL
+    assert fn(o=P + 8) == E_ALIGN and fn(rstd=P + 2) == E_ALIGN
+    assert fn(ws=None, wb=0) == E_WS and fn(wb=need_f - 1) == E_WS
+    bn = lambda o=P, rstd=P, d_u=P, dq=P, ws=P, wb=need_b: lib.la2_bwd_norm(ref, P, P, P, o, rstd, P, P, d_u, dq, P, P, ws,
+                                                                          wb, None)
+    assert bn(o=None) == E_NULL and bn(rstd=None) == E_NULL and bn(d_u=None) == E_NULL and bn(dq=None) == E_NULL
+    assert bn(d_u=P + 4) == E_ALIGN and bn(rstd=P + 1) == E_ALIGN
+    assert bn(ws=None, wb=0) == E_WS and bn(wb=need_b - 1) == E_WS
+

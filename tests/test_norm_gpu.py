@@ -145,6 +145,23 @@ def test_norm_full_size_sampled(wl):
     """Benchmark shapes, in the launch configuration bench.py times: sampled rows of three chains against the
     oracle (the chain's un-normalised output from the recurrent form, then the row formulas), and two
     properties of the full result."""
+    check_norm_sampled(wl, ((0, 0), (wl.batch - 1, wl.heads // 2), (0, wl.heads - 1)))
+
+
+@pytest.mark.parametrize("b,H,n,d,dtype", [(20, 16, 2048, 128, torch.bfloat16), (18, 16, 2048, 64, torch.float16),
+                                           (34, 8, 2048, 256, torch.bfloat16), (18, 16, 2048, 96, torch.bfloat16),
+                                           (20, 16, 1024, 64, torch.float32)])
+def test_norm_of_batches_a_little_above_the_compute_unit_count(b, H, n, d, dtype):
+    """la2_fwd_norm / la2_bwd_norm run such a batch as two calls, like la2_fwd / la2_bwd: the rows that give every
+    compute unit one chain un-chunked, the remaining rows in chunks.  Chains on both sides of the cut; rstd and
+    d_u are addressed per call as well."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    cut = min(max((b * H // cus) * cus // H, 1), b - 1)
+    wl = workloads.Workload("b%d_h%d_n%d_d%d" % (b, H, n, d), b, H, n, d, dtype, seed=67, backward=True)
+    check_norm_sampled(wl, ((0, 0), (cut - 1, H - 1), (cut, 0), (cut, H // 2), (b - 1, H - 1)))
+
+
+def check_norm_sampled(wl, chains):
     eps = 1e-6
     t = wl.tensors()
     g = {k: v.to(DEV) for k, v in t.items()}
@@ -153,8 +170,8 @@ def test_norm_full_size_sampled(wl):
     dq, dk, dv = binding.la2_bwd_norm(g["q"], g["k"], g["v"], o, rstd, g["d_o"], g["lam"], d_u=d_u)
     torch.cuda.synchronize()
     rng = np.random.default_rng(wl.seed)
-    H, tol = wl.heads, TOL[wl.dtype]
-    for b, h in ((0, 0), (wl.batch - 1, H // 2), (0, H - 1)):
+    tol = TOL[wl.dtype]
+    for b, h in chains:
         rows = _sampled_rows(wl.seqlen, rng)
         q, k, v, do = (to64(t[x][b, h]) for x in ("q", "k", "v", "d_o"))
         lam = float(t["lam"][h].double())
