@@ -413,17 +413,20 @@ def main():
                                     "fwd_algorithmic_GBs": round(4 * unit / f_ms / 1e6, 1),
                                     "bwd_algorithmic_GBs": round(10 * unit / b_ms / 1e6, 1)})
             del g_h
-    # a batch a little above one chain per compute unit (320 chains on 256 units): la2_fwd / la2_bwd run it as two
-    # calls, the first 256 chains whole and the other 64 in chunks; the state entry points run it as one call, in which
-    # 64 units get a second workgroup and set the launch's time
+    # a batch a little above one chain per compute unit (320 chains on 256 units): the library runs it as two calls,
+    # the first 256 chains whole and the other 64 in chunks; with a chunk size set by the caller (here the whole
+    # sequence) it runs as one call, in which 64 units get a second workgroup and set the launch's time
     wl_u = workloads.Workload("b20_n4096_h16_d128", 20, 16, 4096, 128, torch.bfloat16, seed=71)
     g_u = stage(wl_u)
     f_ms = time_ms(lambda: fwd(g_u), iters, warm=40, settle_ms=80)
     b_ms = time_ms(lambda: bwd(g_u), iters, warm=40, settle_ms=80)
-    f1_ms = time_ms(lambda: binding.la2_fwd_state(g_u["q"], g_u["k"], g_u["v"], g_u["lam"], want_final=False,
-                                                  out=g_u["o"]), iters, warm=40, settle_ms=80)
-    b1_ms = time_ms(lambda: binding.la2_bwd_state(g_u["q"], g_u["k"], g_u["v"], g_u["d_o"], g_u["lam"],
-                                                  want_d_kv_init=False, out=g_u["grads"]), iters, warm=40, settle_ms=80)
+    binding.la2_set_chunk_tokens(wl_u.seqlen)
+    try:
+        assert binding.la2_workspace_bytes(g_u["q"], binding.LA2_OP_BWD) == 0
+        f1_ms = time_ms(lambda: fwd(g_u), iters, warm=40, settle_ms=80)
+        b1_ms = time_ms(lambda: bwd(g_u), iters, warm=40, settle_ms=80)
+    finally:
+        binding.la2_set_chunk_tokens(0)
     uneven = {"workload": wl_u.name, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
               "tokens_per_s": round(wl_u.tokens / ((f_ms + b_ms) * 1e-3), 1),
               "as_one_call": {"fwd_ms": round(f1_ms, 4), "bwd_ms": round(b1_ms, 4),

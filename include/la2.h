@@ -100,12 +100,15 @@ size_t la2_workspace_bytes(const la2_desc* desc, int32_t op);
  * compute-unit count and on la2_set_chunk_tokens(), like la2_workspace_bytes().
  * One case it does not describe: a batch with a few more chains than one (or two) per compute unit, which as one
  * launch gives some units a workgroup more than the others and takes nearly as long as the next whole round (fp32:
- * twice the time of one chain per unit for anything between one and two).  la2_fwd / la2_bwd and la2_fwd_norm /
- * la2_bwd_norm run it as two calls on the given stream: the first floor(rounds * units / heads) batch rows by the
- * plan of that many rows (one chunk), the remaining rows by the plan of a descriptor with that many rows (several);
- * la2_workspace_bytes(LA2_OP_FWD / LA2_OP_BWD) answers for both.  Which shapes: seqlen >= 2048 (fp32: 1024), no
- * la2_set_chunk_tokens(), and a partial round of at most 1/8 to 4/8 of the unit count, by dtype and head_dim, as
- * measured.  Results are those of the same block loop either way, up to the rounding of the chunk states.
+ * twice the time of one chain per unit for anything between one and two).  Every entry point that takes a dense
+ * batch (la2_fwd, la2_bwd, their _state, _saved, _norm and _noalloc forms) runs it as two calls on the given
+ * stream: the first floor(rounds * units / heads) batch rows by the plan of that many rows (one chunk), the
+ * remaining rows, with their rows of the states and of rstd, by the plan of a descriptor with that many rows
+ * (several chunks); la2_workspace_bytes() answers for both, and what either part would refuse is refused before the
+ * first launch.  A forward call's workspace then holds the chunk states of its second part, which is what
+ * la2_bwd_saved reads.  Which shapes: seqlen >= 2048 (fp32: 1024), no la2_set_chunk_tokens(), and a partial round
+ * of at most 1/8 to 4/8 of the unit count, by dtype and head_dim, as measured.  Results are those of the same block
+ * loop either way, up to the rounding of the chunk states.
  */
 la2_status la2_chunk_plan(const la2_desc* desc, int32_t* nchunks, int32_t* chunk_tokens);
 
@@ -128,8 +131,7 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
  * that is part of the library's code object (each GPU the library runs on holds that much until the process
  * ends).  The call allocates nothing and frees nothing; its first use on a device looks up the scratch
  * address there (which may load the code object on that device), later calls only enqueue kernels.
- *   - Always one call with the plan of la2_chunk_plan().  A problem whose plan has more than one chunk and whose
- *     start states (batch * heads * nchunks * head_dim^2 fp32) exceed LA2_NOALLOC_SCRATCH_BYTES is refused with
+ *   - A problem whose la2_workspace_bytes(desc, LA2_OP_FWD) exceeds LA2_NOALLOC_SCRATCH_BYTES is refused with
  *     LA2_ERR_WORKSPACE before anything is launched (the sweep's (4, 16K) and (1, 64K) points need exactly
  *     that much on a 256-CU device; problems whose chains fill the device need none).
  *   - All calls on one GPU share that GPU's scratch, whatever their stream: calls that overlap in time on one

@@ -306,17 +306,39 @@ int rows_of_first_call(const la2_desc* d) {
   return (int)rows;
 }
 
-// Workspace of the two calls (they run one after the other on one stream and share it).
-size_t split_workspace(const la2_desc* d, int rows, bool bwd) {
-  size_t need = 0;
-  for (int part = 0; part < 2; ++part) {
-    la2_desc s = *d;
-    s.batch = part == 0 ? rows : d->batch - rows;
-    // backward: the chunk states of the dQ scan and (when its launch forms them) those of the dK / dV scan
-    const size_t w = make_plan(&s).workspace * ((bwd && fuses_reverse_states(&s)) ? 2 : 1);
-    need = w > need ? w : need;
-  }
-  return need;
+// The two parts of such a batch: the first `rows` batch rows and the others.  Byte offsets of the second part in
+// the [batch, heads, seqlen, head_dim] tensors, element offsets in the fp32 states and in rstd.
+struct RowParts {
+  la2_desc first, rest;
+  int64_t bytes, state, rstd;
+};
+
+RowParts row_parts(const la2_desc* d, int rows) {
+  RowParts p{*d, *d, 0, 0, 0};
+  p.first.batch = rows;
+  p.rest.batch = d->batch - rows;
+  p.bytes = (int64_t)rows * d->stride_b * elem_size(d->dtype);   // stride_b is a multiple of 16 bytes
+  p.state = (int64_t)rows * d->heads * d->head_dim * d->head_dim;
+  p.rstd = (int64_t)rows * d->heads * d->seqlen;
+  return p;
+}
+
+template <typename T>
+T* shifted(T* p, int64_t elements) { return p == nullptr ? nullptr : p + elements; }
+const void* shifted_bytes(const void* p, int64_t bytes) {
+  return p == nullptr ? nullptr : static_cast<const char*>(p) + bytes;
+}
+void* shifted_bytes(void* p, int64_t bytes) { return p == nullptr ? nullptr : static_cast<char*>(p) + bytes; }
+
+// A workspace size that holds for the call as it runs: the larger of the two parts' (they run one after the other on
+// one stream and share the workspace), or the whole batch's when it runs as one call.
+template <typename F>
+size_t over_parts(const la2_desc* d, F bytes_of) {
+  const int rows = rows_of_first_call(d);
+  if (rows == 0) return bytes_of(d);
+  const RowParts p = row_parts(d, rows);
+  const size_t a = bytes_of(&p.first), b = bytes_of(&p.rest);
+  return a > b ? a : b;
 }
 
 struct ScanArgs {
@@ -524,13 +546,11 @@ void la2_desc_dense(la2_desc* desc, int32_t batch, int32_t heads, int32_t seqlen
 
 size_t la2_workspace_bytes(const la2_desc* desc, int32_t op) {
   if (check_desc(desc) != LA2_OK) return 0;
-  if (op == LA2_OP_FWD || op == LA2_OP_BWD) {
-    const int rows = rows_of_first_call(desc);
-    if (rows > 0) return split_workspace(desc, rows, op == LA2_OP_BWD);
-    // backward: the chunk states of the dQ scan and (when its launch forms them) those of the dK / dV scan
-    return make_plan(desc).workspace * ((op == LA2_OP_BWD && fuses_reverse_states(desc)) ? 2 : 1);
-  }
-  if (op == LA2_OP_FWD_STATE || op == LA2_OP_BWD_STATE) return state_workspace(desc, op == LA2_OP_BWD_STATE).total;
+  if (op == LA2_OP_FWD) return over_parts(desc, [](const la2_desc* d) { return make_plan(d).workspace; });
+  if (op == LA2_OP_BWD)   // the chunk states of the dQ scan and (when its launch forms them) those of the dK / dV scan
+    return over_parts(desc, [](const la2_desc* d) { return make_plan(d).workspace * (fuses_reverse_states(d) ? 2 : 1); });
+  if (op == LA2_OP_FWD_STATE) return over_parts(desc, [](const la2_desc* d) { return state_workspace(d, false).total; });
+  if (op == LA2_OP_BWD_STATE) return over_parts(desc, [](const la2_desc* d) { return state_workspace(d, true).total; });
   return 0;
 }
 
@@ -570,9 +590,10 @@ void la2_set_scan_variant(int32_t variant) { g_scan_variant.store((variant == 1 
 namespace {
 
 // la2_fwd_state, and with rstd != nullptr the same with the Norm epilogue (eps validated by the caller)
-la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
-                          const float* kv_init, void* o, float* kv_final, float* rstd, float eps, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+// check_only: return after everything that can be refused has been checked, before the first launch.
+la2_status fwd_state_one_call(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                              const float* kv_init, void* o, float* kv_final, float* rstd, float eps, void* workspace,
+                              size_t workspace_bytes, void* hip_stream, bool check_only) {
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   const int64_t chains = (int64_t)desc->batch * desc->heads;
@@ -580,7 +601,7 @@ la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, co
   if (!aligned(kv_init, 16) || !aligned(kv_final, 16)) return LA2_ERR_STRIDE_ALIGN;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   if (desc->seqlen == 0) {  // the state passes through
-    if (kv_final == nullptr) return LA2_OK;
+    if (kv_final == nullptr || check_only) return LA2_OK;
     return la2::launch_state_copy(kv_final, kv_init, chains * desc->head_dim * desc->head_dim, s) == hipSuccess
                ? LA2_OK : LA2_ERR_LAUNCH;
   }
@@ -596,6 +617,7 @@ la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, co
     return la2::launch_norm_fwd_rows(desc->head_dim, desc->dtype, np, eps, s) == hipSuccess ? LA2_OK : LA2_ERR_LAUNCH;
   };
   if (wide(desc->head_dim) && !is16(desc->dtype)) {   // fp32 at head_dim 96 / 256: token by token
+    if (check_only) return LA2_OK;
     la2::RecurParams r = recur_params(desc, lambda, 0, desc->seqlen, false);
     r.x[0] = q; r.y[0] = k; r.z[0] = v; r.w[0] = o;
     r.init[0] = kv_init;
@@ -608,6 +630,7 @@ la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, co
   const Plan pl = make_plan(&blocks);
   if (pl.workspace > 0 && (workspace == nullptr || workspace_bytes < pl.workspace)) return LA2_ERR_WORKSPACE;
   if (pl.workspace > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  if (check_only) return LA2_OK;
   if (blocks.seqlen > 0) {
     ScanArgs a{q, k, v, o};
     a.init = kv_init;
@@ -628,6 +651,28 @@ la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, co
   return rstd != nullptr ? normalise_rows(blocks.seqlen, desc->seqlen) : LA2_OK;
 }
 
+// All dense forward entry points: one call, or two for a batch a little above a whole number of chains per compute
+// unit (rows_of_first_call).  Everything either part would refuse is refused before the first launch.
+la2_status fwd_state_impl(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
+                          const float* kv_init, void* o, float* kv_final, float* rstd, float eps, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
+  if (rows == 0)
+    return fwd_state_one_call(desc, q, k, v, lambda, kv_init, o, kv_final, rstd, eps, workspace, workspace_bytes,
+                              hip_stream, false);
+  const RowParts p = row_parts(desc, rows);
+  for (int pass = 0; pass < 2; ++pass) {   // 0: check both parts, 1: run them
+    la2_status st = fwd_state_one_call(&p.first, q, k, v, lambda, kv_init, o, kv_final, rstd, eps, workspace,
+                                       workspace_bytes, hip_stream, pass == 0);
+    if (st != LA2_OK) return st;
+    st = fwd_state_one_call(&p.rest, shifted_bytes(q, p.bytes), shifted_bytes(k, p.bytes), shifted_bytes(v, p.bytes),
+                            lambda, shifted(kv_init, p.state), shifted_bytes(o, p.bytes), shifted(kv_final, p.state),
+                            shifted(rstd, p.rstd), eps, workspace, workspace_bytes, hip_stream, pass == 0);
+    if (st != LA2_OK) return st;
+  }
+  return LA2_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -641,24 +686,6 @@ la2_status la2_fwd_state(const la2_desc* desc, const void* q, const void* k, con
 
 la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
                    void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
-  if (rows > 0) {
-    // everything the two calls check, before the first launch
-    if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
-    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
-      return LA2_ERR_STRIDE_ALIGN;
-    la2_desc a = *desc, b = *desc;
-    a.batch = rows;
-    b.batch = desc->batch - rows;
-    const size_t need = split_workspace(desc, rows, false);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
-    const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
-    const la2_status st = la2_fwd_state(&a, q, k, v, lambda, nullptr, o, nullptr, workspace, workspace_bytes, hip_stream);
-    if (st != LA2_OK) return st;
-    return la2_fwd_state(&b, static_cast<const char*>(q) + off, static_cast<const char*>(k) + off,
-                         static_cast<const char*>(v) + off, lambda, nullptr, static_cast<char*>(o) + off, nullptr,
-                         workspace, workspace_bytes, hip_stream);
-  }
   return la2_fwd_state(desc, q, k, v, lambda, nullptr, o, nullptr, workspace, workspace_bytes, hip_stream);
 }
 
@@ -670,7 +697,7 @@ la2_status la2_fwd_noalloc(const la2_desc* desc, const void* q, const void* k, c
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  const size_t need = make_plan(desc).workspace;
+  const size_t need = over_parts(desc, [](const la2_desc* d) { return make_plan(d).workspace; });
   if (need > (size_t)LA2_NOALLOC_SCRATCH_BYTES) return LA2_ERR_WORKSPACE;   // chunk states beyond the built-in scratch
   void* ws = nullptr;
   if (need > 0) {
@@ -682,10 +709,16 @@ la2_status la2_fwd_noalloc(const la2_desc* desc, const void* q, const void* k, c
   return fwd_state_impl(desc, q, k, v, lambda, nullptr, o, nullptr, nullptr, 0.f, ws, need, hip_stream);
 }
 
-la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
-                         const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
-                         void* dv, float* d_kv_init, const void* fwd_workspace, size_t fwd_workspace_bytes,
-                         int32_t fwd_wrote_kv_final, void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// check_only: return after everything that can be refused has been checked, before the first launch.
+la2_status bwd_saved_one_call(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+                              const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
+                              void* dv, float* d_kv_init, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                              int32_t fwd_wrote_kv_final, void* workspace, size_t workspace_bytes, void* hip_stream,
+                              bool check_only) {
   la2_status st = check_desc(desc);
   if (st == LA2_OK && !aligned(fwd_workspace, 256)) return LA2_ERR_WORKSPACE;
   if (st != LA2_OK) return st;
@@ -694,7 +727,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   if (!aligned(kv_init, 16) || !aligned(d_kv_final, 16) || !aligned(d_kv_init, 16)) return LA2_ERR_STRIDE_ALIGN;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   if (desc->seqlen == 0) {  // the gradient of the state passes through
-    if (d_kv_init == nullptr) return LA2_OK;
+    if (d_kv_init == nullptr || check_only) return LA2_OK;
     return la2::launch_state_copy(d_kv_init, d_kv_final, chains * desc->head_dim * desc->head_dim, s) == hipSuccess
                ? LA2_OK : LA2_ERR_LAUNCH;
   }
@@ -703,6 +736,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
       !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
   if (wide(desc->head_dim) && !is16(desc->dtype)) {   // fp32 at head_dim 96 / 256: token by token
+    if (check_only) return LA2_OK;
     la2::RecurParams f = recur_params(desc, lambda, 0, desc->seqlen, false);
     f.x[0] = d_o; f.y[0] = v; f.z[0] = k; f.w[0] = dq;      // dq_t = do_t KV_t^T: the (V, K) state is KV^T
     f.init[0] = kv_init;
@@ -750,6 +784,7 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   const size_t need = split ? sw.total : fuse ? pl.workspace * (for_dq.saved_states != nullptr ? 1 : 2) : pl.workspace;
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LA2_ERR_WORKSPACE;
   if (need > 0 && !aligned(workspace, 256)) return LA2_ERR_WORKSPACE;
+  if (check_only) return LA2_OK;
   float* handoff = split ? reinterpret_cast<float*>(static_cast<char*>(workspace) + sw.chunk_states) : nullptr;
   void* rev_workspace = workspace;
   if (fuse) {
@@ -789,6 +824,37 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
   return run_scan(&blocks, pl_rev, true, for_dk, lambda, workspace, s);
 }
 
+}  // namespace
+
+extern "C" {
+
+// One call, or two for a batch a little above a whole number of chains per compute unit (rows_of_first_call), each
+// part with its own states; the forward call's workspace holds the chunk states of its second part, which is the
+// part whose backward reads them.
+la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
+                         void* dv, float* d_kv_init, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                         int32_t fwd_wrote_kv_final, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
+  if (rows == 0)
+    return bwd_saved_one_call(desc, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, fwd_workspace,
+                              fwd_workspace_bytes, fwd_wrote_kv_final, workspace, workspace_bytes, hip_stream, false);
+  const RowParts p = row_parts(desc, rows);
+  for (int pass = 0; pass < 2; ++pass) {   // 0: check both parts, 1: run them
+    la2_status st = bwd_saved_one_call(&p.first, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init,
+                                       fwd_workspace, fwd_workspace_bytes, fwd_wrote_kv_final, workspace,
+                                       workspace_bytes, hip_stream, pass == 0);
+    if (st != LA2_OK) return st;
+    st = bwd_saved_one_call(&p.rest, shifted_bytes(q, p.bytes), shifted_bytes(k, p.bytes), shifted_bytes(v, p.bytes),
+                            shifted_bytes(d_o, p.bytes), lambda, shifted(kv_init, p.state), shifted(d_kv_final, p.state),
+                            shifted_bytes(dq, p.bytes), shifted_bytes(dk, p.bytes), shifted_bytes(dv, p.bytes),
+                            shifted(d_kv_init, p.state), fwd_workspace, fwd_workspace_bytes, fwd_wrote_kv_final,
+                            workspace, workspace_bytes, hip_stream, pass == 0);
+    if (st != LA2_OK) return st;
+  }
+  return LA2_OK;
+}
+
 la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                          const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
                          void* dv, float* d_kv_init, void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -799,26 +865,6 @@ la2_status la2_bwd_state(const la2_desc* desc, const void* q, const void* k, con
 la2_status la2_bwd(const la2_desc* desc, const void* q, const void* k, const void* v, const void* d_o,
                    const float* lambda, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
-  const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
-  if (rows > 0) {   // as in la2_fwd
-    if (!q || !k || !v || !d_o || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
-    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
-        !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lambda, 4))
-      return LA2_ERR_STRIDE_ALIGN;
-    la2_desc a = *desc, b = *desc;
-    a.batch = rows;
-    b.batch = desc->batch - rows;
-    const size_t need = split_workspace(desc, rows, true);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
-    const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
-    auto at = [off](const void* p) { return static_cast<const void*>(static_cast<const char*>(p) + off); };
-    auto atw = [off](void* p) { return static_cast<void*>(static_cast<char*>(p) + off); };
-    const la2_status st = la2_bwd_saved(&a, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, nullptr, 0, 0,
-                                        workspace, workspace_bytes, hip_stream);
-    if (st != LA2_OK) return st;
-    return la2_bwd_saved(&b, at(q), at(k), at(v), at(d_o), lambda, nullptr, nullptr, atw(dq), atw(dk), atw(dv), nullptr,
-                         nullptr, 0, 0, workspace, workspace_bytes, hip_stream);
-  }
   return la2_bwd_saved(desc, q, k, v, d_o, lambda, nullptr, nullptr, dq, dk, dv, nullptr, nullptr, 0, 0, workspace,
                        workspace_bytes, hip_stream);
 }
@@ -837,27 +883,6 @@ la2_status la2_fwd_state_norm(const la2_desc* desc, const void* q, const void* k
 la2_status la2_fwd_norm(const la2_desc* desc, const void* q, const void* k, const void* v, const float* lambda,
                         float eps, void* o, float* rstd, void* workspace, size_t workspace_bytes,
                         void* hip_stream) {
-  const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
-  if (rows > 0) {   // two calls, as in la2_fwd; rstd is [batch][heads][seqlen]
-    if (!(eps >= 0.f) || eps > 3.0e38f) return LA2_ERR_VALUE;
-    if (!q || !k || !v || !o || !lambda || !rstd) return LA2_ERR_NULL;
-    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4) ||
-        !aligned(rstd, 4))
-      return LA2_ERR_STRIDE_ALIGN;
-    la2_desc a = *desc, b = *desc;
-    a.batch = rows;
-    b.batch = desc->batch - rows;
-    const size_t need = split_workspace(desc, rows, false);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
-    const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
-    const int64_t roff = (int64_t)rows * desc->heads * desc->seqlen;
-    const la2_status st = la2_fwd_state_norm(&a, q, k, v, lambda, nullptr, eps, o, rstd, nullptr, workspace,
-                                             workspace_bytes, hip_stream);
-    if (st != LA2_OK) return st;
-    return la2_fwd_state_norm(&b, static_cast<const char*>(q) + off, static_cast<const char*>(k) + off,
-                              static_cast<const char*>(v) + off, lambda, nullptr, eps, static_cast<char*>(o) + off,
-                              rstd + roff, nullptr, workspace, workspace_bytes, hip_stream);
-  }
   return la2_fwd_state_norm(desc, q, k, v, lambda, nullptr, eps, o, rstd, nullptr, workspace, workspace_bytes,
                             hip_stream);
 }
@@ -877,7 +902,8 @@ la2_status la2_bwd_state_norm(const la2_desc* desc, const void* q, const void* k
       !aligned(dv, 16) || !aligned(lambda, 4) || !aligned(kv_init, 16) || !aligned(d_kv_final, 16) ||
       !aligned(d_kv_init, 16))
     return LA2_ERR_STRIDE_ALIGN;
-  const size_t need = bwd_workspace_need(desc, d_kv_final != nullptr);
+  const bool has_final = d_kv_final != nullptr;
+  const size_t need = over_parts(desc, [has_final](const la2_desc* d) { return bwd_workspace_need(d, has_final); });
   if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256)))
     return LA2_ERR_WORKSPACE;
   const la2::NormBwdParams np{o, d_o, rstd, d_u, desc->stride_b, desc->stride_h, desc->stride_n,
@@ -895,28 +921,6 @@ la2_status la2_bwd_norm(const la2_desc* desc, const void* q, const void* k, cons
   la2_status st = check_desc(desc);
   if (st != LA2_OK) return st;
   if ((int64_t)desc->batch * desc->heads * desc->seqlen == 0) return LA2_OK;  // nothing to do
-  const int rows = rows_of_first_call(desc);
-  if (rows > 0) {   // two calls, as in la2_bwd
-    if (!q || !k || !v || !o || !rstd || !d_o || !d_u || !dq || !dk || !dv || !lambda) return LA2_ERR_NULL;
-    if (!aligned(o, 16) || !aligned(d_o, 16) || !aligned(d_u, 16) || !aligned(rstd, 4) || !aligned(q, 16) ||
-        !aligned(k, 16) || !aligned(v, 16) || !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) ||
-        !aligned(lambda, 4))
-      return LA2_ERR_STRIDE_ALIGN;
-    la2_desc a = *desc, b = *desc;
-    a.batch = rows;
-    b.batch = desc->batch - rows;
-    const size_t need = split_workspace(desc, rows, true);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned(workspace, 256))) return LA2_ERR_WORKSPACE;
-    const int64_t off = (int64_t)rows * desc->stride_b * elem_size(desc->dtype);
-    const int64_t roff = (int64_t)rows * desc->heads * desc->seqlen;
-    auto at = [off](const void* p) { return static_cast<const void*>(static_cast<const char*>(p) + off); };
-    auto atw = [off](void* p) { return static_cast<void*>(static_cast<char*>(p) + off); };
-    st = la2_bwd_state_norm(&a, q, k, v, o, rstd, d_o, lambda, nullptr, nullptr, d_u, dq, dk, dv, nullptr, workspace,
-                            workspace_bytes, hip_stream);
-    if (st != LA2_OK) return st;
-    return la2_bwd_state_norm(&b, at(q), at(k), at(v), at(o), rstd + roff, at(d_o), lambda, nullptr, nullptr, atw(d_u),
-                              atw(dq), atw(dk), atw(dv), nullptr, workspace, workspace_bytes, hip_stream);
-  }
   return la2_bwd_state_norm(desc, q, k, v, o, rstd, d_o, lambda, nullptr, nullptr, d_u, dq, dk, dv, nullptr,
                             workspace, workspace_bytes, hip_stream);
 }

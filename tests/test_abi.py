@@ -596,8 +596,8 @@ def test_the_chunk_planner_keeps_its_measured_rules(lib):
 
 
 def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remaining_rows(lib):
-    """la2_fwd / la2_bwd run a batch with a few more chains than one (or two) per compute unit as two calls: the rows
-    that make whole rounds, un-chunked, and the remaining rows by their own plan.  The workspace query answers for
+    """Every dense entry point runs a batch with a few more chains than one (or two) per compute unit as two calls:
+    the rows that make whole rounds, un-chunked, and the remaining rows by their own plan.  The workspace query answers for
     exactly that (256 units assumed without a device); la2_chunk_plan still describes one call over the whole batch.
     Which shapes: those where two calls measured at least 5 % faster than one."""
     lib.la2_set_chunk_tokens(0)
@@ -615,9 +615,8 @@ def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remai
         assert plan(lib, b, h, n, d, dt)[0] == 1
         assert plan(lib, first, h, n, d, dt)[0] == 1
         assert plan(lib, b - first, h, n, d, dt)[0] > 1
-        for op in (0, 1):
+        for op in (0, 1, 2, 3):           # plain and state entry points alike
             assert ws(whole, op) == ws(rest, op) > 0, (b, h, n, d, dt, op)
-        assert ws(whole, 3) == 0          # the state entry points run the batch as one call
     # not split: too many chains for the shape, a whole number of rounds, sequences too short, three rounds
     for b, h, n, d, dt in ((23, 16, 4096, 128, BF), (21, 16, 2048, 128, BF), (16, 16, 4096, 128, BF),
                            (20, 16, 1024, 128, BF), (20, 16, 2047, 64, F16), (36, 16, 2048, 128, BF),

@@ -227,6 +227,31 @@ def test_decode_multi_config5_shape():
     assert_close("config5 multi state", state[rows], rs, torch.bfloat16)
 
 
+@pytest.mark.parametrize("b,H,n,d,dtype", [(20, 16, 2048, 128, torch.bfloat16), (18, 16, 2100, 64, torch.float16),
+                                           (20, 16, 1100, 128, torch.float32), (34, 8, 2048, 256, torch.bfloat16)])
+def test_states_of_batches_a_little_above_the_compute_unit_count(b, H, n, d, dtype):
+    """Such a batch runs as two calls (the rows that give every compute unit one chain, then the others in chunks):
+    each part takes its own rows of kv_init / d_kv_final and writes its own rows of kv_final / d_kv_init.  Whole
+    lengths and ragged ones, full tensors against the oracle's recurrent form; then the training-step pair, the
+    backward reading the chunk states the forward call left in its workspace."""
+    t = inputs(b, H, n, d, dtype, seed=1700 + n + d)
+    check_segment(t, dtype, "two calls %s b%d n%d d%d" % (dtype, b, n, d))
+    g = {k: v.to(DEV) for k, v in t.items()}
+    need = binding.la2_workspace_bytes(g["q"], binding.LA2_OP_BWD_STATE)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert need > 0 and binding.la2_chunk_plan(g["q"])[0] == 1      # one call would need none
+    ws_f = torch.empty(max(256, need), dtype=torch.uint8, device=DEV)
+    ws_b = torch.empty(max(256, need), dtype=torch.uint8, device=DEV)
+    binding.la2_fwd_state(g["q"], g["k"], g["v"], g["lam"], kv_init=g["kv_init"], want_final=False, workspace=ws_f)
+    dq, dk, dv, g0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], g["lam"], kv_init=g["kv_init"],
+                                           workspace=ws_b, fwd_workspace=ws_f)
+    torch.cuda.synchronize()
+    q, k, v, do, lam = (to64(t[x]) for x in ("q", "k", "v", "d_o", "lam"))
+    rdq, rdk, rdv, rg0 = oracle.bwd_recurrent_state(q, k, v, do, lam, kv_init=to64(t["kv_init"]))
+    for name, got, ref in (("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv), ("d_kv_init", g0, rg0)):
+        assert_close("two calls, saved states " + name, got, ref, dtype)
+
+
 @pytest.mark.parametrize("dtype,d,n,chunk", [(torch.bfloat16, 128, 1024, 256), (torch.bfloat16, 64, 1000, 128),
                                              (torch.float32, 128, 640, 128), (torch.bfloat16, 128, 900, 0)])
 def test_backward_reuses_the_forward_chunk_states(dtype, d, n, chunk):

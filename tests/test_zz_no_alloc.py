@@ -23,6 +23,9 @@ CASES = [
     (2, 3, 2500, 64, torch.bfloat16),
     (1, 2, 3000, 128, torch.float32),
     (64, 4, 512, 128, torch.bfloat16),   # chains fill the device: no scratch needed at all
+    # a few more chains than compute units: the first rows whole, the other rows in chunks whose states take the
+    # scratch (all 16 MiB of it on a device of 256 units)
+    (20, 16, 2048, 128, torch.bfloat16),
 ]
 
 
