@@ -118,7 +118,11 @@ def main():
                     help="for rocprofv3 passes: after the plain-copy reference and a warm-up, loop one operation on one "
                          "workload and print its time.  OP: fwd, bwd, bwd_saved (backward from the forward's chunk "
                          "states), fwd_norm, bwd_norm, decode, decode8 (8 tokens per launch).  WORKLOAD: c3_0 .. c3_3 "
-                         "(the sweep points), c2, c4, w256, w96 (head_dim 256 / 96 at batch 64, n 1024); decode ops take c5")
+                         "(the sweep points), c2, c4, w256, w96 (head_dim 256 / 96 at batch 64, n 1024), b20 (batch 20, n 4096: 320 "
+                         "chains, run as two calls); decode ops take c5")
+    ap.add_argument("--profile-chunk-tokens", type=int, default=0,
+                    help="with --profile: the caller's chunk size (la2_set_chunk_tokens); the sequence length gives one "
+                         "call with one chunk")
     ap.add_argument("--profile-iters", type=int, default=400)
     ap.add_argument("--profile-settle-ms", type=float, default=80.0,
                     help="with --profile: call the operation for this long before the timed loop (0 for counter passes, "
@@ -214,8 +218,10 @@ def main():
         # the other head dimensions, as in other_head_dims below
         table.update({"w256": workloads.Workload("b64_n1024_h8_d256", 64, 8, 1024, 256, torch.bfloat16, seed=60 + 256),
                       "w96": workloads.Workload("b64_n1024_h16_d96", 64, 16, 1024, 96, torch.bfloat16, seed=60 + 96)})
+        table["b20"] = workloads.Workload("b20_n4096_h16_d128", 20, 16, 4096, 128, torch.bfloat16, seed=71)
         wl_p = table[wname]
         g_p = stage(wl_p)
+        binding.la2_set_chunk_tokens(args.profile_chunk_tokens)
         settle = args.profile_settle_ms
         if op == "fwd":
             ms = time_ms(lambda: fwd(g_p), iters, settle_ms=settle)
