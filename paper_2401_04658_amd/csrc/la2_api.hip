@@ -260,7 +260,7 @@ la2_status check_desc(const la2_desc* d) {
 
 // A dense batch with a few more chains than a whole number of chains per compute unit: the units that get one
 // workgroup more set the launch's time (n 4096, head_dim 128, bf16, forward + backward: 256 chains 0.67 ms, 320
-// chains 1.14 ms; fp32: 9.5 ms for anything from 272 to 480 chains).  la2_fwd / la2_bwd run such a batch as two
+// chains 1.14 ms; fp32: 9.5 ms for anything from 272 to 480 chains).  The dense entry points run such a batch as two
 // calls: the first rows, one or two chains per unit, whole; the rest by the plan for that many chains, i.e. in
 // chunks (320 chains: 0.67 + 0.27 ms).  Returns the rows of the first call, 0 for one call.
 // Measured, two calls against one, forward + backward, n 2048 / 4096 / 8192 (256 units):
