@@ -835,15 +835,17 @@ la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, con
                          const float* lambda, const float* kv_init, const float* d_kv_final, void* dq, void* dk,
                          void* dv, float* d_kv_init, const void* fwd_workspace, size_t fwd_workspace_bytes,
                          int32_t fwd_wrote_kv_final, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (check_desc(desc) == LA2_OK && !aligned(fwd_workspace, 256)) return LA2_ERR_WORKSPACE;
   const int rows = check_desc(desc) == LA2_OK ? rows_of_first_call(desc) : 0;
   if (rows == 0)
     return bwd_saved_one_call(desc, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init, fwd_workspace,
                               fwd_workspace_bytes, fwd_wrote_kv_final, workspace, workspace_bytes, hip_stream, false);
   const RowParts p = row_parts(desc, rows);
   for (int pass = 0; pass < 2; ++pass) {   // 0: check both parts, 1: run them
+    // the first part never reads the forward call's workspace: should its plan cut (fewer chains than units when the
+    // heads do not divide them), its chunk states were overwritten there by the second part's
     la2_status st = bwd_saved_one_call(&p.first, q, k, v, d_o, lambda, kv_init, d_kv_final, dq, dk, dv, d_kv_init,
-                                       fwd_workspace, fwd_workspace_bytes, fwd_wrote_kv_final, workspace,
-                                       workspace_bytes, hip_stream, pass == 0);
+                                       nullptr, 0, 0, workspace, workspace_bytes, hip_stream, pass == 0);
     if (st != LA2_OK) return st;
     st = bwd_saved_one_call(&p.rest, shifted_bytes(q, p.bytes), shifted_bytes(k, p.bytes), shifted_bytes(v, p.bytes),
                             shifted_bytes(d_o, p.bytes), lambda, shifted(kv_init, p.state), shifted(d_kv_final, p.state),

@@ -228,7 +228,10 @@ def test_decode_multi_config5_shape():
 
 
 @pytest.mark.parametrize("b,H,n,d,dtype", [(20, 16, 2048, 128, torch.bfloat16), (18, 16, 2100, 64, torch.float16),
-                                           (20, 16, 1100, 128, torch.float32), (34, 8, 2048, 256, torch.bfloat16)])
+                                           (20, 16, 1100, 128, torch.float32), (34, 8, 2048, 256, torch.bfloat16),
+                                           # 12 heads do not divide 256 units: the first part has 252 chains, which the
+                                           # fp32 head_dim 64 plan cuts in three, so both parts use the workspace
+                                           (22, 12, 1024, 64, torch.float32)])
 def test_states_of_batches_a_little_above_the_compute_unit_count(b, H, n, d, dtype):
     """Such a batch runs as two calls (the rows that give every compute unit one chain, then the others in chunks):
     each part takes its own rows of kv_init / d_kv_final and writes its own rows of kv_final / d_kv_init.  Whole
