@@ -216,3 +216,55 @@ def run_case(i, c):
             assert_close(tag + " " + name, got, ref, dtype)
     for x in (g["q"], o):
         assert x.stride() == g["q"].stride()
+
+
+def rel_diff(a, b):
+    a, b = a.double(), b.double()
+    return float((a - b).abs().max() / b.abs().max().clamp_min(1e-30))
+
+
+@pytest.mark.parametrize("i", range(10))
+def test_random_batch_above_whole_rounds_two_calls_against_one(i):
+    """Batches with a few more chains than one or two per compute unit, which the library runs as two calls, against
+    the same entry points run as one call (the caller's chunk size set to the whole sequence): heads that do and do
+    not divide the unit count, both storage layouts, states and their gradients, the Norm pair.  The two differ by
+    the rounding of the second part's chunk states only; each way is held to the oracle by the fixed cases."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    rng = np.random.default_rng(4711 + i)
+    dtype = DTYPES[int(rng.integers(0, 3))]
+    d = int(rng.choice([64, 128])) if dtype == torch.float32 else int(rng.choice([64, 128, 128, 96, 256]))
+    H = int(rng.choice([4, 8, 12, 16, 20, 24, 32]))
+    rounds = int(rng.choice([1, 1, 1, 2]))
+    b = max(2, int(np.ceil(cus * (rounds + rng.uniform(0.02, 0.3)) / H)))
+    n = int(rng.integers(1024, 2500)) if dtype == torch.float32 or rounds == 2 else int(rng.integers(2048, 4200))
+    if rounds == 2 and dtype != torch.float32:
+        n = int(rng.integers(4096, 4300))
+    layout = str(rng.choice(["bhnd", "bnhd"]))
+    t = workloads.Workload("case", b, H, n, d, dtype, seed=int(rng.integers(0, 1 << 30)), backward=True).tensors()
+    g = {name: place(t[name], layout) for name in ("q", "k", "v", "d_o")}
+    lam = t["lam"].to(DEV)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(i)
+    kv0 = (torch.randn((b, H, d, d), generator=gen) * 0.3).to(DEV)
+    dkvf = (torch.randn((b, H, d, d), generator=gen) * 0.3).to(DEV)
+
+    def run():
+        o, kvf = binding.la2_fwd_state(g["q"], g["k"], g["v"], lam, kv_init=kv0, want_final=True)
+        dq, dk, dv, dkv0 = binding.la2_bwd_state(g["q"], g["k"], g["v"], g["d_o"], lam, kv_init=kv0, d_kv_final=dkvf)
+        on, rstd = binding.la2_fwd_norm(g["q"], g["k"], g["v"], lam, 1e-6)
+        du = torch.empty_like(g["d_o"])
+        nq, nk, nv = binding.la2_bwd_norm(g["q"], g["k"], g["v"], on, rstd, g["d_o"], lam, d_u=du)
+        torch.cuda.synchronize()
+        return dict(o=o, kv_final=kvf, dq=dq, dk=dk, dv=dv, d_kv_init=dkv0, o_norm=on, rstd=rstd, d_u=du, dq_norm=nq,
+                    dk_norm=nk, dv_norm=nv)
+
+    two_calls = binding.la2_chunk_plan(g["q"])[0] == 1 and binding.la2_workspace_bytes(g["q"], binding.LA2_OP_FWD) > 0
+    print("case", i, dtype, (b, H, n, d), layout, "two calls" if two_calls else "one call", flush=True)
+    got = run()
+    binding.la2_set_chunk_tokens(n)
+    assert binding.la2_workspace_bytes(g["q"], binding.LA2_OP_FWD) == 0 or n % 64 != 0
+    ref = run()
+    tol = {torch.float32: 2e-5, torch.bfloat16: 2e-2, torch.float16: 3e-3}[dtype]
+    for name in got:
+        assert torch.isfinite(got[name].float()).all(), name
+        assert rel_diff(got[name], ref[name]) <= tol, (name, rel_diff(got[name], ref[name]))
