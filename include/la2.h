@@ -133,7 +133,9 @@ la2_status la2_fwd(const la2_desc* desc, const void* q, const void* k, const voi
  * address there (which may load the code object on that device), later calls only enqueue kernels.
  *   - A problem whose la2_workspace_bytes(desc, LA2_OP_FWD) exceeds LA2_NOALLOC_SCRATCH_BYTES is refused with
  *     LA2_ERR_WORKSPACE before anything is launched (the sweep's (4, 16K) and (1, 64K) points need exactly
- *     that much on a 256-CU device; problems whose chains fill the device in whole rounds need none).
+ *     that much on a 256-CU device; problems whose chains fill the device in whole rounds need none).  One
+ *     exception: a batch that la2_fwd would run as two calls (see la2_chunk_plan) and whose second part's chunk
+ *     states exceed the scratch runs here as one call, which needs none.
  *   - All calls on one GPU share that GPU's scratch, whatever their stream: calls that overlap in time on one
  *     GPU race on it.  Calls on one stream, or otherwise ordered, are fine; the scratch keeps the previous
  *     call's contents and every call overwrites what it reads, so nothing needs clearing in between.

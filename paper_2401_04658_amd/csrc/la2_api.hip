@@ -697,8 +697,15 @@ la2_status la2_fwd_noalloc(const la2_desc* desc, const void* q, const void* k, c
   if (!q || !k || !v || !o || !lambda) return LA2_ERR_NULL;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lambda, 4))
     return LA2_ERR_STRIDE_ALIGN;
-  const size_t need = over_parts(desc, [](const la2_desc* d) { return make_plan(d).workspace; });
-  if (need > (size_t)LA2_NOALLOC_SCRATCH_BYTES) return LA2_ERR_WORKSPACE;   // chunk states beyond the built-in scratch
+  size_t need = over_parts(desc, [](const la2_desc* d) { return make_plan(d).workspace; });
+  bool one_call = false;
+  if (need > (size_t)LA2_NOALLOC_SCRATCH_BYTES) {
+    // chunk states beyond the built-in scratch.  A batch that would run as two calls (rows_of_first_call) and whose
+    // second part asks for that much still runs as one call, which needs none.
+    one_call = rows_of_first_call(desc) > 0;
+    need = make_plan(desc).workspace;
+    if (!one_call || need > (size_t)LA2_NOALLOC_SCRATCH_BYTES) return LA2_ERR_WORKSPACE;
+  }
   void* ws = nullptr;
   if (need > 0) {
     st = scratch_on_current_device(&ws);
@@ -706,6 +713,8 @@ la2_status la2_fwd_noalloc(const la2_desc* desc, const void* q, const void* k, c
   }
   // Nothing in the scratch has to start at zero: the pre-pass writes the local state of every chunk that has a
   // successor and the state scan overwrites all of them, before the scan kernel reads any.
+  if (one_call)
+    return fwd_state_one_call(desc, q, k, v, lambda, nullptr, o, nullptr, nullptr, 0.f, ws, need, hip_stream, false);
   return fwd_state_impl(desc, q, k, v, lambda, nullptr, o, nullptr, nullptr, 0.f, ws, need, hip_stream);
 }
 

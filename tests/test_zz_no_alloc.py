@@ -26,6 +26,9 @@ CASES = [
     # a few more chains than compute units: the first rows whole, the other rows in chunks whose states take the
     # scratch (all 16 MiB of it on a device of 256 units)
     (20, 16, 2048, 128, torch.bfloat16),
+    # the same kind at head_dim 256: the other rows' chunk states (64 MiB) do not fit the scratch, so the batch runs
+    # as one un-chunked call here, which needs none
+    (34, 8, 2048, 256, torch.bfloat16),
 ]
 
 
@@ -38,7 +41,10 @@ def test_noalloc_matches_la2_fwd_two_calls_in_a_row():
         print("case", i, (b, h, n, d, dt), "workspace bytes", binding.la2_workspace_bytes(g["q"]), flush=True)
         if i < 4:
             assert binding.la2_workspace_bytes(g["q"]) > 0, "case is meant to use the scratch"
+        if i == 6 and binding.la2_workspace_bytes(g["q"]) > (16 << 20):   # la2_fwd as one call as well
+            binding.la2_set_chunk_tokens(n)
         ref = binding.la2_fwd(g["q"], g["k"], g["v"], g["lam"])
+        binding.la2_set_chunk_tokens(0)
         out = torch.full_like(g["q"], float("nan"))
         binding.la2_fwd_noalloc(g["q"], g["k"], g["v"], g["lam"], out)
         torch.cuda.synchronize()
