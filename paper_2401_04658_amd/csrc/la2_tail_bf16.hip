@@ -15,10 +15,14 @@ namespace la2 {
 namespace {
 using namespace bf16k;
 
+// Three waves per SIMD at head_dim 128 (168 registers, no spills; the allocator takes 222 and two waves when left
+// alone): a workgroup loads its state slice, computes and stores one after the other, and a third resident workgroup
+// per compute unit keeps more of the state in flight (8 tokens x 4096 chains: 0.0907 against 0.0942 ms; four waves
+// spill and take 0.148 ms).
 // NORM: the Norm epilogue of eq. (2) (the waves exchange the sums of squares of their 32 features of every row
 // through LDS, one more barrier per block; wave 0 stores r).
 template <typename E, int D, bool NORM = false>
-__global__ __launch_bounds__(2 * D) void tail_bf16_kernel(RecurParams p) {
+__global__ __launch_bounds__(2 * D) __attribute__((amdgpu_waves_per_eu(D == 128 ? 3 : 1))) void tail_bf16_kernel(RecurParams p) {
   constexpr int B = 32;
   using C = Cfg<D, B>;
   constexpr int KS = C::KS, NT = C::NT, TILE = C::TILE;
