@@ -362,7 +362,9 @@ def main():
         del st
     # the operator with its output normalisation (eq. (2); la2_fwd_norm / la2_bwd_norm) beside the plain one
     normed = []
-    for wl, g in sweep[1:3]:
+    # two sweep points, and head_dim 64: config 2 and a batch that gives every compute unit one chain
+    wl_n64 = workloads.Workload("b16_n4096_h16_d64", 16, 16, 4096, 64, torch.bfloat16, seed=72)
+    for wl, g in sweep[1:3] + [(workloads.CONFIG2, stage(workloads.CONFIG2)), (wl_n64, stage(wl_n64))]:
         rstd = torch.empty(g["q"].shape[:3], dtype=torch.float32, device=dev)
         d_u = torch.empty_like(g["q"])
         f_ms = time_ms(lambda: binding.la2_fwd_norm(g["q"], g["k"], g["v"], g["lam"], 1e-6, out=g["o"], rstd=rstd,
