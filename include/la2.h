@@ -334,6 +334,8 @@ la2_status la2_decode_step_norm(int32_t batch, int32_t heads, int32_t head_dim, 
  *                            la2_fwd_state); if that plan differs from this call's, the saved states are not used
  *                            and the result is that of la2_bwd_state.
  * The chunk plan also depends on la2_set_chunk_tokens() and the device: both calls must see the same.
+ * A batch that runs as two calls (see la2_chunk_plan) left only its second part's chunk states in fwd_workspace; the
+ * second part of this call reads them, the first part, should its own plan cut, recomputes.
  */
 la2_status la2_bwd_saved(const la2_desc* desc, const void* q, const void* k, const void* v,
                          const void* d_o, const float* lambda, const float* kv_init,
