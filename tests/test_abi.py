@@ -617,6 +617,12 @@ def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remai
         assert plan(lib, b - first, h, n, d, dt)[0] > 1
         for op in (0, 1, 2, 3):           # plain and state entry points alike
             assert ws(whole, op) == ws(rest, op) > 0, (b, h, n, d, dt, op)
+    # heads that do not divide the unit count: the first part has 21 x 12 = 252 chains, which the fp32 head_dim 64 plan
+    # cuts in three; both parts then use the workspace, one after the other, and the query answers for the larger
+    parts = [dense(lib, 21, 12, 1024, 64, F32), dense(lib, 1, 12, 1024, 64, F32)]
+    assert plan(lib, 21, 12, 1024, 64, F32)[0] == 3 and plan(lib, 1, 12, 1024, 64, F32)[0] > 1
+    for op in (0, 1, 2, 3):
+        assert ws(dense(lib, 22, 12, 1024, 64, F32), op) == max(ws(p_, op) for p_ in parts) > 0
     # not split: too many chains for the shape, a whole number of rounds, sequences too short, three rounds
     for b, h, n, d, dt in ((23, 16, 4096, 128, BF), (21, 16, 2048, 128, BF), (16, 16, 4096, 128, BF),
                            (20, 16, 1024, 128, BF), (20, 16, 2047, 64, F16), (36, 16, 2048, 128, BF),
