@@ -98,8 +98,8 @@ size_t la2_workspace_bytes(const la2_desc* desc, int32_t op);
  * loop of Algorithm 1 / 2 runs over the whole sequence in one workgroup per (batch, head).  The workspace
  * holds one d x d fp32 start state per (batch, head, chunk) when nchunks > 1.  Depends on the device's
  * compute-unit count and on la2_set_chunk_tokens(), like la2_workspace_bytes().
- * One case it does not describe: a batch with a few more chains than one (or two) per compute unit, which as one
- * launch gives some units a workgroup more than the others and takes nearly as long as the next whole round (fp32:
+ * One case it does not describe: a batch with a few more chains than a whole number (one to four) per compute unit,
+ * which as one launch gives some units a workgroup more than the others and takes nearly as long as the next whole round (fp32:
  * twice the time of one chain per unit for anything between one and two).  Every entry point that takes a dense
  * batch (la2_fwd, la2_bwd, their _state, _saved, _norm and _noalloc forms) runs it as two calls on the given
  * stream: the first floor(rounds * units / heads) batch rows by the plan of that many rows (one chunk), the

@@ -261,7 +261,7 @@ la2_status check_desc(const la2_desc* d) {
 // A dense batch with a few more chains than a whole number of chains per compute unit: the units that get one
 // workgroup more set the launch's time (n 4096, head_dim 128, bf16, forward + backward: 256 chains 0.67 ms, 320
 // chains 1.14 ms; fp32: 9.5 ms for anything from 272 to 480 chains).  The dense entry points run such a batch as two
-// calls: the first rows, one or two chains per unit, whole; the rest by the plan for that many chains, i.e. in
+// calls: the first rows, a whole number of chains per unit (up to four), whole; the rest by the plan for that many chains, i.e. in
 // chunks (320 chains: 0.67 + 0.27 ms).  Returns the rows of the first call, 0 for one call.
 // Measured, two calls against one, forward + backward, n 2048 / 4096 / 8192 (256 units):
 //   chains           272          288          320          352          384
@@ -276,6 +276,8 @@ la2_status check_desc(const la2_desc* d) {
 //   bf16 d 256       0.96         1.01         1.01
 //   fp32 d 128       0.73         0.79         0.91         (n 4096)
 //   fp32 d 64        1.06         1.11         1.23         (two workgroups per unit: no step at 512)
+//   chains           800          832          864          1056         1088
+//   bf16 d 64, 128   0.90-0.93    0.93-0.95    0.97-0.99    0.94         0.96         (n 4096 and 8192)
 // The rule below takes the cells at 0.95 or under.
 int rows_of_first_call(const la2_desc* d) {
   if (g_chunk_tokens_override.load(std::memory_order_relaxed) > 0) return 0;   // the caller plans
@@ -283,19 +285,21 @@ int rows_of_first_call(const la2_desc* d) {
   const int n = d->seqlen, hd = d->head_dim;
   const int64_t chains = (int64_t)d->batch * d->heads;
   const int64_t k = chains / cus;   // whole rounds of one chain per unit
-  if (k < 1 || k > 2 || d->heads > cus) return 0;
+  if (k < 1 || k > 4 || d->heads > cus) return 0;
   // the largest partial round, in eighths of the unit count, that is worth a call of its own
   int eighths = 0;
   if (d->dtype == LA2_F32) {
     if (wide(hd)) return 0;
     if (k == 1) eighths = n >= 1024 ? 4 : 0;
-    else eighths = hd == 128 && n >= 2048 ? 2 : 0;
+    else eighths = k == 2 && hd == 128 && n >= 2048 ? 2 : 0;
   } else if (hd == 256) {
     eighths = k == 1 && n >= 2048 ? 1 : 0;
   } else if (hd == 96) {
-    eighths = k == 1 ? (n >= 4096 ? 2 : n >= 2048 ? 1 : 0) : (n >= 4096 ? 1 : 0);
+    eighths = k == 1 ? (n >= 4096 ? 2 : n >= 2048 ? 1 : 0) : (k == 2 && n >= 4096 ? 1 : 0);
+  } else if (k == 1) {
+    eighths = n >= 4096 ? 3 : n >= 2048 ? 2 : 0;
   } else {
-    eighths = k == 1 ? (n >= 4096 ? 3 : n >= 2048 ? 2 : 0) : (n >= 4096 ? 2 : 0);
+    eighths = n >= 4096 ? (k <= 3 ? 2 : 1) : 0;
   }
   const int64_t rows = k * cus / d->heads;
   const int64_t rest_chains = chains - rows * d->heads;

@@ -606,6 +606,7 @@ def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remai
     split = [(20, 16, 4096, 128, BF), (18, 16, 2048, 64, F16), (11, 32, 4096, 128, BF), (22, 16, 4096, 128, F16),
              (20, 16, 2048, 128, BF), (40, 8, 3072, 64, BF), (22, 12, 4096, 128, BF),      # up to 1.25 / 1.375 per unit
              (36, 16, 4096, 128, BF), (34, 16, 8192, 64, F16),                             # a little above two per unit
+             (52, 16, 4096, 128, BF), (50, 16, 8192, 64, F16), (66, 16, 4096, 64, BF),     # ... three and four
              (34, 8, 2048, 256, BF), (36, 8, 4096, 256, F16),                              # head_dim 256: up to 1.125
              (18, 16, 2048, 96, BF), (20, 16, 4096, 96, BF), (34, 16, 4096, 96, F16),      # head_dim 96
              (20, 16, 4096, 128, F32), (24, 16, 1024, 64, F32), (34, 16, 4096, 128, F32)]  # fp32: up to 1.5
@@ -623,13 +624,16 @@ def test_batches_a_little_above_the_unit_count_take_the_workspace_of_their_remai
     assert plan(lib, 21, 12, 1024, 64, F32)[0] == 3 and plan(lib, 1, 12, 1024, 64, F32)[0] > 1
     for op in (0, 1, 2, 3):
         assert ws(dense(lib, 22, 12, 1024, 64, F32), op) == max(ws(p_, op) for p_ in parts) > 0
-    # not split: too many chains for the shape, a whole number of rounds, sequences too short, three rounds
+    # not split: too many chains for the shape, a whole number of rounds, sequences too short, five rounds, three
+    # rounds of the kernels whose rule stops at two
     for b, h, n, d, dt in ((23, 16, 4096, 128, BF), (21, 16, 2048, 128, BF), (16, 16, 4096, 128, BF),
                            (20, 16, 1024, 128, BF), (20, 16, 2047, 64, F16), (36, 16, 2048, 128, BF),
                            (38, 8, 2048, 256, BF), (34, 8, 1024, 256, BF), (68, 8, 4096, 256, BF),
                            (20, 16, 2048, 96, BF), (36, 16, 4096, 96, BF), (25, 16, 4096, 64, F32),
-                           (24, 16, 512, 64, F32), (34, 16, 4096, 64, F32), (50, 16, 4096, 128, BF),
-                           (32, 16, 4096, 128, BF)):
+                           (24, 16, 512, 64, F32), (34, 16, 4096, 64, F32), (48, 16, 4096, 128, BF),
+                           (32, 16, 4096, 128, BF), (54, 16, 4096, 128, BF), (68, 16, 4096, 128, BF),
+                           (82, 16, 4096, 128, BF), (50, 16, 2048, 128, BF), (50, 16, 4096, 96, BF),
+                           (50, 16, 4096, 128, F32)):
         assert ws(dense(lib, b, h, n, d, dt), 0) == 0, (b, h, n, d, dt)
     lib.la2_set_chunk_tokens(1024)       # a caller's chunk size: one call, cut as asked
     try:

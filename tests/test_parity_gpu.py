@@ -242,6 +242,7 @@ def test_strided_layout():
 SPLIT_CASES = [(b, H, n, d, st, dt) for dt in (torch.bfloat16, torch.float16)
                for b, H, n, d, st in ((20, 16, 2048, 128, False), (18, 16, 2100, 64, True), (11, 32, 4096, 128, False))]
 SPLIT_CASES += [(36, 16, 4096, 128, False, torch.float16), (34, 16, 4100, 64, True, torch.bfloat16),   # two rounds
+                (50, 16, 4096, 64, False, torch.bfloat16),                                           # three
                 (34, 8, 2048, 256, False, torch.bfloat16), (36, 8, 2100, 256, True, torch.float16),
                 (18, 16, 2048, 96, False, torch.float16), (34, 16, 4096, 96, False, torch.bfloat16),
                 (24, 16, 1024, 64, False, torch.float32), (20, 16, 1100, 128, True, torch.float32),
